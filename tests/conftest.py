@@ -1,0 +1,33 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+def load_golden(name):
+    """Parse a tests/golden/*.txt fixture: '#' comments, 'key: v v v' lines."""
+    import numpy as np
+
+    out = {}
+    with open(os.path.join(ROOT, "tests", "golden", name)) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, vals = line.split(":", 1)
+            arr = np.array([float(v) for v in vals.split()], dtype=np.float64)
+            out[key.strip()] = arr
+    return out
+
+
+@pytest.fixture(scope="session")
+def golden():
+    return load_golden

@@ -1,0 +1,303 @@
+"""Pins for the CPU oracle: it is checked against what the paper and the mathematics fix,
+never against itself.  Each test names the passage or fact it rests on.
+"""
+import numpy as np
+import pytest
+import scipy.linalg
+
+import oracle
+from oracle import dense
+
+TINY_SQUARE = [2, 3, 4, 5]
+TINY_RECT = [(2, 3, 4, 2), (2, 4, 4, 4), (3, 2, 6, 5), (4, 3, 8, 2), (1, 5, 3, 4), (3, 4, 5, 2), (4, 2, 6, 3)]
+READINGS = [oracle.READING_A, oracle.READING_B]
+
+
+def _rand(rng, k, p, q, s, B=3):
+    return (rng.standard_normal((B, k * p)), rng.standard_normal((k, q, p)),
+            rng.standard_normal((k, s, q)), rng.standard_normal((B, k * s)))
+
+
+# ---------------------------------------------------------------- forward ----
+
+@pytest.mark.parametrize("reading", READINGS)
+@pytest.mark.parametrize("shape", [(m, m, m, m) for m in TINY_SQUARE] + TINY_RECT)
+def test_fwd_equals_literal_dense_product(shape, reading):
+    """Def. 3.1: y = (P L P^T R) x with every factor materialised (brute force)."""
+    k, p, q, s = shape
+    rng = np.random.default_rng(hash(shape) % 1000 + reading)
+    x, R, L, _ = _rand(rng, k, p, q, s)
+    M = dense.monarch_dense(R, L, reading)
+    assert M.shape == (k * s, k * p)
+    assert oracle.rel_fro(oracle.fwd(x, R, L, reading), x @ M.T) < 1e-13
+
+
+@pytest.mark.parametrize("m", TINY_SQUARE)
+def test_square_dense_entries_match_equation_1(m):
+    """Eq. (1): M[l*m+j, k*m+i] = L[j,l,k] R[k,j,i]; both readings coincide for k == q."""
+    rng = np.random.default_rng(m)
+    x, R, L, _ = _rand(rng, m, m, m, m, B=m * m)
+    M = dense.eq1_dense_square(R, L)
+    assert np.allclose(dense.monarch_dense(R, L, 0), M, rtol=0, atol=1e-14)
+    assert np.allclose(dense.monarch_dense(R, L, 1), M, rtol=0, atol=1e-14)
+    # columns of M through the oracle: fwd(I) = M^T
+    eye = np.eye(m * m)
+    for reading in READINGS:
+        assert np.allclose(oracle.fwd(eye, R, L, reading), M.T, rtol=0, atol=1e-13)
+
+
+def test_hand_fixture_square_m2(golden):
+    g = golden("square_m2.txt")
+    R = g["R"].reshape(2, 2, 2)
+    L = g["L"].reshape(2, 2, 2)
+    x = g["x"].reshape(1, 4)
+    for reading in READINGS:
+        assert np.array_equal(oracle.fwd(x, R, L, reading)[0], g["y"])
+        assert np.array_equal(oracle.fwd(np.eye(4), R, L, reading).T, g["M"].reshape(4, 4))
+    assert np.array_equal(dense.monarch_dense(R, L), g["M"].reshape(4, 4))
+
+
+def test_hand_fixture_rectangular(golden):
+    g = golden("rect_k2_p3_q4_s2.txt")
+    R = g["R"].reshape(2, 4, 3)
+    L = g["L"].reshape(2, 2, 4)
+    x = g["x"].reshape(1, 6)
+    assert np.array_equal(oracle.fwd(x, R, L, oracle.READING_A)[0], g["y_A"])
+    assert np.array_equal(oracle.fwd(x, R, L, oracle.READING_B)[0], g["y_B"])
+    # the permutation alone: identity L blocks are impossible here (s != q), so check pi directly
+    UA = np.array([g["Y1"][oracle.pi(f, 2, 4, oracle.READING_A)] for f in range(8)])
+    UB = np.array([g["Y1"][oracle.pi(f, 2, 4, oracle.READING_B)] for f in range(8)])
+    assert np.array_equal(UA, g["U_A"]) and np.array_equal(UB, g["U_B"])
+
+
+@pytest.mark.parametrize("m", [2, 3, 4, 7])
+def test_identity_blocks_square_give_identity(m):
+    """P = P^T is an involution (Section 3.1), so identity blocks give M = P P^T = I."""
+    eye_blocks = np.broadcast_to(np.eye(m), (m, m, m)).copy()
+    x = np.random.default_rng(m).standard_normal((4, m * m))
+    for reading in READINGS:
+        assert np.array_equal(oracle.fwd(x, eye_blocks, eye_blocks, reading), x)
+
+
+def test_identity_blocks_rectangular_grid_give_pure_permutation():
+    """k != q with identity blocks: reading A composes the same 'transpose a (k, .) grid' twice,
+    reading B composes it with its inverse."""
+    k, q = 2, 4
+    eye_blocks = np.broadcast_to(np.eye(q), (k, q, q)).copy()
+    x = np.arange(8, dtype=np.float64).reshape(1, 8)
+    assert np.array_equal(oracle.fwd(x, eye_blocks, eye_blocks, oracle.READING_A)[0],
+                          np.array([0, 2, 4, 6, 1, 3, 5, 7], dtype=np.float64))
+    assert np.array_equal(oracle.fwd(x, eye_blocks, eye_blocks, oracle.READING_B)[0], x[0])
+    # general (k, q): reading A == x.reshape(k,q).T.reshape(k,q).T (two grid transposes)
+    for (k, q) in [(3, 6), (4, 8), (2, 5)]:
+        eb = np.broadcast_to(np.eye(q), (k, q, q)).copy()
+        x = np.random.default_rng(k * q).standard_normal((2, k * q))
+        want = np.stack([row.reshape(k, q).T.ravel().reshape(k, q).T.ravel() for row in x])
+        assert np.array_equal(oracle.fwd(x, eb, eb, oracle.READING_A), want)
+        assert np.array_equal(oracle.fwd(x, eb, eb, oracle.READING_B), x)
+
+
+@pytest.mark.parametrize("m", [2, 3, 4, 8])
+def test_kronecker_special_case(m):
+    """All R blocks = Bm, all L blocks = A  =>  M = A (x) Bm   (from Eq. 1:
+    M[(l,j),(k,i)] = A[l,k] Bm[j,i]); numpy.kron is the independent routine."""
+    rng = np.random.default_rng(10 + m)
+    A = rng.standard_normal((m, m))
+    Bm = rng.standard_normal((m, m))
+    R = np.broadcast_to(Bm, (m, m, m)).copy()
+    L = np.broadcast_to(A, (m, m, m)).copy()
+    x = rng.standard_normal((5, m * m))
+    assert oracle.rel_fro(oracle.fwd(x, R, L), x @ np.kron(A, Bm).T) < 1e-13
+
+
+@pytest.mark.parametrize("m", [2, 4, 8, 16])
+def test_hadamard_is_monarch(m):
+    """Hadamard matrices are Monarch (Prop. 3.2 / butterfly containment): Sylvester
+    H_n = H_m (x) H_m.  Checked against scipy's Hadamard matrix and a textbook fast
+    Walsh-Hadamard transform; all values are small integers, so equality is exact."""
+    H = scipy.linalg.hadamard(m).astype(np.float64)
+    R = np.broadcast_to(H, (m, m, m)).copy()
+    L = np.broadcast_to(H, (m, m, m)).copy()
+    n = m * m
+    rng = np.random.default_rng(m)
+    x = rng.integers(-1, 2, size=(6, n)).astype(np.float64)
+    y = oracle.fwd(x, R, L)
+    assert np.array_equal(y, x @ scipy.linalg.hadamard(n).astype(np.float64).T)
+
+    def fwht(v):
+        v = v.copy()
+        h = 1
+        while h < len(v):
+            for i in range(0, len(v), 2 * h):
+                for j in range(i, i + h):
+                    a, b = v[j], v[j + h]
+                    v[j], v[j + h] = a + b, a - b
+            h *= 2
+        return v
+
+    assert np.array_equal(y, np.stack([fwht(r) for r in x]))
+    # H_n H_n = n I
+    assert np.array_equal(oracle.fwd(y, R, L), n * x)
+
+
+def test_single_block_is_two_dense_products():
+    """k = 1: both permutations are trivial, y = L0 (R0 x)."""
+    rng = np.random.default_rng(5)
+    x, R, L, _ = _rand(rng, 1, 5, 3, 4, B=6)
+    for reading in READINGS:
+        assert oracle.rel_fro(oracle.fwd(x, R, L, reading), x @ R[0].T @ L[0].T) < 1e-14
+
+
+@pytest.mark.parametrize("m", [3, 4])
+def test_rank_one_slices_of_square_monarch(m):
+    """Section 3.3: viewed as an m x m x m x m tensor, every slice M[:, j, k, :] has rank 1."""
+    rng = np.random.default_rng(m)
+    _, R, L, _ = _rand(rng, m, m, m, m)
+    M = oracle.fwd(np.eye(m * m), R, L).T.reshape(m, m, m, m)  # [l, j, k, i]
+    for j in range(m):
+        for k in range(m):
+            sv = np.linalg.svd(M[:, j, k, :], compute_uv=False)
+            assert sv[1] < 1e-12 * sv[0]
+
+
+def test_parameter_and_sparsity_count():
+    """Section 3.2.2: a square Monarch matrix has 2 n sqrt(n) parameters; with generic
+    factors every entry of M is a single product (Eq. 1) and therefore non-zero."""
+    m = 4
+    rng = np.random.default_rng(0)
+    _, R, L, _ = _rand(rng, m, m, m, m)
+    assert R.size + L.size == 2 * (m * m) * m
+    assert np.count_nonzero(oracle.fwd(np.eye(m * m), R, L)) == (m * m) ** 2
+
+
+@pytest.mark.parametrize("reading", READINGS)
+def test_forward_is_linear_in_each_argument(reading):
+    rng = np.random.default_rng(3)
+    k, p, q, s = 3, 4, 6, 5
+    x, R, L, _ = _rand(rng, k, p, q, s)
+    x2, R2, L2, _ = _rand(rng, k, p, q, s)
+    a, b = 0.7, -1.3
+    f = lambda x_, R_, L_: oracle.fwd(x_, R_, L_, reading)
+    assert oracle.rel_fro(f(a * x + b * x2, R, L), a * f(x, R, L) + b * f(x2, R, L)) < 1e-13
+    assert oracle.rel_fro(f(x, a * R + b * R2, L), a * f(x, R, L) + b * f(x, R2, L)) < 1e-13
+    assert oracle.rel_fro(f(x, R, a * L + b * L2), a * f(x, R, L) + b * f(x, R, L2)) < 1e-13
+
+
+def test_readings_are_inverse_permutations():
+    for (k, q) in [(2, 4), (3, 6), (4, 48), (5, 3), (4, 4)]:
+        A = [oracle.pi(f, k, q, 0) for f in range(k * q)]
+        Bp = [oracle.pi(f, k, q, 1) for f in range(k * q)]
+        assert sorted(A) == list(range(k * q))
+        assert all(Bp[A[f]] == f for f in range(k * q))
+        if k == q:
+            assert A == Bp
+
+
+# --------------------------------------------------------------- backward ----
+
+@pytest.mark.parametrize("reading", READINGS)
+@pytest.mark.parametrize("shape", [(2, 2, 2, 2), (3, 3, 3, 3)] + TINY_RECT)
+def test_bwd_matches_unit_step_finite_differences(shape, reading):
+    """loss = <dy, fwd(x; R, L)> is linear in each argument, so a one-sided difference
+    with step 1 in a single coordinate is the exact partial derivative."""
+    k, p, q, s = shape
+    rng = np.random.default_rng(sum(shape) + reading)
+    x, R, L, dy = _rand(rng, k, p, q, s, B=2)
+    dx, dR, dL = oracle.bwd(dy, x, R, L, reading)
+    base = float(np.sum(dy * oracle.fwd(x, R, L, reading)))
+
+    def loss(x_, R_, L_):
+        return float(np.sum(dy * oracle.fwd(x_, R_, L_, reading)))
+
+    for arr, grad, which in ((x, dx, 0), (R, dR, 1), (L, dL, 2)):
+        flat = arr.reshape(-1)
+        g = grad.reshape(-1)
+        for e in range(flat.size):
+            old = flat[e]
+            flat[e] = old + 1.0
+            fd = loss(x, R, L) - base
+            flat[e] = old
+            assert abs(fd - g[e]) <= 1e-10 * max(1.0, abs(g[e])), (which, e, fd, g[e])
+
+
+@pytest.mark.parametrize("reading", READINGS)
+@pytest.mark.parametrize("shape", [(3, 3, 3, 3)] + TINY_RECT)
+def test_bwd_matches_autograd_through_literal_definition(shape, reading):
+    """Independent derivation: torch autograd (float64, CPU) through the explicit dense
+    product Pout BD(L) Pmid BD(R) of Def. 3.1."""
+    torch = pytest.importorskip("torch")
+    k, p, q, s = shape
+    rng = np.random.default_rng(7 * sum(shape) + reading)
+    x, R, L, dy = _rand(rng, k, p, q, s, B=4)
+    xt, Rt, Lt = (torch.tensor(a, dtype=torch.float64, requires_grad=True) for a in (x, R, L))
+    Pmid = torch.tensor(dense.mid_perm(k, q, reading))
+    Pout = torch.tensor(dense.out_perm(k, s))
+    M = Pout @ torch.block_diag(*Lt) @ Pmid @ torch.block_diag(*Rt)
+    y = xt @ M.T
+    y.backward(torch.tensor(dy))
+    dx, dR, dL = oracle.bwd(dy, x, R, L, reading)
+    assert oracle.rel_fro(dx, xt.grad.numpy()) < 1e-13
+    assert oracle.rel_fro(dR, Rt.grad.numpy()) < 1e-13
+    assert oracle.rel_fro(dL, Lt.grad.numpy()) < 1e-13
+
+
+@pytest.mark.parametrize("reading", READINGS)
+def test_dx_is_the_transposed_dense_matrix(reading):
+    rng = np.random.default_rng(11)
+    k, p, q, s = 4, 3, 8, 2
+    x, R, L, dy = _rand(rng, k, p, q, s, B=5)
+    dx, _, _ = oracle.bwd(dy, x, R, L, reading)
+    assert oracle.rel_fro(dx, dy @ dense.monarch_dense(R, L, reading)) < 1e-13
+
+
+@pytest.mark.parametrize("shape", [(4, 4, 4, 4), (4, 12, 8, 20), (2, 6, 10, 4)])
+def test_adjoint_and_euler_identities(shape):
+    """<dy, y> = <dx, x> = <dR, R> = <dL, L> for the form that is linear in x, R and L."""
+    k, p, q, s = shape
+    rng = np.random.default_rng(sum(shape))
+    x, R, L, dy = _rand(rng, k, p, q, s, B=9)
+    for reading in READINGS:
+        y = oracle.fwd(x, R, L, reading)
+        dx, dR, dL = oracle.bwd(dy, x, R, L, reading)
+        ref = np.sum(dy * y)
+        for v in (np.sum(dx * x), np.sum(dR * R), np.sum(dL * L)):
+            assert abs(v - ref) < 1e-11 * abs(ref)
+
+
+def test_bwd_square_matches_einsum_of_section_3_3():
+    """Square case: z[l,j] = sum_{k,i} L[j,l,k] R[k,j,i] x[k,i]  (Section 3.3) differentiated
+    by hand: dR[k,j,i] = sum_b x[b,k,i] sum_l L[j,l,k] dz[b,l,j], etc., written as einsums."""
+    m = 4
+    rng = np.random.default_rng(2)
+    x, R, L, dy = _rand(rng, m, m, m, m, B=6)
+    X = x.reshape(-1, m, m)
+    dZ = dy.reshape(-1, m, m)
+    y = np.einsum("jlk,kji,bki->blj", L, R, X).reshape(-1, m * m)
+    assert oracle.rel_fro(oracle.fwd(x, R, L), y) < 1e-13
+    dx, dR, dL = oracle.bwd(dy, x, R, L)
+    assert oracle.rel_fro(dx, np.einsum("jlk,kji,blj->bki", L, R, dZ).reshape(-1, m * m)) < 1e-13
+    assert oracle.rel_fro(dR, np.einsum("jlk,bki,blj->kji", L, X, dZ)) < 1e-13
+    assert oracle.rel_fro(dL, np.einsum("kji,bki,blj->jlk", R, X, dZ)) < 1e-13
+
+
+def test_empty_batch_and_bad_shapes():
+    R = np.zeros((2, 4, 3))
+    L = np.zeros((2, 2, 4))
+    assert oracle.fwd(np.zeros((0, 6)), R, L).shape == (0, 4)
+    dx, dR, dL = oracle.bwd(np.zeros((0, 4)), np.zeros((0, 6)), R, L)
+    assert dx.shape == (0, 6) and not dR.any() and not dL.any()
+    with pytest.raises(ValueError):
+        oracle.fwd(np.zeros((1, 5)), R, L)
+    with pytest.raises(ValueError):
+        oracle.fwd(np.zeros((1, 6)), R, np.zeros((2, 2, 5)))
+
+
+def test_thread_count_does_not_change_results():
+    """The OpenMP split is over rows only; the weight-gradient partials are summed in a fixed
+    order, so results are reproducible run to run."""
+    rng = np.random.default_rng(9)
+    x, R, L, dy = _rand(rng, 4, 8, 8, 8, B=37)
+    a = oracle.bwd(dy, x, R, L)
+    b = oracle.bwd(dy, x, R, L)
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)
