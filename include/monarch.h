@@ -1,0 +1,126 @@
+/*
+ * monarch.h -- C ABI of the MI355X (gfx950) Monarch multiply library.
+ *
+ * The library applies a Monarch matrix  M = P L P^T R  (Dao et al., "Monarch:
+ * Expressive Structured Matrices for Efficient and Accurate Training",
+ * Definition 3.1) to a batch of row vectors, forward and backward.  R and L are
+ * block-diagonal, P is the "reshape as a grid, transpose, flatten" permutation.
+ * The rectangular / larger-block form used for Transformer layers (Section 3.1,
+ * "Extension to Rectangular Matrices") is covered by the same calls: both
+ * factors have k blocks, R's blocks are q x p and L's blocks are s x q.
+ *
+ * Operation (Section 3.3, "Steps to multiply x by a Monarch matrix", steps 1-3),
+ * for every row b of the batch, 0-based indices, p = n_in / k:
+ *
+ *   step 1   Y1[b][kk][j] = sum_{i<p} R[kk][j][i] * x[b][kk*p + i]        kk<k, j<q
+ *   P^T      U[b][c*q + r] = Y1[b][f mod k][f div k],  f = c*q + r        c<k,  r<q
+ *   step 2   W[b][c][l]   = sum_{r<q} L[c][l][r] * U[b][c*q + r]          l<s
+ *   step 3   y[b][l*k + c] = W[b][c][l]
+ *
+ * In the square case n = m^2, k = p = q = s = m this is literally
+ * z[l][j] = sum_k L[j][l][k] * (sum_i R[k][j][i] x[k][i]),  y[l*m + j] = z[l][j],
+ * i.e. Equation (1): M[l*m + j][k*m + i] = L[j][l][k] * R[k][j][i].
+ *
+ * The paper defines P only for the square case.  For k != q the default above
+ * takes the (k, q) grid of stage-1 outputs, transposes it to (q, k), flattens,
+ * and cuts the result into k chunks of length q.  MONARCH_FLAG_PERM_B selects
+ * the inverse permutation instead:  U[b][c*q + r] = Y1flat[b][r*k + c].
+ * The two agree whenever k == q.
+ *
+ * Layout: every tensor is dense, row-major, last index fastest.
+ *   x, dx  (batch, n_in)        R, dR  (k, q, n_in/k)
+ *   y, dy  (batch, k*s)         L, dL  (k, s, q)
+ * Element type is `dtype` for all of them: MONARCH_F32 = IEEE binary32,
+ * MONARCH_BF16 = the upper 16 bits of a binary32 stored as uint16_t.  Products
+ * are accumulated in fp32; in the bf16 path the on-chip intermediate between
+ * the two stages is rounded to bf16 (nearest even) and each output is rounded
+ * once on store.  With MONARCH_FLAG_WGRAD_F32, dR and dL are written as fp32
+ * regardless of dtype.
+ *
+ * Ownership: all pointers are DEVICE pointers owned by the caller, 16-byte
+ * aligned, valid until `stream` has passed the call.  Outputs must not alias
+ * inputs.  The library keeps no state, allocates nothing and frees nothing;
+ * scratch memory is the caller's `workspace` (monarch_bwd only).  All work is
+ * enqueued on `stream` (a hipStream_t passed as void*, NULL = the default
+ * stream) and the calls return without synchronising.
+ *
+ * Errors: every call returns MONARCH_OK (0) or a negative status.  Arguments
+ * are validated on the host before anything is launched, so the error paths
+ * need no GPU.  batch == 0 is a successful no-op (monarch_bwd then still
+ * zero-fills dR and dL).  Nothing is printed and nothing aborts.
+ */
+#ifndef MONARCH_H_
+#define MONARCH_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { MONARCH_F32 = 0, MONARCH_BF16 = 1 } monarch_dtype;
+
+enum {
+    MONARCH_OK = 0,
+    MONARCH_ERR_INVALID = -1,     /* null pointer, non-positive size, n_in % k != 0, bad dtype/flags */
+    MONARCH_ERR_UNSUPPORTED = -2, /* shape too large for any kernel of this build */
+    MONARCH_ERR_WORKSPACE = -3,   /* workspace missing, misaligned or too small */
+    MONARCH_ERR_HIP = -4          /* the HIP runtime refused a launch */
+};
+
+#define MONARCH_FLAG_WGRAD_F32 1u /* monarch_bwd: dR, dL are float even when dtype is bf16 */
+#define MONARCH_FLAG_PERM_B    2u /* use the inverse mid permutation (see above) */
+#define MONARCH_FLAG_GENERIC   4u /* force the shape-generic kernels (testing aid) */
+
+/* Forward: y = x M^T  (Section 3.3 steps 1-3; one fused pass, the intermediate
+ * Y1/U never leaves the chip).  x (batch, n_in), R (k, q, n_in/k), L (k, s, q),
+ * y (batch, k*s); all device pointers. */
+int monarch_fwd(const void* x, const void* R, const void* L, void* y,
+                int64_t batch, int n_in, int k, int q, int s,
+                monarch_dtype dtype, void* stream);
+
+/* Same as monarch_fwd with `flags` (MONARCH_FLAG_PERM_B, MONARCH_FLAG_GENERIC). */
+int monarch_fwd_ex(const void* x, const void* R, const void* L, void* y,
+                   int64_t batch, int n_in, int k, int q, int s,
+                   monarch_dtype dtype, void* stream, unsigned flags);
+
+/* Backward: the adjoint of steps 3, 2, P^T, 1 in that order (the paper obtains it
+ * by automatic differentiation, Section 4):
+ *   dW[b][c][l]  = dy[b][l*k + c]
+ *   dL[c][l][r]  = sum_b dW[b][c][l] * U[b][c*q + r]
+ *   dU[b][c*q+r] = sum_l L[c][l][r] * dW[b][c][l]
+ *   dY1          = inverse mid permutation of dU
+ *   dR[kk][j][i] = sum_b dY1[b][kk][j] * x[b][kk*p + i]
+ *   dx[b][kk*p+i]= sum_j R[kk][j][i] * dY1[b][kk][j]
+ * U is recomputed from x (no activation is saved by the forward call).  dx, dR
+ * and dL are overwritten, never accumulated into.  The batch reduction of dR/dL
+ * uses fp32 atomics across workgroups, so they are reproducible only up to
+ * fp32 summation order.  `workspace` must hold at least
+ * monarch_bwd_workspace_bytes(...) bytes (device memory, 256-byte aligned);
+ * its contents on entry are ignored and on exit are unspecified. */
+int monarch_bwd(const void* dy, const void* x, const void* R, const void* L,
+                void* dx, void* dR, void* dL,
+                int64_t batch, int n_in, int k, int q, int s,
+                monarch_dtype dtype, void* stream,
+                void* workspace, size_t workspace_bytes, unsigned flags);
+
+/* Bytes of device scratch monarch_bwd needs for this problem (0 on invalid arguments). */
+size_t monarch_bwd_workspace_bytes(int64_t batch, int n_in, int k, int q, int s,
+                                   monarch_dtype dtype, unsigned flags);
+
+/* Name of the kernel family the dispatcher picks for this problem: pass 0 = forward,
+ * 1 = backward.  Static string, never NULL ("invalid" / "unsupported" on bad input). */
+const char* monarch_kernel_name(int pass, int n_in, int k, int q, int s,
+                                monarch_dtype dtype, unsigned flags);
+
+/* Human-readable text for a status code.  Static string, never NULL. */
+const char* monarch_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int monarch_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MONARCH_H_ */

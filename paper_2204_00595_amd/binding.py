@@ -1,0 +1,170 @@
+"""Thin ctypes binding over libmonarch.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (``include/monarch.h``).
+PyTorch supplies device memory and the current HIP stream; all arithmetic runs in
+the library's kernels.  There is no fallback: if the library is missing, loading
+fails with an error that says how to build it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmonarch.so")
+
+MONARCH_F32 = 0
+MONARCH_BF16 = 1
+MONARCH_OK = 0
+MONARCH_ERR_INVALID = -1
+MONARCH_ERR_UNSUPPORTED = -2
+MONARCH_ERR_WORKSPACE = -3
+MONARCH_ERR_HIP = -4
+MONARCH_FLAG_WGRAD_F32 = 1
+MONARCH_FLAG_PERM_B = 2
+MONARCH_FLAG_GENERIC = 4
+
+# every symbol include/monarch.h declares
+EXPORTS = (
+    "monarch_fwd", "monarch_fwd_ex", "monarch_bwd", "monarch_bwd_workspace_bytes",
+    "monarch_kernel_name", "monarch_status_string", "monarch_version",
+)
+
+_lib = None
+
+
+class MonarchError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %d (%s)" % (where, status, monarch_status_string(status)))
+
+
+def lib() -> ctypes.CDLL:
+    """Load libmonarch.so (built in-tree by ``paper_2204_00595_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "%s is missing: build it with `python -m paper_2204_00595_amd.build` "
+                "(or __graft_entry__.build()); there is no fallback path" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, ci, cu, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint, ctypes.c_size_t
+        L.monarch_fwd.restype = ci
+        L.monarch_fwd.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp]
+        L.monarch_fwd_ex.restype = ci
+        L.monarch_fwd_ex.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp, cu]
+        L.monarch_bwd.restype = ci
+        L.monarch_bwd.argtypes = [vp] * 7 + [i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
+        L.monarch_bwd_workspace_bytes.restype = sz
+        L.monarch_bwd_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci, cu]
+        L.monarch_kernel_name.restype = ctypes.c_char_p
+        L.monarch_kernel_name.argtypes = [ci, ci, ci, ci, ci, ci, cu]
+        L.monarch_status_string.restype = ctypes.c_char_p
+        L.monarch_status_string.argtypes = [ci]
+        L.monarch_version.restype = ci
+        L.monarch_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return MONARCH_F32
+    if t.dtype == torch.bfloat16:
+        return MONARCH_BF16
+    raise TypeError("dtype must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _check(t: torch.Tensor, name: str, shape, dtype, device):
+    if not t.is_cuda or t.device != device:
+        raise ValueError("%s must live on %s" % (name, device))
+    if t.dtype != dtype:
+        raise TypeError("%s: dtype %s, expected %s" % (name, t.dtype, dtype))
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError("%s: shape %s, expected %s" % (name, tuple(t.shape), tuple(shape)))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+
+
+def _stream_ptr(stream) -> int:
+    st = torch.cuda.current_stream() if stream is None else stream
+    return int(st.cuda_stream)
+
+
+def monarch_version() -> int:
+    return int(lib().monarch_version())
+
+
+def monarch_status_string(status: int) -> str:
+    return lib().monarch_status_string(int(status)).decode()
+
+
+def monarch_kernel_name(pass_: int, n_in: int, k: int, q: int, s: int, dtype: int, flags: int = 0) -> str:
+    return lib().monarch_kernel_name(pass_, n_in, k, q, s, dtype, flags).decode()
+
+
+def monarch_bwd_workspace_bytes(batch: int, n_in: int, k: int, q: int, s: int, dtype: int, flags: int = 0) -> int:
+    return int(lib().monarch_bwd_workspace_bytes(batch, n_in, k, q, s, dtype, flags))
+
+
+def monarch_fwd(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.Tensor | None = None,
+                flags: int = 0, stream=None) -> torch.Tensor:
+    """y = x M^T.  x (B, k*p), R (k, q, p), L (k, s, q) on the GPU; returns y (B, k*s)."""
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    dev, dt = x.device, x.dtype
+    _check(x, "x", (B, k * p), dt, dev)
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    if y is None:
+        y = torch.empty((B, k * s), dtype=dt, device=dev)
+    _check(y, "y", (B, k * s), dt, dev)
+    with torch.cuda.device(dev):
+        if flags:
+            rc = lib().monarch_fwd_ex(x.data_ptr(), R.data_ptr(), L.data_ptr(), y.data_ptr(), B, k * p, k, q, s,
+                                      _dtype_code(x), _stream_ptr(stream), flags)
+        else:
+            rc = lib().monarch_fwd(x.data_ptr(), R.data_ptr(), L.data_ptr(), y.data_ptr(), B, k * p, k, q, s,
+                                   _dtype_code(x), _stream_ptr(stream))
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_fwd")
+    return y
+
+
+def monarch_bwd(dy: torch.Tensor, x: torch.Tensor, R: torch.Tensor, L: torch.Tensor,
+                dx: torch.Tensor | None = None, dR: torch.Tensor | None = None, dL: torch.Tensor | None = None,
+                workspace: torch.Tensor | None = None, flags: int = 0, stream=None):
+    """(dx, dR, dL) for upstream gradient dy (B, k*s).  Buffers are allocated when not given."""
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    dev, dt = x.device, x.dtype
+    _check(x, "x", (B, k * p), dt, dev)
+    _check(dy, "dy", (B, k * s), dt, dev)
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    gdt = torch.float32 if (flags & MONARCH_FLAG_WGRAD_F32) else dt
+    if dx is None:
+        dx = torch.empty_like(x)
+    if dR is None:
+        dR = torch.empty((k, q, p), dtype=gdt, device=dev)
+    if dL is None:
+        dL = torch.empty((k, s, q), dtype=gdt, device=dev)
+    _check(dx, "dx", (B, k * p), dt, dev)
+    _check(dR, "dR", (k, q, p), gdt, dev)
+    _check(dL, "dL", (k, s, q), gdt, dev)
+    need = monarch_bwd_workspace_bytes(B, k * p, k, q, s, _dtype_code(x), flags)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_ptr = workspace.data_ptr() if workspace is not None else 0
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(dev):
+        rc = lib().monarch_bwd(dy.data_ptr(), x.data_ptr(), R.data_ptr(), L.data_ptr(), dx.data_ptr(),
+                               dR.data_ptr(), dL.data_ptr(), B, k * p, k, q, s, _dtype_code(x),
+                               _stream_ptr(stream), ws_ptr, ws_len, flags)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_bwd")
+    return dx, dR, dL

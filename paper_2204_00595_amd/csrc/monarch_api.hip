@@ -1,0 +1,136 @@
+// C-ABI front end: argument validation, kernel-family dispatch, workspace sizing.
+// Everything here runs on the host; validation never touches the GPU.
+#include "../../include/monarch.h"
+#include "monarch_internal.h"
+
+using namespace monarch;
+
+namespace {
+
+constexpr unsigned kKnownFlags = MONARCH_FLAG_WGRAD_F32 | MONARCH_FLAG_PERM_B | MONARCH_FLAG_GENERIC;
+
+// Fills pb; returns MONARCH_OK or MONARCH_ERR_INVALID.
+int make_problem(Problem& pb, int64_t batch, int n_in, int k, int q, int s, int dtype, unsigned flags)
+{
+    if (batch < 0 || n_in <= 0 || k <= 0 || q <= 0 || s <= 0) return MONARCH_ERR_INVALID;
+    if (n_in % k != 0) return MONARCH_ERR_INVALID;
+    if (dtype != MONARCH_F32 && dtype != MONARCH_BF16) return MONARCH_ERR_INVALID;
+    if (flags & ~kKnownFlags) return MONARCH_ERR_INVALID;
+    // keep every per-row extent and weight count inside 31 bits
+    if ((int64_t)k * q > (1 << 24) || (int64_t)k * s > (1 << 24) || n_in > (1 << 24)) return MONARCH_ERR_UNSUPPORTED;
+    if ((int64_t)k * q * (n_in / k) > 0x7fffffffLL || (int64_t)k * s * q > 0x7fffffffLL) return MONARCH_ERR_UNSUPPORTED;
+    pb.B = batch;
+    pb.n_in = n_in;
+    pb.k = k;
+    pb.p = n_in / k;
+    pb.q = q;
+    pb.s = s;
+    pb.dtype = dtype;
+    pb.flags = flags;
+    return MONARCH_OK;
+}
+
+enum Family { FAM_NONE = 0, FAM_GENERIC, FAM_MFMA };
+
+Family pick_fwd(const Problem& pb)
+{
+    if (!(pb.flags & MONARCH_FLAG_GENERIC) && mfma_fwd_supported(pb)) return FAM_MFMA;
+    if (generic_fwd_supported(pb)) return FAM_GENERIC;
+    return FAM_NONE;
+}
+
+Family pick_bwd(const Problem& pb)
+{
+    if (!(pb.flags & MONARCH_FLAG_GENERIC) && mfma_bwd_supported(pb)) return FAM_MFMA;
+    if (generic_bwd_supported(pb)) return FAM_GENERIC;
+    return FAM_NONE;
+}
+
+bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+int monarch_fwd_ex(const void* x, const void* R, const void* L, void* y, int64_t batch, int n_in, int k,
+                   int q, int s, monarch_dtype dtype, void* stream, unsigned flags)
+{
+    Problem pb;
+    int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
+    if (rc) return rc;
+    if (flags & MONARCH_FLAG_WGRAD_F32) return MONARCH_ERR_INVALID;  // backward-only flag
+    if (!x || !R || !L || !y) return MONARCH_ERR_INVALID;
+    if (!aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(y, 16)) return MONARCH_ERR_INVALID;
+    const Family fam = pick_fwd(pb);
+    if (fam == FAM_NONE) return MONARCH_ERR_UNSUPPORTED;
+    if (batch == 0) return MONARCH_OK;
+    hipStream_t st = (hipStream_t)stream;
+    return fam == FAM_MFMA ? mfma_fwd(pb, x, R, L, y, st) : generic_fwd(pb, x, R, L, y, st);
+}
+
+int monarch_fwd(const void* x, const void* R, const void* L, void* y, int64_t batch, int n_in, int k,
+                int q, int s, monarch_dtype dtype, void* stream)
+{
+    return monarch_fwd_ex(x, R, L, y, batch, n_in, k, q, s, dtype, stream, 0u);
+}
+
+size_t monarch_bwd_workspace_bytes(int64_t batch, int n_in, int k, int q, int s, monarch_dtype dtype,
+                                   unsigned flags)
+{
+    Problem pb;
+    if (make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags)) return 0;
+    switch (pick_bwd(pb)) {
+        case FAM_MFMA: return mfma_bwd_workspace(pb);
+        case FAM_GENERIC: return generic_bwd_workspace(pb);
+        default: return 0;
+    }
+}
+
+int monarch_bwd(const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR, void* dL,
+                int64_t batch, int n_in, int k, int q, int s, monarch_dtype dtype, void* stream,
+                void* workspace, size_t workspace_bytes, unsigned flags)
+{
+    Problem pb;
+    int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
+    if (rc) return rc;
+    if (!dy || !x || !R || !L || !dx || !dR || !dL) return MONARCH_ERR_INVALID;
+    if (!aligned(dy, 16) || !aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(dx, 16) ||
+        !aligned(dR, 16) || !aligned(dL, 16))
+        return MONARCH_ERR_INVALID;
+    const Family fam = pick_bwd(pb);
+    if (fam == FAM_NONE) return MONARCH_ERR_UNSUPPORTED;
+    const size_t need = fam == FAM_MFMA ? mfma_bwd_workspace(pb) : generic_bwd_workspace(pb);
+    if (need > 0 && (!workspace || workspace_bytes < need || !aligned(workspace, 256)))
+        return MONARCH_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    if (fam == FAM_MFMA) return mfma_bwd(pb, dy, x, R, L, dx, dR, dL, workspace, st);
+    return generic_bwd(pb, dy, x, R, L, dx, dR, dL, workspace, st);
+}
+
+const char* monarch_kernel_name(int pass, int n_in, int k, int q, int s, monarch_dtype dtype, unsigned flags)
+{
+    Problem pb;
+    int rc = make_problem(pb, 1, n_in, k, q, s, (int)dtype, flags);
+    if (rc == MONARCH_ERR_UNSUPPORTED) return "unsupported";
+    if (rc || (pass != 0 && pass != 1)) return "invalid";
+    const Family fam = pass == 0 ? pick_fwd(pb) : pick_bwd(pb);
+    if (fam == FAM_GENERIC) return pass == 0 ? "generic_fwd" : "generic_bwd";
+    if (fam == FAM_MFMA) return pass == 0 ? mfma_fwd_name(pb) : mfma_bwd_name(pb);
+    return "unsupported";
+}
+
+const char* monarch_status_string(int status)
+{
+    switch (status) {
+        case MONARCH_OK: return "ok";
+        case MONARCH_ERR_INVALID: return "invalid argument";
+        case MONARCH_ERR_UNSUPPORTED: return "unsupported shape";
+        case MONARCH_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case MONARCH_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int monarch_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,357 @@
+// Shape-generic fused kernels for the Monarch multiply: any k, p, q, s, fp32 or bf16
+// storage, both readings of the mid permutation.  They are the fallback for shapes the
+// MFMA kernels do not cover; plain fp32 FMA, one workgroup per tile of BM batch rows,
+// the intermediate (Y1 / U of Section 3.3) lives in LDS only.
+#include "monarch_internal.h"
+#include "monarch_device.h"
+
+namespace monarch {
+
+static constexpr int kThreads = 256;
+
+// ------------------------------------------------------------------ utilities ----
+
+__global__ void fill_zero_f32_kernel(float* p, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = 0.f;
+}
+
+__global__ void fill_zero_u16_kernel(uint16_t* p, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = 0;
+}
+
+__global__ void f32_to_bf16_kernel(const float* src, uint16_t* dst, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] = f32_to_bf16(src[i]);
+}
+
+static int grid_for(size_t n)
+{
+    size_t g = (n + kThreads - 1) / kThreads;
+    if (g > 2048) g = 2048;
+    if (g < 1) g = 1;
+    return (int)g;
+}
+
+int launch_fill_zero_f32(float* p, size_t n, hipStream_t st)
+{
+    if (n == 0) return 0;
+    hipLaunchKernelGGL(fill_zero_f32_kernel, dim3(grid_for(n)), dim3(kThreads), 0, st, p, n);
+    return hip_status(hipGetLastError());
+}
+
+int launch_fill_zero_u16(uint16_t* p, size_t n, hipStream_t st)
+{
+    if (n == 0) return 0;
+    hipLaunchKernelGGL(fill_zero_u16_kernel, dim3(grid_for(n)), dim3(kThreads), 0, st, p, n);
+    return hip_status(hipGetLastError());
+}
+
+int launch_f32_to_bf16(const float* src, uint16_t* dst, size_t n, hipStream_t st)
+{
+    if (n == 0) return 0;
+    hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(grid_for(n)), dim3(kThreads), 0, st, src, dst, n);
+    return hip_status(hipGetLastError());
+}
+
+// -------------------------------------------------------------------- forward ----
+//
+// LDS: xs[BM][n_in] and us[BM][k*q], both fp32.  Each thread owns one output column at a
+// time and keeps BM row accumulators, so every weight is read once per workgroup.
+
+template <typename T, int BM>
+__global__ void __launch_bounds__(kThreads)
+generic_fwd_kernel(const T* __restrict__ x, const T* __restrict__ R, const T* __restrict__ L,
+                   T* __restrict__ y, int64_t B, int k, int p, int q, int s, int perm_b)
+{
+    extern __shared__ float lds[];
+    const int n_in = k * p, kq = k * q, n_out = k * s;
+    float* xs = lds;
+    float* us = lds + (size_t)BM * n_in;
+    const int64_t b0 = (int64_t)blockIdx.x * BM;
+    const int tid = threadIdx.x;
+
+    for (int e = tid; e < BM * n_in; e += kThreads) {
+        int b = e / n_in, c = e - b * n_in;
+        int64_t row = b0 + b;
+        xs[e] = row < B ? Elem<T>::load(x + row * n_in + c) : 0.f;
+    }
+    __syncthreads();
+
+    // step 1 (block-diagonal R) with the mid permutation folded into the LDS store
+    for (int f = tid; f < kq; f += kThreads) {
+        const int kk = f / q;
+        const T* Rrow = R + (size_t)f * p;
+        const float* xk = xs + kk * p;
+        float acc[BM];
+#pragma unroll
+        for (int b = 0; b < BM; ++b) acc[b] = 0.f;
+        for (int i = 0; i < p; ++i) {
+            const float w = Elem<T>::load(Rrow + i);
+#pragma unroll
+            for (int b = 0; b < BM; ++b) acc[b] = fmaf(w, xk[b * n_in + i], acc[b]);
+        }
+        const int g = mid_dest(f, k, q, perm_b != 0);
+#pragma unroll
+        for (int b = 0; b < BM; ++b) us[b * kq + g] = acc[b];
+    }
+    __syncthreads();
+
+    // step 2 (block-diagonal L) and step 3 (output index l*k + c)
+    for (int o = tid; o < n_out; o += kThreads) {
+        const int l = o / k, c = o - l * k;
+        const T* Lrow = L + ((size_t)c * s + l) * q;
+        const float* uc = us + c * q;
+        float acc[BM];
+#pragma unroll
+        for (int b = 0; b < BM; ++b) acc[b] = 0.f;
+        for (int r = 0; r < q; ++r) {
+            const float w = Elem<T>::load(Lrow + r);
+#pragma unroll
+            for (int b = 0; b < BM; ++b) acc[b] = fmaf(w, uc[b * kq + r], acc[b]);
+        }
+#pragma unroll
+        for (int b = 0; b < BM; ++b) {
+            int64_t row = b0 + b;
+            if (row < B) Elem<T>::store(y + row * n_out + o, acc[b]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------- backward ----
+//
+// LDS (fp32): xs[BM][n_in], us[BM][kq] (U recomputed), dws[BM][k*s] (dW[b][c*s+l]),
+// dus[BM][kq] (dU; dY1[f] is read back as dus[mid_dest(f)]).
+// dx is written directly; dR and dL contributions of the tile are added with fp32 atomics
+// into accumulators that the host zero-filled before the launch.
+
+template <typename T, int BM>
+__global__ void __launch_bounds__(kThreads)
+generic_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x, const T* __restrict__ R,
+                   const T* __restrict__ L, T* __restrict__ dx, float* __restrict__ dRacc,
+                   float* __restrict__ dLacc, int64_t B, int k, int p, int q, int s, int perm_b)
+{
+    extern __shared__ float lds[];
+    const int n_in = k * p, kq = k * q, n_out = k * s;
+    float* xs = lds;
+    float* us = xs + (size_t)BM * n_in;
+    float* dws = us + (size_t)BM * kq;
+    float* dus = dws + (size_t)BM * n_out;
+    const int64_t b0 = (int64_t)blockIdx.x * BM;
+    const int tid = threadIdx.x;
+    const bool pb = perm_b != 0;
+
+    for (int e = tid; e < BM * n_in; e += kThreads) {
+        int b = e / n_in, c = e - b * n_in;
+        int64_t row = b0 + b;
+        xs[e] = row < B ? Elem<T>::load(x + row * n_in + c) : 0.f;
+    }
+    for (int e = tid; e < BM * n_out; e += kThreads) {
+        int b = e / n_out, o = e - b * n_out;
+        int l = o / k, c = o - l * k;
+        int64_t row = b0 + b;
+        dws[b * n_out + c * s + l] = row < B ? Elem<T>::load(dy + row * n_out + o) : 0.f;
+    }
+    __syncthreads();
+
+    // recompute step 1 + mid permutation
+    for (int f = tid; f < kq; f += kThreads) {
+        const int kk = f / q;
+        const T* Rrow = R + (size_t)f * p;
+        const float* xk = xs + kk * p;
+        float acc[BM];
+#pragma unroll
+        for (int b = 0; b < BM; ++b) acc[b] = 0.f;
+        for (int i = 0; i < p; ++i) {
+            const float w = Elem<T>::load(Rrow + i);
+#pragma unroll
+            for (int b = 0; b < BM; ++b) acc[b] = fmaf(w, xk[b * n_in + i], acc[b]);
+        }
+        const int g = mid_dest(f, k, q, pb);
+#pragma unroll
+        for (int b = 0; b < BM; ++b) us[b * kq + g] = acc[b];
+    }
+    // adjoint of step 2: dU[c*q + r] = sum_l L[c][l][r] dW[c][l]
+    for (int g = tid; g < kq; g += kThreads) {
+        const int c = g / q, r = g - c * q;
+        const T* Lcol = L + (size_t)c * s * q + r;
+        const float* dwc = dws + c * s;
+        float acc[BM];
+#pragma unroll
+        for (int b = 0; b < BM; ++b) acc[b] = 0.f;
+        for (int l = 0; l < s; ++l) {
+            const float w = Elem<T>::load(Lcol + (size_t)l * q);
+#pragma unroll
+            for (int b = 0; b < BM; ++b) acc[b] = fmaf(w, dwc[b * n_out + l], acc[b]);
+        }
+#pragma unroll
+        for (int b = 0; b < BM; ++b) dus[b * kq + g] = acc[b];
+    }
+    __syncthreads();
+
+    // adjoint of step 1, data part: dx[kk*p + i] = sum_j R[kk][j][i] dY1[kk][j]
+    for (int n = tid; n < n_in; n += kThreads) {
+        const int kk = n / p, i = n - kk * p;
+        const T* Rcol = R + (size_t)kk * q * p + i;
+        float acc[BM];
+#pragma unroll
+        for (int b = 0; b < BM; ++b) acc[b] = 0.f;
+        for (int j = 0; j < q; ++j) {
+            const float w = Elem<T>::load(Rcol + (size_t)j * p);
+            const int g = mid_dest(kk * q + j, k, q, pb);
+#pragma unroll
+            for (int b = 0; b < BM; ++b) acc[b] = fmaf(w, dus[b * kq + g], acc[b]);
+        }
+#pragma unroll
+        for (int b = 0; b < BM; ++b) {
+            int64_t row = b0 + b;
+            if (row < B) Elem<T>::store(dx + row * n_in + n, acc[b]);
+        }
+    }
+    // weight gradients of this tile (rows beyond B contribute zeros)
+    const int nL = k * s * q;
+    for (int e = tid; e < nL; e += kThreads) {
+        const int cl = e / q, r = e - cl * q;
+        const int c = cl / s;
+        float v = 0.f;
+#pragma unroll
+        for (int b = 0; b < BM; ++b) v = fmaf(dws[b * n_out + cl], us[b * kq + c * q + r], v);
+        unsafeAtomicAdd(dLacc + e, v);
+    }
+    const int nR = kq * p;
+    for (int e = tid; e < nR; e += kThreads) {
+        const int f = e / p, i = e - f * p;
+        const int kk = f / q;
+        const int g = mid_dest(f, k, q, pb);
+        float v = 0.f;
+#pragma unroll
+        for (int b = 0; b < BM; ++b) v = fmaf(dus[b * kq + g], xs[b * n_in + kk * p + i], v);
+        unsafeAtomicAdd(dRacc + e, v);
+    }
+}
+
+// ------------------------------------------------------------------ launchers ----
+
+static int pick_bm(size_t floats_per_row)
+{
+    for (int bm = 8; bm >= 1; bm >>= 1)
+        if ((size_t)bm * floats_per_row * sizeof(float) <= kMaxLdsBytes) return bm;
+    return 0;
+}
+
+static size_t fwd_floats_per_row(const Problem& pb) { return (size_t)pb.n_in + pb.kq(); }
+static size_t bwd_floats_per_row(const Problem& pb)
+{
+    return (size_t)pb.n_in + 2 * (size_t)pb.kq() + pb.n_out();
+}
+
+bool generic_fwd_supported(const Problem& pb) { return pick_bm(fwd_floats_per_row(pb)) > 0; }
+bool generic_bwd_supported(const Problem& pb) { return pick_bm(bwd_floats_per_row(pb)) > 0; }
+
+size_t generic_bwd_workspace(const Problem& pb)
+{
+    if (pb.wgrad_f32()) return 0;  // atomics go straight into dR / dL
+    return align_up(pb.n_R() * sizeof(float), 256) + align_up(pb.n_L() * sizeof(float), 256);
+}
+
+template <typename T, int BM>
+static int launch_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y,
+                      hipStream_t st)
+{
+    const size_t lds = (size_t)BM * fwd_floats_per_row(pb) * sizeof(float);
+    auto kern = generic_fwd_kernel<T, BM>;
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return -4;
+    const int64_t grid = (pb.B + BM - 1) / BM;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, st, (const T*)x, (const T*)R,
+                       (const T*)L, (T*)y, pb.B, pb.k, pb.p, pb.q, pb.s, pb.perm_b() ? 1 : 0);
+    return hip_status(hipGetLastError());
+}
+
+template <typename T>
+static int dispatch_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y,
+                        hipStream_t st)
+{
+    switch (pick_bm(fwd_floats_per_row(pb))) {
+        case 8: return launch_fwd<T, 8>(pb, x, R, L, y, st);
+        case 4: return launch_fwd<T, 4>(pb, x, R, L, y, st);
+        case 2: return launch_fwd<T, 2>(pb, x, R, L, y, st);
+        case 1: return launch_fwd<T, 1>(pb, x, R, L, y, st);
+        default: return -2;
+    }
+}
+
+int generic_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
+{
+    if ((pb.B + 7) / 8 > 0x7fffffffLL) return -2;
+    return pb.dtype == 0 ? dispatch_fwd<float>(pb, x, R, L, y, st)
+                         : dispatch_fwd<bf16_t>(pb, x, R, L, y, st);
+}
+
+template <typename T, int BM>
+static int launch_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L,
+                      void* dx, float* dRacc, float* dLacc, hipStream_t st)
+{
+    const size_t lds = (size_t)BM * bwd_floats_per_row(pb) * sizeof(float);
+    auto kern = generic_bwd_kernel<T, BM>;
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return -4;
+    const int64_t grid = (pb.B + BM - 1) / BM;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, st, (const T*)dy, (const T*)x,
+                       (const T*)R, (const T*)L, (T*)dx, dRacc, dLacc, pb.B, pb.k, pb.p, pb.q, pb.s,
+                       pb.perm_b() ? 1 : 0);
+    return hip_status(hipGetLastError());
+}
+
+template <typename T>
+static int dispatch_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L,
+                        void* dx, float* dRacc, float* dLacc, hipStream_t st)
+{
+    switch (pick_bm(bwd_floats_per_row(pb))) {
+        case 8: return launch_bwd<T, 8>(pb, dy, x, R, L, dx, dRacc, dLacc, st);
+        case 4: return launch_bwd<T, 4>(pb, dy, x, R, L, dx, dRacc, dLacc, st);
+        case 2: return launch_bwd<T, 2>(pb, dy, x, R, L, dx, dRacc, dLacc, st);
+        case 1: return launch_bwd<T, 1>(pb, dy, x, R, L, dx, dRacc, dLacc, st);
+        default: return -2;
+    }
+}
+
+int generic_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L,
+                void* dx, void* dR, void* dL, void* ws, hipStream_t st)
+{
+    if ((pb.B + 7) / 8 > 0x7fffffffLL) return -2;
+    float* dRacc;
+    float* dLacc;
+    if (pb.wgrad_f32()) {
+        dRacc = (float*)dR;
+        dLacc = (float*)dL;
+    } else {
+        dRacc = (float*)ws;
+        dLacc = (float*)((char*)ws + align_up(pb.n_R() * sizeof(float), 256));
+    }
+    int rc = launch_fill_zero_f32(dRacc, pb.n_R(), st);
+    if (rc) return rc;
+    rc = launch_fill_zero_f32(dLacc, pb.n_L(), st);
+    if (rc) return rc;
+    if (pb.B > 0) {
+        rc = pb.dtype == 0 ? dispatch_bwd<float>(pb, dy, x, R, L, dx, dRacc, dLacc, st)
+                           : dispatch_bwd<bf16_t>(pb, dy, x, R, L, dx, dRacc, dLacc, st);
+        if (rc) return rc;
+    }
+    if (!pb.wgrad_f32()) {
+        rc = launch_f32_to_bf16(dRacc, (uint16_t*)dR, pb.n_R(), st);
+        if (rc) return rc;
+        rc = launch_f32_to_bf16(dLacc, (uint16_t*)dL, pb.n_L(), st);
+        if (rc) return rc;
+    }
+    return 0;
+}
+
+}  // namespace monarch

@@ -1,0 +1,53 @@
+// Internal interface between the C-ABI front end and the kernel families.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace monarch {
+
+struct Problem {
+    int64_t B;       // batch rows
+    int n_in, k, p, q, s;
+    int dtype;       // 0 = f32, 1 = bf16
+    unsigned flags;  // MONARCH_FLAG_*
+    int n_out() const { return k * s; }
+    int kq() const { return k * q; }
+    size_t esize() const { return dtype == 0 ? 4 : 2; }
+    bool perm_b() const { return (flags & 2u) != 0; }
+    bool wgrad_f32() const { return dtype == 0 || (flags & 1u) != 0; }
+    size_t n_R() const { return (size_t)k * q * p; }
+    size_t n_L() const { return (size_t)k * s * q; }
+};
+
+// LDS a workgroup may ask for on gfx950 (160 KiB per CU, one workgroup resident).
+constexpr size_t kMaxLdsBytes = 160 * 1024;
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- shape-generic SIMT kernels (any k, p, q, s; both permutation readings) ----
+bool generic_fwd_supported(const Problem& pb);
+bool generic_bwd_supported(const Problem& pb);
+size_t generic_bwd_workspace(const Problem& pb);
+int generic_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
+int generic_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L,
+                void* dx, void* dR, void* dL, void* ws, hipStream_t st);
+
+// ---- MFMA kernels for the shapes they are instantiated for (bf16 / fp32 matrix cores) ----
+bool mfma_fwd_supported(const Problem& pb);
+bool mfma_bwd_supported(const Problem& pb);
+size_t mfma_bwd_workspace(const Problem& pb);
+const char* mfma_fwd_name(const Problem& pb);
+const char* mfma_bwd_name(const Problem& pb);
+int mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
+int mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L,
+             void* dx, void* dR, void* dL, void* ws, hipStream_t st);
+
+// ---- small utility launches shared by the families ----
+int launch_fill_zero_f32(float* p, size_t n, hipStream_t st);
+int launch_fill_zero_u16(uint16_t* p, size_t n, hipStream_t st);
+int launch_f32_to_bf16(const float* src, uint16_t* dst, size_t n, hipStream_t st);
+
+static inline int hip_status(hipError_t e) { return e == hipSuccess ? 0 : -4; }
+
+}  // namespace monarch

@@ -1,0 +1,168 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports what the header
+declares, and rejects bad arguments before launching anything; the input generator is pinned."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2204_00595_amd import binding as b
+    if not os.path.exists(b.LIB_PATH):
+        from paper_2204_00595_amd import build
+        build.build()
+    return b
+
+
+def test_library_exports_every_declared_symbol(binding):
+    header = open(os.path.join(ROOT, "include", "monarch.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(monarch_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_version_and_status_strings(binding):
+    assert binding.monarch_version() >= 100
+    seen = set()
+    for code in (0, -1, -2, -3, -4):
+        sname = binding.monarch_status_string(code)
+        assert sname and sname != "unknown status"
+        seen.add(sname)
+    assert len(seen) == 5
+    assert binding.monarch_status_string(-99) == "unknown status"
+
+
+def test_forward_rejects_bad_arguments_without_a_gpu(binding):
+    L = binding.lib()
+    ok_ptr = 4096  # never dereferenced: validation fails first or batch == 0 returns early
+    args = dict(batch=0, n_in=768, k=4, q=192, s=192, dtype=1)
+
+    def call(x=ok_ptr, R=ok_ptr, Lp=ok_ptr, y=ok_ptr, flags=0, **kw):
+        a = dict(args, **kw)
+        return L.monarch_fwd_ex(x, R, Lp, y, a["batch"], a["n_in"], a["k"], a["q"], a["s"], a["dtype"], None, flags)
+
+    assert call() == binding.MONARCH_OK                      # empty batch: no-op
+    assert call(x=None) == binding.MONARCH_ERR_INVALID
+    assert call(R=None) == binding.MONARCH_ERR_INVALID
+    assert call(Lp=None) == binding.MONARCH_ERR_INVALID
+    assert call(y=None) == binding.MONARCH_ERR_INVALID
+    assert call(x=4098) == binding.MONARCH_ERR_INVALID       # misaligned
+    assert call(batch=-1) == binding.MONARCH_ERR_INVALID
+    assert call(n_in=770) == binding.MONARCH_ERR_INVALID     # n_in % k != 0
+    for key in ("n_in", "k", "q", "s"):
+        assert call(**{key: 0}) == binding.MONARCH_ERR_INVALID
+        assert call(**{key: -3}) == binding.MONARCH_ERR_INVALID
+    assert call(dtype=7) == binding.MONARCH_ERR_INVALID
+    assert call(flags=64) == binding.MONARCH_ERR_INVALID
+    assert call(flags=binding.MONARCH_FLAG_WGRAD_F32) == binding.MONARCH_ERR_INVALID
+    # a row far too wide for any kernel of this build
+    assert call(n_in=4 * 2000000, q=2000000, s=4) == binding.MONARCH_ERR_UNSUPPORTED
+    assert L.monarch_fwd(ok_ptr, ok_ptr, ok_ptr, ok_ptr, 0, 768, 4, 192, 192, 1, None) == binding.MONARCH_OK
+
+
+def test_backward_rejects_bad_arguments_without_a_gpu(binding):
+    L = binding.lib()
+    p = 4096
+
+    def call(ptrs=(p,) * 7, batch=1, n_in=768, k=4, q=192, s=192, dtype=1, ws=None, ws_bytes=0, flags=0):
+        return L.monarch_bwd(*ptrs, batch, n_in, k, q, s, dtype, None, ws, ws_bytes, flags)
+
+    for bad in range(7):
+        ptrs = [p] * 7
+        ptrs[bad] = None
+        assert call(tuple(ptrs)) == binding.MONARCH_ERR_INVALID
+    assert call(n_in=769) == binding.MONARCH_ERR_INVALID
+    assert call(flags=1024) == binding.MONARCH_ERR_INVALID
+    need = binding.monarch_bwd_workspace_bytes(1, 768, 4, 192, 192, 1, binding.MONARCH_FLAG_GENERIC)
+    assert need > 0
+    g = binding.MONARCH_FLAG_GENERIC
+    assert call(flags=g) == binding.MONARCH_ERR_WORKSPACE                          # none given
+    assert call(ws=4096, ws_bytes=need - 1, flags=g) == binding.MONARCH_ERR_WORKSPACE  # too small
+    assert call(ws=4096 + 16, ws_bytes=need, flags=g) == binding.MONARCH_ERR_WORKSPACE  # misaligned
+    assert binding.monarch_bwd_workspace_bytes(1, 769, 4, 192, 192, 1, 0) == 0
+
+
+def test_kernel_name_reports_dispatch(binding):
+    assert binding.monarch_kernel_name(0, 770, 4, 192, 192, 1) == "invalid"
+    assert binding.monarch_kernel_name(2, 768, 4, 192, 192, 1) == "invalid"
+    assert binding.monarch_kernel_name(0, 6, 2, 4, 2, 0) == "generic_fwd"
+    assert binding.monarch_kernel_name(1, 6, 2, 4, 2, 0) == "generic_bwd"
+    assert binding.monarch_kernel_name(0, 768, 4, 192, 192, 1, binding.MONARCH_FLAG_GENERIC) == "generic_fwd"
+    assert binding.monarch_kernel_name(0, 4 * 2000000, 4, 2000000, 4, 1) == "unsupported"
+
+
+def test_python_binding_fails_loudly_without_the_library(binding, monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        binding.lib()
+
+
+def test_product_package_never_touches_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2204_00595_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath:
+            continue
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, fn)).read()
+                for needle in ("import oracle", "from oracle", "monarch_oracle", "oracle/", "oracle."):
+                    assert needle not in text, (os.path.join(dirpath, fn), needle)
+
+
+# ------------------------------------------------------------ input generator ----
+
+def test_generator_is_counter_based_and_normal():
+    from paper_2204_00595_amd import synth
+    a = synth.normal(42, (200000,))
+    assert np.array_equal(a[:1000], synth.normal(42, (1000,)))          # prefix property
+    assert np.array_equal(a.reshape(400, 500), synth.normal(42, (400, 500)))
+    assert not np.array_equal(a[:1000], synth.normal(43, (1000,)))
+    assert abs(float(a.mean())) < 0.01 and abs(float(a.std()) - 1.0) < 0.01
+    assert abs(float(np.mean(a.astype(np.float64) ** 4)) - 3.0) < 0.1    # kurtosis of a normal
+    b = synth.normal(42, (200000,), std=0.25)
+    assert abs(float(b.std()) - 0.25) < 0.005
+
+
+def test_bf16_rounding_is_nearest_even_and_widening_is_exact():
+    from paper_2204_00595_amd import synth
+    # 1 + 2^-8 is a tie between 1.0 and 1 + 2^-7: even mantissa wins (1.0);
+    # 1 + 3*2^-8 is a tie between 1 + 2^-7 and 1 + 2^-6: even wins (1 + 2^-6).
+    vals = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, -2.5, 0.0, 3.0e38],
+                    dtype=np.float32)
+    got = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(vals))
+    want = np.array([1.0, 1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7, -2.5, 0.0, 2.9907e38], dtype=np.float32)
+    assert np.allclose(got[:6], want[:6], rtol=0, atol=0)
+    assert abs(float(got[6]) / 3.0e38 - 1) < 2.0 ** -8 and np.isfinite(got[6])
+    torch = pytest.importorskip("torch")
+    a = synth.normal(1, (50000,))
+    ref = torch.from_numpy(a).to(torch.bfloat16)
+    assert np.array_equal(synth.f32_to_bf16_bits(a), ref.view(torch.int16).numpy().view(np.uint16))
+    assert np.array_equal(synth.quantize(a, "bf16"), ref.float().numpy())
+    assert np.array_equal(synth.quantize(a, "f32"), a)
+
+
+def test_workload_table_matches_the_stated_shapes():
+    from paper_2204_00595_amd import synth
+    w = synth.WORKLOADS
+    assert (w["sq256_f32"].n_in, w["sq256_f32"].n_out, w["sq256_f32"].B) == (256, 256, 64)
+    assert (w["vitb_proj"].n_in, w["vitb_proj"].n_out, w["vitb_proj"].B) == (768, 768, 12608)
+    assert (w["gpt2s_fc1"].n_in, w["gpt2s_fc1"].n_out, w["gpt2s_fc1"].B) == (768, 3072, 8192)
+    assert (w["sq4096"].n_in, w["sq4096"].n_out, w["sq4096"].B) == (4096, 4096, 16384)
+    assert (w["gpt2m_fc1"].n_in, w["gpt2m_fc1"].n_out) == (1024, 4096)
+    assert (w["gpt2m_fc2"].n_in, w["gpt2m_fc2"].n_out) == (4096, 1024)
+    # square Monarch: 2 n sqrt(n) parameters, O(n sqrt n) work (Section 3.2.2)
+    sq = w["sq4096"]
+    assert sq.k * sq.q * (sq.p + sq.s) == 2 * 4096 * 64
+    assert sq.fwd_flops() == 2 * (2 * 4096 * 64) * sq.B
+    x, R, L, dy = synth.make_inputs(w["vitb_proj"], rows=8)
+    assert x.shape == (8, 768) and R.shape == (4, 192, 192) and L.shape == (4, 192, 192) and dy.shape == (8, 768)
+    assert abs(float(R.std()) - 192 ** -0.5) < 0.002
