@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the Monarch multiply hot path (forward + backward) on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input:
+monarch_fwd followed by monarch_bwd on the workload's shape, inputs resident in HBM.
+Prints ONE JSON line (see the keys below).  `--gpus N` with N > 1 is refused: the
+library is a single-GPU kernel library.
+
+Timing: K steps bracketed by torch.cuda.synchronize(); per-call durations come from HIP
+events recorded on the stream the kernels are launched on (torch's current stream).
+Buffers rotate through enough distinct (x, y, dy, dx) sets that the footprint exceeds the
+256 MB Infinity Cache, so repeats are served from HBM; the weights stay hot, as they would
+in training.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+ROTATE_BYTES = 1 << 30
+
+
+def _events(n):
+    import torch
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True):
+    import numpy as np
+    import torch
+    from paper_2204_00595_amd import binding, synth
+
+    sh = synth.WORKLOADS[name]
+    dt = torch.float32 if sh.dtype == "f32" else torch.bfloat16
+    code = 0 if sh.dtype == "f32" else 1
+    dev = torch.device("cuda:0")
+    gen_rows = min(sh.B, 65536)  # larger batches repeat a generated block (timing only)
+    x, R, L, dy = synth.make_inputs(sh, rows=gen_rows)
+    Rd, Ld = (torch.from_numpy(a).to(dev).to(dt) for a in (R, L))
+    x0 = torch.from_numpy(x).to(dev).to(dt).repeat(sh.B // gen_rows, 1)
+    dy0 = torch.from_numpy(dy).to(dev).to(dt).repeat(sh.B // gen_rows, 1)
+    per_set = sh.esize * sh.B * (2 * sh.n_in + 2 * sh.n_out)
+    nsets = max(2, min(64, -(-ROTATE_BYTES // per_set)))
+    sets = []
+    for i in range(nsets):
+        xs = x0 if i == 0 else x0.roll(i, 0).contiguous()
+        dys = dy0 if i == 0 else dy0.roll(i, 0).contiguous()
+        sets.append((xs, dys, torch.empty((sh.B, sh.n_out), dtype=dt, device=dev), torch.empty_like(xs)))
+    dR = torch.empty_like(Rd)
+    dL = torch.empty_like(Ld)
+    need = binding.monarch_bwd_workspace_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, code, 0)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+
+    def step(i, ev=None):
+        xs, dys, y, dx = sets[i % nsets]
+        if ev:
+            ev[0].record()
+        binding.monarch_fwd(xs, Rd, Ld, y)
+        if ev:
+            ev[1].record()
+        binding.monarch_bwd(dys, xs, Rd, Ld, dx, dR, dL, workspace=ws)
+        if ev:
+            ev[2].record()
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    # per-call durations (HIP events on the launch stream), same rotation
+    evs = [_events(3) for _ in range(steps)]
+    for i in range(steps):
+        step(i, evs[i])
+    torch.cuda.synchronize()
+    fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    bwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
+    fwd_min = float(np.min([e[0].elapsed_time(e[1]) for e in evs]))
+    bwd_min = float(np.min([e[1].elapsed_time(e[2]) for e in evs]))
+
+    out = {
+        "workload": name, "ms_per_step": wall / steps * 1e3,
+        "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "fwd_ms_min": fwd_min, "bwd_ms_min": bwd_min,
+        "fwd_kernel": binding.monarch_kernel_name(0, sh.n_in, sh.k, sh.q, sh.s, code),
+        "bwd_kernel": binding.monarch_kernel_name(1, sh.n_in, sh.k, sh.q, sh.s, code),
+        "fwd_tflops": sh.fwd_flops() / (fwd_ms * 1e-3) / 1e12,
+        "bwd_tflops": sh.bwd_flops() / (bwd_ms * 1e-3) / 1e12,
+        "fwd_gbs": sh.fwd_bytes() / (fwd_ms * 1e-3) / 1e9,
+        "bwd_gbs": sh.bwd_bytes() / (bwd_ms * 1e-3) / 1e9,
+        "rotating_sets": nsets,
+    }
+    for ps, flops, nbytes, ms in (("fwd", sh.fwd_flops(), sh.fwd_bytes(), fwd_ms), ("bwd", sh.bwd_flops(), sh.bwd_bytes(), bwd_ms)):
+        t_hbm = nbytes / (HBM_PEAK_GBS * 1e9)
+        t_mfma = flops / (MFMA_PEAK_TFLOPS[sh.dtype] * 1e12)
+        out[ps + "_roofline_frac"] = max(t_hbm, t_mfma) / (ms * 1e-3)
+        out[ps + "_bound"] = "hbm" if t_hbm >= t_mfma else "mfma"
+
+    if with_dense:
+        # vendor dense GEMM of the same (B, n_in, n_out): 1 GEMM forward, 2 GEMMs backward
+        W = torch.randn(sh.n_out, sh.n_in, device=dev, dtype=dt)
+        for _ in range(3):
+            sets[0][0] @ W.t()
+        torch.cuda.synchronize()
+        ev = [_events(3) for _ in range(steps)]
+        for i in range(steps):
+            xs, dys, _, _ = sets[i % nsets]
+            ev[i][0].record()
+            xs @ W.t()
+            ev[i][1].record()
+            dys @ W
+            dys.t() @ xs
+            ev[i][2].record()
+        torch.cuda.synchronize()
+        out["dense_fwd_ms"] = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+        out["dense_bwd_ms"] = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+        out["speedup_vs_dense"] = (out["dense_fwd_ms"] + out["dense_bwd_ms"]) / (fwd_ms + bwd_ms)
+    return sh, out
+
+
+def cpu_baseline(name: str, budget_s: float = 15.0):
+    """The CPU oracle as it stands, timed on this host: forward + backward on the first rows of
+    the workload (as many rows as fit the time budget, at most the whole batch)."""
+    import oracle
+    from paper_2204_00595_amd import synth
+
+    sh = synth.WORKLOADS[name]
+    rows = min(sh.B, 1024)
+    x, R, L, dy = synth.make_inputs(sh, rows=rows)
+    t0 = time.perf_counter()
+    oracle.fwd(x, R, L)
+    oracle.bwd(dy, x, R, L)
+    probe = time.perf_counter() - t0
+    target = int(rows * budget_s / max(probe, 1e-3))
+    rows2 = max(rows, min(sh.B, target))
+    if rows2 != rows:
+        x, R, L, dy = synth.make_inputs(sh, rows=rows2)
+    t0 = time.perf_counter()
+    oracle.fwd(x, R, L)
+    oracle.bwd(dy, x, R, L)
+    dt_s = time.perf_counter() - t0
+    flops = (sh.fwd_flops() + sh.bwd_flops()) * rows2 / sh.B
+    return {"value": flops / dt_s / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "fwd+bwd of the first %d of %d rows of %s, fp64, %.2f s" % (rows2, sh.B, name, dt_s)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="vitb_proj")
+    ap.add_argument("--all", action="store_true", help="also time the other workloads (extra keys)")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.stderr.write("bench.py: this library runs on ONE GPU; --gpus N with N > 1 is not supported "
+                         "(the path shards over batch rows only, see DESIGN.md).\n")
+        sys.exit(2)
+    import torch
+    from paper_2204_00595_amd import binding
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py needs a GPU\n")
+        sys.exit(2)
+    binding.lib()
+
+    sh, r = run_workload(args.workload, args.steps, args.warmup, with_dense=not args.no_dense)
+    flops = sh.fwd_flops() + sh.bwd_flops()
+    nbytes = sh.fwd_bytes() + sh.bwd_bytes()
+    step_s = r["ms_per_step"] * 1e-3
+    # roofline of the dominant call (the one with the larger duration)
+    dom = "bwd" if r["bwd_ms"] >= r["fwd_ms"] else "fwd"
+    dom_bytes = sh.bwd_bytes() if dom == "bwd" else sh.fwd_bytes()
+    dom_flops = sh.bwd_flops() if dom == "bwd" else sh.fwd_flops()
+    dom_ms = r[dom + "_ms"]
+    if r[dom + "_bound"] == "hbm":
+        roof = {"bound": "hbm", "achieved": dom_bytes / (dom_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": dom_flops / (dom_ms * 1e-3) / 1e12,
+                "peak": MFMA_PEAK_TFLOPS[sh.dtype], "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = r[dom + "_kernel"]
+    roof["call"] = "monarch_" + dom
+    roof["avg_ms"] = dom_ms
+    line = {
+        "metric": "monarch_fwd_bwd_tflops", "value": flops / step_s / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": sh.dtype, "data": "synthetic",
+        "config": {"workload": "%s: k=%d p=%d q=%d s=%d (%d->%d), B=%d rows, fwd+bwd" % (
+            sh.name, sh.k, sh.p, sh.q, sh.s, sh.n_in, sh.n_out, sh.B)},
+        "gb_per_s": nbytes / step_s / 1e9,
+        "roofline": roof,
+        "detail": r,
+    }
+    if args.all:
+        others = {}
+        for name in ("sq256_f32", "sq256_f32_big", "gpt2s_fc1", "sq4096", "gpt2m_fc1", "gpt2m_fc2"):
+            if name != args.workload:
+                others[name] = run_workload(name, max(5, args.steps // 2), max(2, args.warmup // 2),
+                                            with_dense=not args.no_dense)[1]
+        line["other_workloads"] = others
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(args.workload)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -47,7 +47,8 @@
  * Errors: every call returns MONARCH_OK (0) or a negative status.  Arguments
  * are validated on the host before anything is launched, so the error paths
  * need no GPU.  batch == 0 is a successful no-op (monarch_bwd then still
- * zero-fills dR and dL).  Nothing is printed and nothing aborts.
+ * zero-fills dR and dL); the per-row pointers x, y, dy, dx may then be NULL.
+ * Nothing is printed and nothing aborts.
  */
 #ifndef MONARCH_H_
 #define MONARCH_H_

@@ -59,7 +59,7 @@ int monarch_fwd_ex(const void* x, const void* R, const void* L, void* y, int64_t
     int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
     if (rc) return rc;
     if (flags & MONARCH_FLAG_WGRAD_F32) return MONARCH_ERR_INVALID;  // backward-only flag
-    if (!x || !R || !L || !y) return MONARCH_ERR_INVALID;
+    if (!R || !L || ((!x || !y) && batch > 0)) return MONARCH_ERR_INVALID;
     if (!aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(y, 16)) return MONARCH_ERR_INVALID;
     const Family fam = pick_fwd(pb);
     if (fam == FAM_NONE) return MONARCH_ERR_UNSUPPORTED;
@@ -93,7 +93,7 @@ int monarch_bwd(const void* dy, const void* x, const void* R, const void* L, voi
     Problem pb;
     int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
     if (rc) return rc;
-    if (!dy || !x || !R || !L || !dx || !dR || !dL) return MONARCH_ERR_INVALID;
+    if (!R || !L || !dR || !dL || ((!dy || !x || !dx) && batch > 0)) return MONARCH_ERR_INVALID;
     if (!aligned(dy, 16) || !aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(dx, 16) ||
         !aligned(dR, 16) || !aligned(dL, 16))
         return MONARCH_ERR_INVALID;

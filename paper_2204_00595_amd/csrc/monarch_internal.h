@@ -43,6 +43,10 @@ int mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, voi
 int mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L,
              void* dx, void* dR, void* dL, void* ws, hipStream_t st);
 
+// bf16, k = 4, wide blocks: fused forward on 32x32x16 MFMA (monarch_mfma_fwd_wide.hip)
+bool fwd_wide_supported(const Problem& pb);
+int fwd_wide(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
+
 // ---- small utility launches shared by the families ----
 int launch_fill_zero_f32(float* p, size_t n, hipStream_t st);
 int launch_fill_zero_u16(uint16_t* p, size_t n, hipStream_t st);

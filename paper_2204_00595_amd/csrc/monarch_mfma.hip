@@ -1,14 +1,19 @@
-// MFMA kernel family: dispatch table (kernels are added per shape family).
+// MFMA kernel family: which shapes have a matrix-core kernel, and which one.
 #include "monarch_internal.h"
 
 namespace monarch {
 
-bool mfma_fwd_supported(const Problem&) { return false; }
+bool mfma_fwd_supported(const Problem& pb) { return fwd_wide_supported(pb); }
+const char* mfma_fwd_name(const Problem& pb) { return fwd_wide_supported(pb) ? "mfma_fwd_wide_bf16" : "unsupported"; }
+int mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
+{
+    if (fwd_wide_supported(pb)) return fwd_wide(pb, x, R, L, y, st);
+    return -2;
+}
+
 bool mfma_bwd_supported(const Problem&) { return false; }
 size_t mfma_bwd_workspace(const Problem&) { return 0; }
-const char* mfma_fwd_name(const Problem&) { return "unsupported"; }
 const char* mfma_bwd_name(const Problem&) { return "unsupported"; }
-int mfma_fwd(const Problem&, const void*, const void*, const void*, void*, hipStream_t) { return -2; }
 int mfma_bwd(const Problem&, const void*, const void*, const void*, const void*, void*, void*, void*, void*,
              hipStream_t)
 {

@@ -1,0 +1,54 @@
+// MFMA helpers for gfx950 (CDNA4): operand types, fragment loads, bf16 packing.
+//
+// Register layouts used throughout (64-lane wavefront, lane = threadIdx.x % 64):
+//   v_mfma_f32_32x32x16_bf16   A (32 x 16): lane holds row  lane%32, K-slots 8*(lane/32) .. +7
+//                              B (16 x 32): lane holds col  lane%32, K-slots 8*(lane/32) .. +7
+//                              D (32 x 32): acc[i] = D[8*(i/4) + 4*(lane/32) + i%4][lane%32]
+//   v_mfma_f32_16x16x32_bf16   A (16 x 32): row lane%16, K-slots 8*(lane/16) .. +7;  B likewise
+//                              D (16 x 16): acc[i] = D[4*(lane/16) + i][lane%16]
+//   v_mfma_f32_16x16x4_f32     A (16 x 4):  row lane%16, K-slot lane/16;             B likewise
+//                              D (16 x 16): acc[i] = D[4*(lane/16) + i][lane%16]
+// Which contraction index sits in which K-slot is free as long as A and B agree; the
+// kernels use that freedom to fold the Monarch permutations into the operand loads.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace monarch {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// two floats -> two bf16 (round to nearest even) packed in one dword, `lo` in the low half
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    f32x2 f = {lo, hi};
+    bf16x2 h = __builtin_convertvector(f, bf16x2);
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+__device__ __forceinline__ u32x4 ldg128(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
+__device__ __forceinline__ u32x4 lds128(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// (lo16 of a) | (lo16 of b) << 16   and   (hi16 of a) | (hi16 of b) << 16
+__device__ __forceinline__ uint32_t pick_lo16(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t pick_hi16(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+
+}  // namespace monarch

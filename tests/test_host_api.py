@@ -50,10 +50,11 @@ def test_forward_rejects_bad_arguments_without_a_gpu(binding):
         return L.monarch_fwd_ex(x, R, Lp, y, a["batch"], a["n_in"], a["k"], a["q"], a["s"], a["dtype"], None, flags)
 
     assert call() == binding.MONARCH_OK                      # empty batch: no-op
-    assert call(x=None) == binding.MONARCH_ERR_INVALID
+    assert call(x=None, y=None) == binding.MONARCH_OK        # ... and then x, y may be NULL
+    assert call(x=None, batch=1) == binding.MONARCH_ERR_INVALID
     assert call(R=None) == binding.MONARCH_ERR_INVALID
     assert call(Lp=None) == binding.MONARCH_ERR_INVALID
-    assert call(y=None) == binding.MONARCH_ERR_INVALID
+    assert call(y=None, batch=1) == binding.MONARCH_ERR_INVALID
     assert call(x=4098) == binding.MONARCH_ERR_INVALID       # misaligned
     assert call(batch=-1) == binding.MONARCH_ERR_INVALID
     assert call(n_in=770) == binding.MONARCH_ERR_INVALID     # n_in % k != 0
