@@ -47,6 +47,32 @@ int mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, co
 bool fwd_wide_supported(const Problem& pb);
 int fwd_wide(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
 
+// bf16, k = 4, wide blocks: backward (monarch_mfma_bwd_wide.hip)
+bool bwd_wide_supported(const Problem& pb);
+size_t bwd_wide_workspace(const Problem& pb);
+int bwd_wide(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx,
+             void* dR, void* dL, void* ws, hipStream_t st);
+
+// Batch-contracted GEMM for the weight gradients (monarch_mfma_wgrad.hip):
+//   P[z][g][m][n] = sum over the rows of batch chunk z of  A[row][g, m] * Bm[row][g, n]
+// A column (g, m):  a_g * g + m            (or 4*m + g when the four groups are interleaved)
+// Bm column (g, n): b_g * g + (n / seg_w) * b_seg + n % seg_w
+struct WgradDesc {
+    const uint16_t* A;
+    int64_t lda;
+    int a_g;
+    const uint16_t* Bm;
+    int64_t ldb;
+    int b_g, b_seg, seg_w;
+    int M, N, G;
+    float* P;
+    int64_t rows;
+    int rows_per_chunk;
+};
+bool wgrad_tile_ok(int M, int N, int seg_w, int* tm, int* tn);
+int wgrad_gemm(const WgradDesc& d, bool interleaved_a, int nz, hipStream_t st);
+int wgrad_reduce(const float* P, void* out, bool out_f32, int nz, size_t total, int N, int seg_w, hipStream_t st);
+
 // ---- small utility launches shared by the families ----
 int launch_fill_zero_f32(float* p, size_t n, hipStream_t st);
 int launch_fill_zero_u16(uint16_t* p, size_t n, hipStream_t st);

@@ -1,0 +1,259 @@
+// Weight gradients of the Monarch multiply as batched "TN" GEMMs on bf16 MFMA:
+//
+//     out[g][m][n] = sum_b  A[b][g, m] * Bm[b][g, n]            (contraction over the batch)
+//
+//   dL[c][l][r]  = sum_b dW[b][c][l] * U[b][c*q + r]     A = dy (column l*k + c),  Bm = U
+//   dR[kk][j][i] = sum_b dY1[b][kk][j] * x[b][kk*p + i]  A = dY1,                  Bm = x
+//
+// (the adjoints of steps 2 and 1 of Section 3.3).  Both operands are stored batch-major, i.e.
+// the contraction index is the slow one, so they are staged row-major in LDS with 16-byte
+// writes and read back with the transposing LDS load of gfx950 (ds_read_b64_tr_b16), which
+// hands every lane four consecutive batch rows of one feature: exactly the MFMA operand layout.
+//
+// One workgroup = four groups g (one per wave), each wave a TM x TN tile of its group's
+// output; the batch is split over gridDim.z chunks whose fp32 partial tiles are summed by
+// `wgrad_reduce_kernel`, which also undoes the column order used for dL and converts to the
+// output type.
+#include "monarch_internal.h"
+#include "monarch_mfma_common.h"
+
+namespace monarch {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+constexpr int KB = 32;  // batch rows per pipeline step
+
+// Transposing LDS read: within each 16 lanes, lane i receives element (i % 4) of lanes
+// i/4, 4 + i/4, 8 + i/4, 12 + i/4.
+__device__ __forceinline__ u32x2 lds_tr16(const uint16_t* p)
+{
+    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(const_cast<uint16_t*>(p)));
+    return __builtin_bit_cast(u32x2, v);
+}
+
+// MFMA operand (32 features x 16 batch rows) from a row-major LDS tile T[row][col]:
+// lane (f = lane % 32, h = lane / 32) gets T[k0 + 8h .. 8h+7][c0 + f].
+__device__ __forceinline__ bf16x8 frag_tr(const uint16_t* T, int stride, int k0, int c0, int lane)
+{
+    const int G = lane >> 4, j = lane & 15;
+    const uint16_t* p = T + (size_t)(k0 + 8 * (G >> 1) + (j >> 2)) * stride + c0 + 16 * (G & 1) + 4 * (j & 3);
+    const u32x2 lo = lds_tr16(p), hi = lds_tr16(p + 4 * stride);
+    const u32x4 v = {lo[0], lo[1], hi[0], hi[1]};
+    return as_bf16x8(v);
+}
+
+template <int TM, int TN, bool DEINT>
+__global__ void __launch_bounds__(256)
+wgrad_gemm_kernel(WgradDesc d)
+{
+    constexpr int MT = TM / 32, NT = TN / 32;
+    constexpr int SA = TM + 8, SB = TN + 8;  // LDS row strides (bf16 elements)
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+    uint16_t* As = lds;                        // [4][KB][SA]
+    uint16_t* Bs = lds + 4 * KB * SA;          // [4][KB][SB]
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tiles_n = d.N / TN;
+    const int m0 = (blockIdx.x / tiles_n) * TM, n0 = (blockIdx.x % tiles_n) * TN;
+    const int g0 = blockIdx.y * 4;
+    const int64_t row_lo = (int64_t)blockIdx.z * d.rows_per_chunk;
+    int64_t row_hi = row_lo + d.rows_per_chunk;
+    if (row_hi > d.rows) row_hi = d.rows;
+
+    // ---- per-thread load tasks (16-byte pieces; DEINT A: 64-byte runs holding 8 m x 4 groups) ----
+    constexpr int A_TASKS = DEINT ? (KB * TM / 8) : (4 * KB * TM / 8);
+    constexpr int B_TASKS = 4 * KB * TN / 8;
+    constexpr int A_PER = (A_TASKS + 255) / 256, B_PER = (B_TASKS + 255) / 256;
+    u32x4 areg[A_PER][DEINT ? 4 : 1], breg[B_PER];
+
+    auto load_step = [&](int64_t r0) {
+#pragma unroll
+        for (int t = 0; t < A_PER; ++t) {
+            const int task = tid + t * 256;
+            if (DEINT) {
+                const int r = task / (TM / 8), u = task % (TM / 8);
+                const int64_t row = r0 + r;
+                const bool ok = task < A_TASKS && row < row_hi;
+                const uint16_t* p = d.A + row * d.lda + (size_t)(m0 + 8 * u) * 4 + g0;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) areg[t][w] = ok ? ldg128(p + 8 * w) : u32x4{0, 0, 0, 0};
+            } else {
+                const int g = task / (KB * TM / 8), rem = task % (KB * TM / 8);
+                const int r = rem / (TM / 8), u = rem % (TM / 8);
+                const int64_t row = r0 + r;
+                const bool ok = task < A_TASKS && row < row_hi;
+                const uint16_t* p = d.A + row * d.lda + (size_t)(g0 + g) * d.a_g + m0 + 8 * u;
+                areg[t][0] = ok ? ldg128(p) : u32x4{0, 0, 0, 0};
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < B_PER; ++t) {
+            const int task = tid + t * 256;
+            const int g = task / (KB * TN / 8), rem = task % (KB * TN / 8);
+            const int r = rem / (TN / 8), u = rem % (TN / 8);
+            const int64_t row = r0 + r;
+            const bool ok = task < B_TASKS && row < row_hi;
+            const int n = n0 + 8 * u;
+            const uint16_t* p = d.Bm + row * d.ldb + (size_t)(g0 + g) * d.b_g + (size_t)(n / d.seg_w) * d.b_seg + (n % d.seg_w);
+            breg[t] = ok ? ldg128(p) : u32x4{0, 0, 0, 0};
+        }
+    };
+    auto store_step = [&]() {
+#pragma unroll
+        for (int t = 0; t < A_PER; ++t) {
+            const int task = tid + t * 256;
+            if (task >= A_TASKS) continue;
+            if (DEINT) {
+                const int r = task / (TM / 8), u = task % (TM / 8);
+                // the run holds elements e = 4*m' + c (m' = 0..7); gather the 8 m' of each group c
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    u32x4 v;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        const uint32_t lo = areg[t][w][c >> 1], hi = areg[t][w][2 + (c >> 1)];
+                        v[w] = (c & 1) ? pick_hi16(lo, hi) : pick_lo16(lo, hi);
+                    }
+                    *reinterpret_cast<u32x4*>(As + ((size_t)c * KB + r) * SA + 8 * u) = v;
+                }
+            } else {
+                const int g = task / (KB * TM / 8), rem = task % (KB * TM / 8);
+                const int r = rem / (TM / 8), u = rem % (TM / 8);
+                *reinterpret_cast<u32x4*>(As + ((size_t)g * KB + r) * SA + 8 * u) = areg[t][0];
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < B_PER; ++t) {
+            const int task = tid + t * 256;
+            if (task >= B_TASKS) continue;
+            const int g = task / (KB * TN / 8), rem = task % (KB * TN / 8);
+            const int r = rem / (TN / 8), u = rem % (TN / 8);
+            *reinterpret_cast<u32x4*>(Bs + ((size_t)g * KB + r) * SB + 8 * u) = breg[t];
+        }
+    };
+
+    f32x16 acc[MT * NT];
+#pragma unroll
+    for (int t = 0; t < MT * NT; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+
+    const uint16_t* Aw = As + (size_t)wave * KB * SA;
+    const uint16_t* Bw = Bs + (size_t)wave * KB * SB;
+    if (row_lo < row_hi) load_step(row_lo);
+    for (int64_t r0 = row_lo; r0 < row_hi; r0 += KB) {
+        __syncthreads();  // previous step's fragment reads are done
+        store_step();
+        __syncthreads();
+        if (r0 + KB < row_hi) load_step(r0 + KB);
+#pragma unroll
+        for (int ks = 0; ks < KB / 16; ++ks) {
+            bf16x8 af[MT], bfr[NT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) af[mt] = frag_tr(Aw, SA, ks * 16, mt * 32, lane);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) bfr[nt] = frag_tr(Bw, SB, ks * 16, nt * 32, lane);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) acc[mt * NT + nt] = mfma32(af[mt], bfr[nt], acc[mt * NT + nt]);
+        }
+    }
+
+    // partial tile: P[z][g][m][n]
+    const int ln = lane & 31, h = lane >> 5;
+    float* Pg = d.P + (((size_t)blockIdx.z * d.G + g0 + wave) * d.M) * d.N;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int m = m0 + mt * 32 + 8 * (i / 4) + 4 * h + (i % 4);
+                Pg[(size_t)m * d.N + n0 + nt * 32 + ln] = acc[mt * NT + nt][i];
+            }
+}
+
+// out[g][m][col(n)] = sum_z P[z][g][m][n];  col(n) = (n % seg_w) * (N / seg_w) + n / seg_w
+// (identity when seg_w == N).  OUT_F32: write float, else bf16.
+template <bool OUT_F32>
+__global__ void wgrad_reduce_kernel(const float* __restrict__ P, void* __restrict__ out, int nz,
+                                    size_t total, int N, int seg_w)
+{
+    const int nseg = N / seg_w;
+    size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; e < total; e += stride) {
+        float s = 0.f;
+        for (int z = 0; z < nz; ++z) s += P[(size_t)z * total + e];
+        const size_t rowbase = e / N * N;
+        const int n = (int)(e - rowbase);
+        const size_t o = rowbase + (size_t)(n % seg_w) * nseg + n / seg_w;
+        if (OUT_F32) {
+            ((float*)out)[o] = s;
+        } else {
+            const uint32_t pk = pack_bf16x2(s, 0.f);
+            ((uint16_t*)out)[o] = (uint16_t)(pk & 0xffffu);
+        }
+    }
+}
+
+template <int TM, int TN, bool DEINT>
+int launch_gemm(const WgradDesc& d, int nz, hipStream_t st)
+{
+    constexpr size_t lds = (size_t)4 * KB * (TM + 8 + TN + 8) * 2;
+    auto kern = wgrad_gemm_kernel<TM, TN, DEINT>;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return -4;
+    dim3 grid((d.M / TM) * (d.N / TN), d.G / 4, nz);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, d);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace
+
+bool wgrad_tile_ok(int M, int N, int seg_w, int* tm, int* tn)
+{
+    // tile shapes instantiated below; a tile's 8-column pieces must not straddle a segment
+    if (seg_w % 8 != 0) return false;
+    const int cand[][2] = {{96, 96}, {64, 128}, {128, 64}, {64, 64}, {32, 32}};
+    for (auto& c : cand)
+        if (M % c[0] == 0 && N % c[1] == 0) {
+            *tm = c[0];
+            *tn = c[1];
+            return true;
+        }
+    return false;
+}
+
+int wgrad_gemm(const WgradDesc& d, bool deint, int nz, hipStream_t st)
+{
+    int tm, tn;
+    if (!wgrad_tile_ok(d.M, d.N, d.seg_w, &tm, &tn) || d.G % 4 != 0) return -2;
+#define MONARCH_WG_CASE(TM_, TN_)                                                        \
+    if (tm == TM_ && tn == TN_)                                                          \
+        return deint ? launch_gemm<TM_, TN_, true>(d, nz, st) : launch_gemm<TM_, TN_, false>(d, nz, st);
+    MONARCH_WG_CASE(96, 96)
+    MONARCH_WG_CASE(64, 128)
+    MONARCH_WG_CASE(128, 64)
+    MONARCH_WG_CASE(64, 64)
+    MONARCH_WG_CASE(32, 32)
+#undef MONARCH_WG_CASE
+    return -2;
+}
+
+int wgrad_reduce(const float* P, void* out, bool out_f32, int nz, size_t total, int N, int seg_w, hipStream_t st)
+{
+    size_t g = (total + 255) / 256;
+    if (g > 4096) g = 4096;
+    if (out_f32)
+        hipLaunchKernelGGL(wgrad_reduce_kernel<true>, dim3((unsigned)g), dim3(256), 0, st, P, out, nz, total, N, seg_w);
+    else
+        hipLaunchKernelGGL(wgrad_reduce_kernel<false>, dim3((unsigned)g), dim3(256), 0, st, P, out, nz, total, N, seg_w);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace monarch
