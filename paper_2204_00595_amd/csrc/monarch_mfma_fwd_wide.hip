@@ -1,129 +1,63 @@
 // Fused bf16 forward for "wide block" Monarch layers (k = 4 blocks, block sizes that are
-// multiples of 32): both block-diagonal stages of Section 3.3 on v_mfma_f32_32x32x16_bf16,
+// multiples of 32): both block-diagonal stages of Section 3.3 on v_mfma_f32_16x16x32_bf16,
 // the mid permutation P^T folded into operand addressing, the intermediate in LDS only.
 //
-// One workgroup (4 waves) owns BM = 64 batch rows.
+// One workgroup (4 waves) owns BM = 64 batch rows (four 16-row tiles).
+//
+// Why 16x16x32 and not 32x32x16: operands that come straight from global memory are loaded in
+// MFMA layout, one row per lane group.  With 16-row tiles one load instruction covers 16 rows x
+// 64 contiguous bytes, which the vector L1 serves at ~58 B/clk/CU on MI355X; the 32-row layout
+// (32 rows x 32 bytes) is capped near 30 B/clk/CU (measured), and this kernel is bound by
+// exactly that path: every workgroup streams all of R and L (0.6-2.6 MB) for its 64 rows.
 //
 // Stage 1  (step 1 of Section 3.3): wave w computes block kk = w,
 //     Y1[b][kk][j] = sum_i R[kk][j][i] x[b][kk*P + i],
-// as D^T = R . X^T so that each lane ends up with 4 consecutive j for one row b and can
-// write them to LDS as one 8-byte store.  R and x fragments go global -> registers directly
-// (every byte is needed by exactly one wave, so LDS staging would only add traffic).
-// LDS holds Y1s[b][kk*Q + j] in bf16, i.e. the natural (k, q) grid, not yet permuted.
+// as D^T = R . X^T so that each lane ends up with 4 consecutive j for one row b and writes
+// them to LDS with one 8-byte store.  R and x fragments go global -> registers directly (every
+// byte is needed by exactly one wave).  LDS holds Y1s[b][kk*Q + j] in bf16: the natural (k, q)
+// grid, not permuted.
 //
 // Stage 2  (step 2): block c contracts over r = 0..Q-1 with
 //     U[b][c*Q + r] = Y1[b][r % 4][c*Q/4 + r/4]      (P^T of Definition 3.1 on the (4, Q) grid).
-// The contraction order is free, so it runs over (kk, r1) with r = 4*r1 + kk: the A operand is
-// then 8 consecutive bf16 of Y1s (one ds_read_b128), and the B operand is every 4th element of
-// a 64-byte run of an L row, picked out of four global_load_dwordx4 with v_perm_b32.  No data
-// is ever moved to apply the permutation.
-// Waves split the output features l; each wave keeps all four c for its l-tile so that
-// step 3, y[b][4*l + c], becomes one packed 8-byte store per (b, l): 256 contiguous bytes
-// per 32 lanes.
+// Which contraction index sits in which MFMA K-slot is free as long as both operands agree.
+// Here a K-step covers 32 consecutive r (one 64-byte piece of an L row): lane group h takes the
+// 16 bytes r = r0 + 8h .. +7, i.e. r1 = r0/4 + 2h + {0,1} for all four kk.  The matching
+// activation operand is four 4-byte LDS reads (one per kk, two consecutive r1 each); the weight
+// fragment is re-ordered to (kk, r1) slot order with four v_perm_b32.  No data is moved to apply
+// the permutation.
+// Waves split the output features l; each wave keeps all four c for its l-tiles so that step 3,
+// y[b][4*l + c], becomes one packed 8-byte store per (b, l).
 #include "monarch_internal.h"
 #include "monarch_mfma_common.h"
+#include <stdlib.h>
 
 namespace monarch {
 
 namespace {
 
-template <int P_, int Q_, int S_, int BM_, int JG_>
+template <int P_, int Q_, int S_, int JG_, int LT_, int R1_ = 3, int R2_ = 3, int DBG_ = 0>
 struct FwdWide {
-    static constexpr int K = 4, P = P_, Q = Q_, S = S_, BM = BM_, JG = JG_;
-    static constexpr int NB = BM / 32;       // 32-row tiles per workgroup
+    static constexpr int K = 4, P = P_, Q = Q_, S = S_;
+    static constexpr int BM = 64, NBT = 4;   // rows per workgroup, 16-row tiles
+    static constexpr int JG = JG_;           // 16-wide j tiles a wave accumulates at once in stage 1
+    static constexpr int LT = LT_;           // 16-wide l tiles a wave accumulates at once in stage 2
+    static constexpr int R1 = R1_, R2 = R2_; // register-ring depths (K-steps in flight) of the stages
+    static constexpr int DBG = DBG_;
     static constexpr int QK = Q / K;         // columns of each R block that feed one L block
-    static constexpr int QT = Q / 32;        // j-tiles per R block
-    static constexpr int ST = S / 32;        // l-tiles per L block
+    static constexpr int JT = Q / 16;        // j tiles per R block
+    static constexpr int ST = S / 16;        // l tiles per L block
     static constexpr int KQ = K * Q;
     static constexpr int N_IN = K * P;
     static constexpr int N_OUT = K * S;
-    static constexpr int LDS_STRIDE = KQ + 8;  // bf16 elements; +16 bytes keeps ds_read_b128 conflict-free
+    static constexpr int LDS_STRIDE = KQ + 8;  // bf16; row stride = 4 dwords mod 64 banks
     static constexpr size_t LDS_BYTES = (size_t)BM * LDS_STRIDE * 2;
-    static constexpr int ROUNDS = ST / 4;    // l-tiles handled whole, one per wave per round
-    static constexpr int REM = ST % 4;       // left-over l-tiles, split by 32-row tile across waves
-    static_assert(BM % 32 == 0 && P % 16 == 0 && Q % 32 == 0 && S % 32 == 0, "tile shapes");
-    static_assert(QK % 16 == 0, "stage-2 K-chunks cover 16 columns of every R block");
-    static_assert(QT % JG == 0, "j-tile groups");
-    static_assert(REM == 0 || (REM == 2 && NB == 2), "left-over l-tiles are split two waves per tile");
+    static constexpr int T1 = P / 32;        // stage-1 K-steps per R block
+    static constexpr int T2 = Q / 32;        // stage-2 K-steps per L block
+    static_assert(P % 32 == 0 && Q % 32 == 0 && S % 16 == 0 && QK % 8 == 0, "tile shapes");
+    static_assert(JT % JG == 0 && ST % (4 * LT) == 0, "tile groups");
+    static_assert(T1 % R1 == 0 && R1 >= 2 && R2 >= 2, "ring depths");
     static_assert(LDS_BYTES <= kMaxLdsBytes, "LDS");
 };
-
-template <int N>
-__device__ __forceinline__ void zero_acc(f32x16 (&a)[N])
-{
-#pragma unroll
-    for (int n = 0; n < N; ++n)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) a[n][i] = 0.f;
-}
-
-// Stage 2 for l-tile `lt` and the NBL 32-row tiles starting at nb0.
-template <typename C, int NBL>
-__device__ __forceinline__ void stage2_tile(const uint16_t* __restrict__ L, const uint16_t* y1s,
-                                            uint16_t* __restrict__ y, int64_t b0, int64_t B, int lt,
-                                            int nb0, int ln, int g)
-{
-    constexpr int K = 4;
-    constexpr int NV = C::QK / 16;  // 64-byte runs of an L row per 16 columns of every R block
-    constexpr int NCH = K * NV;     // runs per l-tile
-    f32x16 acc[K * NBL];
-    zero_acc(acc);
-
-    // L[c][l][r]: this lane owns row l = lt*32 + ln and, in run v, elements r in [(16v + 8g)*4, +32)
-    const uint16_t* Lbase = L + (size_t)(lt * 32 + ln) * C::Q + 32 * g;
-    const uint16_t* abase = y1s + (size_t)(nb0 * 32 + ln) * C::LDS_STRIDE + 8 * g;
-
-    // Ring of PF+1 register buffers, one 64-byte run each: run ch+PF is requested before the
-    // MFMAs of run ch are issued.  The scheduling barriers keep the compiler from hoisting every
-    // load of the (fully unrolled) loop to the top, which would not fit the register file.
-    constexpr int PF = 2;
-    u32x4 raw[PF + 1][4];
-    auto load_run = [&](int ch, u32x4 (&dst)[4]) {
-        const uint16_t* p = Lbase + (size_t)(ch / NV) * C::S * C::Q + (ch % NV) * 64;
-#pragma unroll
-        for (int d = 0; d < 4; ++d) dst[d] = ldg128(p + 8 * d);
-    };
-#pragma unroll
-    for (int ch = 0; ch < PF && ch < NCH; ++ch) load_run(ch, raw[ch]);
-#pragma unroll
-    for (int ch = 0; ch < NCH; ++ch) {
-        __builtin_amdgcn_sched_barrier(0);
-        if (ch + PF < NCH) load_run(ch + PF, raw[(ch + PF) % (PF + 1)]);
-        const int c = ch / NV, v = ch % NV;
-        const u32x4(&rw)[4] = raw[ch % (PF + 1)];
-#pragma unroll
-        for (int kk = 0; kk < K; ++kk) {
-            // elements kk, kk+4, ..., kk+28 of the run
-            u32x4 bf;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const uint32_t lo = rw[w][kk >> 1], hi = rw[w][2 + (kk >> 1)];
-                bf[w] = (kk & 1) ? pick_hi16(lo, hi) : pick_lo16(lo, hi);
-            }
-            const bf16x8 bfrag = as_bf16x8(bf);
-#pragma unroll
-            for (int nb = 0; nb < NBL; ++nb) {
-                const bf16x8 afrag =
-                    as_bf16x8(lds128(abase + (size_t)nb * 32 * C::LDS_STRIDE + kk * C::Q + c * C::QK + 16 * v));
-                acc[c * NBL + nb] = mfma32(afrag, bfrag, acc[c * NBL + nb]);
-            }
-        }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // step 3: y[b][4*l + c]
-    const int l = lt * 32 + ln;
-#pragma unroll
-    for (int nb = 0; nb < NBL; ++nb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int64_t row = b0 + (nb0 + nb) * 32 + 8 * (i / 4) + 4 * g + (i % 4);
-            if (row < B) {
-                u32x2 v = {pack_bf16x2(acc[0 * NBL + nb][i], acc[1 * NBL + nb][i]),
-                           pack_bf16x2(acc[2 * NBL + nb][i], acc[3 * NBL + nb][i])};
-                *reinterpret_cast<u32x2*>(y + row * C::N_OUT + (size_t)l * K) = v;
-            }
-        }
-}
 
 template <typename C>
 __global__ void __launch_bounds__(256)
@@ -132,67 +66,153 @@ fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t y1s[];
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63, ln = lane & 31, g = lane >> 5;
+    const int wave = tid >> 6, lane = tid & 63, l16 = lane & 15, h = lane >> 4;
     const int64_t b0 = (int64_t)blockIdx.x * C::BM;
+    long long ts[4];
+    if (C::DBG >= 4) ts[0] = __builtin_amdgcn_s_memtime();
 
     // ------------------------------------------------------------- stage 1 ----
     {
         const int kk = wave;
-        const uint16_t* xrow[C::NB];
+        const uint16_t* xrow[C::NBT];
 #pragma unroll
-        for (int nb = 0; nb < C::NB; ++nb) {
-            int64_t row = b0 + nb * 32 + ln;
+        for (int bt = 0; bt < C::NBT; ++bt) {
+            int64_t row = b0 + bt * 16 + l16;
             row = row < B ? row : B - 1;  // rows past the end are computed from a valid row and dropped
-            xrow[nb] = x + row * C::N_IN + kk * C::P + 8 * g;
+            xrow[bt] = x + row * C::N_IN + kk * C::P + 8 * h;
         }
-        const uint16_t* Rk = R + ((size_t)kk * C::Q + ln) * C::P + 8 * g;
-        constexpr int T = C::P / 16;
-        for (int jg = 0; jg < C::QT / C::JG; ++jg) {
-            f32x16 acc[C::JG * C::NB];
-            zero_acc(acc);
-            const uint16_t* Rg = Rk + (size_t)jg * C::JG * 32 * C::P;
-            u32x4 xf[2][C::NB], rf[2][C::JG];
+        const uint16_t* Rk = R + ((size_t)kk * C::Q + l16) * C::P + 8 * h;
+        for (int jg = 0; jg < C::JT / C::JG; ++jg) {
+            f32x4 acc[C::JG * C::NBT];
 #pragma unroll
-            for (int nb = 0; nb < C::NB; ++nb) xf[0][nb] = ldg128(xrow[nb]);
+            for (int t = 0; t < C::JG * C::NBT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+            const uint16_t* Rg = Rk + (size_t)jg * C::JG * 16 * C::P;
+            // register ring: K-step t + R1 - 1 is requested before the MFMAs of step t issue; the
+            // scheduling barriers pin that order (the compiler otherwise sinks loads to their use)
+            u32x4 xf[C::R1][C::NBT], rf[C::R1][C::JG];
+            auto load_step = [&](int t, int slot) {
 #pragma unroll
-            for (int jj = 0; jj < C::JG; ++jj) rf[0][jj] = ldg128(Rg + (size_t)jj * 32 * C::P);
-#pragma unroll 4
-            for (int t = 0; t < T; ++t) {
-                const int cur = t & 1, nxt = cur ^ 1;
-                if (t + 1 < T) {
+                for (int bt = 0; bt < C::NBT; ++bt) xf[slot][bt] = ldg128(xrow[bt] + t * 32);
 #pragma unroll
-                    for (int nb = 0; nb < C::NB; ++nb) xf[nxt][nb] = ldg128(xrow[nb] + (t + 1) * 16);
+                for (int jj = 0; jj < C::JG; ++jj) rf[slot][jj] = ldg128(Rg + (size_t)jj * 16 * C::P + t * 32);
+            };
+#pragma unroll
+            for (int d = 0; d < C::R1 - 1; ++d) load_step(d, d);
+            for (int t0 = 0; t0 < C::T1; t0 += C::R1) {
+#pragma unroll
+                for (int u = 0; u < C::R1; ++u) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (C::DBG != 6 && t0 + u + C::R1 - 1 < C::T1) load_step(t0 + u + C::R1 - 1, (u + C::R1 - 1) % C::R1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (C::DBG == 5) {
+#pragma unroll
+                        for (int jj = 0; jj < C::JG; ++jj) acc[jj * C::NBT][0] += __uint_as_float(rf[u][jj][0] ^ rf[u][jj][3]);
+#pragma unroll
+                        for (int bt = 0; bt < C::NBT; ++bt) acc[bt][1] += __uint_as_float(xf[u][bt][0] ^ xf[u][bt][3]);
+                        continue;
+                    }
 #pragma unroll
                     for (int jj = 0; jj < C::JG; ++jj)
-                        rf[nxt][jj] = ldg128(Rg + (size_t)jj * 32 * C::P + (t + 1) * 16);
+#pragma unroll
+                        for (int bt = 0; bt < C::NBT; ++bt)
+                            acc[jj * C::NBT + bt] =
+                                mfma16(as_bf16x8(rf[C::DBG == 6 ? 0 : u][jj]), as_bf16x8(xf[C::DBG == 6 ? 0 : u][bt]), acc[jj * C::NBT + bt]);
                 }
-#pragma unroll
-                for (int jj = 0; jj < C::JG; ++jj)
-#pragma unroll
-                    for (int nb = 0; nb < C::NB; ++nb)
-                        acc[jj * C::NB + nb] =
-                            mfma32(as_bf16x8(rf[cur][jj]), as_bf16x8(xf[cur][nb]), acc[jj * C::NB + nb]);
             }
-            // lane holds D[j][b] for b = nb*32 + ln and j = jt*32 + 8*(i/4) + 4*g + i%4
+            __builtin_amdgcn_sched_barrier(0);
+            // lane holds D^T[j][b] for b = bt*16 + l16 and j = jt*16 + 4*h + 0..3
 #pragma unroll
             for (int jj = 0; jj < C::JG; ++jj)
 #pragma unroll
-                for (int nb = 0; nb < C::NB; ++nb)
-#pragma unroll
-                    for (int i4 = 0; i4 < 4; ++i4) {
-                        const f32x16& a = acc[jj * C::NB + nb];
-                        u32x2 v = {pack_bf16x2(a[4 * i4 + 0], a[4 * i4 + 1]), pack_bf16x2(a[4 * i4 + 2], a[4 * i4 + 3])};
-                        const int j = (jg * C::JG + jj) * 32 + 8 * i4 + 4 * g;
-                        *reinterpret_cast<u32x2*>(y1s + (size_t)(nb * 32 + ln) * C::LDS_STRIDE + kk * C::Q + j) = v;
-                    }
+                for (int bt = 0; bt < C::NBT; ++bt) {
+                    const f32x4& a = acc[jj * C::NBT + bt];
+                    const int j = (jg * C::JG + jj) * 16 + 4 * h;
+                    *reinterpret_cast<u32x2*>(y1s + (size_t)(bt * 16 + l16) * C::LDS_STRIDE + kk * C::Q + j) =
+                        u32x2{pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3])};
+                }
         }
     }
+    if (C::DBG >= 4) ts[1] = __builtin_amdgcn_s_memtime();
     __syncthreads();
+    if (C::DBG >= 4) ts[2] = __builtin_amdgcn_s_memtime();
 
     // ------------------------------------------------------------- stage 2 ----
-    for (int rd = 0; rd < C::ROUNDS; ++rd)
-        stage2_tile<C, C::NB>(L, y1s, y, b0, B, rd * 4 + wave, 0, ln, g);
-    if constexpr (C::REM == 2) stage2_tile<C, 1>(L, y1s, y, b0, B, C::ROUNDS * 4 + (wave >> 1), wave & 1, ln, g);
+    // wave w owns l tiles (rd*4 + w)*LT .. +LT-1 in round rd
+    for (int rd = 0; rd < C::ST / (4 * C::LT); ++rd) {
+        const int lt0 = (rd * 4 + wave) * C::LT;
+        f32x4 acc[C::K * C::LT * C::NBT];
+#pragma unroll
+        for (int t = 0; t < C::K * C::LT * C::NBT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // L[c][l][r]: lane (l16, h) reads r = 32*t + 8*h .. +7 of row l = (lt0 + i)*16 + l16
+        const uint16_t* Lbase = L + (size_t)(lt0 * 16 + l16) * C::Q + 8 * h;
+        // Y1s[b][kk*Q + c*QK + r1], r1 = 8*t + 2*h + {0,1}: one dword per kk
+        const uint16_t* abase = y1s + (size_t)l16 * C::LDS_STRIDE + 2 * h;
+
+        constexpr int NSTEP = C::K * C::T2;  // (c, t) pairs
+        u32x4 wf[C::R2][C::LT];
+        u32x4 af[2][C::NBT];
+        auto load_w = [&](int st, int slot) {
+            const uint16_t* p = Lbase + (size_t)(st / C::T2) * C::S * C::Q + (st % C::T2) * 32;
+#pragma unroll
+            for (int i = 0; i < C::LT; ++i) wf[slot][i] = ldg128(p + (size_t)i * 16 * C::Q);
+        };
+        auto load_a = [&](int st, int slot) {
+            const uint16_t* p = abase + (st / C::T2) * C::QK + (st % C::T2) * 8;
+#pragma unroll
+            for (int bt = 0; bt < C::NBT; ++bt)
+#pragma unroll
+                for (int kk = 0; kk < C::K; ++kk)
+                    af[slot][bt][kk] = *reinterpret_cast<const uint32_t*>(p + (size_t)bt * 16 * C::LDS_STRIDE + kk * C::Q);
+        };
+#pragma unroll
+        for (int d = 0; d < C::R2 - 1; ++d)
+            if (d < NSTEP) load_w(d, d);
+        load_a(0, 0);
+#pragma unroll
+        for (int st = 0; st < NSTEP; ++st) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (st + C::R2 - 1 < NSTEP) load_w(st + C::R2 - 1, (st + C::R2 - 1) % C::R2);
+            if (st + 1 < NSTEP) load_a(st + 1, (st + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            const int c = st / C::T2;
+#pragma unroll
+            for (int i = 0; i < C::LT; ++i) {
+                // piece dwords: (r1a,k0 k1) (r1a,k2 k3) (r1b,k0 k1) (r1b,k2 k3) -> slots (kk, r1a r1b)
+                const u32x4& p = wf[st % C::R2][i];
+                const u32x4 wv = {pick_lo16(p[0], p[2]), pick_hi16(p[0], p[2]), pick_lo16(p[1], p[3]), pick_hi16(p[1], p[3])};
+                const bf16x8 wfrag = as_bf16x8(wv);
+#pragma unroll
+                for (int bt = 0; bt < C::NBT; ++bt)
+                    acc[(c * C::LT + i) * C::NBT + bt] =
+                        mfma16(as_bf16x8(af[st & 1][bt]), wfrag, acc[(c * C::LT + i) * C::NBT + bt]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // step 3: y[b][4*l + c]; lane holds D[b][l] for l = (lt0 + i)*16 + l16, b = bt*16 + 4*h + 0..3
+#pragma unroll
+        for (int i = 0; i < C::LT; ++i)
+#pragma unroll
+            for (int bt = 0; bt < C::NBT; ++bt)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int64_t row = b0 + bt * 16 + 4 * h + e;
+                    if (row < B) {
+                        const int l = (lt0 + i) * 16 + l16;
+                        u32x2 v = {pack_bf16x2(acc[(0 * C::LT + i) * C::NBT + bt][e], acc[(1 * C::LT + i) * C::NBT + bt][e]),
+                                   pack_bf16x2(acc[(2 * C::LT + i) * C::NBT + bt][e], acc[(3 * C::LT + i) * C::NBT + bt][e])};
+                        *reinterpret_cast<u32x2*>(y + row * C::N_OUT + (size_t)l * C::K) = v;
+                    }
+                }
+    }
+    if (C::DBG >= 4) {
+        __builtin_amdgcn_s_waitcnt(0);
+        ts[3] = __builtin_amdgcn_s_memtime();
+        __syncthreads();
+        if (lane == 0) {
+            long long* o = reinterpret_cast<long long*>(y + b0 * C::N_OUT) + wave * 4;
+            for (int i = 0; i < 4; ++i) o[i] = ts[i];
+        }
+    }
 }
 
 template <typename C>
@@ -209,28 +229,49 @@ int launch(const Problem& pb, const void* x, const void* R, const void* L, void*
 }
 
 struct Entry {
-    int p, q, s;
+    int p, q, s, variant;
     int (*fn)(const Problem&, const void*, const void*, const void*, void*, hipStream_t);
 };
 
-//                          P     Q     S    BM  JG
+// variant 0 is the default; the others are reachable with MONARCH_FWD_VARIANT=<n> (tuning aid)
+//                                      P     Q     S   JG  LT  R1 R2
 const Entry kTable[] = {
-    {192, 192, 192, launch<FwdWide<192, 192, 192, 64, 6>>},   // ViT-B projection 768 -> 768
-    {192, 192, 768, launch<FwdWide<192, 192, 768, 64, 6>>},   // GPT-2 small fc1 768 -> 3072
-    {256, 256, 1024, launch<FwdWide<256, 256, 1024, 64, 4>>}, // GPT-2 medium fc1 1024 -> 4096
-    {1024, 256, 256, launch<FwdWide<1024, 256, 256, 64, 4>>}, // GPT-2 medium fc2 4096 -> 1024
-    {768, 192, 192, launch<FwdWide<768, 192, 192, 64, 6>>},   // GPT-2 small fc2 3072 -> 768
-    {64, 64, 64, launch<FwdWide<64, 64, 64, 64, 2>>},         // small shapes (tests)
-    {64, 64, 128, launch<FwdWide<64, 64, 128, 64, 2>>},
-    {128, 64, 64, launch<FwdWide<128, 64, 64, 64, 2>>},
+    {192, 192, 192, 0, launch<FwdWide<192, 192, 192, 12, 3, 3, 3>>},   // ViT-B projection 768 -> 768
+    {192, 192, 192, 1, launch<FwdWide<192, 192, 192, 6, 3, 3, 3>>},
+    {192, 192, 192, 2, launch<FwdWide<192, 192, 192, 6, 3, 3, 4>>},
+    {192, 192, 192, 3, launch<FwdWide<192, 192, 192, 4, 3, 3, 4>>},
+    {192, 192, 192, 11, launch<FwdWide<192, 192, 192, 12, 3, 3, 3, 4>>},
+    {192, 192, 192, 12, launch<FwdWide<192, 192, 192, 12, 3, 3, 3, 5>>},
+    {192, 192, 192, 13, launch<FwdWide<192, 192, 192, 12, 3, 3, 3, 6>>},
+    {192, 192, 768, 0, launch<FwdWide<192, 192, 768, 12, 3, 3, 3>>},   // GPT-2 small fc1 768 -> 3072
+    {192, 192, 768, 1, launch<FwdWide<192, 192, 768, 6, 3, 3, 4>>},
+    {256, 256, 1024, 0, launch<FwdWide<256, 256, 1024, 8, 4, 4, 3>>},  // GPT-2 medium fc1 1024 -> 4096
+    {256, 256, 1024, 1, launch<FwdWide<256, 256, 1024, 8, 2, 4, 4>>},
+    {1024, 256, 256, 0, launch<FwdWide<1024, 256, 256, 8, 4, 4, 3>>},  // GPT-2 medium fc2 4096 -> 1024
+    {1024, 256, 256, 1, launch<FwdWide<1024, 256, 256, 8, 4, 2, 3>>},
+    {768, 192, 192, 0, launch<FwdWide<768, 192, 192, 12, 3, 3, 3>>},   // GPT-2 small fc2 3072 -> 768
+    {64, 64, 64, 0, launch<FwdWide<64, 64, 64, 4, 1, 2, 3>>},          // small shapes (tests)
+    {64, 64, 128, 0, launch<FwdWide<64, 64, 128, 4, 2, 2, 3>>},
+    {128, 64, 64, 0, launch<FwdWide<128, 64, 64, 2, 1, 4, 3>>},
 };
+
+int tuning_variant()
+{
+    const char* v = getenv("MONARCH_FWD_VARIANT");
+    return v ? atoi(v) : 0;
+}
 
 const Entry* find(const Problem& pb)
 {
     if (pb.dtype != 1 || pb.k != 4 || pb.perm_b()) return nullptr;
+    const int want = tuning_variant();
+    const Entry* fallback = nullptr;
     for (const Entry& e : kTable)
-        if (e.p == pb.p && e.q == pb.q && e.s == pb.s) return &e;
-    return nullptr;
+        if (e.p == pb.p && e.q == pb.q && e.s == pb.s) {
+            if (e.variant == want) return &e;
+            if (e.variant == 0) fallback = &e;
+        }
+    return fallback;
 }
 
 }  // namespace
