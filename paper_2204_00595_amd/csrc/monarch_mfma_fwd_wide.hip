@@ -1,32 +1,34 @@
 // Fused bf16 forward for "wide block" Monarch layers (k = 4 blocks, block sizes that are
-// multiples of 32): both block-diagonal stages of Section 3.3 on v_mfma_f32_16x16x32_bf16,
+// multiples of 32): both block-diagonal stages of Section 3.3 on v_mfma_f32_32x32x16_bf16,
 // the mid permutation P^T folded into operand addressing, the intermediate in LDS only.
 //
-// One workgroup (4 waves) owns BM = 64 batch rows (four 16-row tiles).
+// One workgroup (4 waves) owns BM = 64 batch rows (two 32-row tiles).
 //
-// Why 16x16x32 and not 32x32x16: operands that come straight from global memory are loaded in
-// MFMA layout, one row per lane group.  With 16-row tiles one load instruction covers 16 rows x
-// 64 contiguous bytes, which the vector L1 serves at ~58 B/clk/CU on MI355X; the 32-row layout
-// (32 rows x 32 bytes) is capped near 30 B/clk/CU (measured), and this kernel is bound by
-// exactly that path: every workgroup streams all of R and L (0.6-2.6 MB) for its 64 rows.
+// Data movement.  Every workgroup streams all of R and L (0.6-2.6 MB) plus its rows of x through
+// the vector L1, and that path is what bounds the kernel.  The L1 serves about one cache-line
+// access per clock, so operands are fetched with adjacent lanes on adjacent 16-byte pieces
+// (16 rows x 64 contiguous bytes per instruction = full rate) and written straight into LDS
+// (global_load_lds_dwordx4, no VGPR staging); the MFMA fragments are then read back from LDS in
+// operand layout (row = lane % 32).  Loading fragments directly from global in operand layout
+// touches 64 lines per instruction and runs at a quarter of that rate (measured).
+// LDS staging blocks are 16 rows x 64 bytes = 1 KiB; the four 16-byte pieces of a row are stored
+// XOR-swizzled with bits 2..3 of the row so that ds_read_b128 of a fragment is conflict-free.
 //
 // Stage 1  (step 1 of Section 3.3): wave w computes block kk = w,
 //     Y1[b][kk][j] = sum_i R[kk][j][i] x[b][kk*P + i],
-// as D^T = R . X^T so that each lane ends up with 4 consecutive j for one row b and writes
-// them to LDS with one 8-byte store.  R and x fragments go global -> registers directly (every
-// byte is needed by exactly one wave).  LDS holds Y1s[b][kk*Q + j] in bf16: the natural (k, q)
-// grid, not permuted.
+// as D^T = R . X^T, accumulating all Q columns in registers while its private LDS ring holds
+// 32-column chunks of R[kk] and x.  When every wave is done the staging space is recycled:
+// Y1 is written to LDS as Y1s[b][kk*Q + j] in bf16 (8-byte stores, natural (k, q) grid).
 //
 // Stage 2  (step 2): block c contracts over r = 0..Q-1 with
 //     U[b][c*Q + r] = Y1[b][r % 4][c*Q/4 + r/4]      (P^T of Definition 3.1 on the (4, Q) grid).
 // Which contraction index sits in which MFMA K-slot is free as long as both operands agree.
-// Here a K-step covers 32 consecutive r (one 64-byte piece of an L row): lane group h takes the
-// 16 bytes r = r0 + 8h .. +7, i.e. r1 = r0/4 + 2h + {0,1} for all four kk.  The matching
-// activation operand is four 4-byte LDS reads (one per kk, two consecutive r1 each); the weight
-// fragment is re-ordered to (kk, r1) slot order with four v_perm_b32.  No data is moved to apply
-// the permutation.
-// Waves split the output features l; each wave keeps all four c for its l-tiles so that step 3,
-// y[b][4*l + c], becomes one packed 8-byte store per (b, l).
+// A K-step covers 16 consecutive r of an L row; lane group g takes the 16 bytes r = r0 + 8g .. +7,
+// i.e. r1 = r0/4 + 2g + {0,1} for all four kk.  The matching activation operand is four 4-byte LDS
+// reads of Y1s (one per kk); the weight fragment is re-ordered to (kk, r1) slot order with four
+// v_perm_b32.  No data is moved to apply the permutation.
+// Work is split over waves in units of (32 features l) x (32 rows); every wave keeps all four c of
+// its units so that step 3, y[b][4*l + c], is one packed 8-byte store per (b, l).
 #include "monarch_internal.h"
 #include "monarch_mfma_common.h"
 #include <stdlib.h>
@@ -35,38 +37,161 @@ namespace monarch {
 
 namespace {
 
-template <int P_, int Q_, int S_, int JG_, int LT_, int R1_ = 3, int R2_ = 3, int DBG_ = 0>
+template <int P_, int Q_, int S_, int UPW_, int D2_ = 3, int DBG_ = 0>
 struct FwdWide {
     static constexpr int K = 4, P = P_, Q = Q_, S = S_;
-    static constexpr int BM = 64, NBT = 4;   // rows per workgroup, 16-row tiles
-    static constexpr int JG = JG_;           // 16-wide j tiles a wave accumulates at once in stage 1
-    static constexpr int LT = LT_;           // 16-wide l tiles a wave accumulates at once in stage 2
-    static constexpr int R1 = R1_, R2 = R2_; // register-ring depths (K-steps in flight) of the stages
+    static constexpr int BM = 64, NB = 2;     // rows per workgroup, 32-row tiles
+    static constexpr int UPW = UPW_;          // stage-2 units (32 l x 32 rows) per wave per pass
+    static constexpr int D1 = 2, D2 = D2_;    // LDS ring depths (chunks in flight) of the two stages
     static constexpr int DBG = DBG_;
-    static constexpr int QK = Q / K;         // columns of each R block that feed one L block
-    static constexpr int JT = Q / 16;        // j tiles per R block
-    static constexpr int ST = S / 16;        // l tiles per L block
+    static constexpr int QK = Q / K;          // columns of each R block that feed one L block
+    static constexpr int QT = Q / 32;         // 32-wide j tiles per R block
     static constexpr int KQ = K * Q;
-    static constexpr int N_IN = K * P;
-    static constexpr int N_OUT = K * S;
-    static constexpr int LDS_STRIDE = KQ + 8;  // bf16; row stride = 4 dwords mod 64 banks
-    static constexpr size_t LDS_BYTES = (size_t)BM * LDS_STRIDE * 2;
-    static constexpr int T1 = P / 32;        // stage-1 K-steps per R block
-    static constexpr int T2 = Q / 32;        // stage-2 K-steps per L block
-    static_assert(P % 32 == 0 && Q % 32 == 0 && S % 16 == 0 && QK % 8 == 0, "tile shapes");
-    static_assert(JT % JG == 0 && ST % (4 * LT) == 0, "tile groups");
-    static_assert(T1 % R1 == 0 && R1 >= 2 && R2 >= 2, "ring depths");
+    static constexpr int N_IN = K * P, N_OUT = K * S;
+    static constexpr int T1 = P / 32;         // stage-1 chunks (32 columns of R / x each)
+    static constexpr int TQ = Q / 32;         // stage-2 chunks per L block (32 columns of L each)
+    static constexpr int NBLK1 = 2 * QT + 4;  // 1 KiB staging blocks per stage-1 chunk: R rows, then x rows
+    static constexpr int UNITS = (S / 32) * NB;
+    static constexpr int PASSES = UNITS / (4 * UPW);
+    static constexpr int NLT = (UPW + 1) / 2; // l tiles a wave touches in one pass
+    static constexpr int NBLK2 = 2 * NLT;     // staging blocks per stage-2 chunk
+    static constexpr int Y1_STRIDE = KQ + 4;  // bf16; row stride = 2 dwords mod 64 banks
+    static constexpr size_t LDS_Y1 = ((size_t)BM * Y1_STRIDE * 2 + 1023) / 1024 * 1024;
+    static constexpr size_t STG1 = (size_t)D1 * NBLK1 * 1024;  // per wave
+    static constexpr size_t STG2 = (size_t)D2 * NBLK2 * 1024;  // per wave
+    static constexpr size_t LDS_S1 = 4 * STG1, LDS_S2 = LDS_Y1 + 4 * STG2;
+    static constexpr size_t LDS_BYTES = LDS_S1 > LDS_S2 ? LDS_S1 : LDS_S2;
+    static_assert(P % 32 == 0 && Q % 32 == 0 && S % 32 == 0 && QK % 8 == 0, "tile shapes");
+    static_assert(UNITS % (4 * UPW) == 0 && UPW >= 1 && UPW <= 4, "stage-2 split");
     static_assert(LDS_BYTES <= kMaxLdsBytes, "LDS");
 };
+
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt = simm16[3:0] | simm16[15:14] << 4)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+
+// one global_load_lds_dwordx4: every lane fetches 16 bytes from its own address, the wave's 1 KiB
+// lands contiguously at `lds_block` (+ lane * 16)
+__device__ __forceinline__ void dma16(const uint16_t* gsrc, uint16_t* lds_block)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                     (__attribute__((address_space(3))) void*)lds_block, 16, 0, 0);
+}
+
+// Stage 2 for one pass of one wave: units u0 .. u0+UPW-1, unit u = (l tile u / 2, row tile u % 2).
+template <typename C, bool ODD>
+__device__ __forceinline__ void stage2_pass(const uint16_t* __restrict__ L, const uint16_t* y1s, uint16_t* stg,
+                                            uint16_t* __restrict__ y, int64_t b0, int64_t B, int u0, int lane)
+{
+    constexpr int UPW = C::UPW, K = 4;
+    const int ln = lane & 31, g = lane >> 5;
+    const int lt_lo = u0 >> 1;
+    // staging source: lane s covers row s/4 of a 16-row block, stored piece s%4 holds logical piece p
+    const int sr = lane >> 2, sp = (lane & 3) ^ ((sr >> 2) & 3);
+    const uint16_t* Lsrc = L + ((size_t)lt_lo * 32 + sr) * C::Q + 8 * sp;
+    // fragment read offsets inside a staged 32-row tile (two blocks), K-step u of the chunk
+    const int rr = ln & 15, sw = (rr >> 2) & 3;
+    const int foff0 = (ln >> 4) * 512 + rr * 32 + 8 * ((0 + g) ^ sw);
+    const int foff1 = (ln >> 4) * 512 + rr * 32 + 8 * ((2 + g) ^ sw);
+    // activation dwords: Y1s[b][kk*Q + c*QK + 8*tq + 4*u + 2*g]
+    const uint16_t* abase = y1s + (size_t)ln * C::Y1_STRIDE + 2 * g;
+
+    f32x16 acc[UPW * K];
+#pragma unroll
+    for (int t = 0; t < UPW * K; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+
+    constexpr int NST = K * C::TQ;
+    auto issue = [&](int st) {
+        const int c = st / C::TQ, tq = st - c * C::TQ;
+        const uint16_t* src = Lsrc + (size_t)c * C::S * C::Q + tq * 32;
+        uint16_t* dst = stg + (size_t)(st % C::D2) * C::NBLK2 * 512;
+#pragma unroll
+        for (int blk = 0; blk < C::NBLK2; ++blk) {
+            // the last l tile of the table is only touched by odd-aligned waves; clamp its rows
+            int roff = blk * 16;
+            if (lt_lo * 32 + roff + 16 > C::S) roff = 0;
+            dma16(src + (size_t)roff * C::Q, dst + blk * 512);
+        }
+    };
+    wait_vmcnt<0>();  // stores of the previous pass: the ring below counts loads only
+#pragma unroll
+    for (int d = 0; d < C::D2 - 1; ++d)
+        if (d < NST) issue(d);
+
+#pragma unroll
+    for (int c = 0; c < K; ++c) {
+        for (int tq = 0; tq < C::TQ; ++tq) {
+            const int st = c * C::TQ + tq;
+            __builtin_amdgcn_sched_barrier(0);
+            if (st + C::D2 - 1 < NST) {
+                issue(st + C::D2 - 1);
+                wait_vmcnt<(C::D2 - 1) * C::NBLK2>();
+            } else if (C::D2 >= 3 && st + C::D2 - 2 < NST) {
+                wait_vmcnt<(C::D2 >= 3 ? C::D2 - 2 : 0) * C::NBLK2>();
+            } else {
+                wait_vmcnt<0>();
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const uint16_t* wbuf = stg + (size_t)(st % C::D2) * C::NBLK2 * 512;
+            const uint16_t* ap = abase + c * C::QK + tq * 8;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                bf16x8 wfr[C::NLT], afr[C::NB];
+#pragma unroll
+                for (int li = 0; li < C::NLT; ++li) {
+                    const u32x4 p = lds128(wbuf + li * 1024 + (u ? foff1 : foff0));
+                    // piece dwords (r1a,k0 k1) (r1a,k2 k3) (r1b,k0 k1) (r1b,k2 k3) -> slots (kk, r1a r1b)
+                    const u32x4 wv = {pick_lo16(p[0], p[2]), pick_hi16(p[0], p[2]), pick_lo16(p[1], p[3]), pick_hi16(p[1], p[3])};
+                    wfr[li] = as_bf16x8(wv);
+                }
+#pragma unroll
+                for (int nb = 0; nb < C::NB; ++nb) {
+                    u32x4 av;
+#pragma unroll
+                    for (int kk = 0; kk < K; ++kk)
+                        av[kk] = *reinterpret_cast<const uint32_t*>(ap + (size_t)nb * 32 * C::Y1_STRIDE + kk * C::Q + 4 * u);
+                    afr[nb] = as_bf16x8(av);
+                }
+#pragma unroll
+                for (int i = 0; i < UPW; ++i) {
+                    const int uu = i + (ODD ? 1 : 0);  // unit index relative to the first staged l tile
+                    acc[i * K + c] = mfma32(afr[uu & 1], wfr[uu >> 1], acc[i * K + c]);
+                }
+            }
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // step 3: y[b][4*l + c]; lane holds D[b][l] for l = lt*32 + ln, b = nb*32 + 8*(i/4) + 4*g + i%4
+#pragma unroll
+    for (int i = 0; i < UPW; ++i) {
+        const int uu = i + (ODD ? 1 : 0);
+        const int l = (lt_lo + (uu >> 1)) * 32 + ln;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int64_t row = b0 + (uu & 1) * 32 + 8 * (e / 4) + 4 * g + (e % 4);
+            if (row < B) {
+                u32x2 v = {pack_bf16x2(acc[i * K + 0][e], acc[i * K + 1][e]), pack_bf16x2(acc[i * K + 2][e], acc[i * K + 3][e])};
+                *reinterpret_cast<u32x2*>(y + row * C::N_OUT + (size_t)l * K) = v;
+            }
+        }
+    }
+}
 
 template <typename C>
 __global__ void __launch_bounds__(256)
 fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
                 const uint16_t* __restrict__ L, uint16_t* __restrict__ y, int64_t B)
 {
-    extern __shared__ __attribute__((aligned(16))) uint16_t y1s[];
+    extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63, l16 = lane & 15, h = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int ln = lane & 31, g = lane >> 5;
     const int64_t b0 = (int64_t)blockIdx.x * C::BM;
     long long ts[4];
     if (C::DBG >= 4) ts[0] = __builtin_amdgcn_s_memtime();
@@ -74,135 +199,88 @@ fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
     // ------------------------------------------------------------- stage 1 ----
     {
         const int kk = wave;
-        const uint16_t* xrow[C::NBT];
+        uint16_t* stg = lds + (size_t)wave * (C::STG1 / 2);
+        // staging sources: lane s covers row s/4 of a block, stored piece s%4 holds logical piece sp
+        const int sr = lane >> 2, sp = (lane & 3) ^ ((sr >> 2) & 3);
+        const uint16_t* Rsrc = R + ((size_t)kk * C::Q + sr) * C::P + 8 * sp;
+        const uint16_t* Xsrc[4];
 #pragma unroll
-        for (int bt = 0; bt < C::NBT; ++bt) {
-            int64_t row = b0 + bt * 16 + l16;
+        for (int xb = 0; xb < 4; ++xb) {
+            int64_t row = b0 + xb * 16 + sr;
             row = row < B ? row : B - 1;  // rows past the end are computed from a valid row and dropped
-            xrow[bt] = x + row * C::N_IN + kk * C::P + 8 * h;
+            Xsrc[xb] = x + row * C::N_IN + kk * C::P + 8 * sp;
         }
-        const uint16_t* Rk = R + ((size_t)kk * C::Q + l16) * C::P + 8 * h;
-        for (int jg = 0; jg < C::JT / C::JG; ++jg) {
-            f32x4 acc[C::JG * C::NBT];
+        auto issue = [&](int t) {
+            uint16_t* dst = stg + (size_t)(t & 1) * C::NBLK1 * 512;
 #pragma unroll
-            for (int t = 0; t < C::JG * C::NBT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-            const uint16_t* Rg = Rk + (size_t)jg * C::JG * 16 * C::P;
-            // register ring: K-step t + R1 - 1 is requested before the MFMAs of step t issue; the
-            // scheduling barriers pin that order (the compiler otherwise sinks loads to their use)
-            u32x4 xf[C::R1][C::NBT], rf[C::R1][C::JG];
-            auto load_step = [&](int t, int slot) {
+            for (int blk = 0; blk < 2 * C::QT; ++blk) dma16(Rsrc + (size_t)blk * 16 * C::P + t * 32, dst + blk * 512);
 #pragma unroll
-                for (int bt = 0; bt < C::NBT; ++bt) xf[slot][bt] = ldg128(xrow[bt] + t * 32);
+            for (int xb = 0; xb < 4; ++xb) dma16(Xsrc[xb] + t * 32, dst + (2 * C::QT + xb) * 512);
+        };
+        const int rr = ln & 15, sw = (rr >> 2) & 3;
+        const int foff0 = (ln >> 4) * 512 + rr * 32 + 8 * ((0 + g) ^ sw);
+        const int foff1 = (ln >> 4) * 512 + rr * 32 + 8 * ((2 + g) ^ sw);
+
+        f32x16 acc[C::QT * C::NB];
 #pragma unroll
-                for (int jj = 0; jj < C::JG; ++jj) rf[slot][jj] = ldg128(Rg + (size_t)jj * 16 * C::P + t * 32);
-            };
+        for (int t = 0; t < C::QT * C::NB; ++t)
 #pragma unroll
-            for (int d = 0; d < C::R1 - 1; ++d) load_step(d, d);
-            for (int t0 = 0; t0 < C::T1; t0 += C::R1) {
-#pragma unroll
-                for (int u = 0; u < C::R1; ++u) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (C::DBG != 6 && t0 + u + C::R1 - 1 < C::T1) load_step(t0 + u + C::R1 - 1, (u + C::R1 - 1) % C::R1);
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (C::DBG == 5) {
-#pragma unroll
-                        for (int jj = 0; jj < C::JG; ++jj) acc[jj * C::NBT][0] += __uint_as_float(rf[u][jj][0] ^ rf[u][jj][3]);
-#pragma unroll
-                        for (int bt = 0; bt < C::NBT; ++bt) acc[bt][1] += __uint_as_float(xf[u][bt][0] ^ xf[u][bt][3]);
-                        continue;
-                    }
-#pragma unroll
-                    for (int jj = 0; jj < C::JG; ++jj)
-#pragma unroll
-                        for (int bt = 0; bt < C::NBT; ++bt)
-                            acc[jj * C::NBT + bt] =
-                                mfma16(as_bf16x8(rf[C::DBG == 6 ? 0 : u][jj]), as_bf16x8(xf[C::DBG == 6 ? 0 : u][bt]), acc[jj * C::NBT + bt]);
-                }
+            for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+
+        issue(0);
+        for (int t = 0; t < C::T1; ++t) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + 1 < C::T1) {
+                if (C::DBG != 6) issue(t + 1);
+                wait_vmcnt<C::NBLK1>();
+            } else {
+                wait_vmcnt<0>();
             }
             __builtin_amdgcn_sched_barrier(0);
-            // lane holds D^T[j][b] for b = bt*16 + l16 and j = jt*16 + 4*h + 0..3
+            if (C::DBG == 5) continue;
+            const uint16_t* buf = stg + (size_t)(t & 1) * C::NBLK1 * 512;
 #pragma unroll
-            for (int jj = 0; jj < C::JG; ++jj)
+            for (int u = 0; u < 2; ++u) {
+                bf16x8 rf[C::QT], xf[C::NB];
 #pragma unroll
-                for (int bt = 0; bt < C::NBT; ++bt) {
-                    const f32x4& a = acc[jj * C::NBT + bt];
-                    const int j = (jg * C::JG + jj) * 16 + 4 * h;
-                    *reinterpret_cast<u32x2*>(y1s + (size_t)(bt * 16 + l16) * C::LDS_STRIDE + kk * C::Q + j) =
-                        u32x2{pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3])};
-                }
+                for (int jt = 0; jt < C::QT; ++jt) rf[jt] = as_bf16x8(lds128(buf + jt * 1024 + (u ? foff1 : foff0)));
+#pragma unroll
+                for (int nb = 0; nb < C::NB; ++nb) xf[nb] = as_bf16x8(lds128(buf + (C::QT + nb) * 1024 + (u ? foff1 : foff0)));
+#pragma unroll
+                for (int jt = 0; jt < C::QT; ++jt)
+#pragma unroll
+                    for (int nb = 0; nb < C::NB; ++nb) acc[jt * C::NB + nb] = mfma32(rf[jt], xf[nb], acc[jt * C::NB + nb]);
+            }
         }
+        __builtin_amdgcn_sched_barrier(0);
+        if (C::DBG >= 4) ts[1] = __builtin_amdgcn_s_memtime();
+        __syncthreads();  // every wave is done with its staging ring: the space becomes Y1s
+        // lane holds D^T[j][b] for b = nb*32 + ln and j = jt*32 + 8*(i/4) + 4*g + i%4
+#pragma unroll
+        for (int jt = 0; jt < C::QT; ++jt)
+#pragma unroll
+            for (int nb = 0; nb < C::NB; ++nb)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const f32x16& a = acc[jt * C::NB + nb];
+                    const int j = jt * 32 + 8 * i4 + 4 * g;
+                    *reinterpret_cast<u32x2*>(lds + (size_t)(nb * 32 + ln) * C::Y1_STRIDE + kk * C::Q + j) =
+                        u32x2{pack_bf16x2(a[4 * i4 + 0], a[4 * i4 + 1]), pack_bf16x2(a[4 * i4 + 2], a[4 * i4 + 3])};
+                }
     }
-    if (C::DBG >= 4) ts[1] = __builtin_amdgcn_s_memtime();
     __syncthreads();
     if (C::DBG >= 4) ts[2] = __builtin_amdgcn_s_memtime();
 
     // ------------------------------------------------------------- stage 2 ----
-    // wave w owns l tiles (rd*4 + w)*LT .. +LT-1 in round rd
-    for (int rd = 0; rd < C::ST / (4 * C::LT); ++rd) {
-        const int lt0 = (rd * 4 + wave) * C::LT;
-        f32x4 acc[C::K * C::LT * C::NBT];
-#pragma unroll
-        for (int t = 0; t < C::K * C::LT * C::NBT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-        // L[c][l][r]: lane (l16, h) reads r = 32*t + 8*h .. +7 of row l = (lt0 + i)*16 + l16
-        const uint16_t* Lbase = L + (size_t)(lt0 * 16 + l16) * C::Q + 8 * h;
-        // Y1s[b][kk*Q + c*QK + r1], r1 = 8*t + 2*h + {0,1}: one dword per kk
-        const uint16_t* abase = y1s + (size_t)l16 * C::LDS_STRIDE + 2 * h;
-
-        constexpr int NSTEP = C::K * C::T2;  // (c, t) pairs
-        u32x4 wf[C::R2][C::LT];
-        u32x4 af[2][C::NBT];
-        auto load_w = [&](int st, int slot) {
-            const uint16_t* p = Lbase + (size_t)(st / C::T2) * C::S * C::Q + (st % C::T2) * 32;
-#pragma unroll
-            for (int i = 0; i < C::LT; ++i) wf[slot][i] = ldg128(p + (size_t)i * 16 * C::Q);
-        };
-        auto load_a = [&](int st, int slot) {
-            const uint16_t* p = abase + (st / C::T2) * C::QK + (st % C::T2) * 8;
-#pragma unroll
-            for (int bt = 0; bt < C::NBT; ++bt)
-#pragma unroll
-                for (int kk = 0; kk < C::K; ++kk)
-                    af[slot][bt][kk] = *reinterpret_cast<const uint32_t*>(p + (size_t)bt * 16 * C::LDS_STRIDE + kk * C::Q);
-        };
-#pragma unroll
-        for (int d = 0; d < C::R2 - 1; ++d)
-            if (d < NSTEP) load_w(d, d);
-        load_a(0, 0);
-#pragma unroll
-        for (int st = 0; st < NSTEP; ++st) {
-            __builtin_amdgcn_sched_barrier(0);
-            if (st + C::R2 - 1 < NSTEP) load_w(st + C::R2 - 1, (st + C::R2 - 1) % C::R2);
-            if (st + 1 < NSTEP) load_a(st + 1, (st + 1) & 1);
-            __builtin_amdgcn_sched_barrier(0);
-            const int c = st / C::T2;
-#pragma unroll
-            for (int i = 0; i < C::LT; ++i) {
-                // piece dwords: (r1a,k0 k1) (r1a,k2 k3) (r1b,k0 k1) (r1b,k2 k3) -> slots (kk, r1a r1b)
-                const u32x4& p = wf[st % C::R2][i];
-                const u32x4 wv = {pick_lo16(p[0], p[2]), pick_hi16(p[0], p[2]), pick_lo16(p[1], p[3]), pick_hi16(p[1], p[3])};
-                const bf16x8 wfrag = as_bf16x8(wv);
-#pragma unroll
-                for (int bt = 0; bt < C::NBT; ++bt)
-                    acc[(c * C::LT + i) * C::NBT + bt] =
-                        mfma16(as_bf16x8(af[st & 1][bt]), wfrag, acc[(c * C::LT + i) * C::NBT + bt]);
-            }
+    {
+        uint16_t* stg = lds + C::LDS_Y1 / 2 + (size_t)wave * (C::STG2 / 2);
+        for (int ps = 0; ps < C::PASSES; ++ps) {
+            const int u0 = (ps * 4 + wave) * C::UPW;
+            if (u0 & 1)
+                stage2_pass<C, true>(L, lds, stg, y, b0, B, u0, lane);
+            else
+                stage2_pass<C, false>(L, lds, stg, y, b0, B, u0, lane);
         }
-        __builtin_amdgcn_sched_barrier(0);
-        // step 3: y[b][4*l + c]; lane holds D[b][l] for l = (lt0 + i)*16 + l16, b = bt*16 + 4*h + 0..3
-#pragma unroll
-        for (int i = 0; i < C::LT; ++i)
-#pragma unroll
-            for (int bt = 0; bt < C::NBT; ++bt)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int64_t row = b0 + bt * 16 + 4 * h + e;
-                    if (row < B) {
-                        const int l = (lt0 + i) * 16 + l16;
-                        u32x2 v = {pack_bf16x2(acc[(0 * C::LT + i) * C::NBT + bt][e], acc[(1 * C::LT + i) * C::NBT + bt][e]),
-                                   pack_bf16x2(acc[(2 * C::LT + i) * C::NBT + bt][e], acc[(3 * C::LT + i) * C::NBT + bt][e])};
-                        *reinterpret_cast<u32x2*>(y + row * C::N_OUT + (size_t)l * C::K) = v;
-                    }
-                }
     }
     if (C::DBG >= 4) {
         __builtin_amdgcn_s_waitcnt(0);
@@ -234,25 +312,20 @@ struct Entry {
 };
 
 // variant 0 is the default; the others are reachable with MONARCH_FWD_VARIANT=<n> (tuning aid)
-//                                      P     Q     S   JG  LT  R1 R2
+//                                      P     Q     S  UPW D2
 const Entry kTable[] = {
-    {192, 192, 192, 0, launch<FwdWide<192, 192, 192, 12, 3, 3, 3>>},   // ViT-B projection 768 -> 768
-    {192, 192, 192, 1, launch<FwdWide<192, 192, 192, 6, 3, 3, 3>>},
-    {192, 192, 192, 2, launch<FwdWide<192, 192, 192, 6, 3, 3, 4>>},
-    {192, 192, 192, 3, launch<FwdWide<192, 192, 192, 4, 3, 3, 4>>},
-    {192, 192, 192, 11, launch<FwdWide<192, 192, 192, 12, 3, 3, 3, 4>>},
-    {192, 192, 192, 12, launch<FwdWide<192, 192, 192, 12, 3, 3, 3, 5>>},
-    {192, 192, 192, 13, launch<FwdWide<192, 192, 192, 12, 3, 3, 3, 6>>},
-    {192, 192, 768, 0, launch<FwdWide<192, 192, 768, 12, 3, 3, 3>>},   // GPT-2 small fc1 768 -> 3072
-    {192, 192, 768, 1, launch<FwdWide<192, 192, 768, 6, 3, 3, 4>>},
-    {256, 256, 1024, 0, launch<FwdWide<256, 256, 1024, 8, 4, 4, 3>>},  // GPT-2 medium fc1 1024 -> 4096
-    {256, 256, 1024, 1, launch<FwdWide<256, 256, 1024, 8, 2, 4, 4>>},
-    {1024, 256, 256, 0, launch<FwdWide<1024, 256, 256, 8, 4, 4, 3>>},  // GPT-2 medium fc2 4096 -> 1024
-    {1024, 256, 256, 1, launch<FwdWide<1024, 256, 256, 8, 4, 2, 3>>},
-    {768, 192, 192, 0, launch<FwdWide<768, 192, 192, 12, 3, 3, 3>>},   // GPT-2 small fc2 3072 -> 768
-    {64, 64, 64, 0, launch<FwdWide<64, 64, 64, 4, 1, 2, 3>>},          // small shapes (tests)
-    {64, 64, 128, 0, launch<FwdWide<64, 64, 128, 4, 2, 2, 3>>},
-    {128, 64, 64, 0, launch<FwdWide<128, 64, 64, 2, 1, 4, 3>>},
+    {192, 192, 192, 0, launch<FwdWide<192, 192, 192, 3, 3>>},    // ViT-B projection 768 -> 768
+    {192, 192, 192, 11, launch<FwdWide<192, 192, 192, 3, 3, 4>>},
+    {192, 192, 192, 12, launch<FwdWide<192, 192, 192, 3, 3, 5>>},
+    {192, 192, 192, 13, launch<FwdWide<192, 192, 192, 3, 3, 6>>},
+    {192, 192, 768, 0, launch<FwdWide<192, 192, 768, 4, 3>>},    // GPT-2 small fc1 768 -> 3072
+    {192, 192, 768, 1, launch<FwdWide<192, 192, 768, 2, 4>>},
+    {256, 256, 1024, 0, launch<FwdWide<256, 256, 1024, 2, 3>>},  // GPT-2 medium fc1 1024 -> 4096
+    {1024, 256, 256, 0, launch<FwdWide<1024, 256, 256, 2, 3>>},  // GPT-2 medium fc2 4096 -> 1024
+    {768, 192, 192, 0, launch<FwdWide<768, 192, 192, 3, 3>>},    // GPT-2 small fc2 3072 -> 768
+    {64, 64, 64, 0, launch<FwdWide<64, 64, 64, 1, 3>>},          // small shapes (tests)
+    {64, 64, 128, 0, launch<FwdWide<64, 64, 128, 2, 3>>},
+    {128, 64, 64, 0, launch<FwdWide<128, 64, 64, 1, 2>>},
 };
 
 int tuning_variant()
