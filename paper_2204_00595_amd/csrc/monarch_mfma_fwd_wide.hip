@@ -37,31 +37,37 @@ namespace monarch {
 
 namespace {
 
-template <int P_, int Q_, int S_, int UPW_, int D2_ = 3, int DBG_ = 0>
+template <int P_, int Q_, int S_, int UPW_, int D2_ = 3, int DBG_ = 0, int RD1_ = 8>
 struct FwdWide {
     static constexpr int K = 4, P = P_, Q = Q_, S = S_;
     static constexpr int BM = 64, NB = 2;     // rows per workgroup, 32-row tiles
     static constexpr int UPW = UPW_;          // stage-2 units (32 l x 32 rows) per wave per pass
-    static constexpr int D1 = 2, D2 = D2_;    // LDS ring depths (chunks in flight) of the two stages
+    static constexpr int RD1 = RD1_;          // stage-1 LDS ring: 4 KiB units (32 rows x 128 bytes)
+    static constexpr int D2 = D2_;            // stage-2 LDS ring depth (chunks, or 4 KiB units)
     static constexpr int DBG = DBG_;
     static constexpr int QK = Q / K;          // columns of each R block that feed one L block
     static constexpr int QT = Q / 32;         // 32-wide j tiles per R block
     static constexpr int KQ = K * Q;
     static constexpr int N_IN = K * P, N_OUT = K * S;
-    static constexpr int T1 = P / 32;         // stage-1 chunks (32 columns of R / x each)
+    static constexpr int C1 = P / 64;         // stage-1 column chunks (one 128-byte line of R / x per row)
+    static constexpr int UPC = QT + 2;        // stage-1 units per chunk: two x units, then the R tiles
+    static constexpr int NU1 = C1 * UPC;
     static constexpr int TQ = Q / 32;         // stage-2 chunks per L block (32 columns of L each)
-    static constexpr int NBLK1 = 2 * QT + 4;  // 1 KiB staging blocks per stage-1 chunk: R rows, then x rows
     static constexpr int UNITS = (S / 32) * NB;
     static constexpr int PASSES = UNITS / (4 * UPW);
     static constexpr int NLT = (UPW + 1) / 2; // l tiles a wave touches in one pass
     static constexpr int NBLK2 = 2 * NLT;     // staging blocks per stage-2 chunk
     static constexpr int Y1_STRIDE = KQ + 4;  // bf16; row stride = 2 dwords mod 64 banks
     static constexpr size_t LDS_Y1 = ((size_t)BM * Y1_STRIDE * 2 + 1023) / 1024 * 1024;
-    static constexpr size_t STG1 = (size_t)D1 * NBLK1 * 1024;  // per wave
-    static constexpr size_t STG2 = (size_t)D2 * NBLK2 * 1024;  // per wave
+    static constexpr size_t STG1 = (size_t)RD1 * 4096;         // per wave
+    // stage 2 streams L in 4 KiB units of full 128-byte lines when the ring fits beside Y1s,
+    // else in 32-column chunks (64 bytes per row)
+    static constexpr bool S2_LINES = (Q % 64 == 0) && (LDS_Y1 + 4 * (size_t)D2 * 4096 <= kMaxLdsBytes);
+    static constexpr size_t STG2 = S2_LINES ? (size_t)D2 * 4096 : (size_t)D2 * NBLK2 * 1024;  // per wave
     static constexpr size_t LDS_S1 = 4 * STG1, LDS_S2 = LDS_Y1 + 4 * STG2;
     static constexpr size_t LDS_BYTES = LDS_S1 > LDS_S2 ? LDS_S1 : LDS_S2;
-    static_assert(P % 32 == 0 && Q % 32 == 0 && S % 32 == 0 && QK % 8 == 0, "tile shapes");
+    static_assert(P % 64 == 0 && Q % 32 == 0 && S % 32 == 0 && QK % 8 == 0, "tile shapes");
+    static_assert(QT % 2 == 0 && RD1 >= 3 && (RD1 - 2) * 4 < 64, "stage-1 stream");
     static_assert(UNITS % (4 * UPW) == 0 && UPW >= 1 && UPW <= 4, "stage-2 split");
     static_assert(LDS_BYTES <= kMaxLdsBytes, "LDS");
 };
@@ -82,7 +88,122 @@ __device__ __forceinline__ void dma16(const uint16_t* gsrc, uint16_t* lds_block)
                                      (__attribute__((address_space(3))) void*)lds_block, 16, 0, 0);
 }
 
-// Stage 2 for one pass of one wave: units u0 .. u0+UPW-1, unit u = (l tile u / 2, row tile u % 2).
+__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
+// 4 KiB staging unit = 32 rows x 128 bytes = four 1 KiB blocks of 8 rows.  One DMA instruction
+// fills a block: lane s fetches row s/8, and its slot s%8 holds logical 16-byte piece
+// (s%8) ^ key, key = (row & 7) ^ ((row >> 3) & 1), which makes the fragment reads conflict-free.
+// A fragment for K-step u (16 columns) is pieces 2u and 2u+1: lane (row = lane%32, g = lane/32).
+__device__ __forceinline__ int unit_frag_off(int ln, int g, int u)
+{
+    const int bi = ln >> 3, r = ln & 7;
+    return bi * 512 + r * 64 + 8 * ((2 * u + g) ^ r ^ (bi & 1));
+}
+
+// Stage 2 on full-line units (Q % 64 == 0 and room for the ring).  One pass of one wave:
+// work units u0 .. u0+UPW-1, work unit w = (l tile w / 2, row tile w % 2).
+template <typename C, bool ODD>
+__device__ __forceinline__ void stage2_pass_lines(const uint16_t* __restrict__ L, const uint16_t* y1s, uint16_t* stg,
+                                                  uint16_t* __restrict__ y, int64_t b0, int64_t B, int u0, int lane)
+{
+    constexpr int UPW = C::UPW, K = 4, NLT = C::NLT, RD = C::D2;
+    constexpr int TQ64 = C::Q / 64;
+    constexpr int NU = K * TQ64 * NLT;  // staged units, in (c, tq, li) order
+    const int ln = lane & 31, g = lane >> 5;
+    const int lt_lo = u0 >> 1;
+    const int rb = lane >> 3, pe = (lane & 7) ^ rb;  // DMA: row in block, logical piece for even blocks
+    // rows of the staged l tiles (the second tile may not exist for the last wave: reuse the first)
+    const bool second_ok = (lt_lo + 1) * 32 < C::S;
+    const uint16_t* Lrow = L + ((size_t)lt_lo * 32 + rb) * C::Q;
+    int foff[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) foff[u] = unit_frag_off(ln, g, u);
+    // activation dwords: Y1s[b][kk*Q + c*QK + 16*tq + 4*u + 2*g]
+    const uint16_t* abase = y1s + (size_t)ln * C::Y1_STRIDE + 2 * g;
+
+    f32x16 acc[UPW * K];
+#pragma unroll
+    for (int t = 0; t < UPW * K; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+
+    auto issue = [&](int n) {
+        const int c = n / (TQ64 * NLT), tq = (n / NLT) % TQ64, li = n % NLT;
+        const uint16_t* src = Lrow + (size_t)c * C::S * C::Q + tq * 64 + (size_t)((li && second_ok) ? 32 : 0) * C::Q;
+        uint16_t* dst = stg + (size_t)(n % RD) * 2048;
+#pragma unroll
+        for (int bi = 0; bi < 4; ++bi) dma16(src + (size_t)bi * 8 * C::Q + 8 * (pe ^ (bi & 1)), dst + bi * 512);
+    };
+    u32x4 wraw[2][4];
+    u32x4 araw[2][4][C::NB];
+    auto read = [&](int n, int slot) {
+        const int c = n / (TQ64 * NLT), tq = (n / NLT) % TQ64;
+        const uint16_t* wbuf = stg + (size_t)(n % RD) * 2048;
+        const uint16_t* ap = abase + c * C::QK + tq * 16;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            wraw[slot][u] = lds128(wbuf + foff[u]);
+#pragma unroll
+            for (int nb = 0; nb < C::NB; ++nb)
+#pragma unroll
+                for (int kk = 0; kk < K; ++kk)
+                    araw[slot][u][nb][kk] = *reinterpret_cast<const uint32_t*>(ap + (size_t)nb * 32 * C::Y1_STRIDE + kk * C::Q + 4 * u);
+        }
+    };
+    wait_vmcnt<0>();  // stores of the previous pass: the ring below counts loads only
+#pragma unroll
+    for (int d = 0; d < RD - 1; ++d)
+        if (d < NU) issue(d);
+    wait_vmcnt<((NU < RD - 1 ? NU : RD - 1) - 1) * 4>();
+    __builtin_amdgcn_sched_barrier(0);
+    read(0, 0);
+#pragma unroll
+    for (int n = 0; n < NU; ++n) {
+        __builtin_amdgcn_sched_barrier(0);
+        wait_lgkmcnt0();
+        if (n + RD - 1 < NU) issue(n + RD - 1);
+        if (n + 1 < NU) {
+            // unit n+1 has landed once at most the units issued after it are outstanding
+            constexpr int dummy = 0; (void)dummy;
+            const int later = (n + RD - 1 < NU ? n + RD - 1 : NU - 1) - (n + 1);
+            if (later >= RD - 2) wait_vmcnt<(RD - 2) * 4>(); else if (later == 1 && RD > 3) wait_vmcnt<4>(); else wait_vmcnt<0>();
+            __builtin_amdgcn_sched_barrier(0);
+            read(n + 1, (n + 1) & 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        const int c = n / (TQ64 * NLT), li = n % NLT;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            // piece dwords (r1a,k0 k1) (r1a,k2 k3) (r1b,k0 k1) (r1b,k2 k3) -> slots (kk, r1a r1b)
+            const u32x4& p = wraw[n & 1][u];
+            const u32x4 wv = {pick_lo16(p[0], p[2]), pick_hi16(p[0], p[2]), pick_lo16(p[1], p[3]), pick_hi16(p[1], p[3])};
+            const bf16x8 wfrag = as_bf16x8(wv);
+#pragma unroll
+            for (int i = 0; i < UPW; ++i) {
+                const int ww = i + (ODD ? 1 : 0);  // work unit relative to the first staged l tile
+                if ((ww >> 1) == li) acc[i * K + c] = mfma32(as_bf16x8(araw[n & 1][u][ww & 1]), wfrag, acc[i * K + c]);
+            }
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // step 3: y[b][4*l + c]; lane holds D[b][l] for l = lt*32 + ln, b = nb*32 + 8*(i/4) + 4*g + i%4
+#pragma unroll
+    for (int i = 0; i < UPW; ++i) {
+        const int ww = i + (ODD ? 1 : 0);
+        const int l = (lt_lo + (ww >> 1)) * 32 + ln;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int64_t row = b0 + (ww & 1) * 32 + 8 * (e / 4) + 4 * g + (e % 4);
+            if (row < B) {
+                u32x2 v = {pack_bf16x2(acc[i * K + 0][e], acc[i * K + 1][e]), pack_bf16x2(acc[i * K + 2][e], acc[i * K + 3][e])};
+                *reinterpret_cast<u32x2*>(y + row * C::N_OUT + (size_t)l * K) = v;
+            }
+        }
+    }
+}
+
+// Stage 2 on 32-column chunks (64 bytes per row).  One pass of one wave: units u0 .. u0+UPW-1,
+// unit u = (l tile u / 2, row tile u % 2).
 template <typename C, bool ODD>
 __device__ __forceinline__ void stage2_pass(const uint16_t* __restrict__ L, const uint16_t* y1s, uint16_t* stg,
                                             uint16_t* __restrict__ y, int64_t b0, int64_t B, int u0, int lane)
@@ -200,26 +321,28 @@ fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
     {
         const int kk = wave;
         uint16_t* stg = lds + (size_t)wave * (C::STG1 / 2);
-        // staging sources: lane s covers row s/4 of a block, stored piece s%4 holds logical piece sp
-        const int sr = lane >> 2, sp = (lane & 3) ^ ((sr >> 2) & 3);
-        const uint16_t* Rsrc = R + ((size_t)kk * C::Q + sr) * C::P + 8 * sp;
-        const uint16_t* Xsrc[4];
+        // The wave consumes a stream of 4 KiB units, per 64-column chunk: x rows 0..31, x rows 32..63,
+        // then the R tiles j = 0..31, 32..63, ...  Unit n sits in ring slot n % RD1.
+        const int rb = lane >> 3, pe = (lane & 7) ^ rb;
+        const uint16_t* Rrow = R + ((size_t)kk * C::Q + rb) * C::P;
+        const uint16_t* Xrow[8];
 #pragma unroll
-        for (int xb = 0; xb < 4; ++xb) {
-            int64_t row = b0 + xb * 16 + sr;
+        for (int i = 0; i < 8; ++i) {
+            int64_t row = b0 + i * 8 + rb;
             row = row < B ? row : B - 1;  // rows past the end are computed from a valid row and dropped
-            Xsrc[xb] = x + row * C::N_IN + kk * C::P + 8 * sp;
+            Xrow[i] = x + row * C::N_IN + kk * C::P;
         }
-        auto issue = [&](int t) {
-            uint16_t* dst = stg + (size_t)(t & 1) * C::NBLK1 * 512;
+        auto issue = [&](int c64, int u) {  // u static: 0, 1 = x units; 2.. = R tile u - 2
+            uint16_t* dst = stg + (size_t)((c64 * C::UPC + u) % C::RD1) * 2048;
 #pragma unroll
-            for (int blk = 0; blk < 2 * C::QT; ++blk) dma16(Rsrc + (size_t)blk * 16 * C::P + t * 32, dst + blk * 512);
-#pragma unroll
-            for (int xb = 0; xb < 4; ++xb) dma16(Xsrc[xb] + t * 32, dst + (2 * C::QT + xb) * 512);
+            for (int bi = 0; bi < 4; ++bi) {
+                const uint16_t* src = u < 2 ? Xrow[u * 4 + bi] : Rrow + (size_t)((u - 2) * 32 + bi * 8) * C::P;
+                dma16(src + c64 * 64 + 8 * (pe ^ (bi & 1)), dst + bi * 512);
+            }
         };
-        const int rr = ln & 15, sw = (rr >> 2) & 3;
-        const int foff0 = (ln >> 4) * 512 + rr * 32 + 8 * ((0 + g) ^ sw);
-        const int foff1 = (ln >> 4) * 512 + rr * 32 + 8 * ((2 + g) ^ sw);
+        int foff[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) foff[u] = unit_frag_off(ln, g, u);
 
         f32x16 acc[C::QT * C::NB];
 #pragma unroll
@@ -227,29 +350,56 @@ fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
-        issue(0);
-        for (int t = 0; t < C::T1; ++t) {
-            __builtin_amdgcn_sched_barrier(0);
-            if (t + 1 < C::T1) {
-                if (C::DBG != 6) issue(t + 1);
-                wait_vmcnt<C::NBLK1>();
-            } else {
-                wait_vmcnt<0>();
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            if (C::DBG == 5) continue;
-            const uint16_t* buf = stg + (size_t)(t & 1) * C::NBLK1 * 512;
+        u32x4 xf[C::NB][4], rf[2][4];
+        auto read = [&](int c64, int u, u32x4 (&dst)[4]) {
+            const uint16_t* buf = stg + (size_t)((c64 * C::UPC + u) % C::RD1) * 2048;
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                bf16x8 rf[C::QT], xf[C::NB];
+            for (int k4 = 0; k4 < 4; ++k4) dst[k4] = lds128(buf + foff[k4]);
+        };
+        // prologue: units 0 .. RD1-2 of the stream
 #pragma unroll
-                for (int jt = 0; jt < C::QT; ++jt) rf[jt] = as_bf16x8(lds128(buf + jt * 1024 + (u ? foff1 : foff0)));
+        for (int d = 0; d < C::RD1 - 1; ++d)
+            if (d < C::NU1) issue(d / C::UPC, d % C::UPC);
+        wait_vmcnt<((C::NU1 < C::RD1 - 1 ? C::NU1 : C::RD1 - 1) - 1) * 4>();
+        __builtin_amdgcn_sched_barrier(0);
+        read(0, 0, xf[0]);
+
+        for (int c64 = 0; c64 < C::C1; ++c64) {
 #pragma unroll
-                for (int nb = 0; nb < C::NB; ++nb) xf[nb] = as_bf16x8(lds128(buf + (C::QT + nb) * 1024 + (u ? foff1 : foff0)));
+            for (int u = 0; u < C::UPC; ++u) {
+                const int n = c64 * C::UPC + u;
+                __builtin_amdgcn_sched_barrier(0);
+                wait_lgkmcnt0();  // no fragment read may still be pending on the slot recycled below
+                {
+                    constexpr int dummy = 0; (void)dummy;
+                    const int ui = (u + C::RD1 - 1) % C::UPC, ci = c64 + (u + C::RD1 - 1) / C::UPC;
+                    if (C::DBG != 6 && n + C::RD1 - 1 < C::NU1) issue(ci, ui);
+                }
+                const bool next_is_x = (u + 1 == C::UPC) || (u + 1 < 2);
+                const int un = (u + 1) % C::UPC, cn = c64 + (u + 1) / C::UPC;
+                auto wait_next = [&]() {
+                    // unit n+1 has landed once only the units issued after it are outstanding
+                    if (n + C::RD1 - 1 < C::NU1) wait_vmcnt<(C::RD1 - 2) * 4>(); else wait_vmcnt<0>();
+                    __builtin_amdgcn_sched_barrier(0);
+                };
+                if (!next_is_x && n + 1 < C::NU1) {
+                    wait_next();
+                    if (C::DBG != 5) read(cn, un, rf[un & 1]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (u >= 2 && C::DBG != 5) {
+                    const int jt = u - 2;
 #pragma unroll
-                for (int jt = 0; jt < C::QT; ++jt)
+                    for (int k4 = 0; k4 < 4; ++k4)
 #pragma unroll
-                    for (int nb = 0; nb < C::NB; ++nb) acc[jt * C::NB + nb] = mfma32(rf[jt], xf[nb], acc[jt * C::NB + nb]);
+                        for (int nb = 0; nb < C::NB; ++nb)
+                            acc[jt * C::NB + nb] = mfma32(as_bf16x8(rf[u & 1][k4]), as_bf16x8(xf[nb][k4]), acc[jt * C::NB + nb]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (next_is_x && n + 1 < C::NU1) {
+                    wait_next();
+                    if (C::DBG != 5) read(cn, un, xf[un]);
+                }
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -276,10 +426,17 @@ fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
         uint16_t* stg = lds + C::LDS_Y1 / 2 + (size_t)wave * (C::STG2 / 2);
         for (int ps = 0; ps < C::PASSES; ++ps) {
             const int u0 = (ps * 4 + wave) * C::UPW;
-            if (u0 & 1)
-                stage2_pass<C, true>(L, lds, stg, y, b0, B, u0, lane);
-            else
-                stage2_pass<C, false>(L, lds, stg, y, b0, B, u0, lane);
+            if constexpr (C::S2_LINES) {
+                if (u0 & 1)
+                    stage2_pass_lines<C, true>(L, lds, stg, y, b0, B, u0, lane);
+                else
+                    stage2_pass_lines<C, false>(L, lds, stg, y, b0, B, u0, lane);
+            } else {
+                if (u0 & 1)
+                    stage2_pass<C, true>(L, lds, stg, y, b0, B, u0, lane);
+                else
+                    stage2_pass<C, false>(L, lds, stg, y, b0, B, u0, lane);
+            }
         }
     }
     if (C::DBG >= 4) {
@@ -315,17 +472,18 @@ struct Entry {
 //                                      P     Q     S  UPW D2
 const Entry kTable[] = {
     {192, 192, 192, 0, launch<FwdWide<192, 192, 192, 3, 3>>},    // ViT-B projection 768 -> 768
+    {192, 192, 192, 1, launch<FwdWide<192, 192, 192, 3, 3, 0, 6>>},
     {192, 192, 192, 11, launch<FwdWide<192, 192, 192, 3, 3, 4>>},
     {192, 192, 192, 12, launch<FwdWide<192, 192, 192, 3, 3, 5>>},
     {192, 192, 192, 13, launch<FwdWide<192, 192, 192, 3, 3, 6>>},
     {192, 192, 768, 0, launch<FwdWide<192, 192, 768, 4, 3>>},    // GPT-2 small fc1 768 -> 3072
-    {192, 192, 768, 1, launch<FwdWide<192, 192, 768, 2, 4>>},
+    {192, 192, 768, 1, launch<FwdWide<192, 192, 768, 2, 3>>},
     {256, 256, 1024, 0, launch<FwdWide<256, 256, 1024, 2, 3>>},  // GPT-2 medium fc1 1024 -> 4096
     {1024, 256, 256, 0, launch<FwdWide<1024, 256, 256, 2, 3>>},  // GPT-2 medium fc2 4096 -> 1024
     {768, 192, 192, 0, launch<FwdWide<768, 192, 192, 3, 3>>},    // GPT-2 small fc2 3072 -> 768
     {64, 64, 64, 0, launch<FwdWide<64, 64, 64, 1, 3>>},          // small shapes (tests)
     {64, 64, 128, 0, launch<FwdWide<64, 64, 128, 2, 3>>},
-    {128, 64, 64, 0, launch<FwdWide<128, 64, 64, 1, 2>>},
+    {128, 64, 64, 0, launch<FwdWide<128, 64, 64, 1, 3>>},
 };
 
 int tuning_variant()
