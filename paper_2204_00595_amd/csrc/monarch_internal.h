@@ -65,13 +65,18 @@ struct WgradDesc {
     int64_t ldb;
     int b_g, b_seg, seg_w;
     int M, N, G;
-    float* P;
+    float* P;        // partial tiles, nz * G * M * N floats
     int64_t rows;
     int rows_per_chunk;
+    int deint;       // A holds the four groups interleaved
+    void* out;       // reduced result [g][m][col(n)], col(n) = (n % seg_w) * (N / seg_w) + n / seg_w
 };
 bool wgrad_tile_ok(int M, int N, int seg_w, int* tm, int* tn);
-int wgrad_gemm(const WgradDesc& d, bool interleaved_a, int nz, hipStream_t st);
-int wgrad_reduce(const float* P, void* out, bool out_f32, int nz, size_t total, int N, int seg_w, hipStream_t st);
+int wgrad_tiles(const WgradDesc& d);  // workgroups per batch chunk (0: shape not supported)
+// both GEMMs over the same nz batch chunks (one launch when their tile shapes agree), then
+// one launch that sums the chunks of both and writes `out` (fp32 or bf16)
+int wgrad_gemm_pair(const WgradDesc& d0, const WgradDesc& d1, int nz, hipStream_t st);
+int wgrad_reduce_pair(const WgradDesc& d0, const WgradDesc& d1, bool out_f32, int nz, hipStream_t st);
 
 // ---- small utility launches shared by the families ----
 int launch_fill_zero_f32(float* p, size_t n, hipStream_t st);

@@ -24,37 +24,40 @@ namespace {
 
 // ------------------------------------------------------------------------ prep ----
 
-// LTp[c][kk*QK + r1][l] = L[c][l][4*r1 + kk];  32 x 32 tiles through LDS.
+// Both re-layouts in one launch, 32 x 32 tiles through LDS; blocks [0, tilesL) do L, the rest R.
+//   LTp[c][kk*QK + r1][l] = L[c][l][4*r1 + kk]
+//   RTp[kk][i][32*u + 8*h + e] = R[kk][j][i],  j = 32*u + 16*(e/4) + 4*h + e%4   (h = 0..3, e = 0..7)
 __global__ void __launch_bounds__(256)
-prep_L_kernel(const uint16_t* __restrict__ L, uint16_t* __restrict__ LTp, int S, int Q)
+prep_kernel(const uint16_t* __restrict__ L, const uint16_t* __restrict__ R, uint16_t* __restrict__ LTp,
+            uint16_t* __restrict__ RTp, int P, int Q, int S)
 {
     __shared__ uint16_t tile[32][33];
-    const int c = blockIdx.z, l0 = blockIdx.y * 32, r0 = blockIdx.x * 32;
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-    const int QK = Q / 4;
-    for (int yy = ty; yy < 32; yy += 8) tile[yy][tx] = L[((size_t)c * S + l0 + yy) * Q + r0 + tx];
-    __syncthreads();
-    for (int yy = ty; yy < 32; yy += 8) {
-        const int r = r0 + yy;
-        const int kappa = (r & 3) * QK + (r >> 2);
-        LTp[((size_t)c * Q + kappa) * S + l0 + tx] = tile[tx][yy];
+    const int tilesL = 4 * (S / 32) * (Q / 32);
+    int t = blockIdx.x;
+    if (t < tilesL) {
+        const int nr = Q / 32, nl = S / 32;
+        const int r0 = (t % nr) * 32, l0 = (t / nr % nl) * 32, c = t / (nr * nl);
+        const int QK = Q / 4;
+        for (int yy = ty; yy < 32; yy += 8) tile[yy][tx] = L[((size_t)c * S + l0 + yy) * Q + r0 + tx];
+        __syncthreads();
+        for (int yy = ty; yy < 32; yy += 8) {
+            const int r = r0 + yy;
+            const int kappa = (r & 3) * QK + (r >> 2);
+            LTp[((size_t)c * Q + kappa) * S + l0 + tx] = tile[tx][yy];
+        }
+    } else {
+        t -= tilesL;
+        const int ni = P / 32, nj = Q / 32;
+        const int i0 = (t % ni) * 32, j0 = (t / ni % nj) * 32, kk = t / (ni * nj);
+        for (int yy = ty; yy < 32; yy += 8) tile[yy][tx] = R[((size_t)kk * Q + j0 + yy) * P + i0 + tx];
+        __syncthreads();
+        // thread tx writes destination column j0 + tx of row i0 + yy
+        const int h = (tx >> 3) & 3, e = tx & 7;
+        const int jsrc = 16 * (e >> 2) + 4 * h + (e & 3);
+        for (int yy = ty; yy < 32; yy += 8)
+            RTp[((size_t)kk * P + i0 + yy) * Q + j0 + tx] = tile[jsrc][yy];
     }
-}
-
-// RTp[kk][i][32*u + 8*h + e] = R[kk][j][i],  j = 32*u + 16*(e/4) + 4*h + e%4   (h = 0..3, e = 0..7).
-__global__ void __launch_bounds__(256)
-prep_R_kernel(const uint16_t* __restrict__ R, uint16_t* __restrict__ RTp, int Q, int P)
-{
-    __shared__ uint16_t tile[32][33];
-    const int kk = blockIdx.z, j0 = blockIdx.y * 32, i0 = blockIdx.x * 32;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-    for (int yy = ty; yy < 32; yy += 8) tile[yy][tx] = R[((size_t)kk * Q + j0 + yy) * P + i0 + tx];
-    __syncthreads();
-    // thread tx writes destination column j0 + tx of row i0 + yy
-    const int h = (tx >> 3) & 3, e = tx & 7;
-    const int jsrc = 16 * (e >> 2) + 4 * h + (e & 3);
-    for (int yy = ty; yy < 32; yy += 8)
-        RTp[((size_t)kk * P + i0 + yy) * Q + j0 + tx] = tile[jsrc][yy];
 }
 
 // ------------------------------------------------------------------------ data ----
@@ -332,40 +335,53 @@ const Entry* find(const Problem& pb)
     return nullptr;
 }
 
-// batch chunks for the weight-gradient GEMMs: enough workgroups to fill 256 CUs, at least
-// 256 rows per chunk so that the partial tiles stay small next to the operands
-int pick_chunks(const Problem& pb, int tiles)
-{
-    int z = (512 + tiles - 1) / tiles;
-    const int64_t maxz = (pb.B + 255) / 256;
-    if (z > maxz) z = (int)maxz;
-    if (z > 64) z = 64;
-    if (z < 1) z = 1;
-    return z;
-}
-
+// The two weight-gradient GEMMs share one split of the batch into nz chunks: about one
+// workgroup per CU in total, chunks of at least 256 rows (multiples of the 32-row pipeline
+// step) so that the fp32 partial tiles stay small next to the operands.
 struct Plan {
-    size_t off_y1, off_dy1, off_ltp, off_rtp, off_part, total;
-    int zL, zR, tmL, tnL, tmR, tnR;
+    size_t off_y1, off_dy1, off_ltp, off_rtp, off_partL, off_partR, total;
+    int nz, rows_per_chunk;
     bool ok;
 };
+
+void fill_descs(const Problem& pb, WgradDesc& dl, WgradDesc& dr)
+{
+    // dL[c][l][4*r1 + kk] = sum_b dy[b][4*l + c] * Y1[b][kk][c*Q/4 + r1]
+    dl = WgradDesc{};
+    dl.lda = pb.n_out(); dl.a_g = 1; dl.deint = 1;
+    dl.ldb = pb.kq(); dl.b_g = pb.q / 4; dl.b_seg = pb.q; dl.seg_w = pb.q / 4;
+    dl.M = pb.s; dl.N = pb.q; dl.G = 4; dl.rows = pb.B;
+    // dR[kk][j][i] = sum_b dY1[b][kk][j] * x[b][kk*P + i]
+    dr = WgradDesc{};
+    dr.lda = pb.kq(); dr.a_g = pb.q; dr.deint = 0;
+    dr.ldb = pb.n_in; dr.b_g = pb.p; dr.b_seg = 0; dr.seg_w = pb.p;
+    dr.M = pb.q; dr.N = pb.p; dr.G = 4; dr.rows = pb.B;
+}
 
 Plan make_plan(const Problem& pb)
 {
     Plan pl{};
-    pl.ok = wgrad_tile_ok(pb.s, pb.q, pb.q / 4, &pl.tmL, &pl.tnL) && wgrad_tile_ok(pb.q, pb.p, pb.p, &pl.tmR, &pl.tnR);
+    WgradDesc dl, dr;
+    fill_descs(pb, dl, dr);
+    const int tiles = wgrad_tiles(dl) + wgrad_tiles(dr);
+    pl.ok = wgrad_tiles(dl) > 0 && wgrad_tiles(dr) > 0;
     if (!pl.ok) return pl;
-    pl.zL = pick_chunks(pb, (pb.s / pl.tmL) * (pb.q / pl.tnL));
-    pl.zR = pick_chunks(pb, (pb.q / pl.tmR) * (pb.p / pl.tnR));
+    int64_t z = (256 + tiles - 1) / tiles;
+    const int64_t maxz = (pb.B + 255) / 256;
+    if (z > maxz) z = maxz;
+    if (z < 1) z = 1;
+    const int64_t rpc = ((pb.B + z - 1) / z + 31) / 32 * 32;
+    pl.rows_per_chunk = (int)(rpc > 0 ? rpc : 32);
+    pl.nz = (int)((pb.B + pl.rows_per_chunk - 1) / pl.rows_per_chunk);
+    if (pl.nz < 1) pl.nz = 1;
     size_t off = 0;
     const size_t act = align_up((size_t)(pb.B > 0 ? pb.B : 1) * pb.kq() * 2, 256);
     pl.off_y1 = off;  off += act;
     pl.off_dy1 = off; off += act;
     pl.off_ltp = off; off += align_up(pb.n_L() * 2, 256);
     pl.off_rtp = off; off += align_up(pb.n_R() * 2, 256);
-    pl.off_part = off;
-    const size_t partL = (size_t)pl.zL * pb.n_L() * 4, partR = (size_t)pl.zR * pb.n_R() * 4;
-    off += align_up(partL > partR ? partL : partR, 256);  // the two reductions run one after the other
+    pl.off_partL = off; off += align_up((size_t)pl.nz * pb.n_L() * 4, 256);
+    pl.off_partR = off; off += align_up((size_t)pl.nz * pb.n_R() * 4, 256);
     pl.total = off;
     return pl;
 }
@@ -387,38 +403,27 @@ int bwd_wide(const Problem& pb, const void* dy, const void* x, const void* R, co
     uint16_t* dY1ws = (uint16_t*)(w + pl.off_dy1);
     uint16_t* LTp = (uint16_t*)(w + pl.off_ltp);
     uint16_t* RTp = (uint16_t*)(w + pl.off_rtp);
-    float* part = (float*)(w + pl.off_part);
     const bool f32out = pb.wgrad_f32();
     if (pb.B == 0) {
         int rc = f32out ? launch_fill_zero_f32((float*)dR, pb.n_R(), st) : launch_fill_zero_u16((uint16_t*)dR, pb.n_R(), st);
         if (rc) return rc;
         return f32out ? launch_fill_zero_f32((float*)dL, pb.n_L(), st) : launch_fill_zero_u16((uint16_t*)dL, pb.n_L(), st);
     }
-    hipLaunchKernelGGL(prep_L_kernel, dim3(pb.q / 32, pb.s / 32, 4), dim3(256), 0, st, (const uint16_t*)L, LTp, pb.s, pb.q);
-    hipLaunchKernelGGL(prep_R_kernel, dim3(pb.p / 32, pb.q / 32, 4), dim3(256), 0, st, (const uint16_t*)R, RTp, pb.q, pb.p);
+    const int prep_blocks = 4 * (pb.s / 32) * (pb.q / 32) + 4 * (pb.q / 32) * (pb.p / 32);
+    hipLaunchKernelGGL(prep_kernel, dim3(prep_blocks), dim3(256), 0, st, (const uint16_t*)L, (const uint16_t*)R,
+                       LTp, RTp, pb.p, pb.q, pb.s);
     if (hipGetLastError() != hipSuccess) return -4;
     int rc = e->fn(pb, dy, x, R, LTp, RTp, dx, Y1ws, dY1ws, st);
     if (rc) return rc;
 
-    // dL[c][l][4*r1 + kk] = sum_b dy[b][4*l + c] * Y1[b][kk][c*Q/4 + r1]
-    WgradDesc d{};
-    d.A = (const uint16_t*)dy; d.lda = pb.n_out(); d.a_g = 1;
-    d.Bm = Y1ws; d.ldb = pb.kq(); d.b_g = pb.q / 4; d.b_seg = pb.q; d.seg_w = pb.q / 4;
-    d.M = pb.s; d.N = pb.q; d.G = 4; d.P = part; d.rows = pb.B;
-    d.rows_per_chunk = (int)(((pb.B + pl.zL - 1) / pl.zL + 31) / 32 * 32);
-    rc = wgrad_gemm(d, true, pl.zL, st);
+    WgradDesc dl, dr;
+    fill_descs(pb, dl, dr);
+    dl.A = (const uint16_t*)dy; dl.Bm = Y1ws; dl.P = (float*)(w + pl.off_partL); dl.out = dL;
+    dr.A = dY1ws; dr.Bm = (const uint16_t*)x; dr.P = (float*)(w + pl.off_partR); dr.out = dR;
+    dl.rows_per_chunk = dr.rows_per_chunk = pl.rows_per_chunk;
+    rc = wgrad_gemm_pair(dl, dr, pl.nz, st);
     if (rc) return rc;
-    rc = wgrad_reduce(part, dL, f32out, pl.zL, pb.n_L(), pb.q, pb.q / 4, st);
-    if (rc) return rc;
-
-    // dR[kk][j][i] = sum_b dY1[b][kk][j] * x[b][kk*P + i]
-    d.A = dY1ws; d.lda = pb.kq(); d.a_g = pb.q;
-    d.Bm = (const uint16_t*)x; d.ldb = pb.n_in; d.b_g = pb.p; d.b_seg = 0; d.seg_w = pb.p;
-    d.M = pb.q; d.N = pb.p;
-    d.rows_per_chunk = (int)(((pb.B + pl.zR - 1) / pl.zR + 31) / 32 * 32);
-    rc = wgrad_gemm(d, false, pl.zR, st);
-    if (rc) return rc;
-    return wgrad_reduce(part, dR, f32out, pl.zR, pb.n_R(), pb.p, pb.p, st);
+    return wgrad_reduce_pair(dl, dr, f32out, pl.nz, st);
 }
 
 }  // namespace monarch

@@ -11,7 +11,7 @@
 // hands every lane four consecutive batch rows of one feature: exactly the MFMA operand layout.
 //
 // One workgroup = four groups g (one per wave), each wave a TM x TN tile of its group's
-// output; the batch is split over gridDim.z chunks whose fp32 partial tiles are summed by
+// output; the batch is split into chunks whose fp32 partial tiles are summed by
 // `wgrad_reduce_kernel`, which also undoes the column order used for dL and converts to the
 // output type.
 #include "monarch_internal.h"
@@ -46,8 +46,7 @@ __device__ __forceinline__ bf16x8 frag_tr(const uint16_t* T, int stride, int k0,
 }
 
 template <int TM, int TN, bool DEINT>
-__global__ void __launch_bounds__(256)
-wgrad_gemm_kernel(WgradDesc d)
+__device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int tile, const int zi)
 {
     constexpr int MT = TM / 32, NT = TN / 32;
     constexpr int SA = TM + 8, SB = TN + 8;  // LDS row strides (bf16 elements)
@@ -57,9 +56,10 @@ wgrad_gemm_kernel(WgradDesc d)
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int tiles_n = d.N / TN;
-    const int m0 = (blockIdx.x / tiles_n) * TM, n0 = (blockIdx.x % tiles_n) * TN;
-    const int g0 = blockIdx.y * 4;
-    const int64_t row_lo = (int64_t)blockIdx.z * d.rows_per_chunk;
+    const int tiles_mn = (d.M / TM) * tiles_n;
+    const int g0 = (tile / tiles_mn) * 4, tmn = tile % tiles_mn;
+    const int m0 = (tmn / tiles_n) * TM, n0 = (tmn % tiles_n) * TN;
+    const int64_t row_lo = (int64_t)zi * d.rows_per_chunk;
     int64_t row_hi = row_lo + d.rows_per_chunk;
     if (row_hi > d.rows) row_hi = d.rows;
 
@@ -165,7 +165,7 @@ wgrad_gemm_kernel(WgradDesc d)
 
     // partial tile: P[z][g][m][n]
     const int ln = lane & 31, h = lane >> 5;
-    float* Pg = d.P + (((size_t)blockIdx.z * d.G + g0 + wave) * d.M) * d.N;
+    float* Pg = d.P + (((size_t)zi * d.G + g0 + wave) * d.M) * d.N;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -177,47 +177,94 @@ wgrad_gemm_kernel(WgradDesc d)
             }
 }
 
-// out[g][m][col(n)] = sum_z P[z][g][m][n];  col(n) = (n % seg_w) * (N / seg_w) + n / seg_w
-// (identity when seg_w == N).  OUT_F32: write float, else bf16.
-template <bool OUT_F32>
-__global__ void wgrad_reduce_kernel(const float* __restrict__ P, void* __restrict__ out, int nz,
-                                    size_t total, int N, int seg_w)
+// One launch for up to two GEMMs over the same batch chunks.  Workgroups are handed to the
+// eight XCDs round-robin by linear id; the id is remapped so that each XCD owns a contiguous
+// range of (chunk, tile) pairs with the tile index fastest: the tiles that re-read the same
+// operand rows then run on one XCD at about the same time and share its L2.
+template <int TM, int TN>
+__global__ void __launch_bounds__(256)
+wgrad_gemm_kernel(WgradDesc d0, WgradDesc d1, int tiles0, int tiles)
 {
-    const int nseg = N / seg_w;
-    size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; e < total; e += stride) {
-        float s = 0.f;
-        for (int z = 0; z < nz; ++z) s += P[(size_t)z * total + e];
-        const size_t rowbase = e / N * N;
-        const int n = (int)(e - rowbase);
-        const size_t o = rowbase + (size_t)(n % seg_w) * nseg + n / seg_w;
-        if (OUT_F32) {
-            ((float*)out)[o] = s;
-        } else {
-            const uint32_t pk = pack_bf16x2(s, 0.f);
-            ((uint16_t*)out)[o] = (uint16_t)(pk & 0xffffu);
-        }
+    const int nwg = gridDim.x, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int per = nwg >> 3, rem = nwg & 7;
+    const int v = xcd * per + (xcd < rem ? xcd : rem) + slot;
+    const int t = v % tiles, zi = v / tiles;
+    if (t < tiles0) {
+        if (d0.deint) wgrad_gemm_body<TM, TN, true>(d0, t, zi);
+        else wgrad_gemm_body<TM, TN, false>(d0, t, zi);
+    } else {
+        if (d1.deint) wgrad_gemm_body<TM, TN, true>(d1, t - tiles0, zi);
+        else wgrad_gemm_body<TM, TN, false>(d1, t - tiles0, zi);
     }
 }
 
-template <int TM, int TN, bool DEINT>
-int launch_gemm(const WgradDesc& d, int nz, hipStream_t st)
+// out[g][m][col(n)] = sum_z P[z][g][m][n];  col(n) = (n % seg_w) * (N / seg_w) + n / seg_w
+// (identity when seg_w == N).  Blocks [0, blocks0) reduce d0, the rest d1; one element per
+// thread, the chunk loop unrolled so that eight loads are in flight.
+template <bool OUT_F32>
+__global__ void __launch_bounds__(256)
+wgrad_reduce_kernel(WgradDesc d0, WgradDesc d1, int blocks0, int nz)
+{
+    const bool first = (int)blockIdx.x < blocks0;
+    const WgradDesc& d = first ? d0 : d1;
+    const size_t total = (size_t)d.G * d.M * d.N;
+    const size_t e = (size_t)(blockIdx.x - (first ? 0 : blocks0)) * 256 + threadIdx.x;
+    if (e >= total) return;
+    const float* P = d.P + e;
+    float s = 0.f;
+    int z = 0;
+    for (; z + 8 <= nz; z += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = P[(size_t)(z + u) * total];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; z < nz; ++z) s += P[(size_t)z * total];
+    const int nseg = d.N / d.seg_w;
+    const size_t rowbase = e / d.N * d.N;
+    const int n = (int)(e - rowbase);
+    const size_t o = rowbase + (size_t)(n % d.seg_w) * nseg + n / d.seg_w;
+    if (OUT_F32) {
+        ((float*)d.out)[o] = s;
+    } else {
+        const uint32_t pk = pack_bf16x2(s, 0.f);
+        ((uint16_t*)d.out)[o] = (uint16_t)(pk & 0xffffu);
+    }
+}
+
+int tiles_of(const WgradDesc& d, int tm, int tn) { return (d.M / tm) * (d.N / tn) * (d.G / 4); }
+
+template <int TM, int TN>
+int launch_gemm(const WgradDesc& d0, const WgradDesc* d1, int nz, hipStream_t st)
 {
     constexpr size_t lds = (size_t)4 * KB * (TM + 8 + TN + 8) * 2;
-    auto kern = wgrad_gemm_kernel<TM, TN, DEINT>;
+    auto kern = wgrad_gemm_kernel<TM, TN>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return -4;
-    dim3 grid((d.M / TM) * (d.N / TN), d.G / 4, nz);
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, d);
+    const int t0 = tiles_of(d0, TM, TN), t1 = d1 ? tiles_of(*d1, TM, TN) : 0;
+    hipLaunchKernelGGL(kern, dim3((t0 + t1) * nz), dim3(256), lds, st, d0, d1 ? *d1 : d0, t0, t0 + t1);
     return hip_status(hipGetLastError());
+}
+
+int launch_gemm_tile(int tm, int tn, const WgradDesc& d0, const WgradDesc* d1, int nz, hipStream_t st)
+{
+#define MONARCH_WG_CASE(TM_, TN_) \
+    if (tm == TM_ && tn == TN_) return launch_gemm<TM_, TN_>(d0, d1, nz, st);
+    MONARCH_WG_CASE(96, 96)
+    MONARCH_WG_CASE(64, 128)
+    MONARCH_WG_CASE(128, 64)
+    MONARCH_WG_CASE(64, 64)
+    MONARCH_WG_CASE(32, 32)
+#undef MONARCH_WG_CASE
+    return -2;
 }
 
 }  // namespace
 
 bool wgrad_tile_ok(int M, int N, int seg_w, int* tm, int* tn)
 {
-    // tile shapes instantiated below; a tile's 8-column pieces must not straddle a segment
+    // tile shapes instantiated above; a tile's 8-column pieces must not straddle a segment
     if (seg_w % 8 != 0) return false;
     const int cand[][2] = {{96, 96}, {64, 128}, {128, 64}, {64, 64}, {32, 32}};
     for (auto& c : cand)
@@ -229,30 +276,31 @@ bool wgrad_tile_ok(int M, int N, int seg_w, int* tm, int* tn)
     return false;
 }
 
-int wgrad_gemm(const WgradDesc& d, bool deint, int nz, hipStream_t st)
+int wgrad_tiles(const WgradDesc& d)
 {
     int tm, tn;
-    if (!wgrad_tile_ok(d.M, d.N, d.seg_w, &tm, &tn) || d.G % 4 != 0) return -2;
-#define MONARCH_WG_CASE(TM_, TN_)                                                        \
-    if (tm == TM_ && tn == TN_)                                                          \
-        return deint ? launch_gemm<TM_, TN_, true>(d, nz, st) : launch_gemm<TM_, TN_, false>(d, nz, st);
-    MONARCH_WG_CASE(96, 96)
-    MONARCH_WG_CASE(64, 128)
-    MONARCH_WG_CASE(128, 64)
-    MONARCH_WG_CASE(64, 64)
-    MONARCH_WG_CASE(32, 32)
-#undef MONARCH_WG_CASE
-    return -2;
+    if (!wgrad_tile_ok(d.M, d.N, d.seg_w, &tm, &tn) || d.G % 4 != 0) return 0;
+    return tiles_of(d, tm, tn);
 }
 
-int wgrad_reduce(const float* P, void* out, bool out_f32, int nz, size_t total, int N, int seg_w, hipStream_t st)
+int wgrad_gemm_pair(const WgradDesc& d0, const WgradDesc& d1, int nz, hipStream_t st)
 {
-    size_t g = (total + 255) / 256;
-    if (g > 4096) g = 4096;
+    int tm0, tn0, tm1, tn1;
+    if (!wgrad_tile_ok(d0.M, d0.N, d0.seg_w, &tm0, &tn0) || d0.G % 4 != 0) return -2;
+    if (!wgrad_tile_ok(d1.M, d1.N, d1.seg_w, &tm1, &tn1) || d1.G % 4 != 0) return -2;
+    if (tm0 == tm1 && tn0 == tn1) return launch_gemm_tile(tm0, tn0, d0, &d1, nz, st);
+    const int rc = launch_gemm_tile(tm0, tn0, d0, nullptr, nz, st);
+    return rc ? rc : launch_gemm_tile(tm1, tn1, d1, nullptr, nz, st);
+}
+
+int wgrad_reduce_pair(const WgradDesc& d0, const WgradDesc& d1, bool out_f32, int nz, hipStream_t st)
+{
+    const size_t b0 = ((size_t)d0.G * d0.M * d0.N + 255) / 256, b1 = ((size_t)d1.G * d1.M * d1.N + 255) / 256;
+    if (b0 + b1 > 0x7fffffffULL) return -2;
     if (out_f32)
-        hipLaunchKernelGGL(wgrad_reduce_kernel<true>, dim3((unsigned)g), dim3(256), 0, st, P, out, nz, total, N, seg_w);
+        hipLaunchKernelGGL(wgrad_reduce_kernel<true>, dim3((unsigned)(b0 + b1)), dim3(256), 0, st, d0, d1, (int)b0, nz);
     else
-        hipLaunchKernelGGL(wgrad_reduce_kernel<false>, dim3((unsigned)g), dim3(256), 0, st, P, out, nz, total, N, seg_w);
+        hipLaunchKernelGGL(wgrad_reduce_kernel<false>, dim3((unsigned)(b0 + b1)), dim3(256), 0, st, d0, d1, (int)b0, nz);
     return hip_status(hipGetLastError());
 }
 
