@@ -19,6 +19,7 @@
 // pieces y[b][l*64 + c0 .. c0+7].
 #include "monarch_internal.h"
 #include "monarch_mfma_common.h"
+#include <cstdlib>
 
 namespace monarch {
 
@@ -29,6 +30,7 @@ constexpr int SQ_BM = 32;                          // rows per workgroup
 constexpr int SQ_ROWB = 32 * 128 + 16;             // bytes per row of the exchange buffer (32 j x 64 kk + pad)
 constexpr size_t SQ_LDS = (size_t)SQ_BM * SQ_ROWB; // 131584 bytes
 
+template <int DBG>
 __global__ void __launch_bounds__(512)
 fwd_sq64_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
                 const uint16_t* __restrict__ L, uint16_t* __restrict__ y, int64_t B)
@@ -53,11 +55,11 @@ fwd_sq64_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
         u32x4 xa[2][4], ra[2][4];
         auto load_x = [&](int t, int s) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) xa[s][u] = ldg128(xrow + t * M64 + 8 * u);
+            for (int u = 0; u < 4; ++u) xa[s][u] = DBG == 4 ? u32x4{(uint32_t)t, 1u, 2u, 3u} : ldg128(xrow + t * M64 + 8 * u);
         };
         auto load_r = [&](int t, int jt) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) ra[jt][u] = ldg128(Rrow + ((size_t)t * M64 + 32 * jt) * M64 + 8 * u);
+            for (int u = 0; u < 4; ++u) ra[jt][u] = DBG == 2 ? u32x4{(uint32_t)t, 1u, 2u, 3u} : ldg128(Rrow + ((size_t)t * M64 + 32 * jt) * M64 + 8 * u);
         };
         load_x(0, 0);
         load_r(0, 0);
@@ -101,7 +103,10 @@ fwd_sq64_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
     }
 
     // ------------------------------------------------- exchange + step 2, two halves ----
+    // po[h][c2][i]: bf16 pair (c0 + 2*c2, c0 + 2*c2 + 1) of W[b = ln][c][l], c0 = 32h + 8cg,
+    // l = 32*lt + 8*(i/4) + 4*g + i%4
     const int cg = wave & 3, lt = wave >> 2;  // eight blocks c of the half, one 32-row tile of l
+    uint32_t po[2][4][16];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         if (h) {
@@ -115,9 +120,6 @@ fwd_sq64_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
         }
         __syncthreads();
 
-        // po[c2][i]: bf16 pair (c0 + 2*c2, c0 + 2*c2 + 1) of W[b = ln][c][l], c0 = 32h + 8cg,
-        // l = 32*lt + 8*(i/4) + 4*g + i%4
-        uint32_t po[4][16];
         const unsigned char* ub = ldsb + (size_t)ln * SQ_ROWB + (8 * cg) * 128 + 64 * g;
         const uint16_t* Lrow = L + (((size_t)(32 * h + 8 * cg)) * M64 + 32 * lt + ln) * M64 + 32 * g;
         u32x4 la[2][4];
@@ -130,7 +132,7 @@ fwd_sq64_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
             __builtin_amdgcn_sched_barrier(0);
             if (cc + 1 < 8) {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) la[s ^ 1][u] = ldg128(Lrow + (size_t)(cc + 1) * M64 * M64 + 8 * u);
+                for (int u = 0; u < 4; ++u) la[s ^ 1][u] = DBG == 3 ? u32x4{(uint32_t)cc, 1u, 2u, 3u} : ldg128(Lrow + (size_t)(cc + 1) * M64 * M64 + 8 * u);
             }
             __builtin_amdgcn_sched_barrier(0);
             f32x16 acc;
@@ -145,17 +147,38 @@ fwd_sq64_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
                 ev = acc;
             } else {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) po[cc >> 1][i] = pack_bf16x2(ev[i], acc[i]);
+                for (int i = 0; i < 16; ++i) po[h][cc >> 1][i] = pack_bf16x2(ev[i], acc[i]);
             }
         }
-        // step 3: y[b][l*64 + c0 .. c0+7]
-        if (row_ok) {
-            uint16_t* yrow = y + row * N64 + 32 * h + 8 * cg;
+    }
+
+    // ---------------------------------------------------------------- step 3 ----
+    // y[b][l*64 + c] is written in full 128-byte lines (all 64 c of one (b, l)): the results are
+    // transposed through LDS, one 32-row tile of l per round.  LDS tile: [b][l][8 pieces of 16 B],
+    // piece index XOR-ed with b % 8 so that the writes of 8 adjacent lanes hit 8 different slots.
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int l = 32 * lt + 8 * (i >> 2) + 4 * g + (i & 3);
-                *reinterpret_cast<u32x4*>(yrow + (size_t)l * M64) = u32x4{po[0][i], po[1][i], po[2][i], po[3][i]};
-            }
+    for (int rnd = 0; rnd < 2; ++rnd) {
+        __syncthreads();  // the exchange buffer (or the previous round's tile) is dead
+        if (lt == rnd) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int l = 8 * (i >> 2) + 4 * g + (i & 3);
+                    const int piece = (4 * h + cg) ^ (ln & 7);
+                    *reinterpret_cast<u32x4*>(ldsb + (size_t)ln * 4096 + l * 128 + piece * 16) =
+                        u32x4{po[h][0][i], po[h][1][i], po[h][2][i], po[h][3][i]};
+                }
+        }
+        __syncthreads();
+        // wave w copies rows b = 4w .. 4w+3: 128 lines, eight per instruction (1 KiB contiguous in y)
+#pragma unroll
+        for (int k2 = 0; k2 < 16; ++k2) {
+            const int line = 8 * k2 + (lane >> 3), pc = lane & 7;
+            const int b = 4 * wave + (line >> 5), l = line & 31;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(ldsb + (size_t)b * 4096 + l * 128 + ((pc ^ (b & 7)) * 16));
+            if (DBG != 1 && b0 + b < B)
+                *reinterpret_cast<u32x4*>(y + (b0 + b) * N64 + (size_t)(32 * rnd + l) * M64 + 8 * pc) = v;
         }
     }
 }
@@ -170,7 +193,8 @@ bool sq64_supported(const Problem& pb)
 int fwd_sq64(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
 {
     if (!sq64_supported(pb)) return -2;
-    auto kern = fwd_sq64_kernel;
+    static const int v = getenv("MONARCH_SQ64_VARIANT") ? atoi(getenv("MONARCH_SQ64_VARIANT")) : 0;  // TUNING
+    auto kern = v == 1 ? fwd_sq64_kernel<1> : v == 2 ? fwd_sq64_kernel<2> : v == 3 ? fwd_sq64_kernel<3> : v == 4 ? fwd_sq64_kernel<4> : fwd_sq64_kernel<0>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ_LDS) != hipSuccess)
         return -4;
     const int64_t grid = (pb.B + SQ_BM - 1) / SQ_BM;
