@@ -56,6 +56,10 @@ int bwd_wide(const Problem& pb, const void* dy, const void* x, const void* R, co
 // bf16, square m = 64 (k = q = s = p = 64): fused forward and backward (monarch_mfma_sq64.hip)
 bool sq64_supported(const Problem& pb);
 int fwd_sq64(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
+bool bwd_sq64_supported(const Problem& pb);
+size_t bwd_sq64_workspace(const Problem& pb);
+int bwd_sq64(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx,
+             void* dR, void* dL, void* ws, hipStream_t st);
 
 // Batch-contracted GEMM for the weight gradients (monarch_mfma_wgrad.hip):
 //   P[z][g][m][n] = sum over the rows of batch chunk z of  A[row][g, m] * Bm[row][g, n]

@@ -17,13 +17,24 @@ int mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, voi
     return -2;
 }
 
-bool mfma_bwd_supported(const Problem& pb) { return bwd_wide_supported(pb); }
-size_t mfma_bwd_workspace(const Problem& pb) { return bwd_wide_supported(pb) ? bwd_wide_workspace(pb) : 0; }
-const char* mfma_bwd_name(const Problem& pb) { return bwd_wide_supported(pb) ? "mfma_bwd_wide_bf16" : "unsupported"; }
+bool mfma_bwd_supported(const Problem& pb) { return bwd_wide_supported(pb) || bwd_sq64_supported(pb); }
+size_t mfma_bwd_workspace(const Problem& pb)
+{
+    if (bwd_wide_supported(pb)) return bwd_wide_workspace(pb);
+    if (bwd_sq64_supported(pb)) return bwd_sq64_workspace(pb);
+    return 0;
+}
+const char* mfma_bwd_name(const Problem& pb)
+{
+    if (bwd_wide_supported(pb)) return "mfma_bwd_wide_bf16";
+    if (bwd_sq64_supported(pb)) return "mfma_bwd_sq64_bf16";
+    return "unsupported";
+}
 int mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
              void* dL, void* ws, hipStream_t st)
 {
     if (bwd_wide_supported(pb)) return bwd_wide(pb, dy, x, R, L, dx, dR, dL, ws, st);
+    if (bwd_sq64_supported(pb)) return bwd_sq64(pb, dy, x, R, L, dx, dR, dL, ws, st);
     return -2;
 }
 
