@@ -3,17 +3,19 @@
 
 namespace monarch {
 
-bool mfma_fwd_supported(const Problem& pb) { return fwd_wide_supported(pb) || sq64_supported(pb); }
+bool mfma_fwd_supported(const Problem& pb) { return fwd_wide_supported(pb) || sq64_supported(pb) || sq16_supported(pb); }
 const char* mfma_fwd_name(const Problem& pb)
 {
     if (fwd_wide_supported(pb)) return "mfma_fwd_wide_bf16";
     if (sq64_supported(pb)) return "mfma_fwd_sq64_bf16";
+    if (sq16_supported(pb)) return "mfma_fwd_sq16_f32";
     return "unsupported";
 }
 int mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
 {
     if (fwd_wide_supported(pb)) return fwd_wide(pb, x, R, L, y, st);
     if (sq64_supported(pb)) return fwd_sq64(pb, x, R, L, y, st);
+    if (sq16_supported(pb)) return fwd_sq16(pb, x, R, L, y, st);
     return -2;
 }
 
