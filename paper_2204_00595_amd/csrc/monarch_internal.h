@@ -64,6 +64,9 @@ int bwd_sq64(const Problem& pb, const void* dy, const void* x, const void* R, co
 // fp32, square m = 16 (k = q = s = p = 16): persistent MFMA kernels (monarch_mfma_sq16.hip)
 bool sq16_supported(const Problem& pb);
 int fwd_sq16(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
+size_t bwd_sq16_workspace(const Problem& pb);
+int bwd_sq16(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx,
+             void* dR, void* dL, void* ws, hipStream_t st);
 
 // Batch-contracted GEMM for the weight gradients (monarch_mfma_wgrad.hip):
 //   P[z][g][m][n] = sum over the rows of batch chunk z of  A[row][g, m] * Bm[row][g, n]

@@ -19,17 +19,19 @@ int mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, voi
     return -2;
 }
 
-bool mfma_bwd_supported(const Problem& pb) { return bwd_wide_supported(pb) || bwd_sq64_supported(pb); }
+bool mfma_bwd_supported(const Problem& pb) { return bwd_wide_supported(pb) || bwd_sq64_supported(pb) || sq16_supported(pb); }
 size_t mfma_bwd_workspace(const Problem& pb)
 {
     if (bwd_wide_supported(pb)) return bwd_wide_workspace(pb);
     if (bwd_sq64_supported(pb)) return bwd_sq64_workspace(pb);
+    if (sq16_supported(pb)) return bwd_sq16_workspace(pb);
     return 0;
 }
 const char* mfma_bwd_name(const Problem& pb)
 {
     if (bwd_wide_supported(pb)) return "mfma_bwd_wide_bf16";
     if (bwd_sq64_supported(pb)) return "mfma_bwd_sq64_bf16";
+    if (sq16_supported(pb)) return "mfma_bwd_sq16_f32";
     return "unsupported";
 }
 int mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
@@ -37,6 +39,7 @@ int mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, co
 {
     if (bwd_wide_supported(pb)) return bwd_wide(pb, dy, x, R, L, dx, dR, dL, ws, st);
     if (bwd_sq64_supported(pb)) return bwd_sq64(pb, dy, x, R, L, dx, dR, dL, ws, st);
+    if (sq16_supported(pb)) return bwd_sq16(pb, dy, x, R, L, dx, dR, dL, ws, st);
     return -2;
 }
 

@@ -131,6 +131,216 @@ fwd_sq16_kernel(const float* __restrict__ x, const float* __restrict__ R, const 
     }
 }
 
+// W[block][row][col] -> transposed operand order: dst[block][lane] = W[block][4 * (lane / 16) + u][lane % 16], u = 0..3
+__device__ __forceinline__ void stage_weights_t(const float* __restrict__ W, unsigned char* dst, int tid, int nthreads)
+{
+    for (int e = tid; e < 16 * 64; e += nthreads) {
+        const int blk = e >> 6, lane = e & 63;
+        const float* p = W + ((size_t)blk * 16 + 4 * (lane >> 4)) * 16 + (lane & 15);
+        *reinterpret_cast<f32x4*>(dst + (size_t)e * 16) = f32x4{p[0], p[16], p[32], p[48]};
+    }
+}
+
+// Backward: one persistent kernel for dx, dR and dL (adjoints of steps 3, 2, P^T, 1 of Section 3.3;
+// the paper leaves them to automatic differentiation, Section 4).  4 waves per workgroup, one per
+// SIMD, so that a wave can keep both weight gradients (2 x 4096 fp32 = 128 registers per lane) in
+// MFMA accumulators for the whole launch next to its operands.  Per 16-row tile a wave runs five
+// groups of 64 MFMAs; its LDS tile is reused between them for the re-layouts:
+//   1. Y1 = step 1 (recomputed)                            -> tile [b][kk][j]
+//   2. dL[c][l][r] += sum_b dy[b][16l + c] Y1[b][r][c]      contraction over the 16 rows: operands
+//      are read "down the rows" (lane = l resp. r, K-slot = row), 16 bytes = four blocks c at once
+//   3. dU[b][c][r] = sum_l L[c][l][r] dy[b][16l + c], i.e. dY1[b][kk = r][j = c] -> tile [b][j][kk]
+//   4. dR[kk][j][i] += sum_b dY1[b][kk][j] x[b][16kk + i]   (x re-laid as tile [b][i][kk])
+//   5. dx[b][16kk + i] = sum_j R[kk][j][i] dY1[b][kk][j]    -> tile, then full-row stores
+// The per-wave gradients go to the workspace and are summed by `reduce_sq16_kernel`.
+constexpr int SQ16B_WAVES = 4;
+constexpr size_t SQ16B_LDS = 4 * SQ16_W_BYTES + SQ16B_WAVES * SQ16_T_BYTES;  // 128 KiB
+
+__global__ void __launch_bounds__(256)
+bwd_sq16_kernel(const float* __restrict__ dy, const float* __restrict__ x, const float* __restrict__ R,
+                const float* __restrict__ L, float* __restrict__ dx, float* __restrict__ P, int64_t B, int64_t ntiles)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char ldsb[];
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int bl = lane & 15, h = lane >> 4;
+    unsigned char* Rop = ldsb;                         // R[kk][j = lane%16][i = 4h + u]
+    unsigned char* RTop = ldsb + SQ16_W_BYTES;         // R[kk][j = 4h + u][i = lane%16]
+    unsigned char* LTop = ldsb + 2 * SQ16_W_BYTES;     // L[c][l = 4h + u][r = lane%16]
+    unsigned char* T = ldsb + 3 * SQ16_W_BYTES + (size_t)wave * SQ16_T_BYTES;
+    stage_weights(R, Rop, tid, 256);
+    stage_weights_t(R, RTop, tid, 256);
+    stage_weights_t(L, LTop, tid, 256);
+    __syncthreads();
+
+    f32x4 accR[16], accL[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        accR[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        accL[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const int64_t stride = (int64_t)gridDim.x * SQ16B_WAVES;
+    int64_t tile = (int64_t)blockIdx.x * SQ16B_WAVES + wave;
+    auto load_x = [&](int64_t tl, f32x4 (&xa)[16]) {
+        int64_t row = tl * 16 + bl;
+        row = row < B ? row : B - 1;
+        const float* p = x + row * N16 + 4 * h;
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) xa[kk] = *reinterpret_cast<const f32x4*>(p + 16 * kk);
+    };
+    // dya[v] = dy[b][64h + 4v .. +3]: element 16u + c is dW[b][c][l = 4h + u]; rows past the end count as zero
+    auto load_dy = [&](int64_t tl, f32x4 (&dya)[16]) {
+        int64_t row = tl * 16 + bl;
+        const float m = row < B ? 1.f : 0.f;
+        row = row < B ? row : B - 1;
+        const float* p = dy + row * N16 + 64 * h;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) dya[v] = *reinterpret_cast<const f32x4*>(p + 4 * v) * m;
+    };
+    f32x4 xa[16], dya[16];
+    if (tile < ntiles) {
+        load_x(tile, xa);
+        load_dy(tile, dya);
+    }
+    for (; tile < ntiles; tile += stride) {
+        const int64_t b0 = tile * 16;
+        const int64_t next = tile + stride;
+        // ---- 1. Y1[b][kk][j = 4h + i] -> tile [b][kk][j]
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            const f32x4 ra = *reinterpret_cast<const f32x4*>(Rop + ((size_t)kk * 64 + lane) * 16);
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc = mfma4(ra[u], xa[kk][u], acc);
+            *reinterpret_cast<f32x4*>(T + t_off(bl, 4 * kk + h)) = acc;
+        }
+        wave_lds_fence();
+        // ---- 2. dL: A lane (l, h) = dy[b0 + 4h + u][16l + c], B lane (r, h) = Y1[b0 + 4h + u][r][c]
+#pragma unroll
+        for (int cq = 0; cq < 4; ++cq) {
+            f32x4 da[4], ub[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                int64_t row = b0 + 4 * h + u;
+                const float m = row < B ? 1.f : 0.f;
+                row = row < B ? row : B - 1;
+                da[u] = *reinterpret_cast<const f32x4*>(dy + row * N16 + 16 * bl + 4 * cq) * m;
+                ub[u] = *reinterpret_cast<const f32x4*>(T + t_off(4 * h + u, 4 * bl + cq));
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) accL[4 * cq + e] = mfma4(da[u][e], ub[u][e], accL[4 * cq + e]);
+        }
+        wave_lds_fence();  // Y1 has been read: the tile is reused
+        // ---- 3. dY1[b][kk = 4h + i][j = c] -> tile [b][j][kk]
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            const f32x4 la = *reinterpret_cast<const f32x4*>(LTop + ((size_t)c * 64 + lane) * 16);
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc = mfma4(la[u], dya[4 * u + (c >> 2)][c & 3], acc);
+            *reinterpret_cast<f32x4*>(T + t_off(bl, 4 * c + h)) = acc;
+        }
+        if (next < ntiles) load_dy(next, dya);  // the next tile's rows are fetched early
+        wave_lds_fence();
+        // operands of 4 (lane (j, h): dY1[b0 + 4h + u][kk][j], four kk per read) and of 5
+        // (lane (b, h): dY1[b][kk][j = 4h + u], four kk per read)
+        f32x4 a2[4][4], db[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                a2[u][v] = *reinterpret_cast<const f32x4*>(T + t_off(4 * h + u, 4 * bl + v));
+                db[u][v] = *reinterpret_cast<const f32x4*>(T + t_off(bl, 4 * (4 * h + u) + v));
+            }
+        wave_lds_fence();
+        // x re-laid as tile [b][i][kk]
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                *reinterpret_cast<f32x4*>(T + t_off(bl, 4 * (4 * h + e) + v)) =
+                    f32x4{xa[4 * v][e], xa[4 * v + 1][e], xa[4 * v + 2][e], xa[4 * v + 3][e]};
+        if (next < ntiles) load_x(next, xa);
+        wave_lds_fence();
+        // ---- 4. dR: B lane (i, h) = x[b0 + 4h + u][16kk + i]
+#pragma unroll
+        for (int kq = 0; kq < 4; ++kq) {
+            f32x4 xb[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) xb[u] = *reinterpret_cast<const f32x4*>(T + t_off(4 * h + u, 4 * bl + kq));
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) accR[4 * kq + e] = mfma4(a2[u][kq][e], xb[u][e], accR[4 * kq + e]);
+        }
+        wave_lds_fence();
+        // ---- 5. dx[b][16kk + 4h + i] -> tile (row-major), then one full row per store instruction
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            const f32x4 rt = *reinterpret_cast<const f32x4*>(RTop + ((size_t)kk * 64 + lane) * 16);
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc = mfma4(rt[u], db[u][kk >> 2][kk & 3], acc);
+            *reinterpret_cast<f32x4*>(T + t_off(bl, 4 * kk + h)) = acc;
+        }
+        wave_lds_fence();
+#pragma unroll
+        for (int k2 = 0; k2 < 16; ++k2) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(T + t_off(k2, lane));
+            if (b0 + k2 < B) *reinterpret_cast<f32x4*>(dx + (b0 + k2) * N16 + 4 * lane) = v;
+        }
+        wave_lds_fence();
+    }
+    // per-wave gradients: P[wave id][0][kk][j][i], P[wave id][1][c][l][r]; acc[e] is row 4h + e, column lane % 16
+    float* Pw = P + ((size_t)blockIdx.x * SQ16B_WAVES + wave) * 8192;
+#pragma unroll
+    for (int t = 0; t < 16; ++t)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            Pw[t * 256 + (4 * h + e) * 16 + bl] = accR[t][e];
+            Pw[4096 + t * 256 + (4 * h + e) * 16 + bl] = accL[t][e];
+        }
+}
+
+// out[e] = sum_z P[z][e] for the 8192 gradient entries (dR then dL); 16 entries x 16 z-lanes per block
+__global__ void __launch_bounds__(256)
+reduce_sq16_kernel(const float* __restrict__ P, float* __restrict__ dR, float* __restrict__ dL, int nz)
+{
+    __shared__ float part[16][17];
+    const int el = threadIdx.x & 15, zl = threadIdx.x >> 4;
+    const int e = blockIdx.x * 16 + el;
+    float s = 0.f;
+    int z = zl;
+    for (; z + 16 * 7 < nz; z += 16 * 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = P[(size_t)(z + 16 * u) * 8192 + e];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; z < nz; z += 16) s += P[(size_t)z * 8192 + e];
+    part[zl][el] = s;
+    __syncthreads();
+    if (zl == 0) {
+        float tot = 0.f;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) tot += part[k][el];
+        if (e < 4096) dR[e] = tot;
+        else dL[e - 4096] = tot;
+    }
+}
+
+int bwd_sq16_grid(const Problem& pb)
+{
+    const int64_t ntiles = (pb.B + 15) / 16;
+    int64_t grid = (ntiles + SQ16B_WAVES - 1) / SQ16B_WAVES;
+    if (grid > 256) grid = 256;  // one persistent workgroup per CU
+    if (grid < 1) grid = 1;
+    return (int)grid;
+}
+
 }  // namespace
 
 bool sq16_supported(const Problem& pb)
@@ -150,6 +360,33 @@ int fwd_sq16(const Problem& pb, const void* x, const void* R, const void* L, voi
     if (grid > 256) grid = 256;  // one persistent workgroup per CU
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), SQ16_LDS, st, (const float*)x, (const float*)R,
                        (const float*)L, (float*)y, pb.B, ntiles);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace monarch
+
+namespace monarch {
+
+size_t bwd_sq16_workspace(const Problem& pb) { return (size_t)bwd_sq16_grid(pb) * SQ16B_WAVES * 8192 * sizeof(float); }
+
+int bwd_sq16(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx,
+             void* dR, void* dL, void* ws, hipStream_t st)
+{
+    if (!sq16_supported(pb)) return -2;
+    if (pb.B == 0) {
+        const int rc = launch_fill_zero_f32((float*)dR, pb.n_R(), st);
+        return rc ? rc : launch_fill_zero_f32((float*)dL, pb.n_L(), st);
+    }
+    auto kern = bwd_sq16_kernel;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ16B_LDS) != hipSuccess)
+        return -4;
+    const int grid = bwd_sq16_grid(pb);
+    const int64_t ntiles = (pb.B + 15) / 16;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), SQ16B_LDS, st, (const float*)dy, (const float*)x, (const float*)R,
+                       (const float*)L, (float*)dx, (float*)ws, pb.B, ntiles);
+    if (hipGetLastError() != hipSuccess) return -4;
+    hipLaunchKernelGGL(reduce_sq16_kernel, dim3(8192 / 16), dim3(256), 0, st, (const float*)ws, (float*)dR, (float*)dL,
+                       grid * SQ16B_WAVES);
     return hip_status(hipGetLastError());
 }
 
