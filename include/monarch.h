@@ -95,9 +95,10 @@ int monarch_fwd_ex(const void* x, const void* R, const void* L, void* y,
  *   dR[kk][j][i] = sum_b dY1[b][kk][j] * x[b][kk*p + i]
  *   dx[b][kk*p+i]= sum_j R[kk][j][i] * dY1[b][kk][j]
  * U is recomputed from x (no activation is saved by the forward call).  dx, dR
- * and dL are overwritten, never accumulated into.  The batch reduction of dR/dL
- * uses fp32 atomics across workgroups, so they are reproducible only up to
- * fp32 summation order.  `workspace` must hold at least
+ * and dL are overwritten, never accumulated into.  The matrix-core kernels sum
+ * per-chunk partial gradients in a fixed order (bit-reproducible); the
+ * shape-generic fallback reduces dR/dL with fp32 atomics across workgroups, so
+ * its results are reproducible only up to fp32 summation order.  `workspace` must hold at least
  * monarch_bwd_workspace_bytes(...) bytes (device memory, 256-byte aligned);
  * its contents on entry are ignored and on exit are unspecified. */
 int monarch_bwd(const void* dy, const void* x, const void* R, const void* L,
@@ -114,6 +115,14 @@ size_t monarch_bwd_workspace_bytes(int64_t batch, int n_in, int k, int q, int s,
  * 1 = backward.  Static string, never NULL ("invalid" / "unsupported" on bad input). */
 const char* monarch_kernel_name(int pass, int n_in, int k, int q, int s,
                                 monarch_dtype dtype, unsigned flags);
+
+/* Measurement aid, not part of the method: a plain streaming device-to-device copy
+ * (16 bytes per lane, grid-stride) of `nbytes` bytes.  bench.py times it as the
+ * empirical HBM roof of the machine, and its known traffic calibrates the
+ * FETCH_SIZE / WRITE_SIZE hardware counters of a profiler run.  dst and src are
+ * device pointers, 16-byte aligned, nbytes a multiple of 16, non-overlapping.
+ * Returns MONARCH_ERR_INVALID otherwise; nbytes == 0 is a successful no-op. */
+int monarch_stream_copy(void* dst, const void* src, size_t nbytes, void* stream);
 
 /* Human-readable text for a status code.  Static string, never NULL. */
 const char* monarch_status_string(int status);

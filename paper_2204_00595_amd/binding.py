@@ -29,7 +29,7 @@ MONARCH_FLAG_GENERIC = 4
 # every symbol include/monarch.h declares
 EXPORTS = (
     "monarch_fwd", "monarch_fwd_ex", "monarch_bwd", "monarch_bwd_workspace_bytes",
-    "monarch_kernel_name", "monarch_status_string", "monarch_version",
+    "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy",
 )
 
 _lib = None
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.monarch_status_string.argtypes = [ci]
         L.monarch_version.restype = ci
         L.monarch_version.argtypes = []
+        L.monarch_stream_copy.restype = ci
+        L.monarch_stream_copy.argtypes = [vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -91,6 +93,20 @@ def _check(t: torch.Tensor, name: str, shape, dtype, device):
 def _stream_ptr(stream) -> int:
     st = torch.cuda.current_stream() if stream is None else stream
     return int(st.cuda_stream)
+
+
+def monarch_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> torch.Tensor:
+    """Plain streaming copy src -> dst (same byte size, contiguous, on one GPU): the measured HBM roof."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or not (dst.is_cuda and src.is_cuda and dst.device == src.device):
+        raise ValueError("dst and src must be GPU tensors of the same byte size on one device")
+    if not (dst.is_contiguous() and src.is_contiguous()):
+        raise ValueError("dst and src must be contiguous")
+    with torch.cuda.device(src.device):
+        rc = lib().monarch_stream_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream))
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_stream_copy")
+    return dst
 
 
 def monarch_version() -> int:

@@ -119,6 +119,16 @@ const char* monarch_kernel_name(int pass, int n_in, int k, int q, int s, monarch
     return "unsupported";
 }
 
+int monarch_stream_copy(void* dst, const void* src, size_t nbytes, void* stream)
+{
+    if (nbytes == 0) return MONARCH_OK;
+    if (!dst || !src || nbytes % 16 != 0 || !aligned(dst, 16) || !aligned(src, 16)) return MONARCH_ERR_INVALID;
+    const char* d = (const char*)dst;
+    const char* s = (const char*)src;
+    if (d < s + nbytes && s < d + nbytes) return MONARCH_ERR_INVALID;  // overlap
+    return launch_stream_copy(dst, src, nbytes, (hipStream_t)stream);
+}
+
 const char* monarch_status_string(int status)
 {
     switch (status) {

@@ -97,6 +97,7 @@ int wgrad_reduce_pair(const WgradDesc& d0, const WgradDesc& d1, bool out_f32, in
 int launch_fill_zero_f32(float* p, size_t n, hipStream_t st);
 int launch_fill_zero_u16(uint16_t* p, size_t n, hipStream_t st);
 int launch_f32_to_bf16(const float* src, uint16_t* dst, size_t n, hipStream_t st);
+int launch_stream_copy(void* dst, const void* src, size_t nbytes, hipStream_t st);
 
 static inline int hip_status(hipError_t e) { return e == hipSuccess ? 0 : -4; }
 

@@ -36,6 +36,11 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 }
 
 __device__ __forceinline__ u32x4 ldg128(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
+// streaming (non-temporal) 16-byte global accesses for data touched once per launch
+__device__ __forceinline__ u32x4 ldg128_nt(const void* p) { return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)); }
+__device__ __forceinline__ void stg128_nt(void* p, u32x4 v) { __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p)); }
+__device__ __forceinline__ f32x4 ldg128f_nt(const void* p) { return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p)); }
+__device__ __forceinline__ void stg128f_nt(void* p, f32x4 v) { __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p)); }
 __device__ __forceinline__ u32x4 lds128(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)

@@ -67,10 +67,6 @@ fwd_sq16_kernel(const float* __restrict__ x, const float* __restrict__ R, const 
     unsigned char* Rop = ldsb;
     unsigned char* Lop = ldsb + SQ16_W_BYTES;
     unsigned char* T = ldsb + 2 * SQ16_W_BYTES + (size_t)wave * SQ16_T_BYTES;
-    stage_weights(R, Rop, tid, 512);
-    stage_weights(L, Lop, tid, 512);
-    __syncthreads();
-
     const int64_t stride = (int64_t)gridDim.x * SQ16_WAVES;
     int64_t tile = (int64_t)blockIdx.x * SQ16_WAVES + wave;
     auto load_x = [&](int64_t tl, f32x4 (&xa)[16]) {
@@ -78,10 +74,13 @@ fwd_sq16_kernel(const float* __restrict__ x, const float* __restrict__ R, const 
         row = row < B ? row : B - 1;  // rows past the end are computed from a valid row and dropped
         const float* p = x + row * N16 + 4 * h;
 #pragma unroll
-        for (int kk = 0; kk < 16; ++kk) xa[kk] = *reinterpret_cast<const f32x4*>(p + 16 * kk);
+        for (int kk = 0; kk < 16; ++kk) xa[kk] = ldg128f_nt(p + 16 * kk);
     };
     f32x4 xa[16];
-    if (tile < ntiles) load_x(tile, xa);
+    if (tile < ntiles) load_x(tile, xa);  // in flight while the weights are staged
+    stage_weights(R, Rop, tid, 512);
+    stage_weights(L, Lop, tid, 512);
+    __syncthreads();
     for (; tile < ntiles; tile += stride) {
         // ---- step 1: Y1[b][kk][j = 4h + i] -> T[b][kk][j]
 #pragma unroll
@@ -125,7 +124,7 @@ fwd_sq16_kernel(const float* __restrict__ x, const float* __restrict__ R, const 
 #pragma unroll
         for (int k2 = 0; k2 < 16; ++k2) {
             const f32x4 v = *reinterpret_cast<const f32x4*>(T + t_off(k2, lane));
-            if (b0 + k2 < B) *reinterpret_cast<f32x4*>(y + (b0 + k2) * N16 + 4 * lane) = v;
+            if (b0 + k2 < B) stg128f_nt(y + (b0 + k2) * N16 + 4 * lane, v);
         }
         wave_lds_fence();  // the tile is free again for the next step 1
     }
@@ -168,11 +167,6 @@ bwd_sq16_kernel(const float* __restrict__ dy, const float* __restrict__ x, const
     unsigned char* RTop = ldsb + SQ16_W_BYTES;         // R[kk][j = 4h + u][i = lane%16]
     unsigned char* LTop = ldsb + 2 * SQ16_W_BYTES;     // L[c][l = 4h + u][r = lane%16]
     unsigned char* T = ldsb + 3 * SQ16_W_BYTES + (size_t)wave * SQ16_T_BYTES;
-    stage_weights(R, Rop, tid, 256);
-    stage_weights_t(R, RTop, tid, 256);
-    stage_weights_t(L, LTop, tid, 256);
-    __syncthreads();
-
     f32x4 accR[16], accL[16];
 #pragma unroll
     for (int t = 0; t < 16; ++t) {
@@ -186,7 +180,7 @@ bwd_sq16_kernel(const float* __restrict__ dy, const float* __restrict__ x, const
         row = row < B ? row : B - 1;
         const float* p = x + row * N16 + 4 * h;
 #pragma unroll
-        for (int kk = 0; kk < 16; ++kk) xa[kk] = *reinterpret_cast<const f32x4*>(p + 16 * kk);
+        for (int kk = 0; kk < 16; ++kk) xa[kk] = ldg128f_nt(p + 16 * kk);
     };
     // dya[v] = dy[b][64h + 4v .. +3]: element 16u + c is dW[b][c][l = 4h + u]; rows past the end count as zero
     auto load_dy = [&](int64_t tl, f32x4 (&dya)[16]) {
@@ -198,10 +192,14 @@ bwd_sq16_kernel(const float* __restrict__ dy, const float* __restrict__ x, const
         for (int v = 0; v < 16; ++v) dya[v] = *reinterpret_cast<const f32x4*>(p + 4 * v) * m;
     };
     f32x4 xa[16], dya[16];
-    if (tile < ntiles) {
+    if (tile < ntiles) {  // in flight while the weights are staged
         load_x(tile, xa);
         load_dy(tile, dya);
     }
+    stage_weights(R, Rop, tid, 256);
+    stage_weights_t(R, RTop, tid, 256);
+    stage_weights_t(L, LTop, tid, 256);
+    __syncthreads();
     for (; tile < ntiles; tile += stride) {
         const int64_t b0 = tile * 16;
         const int64_t next = tile + stride;
@@ -289,7 +287,7 @@ bwd_sq16_kernel(const float* __restrict__ dy, const float* __restrict__ x, const
 #pragma unroll
         for (int k2 = 0; k2 < 16; ++k2) {
             const f32x4 v = *reinterpret_cast<const f32x4*>(T + t_off(k2, lane));
-            if (b0 + k2 < B) *reinterpret_cast<f32x4*>(dx + (b0 + k2) * N16 + 4 * lane) = v;
+            if (b0 + k2 < B) stg128f_nt(dx + (b0 + k2) * N16 + 4 * lane, v);
         }
         wave_lds_fence();
     }

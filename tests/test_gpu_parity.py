@@ -218,3 +218,13 @@ def test_mlp_pair_end_to_end(B):
     compare(sh, [host(t) for t in (h, y, dh, dR2, dL2, dx, dR1, dL1)],
             [ho, yo, dho, dR2o, dL2o, dxo, dR1o, dL1o],
             ["h", "y", "dh", "dR2", "dL2", "dx", "dR1", "dL1"])
+
+
+def test_stream_copy_is_bit_exact(B):
+    n = (1 << 20) + 48  # bytes: several grid strides plus a ragged tail of three 16-byte pieces
+    src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
+    buf = torch.full((n + 2 * GUARD,), 7, dtype=torch.uint8, device="cuda")
+    B.monarch_stream_copy(buf[GUARD:GUARD + n], src)
+    torch.cuda.synchronize()
+    assert bool((buf[GUARD:GUARD + n] == src).all())
+    assert bool((buf[:GUARD] == 7).all()) and bool((buf[-GUARD:] == 7).all())

@@ -91,6 +91,15 @@ def test_backward_rejects_bad_arguments_without_a_gpu(binding):
     assert binding.monarch_bwd_workspace_bytes(1, 769, 4, 192, 192, 1, 0) == 0
 
 
+def test_stream_copy_rejects_bad_arguments_without_a_gpu(binding):
+    L = binding.lib()
+    assert L.monarch_stream_copy(None, None, 0, None) == binding.MONARCH_OK          # empty copy: no-op
+    assert L.monarch_stream_copy(None, 4096, 64, None) == binding.MONARCH_ERR_INVALID
+    assert L.monarch_stream_copy(4096, 8192, 24, None) == binding.MONARCH_ERR_INVALID   # not a multiple of 16
+    assert L.monarch_stream_copy(4100, 8192, 64, None) == binding.MONARCH_ERR_INVALID   # misaligned
+    assert L.monarch_stream_copy(4096, 4128, 64, None) == binding.MONARCH_ERR_INVALID   # overlap
+
+
 def test_kernel_name_reports_dispatch(binding):
     assert binding.monarch_kernel_name(0, 770, 4, 192, 192, 1) == "invalid"
     assert binding.monarch_kernel_name(2, 768, 4, 192, 192, 1) == "invalid"
