@@ -196,7 +196,7 @@ __device__ __forceinline__ void stage2_pass_lines(const uint16_t* __restrict__ L
             const int64_t row = b0 + (ww & 1) * 32 + 8 * (e / 4) + 4 * g + (e % 4);
             if (row < B) {
                 u32x2 v = {pack_bf16x2(acc[i * K + 0][e], acc[i * K + 1][e]), pack_bf16x2(acc[i * K + 2][e], acc[i * K + 3][e])};
-                *reinterpret_cast<u32x2*>(y + row * C::N_OUT + (size_t)l * K) = v;
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(y + row * C::N_OUT + (size_t)l * K));
             }
         }
     }
@@ -298,7 +298,7 @@ __device__ __forceinline__ void stage2_pass(const uint16_t* __restrict__ L, cons
             const int64_t row = b0 + (uu & 1) * 32 + 8 * (e / 4) + 4 * g + (e % 4);
             if (row < B) {
                 u32x2 v = {pack_bf16x2(acc[i * K + 0][e], acc[i * K + 1][e]), pack_bf16x2(acc[i * K + 2][e], acc[i * K + 3][e])};
-                *reinterpret_cast<u32x2*>(y + row * C::N_OUT + (size_t)l * K) = v;
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(y + row * C::N_OUT + (size_t)l * K));
             }
         }
     }

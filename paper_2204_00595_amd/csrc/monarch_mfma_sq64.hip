@@ -168,7 +168,11 @@ __device__ __forceinline__ void copy_out(const Lane& t_, const unsigned char* ld
         const unsigned char* src = SWZ ? ldsb + (size_t)b * 4096 + jl * 128 + ((pc ^ (b & 7)) * 16)
                                        : ldsb + (size_t)b * SQ_ROWB + jl * 128 + pc * 16;
         const u32x4 v = *reinterpret_cast<const u32x4*>(src);
-        if (b0 + b < B) *reinterpret_cast<u32x4*>(dst + (b0 + b) * N64 + (size_t)(col0 + jl) * M64 + 8 * pc) = v;
+        if (b0 + b < B) {
+            uint16_t* p = dst + (b0 + b) * N64 + (size_t)(col0 + jl) * M64 + 8 * pc;
+            if (SWZ) stg128_nt(p, v);  // final outputs: streamed; workspace copies stay cacheable for the next kernel
+            else *reinterpret_cast<u32x4*>(p) = v;
+        }
     }
 }
 
