@@ -1,10 +1,10 @@
 // bf16 backward for "wide block" Monarch layers (k = 4): the adjoints of steps 3, 2, P^T, 1 of
 // Section 3.3 (the paper leaves them to automatic differentiation, Section 4).
 //
-//   prep      re-lays the weights once per call so that every MFMA operand below is one
-//             16-byte load:  LTp[c][kk*Q/4 + r1][l] = L[c][l][4*r1 + kk]   (L transposed, rows in the
-//             order the mid permutation scatters them),  RTp[kk][i][.] = R[kk][.][i] (R transposed,
-//             columns in the order the chained accumulators of `data` hold them).
+//   prep      re-lays the weights once per call in MFMA fragment order (see prep_frag_kernel): every
+//             weight operand below is then one contiguous, fully coalesced 1 KiB read per wave.
+//             L is transposed with its rows picked in the order the mid permutation scatters them,
+//             R is transposed with its K-slots in the order the chained accumulators of `data` hold dY1.
 //   data      one workgroup per 64 batch rows, wave w <-> R block kk = w:
 //               X) recompute step 1, Y1[b][kk][j], and write it to the workspace (dL needs U);
 //               A) dY1[b][kk][c*Q/4 + r1] = sum_l dy[b][4*l + c] * L[c][l][4*r1 + kk]
@@ -17,6 +17,7 @@
 //             (monarch_mfma_wgrad.hip), split over the batch, then one reduction pass.
 #include "monarch_internal.h"
 #include "monarch_mfma_common.h"
+#include <cstdlib>
 
 namespace monarch {
 
@@ -24,46 +25,77 @@ namespace {
 
 // ------------------------------------------------------------------------ prep ----
 
-// Both re-layouts in one launch, 32 x 32 tiles through LDS; blocks [0, tilesL) do L, the rest R.
-//   LTp[c][kk*QK + r1][l] = L[c][l][4*r1 + kk]
-//   RTp[kk][i][32*u + 8*h + e] = R[kk][j][i],  j = 32*u + 16*(e/4) + 4*h + e%4   (h = 0..3, e = 0..7)
+// The weights are re-laid once per call in MFMA *fragment order*: for every (tile, K-step) the 64
+// lanes' 16-byte operand pieces are stored back to back, so that a fragment load in the data kernel
+// is one contiguous, fully coalesced 1 KiB read (eight cache lines) instead of 32 or 64 lines.
+// One thread builds one 16-byte piece (eight gathered elements).  Three arrays:
+//   XF[kk][jg][t][jj][lane][e]   = R[kk][32*(jg*JG + jj) + lane%32][64*(t/4) + 32*(lane/32) + 8*(t%4) + e]
+//       (step-1 recompute, 32x32x16; K-step t of lane group g covers 8 columns so that a lane's four
+//        steps of x are 64 contiguous bytes)
+//   LF[kk][c][kt][jt][lane][e]   = L[c][32*kt + 8*(lane/16) + e][4*(16*jt + lane%16) + kk]
+//       (dY1 stage, 16x16x32: L transposed, rows picked as the mid permutation scatters them)
+//   RF[kk][ig][u][it][lane][e]   = R[kk][32*u + 16*(e/4) + 4*(lane/16) + e%4][16*(ig*IG + it) + lane%16]
+//       (dx stage, 16x16x32: R transposed, K-slots in the order the chained accumulators hold dY1)
 __global__ void __launch_bounds__(256)
-prep_kernel(const uint16_t* __restrict__ L, const uint16_t* __restrict__ R, uint16_t* __restrict__ LTp,
-            uint16_t* __restrict__ RTp, int P, int Q, int S)
+prep_frag_kernel(const uint16_t* __restrict__ L, const uint16_t* __restrict__ R, uint16_t* __restrict__ XF,
+                 uint16_t* __restrict__ LF, uint16_t* __restrict__ RF, int P, int Q, int S, int JG, int IG)
 {
-    __shared__ uint16_t tile[32][33];
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-    const int tilesL = 4 * (S / 32) * (Q / 32);
-    int t = blockIdx.x;
-    if (t < tilesL) {
-        const int nr = Q / 32, nl = S / 32;
-        const int r0 = (t % nr) * 32, l0 = (t / nr % nl) * 32, c = t / (nr * nl);
-        const int QK = Q / 4;
-        for (int yy = ty; yy < 32; yy += 8) tile[yy][tx] = L[((size_t)c * S + l0 + yy) * Q + r0 + tx];
-        __syncthreads();
-        for (int yy = ty; yy < 32; yy += 8) {
-            const int r = r0 + yy;
-            const int kappa = (r & 3) * QK + (r >> 2);
-            LTp[((size_t)c * Q + kappa) * S + l0 + tx] = tile[tx][yy];
-        }
+    const int nR = 4 * Q * P / 8, nL = 4 * S * Q / 8;  // pieces per array
+    int pc = blockIdx.x * 256 + threadIdx.x;
+    uint16_t v[8];
+    uint16_t* dst;
+    if (pc < nR) {
+        const int lane = pc & 63;
+        int rest = pc >> 6;
+        const int jj = rest % JG; rest /= JG;
+        const int T = P / 16;
+        const int t = rest % T; rest /= T;
+        const int njg = Q / 32 / JG;
+        const int jg = rest % njg, kk = rest / njg;
+        const uint16_t* src = R + ((size_t)kk * Q + 32 * (jg * JG + jj) + (lane & 31)) * P + 64 * (t >> 2) + 32 * (lane >> 5) + 8 * (t & 3);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = src[e];
+        dst = XF + (size_t)pc * 8;
+    } else if (pc < nR + nL) {
+        pc -= nR;
+        const int lane = pc & 63;
+        int rest = pc >> 6;
+        const int JT = Q / 4 / 16;
+        const int jt = rest % JT; rest /= JT;
+        const int KT = S / 32;
+        const int kt = rest % KT; rest /= KT;
+        const int c = rest & 3, kk = rest >> 2;
+        const uint16_t* src = L + ((size_t)c * S + 32 * kt + 8 * (lane >> 4)) * Q + 4 * (16 * jt + (lane & 15)) + kk;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = src[(size_t)e * Q];
+        dst = LF + (size_t)pc * 8;
+    } else if (pc < 2 * nR + nL) {
+        pc -= nR + nL;
+        const int lane = pc & 63;
+        int rest = pc >> 6;
+        const int it = rest % IG; rest /= IG;
+        const int U = Q / 32;
+        const int u = rest % U; rest /= U;
+        const int nig = P / 16 / IG;
+        const int ig = rest % nig, kk = rest / nig;
+        const uint16_t* src = R + ((size_t)kk * Q + 32 * u + 4 * (lane >> 4)) * P + 16 * (ig * IG + it) + (lane & 15);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = src[(size_t)(16 * (e >> 2) + (e & 3)) * P];
+        dst = RF + (size_t)pc * 8;
     } else {
-        t -= tilesL;
-        const int ni = P / 32, nj = Q / 32;
-        const int i0 = (t % ni) * 32, j0 = (t / ni % nj) * 32, kk = t / (ni * nj);
-        for (int yy = ty; yy < 32; yy += 8) tile[yy][tx] = R[((size_t)kk * Q + j0 + yy) * P + i0 + tx];
-        __syncthreads();
-        // thread tx writes destination column j0 + tx of row i0 + yy
-        const int h = (tx >> 3) & 3, e = tx & 7;
-        const int jsrc = 16 * (e >> 2) + 4 * h + (e & 3);
-        for (int yy = ty; yy < 32; yy += 8)
-            RTp[((size_t)kk * P + i0 + yy) * Q + j0 + tx] = tile[jsrc][yy];
+        return;
     }
+    u32x4 o;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) o[w] = (uint32_t)v[2 * w] | ((uint32_t)v[2 * w + 1] << 16);
+    *reinterpret_cast<u32x4*>(dst) = o;
 }
 
 // ------------------------------------------------------------------------ data ----
 
-template <int P_, int Q_, int S_, int JG_, int LC_, int IG_>
+template <int P_, int Q_, int S_, int JG_, int LC_, int IG_, int DBG_ = 0, int NS_ = 0, int NSX_ = 0>
 struct BwdWide {
+    static constexpr int DBG = DBG_, NS_OVR = NS_, NSX_OVR = NSX_;
     static constexpr int K = 4, P = P_, Q = Q_, S = S_, JG = JG_, LC = LC_, IG = IG_;
     static constexpr int BM = 64, NB = 2;   // stage X uses 32 x 32 tiles (2 row tiles)
     static constexpr int NBT = 4;           // stages A, B use 16 x 16 tiles (4 row tiles)
@@ -78,29 +110,66 @@ struct BwdWide {
     static constexpr size_t LDS_DW = (size_t)K * BM * DW_STRIDE * 2;
     static constexpr size_t LDS_DX = (size_t)4 * BM * DX_STRIDE * 2;
     static constexpr size_t LDS_BYTES = LDS_Y1 > LDS_DW ? (LDS_Y1 > LDS_DX ? LDS_Y1 : LDS_DX) : (LDS_DW > LDS_DX ? LDS_DW : LDS_DX);
-    static_assert(P % 16 == 0 && Q % 32 == 0 && S % 32 == 0 && QK % 16 == 0, "tile shapes");
+    static_assert(P % 64 == 0 && Q % 32 == 0 && S % 32 == 0 && QK % 16 == 0, "tile shapes");
     static_assert(QT % JG == 0 && S % LC == 0 && LC % 32 == 0 && (P / 16) % IG == 0, "loop splits");
     static_assert(DX_COLS % 8 == 0 && (64 % (DX_COLS / 8) == 0), "dx staging copy-out");
     static_assert(LDS_BYTES <= kMaxLdsBytes, "LDS");
 };
 
-// cooperative copy of a [64][cols] bf16 LDS tile (row stride `stride`) to global rows b0.. (row pitch ld)
+// cooperative copy of a [64][COLS] bf16 LDS tile (row stride `stride`) to global rows b0.. (row pitch ld);
+// eight LDS reads are in flight per thread before the first store.  NT: streaming (non-temporal) stores.
+template <int COLS, int NTHREADS, bool NT>
 __device__ __forceinline__ void copy_out_tile(const uint16_t* src, int stride, uint16_t* dst, int64_t ld,
-                                              int cols, int64_t b0, int64_t B, int tid, int nthreads)
+                                              int64_t b0, int64_t B, int tid)
 {
-    const int per_row = cols / 8;
-    for (int t = tid; t < 64 * per_row; t += nthreads) {
-        const int r = t / per_row, u = t - r * per_row;
-        if (b0 + r < B)
-            *reinterpret_cast<u32x4*>(dst + (b0 + r) * ld + 8 * u) = lds128(src + (size_t)r * stride + 8 * u);
+    constexpr int PER_ROW = COLS / 8, TASKS = 64 * PER_ROW, PER = (TASKS + NTHREADS - 1) / NTHREADS;
+#pragma unroll
+    for (int i0 = 0; i0 < PER; i0 += 8) {
+        u32x4 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int t = tid + (i0 + i) * NTHREADS;
+            if (i0 + i < PER && t < TASKS) v[i] = lds128(src + (size_t)(t / PER_ROW) * stride + 8 * (t % PER_ROW));
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int t = tid + (i0 + i) * NTHREADS;
+            const int r = t / PER_ROW, u = t % PER_ROW;
+            if (i0 + i < PER && t < TASKS && b0 + r < B) {
+                uint16_t* p = dst + (b0 + r) * ld + 8 * u;
+                if (NT) stg128_nt(p, v[i]);
+                else *reinterpret_cast<u32x4*>(p) = v[i];
+            }
+        }
     }
+}
+
+// orders the LDS traffic of one wave (what its lanes wrote is visible to its later reads)
+__device__ __forceinline__ void wave_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// TUNING: DBG 2 = no MFMA (loads kept alive by an xor sink), 3 = no weight/x loads
+template <int DBG> __device__ __forceinline__ u32x4 dbg_ldg(const void* p) { return DBG == 3 ? u32x4{1u, 2u, 3u, (uint32_t)(uintptr_t)p} : ldg128(p); }
+template <int DBG> __device__ __forceinline__ f32x16 dbg_mfma32(u32x4 a, u32x4 b, f32x16 c)
+{
+    if (DBG == 2) { c[0] = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, c[0]) ^ a[0] ^ a[1] ^ a[2] ^ a[3] ^ b[0] ^ b[1] ^ b[2] ^ b[3]); return c; }
+    return mfma32(as_bf16x8(a), as_bf16x8(b), c);
+}
+template <int DBG> __device__ __forceinline__ f32x4 dbg_mfma16(u32x4 a, bf16x8 b, f32x4 c)
+{
+    if (DBG == 2) { const u32x4 bb = __builtin_bit_cast(u32x4, b); c[0] = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, c[0]) ^ a[0] ^ a[1] ^ a[2] ^ a[3] ^ bb[0] ^ bb[1] ^ bb[2] ^ bb[3]); return c; }
+    return mfma16(as_bf16x8(a), b, c);
 }
 
 template <typename C>
 __global__ void __launch_bounds__(256)
 bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ x,
-                     const uint16_t* __restrict__ R, const uint16_t* __restrict__ LTp,
-                     const uint16_t* __restrict__ RTp, uint16_t* __restrict__ dx,
+                     const uint16_t* __restrict__ XF, const uint16_t* __restrict__ LF,
+                     const uint16_t* __restrict__ RF, uint16_t* __restrict__ dx,
                      uint16_t* __restrict__ Y1ws, uint16_t* __restrict__ dY1ws, int64_t B)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
@@ -108,6 +177,27 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
     const int wave = tid >> 6, lane = tid & 63;
     const int64_t b0 = (int64_t)blockIdx.x * C::BM;
     const int kk = wave;
+    long long ts[8];
+    if (C::DBG) ts[0] = __builtin_amdgcn_s_memtime();
+
+    // dy is consumed in chunks of LC features l; a chunk (64 rows x 4*LC columns) is fetched into
+    // registers well before it is de-interleaved into LDS, so that its HBM latency is hidden
+    constexpr int RUNS = C::LC / 8;                 // 64-byte runs per row and chunk
+    constexpr int DYT = 64 * RUNS / 256;            // runs per thread
+    static_assert(64 * RUNS % 256 == 0, "dy chunk split");
+    u32x4 raw[DYT][4];
+    auto load_dy = [&](int l0) {
+#pragma unroll
+        for (int i = 0; i < DYT; ++i) {
+            const int t = tid + i * 256;
+            const int r = t / RUNS, u = t - r * RUNS;
+            int64_t row = b0 + r;
+            row = row < B ? row : B - 1;
+            const uint16_t* p = dy + row * C::N_OUT + (size_t)(l0 + 8 * u) * 4;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) raw[i][w] = ldg128(p + 8 * w);  // cached: the weight-gradient GEMM re-reads dy
+        }
+    };
 
     // ------------------------------------------------- X: recompute step 1 -> workspace ----
     {
@@ -117,38 +207,53 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
         for (int nb = 0; nb < C::NB; ++nb) {
             int64_t row = b0 + nb * 32 + ln;
             row = row < B ? row : B - 1;
-            xrow[nb] = x + row * C::N_IN + kk * C::P + 8 * g;
+            xrow[nb] = x + row * C::N_IN + kk * C::P + 32 * g;
         }
-        const uint16_t* Rk = R + ((size_t)kk * C::Q + ln) * C::P + 8 * g;
-        constexpr int T = C::P / 16;
+        // rings of K-steps: NS for the weight fragments (L2 latency), NSX for x (HBM latency)
+        constexpr int T = C::P / 16, NS = C::NS_OVR ? C::NS_OVR : 4;
+        constexpr int NSX = C::NSX_OVR ? C::NSX_OVR : ((T == 12) ? 12 : ((T % 8 == 0) ? 8 : 4));
+        static_assert(T % NS == 0 && T % NSX == 0 && NSX % NS == 0, "ring");
+        // fragment (jg, t, jj) of XF; K-step t of lane group g covers columns 64*(t/4) + 32*g + 8*(t%4) ..
+        const uint16_t* Xk = XF + ((size_t)kk * (C::QT / C::JG) * T * C::JG * 64 + lane) * 8;
+        auto xcol = [](int t) { return 64 * (t >> 2) + 8 * (t & 3); };
         for (int jg = 0; jg < C::QT / C::JG; ++jg) {
             f32x16 acc[C::JG * C::NB];
 #pragma unroll
             for (int t = 0; t < C::JG * C::NB; ++t)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
-            const uint16_t* Rg = Rk + (size_t)jg * C::JG * 32 * C::P;
-            u32x4 xf[2][C::NB], rf[2][C::JG];
+            const uint16_t* Rg = Xk + (size_t)jg * T * C::JG * 512;
+            // operands run through a ring of NS K-steps so that NS - 1 steps of loads are in flight
+            // (one step of MFMAs is shorter than the L2 latency)
+            u32x4 xf[NSX][C::NB], rf[NS][C::JG];
+            auto issue_x = [&](int t, int slot) {
 #pragma unroll
-            for (int nb = 0; nb < C::NB; ++nb) xf[0][nb] = ldg128(xrow[nb]);
+                for (int nb = 0; nb < C::NB; ++nb) xf[slot][nb] = dbg_ldg<C::DBG>(xrow[nb] + xcol(t));
+            };
+            auto issue_r = [&](int t, int slot) {
 #pragma unroll
-            for (int jj = 0; jj < C::JG; ++jj) rf[0][jj] = ldg128(Rg + (size_t)jj * 32 * C::P);
-#pragma unroll 4
-            for (int t = 0; t < T; ++t) {
-                const int cur = t & 1, nxt = cur ^ 1;
-                if (t + 1 < T) {
+                for (int jj = 0; jj < C::JG; ++jj) rf[slot][jj] = dbg_ldg<C::DBG>(Rg + (size_t)(t * C::JG + jj) * 512);
+            };
+            // weights first: they come from L2 and the in-order load counter must not hold them behind x
 #pragma unroll
-                    for (int nb = 0; nb < C::NB; ++nb) xf[nxt][nb] = ldg128(xrow[nb] + (t + 1) * 16);
+            for (int d = 0; d < NS - 1; ++d) issue_r(d, d);
+#pragma unroll
+            for (int d = 0; d < NSX - 1; ++d) issue_x(d, d);
+            for (int t0 = 0; t0 < T; t0 += NSX) {
+#pragma unroll
+                for (int k4 = 0; k4 < NSX; ++k4) {
+                    const int t = t0 + k4;
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (t + NS - 1 < T) issue_r(t + NS - 1, (k4 + NS - 1) % NS);
+                    if (t + NSX - 1 < T) issue_x(t + NSX - 1, (k4 + NSX - 1) % NSX);
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int jj = 0; jj < C::JG; ++jj)
-                        rf[nxt][jj] = ldg128(Rg + (size_t)jj * 32 * C::P + (t + 1) * 16);
+#pragma unroll
+                        for (int nb = 0; nb < C::NB; ++nb)
+                            acc[jj * C::NB + nb] =
+                                dbg_mfma32<C::DBG>(rf[k4 % NS][jj], xf[k4][nb], acc[jj * C::NB + nb]);
                 }
-#pragma unroll
-                for (int jj = 0; jj < C::JG; ++jj)
-#pragma unroll
-                    for (int nb = 0; nb < C::NB; ++nb)
-                        acc[jj * C::NB + nb] =
-                            mfma32(as_bf16x8(rf[cur][jj]), as_bf16x8(xf[cur][nb]), acc[jj * C::NB + nb]);
             }
 #pragma unroll
             for (int jj = 0; jj < C::JG; ++jj)
@@ -162,9 +267,12 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
                         *reinterpret_cast<u32x2*>(lds + (size_t)(nb * 32 + ln) * C::Y1_STRIDE + kk * C::Q + j) = v;
                     }
         }
+        load_dy(0);  // in flight during the copy-out below
+        if (C::DBG) ts[1] = __builtin_amdgcn_s_memtime();
         __syncthreads();
-        copy_out_tile(lds, C::Y1_STRIDE, Y1ws, C::KQ, C::KQ, b0, B, tid, 256);
+        copy_out_tile<C::KQ, 256, false>(lds, C::Y1_STRIDE, Y1ws, C::KQ, b0, B, tid);
         __syncthreads();
+        if (C::DBG) ts[2] = __builtin_amdgcn_s_memtime();
     }
 
     // 16 x 16 tile coordinates for stages A and B
@@ -177,60 +285,63 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
     for (int t = 0; t < C::K * C::JT * C::NBT; ++t) accA[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     for (int l0 = 0; l0 < C::S; l0 += C::LC) {
-        // de-interleave dy[b][4*l + c] into LDS dWs[c][b][l - l0]
-        constexpr int RUNS = C::LC / 8;  // 64-byte runs per row
-        for (int t0 = 0; t0 < 64 * RUNS; t0 += 256) {
-            const int t = t0 + tid;
-            const int r = t / RUNS, u = t - r * RUNS;
-            int64_t row = b0 + r;
-            row = row < B ? row : B - 1;
-            const uint16_t* p = dy + row * C::N_OUT + (size_t)(l0 + 8 * u) * 4;
-            u32x4 raw[4];
+        // A operand: fragment (c, kt, jt) of LF (rows kk*QK + jt*16 + l16 of L^T), streamed through a
+        // ring of NSA K-steps over the flattened (c, t) loop; the first loads are issued before the
+        // de-interleave below so that they overlap it.
+        constexpr int T = C::LC / 32, NSA = 4, NSTEP = C::K * T;
+        const uint16_t* Lk = LF + (((size_t)kk * 4 * (C::S / 32) + l0 / 32) * C::JT * 64 + lane) * 8;
+        u32x4 af[NSA][C::JT];
+        auto issue = [&](int n, int slot) {
+            const int c = n / T, t = n % T;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) raw[w] = ldg128(p + 8 * w);
+            for (int jt = 0; jt < C::JT; ++jt)
+                af[slot][jt] = dbg_ldg<C::DBG>(Lk + ((size_t)(c * (C::S / 32) + t) * C::JT + jt) * 512);
+        };
+#pragma unroll
+        for (int d = 0; d < NSA - 1; ++d)
+            if (d < NSTEP) issue(d, d);
+        __builtin_amdgcn_sched_barrier(0);
+        // de-interleave the chunk (loaded earlier, see load_dy) into LDS dWs[c][b][l - l0]
+#pragma unroll
+        for (int i = 0; i < DYT; ++i) {
+            const int t = tid + i * 256;
+            const int r = t / RUNS, u = t - r * RUNS;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 u32x4 v;
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
-                    const uint32_t lo = raw[w][c >> 1], hi = raw[w][2 + (c >> 1)];
+                    const uint32_t lo = raw[i][w][c >> 1], hi = raw[i][w][2 + (c >> 1)];
                     v[w] = (c & 1) ? pick_hi16(lo, hi) : pick_lo16(lo, hi);
                 }
                 *reinterpret_cast<u32x4*>(lds + ((size_t)c * 64 + r) * C::DW_STRIDE + 8 * u) = v;
             }
         }
         __syncthreads();
+        if (l0 + C::LC < C::S) load_dy(l0 + C::LC);  // the next chunk is in flight during the MFMA loop
 #pragma unroll
-        for (int c = 0; c < C::K; ++c) {
-            // A operand rows: LTp[c][kk*QK + jt*16 + l16][l],  B operand: dWs[c][bt*16 + l16][l]
-            const uint16_t* Lc = LTp + ((size_t)c * C::Q + kk * C::QK + l16) * C::S + l0 + 8 * h;
+        for (int n = 0; n < NSTEP; ++n) {
+            const int c = n / T, t = n % T;
+            __builtin_amdgcn_sched_barrier(0);
+            if (n + NSA - 1 < NSTEP) issue(n + NSA - 1, (n + NSA - 1) % NSA);
+            __builtin_amdgcn_sched_barrier(0);
+            // B operand: dWs[c][bt*16 + l16][l]
             const uint16_t* Wc = lds + ((size_t)c * 64 + l16) * C::DW_STRIDE + 8 * h;
-            constexpr int T = C::LC / 32;
-            u32x4 af[2][C::JT];
+            bf16x8 bfr[C::NBT];
 #pragma unroll
-            for (int jt = 0; jt < C::JT; ++jt) af[0][jt] = ldg128(Lc + (size_t)jt * 16 * C::S);
-#pragma unroll 2
-            for (int t = 0; t < T; ++t) {
-                const int cur = t & 1, nxt = cur ^ 1;
-                if (t + 1 < T) {
+            for (int bt = 0; bt < C::NBT; ++bt)
+                bfr[bt] = as_bf16x8(lds128(Wc + (size_t)bt * 16 * C::DW_STRIDE + t * 32));
 #pragma unroll
-                    for (int jt = 0; jt < C::JT; ++jt) af[nxt][jt] = ldg128(Lc + (size_t)jt * 16 * C::S + (t + 1) * 32);
-                }
-                bf16x8 bfr[C::NBT];
+            for (int jt = 0; jt < C::JT; ++jt)
 #pragma unroll
                 for (int bt = 0; bt < C::NBT; ++bt)
-                    bfr[bt] = as_bf16x8(lds128(Wc + (size_t)bt * 16 * C::DW_STRIDE + t * 32));
-#pragma unroll
-                for (int jt = 0; jt < C::JT; ++jt)
-#pragma unroll
-                    for (int bt = 0; bt < C::NBT; ++bt)
-                        accA[(c * C::JT + jt) * C::NBT + bt] =
-                            mfma16(as_bf16x8(af[cur][jt]), bfr[bt], accA[(c * C::JT + jt) * C::NBT + bt]);
-            }
+                    accA[(c * C::JT + jt) * C::NBT + bt] =
+                        dbg_mfma16<C::DBG>(af[n % NSA][jt], bfr[bt], accA[(c * C::JT + jt) * C::NBT + bt]);
         }
         __syncthreads();
     }
 
+    if (C::DBG) ts[3] = __builtin_amdgcn_s_memtime();
     // bf16 fragments of dY1: dfr[J][bt] holds j = J*16 + 4*h + 0..3 (J = c*JT + jt) for row bt*16 + l16
     u32x2 dfr[C::K * C::JT][C::NBT];
 #pragma unroll
@@ -247,37 +358,45 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
         for (int bt = 0; bt < C::NBT; ++bt)
             *reinterpret_cast<u32x2*>(lds + (size_t)(bt * 16 + l16) * C::Y1_STRIDE + kk * C::Q + J * 16 + 4 * h) = dfr[J][bt];
     __syncthreads();
-    copy_out_tile(lds, C::Y1_STRIDE, dY1ws, C::KQ, C::KQ, b0, B, tid, 256);
+    copy_out_tile<C::KQ, 256, false>(lds, C::Y1_STRIDE, dY1ws, C::KQ, b0, B, tid);
     __syncthreads();
+    if (C::DBG) ts[4] = __builtin_amdgcn_s_memtime();
 
     // ------------------------------------------------- B: dx from the chained fragments ----
     // K-step u covers j in [32u, 32u+32): lane slots 0..3 <- tile 2u, slots 4..7 <- tile 2u+1;
-    // RTp rows are laid out in exactly that order, so its operand is one 16-byte load.
+    // the RF fragments are laid out in exactly that order.
     uint16_t* stage = lds + (size_t)wave * 64 * C::DX_STRIDE;
-    const uint16_t* Rt = RTp + ((size_t)kk * C::P + l16) * C::Q + 8 * h;
     constexpr int U = C::Q / 32;
-    for (int ig = 0; ig < (C::P / 16) / C::IG; ++ig) {
+    const uint16_t* Rt = RF + ((size_t)kk * (C::P / 16 / C::IG) * U * C::IG * 64 + lane) * 8;
+    // The fragments of all (ig, u) steps are contiguous in RF: step n = ig*U + u.  They run through a
+    // ring of NSB steps that continues across the ig loop (U % NSB == 0 keeps the slot numbers static).
+    constexpr int NIG = (C::P / 16) / C::IG;
+    constexpr int NSB = (U % 4 == 0) ? 4 : ((U % 3 == 0) ? 3 : 2);
+    static_assert(U % NSB == 0, "ring");
+    u32x4 af[NSB][C::IG];
+    auto issue = [&](int n, int slot) {
+#pragma unroll
+        for (int it = 0; it < C::IG; ++it) af[slot][it] = dbg_ldg<C::DBG>(Rt + ((size_t)n * C::IG + it) * 512);
+    };
+#pragma unroll
+    for (int d = 0; d < NSB - 1; ++d) issue(d, d);
+    for (int ig = 0; ig < NIG; ++ig) {
         f32x4 acc[C::IG * C::NBT];
 #pragma unroll
         for (int t = 0; t < C::IG * C::NBT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-        const uint16_t* Rg = Rt + (size_t)ig * C::IG * 16 * C::Q;
-        u32x4 af[2][C::IG];
-#pragma unroll
-        for (int it = 0; it < C::IG; ++it) af[0][it] = ldg128(Rg + (size_t)it * 16 * C::Q);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int cur = u & 1, nxt = cur ^ 1;
-            if (u + 1 < U) {
-#pragma unroll
-                for (int it = 0; it < C::IG; ++it) af[nxt][it] = ldg128(Rg + (size_t)it * 16 * C::Q + (u + 1) * 32);
-            }
+            const int n = ig * U + u;
+            __builtin_amdgcn_sched_barrier(0);
+            if (n + NSB - 1 < NIG * U) issue(n + NSB - 1, (u + NSB - 1) % NSB);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int bt = 0; bt < C::NBT; ++bt) {
                 const u32x4 bv = {dfr[2 * u][bt][0], dfr[2 * u][bt][1], dfr[2 * u + 1][bt][0], dfr[2 * u + 1][bt][1]};
                 const bf16x8 bfr = as_bf16x8(bv);
 #pragma unroll
                 for (int it = 0; it < C::IG; ++it)
-                    acc[it * C::NBT + bt] = mfma16(as_bf16x8(af[cur][it]), bfr, acc[it * C::NBT + bt]);
+                    acc[it * C::NBT + bt] = dbg_mfma16<C::DBG>(af[u % NSB][it], bfr, acc[it * C::NBT + bt]);
             }
         }
         // D^T[i][b]: lane holds i = it*16 + 4*h + 0..3 for row b = bt*16 + l16
@@ -289,15 +408,25 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
                 *reinterpret_cast<u32x2*>(stage + (size_t)(bt * 16 + l16) * C::DX_STRIDE + it * 16 + 4 * h) =
                     u32x2{pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3])};
             }
+        // the staging tile is private to the wave: no workgroup barrier
+        wave_fence();
+        copy_out_tile<C::DX_COLS, 64, true>(stage, C::DX_STRIDE, dx + kk * C::P + ig * C::DX_COLS, C::N_IN, b0, B, lane);
+        wave_fence();
+    }
+    if (C::DBG) {
+        __builtin_amdgcn_s_waitcnt(0);
+        ts[5] = __builtin_amdgcn_s_memtime();
         __syncthreads();
-        copy_out_tile(stage, C::DX_STRIDE, dx + kk * C::P + ig * C::DX_COLS, C::N_IN, C::DX_COLS, b0, B, lane, 64);
-        __syncthreads();
+        if (lane == 0) {
+            long long* o = reinterpret_cast<long long*>(Y1ws + b0 * C::KQ) + wave * 8;
+            for (int i = 0; i < 6; ++i) o[i] = ts[i];
+        }
     }
 }
 
 template <typename C>
-int launch_data(const Problem& pb, const void* dy, const void* x, const void* R, const uint16_t* LTp,
-                const uint16_t* RTp, void* dx, uint16_t* Y1ws, uint16_t* dY1ws, hipStream_t st)
+int launch_data(const Problem& pb, const void* dy, const void* x, const uint16_t* XF, const uint16_t* LF,
+                const uint16_t* RF, void* dx, uint16_t* Y1ws, uint16_t* dY1ws, hipStream_t st)
 {
     auto kern = bwd_wide_data_kernel<C>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES) != hipSuccess)
@@ -305,31 +434,43 @@ int launch_data(const Problem& pb, const void* dy, const void* x, const void* R,
     const int64_t grid = (pb.B + C::BM - 1) / C::BM;
     if (grid > 0x7fffffffLL) return -2;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), C::LDS_BYTES, st, (const uint16_t*)dy,
-                       (const uint16_t*)x, (const uint16_t*)R, LTp, RTp, (uint16_t*)dx, Y1ws, dY1ws, pb.B);
+                       (const uint16_t*)x, XF, LF, RF, (uint16_t*)dx, Y1ws, dY1ws, pb.B);
     return hip_status(hipGetLastError());
 }
 
 struct Entry {
-    int p, q, s;
-    int (*fn)(const Problem&, const void*, const void*, const void*, const uint16_t*, const uint16_t*, void*,
+    int p, q, s, jg, ig;  // jg, ig: the data kernel's loop splits, which fix the fragment order of the weights
+    int (*fn)(const Problem&, const void*, const void*, const uint16_t*, const uint16_t*, const uint16_t*, void*,
               uint16_t*, uint16_t*, hipStream_t);
 };
 
 //                                 P     Q     S   JG   LC  IG
 const Entry kTable[] = {
-    {192, 192, 192, launch_data<BwdWide<192, 192, 192, 6, 192, 4>>},
-    {192, 192, 768, launch_data<BwdWide<192, 192, 768, 6, 256, 4>>},
-    {256, 256, 1024, launch_data<BwdWide<256, 256, 1024, 4, 256, 4>>},
-    {1024, 256, 256, launch_data<BwdWide<1024, 256, 256, 4, 256, 4>>},
-    {768, 192, 192, launch_data<BwdWide<768, 192, 192, 6, 192, 4>>},
-    {64, 64, 64, launch_data<BwdWide<64, 64, 64, 2, 64, 4>>},
-    {64, 64, 128, launch_data<BwdWide<64, 64, 128, 2, 64, 4>>},
-    {128, 64, 64, launch_data<BwdWide<128, 64, 64, 2, 64, 4>>},
+    {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4>>},
+    {192, 192, 768, 6, 4, launch_data<BwdWide<192, 192, 768, 6, 192, 4>>},
+    {256, 256, 1024, 4, 4, launch_data<BwdWide<256, 256, 1024, 4, 128, 4>>},
+    {1024, 256, 256, 4, 4, launch_data<BwdWide<1024, 256, 256, 4, 128, 4>>},
+    {768, 192, 192, 6, 4, launch_data<BwdWide<768, 192, 192, 6, 192, 4>>},
+    {64, 64, 64, 2, 4, launch_data<BwdWide<64, 64, 64, 2, 64, 4>>},
+    {64, 64, 128, 2, 4, launch_data<BwdWide<64, 64, 128, 2, 64, 4>>},
+    {128, 64, 64, 2, 4, launch_data<BwdWide<128, 64, 64, 2, 64, 4>>},
 };
+
+const Entry kDbgEntry[] = {{192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 1>>},  // TUNING: phase timestamps
+                            {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 2>>},
+                            {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 3>>},
+                            {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 1, 2, 2>>},    // 4
+                            {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 1, 2, 12>>},   // 5
+                            {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 1, 3, 3>>},    // 6
+                            {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 1, 3, 12>>},   // 7
+                            {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 1, 4, 4>>},    // 8
+                            {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 1, 6, 6>>}};   // 9
+
 
 const Entry* find(const Problem& pb)
 {
     if (pb.dtype != 1 || pb.k != 4 || pb.perm_b()) return nullptr;
+    if (getenv("MONARCH_BWD_DBG") && pb.p == 192 && pb.q == 192 && pb.s == 192) return &kDbgEntry[atoi(getenv("MONARCH_BWD_DBG")) - 1];
     for (const Entry& e : kTable)
         if (e.p == pb.p && e.q == pb.q && e.s == pb.s) return &e;
     return nullptr;
@@ -339,7 +480,7 @@ const Entry* find(const Problem& pb)
 // workgroup per CU in total, chunks of at least 256 rows (multiples of the 32-row pipeline
 // step) so that the fp32 partial tiles stay small next to the operands.
 struct Plan {
-    size_t off_y1, off_dy1, off_ltp, off_rtp, off_partL, off_partR, total;
+    size_t off_y1, off_dy1, off_xf, off_lf, off_rf, off_partL, off_partR, total;
     int nz, rows_per_chunk;
     bool ok;
 };
@@ -378,8 +519,9 @@ Plan make_plan(const Problem& pb)
     const size_t act = align_up((size_t)(pb.B > 0 ? pb.B : 1) * pb.kq() * 2, 256);
     pl.off_y1 = off;  off += act;
     pl.off_dy1 = off; off += act;
-    pl.off_ltp = off; off += align_up(pb.n_L() * 2, 256);
-    pl.off_rtp = off; off += align_up(pb.n_R() * 2, 256);
+    pl.off_xf = off; off += align_up(pb.n_R() * 2, 256);
+    pl.off_lf = off; off += align_up(pb.n_L() * 2, 256);
+    pl.off_rf = off; off += align_up(pb.n_R() * 2, 256);
     pl.off_partL = off; off += align_up((size_t)pl.nz * pb.n_L() * 4, 256);
     pl.off_partR = off; off += align_up((size_t)pl.nz * pb.n_R() * 4, 256);
     pl.total = off;
@@ -401,19 +543,20 @@ int bwd_wide(const Problem& pb, const void* dy, const void* x, const void* R, co
     char* w = (char*)ws;
     uint16_t* Y1ws = (uint16_t*)(w + pl.off_y1);
     uint16_t* dY1ws = (uint16_t*)(w + pl.off_dy1);
-    uint16_t* LTp = (uint16_t*)(w + pl.off_ltp);
-    uint16_t* RTp = (uint16_t*)(w + pl.off_rtp);
+    uint16_t* XF = (uint16_t*)(w + pl.off_xf);
+    uint16_t* LF = (uint16_t*)(w + pl.off_lf);
+    uint16_t* RF = (uint16_t*)(w + pl.off_rf);
     const bool f32out = pb.wgrad_f32();
     if (pb.B == 0) {
         int rc = f32out ? launch_fill_zero_f32((float*)dR, pb.n_R(), st) : launch_fill_zero_u16((uint16_t*)dR, pb.n_R(), st);
         if (rc) return rc;
         return f32out ? launch_fill_zero_f32((float*)dL, pb.n_L(), st) : launch_fill_zero_u16((uint16_t*)dL, pb.n_L(), st);
     }
-    const int prep_blocks = 4 * (pb.s / 32) * (pb.q / 32) + 4 * (pb.q / 32) * (pb.p / 32);
-    hipLaunchKernelGGL(prep_kernel, dim3(prep_blocks), dim3(256), 0, st, (const uint16_t*)L, (const uint16_t*)R,
-                       LTp, RTp, pb.p, pb.q, pb.s);
+    const size_t pieces = (2 * pb.n_R() + pb.n_L()) / 8;
+    hipLaunchKernelGGL(prep_frag_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st, (const uint16_t*)L,
+                       (const uint16_t*)R, XF, LF, RF, pb.p, pb.q, pb.s, e->jg, e->ig);
     if (hipGetLastError() != hipSuccess) return -4;
-    int rc = e->fn(pb, dy, x, R, LTp, RTp, dx, Y1ws, dY1ws, st);
+    int rc = e->fn(pb, dy, x, XF, LF, RF, dx, Y1ws, dY1ws, st);
     if (rc) return rc;
 
     WgradDesc dl, dr;
