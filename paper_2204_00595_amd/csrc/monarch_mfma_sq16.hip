@@ -191,7 +191,18 @@ bwd_sq16_kernel(const float* __restrict__ dy, const float* __restrict__ x, const
 #pragma unroll
         for (int v = 0; v < 16; ++v) dya[v] = *reinterpret_cast<const f32x4*>(p + 4 * v) * m;
     };
-    f32x4 xa[16], dya[16];
+    // daq[cq][u] = dy[b0 + 4h + u][16*bl + 4cq .. +3]: the same rows "down the batch" for the dL product
+    auto load_da = [&](int64_t tl, f32x4 (&daq)[4][4]) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            int64_t row = tl * 16 + 4 * h + u;
+            const float m = row < B ? 1.f : 0.f;
+            row = row < B ? row : B - 1;
+#pragma unroll
+            for (int cq = 0; cq < 4; ++cq) daq[cq][u] = *reinterpret_cast<const f32x4*>(dy + row * N16 + 16 * bl + 4 * cq) * m;
+        }
+    };
+    f32x4 xa[16], dya[16], daq[4][4];
     if (tile < ntiles) {  // in flight while the weights are staged
         load_x(tile, xa);
         load_dy(tile, dya);
@@ -203,6 +214,7 @@ bwd_sq16_kernel(const float* __restrict__ dy, const float* __restrict__ x, const
     for (; tile < ntiles; tile += stride) {
         const int64_t b0 = tile * 16;
         const int64_t next = tile + stride;
+        load_da(tile, daq);  // second look at this tile's dy rows (cache hits), in flight during step 1
         // ---- 1. Y1[b][kk][j = 4h + i] -> tile [b][kk][j]
 #pragma unroll
         for (int kk = 0; kk < 16; ++kk) {
@@ -216,19 +228,13 @@ bwd_sq16_kernel(const float* __restrict__ dy, const float* __restrict__ x, const
         // ---- 2. dL: A lane (l, h) = dy[b0 + 4h + u][16l + c], B lane (r, h) = Y1[b0 + 4h + u][r][c]
 #pragma unroll
         for (int cq = 0; cq < 4; ++cq) {
-            f32x4 da[4], ub[4];
+            f32x4 ub[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                int64_t row = b0 + 4 * h + u;
-                const float m = row < B ? 1.f : 0.f;
-                row = row < B ? row : B - 1;
-                da[u] = *reinterpret_cast<const f32x4*>(dy + row * N16 + 16 * bl + 4 * cq) * m;
-                ub[u] = *reinterpret_cast<const f32x4*>(T + t_off(4 * h + u, 4 * bl + cq));
-            }
+            for (int u = 0; u < 4; ++u) ub[u] = *reinterpret_cast<const f32x4*>(T + t_off(4 * h + u, 4 * bl + cq));
 #pragma unroll
             for (int e = 0; e < 4; ++e)
 #pragma unroll
-                for (int u = 0; u < 4; ++u) accL[4 * cq + e] = mfma4(da[u][e], ub[u][e], accL[4 * cq + e]);
+                for (int u = 0; u < 4; ++u) accL[4 * cq + e] = mfma4(daq[cq][u][e], ub[u][e], accL[4 * cq + e]);
         }
         wave_lds_fence();  // Y1 has been read: the tile is reused
         // ---- 3. dY1[b][kk = 4h + i][j = c] -> tile [b][j][kk]
