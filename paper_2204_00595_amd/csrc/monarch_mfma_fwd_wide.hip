@@ -57,7 +57,7 @@ struct FwdWide {
     static constexpr int PASSES = UNITS / (4 * UPW);
     static constexpr int NLT = (UPW + 1) / 2; // l tiles a wave touches in one pass
     static constexpr int NBLK2 = 2 * NLT;     // staging blocks per stage-2 chunk
-    static constexpr int Y1_STRIDE = KQ + 4;  // bf16; row stride = 2 dwords mod 64 banks
+    static constexpr int Y1_STRIDE = KQ + 8;  // bf16; row stride = 4 dwords mod 64 banks (16-byte reads, row = lane)
     static constexpr size_t LDS_Y1 = ((size_t)BM * Y1_STRIDE * 2 + 1023) / 1024 * 1024;
     static constexpr size_t STG1 = (size_t)RD1 * 4096;         // per wave
     // stage 2 streams L in 4 KiB units of full 128-byte lines when the ring fits beside Y1s,
@@ -88,6 +88,22 @@ __device__ __forceinline__ void dma16(const uint16_t* gsrc, uint16_t* lds_block)
                                      (__attribute__((address_space(3))) void*)lds_block, 16, 0, 0);
 }
 
+// vmcnt(4 * units) for a unit count known after unrolling (a unit = four DMA instructions)
+__device__ __forceinline__ void wait_vmcnt_units(int units)
+{
+    switch (units) {
+        case 0: wait_vmcnt<0>(); break;
+        case 1: wait_vmcnt<4>(); break;
+        case 2: wait_vmcnt<8>(); break;
+        case 3: wait_vmcnt<12>(); break;
+        case 4: wait_vmcnt<16>(); break;
+        case 5: wait_vmcnt<20>(); break;
+        case 6: wait_vmcnt<24>(); break;
+        case 7: wait_vmcnt<28>(); break;
+        default: wait_vmcnt<32>(); break;
+    }
+}
+
 __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
 // 4 KiB staging unit = 32 rows x 128 bytes = four 1 KiB blocks of 8 rows.  One DMA instruction
@@ -98,6 +114,13 @@ __device__ __forceinline__ int unit_frag_off(int ln, int g, int u)
 {
     const int bi = ln >> 3, r = ln & 7;
     return bi * 512 + r * 64 + 8 * ((2 * u + g) ^ r ^ (bi & 1));
+}
+
+// same, for an explicit 16-byte piece index (0..7) of the row
+__device__ __forceinline__ int unit_piece_off(int ln, int piece)
+{
+    const int bi = ln >> 3, r = ln & 7;
+    return bi * 512 + r * 64 + 8 * (piece ^ r ^ (bi & 1));
 }
 
 // Stage 2 on full-line units (Q % 64 == 0 and room for the ring).  One pass of one wave:
@@ -115,11 +138,13 @@ __device__ __forceinline__ void stage2_pass_lines(const uint16_t* __restrict__ L
     // rows of the staged l tiles (the second tile may not exist for the last wave: reuse the first)
     const bool second_ok = (lt_lo + 1) * 32 < C::S;
     const uint16_t* Lrow = L + ((size_t)lt_lo * 32 + rb) * C::Q;
+    // K-step (pp, m) of a unit: lane group g contracts over the 8 r = 16*(2pp + g) + 8m .. +7 of the
+    // unit's 64, i.e. half m of the 32-byte block 2pp + g of Y1s: piece 4pp + 2g + m of the L row
     int foff[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) foff[u] = unit_frag_off(ln, g, u);
-    // activation dwords: Y1s[b][kk*Q + c*QK + 16*tq + 4*u + 2*g]
-    const uint16_t* abase = y1s + (size_t)ln * C::Y1_STRIDE + 2 * g;
+    for (int u = 0; u < 4; ++u) foff[u] = unit_piece_off(ln, 4 * (u >> 1) + 2 * g + (u & 1));
+    // activation block: Y1s[b][16 * (c*QK/4 + 4*tq + 2*pp + g) ..], 32 bytes = (kk, j%4) for four j
+    const uint16_t* abase = y1s + (size_t)ln * C::Y1_STRIDE + 16 * g;
 
     f32x16 acc[UPW * K];
 #pragma unroll
@@ -135,38 +160,39 @@ __device__ __forceinline__ void stage2_pass_lines(const uint16_t* __restrict__ L
         for (int bi = 0; bi < 4; ++bi) dma16(src + (size_t)bi * 8 * C::Q + 8 * (pe ^ (bi & 1)), dst + bi * 512);
     };
     u32x4 wraw[2][4];
-    u32x4 araw[2][4][C::NB];
+    u32x4 ablk[2][2][C::NB][2];  // [slot][pp][nb][lo/hi 16 bytes of the block]
     auto read = [&](int n, int slot) {
         const int c = n / (TQ64 * NLT), tq = (n / NLT) % TQ64;
         const uint16_t* wbuf = stg + (size_t)(n % RD) * 2048;
-        const uint16_t* ap = abase + c * C::QK + tq * 16;
+        const uint16_t* ap = abase + 16 * (c * (C::QK / 4) + 4 * tq);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            wraw[slot][u] = lds128(wbuf + foff[u]);
+        for (int u = 0; u < 4; ++u) wraw[slot][u] = lds128(wbuf + foff[u]);
 #pragma unroll
-            for (int nb = 0; nb < C::NB; ++nb)
+        for (int pp = 0; pp < 2; ++pp)
 #pragma unroll
-                for (int kk = 0; kk < K; ++kk)
-                    araw[slot][u][nb][kk] = *reinterpret_cast<const uint32_t*>(ap + (size_t)nb * 32 * C::Y1_STRIDE + kk * C::Q + 4 * u);
-        }
+            for (int nb = 0; nb < C::NB; ++nb) {
+                ablk[slot][pp][nb][0] = lds128(ap + (size_t)nb * 32 * C::Y1_STRIDE + 32 * pp);
+                ablk[slot][pp][nb][1] = lds128(ap + (size_t)nb * 32 * C::Y1_STRIDE + 32 * pp + 8);
+            }
     };
     wait_vmcnt<0>();  // stores of the previous pass: the ring below counts loads only
+    // A ring slot is free as soon as its fragments are in registers, one step before their MFMAs:
+    // RD units are in flight or landed at any time (unit n + RD is issued in step n).
 #pragma unroll
-    for (int d = 0; d < RD - 1; ++d)
+    for (int d = 0; d < RD; ++d)
         if (d < NU) issue(d);
-    wait_vmcnt<((NU < RD - 1 ? NU : RD - 1) - 1) * 4>();
+    wait_vmcnt<((NU < RD ? NU : RD) - 1) * 4>();
     __builtin_amdgcn_sched_barrier(0);
     read(0, 0);
 #pragma unroll
     for (int n = 0; n < NU; ++n) {
         __builtin_amdgcn_sched_barrier(0);
-        wait_lgkmcnt0();
-        if (n + RD - 1 < NU) issue(n + RD - 1);
+        wait_lgkmcnt0();  // the fragments of unit n are in registers: its slot is recycled below
+        if (n + RD < NU) issue(n + RD);
         if (n + 1 < NU) {
             // unit n+1 has landed once at most the units issued after it are outstanding
-            constexpr int dummy = 0; (void)dummy;
-            const int later = (n + RD - 1 < NU ? n + RD - 1 : NU - 1) - (n + 1);
-            if (later >= RD - 2) wait_vmcnt<(RD - 2) * 4>(); else if (later == 1 && RD > 3) wait_vmcnt<4>(); else wait_vmcnt<0>();
+            const int later = (n + RD < NU ? n + RD : NU - 1) - (n + 1);
+            wait_vmcnt_units(later);
             __builtin_amdgcn_sched_barrier(0);
             read(n + 1, (n + 1) & 1);
         }
@@ -181,7 +207,14 @@ __device__ __forceinline__ void stage2_pass_lines(const uint16_t* __restrict__ L
 #pragma unroll
             for (int i = 0; i < UPW; ++i) {
                 const int ww = i + (ODD ? 1 : 0);  // work unit relative to the first staged l tile
-                if ((ww >> 1) == li) acc[i * K + c] = mfma32(as_bf16x8(araw[n & 1][u][ww & 1]), wfrag, acc[i * K + c]);
+                if ((ww >> 1) == li) {
+                    // dword 2*kk + m of the block holds (j%4 = 2m, 2m+1) for kk: slots (kk, r1a r1b)
+                    const u32x4& b0v = ablk[n & 1][u >> 1][ww & 1][0];
+                    const u32x4& b1v = ablk[n & 1][u >> 1][ww & 1][1];
+                    const int m = u & 1;
+                    const u32x4 av = {b0v[m], b0v[2 + m], b1v[m], b1v[2 + m]};
+                    acc[i * K + c] = mfma32(as_bf16x8(av), wfrag, acc[i * K + c]);
+                }
             }
         }
     }
@@ -216,10 +249,11 @@ __device__ __forceinline__ void stage2_pass(const uint16_t* __restrict__ L, cons
     const uint16_t* Lsrc = L + ((size_t)lt_lo * 32 + sr) * C::Q + 8 * sp;
     // fragment read offsets inside a staged 32-row tile (two blocks), K-step u of the chunk
     const int rr = ln & 15, sw = (rr >> 2) & 3;
-    const int foff0 = (ln >> 4) * 512 + rr * 32 + 8 * ((0 + g) ^ sw);
-    const int foff1 = (ln >> 4) * 512 + rr * 32 + 8 * ((2 + g) ^ sw);
-    // activation dwords: Y1s[b][kk*Q + c*QK + 8*tq + 4*u + 2*g]
-    const uint16_t* abase = y1s + (size_t)ln * C::Y1_STRIDE + 2 * g;
+    // K-step m of a chunk: lane group g contracts over r = 16g + 8m .. +7 of the chunk's 32 (piece 2g + m)
+    const int foff0 = (ln >> 4) * 512 + rr * 32 + 8 * ((2 * g + 0) ^ sw);
+    const int foff1 = (ln >> 4) * 512 + rr * 32 + 8 * ((2 * g + 1) ^ sw);
+    // activation block: Y1s[b][16 * (c*QK/4 + 2*tq + g) ..], 32 bytes = (kk, j%4) for four j
+    const uint16_t* abase = y1s + (size_t)ln * C::Y1_STRIDE + 16 * g;
 
     f32x16 acc[UPW * K];
 #pragma unroll
@@ -260,7 +294,13 @@ __device__ __forceinline__ void stage2_pass(const uint16_t* __restrict__ L, cons
             }
             __builtin_amdgcn_sched_barrier(0);
             const uint16_t* wbuf = stg + (size_t)(st % C::D2) * C::NBLK2 * 512;
-            const uint16_t* ap = abase + c * C::QK + tq * 8;
+            const uint16_t* ap = abase + 16 * (c * (C::QK / 4) + 2 * tq);
+            u32x4 ablk[C::NB][2];
+#pragma unroll
+            for (int nb = 0; nb < C::NB; ++nb) {
+                ablk[nb][0] = lds128(ap + (size_t)nb * 32 * C::Y1_STRIDE);
+                ablk[nb][1] = lds128(ap + (size_t)nb * 32 * C::Y1_STRIDE + 8);
+            }
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 bf16x8 wfr[C::NLT], afr[C::NB];
@@ -273,10 +313,8 @@ __device__ __forceinline__ void stage2_pass(const uint16_t* __restrict__ L, cons
                 }
 #pragma unroll
                 for (int nb = 0; nb < C::NB; ++nb) {
-                    u32x4 av;
-#pragma unroll
-                    for (int kk = 0; kk < K; ++kk)
-                        av[kk] = *reinterpret_cast<const uint32_t*>(ap + (size_t)nb * 32 * C::Y1_STRIDE + kk * C::Q + 4 * u);
+                    // dword 2*kk + u of the block holds (j%4 = 2u, 2u+1) for kk: slots (kk, r1a r1b)
+                    const u32x4 av = {ablk[nb][0][u], ablk[nb][0][2 + u], ablk[nb][1][u], ablk[nb][1][2 + u]};
                     afr[nb] = as_bf16x8(av);
                 }
 #pragma unroll
@@ -413,8 +451,8 @@ fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
 #pragma unroll
                 for (int i4 = 0; i4 < 4; ++i4) {
                     const f32x16& a = acc[jt * C::NB + nb];
-                    const int j = jt * 32 + 8 * i4 + 4 * g;
-                    *reinterpret_cast<u32x2*>(lds + (size_t)(nb * 32 + ln) * C::Y1_STRIDE + kk * C::Q + j) =
+                    const int j = jt * 32 + 8 * i4 + 4 * g;  // four consecutive j: one 8-byte slot of block j/4
+                    *reinterpret_cast<u32x2*>(lds + (size_t)(nb * 32 + ln) * C::Y1_STRIDE + (j >> 2) * 16 + kk * 4) =
                         u32x2{pack_bf16x2(a[4 * i4 + 0], a[4 * i4 + 1]), pack_bf16x2(a[4 * i4 + 2], a[4 * i4 + 3])};
                 }
     }
