@@ -359,11 +359,11 @@ Plan64 make_plan64(const Problem& pb)
     const int tiles = wgrad_tiles(dl) + wgrad_tiles(dr);
     pl.ok = wgrad_tiles(dl) > 0 && wgrad_tiles(dr) > 0;
     if (!pl.ok) return pl;
-    int64_t z = (256 + tiles - 1) / tiles;
+    int64_t z = 256 / tiles;  // at most one workgroup per CU: its two LDS buffers leave room for one only
     const int64_t maxz = (pb.B + 255) / 256;
     if (z > maxz) z = maxz;
     if (z < 1) z = 1;
-    const int64_t rpc = ((pb.B + z - 1) / z + 31) / 32 * 32;
+    const int64_t rpc = ((pb.B + z - 1) / z + 63) / 64 * 64;  // whole pipeline rounds (two 32-row steps)
     pl.rows_per_chunk = (int)(rpc > 0 ? rpc : 32);
     pl.nz = (int)((pb.B + pl.rows_per_chunk - 1) / pl.rows_per_chunk);
     if (pl.nz < 1) pl.nz = 1;

@@ -50,9 +50,8 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
 {
     constexpr int MT = TM / 32, NT = TN / 32;
     constexpr int SA = TM + 8, SB = TN + 8;  // LDS row strides (bf16 elements)
+    constexpr int BUF = 4 * KB * (SA + SB);  // one pipeline buffer: As [4][KB][SA], then Bs [4][KB][SB]
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-    uint16_t* As = lds;                        // [4][KB][SA]
-    uint16_t* Bs = lds + 4 * KB * SA;          // [4][KB][SB]
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int tiles_n = d.N / TN;
@@ -62,76 +61,95 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
     const int64_t row_lo = (int64_t)zi * d.rows_per_chunk;
     int64_t row_hi = row_lo + d.rows_per_chunk;
     if (row_hi > d.rows) row_hi = d.rows;
+    const int64_t nrows = row_hi > row_lo ? row_hi - row_lo : 0;
 
     // ---- per-thread load tasks (16-byte pieces; DEINT A: 64-byte runs holding 8 m x 4 groups) ----
+    // Addresses are fixed for the whole chunk: global pointers at row_lo (advanced by a uniform row
+    // offset per step), LDS offsets inside a buffer, and the row of the task inside a step.
     constexpr int A_TASKS = DEINT ? (KB * TM / 8) : (4 * KB * TM / 8);
     constexpr int B_TASKS = 4 * KB * TN / 8;
     constexpr int A_PER = (A_TASKS + 255) / 256, B_PER = (B_TASKS + 255) / 256;
-    u32x4 areg[A_PER][DEINT ? 4 : 1], breg[B_PER];
+    u32x4 areg[2][A_PER][DEINT ? 4 : 1], breg[2][B_PER];
+    const uint16_t* pa[A_PER];
+    const uint16_t* pb[B_PER];
+    int ra[A_PER], rb[B_PER], la[A_PER], lb[B_PER];
+#pragma unroll
+    for (int t = 0; t < A_PER; ++t) {
+        // a thread without a task in this slot repeats task 0 (its loads are unconditional and must
+        // stay in bounds; it stores nothing)
+        const int task = tid + t * 256 < A_TASKS ? tid + t * 256 : 0;
+        if (DEINT) {
+            const int r = task / (TM / 8), u = task % (TM / 8);
+            ra[t] = tid + t * 256 < A_TASKS ? r : (1 << 30);
+            pa[t] = d.A + (row_lo + r) * d.lda + (size_t)(m0 + 8 * u) * 4 + g0;
+            la[t] = r * SA + 8 * u;
+        } else {
+            const int g = task / (KB * TM / 8), rem = task % (KB * TM / 8);
+            const int r = rem / (TM / 8), u = rem % (TM / 8);
+            ra[t] = tid + t * 256 < A_TASKS ? r : (1 << 30);
+            pa[t] = d.A + (row_lo + r) * d.lda + (size_t)(g0 + g) * d.a_g + m0 + 8 * u;
+            la[t] = (g * KB + r) * SA + 8 * u;
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < B_PER; ++t) {
+        const int task = tid + t * 256 < B_TASKS ? tid + t * 256 : 0;
+        const int g = task / (KB * TN / 8), rem = task % (KB * TN / 8);
+        const int r = rem / (TN / 8), u = rem % (TN / 8);
+        const int n = n0 + 8 * u;
+        rb[t] = tid + t * 256 < B_TASKS ? r : (1 << 30);
+        pb[t] = d.Bm + (row_lo + r) * d.ldb + (size_t)(g0 + g) * d.b_g + (size_t)(n / d.seg_w) * d.b_seg + (n % d.seg_w);
+        lb[t] = 4 * KB * SA + (g * KB + r) * SB + 8 * u;
+    }
 
-    auto load_step = [&](int64_t r0) {
+    // rows r0 .. r0+KB-1 of the chunk -> register stage `stg`.  The loads are unconditional (rows past
+    // the end of the chunk re-read its last row and are zeroed in store_step): a predicated load
+    // becomes a branch, and across branches the compiler waits for ALL outstanding loads (vmcnt(0))
+    // in every step, which exposes the full memory latency per step.
+    const int64_t last = nrows > 0 ? nrows - 1 : 0;
+    auto load_step = [&](int64_t r0, int stg) {
 #pragma unroll
         for (int t = 0; t < A_PER; ++t) {
-            const int task = tid + t * 256;
-            if (DEINT) {
-                const int r = task / (TM / 8), u = task % (TM / 8);
-                const int64_t row = r0 + r;
-                const bool ok = task < A_TASKS && row < row_hi;
-                const uint16_t* p = d.A + row * d.lda + (size_t)(m0 + 8 * u) * 4 + g0;
+            int64_t r = r0 + (ra[t] < KB ? ra[t] : 0);
+            r = r < last ? r : last;
+            const uint16_t* p = pa[t] + (r - (ra[t] < KB ? ra[t] : 0)) * d.lda;
 #pragma unroll
-                for (int w = 0; w < 4; ++w) areg[t][w] = ok ? ldg128(p + 8 * w) : u32x4{0, 0, 0, 0};
-            } else {
-                const int g = task / (KB * TM / 8), rem = task % (KB * TM / 8);
-                const int r = rem / (TM / 8), u = rem % (TM / 8);
-                const int64_t row = r0 + r;
-                const bool ok = task < A_TASKS && row < row_hi;
-                const uint16_t* p = d.A + row * d.lda + (size_t)(g0 + g) * d.a_g + m0 + 8 * u;
-                areg[t][0] = ok ? ldg128(p) : u32x4{0, 0, 0, 0};
-            }
+            for (int w = 0; w < (DEINT ? 4 : 1); ++w) areg[stg][t][w] = ldg128(p + 8 * w);
         }
 #pragma unroll
         for (int t = 0; t < B_PER; ++t) {
-            const int task = tid + t * 256;
-            const int g = task / (KB * TN / 8), rem = task % (KB * TN / 8);
-            const int r = rem / (TN / 8), u = rem % (TN / 8);
-            const int64_t row = r0 + r;
-            const bool ok = task < B_TASKS && row < row_hi;
-            const int n = n0 + 8 * u;
-            const uint16_t* p = d.Bm + row * d.ldb + (size_t)(g0 + g) * d.b_g + (size_t)(n / d.seg_w) * d.b_seg + (n % d.seg_w);
-            breg[t] = ok ? ldg128(p) : u32x4{0, 0, 0, 0};
+            int64_t r = r0 + (rb[t] < KB ? rb[t] : 0);
+            r = r < last ? r : last;
+            breg[stg][t] = ldg128(pb[t] + (r - (rb[t] < KB ? rb[t] : 0)) * d.ldb);
         }
     };
-    auto store_step = [&]() {
+    // register stage (rows r0 ..) -> LDS buffer; rows past the end of the chunk are stored as zeros
+    auto store_step = [&](int64_t r0, int stg, uint16_t* buf) {
 #pragma unroll
         for (int t = 0; t < A_PER; ++t) {
-            const int task = tid + t * 256;
-            if (task >= A_TASKS) continue;
+            if (ra[t] >= KB) continue;
+            const bool ok = r0 + ra[t] < nrows;
             if (DEINT) {
-                const int r = task / (TM / 8), u = task % (TM / 8);
                 // the run holds elements e = 4*m' + c (m' = 0..7); gather the 8 m' of each group c
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     u32x4 v;
 #pragma unroll
                     for (int w = 0; w < 4; ++w) {
-                        const uint32_t lo = areg[t][w][c >> 1], hi = areg[t][w][2 + (c >> 1)];
-                        v[w] = (c & 1) ? pick_hi16(lo, hi) : pick_lo16(lo, hi);
+                        const uint32_t lo = areg[stg][t][w][c >> 1], hi = areg[stg][t][w][2 + (c >> 1)];
+                        v[w] = ok ? ((c & 1) ? pick_hi16(lo, hi) : pick_lo16(lo, hi)) : 0u;
                     }
-                    *reinterpret_cast<u32x4*>(As + ((size_t)c * KB + r) * SA + 8 * u) = v;
+                    *reinterpret_cast<u32x4*>(buf + c * KB * SA + la[t]) = v;
                 }
             } else {
-                const int g = task / (KB * TM / 8), rem = task % (KB * TM / 8);
-                const int r = rem / (TM / 8), u = rem % (TM / 8);
-                *reinterpret_cast<u32x4*>(As + ((size_t)g * KB + r) * SA + 8 * u) = areg[t][0];
+                *reinterpret_cast<u32x4*>(buf + la[t]) = ok ? areg[stg][t][0] : u32x4{0, 0, 0, 0};
             }
         }
 #pragma unroll
         for (int t = 0; t < B_PER; ++t) {
-            const int task = tid + t * 256;
-            if (task >= B_TASKS) continue;
-            const int g = task / (KB * TN / 8), rem = task % (KB * TN / 8);
-            const int r = rem / (TN / 8), u = rem % (TN / 8);
-            *reinterpret_cast<u32x4*>(Bs + ((size_t)g * KB + r) * SB + 8 * u) = breg[t];
+            if (rb[t] >= KB) continue;
+            const bool ok = r0 + rb[t] < nrows;
+            *reinterpret_cast<u32x4*>(buf + lb[t]) = ok ? breg[stg][t] : u32x4{0, 0, 0, 0};
         }
     };
 
@@ -141,26 +159,46 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
-    const uint16_t* Aw = As + (size_t)wave * KB * SA;
-    const uint16_t* Bw = Bs + (size_t)wave * KB * SB;
-    if (row_lo < row_hi) load_step(row_lo);
-    for (int64_t r0 = row_lo; r0 < row_hi; r0 += KB) {
-        __syncthreads();  // previous step's fragment reads are done
-        store_step();
-        __syncthreads();
-        if (r0 + KB < row_hi) load_step(r0 + KB);
+    // Pipeline (one workgroup barrier per 32-row step, two LDS buffers, two register stages):
+    // in step s the MFMAs read buffer s%2 while the rows of step s+1 go from registers to buffer
+    // (s+1)%2 and the rows of step s+3 are fetched into the registers just freed.  The fragments of
+    // the second K-step are read before the MFMAs of the first, so that LDS latency hides behind them.
+    // The loop body has no branches (a step past the end of the chunk works on zeros): control flow
+    // here makes the compiler shuffle the accumulators between blocks.
+    if (nrows > 0) {  // (uniform) an empty chunk touches no memory and yields a zero partial tile
+    load_step(0, 0);
+    load_step(KB, 1);
+    store_step(0, 0, lds);
+    load_step(2 * KB, 0);
+    const int woff_a = wave * KB * SA, woff_b = 4 * KB * SA + wave * KB * SB;
+    for (int64_t r0 = 0; r0 < nrows; r0 += 2 * KB) {
 #pragma unroll
-        for (int ks = 0; ks < KB / 16; ++ks) {
-            bf16x8 af[MT], bfr[NT];
+        for (int k = 0; k < 2; ++k) {
+            const uint16_t* cur = lds + k * BUF;
+            uint16_t* nxt = lds + (k ^ 1) * BUF;
+            __syncthreads();
+            bf16x8 af[2][MT], bfr[2][NT];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) af[mt] = frag_tr(Aw, SA, ks * 16, mt * 32, lane);
+            for (int mt = 0; mt < MT; ++mt) af[0][mt] = frag_tr(cur + woff_a, SA, 0, mt * 32, lane);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) bfr[nt] = frag_tr(Bw, SB, ks * 16, nt * 32, lane);
+            for (int nt = 0; nt < NT; ++nt) bfr[0][nt] = frag_tr(cur + woff_b, SB, 0, nt * 32, lane);
+            __builtin_amdgcn_sched_barrier(0);
+            store_step(r0 + (k + 1) * KB, k ^ 1, nxt);
+            load_step(r0 + (k + 3) * KB, k ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+            for (int mt = 0; mt < MT; ++mt) af[1][mt] = frag_tr(cur + woff_a, SA, 16, mt * 32, lane);
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) acc[mt * NT + nt] = mfma32(af[mt], bfr[nt], acc[mt * NT + nt]);
+            for (int nt = 0; nt < NT; ++nt) bfr[1][nt] = frag_tr(cur + woff_b, SB, 16, nt * 32, lane);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) acc[mt * NT + nt] = mfma32(af[ks][mt], bfr[ks][nt], acc[mt * NT + nt]);
         }
+    }
     }
 
     // partial tile: P[z][g][m][n]
@@ -238,7 +276,7 @@ int tiles_of(const WgradDesc& d, int tm, int tn) { return (d.M / tm) * (d.N / tn
 template <int TM, int TN>
 int launch_gemm(const WgradDesc& d0, const WgradDesc* d1, int nz, hipStream_t st)
 {
-    constexpr size_t lds = (size_t)4 * KB * (TM + 8 + TN + 8) * 2;
+    constexpr size_t lds = (size_t)2 * 4 * KB * (TM + 8 + TN + 8) * 2;  // two pipeline buffers
     auto kern = wgrad_gemm_kernel<TM, TN>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return -4;
