@@ -17,7 +17,6 @@
 //             (monarch_mfma_wgrad.hip), split over the batch, then one reduction pass.
 #include "monarch_internal.h"
 #include "monarch_mfma_common.h"
-#include <cstdlib>
 
 namespace monarch {
 
@@ -93,9 +92,8 @@ prep_frag_kernel(const uint16_t* __restrict__ L, const uint16_t* __restrict__ R,
 
 // ------------------------------------------------------------------------ data ----
 
-template <int P_, int Q_, int S_, int JG_, int LC_, int IG_, int DBG_ = 0, int NS_ = 0, int NSX_ = 0>
+template <int P_, int Q_, int S_, int JG_, int LC_, int IG_>
 struct BwdWide {
-    static constexpr int DBG = DBG_, NS_OVR = NS_, NSX_OVR = NSX_;
     static constexpr int K = 4, P = P_, Q = Q_, S = S_, JG = JG_, LC = LC_, IG = IG_;
     static constexpr int BM = 64, NB = 2;   // stage X uses 32 x 32 tiles (2 row tiles)
     static constexpr int NBT = 4;           // stages A, B use 16 x 16 tiles (4 row tiles)
@@ -152,19 +150,6 @@ __device__ __forceinline__ void wave_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// TUNING: DBG 2 = no MFMA (loads kept alive by an xor sink), 3 = no weight/x loads
-template <int DBG> __device__ __forceinline__ u32x4 dbg_ldg(const void* p) { return DBG == 3 ? u32x4{1u, 2u, 3u, (uint32_t)(uintptr_t)p} : ldg128(p); }
-template <int DBG> __device__ __forceinline__ f32x16 dbg_mfma32(u32x4 a, u32x4 b, f32x16 c)
-{
-    if (DBG == 2) { c[0] = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, c[0]) ^ a[0] ^ a[1] ^ a[2] ^ a[3] ^ b[0] ^ b[1] ^ b[2] ^ b[3]); return c; }
-    return mfma32(as_bf16x8(a), as_bf16x8(b), c);
-}
-template <int DBG> __device__ __forceinline__ f32x4 dbg_mfma16(u32x4 a, bf16x8 b, f32x4 c)
-{
-    if (DBG == 2) { const u32x4 bb = __builtin_bit_cast(u32x4, b); c[0] = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, c[0]) ^ a[0] ^ a[1] ^ a[2] ^ a[3] ^ bb[0] ^ bb[1] ^ bb[2] ^ bb[3]); return c; }
-    return mfma16(as_bf16x8(a), b, c);
-}
-
 template <typename C>
 __global__ void __launch_bounds__(256)
 bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ x,
@@ -177,8 +162,6 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
     const int wave = tid >> 6, lane = tid & 63;
     const int64_t b0 = (int64_t)blockIdx.x * C::BM;
     const int kk = wave;
-    long long ts[8];
-    if (C::DBG) ts[0] = __builtin_amdgcn_s_memtime();
 
     // dy is consumed in chunks of LC features l; a chunk (64 rows x 4*LC columns) is fetched into
     // registers well before it is de-interleaved into LDS, so that its HBM latency is hidden
@@ -210,8 +193,8 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
             xrow[nb] = x + row * C::N_IN + kk * C::P + 32 * g;
         }
         // rings of K-steps: NS for the weight fragments (L2 latency), NSX for x (HBM latency)
-        constexpr int T = C::P / 16, NS = C::NS_OVR ? C::NS_OVR : 4;
-        constexpr int NSX = C::NSX_OVR ? C::NSX_OVR : ((T == 12) ? 12 : ((T % 8 == 0) ? 8 : 4));
+        constexpr int T = C::P / 16, NS = 4;
+        constexpr int NSX = (T == 12) ? 12 : ((T % 8 == 0) ? 8 : 4);
         static_assert(T % NS == 0 && T % NSX == 0 && NSX % NS == 0, "ring");
         // fragment (jg, t, jj) of XF; K-step t of lane group g covers columns 64*(t/4) + 32*g + 8*(t%4) ..
         const uint16_t* Xk = XF + ((size_t)kk * (C::QT / C::JG) * T * C::JG * 64 + lane) * 8;
@@ -228,11 +211,11 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
             u32x4 xf[NSX][C::NB], rf[NS][C::JG];
             auto issue_x = [&](int t, int slot) {
 #pragma unroll
-                for (int nb = 0; nb < C::NB; ++nb) xf[slot][nb] = dbg_ldg<C::DBG>(xrow[nb] + xcol(t));
+                for (int nb = 0; nb < C::NB; ++nb) xf[slot][nb] = ldg128(xrow[nb] + xcol(t));
             };
             auto issue_r = [&](int t, int slot) {
 #pragma unroll
-                for (int jj = 0; jj < C::JG; ++jj) rf[slot][jj] = dbg_ldg<C::DBG>(Rg + (size_t)(t * C::JG + jj) * 512);
+                for (int jj = 0; jj < C::JG; ++jj) rf[slot][jj] = ldg128(Rg + (size_t)(t * C::JG + jj) * 512);
             };
             // weights first: they come from L2 and the in-order load counter must not hold them behind x
 #pragma unroll
@@ -252,7 +235,7 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
 #pragma unroll
                         for (int nb = 0; nb < C::NB; ++nb)
                             acc[jj * C::NB + nb] =
-                                dbg_mfma32<C::DBG>(rf[k4 % NS][jj], xf[k4][nb], acc[jj * C::NB + nb]);
+                                mfma32(as_bf16x8(rf[k4 % NS][jj]), as_bf16x8(xf[k4][nb]), acc[jj * C::NB + nb]);
                 }
             }
 #pragma unroll
@@ -268,11 +251,9 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
                     }
         }
         load_dy(0);  // in flight during the copy-out below
-        if (C::DBG) ts[1] = __builtin_amdgcn_s_memtime();
         __syncthreads();
         copy_out_tile<C::KQ, 256, false>(lds, C::Y1_STRIDE, Y1ws, C::KQ, b0, B, tid);
         __syncthreads();
-        if (C::DBG) ts[2] = __builtin_amdgcn_s_memtime();
     }
 
     // 16 x 16 tile coordinates for stages A and B
@@ -295,7 +276,7 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
             const int c = n / T, t = n % T;
 #pragma unroll
             for (int jt = 0; jt < C::JT; ++jt)
-                af[slot][jt] = dbg_ldg<C::DBG>(Lk + ((size_t)(c * (C::S / 32) + t) * C::JT + jt) * 512);
+                af[slot][jt] = ldg128(Lk + ((size_t)(c * (C::S / 32) + t) * C::JT + jt) * 512);
         };
 #pragma unroll
         for (int d = 0; d < NSA - 1; ++d)
@@ -336,12 +317,10 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
 #pragma unroll
                 for (int bt = 0; bt < C::NBT; ++bt)
                     accA[(c * C::JT + jt) * C::NBT + bt] =
-                        dbg_mfma16<C::DBG>(af[n % NSA][jt], bfr[bt], accA[(c * C::JT + jt) * C::NBT + bt]);
+                        mfma16(as_bf16x8(af[n % NSA][jt]), bfr[bt], accA[(c * C::JT + jt) * C::NBT + bt]);
         }
         __syncthreads();
     }
-
-    if (C::DBG) ts[3] = __builtin_amdgcn_s_memtime();
     // bf16 fragments of dY1: dfr[J][bt] holds j = J*16 + 4*h + 0..3 (J = c*JT + jt) for row bt*16 + l16
     u32x2 dfr[C::K * C::JT][C::NBT];
 #pragma unroll
@@ -360,7 +339,6 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
     __syncthreads();
     copy_out_tile<C::KQ, 256, false>(lds, C::Y1_STRIDE, dY1ws, C::KQ, b0, B, tid);
     __syncthreads();
-    if (C::DBG) ts[4] = __builtin_amdgcn_s_memtime();
 
     // ------------------------------------------------- B: dx from the chained fragments ----
     // K-step u covers j in [32u, 32u+32): lane slots 0..3 <- tile 2u, slots 4..7 <- tile 2u+1;
@@ -376,7 +354,7 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
     u32x4 af[NSB][C::IG];
     auto issue = [&](int n, int slot) {
 #pragma unroll
-        for (int it = 0; it < C::IG; ++it) af[slot][it] = dbg_ldg<C::DBG>(Rt + ((size_t)n * C::IG + it) * 512);
+        for (int it = 0; it < C::IG; ++it) af[slot][it] = ldg128(Rt + ((size_t)n * C::IG + it) * 512);
     };
 #pragma unroll
     for (int d = 0; d < NSB - 1; ++d) issue(d, d);
@@ -396,7 +374,7 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
                 const bf16x8 bfr = as_bf16x8(bv);
 #pragma unroll
                 for (int it = 0; it < C::IG; ++it)
-                    acc[it * C::NBT + bt] = dbg_mfma16<C::DBG>(af[u % NSB][it], bfr, acc[it * C::NBT + bt]);
+                    acc[it * C::NBT + bt] = mfma16(as_bf16x8(af[u % NSB][it]), bfr, acc[it * C::NBT + bt]);
             }
         }
         // D^T[i][b]: lane holds i = it*16 + 4*h + 0..3 for row b = bt*16 + l16
@@ -412,15 +390,6 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
         wave_fence();
         copy_out_tile<C::DX_COLS, 64, true>(stage, C::DX_STRIDE, dx + kk * C::P + ig * C::DX_COLS, C::N_IN, b0, B, lane);
         wave_fence();
-    }
-    if (C::DBG) {
-        __builtin_amdgcn_s_waitcnt(0);
-        ts[5] = __builtin_amdgcn_s_memtime();
-        __syncthreads();
-        if (lane == 0) {
-            long long* o = reinterpret_cast<long long*>(Y1ws + b0 * C::KQ) + wave * 8;
-            for (int i = 0; i < 6; ++i) o[i] = ts[i];
-        }
     }
 }
 
@@ -456,21 +425,9 @@ const Entry kTable[] = {
     {128, 64, 64, 2, 4, launch_data<BwdWide<128, 64, 64, 2, 64, 4>>},
 };
 
-const Entry kDbgEntry[] = {{192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 1>>},  // TUNING: phase timestamps
-                            {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 2>>},
-                            {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 3>>},
-                            {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 1, 2, 2>>},    // 4
-                            {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 1, 2, 12>>},   // 5
-                            {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 1, 3, 3>>},    // 6
-                            {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 1, 3, 12>>},   // 7
-                            {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 1, 4, 4>>},    // 8
-                            {192, 192, 192, 6, 4, launch_data<BwdWide<192, 192, 192, 6, 192, 4, 1, 6, 6>>}};   // 9
-
-
 const Entry* find(const Problem& pb)
 {
     if (pb.dtype != 1 || pb.k != 4 || pb.perm_b()) return nullptr;
-    if (getenv("MONARCH_BWD_DBG") && pb.p == 192 && pb.q == 192 && pb.s == 192) return &kDbgEntry[atoi(getenv("MONARCH_BWD_DBG")) - 1];
     for (const Entry& e : kTable)
         if (e.p == pb.p && e.q == pb.q && e.s == pb.s) return &e;
     return nullptr;

@@ -31,20 +31,18 @@
 // its units so that step 3, y[b][4*l + c], is one packed 8-byte store per (b, l).
 #include "monarch_internal.h"
 #include "monarch_mfma_common.h"
-#include <stdlib.h>
 
 namespace monarch {
 
 namespace {
 
-template <int P_, int Q_, int S_, int UPW_, int D2_ = 3, int DBG_ = 0, int RD1_ = 8>
+template <int P_, int Q_, int S_, int UPW_, int D2_ = 3, int RD1_ = 8>
 struct FwdWide {
     static constexpr int K = 4, P = P_, Q = Q_, S = S_;
     static constexpr int BM = 64, NB = 2;     // rows per workgroup, 32-row tiles
     static constexpr int UPW = UPW_;          // stage-2 units (32 l x 32 rows) per wave per pass
     static constexpr int RD1 = RD1_;          // stage-1 LDS ring: 4 KiB units (32 rows x 128 bytes)
     static constexpr int D2 = D2_;            // stage-2 LDS ring depth (chunks, or 4 KiB units)
-    static constexpr int DBG = DBG_;
     static constexpr int QK = Q / K;          // columns of each R block that feed one L block
     static constexpr int QT = Q / 32;         // 32-wide j tiles per R block
     static constexpr int KQ = K * Q;
@@ -352,8 +350,6 @@ fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int ln = lane & 31, g = lane >> 5;
     const int64_t b0 = (int64_t)blockIdx.x * C::BM;
-    long long ts[4];
-    if (C::DBG >= 4) ts[0] = __builtin_amdgcn_s_memtime();
 
     // ------------------------------------------------------------- stage 1 ----
     {
@@ -411,7 +407,7 @@ fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
                 {
                     constexpr int dummy = 0; (void)dummy;
                     const int ui = (u + C::RD1 - 1) % C::UPC, ci = c64 + (u + C::RD1 - 1) / C::UPC;
-                    if (C::DBG != 6 && n + C::RD1 - 1 < C::NU1) issue(ci, ui);
+                    if (n + C::RD1 - 1 < C::NU1) issue(ci, ui);
                 }
                 const bool next_is_x = (u + 1 == C::UPC) || (u + 1 < 2);
                 const int un = (u + 1) % C::UPC, cn = c64 + (u + 1) / C::UPC;
@@ -422,10 +418,10 @@ fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
                 };
                 if (!next_is_x && n + 1 < C::NU1) {
                     wait_next();
-                    if (C::DBG != 5) read(cn, un, rf[un & 1]);
+                    read(cn, un, rf[un & 1]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                if (u >= 2 && C::DBG != 5) {
+                if (u >= 2) {
                     const int jt = u - 2;
 #pragma unroll
                     for (int k4 = 0; k4 < 4; ++k4)
@@ -436,12 +432,11 @@ fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
                 __builtin_amdgcn_sched_barrier(0);
                 if (next_is_x && n + 1 < C::NU1) {
                     wait_next();
-                    if (C::DBG != 5) read(cn, un, xf[un]);
+                    read(cn, un, xf[un]);
                 }
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-        if (C::DBG >= 4) ts[1] = __builtin_amdgcn_s_memtime();
         __syncthreads();  // every wave is done with its staging ring: the space becomes Y1s
         // lane holds D^T[j][b] for b = nb*32 + ln and j = jt*32 + 8*(i/4) + 4*g + i%4
 #pragma unroll
@@ -457,7 +452,6 @@ fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
                 }
     }
     __syncthreads();
-    if (C::DBG >= 4) ts[2] = __builtin_amdgcn_s_memtime();
 
     // ------------------------------------------------------------- stage 2 ----
     {
@@ -477,15 +471,6 @@ fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
             }
         }
     }
-    if (C::DBG >= 4) {
-        __builtin_amdgcn_s_waitcnt(0);
-        ts[3] = __builtin_amdgcn_s_memtime();
-        __syncthreads();
-        if (lane == 0) {
-            long long* o = reinterpret_cast<long long*>(y + b0 * C::N_OUT) + wave * 4;
-            for (int i = 0; i < 4; ++i) o[i] = ts[i];
-        }
-    }
 }
 
 template <typename C>
@@ -502,45 +487,28 @@ int launch(const Problem& pb, const void* x, const void* R, const void* L, void*
 }
 
 struct Entry {
-    int p, q, s, variant;
+    int p, q, s;
     int (*fn)(const Problem&, const void*, const void*, const void*, void*, hipStream_t);
 };
 
-// variant 0 is the default; the others are reachable with MONARCH_FWD_VARIANT=<n> (tuning aid)
-//                                      P     Q     S  UPW D2
+//                                 P     Q     S  UPW
 const Entry kTable[] = {
-    {192, 192, 192, 0, launch<FwdWide<192, 192, 192, 3, 3>>},    // ViT-B projection 768 -> 768
-    {192, 192, 192, 1, launch<FwdWide<192, 192, 192, 3, 3, 0, 6>>},
-    {192, 192, 192, 11, launch<FwdWide<192, 192, 192, 3, 3, 4>>},
-    {192, 192, 192, 12, launch<FwdWide<192, 192, 192, 3, 3, 5>>},
-    {192, 192, 192, 13, launch<FwdWide<192, 192, 192, 3, 3, 6>>},
-    {192, 192, 768, 0, launch<FwdWide<192, 192, 768, 4, 3>>},    // GPT-2 small fc1 768 -> 3072
-    {192, 192, 768, 1, launch<FwdWide<192, 192, 768, 2, 3>>},
-    {256, 256, 1024, 0, launch<FwdWide<256, 256, 1024, 2, 3>>},  // GPT-2 medium fc1 1024 -> 4096
-    {1024, 256, 256, 0, launch<FwdWide<1024, 256, 256, 2, 3>>},  // GPT-2 medium fc2 4096 -> 1024
-    {768, 192, 192, 0, launch<FwdWide<768, 192, 192, 3, 3>>},    // GPT-2 small fc2 3072 -> 768
-    {64, 64, 64, 0, launch<FwdWide<64, 64, 64, 1, 3>>},          // small shapes (tests)
-    {64, 64, 128, 0, launch<FwdWide<64, 64, 128, 2, 3>>},
-    {128, 64, 64, 0, launch<FwdWide<128, 64, 64, 1, 3>>},
+    {192, 192, 192, launch<FwdWide<192, 192, 192, 3>>},    // ViT-B projection 768 -> 768
+    {192, 192, 768, launch<FwdWide<192, 192, 768, 4>>},    // GPT-2 small fc1 768 -> 3072
+    {256, 256, 1024, launch<FwdWide<256, 256, 1024, 2>>},  // GPT-2 medium fc1 1024 -> 4096
+    {1024, 256, 256, launch<FwdWide<1024, 256, 256, 2>>},  // GPT-2 medium fc2 4096 -> 1024
+    {768, 192, 192, launch<FwdWide<768, 192, 192, 3>>},    // GPT-2 small fc2 3072 -> 768
+    {64, 64, 64, launch<FwdWide<64, 64, 64, 1>>},          // small shapes (tests)
+    {64, 64, 128, launch<FwdWide<64, 64, 128, 2>>},
+    {128, 64, 64, launch<FwdWide<128, 64, 64, 1>>},
 };
-
-int tuning_variant()
-{
-    const char* v = getenv("MONARCH_FWD_VARIANT");
-    return v ? atoi(v) : 0;
-}
 
 const Entry* find(const Problem& pb)
 {
     if (pb.dtype != 1 || pb.k != 4 || pb.perm_b()) return nullptr;
-    const int want = tuning_variant();
-    const Entry* fallback = nullptr;
     for (const Entry& e : kTable)
-        if (e.p == pb.p && e.q == pb.q && e.s == pb.s) {
-            if (e.variant == want) return &e;
-            if (e.variant == 0) fallback = &e;
-        }
-    return fallback;
+        if (e.p == pb.p && e.q == pb.q && e.s == pb.s) return &e;
+    return nullptr;
 }
 
 }  // namespace
