@@ -40,7 +40,7 @@
  * Ownership: all pointers are DEVICE pointers owned by the caller, 16-byte
  * aligned, valid until `stream` has passed the call.  Outputs must not alias
  * inputs.  The library keeps no state, allocates nothing and frees nothing;
- * scratch memory is the caller's `workspace` (monarch_bwd only).  All work is
+ * scratch memory is the caller's `workspace` (monarch_bwd, monarch_fwd_ws).  All work is
  * enqueued on `stream` (a hipStream_t passed as void*, NULL = the default
  * stream) and the calls return without synchronising.
  *
@@ -86,6 +86,25 @@ int monarch_fwd_ex(const void* x, const void* R, const void* L, void* y,
                    int64_t batch, int n_in, int k, int q, int s,
                    monarch_dtype dtype, void* stream, unsigned flags);
 
+/* Forward with scratch memory (same operation, same arguments and result as monarch_fwd_ex;
+ * Section 3.3 steps 1-3).  For the shapes that have a packed-weight kernel (bf16, k = 4 wide
+ * blocks) the call first re-lays R and L in matrix-core fragment order into `workspace` and then
+ * runs the fused forward on the packed copies, which removes the weights from the LDS traffic of
+ * the kernel; every other shape runs exactly as monarch_fwd_ex and ignores the workspace.
+ * `workspace` (device memory, 256-byte aligned, caller-owned) must hold at least
+ * monarch_fwd_workspace_bytes(...) bytes when that is non-zero; its contents on entry are ignored
+ * and on exit are unspecified.  Returns MONARCH_ERR_WORKSPACE if it is missing, misaligned or too
+ * small. */
+int monarch_fwd_ws(const void* x, const void* R, const void* L, void* y,
+                   int64_t batch, int n_in, int k, int q, int s,
+                   monarch_dtype dtype, void* stream,
+                   void* workspace, size_t workspace_bytes, unsigned flags);
+
+/* Bytes of device scratch monarch_fwd_ws needs for this problem (0 when the shape has no
+ * packed-weight kernel, and on invalid arguments). */
+size_t monarch_fwd_workspace_bytes(int64_t batch, int n_in, int k, int q, int s,
+                                   monarch_dtype dtype, unsigned flags);
+
 /* Backward: the adjoint of steps 3, 2, P^T, 1 in that order (the paper obtains it
  * by automatic differentiation, Section 4):
  *   dW[b][c][l]  = dy[b][l*k + c]
@@ -111,8 +130,8 @@ int monarch_bwd(const void* dy, const void* x, const void* R, const void* L,
 size_t monarch_bwd_workspace_bytes(int64_t batch, int n_in, int k, int q, int s,
                                    monarch_dtype dtype, unsigned flags);
 
-/* Name of the kernel family the dispatcher picks for this problem: pass 0 = forward,
- * 1 = backward.  Static string, never NULL ("invalid" / "unsupported" on bad input). */
+/* Name of the kernel family the dispatcher picks for this problem: pass 0 = forward
+ * (monarch_fwd / monarch_fwd_ex), 1 = backward, 2 = forward with workspace (monarch_fwd_ws).  Static string, never NULL ("invalid" / "unsupported" on bad input). */
 const char* monarch_kernel_name(int pass, int n_in, int k, int q, int s,
                                 monarch_dtype dtype, unsigned flags);
 

@@ -28,7 +28,8 @@ MONARCH_FLAG_GENERIC = 4
 
 # every symbol include/monarch.h declares
 EXPORTS = (
-    "monarch_fwd", "monarch_fwd_ex", "monarch_bwd", "monarch_bwd_workspace_bytes",
+    "monarch_fwd", "monarch_fwd_ex", "monarch_fwd_ws", "monarch_fwd_workspace_bytes", "monarch_bwd",
+    "monarch_bwd_workspace_bytes",
     "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy",
 )
 
@@ -55,6 +56,10 @@ def lib() -> ctypes.CDLL:
         L.monarch_fwd.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp]
         L.monarch_fwd_ex.restype = ci
         L.monarch_fwd_ex.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp, cu]
+        L.monarch_fwd_ws.restype = ci
+        L.monarch_fwd_ws.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
+        L.monarch_fwd_workspace_bytes.restype = sz
+        L.monarch_fwd_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci, cu]
         L.monarch_bwd.restype = ci
         L.monarch_bwd.argtypes = [vp] * 7 + [i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
         L.monarch_bwd_workspace_bytes.restype = sz
@@ -123,6 +128,36 @@ def monarch_kernel_name(pass_: int, n_in: int, k: int, q: int, s: int, dtype: in
 
 def monarch_bwd_workspace_bytes(batch: int, n_in: int, k: int, q: int, s: int, dtype: int, flags: int = 0) -> int:
     return int(lib().monarch_bwd_workspace_bytes(batch, n_in, k, q, s, dtype, flags))
+
+
+def monarch_fwd_workspace_bytes(batch: int, n_in: int, k: int, q: int, s: int, dtype: int, flags: int = 0) -> int:
+    return int(lib().monarch_fwd_workspace_bytes(batch, n_in, k, q, s, dtype, flags))
+
+
+def monarch_fwd_ws(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.Tensor | None = None,
+                   workspace: torch.Tensor | None = None, flags: int = 0, stream=None) -> torch.Tensor:
+    """y = x M^T through monarch_fwd_ws.  The workspace is allocated when not given."""
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    dev, dt = x.device, x.dtype
+    _check(x, "x", (B, k * p), dt, dev)
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    if y is None:
+        y = torch.empty((B, k * s), dtype=dt, device=dev)
+    _check(y, "y", (B, k * s), dt, dev)
+    need = monarch_fwd_workspace_bytes(B, k * p, k, q, s, _dtype_code(x), flags)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_ptr = workspace.data_ptr() if workspace is not None else 0
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(dev):
+        rc = lib().monarch_fwd_ws(x.data_ptr(), R.data_ptr(), L.data_ptr(), y.data_ptr(), B, k * p, k, q, s,
+                                  _dtype_code(x), _stream_ptr(stream), ws_ptr, ws_len, flags)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_fwd_ws")
+    return y
 
 
 def monarch_fwd(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.Tensor | None = None,

@@ -47,6 +47,12 @@ int mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, co
 bool fwd_wide_supported(const Problem& pb);
 int fwd_wide(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
 
+// bf16, k = 4, wide blocks: fused forward with the weights packed in MFMA fragment order into a
+// caller-provided workspace (monarch_mfma_fwd_frag.hip)
+bool fwd_frag_supported(const Problem& pb);
+size_t fwd_frag_workspace(const Problem& pb);
+int fwd_frag(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);
+
 // bf16, k = 4, wide blocks: backward (monarch_mfma_bwd_wide.hip)
 bool bwd_wide_supported(const Problem& pb);
 size_t bwd_wide_workspace(const Problem& pb);

@@ -464,7 +464,7 @@ Plan make_plan(const Problem& pb)
     const int tiles = wgrad_tiles(dl) + wgrad_tiles(dr);
     pl.ok = wgrad_tiles(dl) > 0 && wgrad_tiles(dr) > 0;
     if (!pl.ok) return pl;
-    int64_t z = 256 / tiles;  // at most one workgroup per CU: its two LDS buffers leave room for one only
+    int64_t z = 256 / tiles;  // one workgroup (eight waves) per CU: its two LDS buffers leave room for one only
     const int64_t maxz = (pb.B + 255) / 256;
     if (z > maxz) z = maxz;
     if (z < 1) z = 1;

@@ -1,0 +1,423 @@
+// Fused bf16 forward for "wide block" Monarch layers (k = 4) with the weights pre-laid in MFMA
+// fragment order (caller-provided workspace).  Both block-diagonal stages of Section 3.3 run on
+// v_mfma_f32_32x32x16_bf16, the mid permutation P^T of Definition 3.1 is folded into the K-slot
+// order of the packed L, the intermediate lives in LDS only.
+//
+// Why packed weights.  Every workgroup streams all of R and L; that stream is three quarters of
+// the bytes a workgroup touches, and it bounds the kernel through the vector L1 (about 50-57 bytes
+// per clock per CU when a wave instruction reads 1 KiB contiguously).  Staging row-major weights
+// through LDS to transpose them into operand layout costs an LDS write plus an LDS read per byte
+// on top, and LDS bandwidth then becomes the bound (measured: stage 2 of the LDS-staged kernel ran
+// at a third of its L1 bound).  With the weights stored fragment by fragment, a weight operand is
+// one fully coalesced 16-byte-per-lane global load straight into registers; LDS carries only the
+// activations (x on the way in, the intermediate between the stages).
+//
+//   pack      (pack_fwd_kernel) one thread builds one 16-byte piece:
+//             RF1[kk][t][jt][lane][e] = R[kk][32*jt + lane%32][16*t + 8*(lane/32) + e]
+//             LF2[c][lt][ks][lane][e] = L[c][32*lt + lane%32][4*(4*ks + e%4) + 2*(lane/32) + e/4]
+//   forward   one workgroup (4 waves) per 64 batch rows (two 32-row tiles):
+//     stage 1 (step 1): wave w computes block kk = w, D^T = R[kk] . X^T, all Q columns in
+//             accumulators.  x arrives through a wave-private LDS ring of 64-column chunks filled by
+//             global_load_lds_dwordx4 in full 128-byte lines (two chunks ahead: HBM latency); the
+//             R fragments arrive in a register ring three K-steps ahead (L2 latency).
+//     Y1      is written to LDS as Y1s[b][j/4][kk][j%4] (bf16): the 32 bytes of block j/4 hold, for
+//             four consecutive j, all four kk.
+//     stage 2 (step 2): U[b][c*Q + r] = Y1[b][r%4][c*Q/4 + r/4] (P^T on the (4, Q) grid), so K-step
+//             ks of block c is exactly LDS block c*Q/16 + ks: lane group g reads its 16-byte half
+//             (kk = 2g, 2g+1; four j each) with one ds_read_b128, and LF2 holds L's columns in the
+//             matching slot order.  No instruction is spent on the permutation.
+//             Work is split over waves in units of (32 features l) x (32 rows); a wave keeps all four
+//             c of its units so that step 3, y[b][4*l + c], is one packed 8-byte store per (b, l).
+#include "monarch_internal.h"
+#include "monarch_mfma_common.h"
+
+namespace monarch {
+
+namespace {
+
+// ------------------------------------------------------------------------ pack ----
+
+__global__ void __launch_bounds__(256)
+pack_fwd_kernel(const uint16_t* __restrict__ R, const uint16_t* __restrict__ L, uint16_t* __restrict__ RF1,
+                uint16_t* __restrict__ LF2, int P, int Q, int S)
+{
+    const int nR = 4 * Q * P / 8, nL = 4 * S * Q / 8;  // 16-byte pieces per array
+    int pc = blockIdx.x * 256 + threadIdx.x;
+    if (pc < nR) {
+        const int lane = pc & 63;
+        int rest = pc >> 6;
+        const int QT = Q / 32, T = P / 16;
+        const int jt = rest % QT; rest /= QT;
+        const int t = rest % T;
+        const int kk = rest / T;
+        const uint16_t* src = R + ((size_t)kk * Q + 32 * jt + (lane & 31)) * P + 16 * t + 8 * (lane >> 5);
+        *reinterpret_cast<u32x4*>(RF1 + (size_t)pc * 8) = *reinterpret_cast<const u32x4*>(src);
+    } else if (pc < nR + nL) {
+        pc -= nR;
+        const int lane = pc & 63;
+        int rest = pc >> 6;
+        const int KS = Q / 16, NLT = S / 32;
+        const int ks = rest % KS; rest /= KS;
+        const int lt = rest % NLT;
+        const int c = rest / NLT;
+        const int g = lane >> 5;
+        const uint16_t* src = L + ((size_t)c * S + 32 * lt + (lane & 31)) * Q + 16 * ks;
+        uint16_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = src[4 * (e & 3) + 2 * g + (e >> 2)];
+        u32x4 o;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) o[w] = (uint32_t)v[2 * w] | ((uint32_t)v[2 * w + 1] << 16);
+        *reinterpret_cast<u32x4*>(LF2 + (size_t)pc * 8) = o;
+    }
+}
+
+// --------------------------------------------------------------------- forward ----
+
+template <int P_, int Q_, int S_, int UPW_, int RW2_>
+struct FwdFrag {
+    static constexpr int K = 4, P = P_, Q = Q_, S = S_;
+    static constexpr int BM = 64, NB = 2;     // rows per workgroup, 32-row tiles
+    static constexpr int UPW = UPW_;          // stage-2 units (32 l x 32 rows) per wave per pass
+    static constexpr int RW2 = RW2_;          // stage-2 weight ring, K-steps
+    static constexpr int QT = Q / 32;         // 32-wide j tiles per R block
+    static constexpr int KQ = K * Q;
+    static constexpr int N_IN = K * P, N_OUT = K * S;
+    static constexpr int T1 = P / 16;         // stage-1 K-steps
+    static constexpr int C1 = P / 64;         // stage-1 x chunks (64 columns = one 128-byte line per row)
+    static constexpr int XR = C1 < 3 ? C1 : 3;  // x ring slots per wave (8 KiB each)
+    static constexpr int KS = Q / 16;         // stage-2 K-steps per L block
+    static constexpr int NLT_ALL = S / 32;
+    static constexpr int UNITS = NLT_ALL * NB;
+    static constexpr int PASSES = UNITS / (4 * UPW);
+    static constexpr int NLT = (UPW + 1) / 2; // l tiles a wave touches in one pass
+    static constexpr int Y1_STRIDE = KQ + 8;  // bf16; row stride = 4 dwords mod 64 banks
+    static constexpr size_t LDS_Y1 = (size_t)BM * Y1_STRIDE * 2;
+    static constexpr size_t LDS_X = (size_t)4 * XR * 8192;
+    static constexpr size_t LDS_BYTES = LDS_Y1 > LDS_X ? LDS_Y1 : LDS_X;
+    // vmcnt values that guarantee an x chunk has landed: at most this many younger VMEM operations
+    // may still be outstanding (stronger than necessary is safe, weaker is not)
+    static constexpr int cap63(int v) { return v < 63 ? v : 63; }
+    static constexpr int W_FIRST = cap63(8 * (XR - 1) + QT * (T1 < 3 ? T1 : 3));
+    static constexpr int W_C0 = cap63(7 * QT + (C1 > 2 ? 8 : 0));
+    static constexpr int W_MID = cap63(8 * QT + 8);
+    static constexpr int W_LAST = cap63(8 * QT);
+    static_assert(P % 64 == 0 && Q % 32 == 0 && S % 32 == 0 && Q % 16 == 0, "tile shapes");
+    static_assert(UNITS % (4 * UPW) == 0 && UPW >= 1 && UPW <= 4, "stage-2 split");
+    static_assert(KS % RW2 == 0 && RW2 % 2 == 0 && RW2 >= 2, "stage-2 ring");
+    static_assert(LDS_BYTES <= kMaxLdsBytes, "LDS");
+};
+
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt = simm16[3:0] | simm16[15:14] << 4)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
+// one global_load_lds_dwordx4: every lane fetches 16 bytes from its own address, the wave's 1 KiB
+// lands contiguously at `lds_block` (+ lane * 16)
+__device__ __forceinline__ void dma16(const uint16_t* gsrc, uint16_t* lds_block)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                     (__attribute__((address_space(3))) void*)lds_block, 16, 0, 0);
+}
+
+// 4 KiB staging unit = 32 rows x 128 bytes = four 1 KiB blocks of 8 rows.  One DMA instruction
+// fills a block: lane s fetches row s/8, and its slot s%8 holds logical 16-byte piece
+// (s%8) ^ key, key = (row & 7) ^ ((row >> 3) & 1), which makes the fragment reads conflict-free.
+// The fragment for K-step u of the chunk (16 columns) is pieces 2u and 2u+1: lane (row = lane%32, g = lane/32).
+__device__ __forceinline__ int unit_frag_off(int ln, int g, int u)
+{
+    const int bi = ln >> 3, r = ln & 7;
+    return bi * 512 + r * 64 + 8 * ((2 * u + g) ^ r ^ (bi & 1));
+}
+
+// Base pointers of the packed L fragments a wave streams in the stage-2 pass that starts at work unit u0:
+// fragment (c, lt, ks) sits at ((c*NLT_ALL + lt)*KS + ks) * 512 elements, + lane * 8.
+template <typename C>
+__device__ __forceinline__ void stage2_wbase(const uint16_t* __restrict__ LF2, int u0, int lane, const uint16_t* (&wbase)[C::NLT])
+{
+    const int lt_lo = u0 >> 1;
+    // the second l tile may not exist for the last wave (its units then never use it): reuse the first
+    const int lt_hi = (lt_lo + 1 < C::NLT_ALL) ? lt_lo + 1 : lt_lo;
+    wbase[0] = LF2 + ((size_t)lt_lo * C::KS * 64 + lane) * 8;
+    if (C::NLT > 1) wbase[C::NLT - 1] = LF2 + ((size_t)lt_hi * C::KS * 64 + lane) * 8;
+}
+
+// weights of K-step (c, ks) into ring slot `slot`
+template <typename C>
+__device__ __forceinline__ void stage2_issue_w(const uint16_t* const (&wbase)[C::NLT], u32x4 (&wr)[C::RW2][C::NLT], int c, int ks, int slot)
+{
+#pragma unroll
+    for (int li = 0; li < C::NLT; ++li)
+        wr[slot][li] = ldg128(wbase[li] + ((size_t)c * C::NLT_ALL * C::KS + ks) * 512);
+}
+
+// One stage-2 pass of one wave: work units u0 .. u0+UPW-1, unit w = (l tile w / 2, row tile w % 2).
+// PRE: the caller has already issued the weights of steps 0 .. RW-2 into `wr` (first pass: they
+// are fetched while the workgroup is still exchanging Y1 through LDS).
+template <typename C, bool ODD, bool PRE>
+__device__ __forceinline__ void stage2_pass(const uint16_t* __restrict__ LF2, const uint16_t* y1s,
+                                            uint16_t* __restrict__ y, int64_t b0, int64_t B, int u0, int lane,
+                                            u32x4 (&wr)[C::RW2][C::NLT])
+{
+    constexpr int UPW = C::UPW, K = 4, NLT = C::NLT, RW = C::RW2, KS = C::KS;
+    constexpr int NSTEP = K * KS;  // flat K-steps n = c*KS + ks; the activation block of step n is LDS block n
+    const int ln = lane & 31, g = lane >> 5;
+    const int lt_lo = u0 >> 1;
+    const uint16_t* wbase[NLT];
+    stage2_wbase<C>(LF2, u0, lane, wbase);
+    const uint16_t* abase = y1s + (size_t)ln * C::Y1_STRIDE + 8 * g;
+
+    f32x16 acc[UPW * K];
+#pragma unroll
+    for (int t = 0; t < UPW * K; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+
+    u32x4 ar[2][C::NB];
+    auto issue_w = [&](int c, int ks, int slot) { stage2_issue_w<C>(wbase, wr, c, ks, slot); };
+    auto read_a = [&](int n, int slot) {
+#pragma unroll
+        for (int nb = 0; nb < C::NB; ++nb) ar[slot][nb] = lds128(abase + (size_t)nb * 32 * C::Y1_STRIDE + n * 16);
+    };
+    // prologue: weights of steps 0 .. RW-2, activations of step 0
+    if (!PRE) {
+#pragma unroll
+        for (int d = 0; d < RW - 1; ++d) issue_w(d / KS, d % KS, d);
+    }
+    read_a(0, 0);
+#pragma unroll
+    for (int c = 0; c < K; ++c) {
+        for (int kg = 0; kg < KS; kg += RW) {
+#pragma unroll
+            for (int kr = 0; kr < RW; ++kr) {
+                const int ks = kg + kr, n = c * KS + ks;
+                __builtin_amdgcn_sched_barrier(0);
+                {
+                    // step n + RW - 1 goes to the slot step n - 1 has just left
+                    const int ksn = ks + RW - 1;
+                    const int cn = c + ksn / KS;
+                    if (cn < K) issue_w(cn, ksn % KS, (kr + RW - 1) % RW);
+                }
+                if (n + 1 < NSTEP) read_a(n + 1, (kr + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < UPW; ++i) {
+                    const int ww = i + (ODD ? 1 : 0);  // work unit relative to the first l tile
+                    acc[i * K + c] = mfma32(as_bf16x8(ar[kr & 1][ww & 1]), as_bf16x8(wr[kr][ww >> 1]), acc[i * K + c]);
+                }
+            }
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // step 3: y[b][4*l + c]; lane holds D[b][l] for l = lt*32 + ln, b = nb*32 + 8*(i/4) + 4*g + i%4
+#pragma unroll
+    for (int i = 0; i < UPW; ++i) {
+        const int ww = i + (ODD ? 1 : 0);
+        const int l = (lt_lo + (ww >> 1)) * 32 + ln;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int64_t row = b0 + (ww & 1) * 32 + 8 * (e / 4) + 4 * g + (e % 4);
+            if (row < B) {
+                u32x2 v = {pack_bf16x2(acc[i * K + 0][e], acc[i * K + 1][e]), pack_bf16x2(acc[i * K + 2][e], acc[i * K + 3][e])};
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(y + row * C::N_OUT + (size_t)l * K));
+            }
+        }
+    }
+}
+
+template <typename C>
+__global__ void __launch_bounds__(256)
+fwd_frag_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ RF1,
+                const uint16_t* __restrict__ LF2, uint16_t* __restrict__ y, int64_t B)
+{
+    extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int ln = lane & 31, g = lane >> 5;
+    const int64_t b0 = (int64_t)blockIdx.x * C::BM;
+
+    u32x4 wr2[C::RW2][C::NLT];  // stage-2 weight ring
+    // ------------------------------------------------------------- stage 1 ----
+    {
+        const int kk = wave;
+        uint16_t* ring = lds + (size_t)wave * C::XR * 4096;  // XR chunks of 8 KiB (two 4 KiB units: rows 0..31, 32..63)
+        const int rb = lane >> 3, pe = (lane & 7) ^ rb;
+        const uint16_t* Xrow[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int64_t row = b0 + i * 8 + rb;
+            row = row < B ? row : B - 1;  // rows past the end are computed from a valid row and dropped
+            Xrow[i] = x + row * C::N_IN + kk * C::P;
+        }
+        auto issue_x = [&](int c64) {
+            uint16_t* dst = ring + (size_t)(c64 % C::XR) * 4096;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                dma16(Xrow[i] + c64 * 64 + 8 * (pe ^ (i & 1)), dst + i * 512);
+        };
+        int foff[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) foff[u] = unit_frag_off(ln, g, u);
+        // fragment (kk, t, jt): ((kk*T1 + t)*QT + jt) * 512 elements, + lane * 8
+        const uint16_t* Rk = RF1 + ((size_t)kk * C::T1 * C::QT * 64 + lane) * 8;
+
+        f32x16 acc[C::QT * C::NB];
+#pragma unroll
+        for (int t = 0; t < C::QT * C::NB; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+
+        u32x4 rf[4][C::QT], xf[2][C::NB];
+        auto issue_r = [&](int t, int slot) {
+#pragma unroll
+            for (int jt = 0; jt < C::QT; ++jt) rf[slot][jt] = ldg128(Rk + (size_t)(t * C::QT + jt) * 512);
+        };
+        auto read_x = [&](int c64, int u, int slot) {
+            const uint16_t* buf = ring + (size_t)(c64 % C::XR) * 4096;
+#pragma unroll
+            for (int nb = 0; nb < C::NB; ++nb) xf[slot][nb] = lds128(buf + nb * 2048 + foff[u]);
+        };
+        // prologue: the first XR chunks of x, then the R fragments of K-steps 0..2
+#pragma unroll
+        for (int c = 0; c < C::XR; ++c) issue_x(c);
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+            if (t < C::T1) issue_r(t, t);
+        wait_vmcnt<C::W_FIRST>();
+        __builtin_amdgcn_sched_barrier(0);
+        read_x(0, 0, 0);
+
+        for (int c64 = 0; c64 < C::C1; ++c64) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int t = c64 * 4 + u;
+                __builtin_amdgcn_sched_barrier(0);
+                if (t + 3 < C::T1) issue_r(t + 3, (u + 3) & 3);
+                if (u < 3) {
+                    read_x(c64, u + 1, (u + 1) & 1);
+                } else if (c64 + 1 < C::C1) {
+                    // chunk c64+1 has landed once only operations issued after its DMAs are outstanding
+                    if (c64 == 0) wait_vmcnt<C::W_C0>();
+                    else if (c64 + 2 < C::C1) wait_vmcnt<C::W_MID>();
+                    else wait_vmcnt<C::W_LAST>();
+                    __builtin_amdgcn_sched_barrier(0);
+                    read_x(c64 + 1, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int jt = 0; jt < C::QT; ++jt)
+#pragma unroll
+                    for (int nb = 0; nb < C::NB; ++nb)
+                        acc[jt * C::NB + nb] = mfma32(as_bf16x8(rf[u][jt]), as_bf16x8(xf[u & 1][nb]), acc[jt * C::NB + nb]);
+                if (u == 3 && c64 + 3 < C::C1) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    wait_lgkmcnt0();  // the fragment reads of chunk c64 are done: its slot takes chunk c64+3
+                    issue_x(c64 + 3);
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        {
+            // the first stage-2 weights travel while the workgroup exchanges Y1 through LDS
+            const uint16_t* wbase[C::NLT];
+            stage2_wbase<C>(LF2, wave * C::UPW, lane, wbase);
+#pragma unroll
+            for (int d = 0; d < C::RW2 - 1; ++d) stage2_issue_w<C>(wbase, wr2, d / C::KS, d % C::KS, d);
+        }
+        __syncthreads();  // every wave is done with its x ring: the space becomes Y1s
+        // lane holds D^T[j][b] for b = nb*32 + ln and j = jt*32 + 8*(i/4) + 4*g + i%4
+#pragma unroll
+        for (int jt = 0; jt < C::QT; ++jt)
+#pragma unroll
+            for (int nb = 0; nb < C::NB; ++nb)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const f32x16& a = acc[jt * C::NB + nb];
+                    const int j = jt * 32 + 8 * i4 + 4 * g;  // four consecutive j: one 8-byte slot of block j/4
+                    *reinterpret_cast<u32x2*>(lds + (size_t)(nb * 32 + ln) * C::Y1_STRIDE + (j >> 2) * 16 + kk * 4) =
+                        u32x2{pack_bf16x2(a[4 * i4 + 0], a[4 * i4 + 1]), pack_bf16x2(a[4 * i4 + 2], a[4 * i4 + 3])};
+                }
+    }
+    __syncthreads();
+
+    // ------------------------------------------------------------- stage 2 ----
+    {
+        const int u0 = wave * C::UPW;
+        if (u0 & 1)
+            stage2_pass<C, true, true>(LF2, lds, y, b0, B, u0, lane, wr2);
+        else
+            stage2_pass<C, false, true>(LF2, lds, y, b0, B, u0, lane, wr2);
+    }
+    for (int ps = 1; ps < C::PASSES; ++ps) {
+        const int u0 = (ps * 4 + wave) * C::UPW;
+        if (u0 & 1)
+            stage2_pass<C, true, false>(LF2, lds, y, b0, B, u0, lane, wr2);
+        else
+            stage2_pass<C, false, false>(LF2, lds, y, b0, B, u0, lane, wr2);
+    }
+}
+
+template <typename C>
+int launch(const Problem& pb, const void* x, const uint16_t* RF1, const uint16_t* LF2, void* y, hipStream_t st)
+{
+    auto kern = fwd_frag_kernel<C>;
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
+    if (e != hipSuccess) return -4;
+    const int64_t grid = (pb.B + C::BM - 1) / C::BM;
+    if (grid > 0x7fffffffLL) return -2;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), C::LDS_BYTES, st, (const uint16_t*)x, RF1, LF2,
+                       (uint16_t*)y, pb.B);
+    return hip_status(hipGetLastError());
+}
+
+struct Entry {
+    int p, q, s;
+    int (*fn)(const Problem&, const void*, const uint16_t*, const uint16_t*, void*, hipStream_t);
+};
+
+//                                 P     Q     S  UPW RW2
+const Entry kTable[] = {
+    {192, 192, 192, launch<FwdFrag<192, 192, 192, 3, 6>>},    // ViT-B projection 768 -> 768
+    {192, 192, 768, launch<FwdFrag<192, 192, 768, 4, 6>>},    // GPT-2 small fc1 768 -> 3072
+    {256, 256, 1024, launch<FwdFrag<256, 256, 1024, 4, 8>>},  // GPT-2 medium fc1 1024 -> 4096
+    {1024, 256, 256, launch<FwdFrag<1024, 256, 256, 4, 8>>},  // GPT-2 medium fc2 4096 -> 1024
+    {768, 192, 192, launch<FwdFrag<768, 192, 192, 3, 6>>},    // GPT-2 small fc2 3072 -> 768
+    {64, 64, 64, launch<FwdFrag<64, 64, 64, 1, 4>>},          // small shapes (tests)
+    {64, 64, 128, launch<FwdFrag<64, 64, 128, 2, 4>>},
+    {128, 64, 64, launch<FwdFrag<128, 64, 64, 1, 4>>},
+};
+
+const Entry* find(const Problem& pb)
+{
+    if (pb.dtype != 1 || pb.k != 4 || pb.perm_b()) return nullptr;
+    for (const Entry& e : kTable)
+        if (e.p == pb.p && e.q == pb.q && e.s == pb.s) return &e;
+    return nullptr;
+}
+
+}  // namespace
+
+bool fwd_frag_supported(const Problem& pb) { return find(pb) != nullptr; }
+
+// packed R then packed L, each the size of its source
+size_t fwd_frag_workspace(const Problem& pb) { return align_up(pb.n_R() * 2, 256) + align_up(pb.n_L() * 2, 256); }
+
+int fwd_frag(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
+{
+    const Entry* e = find(pb);
+    if (!e) return -2;
+    uint16_t* RF1 = (uint16_t*)ws;
+    uint16_t* LF2 = (uint16_t*)((char*)ws + align_up(pb.n_R() * 2, 256));
+    const size_t pieces = (pb.n_R() + pb.n_L()) / 8;
+    hipLaunchKernelGGL(pack_fwd_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st,
+                       (const uint16_t*)R, (const uint16_t*)L, RF1, LF2, pb.p, pb.q, pb.s);
+    if (hipGetLastError() != hipSuccess) return -4;
+    return e->fn(pb, x, RF1, LF2, y, st);
+}
+
+}  // namespace monarch

@@ -10,8 +10,9 @@
 // writes and read back with the transposing LDS load of gfx950 (ds_read_b64_tr_b16), which
 // hands every lane four consecutive batch rows of one feature: exactly the MFMA operand layout.
 //
-// One workgroup = four groups g (one per wave), each wave a TM x TN tile of its group's
-// output; the batch is split into chunks whose fp32 partial tiles are summed by
+// One workgroup = four groups g, two waves per group (each takes every other 16-row K-step on its own
+// accumulators: two waves per SIMD hide each other's staging and LDS latencies), a TM x TN tile of
+// each group's output; the batch is split into chunks whose fp32 partial tiles are summed by
 // `wgrad_reduce_kernel`, which also undoes the column order used for dL and converts to the
 // output type.
 #include "monarch_internal.h"
@@ -23,7 +24,9 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-constexpr int KB = 32;  // batch rows per pipeline step
+constexpr int KB = 32;    // batch rows per pipeline step (two 16-row K-steps, one per wave of a group)
+constexpr int NTHR = 512;  // eight waves per workgroup
+constexpr int NSTG = 1;     // register stages of the operand loads (rows fetched NSTG steps before they are stored)
 
 // Transposing LDS read: within each 16 lanes, lane i receives element (i % 4) of lanes
 // i/4, 4 + i/4, 8 + i/4, 12 + i/4.
@@ -53,7 +56,10 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
     constexpr int BUF = 4 * KB * (SA + SB);  // one pipeline buffer: As [4][KB][SA], then Bs [4][KB][SB]
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
 
+    // eight waves: wave = (group g, K half kh); the two waves of a group each take one 16-row K-step of every
+    // 32-row pipeline step on their own accumulators, which are summed through LDS at the end
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int grp = wave & 3, kh = wave >> 2;
     const int tiles_n = d.N / TN;
     const int tiles_mn = (d.M / TM) * tiles_n;
     const int g0 = (tile / tiles_mn) * 4, tmn = tile % tiles_mn;
@@ -68,8 +74,8 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
     // offset per step), LDS offsets inside a buffer, and the row of the task inside a step.
     constexpr int A_TASKS = DEINT ? (KB * TM / 8) : (4 * KB * TM / 8);
     constexpr int B_TASKS = 4 * KB * TN / 8;
-    constexpr int A_PER = (A_TASKS + 255) / 256, B_PER = (B_TASKS + 255) / 256;
-    u32x4 areg[2][A_PER][DEINT ? 4 : 1], breg[2][B_PER];
+    constexpr int A_PER = (A_TASKS + NTHR - 1) / NTHR, B_PER = (B_TASKS + NTHR - 1) / NTHR;
+    u32x4 areg[NSTG][A_PER][DEINT ? 4 : 1], breg[NSTG][B_PER];
     const uint16_t* pa[A_PER];
     const uint16_t* pb[B_PER];
     int ra[A_PER], rb[B_PER], la[A_PER], lb[B_PER];
@@ -77,27 +83,27 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
     for (int t = 0; t < A_PER; ++t) {
         // a thread without a task in this slot repeats task 0 (its loads are unconditional and must
         // stay in bounds; it stores nothing)
-        const int task = tid + t * 256 < A_TASKS ? tid + t * 256 : 0;
+        const int task = tid + t * NTHR < A_TASKS ? tid + t * NTHR : 0;
         if (DEINT) {
             const int r = task / (TM / 8), u = task % (TM / 8);
-            ra[t] = tid + t * 256 < A_TASKS ? r : (1 << 30);
+            ra[t] = tid + t * NTHR < A_TASKS ? r : (1 << 30);
             pa[t] = d.A + (row_lo + r) * d.lda + (size_t)(m0 + 8 * u) * 4 + g0;
             la[t] = r * SA + 8 * u;
         } else {
             const int g = task / (KB * TM / 8), rem = task % (KB * TM / 8);
             const int r = rem / (TM / 8), u = rem % (TM / 8);
-            ra[t] = tid + t * 256 < A_TASKS ? r : (1 << 30);
+            ra[t] = tid + t * NTHR < A_TASKS ? r : (1 << 30);
             pa[t] = d.A + (row_lo + r) * d.lda + (size_t)(g0 + g) * d.a_g + m0 + 8 * u;
             la[t] = (g * KB + r) * SA + 8 * u;
         }
     }
 #pragma unroll
     for (int t = 0; t < B_PER; ++t) {
-        const int task = tid + t * 256 < B_TASKS ? tid + t * 256 : 0;
+        const int task = tid + t * NTHR < B_TASKS ? tid + t * NTHR : 0;
         const int g = task / (KB * TN / 8), rem = task % (KB * TN / 8);
         const int r = rem / (TN / 8), u = rem % (TN / 8);
         const int n = n0 + 8 * u;
-        rb[t] = tid + t * 256 < B_TASKS ? r : (1 << 30);
+        rb[t] = tid + t * NTHR < B_TASKS ? r : (1 << 30);
         pb[t] = d.Bm + (row_lo + r) * d.ldb + (size_t)(g0 + g) * d.b_g + (size_t)(n / d.seg_w) * d.b_seg + (n % d.seg_w);
         lb[t] = 4 * KB * SA + (g * KB + r) * SB + 8 * u;
     }
@@ -154,51 +160,69 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
-    // Pipeline (one workgroup barrier per 32-row step, two LDS buffers, two register stages):
+    // Pipeline (one workgroup barrier per 32-row step, two LDS buffers, one register stage):
     // in step s the MFMAs read buffer s%2 while the rows of step s+1 go from registers to buffer
-    // (s+1)%2 and the rows of step s+3 are fetched into the registers just freed.  The fragments of
-    // the second K-step are read before the MFMAs of the first, so that LDS latency hides behind them.
-    // The loop body has no branches (a step past the end of the chunk works on zeros): control flow
-    // here makes the compiler shuffle the accumulators between blocks.
+    // (s+1)%2 and the rows of step s+2 are fetched into the registers just freed.  A wave reads the
+    // fragments of its own K-step (rows 16*kh .. 16*kh+15 of the step) before the staging work, so that
+    // their LDS latency hides behind it.  The loop body has no branches (a step past the end of the
+    // chunk works on zeros): control flow here makes the compiler shuffle the accumulators between blocks.
     if (nrows > 0) {  // (uniform) an empty chunk touches no memory and yields a zero partial tile
     load_step(0, 0);
-    load_step(KB, 1);
     store_step(0, 0, lds);
-    load_step(2 * KB, 0);
-    const int woff_a = wave * KB * SA, woff_b = 4 * KB * SA + wave * KB * SB;
+    load_step(KB, 0);
+    const int woff_a = grp * KB * SA, woff_b = 4 * KB * SA + grp * KB * SB;
     for (int64_t r0 = 0; r0 < nrows; r0 += 2 * KB) {
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
             const uint16_t* cur = lds + k * BUF;
             uint16_t* nxt = lds + (k ^ 1) * BUF;
             __syncthreads();
-            bf16x8 af[2][MT], bfr[2][NT];
+            bf16x8 af[MT], bfr[NT];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) af[0][mt] = frag_tr(cur + woff_a, SA, 0, mt * 32, lane);
+            for (int mt = 0; mt < MT; ++mt) af[mt] = frag_tr(cur + woff_a, SA, 16 * kh, mt * 32, lane);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) bfr[0][nt] = frag_tr(cur + woff_b, SB, 0, nt * 32, lane);
+            for (int nt = 0; nt < NT; ++nt) bfr[nt] = frag_tr(cur + woff_b, SB, 16 * kh, nt * 32, lane);
             __builtin_amdgcn_sched_barrier(0);
-            store_step(r0 + (k + 1) * KB, k ^ 1, nxt);
-            load_step(r0 + (k + 3) * KB, k ^ 1);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) af[1][mt] = frag_tr(cur + woff_a, SA, 16, mt * 32, lane);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) bfr[1][nt] = frag_tr(cur + woff_b, SB, 16, nt * 32, lane);
+            store_step(r0 + (k + 1) * KB, 0, nxt);
+            load_step(r0 + (k + 2) * KB, 0);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) acc[mt * NT + nt] = mfma32(af[ks][mt], bfr[ks][nt], acc[mt * NT + nt]);
+                for (int nt = 0; nt < NT; ++nt) acc[mt * NT + nt] = mfma32(af[mt], bfr[nt], acc[mt * NT + nt]);
         }
     }
     }
 
+    // sum the two K halves of every group through LDS (fp32, in two rounds of at most R1 tiles per
+    // wave: the staging buffers hold 4 x R1 tiles), then the kh = 0 wave owns the group's partial tile
+    {
+        constexpr int NTILE = MT * NT, R1 = (NTILE + 1) / 2;
+        static_assert((size_t)4 * R1 * 4096 <= (size_t)2 * BUF * 2, "reduction staging fits the pipeline buffers");
+        float* red = reinterpret_cast<float*>(lds) + (size_t)grp * R1 * 1024 + lane;
+#pragma unroll
+        for (int t0 = 0; t0 < NTILE; t0 += R1) {
+            __syncthreads();  // the buffers (or the previous round) are no longer read
+            if (kh == 1) {
+#pragma unroll
+                for (int t = t0; t < t0 + R1 && t < NTILE; ++t)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) red[(t - t0) * 1024 + i * 64] = acc[t][i];
+            }
+            __syncthreads();
+            if (kh == 0) {
+#pragma unroll
+                for (int t = t0; t < t0 + R1 && t < NTILE; ++t)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[t][i] += red[(t - t0) * 1024 + i * 64];
+            }
+        }
+    }
+    if (kh != 0) return;
+
     // partial tile: P[z][g][m][n]
     const int ln = lane & 31, h = lane >> 5;
-    float* Pg = d.P + (((size_t)zi * d.G + g0 + wave) * d.M) * d.N;
+    float* Pg = d.P + (((size_t)zi * d.G + g0 + grp) * d.M) * d.N;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -215,7 +239,7 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
 // range of (chunk, tile) pairs with the tile index fastest: the tiles that re-read the same
 // operand rows then run on one XCD at about the same time and share its L2.
 template <int TM, int TN>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(NTHR)
 wgrad_gemm_kernel(WgradDesc d0, WgradDesc d1, int tiles0, int tiles)
 {
     const int nwg = gridDim.x, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -276,7 +300,7 @@ int launch_gemm(const WgradDesc& d0, const WgradDesc* d1, int nz, hipStream_t st
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return -4;
     const int t0 = tiles_of(d0, TM, TN), t1 = d1 ? tiles_of(*d1, TM, TN) : 0;
-    hipLaunchKernelGGL(kern, dim3((t0 + t1) * nz), dim3(256), lds, st, d0, d1 ? *d1 : d0, t0, t0 + t1);
+    hipLaunchKernelGGL(kern, dim3((t0 + t1) * nz), dim3(NTHR), lds, st, d0, d1 ? *d1 : d0, t0, t0 + t1);
     return hip_status(hipGetLastError());
 }
 

@@ -45,10 +45,20 @@ def host(t):
     return t.float().cpu().numpy().astype(np.float64)
 
 
-def run_fwd(B, sh, x, R, L, flags=0):
+def run_fwd(B, sh, x, R, L, flags=0, ws=False):
+    """monarch_fwd / monarch_fwd_ex, or (ws=True) monarch_fwd_ws with a guarded workspace."""
     ybuf, y = guarded((x.shape[0], sh.n_out), tdtype(sh.dtype))
-    B.monarch_fwd(dev(x, sh.dtype), dev(R, sh.dtype), dev(L, sh.dtype), y, flags=flags)
-    torch.cuda.synchronize()
+    if ws:
+        code = 0 if sh.dtype == "f32" else 1
+        need = B.monarch_fwd_workspace_bytes(x.shape[0], sh.n_in, sh.k, sh.q, sh.s, code, flags)
+        wbuf = torch.full((need + 512 + 2 * GUARD,), 0x5A, dtype=torch.uint8, device="cuda")
+        off = (-(wbuf.data_ptr() + GUARD)) % 256 + GUARD  # 256-byte aligned start inside the canary
+        B.monarch_fwd_ws(dev(x, sh.dtype), dev(R, sh.dtype), dev(L, sh.dtype), y, workspace=wbuf[off:off + need], flags=flags)
+        torch.cuda.synchronize()
+        assert bool((wbuf[:off] == 0x5A).all()) and bool((wbuf[off + need:] == 0x5A).all()), "workspace: wrote out of bounds"
+    else:
+        B.monarch_fwd(dev(x, sh.dtype), dev(R, sh.dtype), dev(L, sh.dtype), y, flags=flags)
+        torch.cuda.synchronize()
     check_guard(ybuf, "y")
     out = host(y)
     assert np.isfinite(out).all(), "y has unwritten or non-finite entries"
@@ -116,6 +126,8 @@ def test_small_shapes_fwd_bwd(B, case, generic):
     x, R, L, dy = synth.make_inputs(sh)
     y = run_fwd(B, sh, x, R, L, flags)
     compare(sh, [y], [oracle.fwd(x, R, L)], ["y"])
+    yw = run_fwd(B, sh, x, R, L, flags, ws=True)
+    compare(sh, [yw], [oracle.fwd(x, R, L)], ["y_ws"])
     got = run_bwd(B, sh, dy, x, R, L, flags)
     compare(sh, got, oracle.bwd(dy, x, R, L), ["dx", "dR", "dL"])
     got32 = run_bwd(B, sh, dy, x, R, L, flags | B.MONARCH_FLAG_WGRAD_F32)
@@ -186,7 +198,10 @@ def test_full_size_workloads(B, name):
     print("\n  kernels: %s / %s" % (B.monarch_kernel_name(0, sh.n_in, sh.k, sh.q, sh.s, code),
                                     B.monarch_kernel_name(1, sh.n_in, sh.k, sh.q, sh.s, code)), flush=True)
     y = run_fwd(B, sh, x, R, L)
-    compare(sh, [y], [oracle.fwd(x, R, L)], ["y"])
+    yo = oracle.fwd(x, R, L)
+    compare(sh, [y], [yo], ["y"])
+    print("  forward with workspace: %s" % B.monarch_kernel_name(2, sh.n_in, sh.k, sh.q, sh.s, code), flush=True)
+    compare(sh, [run_fwd(B, sh, x, R, L, ws=True)], [yo], ["y_ws"])
     got = run_bwd(B, sh, dy, x, R, L)
     want = oracle.bwd(dy, x, R, L)
     compare(sh, got, want, ["dx", "dR", "dL"])

@@ -69,6 +69,31 @@ def test_forward_rejects_bad_arguments_without_a_gpu(binding):
     assert L.monarch_fwd(ok_ptr, ok_ptr, ok_ptr, ok_ptr, 0, 768, 4, 192, 192, 1, None) == binding.MONARCH_OK
 
 
+def test_forward_with_workspace_rejects_bad_arguments_without_a_gpu(binding):
+    L = binding.lib()
+    p = 4096  # never dereferenced
+    need = binding.monarch_fwd_workspace_bytes(0, 768, 4, 192, 192, 1)
+    assert need == 2 * 2 * 4 * 192 * 192                       # packed copies of R and L
+    assert binding.monarch_fwd_workspace_bytes(0, 6, 2, 4, 2, 0) == 0        # shape without a packed-weight kernel
+    assert binding.monarch_fwd_workspace_bytes(0, 768, 4, 192, 192, 1, binding.MONARCH_FLAG_GENERIC) == 0
+    assert binding.monarch_fwd_workspace_bytes(0, 770, 4, 192, 192, 1) == 0  # invalid arguments
+
+    def call(x=p, R=p, Lp=p, y=p, ws=p, ws_bytes=need, flags=0, batch=0, n_in=768, k=4, q=192, s=192, dtype=1):
+        return L.monarch_fwd_ws(x, R, Lp, y, batch, n_in, k, q, s, dtype, None, ws, ws_bytes, flags)
+
+    assert call() == binding.MONARCH_OK
+    assert call(ws=None) == binding.MONARCH_ERR_WORKSPACE
+    assert call(ws_bytes=need - 1) == binding.MONARCH_ERR_WORKSPACE
+    assert call(ws=p + 16) == binding.MONARCH_ERR_WORKSPACE     # not 256-byte aligned
+    assert call(R=None) == binding.MONARCH_ERR_INVALID
+    assert call(x=None, batch=1) == binding.MONARCH_ERR_INVALID
+    assert call(n_in=770) == binding.MONARCH_ERR_INVALID
+    assert call(flags=binding.MONARCH_FLAG_WGRAD_F32) == binding.MONARCH_ERR_INVALID
+    # shapes without a packed-weight kernel behave as monarch_fwd_ex and need no workspace
+    assert call(ws=None, ws_bytes=0, n_in=6, k=2, q=4, s=2, dtype=0) == binding.MONARCH_OK
+    assert call(ws=None, ws_bytes=0, flags=binding.MONARCH_FLAG_GENERIC) == binding.MONARCH_OK
+
+
 def test_backward_rejects_bad_arguments_without_a_gpu(binding):
     L = binding.lib()
     p = 4096
@@ -102,7 +127,9 @@ def test_stream_copy_rejects_bad_arguments_without_a_gpu(binding):
 
 def test_kernel_name_reports_dispatch(binding):
     assert binding.monarch_kernel_name(0, 770, 4, 192, 192, 1) == "invalid"
-    assert binding.monarch_kernel_name(2, 768, 4, 192, 192, 1) == "invalid"
+    assert binding.monarch_kernel_name(3, 768, 4, 192, 192, 1) == "invalid"
+    assert binding.monarch_kernel_name(2, 768, 4, 192, 192, 1) == "mfma_fwd_frag_bf16"
+    assert binding.monarch_kernel_name(2, 6, 2, 4, 2, 0) == "generic_fwd"   # no packed-weight kernel: same as pass 0
     assert binding.monarch_kernel_name(0, 6, 2, 4, 2, 0) == "generic_fwd"
     assert binding.monarch_kernel_name(1, 6, 2, 4, 2, 0) == "generic_bwd"
     assert binding.monarch_kernel_name(0, 768, 4, 192, 192, 1, binding.MONARCH_FLAG_GENERIC) == "generic_fwd"
