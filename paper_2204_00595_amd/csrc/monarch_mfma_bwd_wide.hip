@@ -6,7 +6,8 @@
 //             L is transposed with its rows picked in the order the mid permutation scatters them,
 //             R is transposed with its K-slots in the order the chained accumulators of `data` hold dY1.
 //   data      one workgroup per 64 batch rows, wave w <-> R block kk = w:
-//               X) recompute step 1, Y1[b][kk][j], and write it to the workspace (dL needs U);
+//               X) recompute step 1, Y1[b][kk][j] (x through a DMA-filled LDS ring, packed R fragments
+//                  straight into registers), and write it to the workspace (dL needs U);
 //               A) dY1[b][kk][c*Q/4 + r1] = sum_l dy[b][4*l + c] * L[c][l][4*r1 + kk]
 //                  (adjoint of steps 3 + 2 + P^T in one contraction; dy is de-interleaved into
 //                  LDS once per workgroup, the result stays in accumulators);
@@ -17,6 +18,7 @@
 //             (monarch_mfma_wgrad.hip), split over the batch, then one reduction pass.
 #include "monarch_internal.h"
 #include "monarch_mfma_common.h"
+#include "monarch_mfma_stage1.h"
 
 namespace monarch {
 
@@ -28,9 +30,8 @@ namespace {
 // lanes' 16-byte operand pieces are stored back to back, so that a fragment load in the data kernel
 // is one contiguous, fully coalesced 1 KiB read (eight cache lines) instead of 32 or 64 lines.
 // One thread builds one 16-byte piece (eight gathered elements).  Three arrays:
-//   XF[kk][jg][t][jj][lane][e]   = R[kk][32*(jg*JG + jj) + lane%32][64*(t/4) + 32*(lane/32) + 8*(t%4) + e]
-//       (step-1 recompute, 32x32x16; K-step t of lane group g covers 8 columns so that a lane's four
-//        steps of x are 64 contiguous bytes)
+//   XF[kk][t][jt][lane][e]      = R[kk][32*jt + lane%32][16*t + 8*(lane/32) + e]
+//       (step-1 recompute, 32x32x16: the layout stage1_block streams)
 //   LF[kk][c][kt][jt][lane][e]   = L[c][32*kt + 8*(lane/16) + e][4*(16*jt + lane%16) + kk]
 //       (dY1 stage, 16x16x32: L transposed, rows picked as the mid permutation scatters them)
 //   RF[kk][ig][u][it][lane][e]   = R[kk][32*u + 16*(e/4) + 4*(lane/16) + e%4][16*(ig*IG + it) + lane%16]
@@ -46,12 +47,10 @@ prep_frag_kernel(const uint16_t* __restrict__ L, const uint16_t* __restrict__ R,
     if (pc < nR) {
         const int lane = pc & 63;
         int rest = pc >> 6;
-        const int jj = rest % JG; rest /= JG;
-        const int T = P / 16;
-        const int t = rest % T; rest /= T;
-        const int njg = Q / 32 / JG;
-        const int jg = rest % njg, kk = rest / njg;
-        const uint16_t* src = R + ((size_t)kk * Q + 32 * (jg * JG + jj) + (lane & 31)) * P + 64 * (t >> 2) + 32 * (lane >> 5) + 8 * (t & 3);
+        const int QT = Q / 32, T = P / 16;
+        const int jt = rest % QT; rest /= QT;
+        const int t = rest % T, kk = rest / T;
+        const uint16_t* src = R + ((size_t)kk * Q + 32 * jt + (lane & 31)) * P + 16 * t + 8 * (lane >> 5);
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = src[e];
         dst = XF + (size_t)pc * 8;
@@ -107,7 +106,9 @@ struct BwdWide {
     static constexpr size_t LDS_Y1 = (size_t)BM * Y1_STRIDE * 2;
     static constexpr size_t LDS_DW = (size_t)K * BM * DW_STRIDE * 2;
     static constexpr size_t LDS_DX = (size_t)4 * BM * DX_STRIDE * 2;
-    static constexpr size_t LDS_BYTES = LDS_Y1 > LDS_DW ? (LDS_Y1 > LDS_DX ? LDS_Y1 : LDS_DX) : (LDS_DW > LDS_DX ? LDS_DW : LDS_DX);
+    using S1 = Stage1<P_, Q_>;               // step-1 recompute (x through an LDS ring, packed R fragments)
+    static constexpr size_t max2(size_t a, size_t b) { return a > b ? a : b; }
+    static constexpr size_t LDS_BYTES = max2(max2(LDS_Y1, LDS_DW), max2(LDS_DX, S1::LDS_X));
     static_assert(P % 64 == 0 && Q % 32 == 0 && S % 32 == 0 && QK % 16 == 0, "tile shapes");
     static_assert(QT % JG == 0 && S % LC == 0 && LC % 32 == 0 && (P / 16) % IG == 0, "loop splits");
     static_assert(DX_COLS % 8 == 0 && (64 % (DX_COLS / 8) == 0), "dx staging copy-out");
@@ -185,71 +186,22 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
     // ------------------------------------------------- X: recompute step 1 -> workspace ----
     {
         const int ln = lane & 31, g = lane >> 5;
-        const uint16_t* xrow[C::NB];
+        f32x16 acc[C::QT * C::NB];
+        stage1_block<typename C::S1>(x, XF, b0, B, kk, lane, lds + (size_t)wave * C::S1::XR * 4096, acc);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();  // every wave is done with its x ring: the space becomes the Y1 tile
+        // lane holds D^T[j][b] for b = nb*32 + ln and j = jt*32 + 8*(i/4) + 4*g + i%4
 #pragma unroll
-        for (int nb = 0; nb < C::NB; ++nb) {
-            int64_t row = b0 + nb * 32 + ln;
-            row = row < B ? row : B - 1;
-            xrow[nb] = x + row * C::N_IN + kk * C::P + 32 * g;
-        }
-        // rings of K-steps: NS for the weight fragments (L2 latency), NSX for x (HBM latency)
-        constexpr int T = C::P / 16, NS = 4;
-        constexpr int NSX = (T == 12) ? 12 : ((T % 8 == 0) ? 8 : 4);
-        static_assert(T % NS == 0 && T % NSX == 0 && NSX % NS == 0, "ring");
-        // fragment (jg, t, jj) of XF; K-step t of lane group g covers columns 64*(t/4) + 32*g + 8*(t%4) ..
-        const uint16_t* Xk = XF + ((size_t)kk * (C::QT / C::JG) * T * C::JG * 64 + lane) * 8;
-        auto xcol = [](int t) { return 64 * (t >> 2) + 8 * (t & 3); };
-        for (int jg = 0; jg < C::QT / C::JG; ++jg) {
-            f32x16 acc[C::JG * C::NB];
+        for (int jt = 0; jt < C::QT; ++jt)
 #pragma unroll
-            for (int t = 0; t < C::JG * C::NB; ++t)
+            for (int nb = 0; nb < C::NB; ++nb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
-            const uint16_t* Rg = Xk + (size_t)jg * T * C::JG * 512;
-            // operands run through a ring of NS K-steps so that NS - 1 steps of loads are in flight
-            // (one step of MFMAs is shorter than the L2 latency)
-            u32x4 xf[NSX][C::NB], rf[NS][C::JG];
-            auto issue_x = [&](int t, int slot) {
-#pragma unroll
-                for (int nb = 0; nb < C::NB; ++nb) xf[slot][nb] = ldg128(xrow[nb] + xcol(t));
-            };
-            auto issue_r = [&](int t, int slot) {
-#pragma unroll
-                for (int jj = 0; jj < C::JG; ++jj) rf[slot][jj] = ldg128(Rg + (size_t)(t * C::JG + jj) * 512);
-            };
-            // weights first: they come from L2 and the in-order load counter must not hold them behind x
-#pragma unroll
-            for (int d = 0; d < NS - 1; ++d) issue_r(d, d);
-#pragma unroll
-            for (int d = 0; d < NSX - 1; ++d) issue_x(d, d);
-            for (int t0 = 0; t0 < T; t0 += NSX) {
-#pragma unroll
-                for (int k4 = 0; k4 < NSX; ++k4) {
-                    const int t = t0 + k4;
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (t + NS - 1 < T) issue_r(t + NS - 1, (k4 + NS - 1) % NS);
-                    if (t + NSX - 1 < T) issue_x(t + NSX - 1, (k4 + NSX - 1) % NSX);
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int jj = 0; jj < C::JG; ++jj)
-#pragma unroll
-                        for (int nb = 0; nb < C::NB; ++nb)
-                            acc[jj * C::NB + nb] =
-                                mfma32(as_bf16x8(rf[k4 % NS][jj]), as_bf16x8(xf[k4][nb]), acc[jj * C::NB + nb]);
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const f32x16& a = acc[jt * C::NB + nb];
+                    u32x2 v = {pack_bf16x2(a[4 * i4 + 0], a[4 * i4 + 1]), pack_bf16x2(a[4 * i4 + 2], a[4 * i4 + 3])};
+                    const int j = jt * 32 + 8 * i4 + 4 * g;
+                    *reinterpret_cast<u32x2*>(lds + (size_t)(nb * 32 + ln) * C::Y1_STRIDE + kk * C::Q + j) = v;
                 }
-            }
-#pragma unroll
-            for (int jj = 0; jj < C::JG; ++jj)
-#pragma unroll
-                for (int nb = 0; nb < C::NB; ++nb)
-#pragma unroll
-                    for (int i4 = 0; i4 < 4; ++i4) {
-                        const f32x16& a = acc[jj * C::NB + nb];
-                        u32x2 v = {pack_bf16x2(a[4 * i4 + 0], a[4 * i4 + 1]), pack_bf16x2(a[4 * i4 + 2], a[4 * i4 + 3])};
-                        const int j = (jg * C::JG + jj) * 32 + 8 * i4 + 4 * g;
-                        *reinterpret_cast<u32x2*>(lds + (size_t)(nb * 32 + ln) * C::Y1_STRIDE + kk * C::Q + j) = v;
-                    }
-        }
         load_dy(0);  // in flight during the copy-out below
         __syncthreads();
         copy_out_tile<C::KQ, 256, false>(lds, C::Y1_STRIDE, Y1ws, C::KQ, b0, B, tid);
