@@ -124,6 +124,14 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True):
         xs, dys, _, dx = sets[i % nsets]
         binding.monarch_bwd(dys, xs, Rd, Ld, dx, dR, dL, workspace=ws)
 
+    fneed = binding.monarch_fwd_workspace_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, code, 0)
+    fws = torch.empty(max(fneed, 256), dtype=torch.uint8, device=dev)
+
+    def fwd_ws_only(i):
+        xs, _, y, _ = sets[i % nsets]
+        binding.monarch_fwd_ws(xs, Rd, Ld, y, workspace=fws)
+
+    fwd_ws_ms = float(np.mean([run_of(fwd_ws_only) for _ in range(3)])) if fneed else None
     fwd_runs = [run_of(fwd_only) for _ in range(3)]
     bwd_runs = [run_of(bwd_only) for _ in range(3)]
     fwd_ms, bwd_ms = float(np.mean(fwd_runs)), float(np.mean(bwd_runs))
@@ -139,6 +147,8 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True):
         "workload": name, "ms_per_step": wall / steps * 1e3,
         "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "fwd_ms_min": fwd_min, "bwd_ms_min": bwd_min,
         "fwd_ms_evented": fwd_ev, "bwd_ms_evented": bwd_ev,
+        # monarch_fwd_ws (weights packed into a caller workspace, pack included); null when the shape has no such kernel
+        "fwd_ws_ms": fwd_ws_ms, "fwd_ws_kernel": binding.monarch_kernel_name(2, sh.n_in, sh.k, sh.q, sh.s, code),
         "fwd_kernel": binding.monarch_kernel_name(0, sh.n_in, sh.k, sh.q, sh.s, code),
         "bwd_kernel": binding.monarch_kernel_name(1, sh.n_in, sh.k, sh.q, sh.s, code),
         "fwd_tflops": sh.fwd_flops() / (fwd_ms * 1e-3) / 1e12,

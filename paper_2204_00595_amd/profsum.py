@@ -7,7 +7,8 @@
 `traffic` scales the FETCH_SIZE / WRITE_SIZE readings (KiB per dispatch) by what the same counter
 shows for the library's plain copy kernel (stream_copy_kernel, N bytes read and N bytes written per
 dispatch), and reports HBM bytes per launch for every kernel of the library, plus the totals per
-C-ABI call (monarch_fwd = the forward kernel, monarch_bwd = every other kernel of the library).
+C-ABI call (monarch_fwd = the forward kernel, monarch_fwd_ws = the pack kernel + the packed-weight
+forward, monarch_bwd = every other kernel of the library).
 """
 from __future__ import annotations
 
@@ -64,7 +65,7 @@ def cmd_traffic(args):
     print("calibration: %s moves %.0f KiB each way; FETCH_SIZE reads %.0f (factor %.3f), WRITE_SIZE reads %.0f (factor %.3f)"
           % (COPY_KERNEL, kib, fetch[COPY_KERNEL], f_scale, write[COPY_KERNEL], w_scale))
     print("%-60s %6s %14s %14s" % ("kernel", "calls", "fetch_MB", "write_MB"))
-    calls = {"monarch_fwd": [0.0, 0.0], "monarch_bwd": [0.0, 0.0]}
+    calls = {"monarch_fwd": [0.0, 0.0], "monarch_fwd_ws": [0.0, 0.0], "monarch_bwd": [0.0, 0.0]}
     per_kernel = {}
     for k in sorted(fetch):
         if k == COPY_KERNEL or not any(t in k for t in ("fwd_", "bwd_", "wgrad_", "prep_", "transpose64", "reduce_sq16", "generic_", "fill_zero", "f32_to_bf16")):
@@ -72,7 +73,12 @@ def cmd_traffic(args):
         fb, wb = fetch[k] * f_scale * 1024.0, write.get(k, 0.0) * w_scale * 1024.0
         per_kernel[k] = {"fetch_bytes": fb, "write_bytes": wb}
         print("%-60s %6d %14.2f %14.2f" % (k[:60], nf[k], fb / 1e6, wb / 1e6))
-        call = "monarch_fwd" if k.startswith("fwd_") or k.startswith("generic_fwd") else "monarch_bwd"
+        if k.startswith("fwd_frag") or k.startswith("pack_fwd"):
+            call = "monarch_fwd_ws"
+        elif k.startswith("fwd_") or k.startswith("generic_fwd"):
+            call = "monarch_fwd"
+        else:
+            call = "monarch_bwd"
         calls[call][0] += fb
         calls[call][1] += wb
     for c, (fb, wb) in calls.items():
