@@ -108,6 +108,8 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True):
     # one entry point (same rotation), so that the events themselves sit outside the timed launches;
     # a single step with an event after every call is kept as the "evented" figure
     def run_of(fn):
+        for i in range(3):  # untimed: first launches of a kernel pay for loading it
+            fn(i)
         e0, e1 = _events(2)
         e0.record()
         for i in range(steps):
