@@ -186,6 +186,22 @@ def test_backward_identities_on_gpu_outputs(B):
         assert abs(v - ref) < 1e-4 * abs(ref)
 
 
+@pytest.mark.parametrize("case", [("k4_192", "bf16", 1000, 4, 192, 192, 192), ("k4_fc1", "bf16", 700, 4, 64, 64, 128),
+                                  ("sq_m64", "bf16", 300, 64, 64, 64, 64), ("sq_m16", "f32", 5000, 16, 16, 16, 16)],
+                         ids=lambda c: c[0])
+def test_matrix_core_backward_is_bit_reproducible(B, case):
+    """The matrix-core backward sums its per-chunk partial gradients in a fixed order: two calls on the
+    same inputs must agree bit for bit (dx, dR and dL), and so must two forward calls."""
+    sh = small_shape(case)
+    x, R, L, dy = synth.make_inputs(sh)
+    a = run_bwd(B, sh, dy, x, R, L)
+    b = run_bwd(B, sh, dy, x, R, L)
+    for u, v, name in zip(a, b, ("dx", "dR", "dL")):
+        assert np.array_equal(u, v), name
+    assert np.array_equal(run_fwd(B, sh, x, R, L), run_fwd(B, sh, x, R, L))
+    assert np.array_equal(run_fwd(B, sh, x, R, L, ws=True), run_fwd(B, sh, x, R, L, ws=True))
+
+
 FULL = ["sq256_f32", "vitb_proj", "gpt2s_fc1", "sq4096", "gpt2m_fc1", "gpt2m_fc2"]
 
 
