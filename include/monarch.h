@@ -87,8 +87,8 @@ int monarch_fwd_ex(const void* x, const void* R, const void* L, void* y,
                    monarch_dtype dtype, void* stream, unsigned flags);
 
 /* Forward with scratch memory (same operation, same arguments and result as monarch_fwd_ex;
- * Section 3.3 steps 1-3).  For the shapes that have a packed-weight kernel (bf16, k = 4 wide
- * blocks) the call first re-lays R and L in matrix-core fragment order into `workspace` and then
+ * Section 3.3 steps 1-3).  For the shapes that have a packed-weight kernel (bf16: k = 4 wide
+ * blocks, and the square m = 64 case) the call first re-lays R and L in matrix-core fragment order into `workspace` and then
  * runs the fused forward on the packed copies, which removes the weights from the LDS traffic of
  * the kernel; every other shape runs exactly as monarch_fwd_ex and ignores the workspace.
  * `workspace` (device memory, 256-byte aligned, caller-owned) must hold at least

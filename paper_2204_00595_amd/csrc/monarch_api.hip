@@ -79,8 +79,8 @@ size_t monarch_fwd_workspace_bytes(int64_t batch, int n_in, int k, int q, int s,
 {
     Problem pb;
     if (make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags)) return 0;
-    if ((flags & MONARCH_FLAG_GENERIC) || !fwd_frag_supported(pb)) return 0;
-    return fwd_frag_workspace(pb);
+    if ((flags & MONARCH_FLAG_GENERIC) || !mfma_fwd_ws_supported(pb)) return 0;
+    return mfma_fwd_ws_workspace(pb);
 }
 
 int monarch_fwd_ws(const void* x, const void* R, const void* L, void* y, int64_t batch, int n_in, int k,
@@ -90,15 +90,15 @@ int monarch_fwd_ws(const void* x, const void* R, const void* L, void* y, int64_t
     Problem pb;
     int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
     if (rc) return rc;
-    if ((flags & MONARCH_FLAG_GENERIC) || !fwd_frag_supported(pb))
+    if ((flags & MONARCH_FLAG_GENERIC) || !mfma_fwd_ws_supported(pb))
         return monarch_fwd_ex(x, R, L, y, batch, n_in, k, q, s, dtype, stream, flags);
     if (flags & MONARCH_FLAG_WGRAD_F32) return MONARCH_ERR_INVALID;  // backward-only flag
     if (!R || !L || ((!x || !y) && batch > 0)) return MONARCH_ERR_INVALID;
     if (!aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(y, 16)) return MONARCH_ERR_INVALID;
-    if (!workspace || workspace_bytes < fwd_frag_workspace(pb) || !aligned(workspace, 256))
+    if (!workspace || workspace_bytes < mfma_fwd_ws_workspace(pb) || !aligned(workspace, 256))
         return MONARCH_ERR_WORKSPACE;
     if (batch == 0) return MONARCH_OK;
-    return fwd_frag(pb, x, R, L, y, workspace, (hipStream_t)stream);
+    return mfma_fwd_ws(pb, x, R, L, y, workspace, (hipStream_t)stream);
 }
 
 size_t monarch_bwd_workspace_bytes(int64_t batch, int n_in, int k, int q, int s, monarch_dtype dtype,
@@ -141,7 +141,7 @@ const char* monarch_kernel_name(int pass, int n_in, int k, int q, int s, monarch
     if (rc == MONARCH_ERR_UNSUPPORTED) return "unsupported";
     if (rc || pass < 0 || pass > 2) return "invalid";
     const Family fam = pass != 1 ? pick_fwd(pb) : pick_bwd(pb);
-    if (pass == 2) return (!(flags & MONARCH_FLAG_GENERIC) && fwd_frag_supported(pb)) ? "mfma_fwd_frag_bf16" : monarch_kernel_name(0, n_in, k, q, s, dtype, flags);
+    if (pass == 2) return (!(flags & MONARCH_FLAG_GENERIC) && mfma_fwd_ws_supported(pb)) ? mfma_fwd_ws_name(pb) : monarch_kernel_name(0, n_in, k, q, s, dtype, flags);
     if (fam == FAM_GENERIC) return pass == 0 ? "generic_fwd" : "generic_bwd";
     if (fam == FAM_MFMA) return pass == 0 ? mfma_fwd_name(pb) : mfma_bwd_name(pb);
     return "unsupported";

@@ -40,6 +40,11 @@ size_t mfma_bwd_workspace(const Problem& pb);
 const char* mfma_fwd_name(const Problem& pb);
 const char* mfma_bwd_name(const Problem& pb);
 int mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
+// forward with a caller workspace (packed weights): shapes that have such a kernel
+bool mfma_fwd_ws_supported(const Problem& pb);
+size_t mfma_fwd_ws_workspace(const Problem& pb);
+const char* mfma_fwd_ws_name(const Problem& pb);
+int mfma_fwd_ws(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);
 int mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L,
              void* dx, void* dR, void* dL, void* ws, hipStream_t st);
 
@@ -62,6 +67,8 @@ int bwd_wide(const Problem& pb, const void* dy, const void* x, const void* R, co
 // bf16, square m = 64 (k = q = s = p = 64): fused forward and backward (monarch_mfma_sq64.hip)
 bool sq64_supported(const Problem& pb);
 int fwd_sq64(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
+size_t fwd_sq64_workspace(const Problem& pb);  // forward on factors packed in fragment order
+int fwd_sq64_ws(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);
 bool bwd_sq64_supported(const Problem& pb);
 size_t bwd_sq64_workspace(const Problem& pb);
 int bwd_sq64(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx,

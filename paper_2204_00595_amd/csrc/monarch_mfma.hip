@@ -19,6 +19,26 @@ int mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, voi
     return -2;
 }
 
+bool mfma_fwd_ws_supported(const Problem& pb) { return fwd_frag_supported(pb) || sq64_supported(pb); }
+size_t mfma_fwd_ws_workspace(const Problem& pb)
+{
+    if (fwd_frag_supported(pb)) return fwd_frag_workspace(pb);
+    if (sq64_supported(pb)) return fwd_sq64_workspace(pb);
+    return 0;
+}
+const char* mfma_fwd_ws_name(const Problem& pb)
+{
+    if (fwd_frag_supported(pb)) return "mfma_fwd_frag_bf16";
+    if (sq64_supported(pb)) return "mfma_fwd_sq64_packed_bf16";
+    return "unsupported";
+}
+int mfma_fwd_ws(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
+{
+    if (fwd_frag_supported(pb)) return fwd_frag(pb, x, R, L, y, ws, st);
+    if (sq64_supported(pb)) return fwd_sq64_ws(pb, x, R, L, y, ws, st);
+    return -2;
+}
+
 bool mfma_bwd_supported(const Problem& pb) { return bwd_wide_supported(pb) || bwd_sq64_supported(pb) || sq16_supported(pb); }
 size_t mfma_bwd_workspace(const Problem& pb)
 {

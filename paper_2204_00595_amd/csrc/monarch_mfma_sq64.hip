@@ -53,12 +53,16 @@ struct Lane {
 // Results: bf16 pairs (block even, block odd) of T[b = ln][block][col], col = 32*jt + 8*(i/4) + 4*g + i%4.
 // The half col < 32 goes to the exchange buffer as it is produced (LDS must be idle), the half
 // col >= 32 is returned in pk1[t2][i].
+// PACKED: W is the factor in fragment order (pack64_kernel): a weight operand is then one contiguous
+// 1 KiB read per wave instruction instead of 32 lines touched twice.
+template <bool PACKED>
 __device__ __forceinline__ void block_stage(const Lane& t_, const uint16_t* __restrict__ act_row,
                                             const uint16_t* __restrict__ W, unsigned char* ldsb, uint32_t (&pk1)[4][16])
 {
     const int wave = t_.wave, ln = t_.ln, g = t_.g;
     const uint16_t* arow = act_row + (size_t)wave * 8 * M64;
-    const uint16_t* Wrow = W + ((size_t)wave * 8 * M64 + ln) * M64 + 32 * g;
+    const uint16_t* Wrow = PACKED ? W + ((size_t)wave * 8 * 8 * 64 + t_.lane) * 8
+                                  : W + ((size_t)wave * 8 * M64 + ln) * M64 + 32 * g;
     u32x4 xa[2][4], ra[2][4];
     auto load_x = [&](int t, int s) {
 #pragma unroll
@@ -66,7 +70,9 @@ __device__ __forceinline__ void block_stage(const Lane& t_, const uint16_t* __re
     };
     auto load_r = [&](int t, int jt) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) ra[jt][u] = ldg128(Wrow + ((size_t)t * M64 + 32 * jt) * M64 + 8 * u);
+        for (int u = 0; u < 4; ++u)
+            ra[jt][u] = PACKED ? ldg128(Wrow + (size_t)((t * 2 + jt) * 4 + u) * 512)
+                               : ldg128(Wrow + ((size_t)t * M64 + 32 * jt) * M64 + 8 * u);
     };
     load_x(0, 0);
     load_r(0, 0);
@@ -122,23 +128,27 @@ __device__ __forceinline__ void exchange_write(const Lane& t_, unsigned char* ld
 
 // Column stage for half h: eight blocks c = 32h + 8cg + cc of W2[c][out][in], output tile lt.
 // acc(cc) = D[out = 32*lt + 8*(i/4) + 4*g + i%4][b = ln]; `sink(cc, acc)` consumes it.
-template <typename Sink>
+template <bool PACKED, typename Sink>
 __device__ __forceinline__ void column_stage(const Lane& t_, const uint16_t* __restrict__ W2, const unsigned char* ldsb,
                                              int h, Sink&& sink)
 {
     const int cg = t_.wave & 3, lt = t_.wave >> 2;
     const unsigned char* ub = ldsb + (size_t)t_.ln * SQ_ROWB + (8 * cg) * 128 + 64 * t_.g;
-    const uint16_t* Wrow = W2 + (((size_t)(32 * h + 8 * cg)) * M64 + 32 * lt + t_.ln) * M64 + 32 * t_.g;
+    // packed: fragment (block c, tile lt, K-step u) at ((c*2 + lt)*4 + u) * 512 elements, + lane * 8
+    const uint16_t* Wrow = PACKED ? W2 + ((size_t)((32 * h + 8 * cg) * 2 + lt) * 4 * 64 + t_.lane) * 8
+                                  : W2 + (((size_t)(32 * h + 8 * cg)) * M64 + 32 * lt + t_.ln) * M64 + 32 * t_.g;
+    constexpr size_t BLK = PACKED ? 8 * 512 : (size_t)M64 * M64;  // elements between consecutive blocks c
+    constexpr size_t KST = PACKED ? 512 : 8;                       // elements between consecutive K-steps u
     u32x4 la[2][4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) la[0][u] = ldg128(Wrow + 8 * u);
+    for (int u = 0; u < 4; ++u) la[0][u] = ldg128(Wrow + u * KST);
 #pragma unroll
     for (int cc = 0; cc < 8; ++cc) {
         const int s = cc & 1;
         __builtin_amdgcn_sched_barrier(0);
         if (cc + 1 < 8) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) la[s ^ 1][u] = ldg128(Wrow + (size_t)(cc + 1) * M64 * M64 + 8 * u);
+            for (int u = 0; u < 4; ++u) la[s ^ 1][u] = ldg128(Wrow + (size_t)(cc + 1) * BLK + u * KST);
         }
         __builtin_amdgcn_sched_barrier(0);
         f32x16 acc;
@@ -189,6 +199,7 @@ __device__ __forceinline__ Lane make_lane()
 
 // ------------------------------------------------------------------------ forward ----
 
+template <bool PACKED>
 __global__ void __launch_bounds__(512)
 fwd_sq64_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
                 const uint16_t* __restrict__ L, uint16_t* __restrict__ y, int64_t B)
@@ -202,7 +213,7 @@ fwd_sq64_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
 
     // step 1: Y1[b][kk][j] -> exchange layout T[b][j][kk]
     uint32_t pk1[4][16];
-    block_stage(t, x + row * N64 + 32 * g, R, ldsb, pk1);
+    block_stage<PACKED>(t, x + row * N64 + 32 * g, R, ldsb, pk1);
 
     // step 2 for the 32 blocks c = j of each half.
     // po[h][c2][i]: bf16 pair (c0 + 2*c2, c0 + 2*c2 + 1) of W[b = ln][c][l], c0 = 32h + 8cg,
@@ -217,7 +228,7 @@ fwd_sq64_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
         }
         __syncthreads();
         f32x16 ev;
-        column_stage(t, L, ldsb, h, [&](int cc, const f32x16& acc) {
+        column_stage<PACKED>(t, L, ldsb, h, [&](int cc, const f32x16& acc) {
             if ((cc & 1) == 0) {
                 ev = acc;
             } else {
@@ -247,6 +258,35 @@ fwd_sq64_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
         __syncthreads();
         copy_out<true>(t, ldsb, y, b0, B, 32 * rnd);
     }
+}
+
+// ------------------------------------------------------------------------ pack ----
+
+// A 64-block factor W[blk][out][in] (64 x 64 each) in MFMA fragment order, for up to three factors in
+// one launch:  dst[blk][t2][u][lane][e] = W'[blk][32*t2 + lane%32][32*(lane/32) + 8*u + e], where W' = W,
+// or W' = W^T per block (tr: the backward multiplies by the transposed factors).  One thread = one
+// 16-byte piece; 32768 pieces per factor.
+struct Pack64Job { const uint16_t* src; uint16_t* dst; int tr; };
+__global__ void __launch_bounds__(256)
+pack64_kernel(Pack64Job j0, Pack64Job j1, Pack64Job j2)
+{
+    const int which = blockIdx.x >> 7;  // 128 blocks of 256 pieces per factor
+    const Pack64Job& j = which == 0 ? j0 : (which == 1 ? j1 : j2);
+    const int pc = (blockIdx.x & 127) * 256 + threadIdx.x;
+    const int lane = pc & 63, ln = lane & 31, g = lane >> 5;
+    const int rest = pc >> 6, u = rest & 3, t2 = (rest >> 2) & 1, blk = rest >> 3;
+    u32x4 o;
+    if (!j.tr) {
+        o = ldg128(j.src + ((size_t)blk * M64 + 32 * t2 + ln) * M64 + 32 * g + 8 * u);
+    } else {
+        const uint16_t* p = j.src + ((size_t)blk * M64 + 32 * g + 8 * u) * M64 + 32 * t2 + ln;
+        uint16_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = p[(size_t)e * M64];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) o[w] = (uint32_t)v[2 * w] | ((uint32_t)v[2 * w + 1] << 16);
+    }
+    *reinterpret_cast<u32x4*>(j.dst + (size_t)pc * 8) = o;
 }
 
 // ------------------------------------------------------------------------ backward ----
@@ -279,8 +319,8 @@ transpose64_kernel(const uint16_t* __restrict__ src, uint16_t* __restrict__ dst)
 
 __global__ void __launch_bounds__(512)
 bwd_sq64_data_kernel(const uint16_t* __restrict__ dW, const uint16_t* __restrict__ x,
-                     const uint16_t* __restrict__ R, const uint16_t* __restrict__ LT,
-                     const uint16_t* __restrict__ RT, uint16_t* __restrict__ dx,
+                     const uint16_t* __restrict__ R /* packed */, const uint16_t* __restrict__ LT /* packed L^T */,
+                     const uint16_t* __restrict__ RT /* packed R^T */, uint16_t* __restrict__ dx,
                      uint16_t* __restrict__ Uws, uint16_t* __restrict__ dY1ws, int64_t B)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char ldsb[];
@@ -292,7 +332,7 @@ bwd_sq64_data_kernel(const uint16_t* __restrict__ dW, const uint16_t* __restrict
 
     uint32_t pk1[4][16];
     // ---- recompute step 1; the exchange layout T[b][j][kk] is U[b][c = j][r = kk]: to the workspace
-    block_stage(t, x + row * N64 + 32 * g, R, ldsb, pk1);
+    block_stage<true>(t, x + row * N64 + 32 * g, R, ldsb, pk1);
     __syncthreads();
     copy_out<false>(t, ldsb, Uws, b0, B, 0);
     __syncthreads();
@@ -304,7 +344,7 @@ bwd_sq64_data_kernel(const uint16_t* __restrict__ dW, const uint16_t* __restrict
     // ---- adjoint of step 2: dU[b][c][r] = sum_l LT[c][r][l] dW[b][c][l]; as dY1[b][kk = r][j = c]
     // the exchange layout T[b][r][c] is dY1[b][kk][j]: operand order of the next stage, and the
     // layout of the workspace copy
-    block_stage(t, dW + row * N64 + 32 * g, LT, ldsb, pk1);
+    block_stage<true>(t, dW + row * N64 + 32 * g, LT, ldsb, pk1);
 
     // ---- adjoint of step 1: dx[b][kk*64 + i] = sum_j RT[kk][i][j] dY1[b][kk][j]
     const int kg = t.wave & 3, it = t.wave >> 2;
@@ -315,7 +355,7 @@ bwd_sq64_data_kernel(const uint16_t* __restrict__ dW, const uint16_t* __restrict
         copy_out<false>(t, ldsb, dY1ws, b0, B, 32 * h);
         // dxr[cc][i4]: dx[b = ln][kk = 32h + 8kg + cc][i = 32*it + 8*i4 + 4*g .. +3]
         u32x2 dxr[8][4];
-        column_stage(t, RT, ldsb, h, [&](int cc, const f32x16& acc) {
+        column_stage<true>(t, RT, ldsb, h, [&](int cc, const f32x16& acc) {
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4)
                 dxr[cc][i4] = u32x2{pack_bf16x2(acc[4 * i4], acc[4 * i4 + 1]), pack_bf16x2(acc[4 * i4 + 2], acc[4 * i4 + 3])};
@@ -336,7 +376,7 @@ bwd_sq64_data_kernel(const uint16_t* __restrict__ dW, const uint16_t* __restrict
 
 // batch chunks of the two weight-gradient GEMMs (64 groups each): about one workgroup per CU
 struct Plan64 {
-    size_t off_u, off_dy1, off_dw, off_lt, off_rt, off_partL, off_partR, total;
+    size_t off_u, off_dy1, off_dw, off_lt, off_rt, off_rp, off_partL, off_partR, total;
     int nz, rows_per_chunk;
     bool ok;
 };
@@ -374,6 +414,7 @@ Plan64 make_plan64(const Problem& pb)
     pl.off_dw = off;  off += act;
     pl.off_lt = off;  off += align_up(pb.n_L() * 2, 256);
     pl.off_rt = off;  off += align_up(pb.n_R() * 2, 256);
+    pl.off_rp = off;  off += align_up(pb.n_R() * 2, 256);
     pl.off_partL = off; off += align_up((size_t)pl.nz * pb.n_L() * 4, 256);
     pl.off_partR = off; off += align_up((size_t)pl.nz * pb.n_R() * 4, 256);
     pl.total = off;
@@ -391,13 +432,33 @@ bool sq64_supported(const Problem& pb)
 int fwd_sq64(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
 {
     if (!sq64_supported(pb)) return -2;
-    auto kern = fwd_sq64_kernel;
+    auto kern = fwd_sq64_kernel<false>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ_LDS) != hipSuccess)
         return -4;
     const int64_t grid = (pb.B + SQ_BM - 1) / SQ_BM;
     if (grid > 0x7fffffffLL) return -2;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), SQ_LDS, st, (const uint16_t*)x, (const uint16_t*)R,
                        (const uint16_t*)L, (uint16_t*)y, pb.B);
+    return hip_status(hipGetLastError());
+}
+
+// forward on packed factors: workspace = packed R, then packed L
+size_t fwd_sq64_workspace(const Problem& pb) { return align_up(pb.n_R() * 2, 256) + align_up(pb.n_L() * 2, 256); }
+
+int fwd_sq64_ws(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
+{
+    if (!sq64_supported(pb)) return -2;
+    uint16_t* Rp = (uint16_t*)ws;
+    uint16_t* Lp = (uint16_t*)((char*)ws + align_up(pb.n_R() * 2, 256));
+    const Pack64Job jr{(const uint16_t*)R, Rp, 0}, jl{(const uint16_t*)L, Lp, 0};
+    hipLaunchKernelGGL(pack64_kernel, dim3(2 * 128), dim3(256), 0, st, jr, jl, jl);
+    if (hipGetLastError() != hipSuccess) return -4;
+    auto kern = fwd_sq64_kernel<true>;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ_LDS) != hipSuccess)
+        return -4;
+    const int64_t grid = (pb.B + SQ_BM - 1) / SQ_BM;
+    if (grid > 0x7fffffffLL) return -2;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), SQ_LDS, st, (const uint16_t*)x, Rp, Lp, (uint16_t*)y, pb.B);
     return hip_status(hipGetLastError());
 }
 
@@ -425,15 +486,16 @@ int bwd_sq64(const Problem& pb, const void* dy, const void* x, const void* R, co
     uint16_t* dWws = (uint16_t*)(w + pl.off_dw);
     uint16_t* LT = (uint16_t*)(w + pl.off_lt);
     uint16_t* RT = (uint16_t*)(w + pl.off_rt);
-    hipLaunchKernelGGL(transpose64_kernel, dim3(M64), dim3(256), 0, st, (const uint16_t*)L, LT);
-    hipLaunchKernelGGL(transpose64_kernel, dim3(M64), dim3(256), 0, st, (const uint16_t*)R, RT);
+    uint16_t* Rp = (uint16_t*)(w + pl.off_rp);
+    const Pack64Job jr{(const uint16_t*)R, Rp, 0}, jlt{(const uint16_t*)L, LT, 1}, jrt{(const uint16_t*)R, RT, 1};
+    hipLaunchKernelGGL(pack64_kernel, dim3(3 * 128), dim3(256), 0, st, jr, jlt, jrt);
     hipLaunchKernelGGL(transpose64_kernel, dim3((unsigned)pb.B), dim3(256), 0, st, (const uint16_t*)dy, dWws);
     if (hipGetLastError() != hipSuccess) return -4;
     auto kern = bwd_sq64_data_kernel;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ_LDS) != hipSuccess)
         return -4;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), SQ_LDS, st, dWws, (const uint16_t*)x, (const uint16_t*)R,
-                       LT, RT, (uint16_t*)dx, Uws, dY1ws, pb.B);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), SQ_LDS, st, dWws, (const uint16_t*)x, Rp, LT, RT,
+                       (uint16_t*)dx, Uws, dY1ws, pb.B);
     if (hipGetLastError() != hipSuccess) return -4;
 
     WgradDesc dl, dr;

@@ -74,6 +74,7 @@ def test_forward_with_workspace_rejects_bad_arguments_without_a_gpu(binding):
     p = 4096  # never dereferenced
     need = binding.monarch_fwd_workspace_bytes(0, 768, 4, 192, 192, 1)
     assert need == 2 * 2 * 4 * 192 * 192                       # packed copies of R and L
+    assert binding.monarch_fwd_workspace_bytes(0, 4096, 64, 64, 64, 1) == 2 * 2 * 64 ** 3   # m = 64: packed R and L
     assert binding.monarch_fwd_workspace_bytes(0, 6, 2, 4, 2, 0) == 0        # shape without a packed-weight kernel
     assert binding.monarch_fwd_workspace_bytes(0, 768, 4, 192, 192, 1, binding.MONARCH_FLAG_GENERIC) == 0
     assert binding.monarch_fwd_workspace_bytes(0, 770, 4, 192, 192, 1) == 0  # invalid arguments
@@ -129,6 +130,7 @@ def test_kernel_name_reports_dispatch(binding):
     assert binding.monarch_kernel_name(0, 770, 4, 192, 192, 1) == "invalid"
     assert binding.monarch_kernel_name(3, 768, 4, 192, 192, 1) == "invalid"
     assert binding.monarch_kernel_name(2, 768, 4, 192, 192, 1) == "mfma_fwd_frag_bf16"
+    assert binding.monarch_kernel_name(2, 4096, 64, 64, 64, 1) == "mfma_fwd_sq64_packed_bf16"
     assert binding.monarch_kernel_name(2, 6, 2, 4, 2, 0) == "generic_fwd"   # no packed-weight kernel: same as pass 0
     assert binding.monarch_kernel_name(0, 6, 2, 4, 2, 0) == "generic_fwd"
     assert binding.monarch_kernel_name(1, 6, 2, 4, 2, 0) == "generic_bwd"
