@@ -8,7 +8,8 @@
 shows for the library's plain copy kernel (stream_copy_kernel, N bytes read and N bytes written per
 dispatch), and reports HBM bytes per launch for every kernel of the library, plus the totals per
 C-ABI call (monarch_fwd = the forward kernel, monarch_fwd_ws = the pack kernel + the packed-weight
-forward, monarch_bwd = every other kernel of the library).
+forward, monarch_bwd = every other kernel of the library; the m = 64 pack kernel serves both
+monarch_fwd_ws and monarch_bwd and is counted with the latter).
 """
 from __future__ import annotations
 
@@ -68,12 +69,12 @@ def cmd_traffic(args):
     calls = {"monarch_fwd": [0.0, 0.0], "monarch_fwd_ws": [0.0, 0.0], "monarch_bwd": [0.0, 0.0]}
     per_kernel = {}
     for k in sorted(fetch):
-        if k == COPY_KERNEL or not any(t in k for t in ("fwd_", "bwd_", "wgrad_", "prep_", "transpose64", "reduce_sq16", "generic_", "fill_zero", "f32_to_bf16")):
+        if k == COPY_KERNEL or not any(t in k for t in ("fwd_", "bwd_", "wgrad_", "prep_", "pack64", "transpose64", "reduce_sq16", "generic_", "fill_zero", "f32_to_bf16")):
             continue
         fb, wb = fetch[k] * f_scale * 1024.0, write.get(k, 0.0) * w_scale * 1024.0
         per_kernel[k] = {"fetch_bytes": fb, "write_bytes": wb}
         print("%-60s %6d %14.2f %14.2f" % (k[:60], nf[k], fb / 1e6, wb / 1e6))
-        if k.startswith("fwd_frag") or k.startswith("pack_fwd"):
+        if k.startswith("fwd_frag") or k.startswith("pack_fwd") or k.startswith("fwd_sq64_kernel<true>"):
             call = "monarch_fwd_ws"
         elif k.startswith("fwd_") or k.startswith("generic_fwd"):
             call = "monarch_fwd"
