@@ -133,7 +133,12 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True):
         xs, _, y, _ = sets[i % nsets]
         binding.monarch_fwd_ws(xs, Rd, Ld, y, workspace=fws)
 
+    def fwd_ws_packed(i):
+        xs, _, y, _ = sets[i % nsets]
+        binding.monarch_fwd_ws(xs, Rd, Ld, y, workspace=fws, flags=binding.MONARCH_FLAG_WS_PACKED)
+
     fwd_ws_ms = float(np.mean([run_of(fwd_ws_only) for _ in range(3)])) if fneed else None
+    fwd_ws_packed_ms = float(np.mean([run_of(fwd_ws_packed) for _ in range(3)])) if fneed else None
     fwd_runs = [run_of(fwd_only) for _ in range(3)]
     bwd_runs = [run_of(bwd_only) for _ in range(3)]
     fwd_ms, bwd_ms = float(np.mean(fwd_runs)), float(np.mean(bwd_runs))
@@ -150,7 +155,8 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True):
         "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "fwd_ms_min": fwd_min, "bwd_ms_min": bwd_min,
         "fwd_ms_evented": fwd_ev, "bwd_ms_evented": bwd_ev,
         # monarch_fwd_ws (weights packed into a caller workspace, pack included); null when the shape has no such kernel
-        "fwd_ws_ms": fwd_ws_ms, "fwd_ws_kernel": binding.monarch_kernel_name(2, sh.n_in, sh.k, sh.q, sh.s, code),
+        "fwd_ws_ms": fwd_ws_ms, "fwd_ws_packed_ms": fwd_ws_packed_ms,  # the latter: pack pass skipped (weights unchanged)
+        "fwd_ws_kernel": binding.monarch_kernel_name(2, sh.n_in, sh.k, sh.q, sh.s, code),
         "fwd_kernel": binding.monarch_kernel_name(0, sh.n_in, sh.k, sh.q, sh.s, code),
         "bwd_kernel": binding.monarch_kernel_name(1, sh.n_in, sh.k, sh.q, sh.s, code),
         "fwd_tflops": sh.fwd_flops() / (fwd_ms * 1e-3) / 1e12,

@@ -73,6 +73,10 @@ enum {
 #define MONARCH_FLAG_WGRAD_F32 1u /* monarch_bwd: dR, dL are float even when dtype is bf16 */
 #define MONARCH_FLAG_PERM_B    2u /* use the inverse mid permutation (see above) */
 #define MONARCH_FLAG_GENERIC   4u /* force the shape-generic kernels (testing aid) */
+#define MONARCH_FLAG_WS_PACKED 8u /* monarch_fwd_ws: the workspace already holds the packed copies of these
+                                     R and L, left there by an earlier monarch_fwd_ws call for the same
+                                     shape without this flag; the pack pass is skipped (weights that stay
+                                     fixed over many calls: inference, several micro-batches per update) */
 
 /* Forward: y = x M^T  (Section 3.3 steps 1-3; one fused pass, the intermediate
  * Y1/U never leaves the chip).  x (batch, n_in), R (k, q, n_in/k), L (k, s, q),
@@ -92,9 +96,10 @@ int monarch_fwd_ex(const void* x, const void* R, const void* L, void* y,
  * runs the fused forward on the packed copies, which removes the weights from the LDS traffic of
  * the kernel; every other shape runs exactly as monarch_fwd_ex and ignores the workspace.
  * `workspace` (device memory, 256-byte aligned, caller-owned) must hold at least
- * monarch_fwd_workspace_bytes(...) bytes when that is non-zero; its contents on entry are ignored
- * and on exit are unspecified.  Returns MONARCH_ERR_WORKSPACE if it is missing, misaligned or too
- * small. */
+ * monarch_fwd_workspace_bytes(...) bytes when that is non-zero.  Without MONARCH_FLAG_WS_PACKED its
+ * contents on entry are ignored; on exit it holds the packed copies of R and L, and a later call with
+ * MONARCH_FLAG_WS_PACKED, the same shape and unchanged R and L may reuse them (R and L must still be
+ * valid pointers but are not read).  Returns MONARCH_ERR_WORKSPACE if the workspace is missing, misaligned or too small. */
 int monarch_fwd_ws(const void* x, const void* R, const void* L, void* y,
                    int64_t batch, int n_in, int k, int q, int s,
                    monarch_dtype dtype, void* stream,

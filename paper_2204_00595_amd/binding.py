@@ -25,6 +25,7 @@ MONARCH_ERR_HIP = -4
 MONARCH_FLAG_WGRAD_F32 = 1
 MONARCH_FLAG_PERM_B = 2
 MONARCH_FLAG_GENERIC = 4
+MONARCH_FLAG_WS_PACKED = 8
 
 # every symbol include/monarch.h declares
 EXPORTS = (
@@ -149,6 +150,8 @@ def monarch_fwd_ws(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.T
     _check(y, "y", (B, k * s), dt, dev)
     need = monarch_fwd_workspace_bytes(B, k * p, k, q, s, _dtype_code(x), flags)
     if workspace is None and need:
+        if flags & MONARCH_FLAG_WS_PACKED:
+            raise ValueError("MONARCH_FLAG_WS_PACKED needs the workspace of the earlier call")
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     ws_ptr = workspace.data_ptr() if workspace is not None else 0
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0

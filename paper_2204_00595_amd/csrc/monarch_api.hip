@@ -7,7 +7,7 @@ using namespace monarch;
 
 namespace {
 
-constexpr unsigned kKnownFlags = MONARCH_FLAG_WGRAD_F32 | MONARCH_FLAG_PERM_B | MONARCH_FLAG_GENERIC;
+constexpr unsigned kKnownFlags = MONARCH_FLAG_WGRAD_F32 | MONARCH_FLAG_PERM_B | MONARCH_FLAG_GENERIC | MONARCH_FLAG_WS_PACKED;
 
 // Fills pb; returns MONARCH_OK or MONARCH_ERR_INVALID.
 int make_problem(Problem& pb, int64_t batch, int n_in, int k, int q, int s, int dtype, unsigned flags)
@@ -58,7 +58,7 @@ int monarch_fwd_ex(const void* x, const void* R, const void* L, void* y, int64_t
     Problem pb;
     int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
     if (rc) return rc;
-    if (flags & MONARCH_FLAG_WGRAD_F32) return MONARCH_ERR_INVALID;  // backward-only flag
+    if (flags & (MONARCH_FLAG_WGRAD_F32 | MONARCH_FLAG_WS_PACKED)) return MONARCH_ERR_INVALID;  // not forward / not without workspace
     if (!R || !L || ((!x || !y) && batch > 0)) return MONARCH_ERR_INVALID;
     if (!aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(y, 16)) return MONARCH_ERR_INVALID;
     const Family fam = pick_fwd(pb);
@@ -91,7 +91,7 @@ int monarch_fwd_ws(const void* x, const void* R, const void* L, void* y, int64_t
     int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
     if (rc) return rc;
     if ((flags & MONARCH_FLAG_GENERIC) || !mfma_fwd_ws_supported(pb))
-        return monarch_fwd_ex(x, R, L, y, batch, n_in, k, q, s, dtype, stream, flags);
+        return monarch_fwd_ex(x, R, L, y, batch, n_in, k, q, s, dtype, stream, flags & ~MONARCH_FLAG_WS_PACKED);
     if (flags & MONARCH_FLAG_WGRAD_F32) return MONARCH_ERR_INVALID;  // backward-only flag
     if (!R || !L || ((!x || !y) && batch > 0)) return MONARCH_ERR_INVALID;
     if (!aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(y, 16)) return MONARCH_ERR_INVALID;
@@ -120,6 +120,7 @@ int monarch_bwd(const void* dy, const void* x, const void* R, const void* L, voi
     Problem pb;
     int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
     if (rc) return rc;
+    if (flags & MONARCH_FLAG_WS_PACKED) return MONARCH_ERR_INVALID;  // forward-with-workspace flag
     if (!R || !L || !dR || !dL || ((!dy || !x || !dx) && batch > 0)) return MONARCH_ERR_INVALID;
     if (!aligned(dy, 16) || !aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(dx, 16) ||
         !aligned(dR, 16) || !aligned(dL, 16))

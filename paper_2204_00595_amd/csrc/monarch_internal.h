@@ -16,6 +16,7 @@ struct Problem {
     size_t esize() const { return dtype == 0 ? 4 : 2; }
     bool perm_b() const { return (flags & 2u) != 0; }
     bool wgrad_f32() const { return dtype == 0 || (flags & 1u) != 0; }
+    bool ws_packed() const { return (flags & 8u) != 0; }  // monarch_fwd_ws: skip the pack pass
     size_t n_R() const { return (size_t)k * q * p; }
     size_t n_L() const { return (size_t)k * s * q; }
 };

@@ -305,10 +305,12 @@ int fwd_frag(const Problem& pb, const void* x, const void* R, const void* L, voi
     if (!e) return -2;
     uint16_t* RF1 = (uint16_t*)ws;
     uint16_t* LF2 = (uint16_t*)((char*)ws + align_up(pb.n_R() * 2, 256));
-    const size_t pieces = (pb.n_R() + pb.n_L()) / 8;
-    hipLaunchKernelGGL(pack_fwd_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st,
-                       (const uint16_t*)R, (const uint16_t*)L, RF1, LF2, pb.p, pb.q, pb.s);
-    if (hipGetLastError() != hipSuccess) return -4;
+    if (!pb.ws_packed()) {
+        const size_t pieces = (pb.n_R() + pb.n_L()) / 8;
+        hipLaunchKernelGGL(pack_fwd_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st,
+                           (const uint16_t*)R, (const uint16_t*)L, RF1, LF2, pb.p, pb.q, pb.s);
+        if (hipGetLastError() != hipSuccess) return -4;
+    }
     return e->fn(pb, x, RF1, LF2, y, st);
 }
 

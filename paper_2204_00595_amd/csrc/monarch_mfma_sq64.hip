@@ -450,9 +450,11 @@ int fwd_sq64_ws(const Problem& pb, const void* x, const void* R, const void* L, 
     if (!sq64_supported(pb)) return -2;
     uint16_t* Rp = (uint16_t*)ws;
     uint16_t* Lp = (uint16_t*)((char*)ws + align_up(pb.n_R() * 2, 256));
-    const Pack64Job jr{(const uint16_t*)R, Rp, 0}, jl{(const uint16_t*)L, Lp, 0};
-    hipLaunchKernelGGL(pack64_kernel, dim3(2 * 128), dim3(256), 0, st, jr, jl, jl);
-    if (hipGetLastError() != hipSuccess) return -4;
+    if (!pb.ws_packed()) {
+        const Pack64Job jr{(const uint16_t*)R, Rp, 0}, jl{(const uint16_t*)L, Lp, 0};
+        hipLaunchKernelGGL(pack64_kernel, dim3(2 * 128), dim3(256), 0, st, jr, jl, jl);
+        if (hipGetLastError() != hipSuccess) return -4;
+    }
     auto kern = fwd_sq64_kernel<true>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ_LDS) != hipSuccess)
         return -4;

@@ -202,6 +202,26 @@ def test_matrix_core_backward_is_bit_reproducible(B, case):
     assert np.array_equal(run_fwd(B, sh, x, R, L, ws=True), run_fwd(B, sh, x, R, L, ws=True))
 
 
+@pytest.mark.parametrize("case", [("k4_192", "bf16", 200, 4, 192, 192, 192), ("k4_fc1", "bf16", 130, 4, 64, 64, 128),
+                                  ("sq_m64", "bf16", 70, 64, 64, 64, 64)], ids=lambda c: c[0])
+def test_forward_reuses_packed_weights(B, case):
+    """monarch_fwd_ws packs R and L into the workspace; a second call with MONARCH_FLAG_WS_PACKED on other
+    rows must use those copies (R and L are passed as NaN to prove that they are not read)."""
+    sh = small_shape(case)
+    x, R, L, _ = synth.make_inputs(sh)
+    x2 = synth.quantize(synth.normal(4242, x.shape), sh.dtype)
+    code = 1
+    need = B.monarch_fwd_workspace_bytes(x.shape[0], sh.n_in, sh.k, sh.q, sh.s, code, 0)
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    Rd, Ld = dev(R, sh.dtype), dev(L, sh.dtype)
+    y1 = B.monarch_fwd_ws(dev(x, sh.dtype), Rd, Ld, workspace=ws)
+    nanR, nanL = torch.full_like(Rd, float("nan")), torch.full_like(Ld, float("nan"))
+    y2 = B.monarch_fwd_ws(dev(x2, sh.dtype), nanR, nanL, workspace=ws, flags=B.MONARCH_FLAG_WS_PACKED)
+    torch.cuda.synchronize()
+    compare(sh, [host(y1), host(y2)], [oracle.fwd(x, R, L), oracle.fwd(x2, R, L)], ["y", "y_packed"])
+
+
 FULL = ["sq256_f32", "vitb_proj", "gpt2s_fc1", "sq4096", "gpt2m_fc1", "gpt2m_fc2"]
 
 

@@ -64,6 +64,7 @@ def test_forward_rejects_bad_arguments_without_a_gpu(binding):
     assert call(dtype=7) == binding.MONARCH_ERR_INVALID
     assert call(flags=64) == binding.MONARCH_ERR_INVALID
     assert call(flags=binding.MONARCH_FLAG_WGRAD_F32) == binding.MONARCH_ERR_INVALID
+    assert call(flags=binding.MONARCH_FLAG_WS_PACKED) == binding.MONARCH_ERR_INVALID   # no workspace to reuse
     # a row far too wide for any kernel of this build
     assert call(n_in=4 * 2000000, q=2000000, s=4) == binding.MONARCH_ERR_UNSUPPORTED
     assert L.monarch_fwd(ok_ptr, ok_ptr, ok_ptr, ok_ptr, 0, 768, 4, 192, 192, 1, None) == binding.MONARCH_OK
@@ -90,6 +91,8 @@ def test_forward_with_workspace_rejects_bad_arguments_without_a_gpu(binding):
     assert call(x=None, batch=1) == binding.MONARCH_ERR_INVALID
     assert call(n_in=770) == binding.MONARCH_ERR_INVALID
     assert call(flags=binding.MONARCH_FLAG_WGRAD_F32) == binding.MONARCH_ERR_INVALID
+    assert call(flags=binding.MONARCH_FLAG_WS_PACKED) == binding.MONARCH_OK
+    assert call(flags=binding.MONARCH_FLAG_WS_PACKED, ws=None) == binding.MONARCH_ERR_WORKSPACE
     # shapes without a packed-weight kernel behave as monarch_fwd_ex and need no workspace
     assert call(ws=None, ws_bytes=0, n_in=6, k=2, q=4, s=2, dtype=0) == binding.MONARCH_OK
     assert call(ws=None, ws_bytes=0, flags=binding.MONARCH_FLAG_GENERIC) == binding.MONARCH_OK
