@@ -139,6 +139,9 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True):
 
     fwd_ws_ms = float(np.mean([run_of(fwd_ws_only) for _ in range(3)])) if fneed else None
     fwd_ws_packed_ms = float(np.mean([run_of(fwd_ws_packed) for _ in range(3)])) if fneed else None
+    Mdense = torch.empty((sh.n_out, sh.n_in), dtype=Rd.dtype, device="cuda")
+    to_dense_ms = float(np.mean([run_of(lambda i: binding.monarch_to_dense(Rd, Ld, Mdense)) for _ in range(3)]))
+    dense_bytes = (sh.k * sh.q * sh.p + sh.k * sh.s * sh.q + sh.n_out * sh.n_in) * sh.esize
     fwd_runs = [run_of(fwd_only) for _ in range(3)]
     bwd_runs = [run_of(bwd_only) for _ in range(3)]
     fwd_ms, bwd_ms = float(np.mean(fwd_runs)), float(np.mean(bwd_runs))
@@ -157,6 +160,8 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True):
         # monarch_fwd_ws (weights packed into a caller workspace, pack included); null when the shape has no such kernel
         "fwd_ws_ms": fwd_ws_ms, "fwd_ws_packed_ms": fwd_ws_packed_ms,  # the latter: pack pass skipped (weights unchanged)
         "fwd_ws_kernel": binding.monarch_kernel_name(2, sh.n_in, sh.k, sh.q, sh.s, code),
+        # monarch_to_dense: M written out as a dense (n_out, n_in) matrix; bytes = R + L read, M written
+        "to_dense_ms": to_dense_ms, "to_dense_gbs": dense_bytes / (to_dense_ms * 1e-3) / 1e9,
         "fwd_kernel": binding.monarch_kernel_name(0, sh.n_in, sh.k, sh.q, sh.s, code),
         "bwd_kernel": binding.monarch_kernel_name(1, sh.n_in, sh.k, sh.q, sh.s, code),
         "fwd_tflops": sh.fwd_flops() / (fwd_ms * 1e-3) / 1e12,

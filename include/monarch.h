@@ -135,6 +135,22 @@ int monarch_bwd(const void* dy, const void* x, const void* R, const void* L,
 size_t monarch_bwd_workspace_bytes(int64_t batch, int n_in, int k, int q, int s,
                                    monarch_dtype dtype, unsigned flags);
 
+/* The Monarch matrix itself as a dense array: M = P L P^T R (Definition 3.1), the matrix for which
+ * monarch_fwd computes y = x M^T.  This is the conversion that sparse-to-dense training makes when it
+ * switches from the Monarch layer to a dense one (Section 4: the factors multiplied out together
+ * with the permutations).  Entry by entry, with o = l*k + c and col = kk*p + i,
+ *   M[o][col] = sum over j < q with  dest(kk, j) in [c*q, (c+1)*q)  of  L[c][l][dest(kk, j) - c*q] * R[kk][j][i]
+ * where dest(kk, j) is the position in U that stage-1 output (kk, j) is moved to (j*k + kk by
+ * default, ((kk*q + j) mod k)*q + (kk*q + j) div k with MONARCH_FLAG_PERM_B).  In the square case
+ * this is Equation (1), M[l*m + j][kk*m + i] = L[j][l][kk] * R[kk][j][i], one product per entry;
+ * otherwise about q/k products are summed in fp32 and the entry is rounded once to `dtype`.
+ * R (k, q, n_in/k), L (k, s, q) and M (k*s, n_in) row-major are device pointers, 16-byte aligned; M
+ * is overwritten in full (structural zeros included).  `flags` may hold MONARCH_FLAG_PERM_B only;
+ * any other flag is MONARCH_ERR_INVALID.  No workspace. */
+int monarch_to_dense(const void* R, const void* L, void* M,
+                     int n_in, int k, int q, int s,
+                     monarch_dtype dtype, void* stream, unsigned flags);
+
 /* Name of the kernel family the dispatcher picks for this problem: pass 0 = forward
  * (monarch_fwd / monarch_fwd_ex), 1 = backward, 2 = forward with workspace (monarch_fwd_ws).  Static string, never NULL ("invalid" / "unsupported" on bad input). */
 const char* monarch_kernel_name(int pass, int n_in, int k, int q, int s,

@@ -31,7 +31,7 @@ MONARCH_FLAG_WS_PACKED = 8
 EXPORTS = (
     "monarch_fwd", "monarch_fwd_ex", "monarch_fwd_ws", "monarch_fwd_workspace_bytes", "monarch_bwd",
     "monarch_bwd_workspace_bytes",
-    "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy",
+    "monarch_to_dense", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy",
 )
 
 _lib = None
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.monarch_bwd.argtypes = [vp] * 7 + [i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
         L.monarch_bwd_workspace_bytes.restype = sz
         L.monarch_bwd_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci, cu]
+        L.monarch_to_dense.restype = ci
+        L.monarch_to_dense.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp, cu]
         L.monarch_kernel_name.restype = ctypes.c_char_p
         L.monarch_kernel_name.argtypes = [ci, ci, ci, ci, ci, ci, cu]
         L.monarch_status_string.restype = ctypes.c_char_p
@@ -186,6 +188,25 @@ def monarch_fwd(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.Tens
     if rc != MONARCH_OK:
         raise MonarchError(rc, "monarch_fwd")
     return y
+
+
+def monarch_to_dense(R: torch.Tensor, L: torch.Tensor, M: torch.Tensor | None = None, flags: int = 0,
+                     stream=None) -> torch.Tensor:
+    """M = P L P^T R as a dense (k*s, k*p) matrix.  R (k, q, p), L (k, s, q) on the GPU."""
+    k, q, p = R.shape
+    s = L.shape[1]
+    dev, dt = R.device, R.dtype
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    if M is None:
+        M = torch.empty((k * s, k * p), dtype=dt, device=dev)
+    _check(M, "M", (k * s, k * p), dt, dev)
+    with torch.cuda.device(dev):
+        rc = lib().monarch_to_dense(R.data_ptr(), L.data_ptr(), M.data_ptr(), k * p, k, q, s, _dtype_code(R),
+                                    _stream_ptr(stream), flags)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_to_dense")
+    return M
 
 
 def monarch_bwd(dy: torch.Tensor, x: torch.Tensor, R: torch.Tensor, L: torch.Tensor,

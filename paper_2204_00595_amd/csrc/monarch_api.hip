@@ -135,6 +135,18 @@ int monarch_bwd(const void* dy, const void* x, const void* R, const void* L, voi
     return generic_bwd(pb, dy, x, R, L, dx, dR, dL, workspace, st);
 }
 
+int monarch_to_dense(const void* R, const void* L, void* M, int n_in, int k, int q, int s, monarch_dtype dtype,
+                     void* stream, unsigned flags)
+{
+    Problem pb;
+    int rc = make_problem(pb, 1, n_in, k, q, s, (int)dtype, flags);
+    if (rc) return rc;
+    if (flags & ~MONARCH_FLAG_PERM_B) return MONARCH_ERR_INVALID;  // the other flags select kernels of other calls
+    if (!R || !L || !M) return MONARCH_ERR_INVALID;
+    if (!aligned(R, 16) || !aligned(L, 16) || !aligned(M, 16)) return MONARCH_ERR_INVALID;
+    return launch_to_dense(pb, R, L, M, (hipStream_t)stream);
+}
+
 const char* monarch_kernel_name(int pass, int n_in, int k, int q, int s, monarch_dtype dtype, unsigned flags)
 {
     Problem pb;

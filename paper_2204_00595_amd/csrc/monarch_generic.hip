@@ -91,6 +91,168 @@ int launch_f32_to_bf16(const float* src, uint16_t* dst, size_t n, hipStream_t st
     return hip_status(hipGetLastError());
 }
 
+// ------------------------------------------------------------- dense form of M ----
+//
+// Entry (o, col) of M = P L P^T R with o = l*k + c and col = kk*p + i is the sum, over the stage-1
+// outputs j of block kk that the mid permutation sends into block c of stage 2 (position r there),
+// of L[c][l][r] * R[kk][j][i]: one term in the square case (Equation (1)), about q/k terms otherwise.
+// In the default reading those j are a contiguous range (g = j*k + kk must fall in [c*q, (c+1)*q)),
+// in the inverse reading every k-th j (f = kk*q + j must be congruent to c mod k).
+// One thread owns CW consecutive columns (CW = 4 when 4 divides p, one 8- or 16-byte load per R row,
+// else 1) and DENSE_LT consecutive l of one c, so an R element is loaded once for DENSE_LT outputs;
+// lanes of a wave read consecutive i (coalesced) and share the L values.
+
+static constexpr int DENSE_LT = 8;
+static constexpr int DENSE_THREADS = 64;
+
+template <typename T, int CW> struct ColVec;
+template <> struct ColVec<float, 1> {
+    static __device__ __forceinline__ void load(const float* p, float* v) { v[0] = *p; }
+    static __device__ __forceinline__ void store(float* p, const float* v) { *p = v[0]; }
+};
+template <> struct ColVec<bf16_t, 1> {
+    static __device__ __forceinline__ void load(const bf16_t* p, float* v) { v[0] = bf16_to_f32(*p); }
+    static __device__ __forceinline__ void store(bf16_t* p, const float* v) { *p = f32_to_bf16(v[0]); }
+};
+template <> struct ColVec<float, 4> {
+    static __device__ __forceinline__ void load(const float* p, float* v)
+    {
+        const float4 t = *(const float4*)p;
+        v[0] = t.x, v[1] = t.y, v[2] = t.z, v[3] = t.w;
+    }
+    static __device__ __forceinline__ void store(float* p, const float* v) { *(float4*)p = make_float4(v[0], v[1], v[2], v[3]); }
+};
+template <> struct ColVec<bf16_t, 4> {
+    static __device__ __forceinline__ void load(const bf16_t* p, float* v)
+    {
+        const uint2 t = *(const uint2*)p;
+        v[0] = __uint_as_float(t.x << 16), v[1] = __uint_as_float(t.x & 0xffff0000u);
+        v[2] = __uint_as_float(t.y << 16), v[3] = __uint_as_float(t.y & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void store(bf16_t* p, const float* v)
+    {
+        uint2 t;
+        t.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+        t.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+        *(uint2*)p = t;
+    }
+};
+
+// The DENSE_JS waves of a workgroup share the same outputs and split the terms of the sum between
+// them (wave w takes terms w, w + DENSE_JS, ...): a wave's chain of dependent-latency loads is
+// DENSE_JS times shorter and a small matrix with long sums still fills the chip (measured, 768 x 768
+// with 48 terms per entry: 8.5 us against 15.5 us with one wave; large matrices and single-term sums
+// are faster with one wave).  The partial sums meet in LDS and wave 0 adds them in wave order (a
+// fixed order: the result is reproducible).
+template <typename T, int CW, int DENSE_JS>
+__global__ void __launch_bounds__(DENSE_THREADS * DENSE_JS)
+to_dense_kernel(const T* __restrict__ R, const T* __restrict__ L, T* __restrict__ M, int k, int p, int q, int s,
+                int perm_b, int col_tiles, int l_tiles)
+{
+    __shared__ float part[DENSE_JS > 1 ? DENSE_JS - 1 : 1][DENSE_LT * CW][DENSE_THREADS];
+    const int n_in = k * p;
+    const int ct = blockIdx.x % col_tiles;
+    const int rest = blockIdx.x / col_tiles;
+    const int lt = rest % l_tiles;
+    const int c = rest / l_tiles;
+    const int lane = threadIdx.x % DENSE_THREADS, wave = threadIdx.x / DENSE_THREADS;
+    const int col = (ct * DENSE_THREADS + lane) * CW;  // CW | p, so the CW columns share kk
+    const bool live = col < n_in;
+    const int kk = live ? col / p : 0, i = live ? col - kk * p : 0;
+    const int l0 = lt * DENSE_LT;
+
+    int j0, j1, jstep;
+    if (!perm_b) {
+        // j*k + kk >= c*q  and  j*k + kk < (c+1)*q
+        const int lo = c * q - kk, hi = (c + 1) * q - kk;
+        j0 = lo <= 0 ? 0 : (lo + k - 1) / k;
+        j1 = hi <= 0 ? 0 : (hi + k - 1) / k;
+        if (j1 > q) j1 = q;
+        jstep = 1;
+    } else {
+        // (kk*q + j) mod k == c
+        const int base = (int)(((int64_t)kk * q) % k);
+        j0 = c - base;
+        if (j0 < 0) j0 += k;
+        j1 = q;
+        jstep = k;
+    }
+    if (!live) j1 = j0;
+
+    float acc[DENSE_LT][CW];
+#pragma unroll
+    for (int u = 0; u < DENSE_LT; ++u)
+#pragma unroll
+        for (int e = 0; e < CW; ++e) acc[u][e] = 0.f;
+    const T* Rk = R + (size_t)kk * q * p + i;
+    const T* Lc = L + (size_t)c * s * q;
+    for (int j = j0 + wave * jstep; j < j1; j += jstep * DENSE_JS) {
+        const int r = mid_dest(kk * q + j, k, q, perm_b != 0) - c * q;
+        float w[CW];
+        ColVec<T, CW>::load(Rk + (size_t)j * p, w);
+#pragma unroll
+        for (int u = 0; u < DENSE_LT; ++u) {
+            const int l = l0 + u < s ? l0 + u : s - 1;
+            const float a = Elem<T>::load(Lc + (size_t)l * q + r);
+#pragma unroll
+            for (int e = 0; e < CW; ++e) acc[u][e] = fmaf(a, w[e], acc[u][e]);
+        }
+    }
+    if (DENSE_JS > 1) {
+        if (wave > 0) {
+#pragma unroll
+            for (int u = 0; u < DENSE_LT; ++u)
+#pragma unroll
+                for (int e = 0; e < CW; ++e) part[wave - 1][u * CW + e][lane] = acc[u][e];
+        }
+        __syncthreads();
+        if (wave > 0) return;
+#pragma unroll
+        for (int w2 = 0; w2 < DENSE_JS - 1; ++w2)
+#pragma unroll
+            for (int u = 0; u < DENSE_LT; ++u)
+#pragma unroll
+                for (int e = 0; e < CW; ++e) acc[u][e] += part[w2][u * CW + e][lane];
+    }
+    if (!live) return;
+#pragma unroll
+    for (int u = 0; u < DENSE_LT; ++u)
+        if (l0 + u < s) ColVec<T, CW>::store(M + ((size_t)(l0 + u) * k + c) * n_in + col, acc[u]);
+}
+
+template <typename T, int CW, int JS>
+static void launch_to_dense_v(const Problem& pb, const void* R, const void* L, void* M, hipStream_t st, unsigned grid,
+                              int col_tiles, int l_tiles)
+{
+    hipLaunchKernelGGL((to_dense_kernel<T, CW, JS>), dim3(grid), dim3(DENSE_THREADS * JS), 0, st, (const T*)R,
+                       (const T*)L, (T*)M, pb.k, pb.p, pb.q, pb.s, pb.perm_b() ? 1 : 0, col_tiles, l_tiles);
+}
+
+template <typename T>
+static int launch_to_dense_t(const Problem& pb, const void* R, const void* L, void* M, hipStream_t st)
+{
+    const int cw = pb.p % 4 == 0 ? 4 : 1;
+    const int col_tiles = (pb.n_in / cw + DENSE_THREADS - 1) / DENSE_THREADS;
+    const int l_tiles = (pb.s + DENSE_LT - 1) / DENSE_LT;
+    const int64_t grid = (int64_t)col_tiles * l_tiles * pb.k;
+    if (grid > 0x7fffffffLL) return -2;
+    const bool split = grid < 2048 && pb.q / pb.k >= 16;  // few workgroups, long sums
+    const unsigned g = (unsigned)grid;
+    if (cw == 4) {
+        if (split) launch_to_dense_v<T, 4, 4>(pb, R, L, M, st, g, col_tiles, l_tiles);
+        else launch_to_dense_v<T, 4, 1>(pb, R, L, M, st, g, col_tiles, l_tiles);
+    } else {
+        if (split) launch_to_dense_v<T, 1, 4>(pb, R, L, M, st, g, col_tiles, l_tiles);
+        else launch_to_dense_v<T, 1, 1>(pb, R, L, M, st, g, col_tiles, l_tiles);
+    }
+    return hip_status(hipGetLastError());
+}
+
+int launch_to_dense(const Problem& pb, const void* R, const void* L, void* M, hipStream_t st)
+{
+    return pb.dtype == 0 ? launch_to_dense_t<float>(pb, R, L, M, st) : launch_to_dense_t<bf16_t>(pb, R, L, M, st);
+}
+
 // -------------------------------------------------------------------- forward ----
 //
 // LDS: xs[BM][n_in] and us[BM][k*q], both fp32.  Each thread owns one output column at a

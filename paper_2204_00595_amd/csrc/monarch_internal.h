@@ -34,6 +34,9 @@ int generic_fwd(const Problem& pb, const void* x, const void* R, const void* L, 
 int generic_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L,
                 void* dx, void* dR, void* dL, void* ws, hipStream_t st);
 
+// dense form of the Monarch matrix, (k*s) x n_in row-major (any shape, both readings)
+int launch_to_dense(const Problem& pb, const void* R, const void* L, void* M, hipStream_t st);
+
 // ---- MFMA kernels for the shapes they are instantiated for (bf16 / fp32 matrix cores) ----
 bool mfma_fwd_supported(const Problem& pb);
 bool mfma_bwd_supported(const Problem& pb);

@@ -271,6 +271,63 @@ def test_mlp_pair_end_to_end(B):
             ["h", "y", "dh", "dR2", "dL2", "dx", "dR1", "dL1"])
 
 
+# Dense form of M: every entry is one fp32 sum of at most q products, rounded once to the storage type
+# (relative 2^-24 / 2^-9 per entry), so the bound is much tighter than for the multiply.
+DENSE_TOL = {"f32": 1e-6, "bf16": 3e-3}
+DENSE_EXTRA = [
+    ("k_gt_q", "f32", 9, 5, 3, 2, 3),          # k > q: some (kk, c) pairs have no term at all
+    ("ragged_cols", "f32", 9, 3, 100, 7, 5),   # n_in = 300: a partial tile of columns, s not a multiple of 4
+    ("ragged_cols_bf16", "bf16", 9, 6, 50, 4, 9),
+    ("long_sums_odd_p", "f32", 9, 2, 5, 40, 3),  # q/k = 20 terms split over the waves of a workgroup, p % 4 != 0
+]
+
+
+def run_dense(B, sh, R, L, flags=0):
+    buf, M = guarded((sh.n_out, sh.n_in), tdtype(sh.dtype))
+    B.monarch_to_dense(dev(R, sh.dtype), dev(L, sh.dtype), M, flags=flags)
+    torch.cuda.synchronize()
+    check_guard(buf, "M")
+    out = host(M)
+    assert np.isfinite(out).all(), "M has unwritten or non-finite entries"
+    return out
+
+
+@pytest.mark.parametrize("reading", [0, 1], ids=["reading_a", "reading_b"])
+@pytest.mark.parametrize("case", [c for c in SMALL if c[0] != "sq_m64_bf16"] + DENSE_EXTRA, ids=lambda c: c[0])
+def test_dense_form_small_shapes(B, case, reading):
+    """monarch_to_dense against the literal product of the four dense matrices of Definition 3.1."""
+    from oracle import dense
+    sh = small_shape(case)
+    x, R, L, _ = synth.make_inputs(sh)
+    got = run_dense(B, sh, R, L, B.MONARCH_FLAG_PERM_B if reading else 0)
+    want = dense.monarch_dense(R, L, reading)
+    err = oracle.rel_fro(got, want)
+    print("\n  %s M=%.2e" % (sh.name, err), flush=True)
+    assert err <= DENSE_TOL[sh.dtype]
+    assert np.all(got[want == 0] == 0), "an entry outside the sparsity pattern of M is not zero"
+    # and it is the matrix the step-by-step multiply applies: y = x M^T
+    assert oracle.rel_fro(x.astype(np.float64) @ got.T, oracle.fwd(x, R, L, reading)) <= TOL[sh.dtype]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_dense_form_full_size(B, name):
+    """Full-size factors: row col of M^T is the oracle's forward applied to the unit vector e_col."""
+    sh = synth.WORKLOADS[name]
+    _, R, L, _ = synth.make_inputs(sh, rows=1)
+    got = run_dense(B, sh, R, L)
+    want = oracle.fwd(np.eye(sh.n_in, dtype=np.float32), R, L).T
+    err = oracle.rel_fro(got, want)
+    print("\n  %s M=%.2e" % (sh.name, err), flush=True)
+    assert err <= DENSE_TOL[sh.dtype]
+    assert np.all(got[want == 0] == 0)
+    if sh.k == sh.q == sh.s == sh.p:  # Equation (1), sampled entries
+        m = sh.k
+        rng = np.random.default_rng(5)
+        for l, j, kk, i in rng.integers(0, m, size=(200, 4)):
+            ref = np.float64(L[j, l, kk]) * np.float64(R[kk, j, i])
+            assert abs(got[l * m + j, kk * m + i] - ref) <= 2.0 ** -8 * abs(ref) + 1e-30
+
+
 def test_stream_copy_is_bit_exact(B):
     n = (1 << 20) + 48  # bytes: several grid strides plus a ragged tail of three 16-byte pieces
     src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")

@@ -98,6 +98,25 @@ def test_forward_with_workspace_rejects_bad_arguments_without_a_gpu(binding):
     assert call(ws=None, ws_bytes=0, flags=binding.MONARCH_FLAG_GENERIC) == binding.MONARCH_OK
 
 
+def test_dense_form_rejects_bad_arguments_without_a_gpu(binding):
+    L = binding.lib()
+    p = 4096  # never dereferenced: every case below is refused before any launch
+
+    def call(R=p, Lp=p, M=p, n_in=768, k=4, q=192, s=192, dtype=1, flags=0):
+        return L.monarch_to_dense(R, Lp, M, n_in, k, q, s, dtype, None, flags)
+
+    assert call(R=None) == binding.MONARCH_ERR_INVALID
+    assert call(Lp=None) == binding.MONARCH_ERR_INVALID
+    assert call(M=None) == binding.MONARCH_ERR_INVALID
+    assert call(M=p + 8) == binding.MONARCH_ERR_INVALID          # not 16-byte aligned
+    assert call(n_in=770) == binding.MONARCH_ERR_INVALID         # k does not divide n_in
+    assert call(q=0) == binding.MONARCH_ERR_INVALID
+    assert call(dtype=2) == binding.MONARCH_ERR_INVALID
+    for f in (binding.MONARCH_FLAG_WGRAD_F32, binding.MONARCH_FLAG_GENERIC, binding.MONARCH_FLAG_WS_PACKED, 1024):
+        assert call(flags=f) == binding.MONARCH_ERR_INVALID
+    assert call(k=1 << 13, n_in=1 << 13, q=1 << 12, s=1) == binding.MONARCH_ERR_UNSUPPORTED
+
+
 def test_backward_rejects_bad_arguments_without_a_gpu(binding):
     L = binding.lib()
     p = 4096
