@@ -13,6 +13,11 @@ Two independent formulations live here:
   explicit 0/1 permutation matrices and explicit block-diagonal matrices
   (``dense.py``, numpy, tiny sizes only).
 
+``fwd_bias`` / ``bwd_bias`` add the bias vector of the linear layer whose weight matrix the
+Monarch matrix replaces (Section 4: the dense weight matrices are swapped for Monarch ones, the rest
+of the layer stays; the appendix on BERT pretraining lists the matrix product with the bias add, and
+the bias gradient in the backward pass, as steps worth fusing with the product).
+
 All arrays are float64, row-major.  Low-precision inputs must be converted
 exactly to float64 by the caller.
 """
@@ -125,6 +130,29 @@ def bwd(dy, x, R, L, reading: int = READING_A):
     if rc != 0:
         raise RuntimeError("monarch_oracle_bwd failed: %d" % rc)
     return dx, dR, dL
+
+
+def fwd_bias(x, R, L, bias, reading: int = READING_A):
+    """y[b][o] = (x M^T)[b][o] + bias[o]: the affine layer built on the Monarch matrix."""
+    y = fwd(x, R, L, reading)
+    bias = _f64(bias, (y.shape[1],))
+    for b in range(y.shape[0]):
+        y[b, :] = y[b, :] + bias
+    return y
+
+
+def bwd_bias(dy, x, R, L, reading: int = READING_A):
+    """Adjoint of :func:`fwd_bias`: (dx, dR, dL, dbias) with dbias[o] = sum_b dy[b][o].
+
+    The bias enters every row of y with coefficient one, so its gradient is the column sum of the
+    upstream gradient; dx, dR and dL do not depend on the bias at all.
+    """
+    dx, dR, dL = bwd(dy, x, R, L, reading)
+    dy = np.asarray(dy, dtype=np.float64)
+    dbias = np.zeros(dy.shape[1], dtype=np.float64)
+    for b in range(dy.shape[0]):
+        dbias += dy[b, :]
+    return dx, dR, dL, dbias
 
 
 def rel_fro(got, want) -> float:

@@ -301,3 +301,42 @@ def test_thread_count_does_not_change_results():
     b = oracle.bwd(dy, x, R, L)
     for u, v in zip(a, b):
         assert np.array_equal(u, v)
+
+
+# ------------------------------------------------------------ affine layer ----
+
+@pytest.mark.parametrize("reading", READINGS)
+@pytest.mark.parametrize("shape", [(3, 3, 3, 3)] + TINY_RECT[:4])
+def test_bias_forward_is_the_dense_affine_map(shape, reading):
+    """y = x M^T + 1 bias^T with M the literal dense product of Definition 3.1; a zero input returns
+    the bias itself and a zero bias returns the plain multiply."""
+    k, p, q, s = shape
+    rng = np.random.default_rng(31)
+    x, R, L, _ = _rand(rng, k, p, q, s, B=4)
+    bias = rng.standard_normal(k * s)
+    M = dense.monarch_dense(R, L, reading)
+    want = x @ M.T + np.ones((4, 1)) @ bias[None, :]
+    assert np.allclose(oracle.fwd_bias(x, R, L, bias, reading), want, rtol=0, atol=1e-12)
+    assert np.array_equal(oracle.fwd_bias(np.zeros_like(x), R, L, bias, reading), np.tile(bias, (4, 1)))
+    assert np.array_equal(oracle.fwd_bias(x, R, L, np.zeros(k * s), reading), oracle.fwd(x, R, L, reading))
+
+
+@pytest.mark.parametrize("shape", [(2, 2, 2, 2), (3, 2, 6, 5)])
+def test_bias_gradient_matches_unit_step_differences(shape):
+    """The loss <dy, y> is linear in the bias, so a unit step in coordinate o changes it by exactly
+    dbias[o] (up to rounding); the other gradients are those of the plain multiply."""
+    k, p, q, s = shape
+    rng = np.random.default_rng(32)
+    x, R, L, dy = _rand(rng, k, p, q, s, B=5)
+    bias = rng.standard_normal(k * s)
+    dx, dR, dL, db = oracle.bwd_bias(dy, x, R, L)
+    base = np.sum(dy * oracle.fwd_bias(x, R, L, bias))
+    for o in range(k * s):
+        step = bias.copy()
+        step[o] += 1.0
+        assert abs(np.sum(dy * oracle.fwd_bias(x, R, L, step)) - base - db[o]) < 1e-11
+    for got, want in zip((dx, dR, dL), oracle.bwd(dy, x, R, L)):
+        assert np.array_equal(got, want)
+    # brute force, and the all-ones upstream gradient counts the rows
+    assert np.allclose(db, [sum(dy[b, o] for b in range(5)) for o in range(k * s)], rtol=0, atol=1e-14)
+    assert np.array_equal(oracle.bwd_bias(np.ones_like(dy), x, R, L)[3], np.full(k * s, 5.0))
