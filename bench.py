@@ -139,6 +139,30 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True):
 
     fwd_ws_ms = float(np.mean([run_of(fwd_ws_only) for _ in range(3)])) if fneed else None
     fwd_ws_packed_ms = float(np.mean([run_of(fwd_ws_packed) for _ in range(3)])) if fneed else None
+    # affine layer: bias fused into the forward (where the kernel has the epilogue), bias gradient with the backward;
+    # beside them the unfused forms (the plain call, then a separate elementwise add / column sum by the framework)
+    biasd = torch.from_numpy(synth.quantize(synth.normal(4242, (sh.n_out,)), sh.dtype)).to(dev).to(dt)
+    dbias = torch.empty_like(biasd)
+
+    def fwd_bias_only(i):
+        xs, _, y, _ = sets[i % nsets]
+        binding.monarch_fwd_bias(xs, Rd, Ld, biasd, y, workspace=fws if fneed else None)
+
+    def fwd_then_add(i):
+        xs, _, y, _ = sets[i % nsets]
+        if fneed:
+            binding.monarch_fwd_ws(xs, Rd, Ld, y, workspace=fws)
+        else:
+            binding.monarch_fwd(xs, Rd, Ld, y)
+        y.add_(biasd)
+
+    def bwd_bias_only(i):
+        xs, dys, _, dx = sets[i % nsets]
+        binding.monarch_bwd_bias(dys, xs, Rd, Ld, dx, dR, dL, dbias, workspace=ws)
+
+    fwd_bias_ms = float(np.mean([run_of(fwd_bias_only) for _ in range(3)]))
+    fwd_then_add_ms = float(np.mean([run_of(fwd_then_add) for _ in range(3)]))
+    bwd_bias_ms = float(np.mean([run_of(bwd_bias_only) for _ in range(3)]))
     Mdense = torch.empty((sh.n_out, sh.n_in), dtype=Rd.dtype, device="cuda")
     to_dense_ms = float(np.mean([run_of(lambda i: binding.monarch_to_dense(Rd, Ld, Mdense)) for _ in range(3)]))
     dense_bytes = (sh.k * sh.q * sh.p + sh.k * sh.s * sh.q + sh.n_out * sh.n_in) * sh.esize
@@ -160,6 +184,8 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True):
         # monarch_fwd_ws (weights packed into a caller workspace, pack included); null when the shape has no such kernel
         "fwd_ws_ms": fwd_ws_ms, "fwd_ws_packed_ms": fwd_ws_packed_ms,  # the latter: pack pass skipped (weights unchanged)
         "fwd_ws_kernel": binding.monarch_kernel_name(2, sh.n_in, sh.k, sh.q, sh.s, code),
+        # monarch_fwd_bias / monarch_bwd_bias (affine layer); fwd_then_add_ms = forward with workspace + a separate torch add
+        "fwd_bias_ms": fwd_bias_ms, "fwd_then_add_ms": fwd_then_add_ms, "bwd_bias_ms": bwd_bias_ms,
         # monarch_to_dense: M written out as a dense (n_out, n_in) matrix; bytes = R + L read, M written
         "to_dense_ms": to_dense_ms, "to_dense_gbs": dense_bytes / (to_dense_ms * 1e-3) / 1e9,
         "fwd_kernel": binding.monarch_kernel_name(0, sh.n_in, sh.k, sh.q, sh.s, code),

@@ -105,6 +105,19 @@ int monarch_fwd_ws(const void* x, const void* R, const void* L, void* y,
                    monarch_dtype dtype, void* stream,
                    void* workspace, size_t workspace_bytes, unsigned flags);
 
+/* Forward of the affine layer built on the Monarch matrix:  y[b][o] = (x M^T)[b][o] + bias[o].
+ * Section 4 swaps a layer's dense weight matrix for a Monarch one and keeps the rest of the layer;
+ * the appendix on BERT pretraining lists the bias add as a step to fuse into the matrix product.
+ * Arguments as monarch_fwd_ws (same workspace, same flags); `bias` (k*s elements of `dtype`, device
+ * pointer, 16-byte aligned) may be NULL, and the call is then monarch_fwd_ws itself.  The bias is
+ * added to the fp32 accumulator before the single rounding to `dtype` in the kernels that have a
+ * bias epilogue (bf16 k = 4 wide blocks, fp32 m = 16, the shape-generic kernels); the bf16 m = 64
+ * kernel has none, there a second in-place pass adds the bias to the rounded y (two roundings). */
+int monarch_fwd_bias(const void* x, const void* R, const void* L, const void* bias, void* y,
+                     int64_t batch, int n_in, int k, int q, int s,
+                     monarch_dtype dtype, void* stream,
+                     void* workspace, size_t workspace_bytes, unsigned flags);
+
 /* Bytes of device scratch monarch_fwd_ws needs for this problem (0 when the shape has no
  * packed-weight kernel, and on invalid arguments). */
 size_t monarch_fwd_workspace_bytes(int64_t batch, int n_in, int k, int q, int s,
@@ -131,7 +144,21 @@ int monarch_bwd(const void* dy, const void* x, const void* R, const void* L,
                 monarch_dtype dtype, void* stream,
                 void* workspace, size_t workspace_bytes, unsigned flags);
 
-/* Bytes of device scratch monarch_bwd needs for this problem (0 on invalid arguments). */
+/* Backward of the affine layer: monarch_bwd plus the bias gradient
+ *   dbias[o] = sum_b dy[b][o]
+ * (the same appendix lists it as fused with the backward product).  `dbias` holds k*s elements, of
+ * `dtype`, or float with MONARCH_FLAG_WGRAD_F32; it is overwritten (zeros when batch == 0); NULL
+ * skips it, and the call is then monarch_bwd itself.  The sum runs in fp32 over fixed row chunks in
+ * a fixed order (bit-reproducible), as its own pass over dy ahead of the other kernels.  Same
+ * workspace as monarch_bwd. */
+int monarch_bwd_bias(const void* dy, const void* x, const void* R, const void* L,
+                     void* dx, void* dR, void* dL, void* dbias,
+                     int64_t batch, int n_in, int k, int q, int s,
+                     monarch_dtype dtype, void* stream,
+                     void* workspace, size_t workspace_bytes, unsigned flags);
+
+/* Bytes of device scratch monarch_bwd and monarch_bwd_bias need for this problem (never 0 for a
+ * valid problem; 0 on invalid arguments). */
 size_t monarch_bwd_workspace_bytes(int64_t batch, int n_in, int k, int q, int s,
                                    monarch_dtype dtype, unsigned flags);
 

@@ -29,7 +29,8 @@ MONARCH_FLAG_WS_PACKED = 8
 
 # every symbol include/monarch.h declares
 EXPORTS = (
-    "monarch_fwd", "monarch_fwd_ex", "monarch_fwd_ws", "monarch_fwd_workspace_bytes", "monarch_bwd",
+    "monarch_fwd", "monarch_fwd_ex", "monarch_fwd_ws", "monarch_fwd_bias", "monarch_fwd_workspace_bytes", "monarch_bwd",
+    "monarch_bwd_bias",
     "monarch_bwd_workspace_bytes",
     "monarch_to_dense", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy",
 )
@@ -59,6 +60,10 @@ def lib() -> ctypes.CDLL:
         L.monarch_fwd_ex.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp, cu]
         L.monarch_fwd_ws.restype = ci
         L.monarch_fwd_ws.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
+        L.monarch_fwd_bias.restype = ci
+        L.monarch_fwd_bias.argtypes = [vp, vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
+        L.monarch_bwd_bias.restype = ci
+        L.monarch_bwd_bias.argtypes = [vp] * 8 + [i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
         L.monarch_fwd_workspace_bytes.restype = sz
         L.monarch_fwd_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci, cu]
         L.monarch_bwd.restype = ci
@@ -243,3 +248,73 @@ def monarch_bwd(dy: torch.Tensor, x: torch.Tensor, R: torch.Tensor, L: torch.Ten
     if rc != MONARCH_OK:
         raise MonarchError(rc, "monarch_bwd")
     return dx, dR, dL
+
+
+def monarch_fwd_bias(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, bias: torch.Tensor,
+                     y: torch.Tensor | None = None, workspace: torch.Tensor | None = None, flags: int = 0,
+                     stream=None) -> torch.Tensor:
+    """y = x M^T + bias.  bias (k*s,) of the same dtype; the workspace is allocated when not given."""
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    dev, dt = x.device, x.dtype
+    _check(x, "x", (B, k * p), dt, dev)
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    _check(bias, "bias", (k * s,), dt, dev)
+    if y is None:
+        y = torch.empty((B, k * s), dtype=dt, device=dev)
+    _check(y, "y", (B, k * s), dt, dev)
+    need = monarch_fwd_workspace_bytes(B, k * p, k, q, s, _dtype_code(x), flags)
+    if workspace is None and need:
+        if flags & MONARCH_FLAG_WS_PACKED:
+            raise ValueError("MONARCH_FLAG_WS_PACKED needs the workspace of the earlier call")
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_ptr = workspace.data_ptr() if workspace is not None else 0
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(dev):
+        rc = lib().monarch_fwd_bias(x.data_ptr(), R.data_ptr(), L.data_ptr(), bias.data_ptr(), y.data_ptr(), B, k * p,
+                                    k, q, s, _dtype_code(x), _stream_ptr(stream), ws_ptr, ws_len, flags)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_fwd_bias")
+    return y
+
+
+def monarch_bwd_bias(dy: torch.Tensor, x: torch.Tensor, R: torch.Tensor, L: torch.Tensor,
+                     dx: torch.Tensor | None = None, dR: torch.Tensor | None = None, dL: torch.Tensor | None = None,
+                     dbias: torch.Tensor | None = None, workspace: torch.Tensor | None = None, flags: int = 0,
+                     stream=None):
+    """(dx, dR, dL, dbias) for upstream gradient dy (B, k*s).  Buffers are allocated when not given."""
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    dev, dt = x.device, x.dtype
+    _check(x, "x", (B, k * p), dt, dev)
+    _check(dy, "dy", (B, k * s), dt, dev)
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    gdt = torch.float32 if (flags & MONARCH_FLAG_WGRAD_F32) else dt
+    if dx is None:
+        dx = torch.empty_like(x)
+    if dR is None:
+        dR = torch.empty((k, q, p), dtype=gdt, device=dev)
+    if dL is None:
+        dL = torch.empty((k, s, q), dtype=gdt, device=dev)
+    if dbias is None:
+        dbias = torch.empty((k * s,), dtype=gdt, device=dev)
+    _check(dx, "dx", (B, k * p), dt, dev)
+    _check(dR, "dR", (k, q, p), gdt, dev)
+    _check(dL, "dL", (k, s, q), gdt, dev)
+    _check(dbias, "dbias", (k * s,), gdt, dev)
+    need = monarch_bwd_workspace_bytes(B, k * p, k, q, s, _dtype_code(x), flags)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_ptr = workspace.data_ptr() if workspace is not None else 0
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(dev):
+        rc = lib().monarch_bwd_bias(dy.data_ptr(), x.data_ptr(), R.data_ptr(), L.data_ptr(), dx.data_ptr(),
+                                    dR.data_ptr(), dL.data_ptr(), dbias.data_ptr(), B, k * p, k, q, s,
+                                    _dtype_code(x), _stream_ptr(stream), ws_ptr, ws_len, flags)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_bwd_bias")
+    return dx, dR, dL, dbias

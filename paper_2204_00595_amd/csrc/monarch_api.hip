@@ -46,6 +46,17 @@ Family pick_bwd(const Problem& pb)
     return FAM_NONE;
 }
 
+// Backward scratch: the kernel family's own area, then the partial rows of the bias gradient.
+size_t bwd_kernel_need(const Problem& pb, Family fam)
+{
+    return align_up(fam == FAM_MFMA ? mfma_bwd_workspace(pb) : generic_bwd_workspace(pb), 256);
+}
+size_t bwd_need(const Problem& pb, Family fam)
+{
+    if (fam == FAM_NONE) return (size_t)-1;
+    return bwd_kernel_need(pb, fam) + colsum_workspace(pb);
+}
+
 bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
 }  // namespace
@@ -101,21 +112,59 @@ int monarch_fwd_ws(const void* x, const void* R, const void* L, void* y, int64_t
     return mfma_fwd_ws(pb, x, R, L, y, workspace, (hipStream_t)stream);
 }
 
+int monarch_fwd_bias(const void* x, const void* R, const void* L, const void* bias, void* y, int64_t batch,
+                     int n_in, int k, int q, int s, monarch_dtype dtype, void* stream, void* workspace,
+                     size_t workspace_bytes, unsigned flags)
+{
+    if (!bias) return monarch_fwd_ws(x, R, L, y, batch, n_in, k, q, s, dtype, stream, workspace, workspace_bytes, flags);
+    Problem pb;
+    int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
+    if (rc) return rc;
+    if (flags & MONARCH_FLAG_WGRAD_F32) return MONARCH_ERR_INVALID;  // backward-only flag
+    if (!R || !L || ((!x || !y) && batch > 0)) return MONARCH_ERR_INVALID;
+    if (!aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(y, 16) || !aligned(bias, 16))
+        return MONARCH_ERR_INVALID;
+    pb.bias = bias;
+    hipStream_t st = (hipStream_t)stream;
+    const bool generic = (flags & MONARCH_FLAG_GENERIC) != 0;
+    if (!generic && mfma_fwd_ws_supported(pb)) {
+        if (!workspace || workspace_bytes < mfma_fwd_ws_workspace(pb) || !aligned(workspace, 256))
+            return MONARCH_ERR_WORKSPACE;
+        if (batch == 0) return MONARCH_OK;
+        rc = mfma_fwd_ws(pb, x, R, L, y, workspace, st);
+        if (rc || mfma_fwd_fuses_bias(pb, true)) return rc;
+        return launch_bias_add(pb, y, st);
+    }
+    pb.flags &= ~MONARCH_FLAG_WS_PACKED;  // no packed-weight kernel: nothing to reuse
+    const Family fam = pick_fwd(pb);
+    if (fam == FAM_NONE) return MONARCH_ERR_UNSUPPORTED;
+    if (batch == 0) return MONARCH_OK;
+    if (fam == FAM_GENERIC) return generic_fwd(pb, x, R, L, y, st);
+    rc = mfma_fwd(pb, x, R, L, y, st);
+    if (rc || mfma_fwd_fuses_bias(pb, false)) return rc;
+    return launch_bias_add(pb, y, st);
+}
+
 size_t monarch_bwd_workspace_bytes(int64_t batch, int n_in, int k, int q, int s, monarch_dtype dtype,
                                    unsigned flags)
 {
     Problem pb;
     if (make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags)) return 0;
-    switch (pick_bwd(pb)) {
-        case FAM_MFMA: return mfma_bwd_workspace(pb);
-        case FAM_GENERIC: return generic_bwd_workspace(pb);
-        default: return 0;
-    }
+    const size_t need = bwd_need(pb, pick_bwd(pb));
+    return need == (size_t)-1 ? 0 : need;
 }
 
 int monarch_bwd(const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR, void* dL,
                 int64_t batch, int n_in, int k, int q, int s, monarch_dtype dtype, void* stream,
                 void* workspace, size_t workspace_bytes, unsigned flags)
+{
+    return monarch_bwd_bias(dy, x, R, L, dx, dR, dL, nullptr, batch, n_in, k, q, s, dtype, stream, workspace,
+                            workspace_bytes, flags);
+}
+
+int monarch_bwd_bias(const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR, void* dL,
+                     void* dbias, int64_t batch, int n_in, int k, int q, int s, monarch_dtype dtype, void* stream,
+                     void* workspace, size_t workspace_bytes, unsigned flags)
 {
     Problem pb;
     int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
@@ -123,14 +172,23 @@ int monarch_bwd(const void* dy, const void* x, const void* R, const void* L, voi
     if (flags & MONARCH_FLAG_WS_PACKED) return MONARCH_ERR_INVALID;  // forward-with-workspace flag
     if (!R || !L || !dR || !dL || ((!dy || !x || !dx) && batch > 0)) return MONARCH_ERR_INVALID;
     if (!aligned(dy, 16) || !aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(dx, 16) ||
-        !aligned(dR, 16) || !aligned(dL, 16))
+        !aligned(dR, 16) || !aligned(dL, 16) || !aligned(dbias, 16))
         return MONARCH_ERR_INVALID;
     const Family fam = pick_bwd(pb);
     if (fam == FAM_NONE) return MONARCH_ERR_UNSUPPORTED;
-    const size_t need = fam == FAM_MFMA ? mfma_bwd_workspace(pb) : generic_bwd_workspace(pb);
-    if (need > 0 && (!workspace || workspace_bytes < need || !aligned(workspace, 256)))
-        return MONARCH_ERR_WORKSPACE;
+    const size_t need = bwd_need(pb, fam);
+    if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return MONARCH_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
+    if (dbias) {
+        void* cws = (char*)workspace + bwd_kernel_need(pb, fam);
+        if (batch > 0 && fam == FAM_MFMA && mfma_bwd_fuses_dbias(pb)) {
+            pb.dbias = dbias;  // computed at the tail of the backward's own launches
+            pb.colsum_ws = cws;
+        } else {
+            rc = launch_colsum(pb, dy, dbias, cws, st);
+            if (rc) return rc;
+        }
+    }
     if (fam == FAM_MFMA) return mfma_bwd(pb, dy, x, R, L, dx, dR, dL, workspace, st);
     return generic_bwd(pb, dy, x, R, L, dx, dR, dL, workspace, st);
 }

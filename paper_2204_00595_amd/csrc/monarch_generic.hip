@@ -4,6 +4,7 @@
 // the intermediate (Y1 / U of Section 3.3) lives in LDS only.
 #include "monarch_internal.h"
 #include "monarch_device.h"
+#include "monarch_colsum.h"
 
 namespace monarch {
 
@@ -104,39 +105,6 @@ int launch_f32_to_bf16(const float* src, uint16_t* dst, size_t n, hipStream_t st
 
 static constexpr int DENSE_LT = 8;
 static constexpr int DENSE_THREADS = 64;
-
-template <typename T, int CW> struct ColVec;
-template <> struct ColVec<float, 1> {
-    static __device__ __forceinline__ void load(const float* p, float* v) { v[0] = *p; }
-    static __device__ __forceinline__ void store(float* p, const float* v) { *p = v[0]; }
-};
-template <> struct ColVec<bf16_t, 1> {
-    static __device__ __forceinline__ void load(const bf16_t* p, float* v) { v[0] = bf16_to_f32(*p); }
-    static __device__ __forceinline__ void store(bf16_t* p, const float* v) { *p = f32_to_bf16(v[0]); }
-};
-template <> struct ColVec<float, 4> {
-    static __device__ __forceinline__ void load(const float* p, float* v)
-    {
-        const float4 t = *(const float4*)p;
-        v[0] = t.x, v[1] = t.y, v[2] = t.z, v[3] = t.w;
-    }
-    static __device__ __forceinline__ void store(float* p, const float* v) { *(float4*)p = make_float4(v[0], v[1], v[2], v[3]); }
-};
-template <> struct ColVec<bf16_t, 4> {
-    static __device__ __forceinline__ void load(const bf16_t* p, float* v)
-    {
-        const uint2 t = *(const uint2*)p;
-        v[0] = __uint_as_float(t.x << 16), v[1] = __uint_as_float(t.x & 0xffff0000u);
-        v[2] = __uint_as_float(t.y << 16), v[3] = __uint_as_float(t.y & 0xffff0000u);
-    }
-    static __device__ __forceinline__ void store(bf16_t* p, const float* v)
-    {
-        uint2 t;
-        t.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-        t.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
-        *(uint2*)p = t;
-    }
-};
 
 // The DENSE_JS waves of a workgroup share the same outputs and split the terms of the sum between
 // them (wave w takes terms w, w + DENSE_JS, ...): a wave's chain of dependent-latency loads is
@@ -253,6 +221,122 @@ int launch_to_dense(const Problem& pb, const void* R, const void* L, void* M, hi
     return pb.dtype == 0 ? launch_to_dense_t<float>(pb, R, L, M, st) : launch_to_dense_t<bf16_t>(pb, R, L, M, st);
 }
 
+// ------------------------------------------------------- bias: add and gradient ----
+//
+// y[b][o] += bias[o] in place, for the forward kernels that have no bias epilogue of their own; y is
+// walked as (row chunk) x (tile of 64 * CW columns) like dy in the column sums (monarch_colsum.h).
+template <typename T, int CW>
+__global__ void __launch_bounds__(64 * ROWCOL_WAVES)
+bias_add_kernel(T* __restrict__ y, const T* __restrict__ bias, int64_t B, int n_out, int col_tiles, int chunks)
+{
+    const int ct = blockIdx.x % col_tiles, ch = blockIdx.x / col_tiles;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = (ct * 64 + lane) * CW;
+    if (col >= n_out) return;
+    const int64_t rows_per = (B + chunks - 1) / chunks;
+    const int64_t r0 = ch * rows_per;
+    int64_t r1 = r0 + rows_per;
+    if (r1 > B) r1 = B;
+    float bv[CW];
+    ColVec<T, CW>::load(bias + col, bv);
+    int64_t r = r0 + wave;
+    for (; r + 3 * ROWCOL_WAVES < r1; r += 4 * ROWCOL_WAVES) {
+        float v[4][CW];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) ColVec<T, CW>::load(y + (size_t)(r + u * ROWCOL_WAVES) * n_out + col, v[u]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int e = 0; e < CW; ++e) v[u][e] += bv[e];
+            ColVec<T, CW>::store(y + (size_t)(r + u * ROWCOL_WAVES) * n_out + col, v[u]);
+        }
+    }
+    for (; r < r1; r += ROWCOL_WAVES) {
+        float v[CW];
+        ColVec<T, CW>::load(y + (size_t)r * n_out + col, v);
+#pragma unroll
+        for (int e = 0; e < CW; ++e) v[e] += bv[e];
+        ColVec<T, CW>::store(y + (size_t)r * n_out + col, v);
+    }
+}
+
+template <typename T>
+static void launch_bias_add_t(const Problem& pb, void* y, hipStream_t st)
+{
+    const int n_out = pb.n_out(), col_tiles = rowcol_col_tiles(n_out), chunks = rowcol_chunks(pb.B, n_out);
+    const dim3 grid((unsigned)(col_tiles * chunks)), block(64 * ROWCOL_WAVES);
+    if (rowcol_cw(n_out) == 4)
+        hipLaunchKernelGGL((bias_add_kernel<T, 4>), grid, block, 0, st, (T*)y, (const T*)pb.bias, pb.B, n_out, col_tiles, chunks);
+    else
+        hipLaunchKernelGGL((bias_add_kernel<T, 1>), grid, block, 0, st, (T*)y, (const T*)pb.bias, pb.B, n_out, col_tiles, chunks);
+}
+
+int launch_bias_add(const Problem& pb, void* y, hipStream_t st)
+{
+    if (pb.B == 0) return 0;
+    if (pb.dtype == 0) launch_bias_add_t<float>(pb, y, st);
+    else launch_bias_add_t<bf16_t>(pb, y, st);
+    return hip_status(hipGetLastError());
+}
+
+// dbias[o] = sum_b dy[b][o] as two kernels of its own (bodies in monarch_colsum.h); the k = 4 matrix-core
+// backward runs the same bodies at the tail of two of its own launches instead.
+size_t colsum_workspace(const Problem& pb)
+{
+    return align_up((size_t)rowcol_chunks(pb.B, pb.n_out()) * pb.n_out() * sizeof(float), 256);
+}
+
+template <typename T, int CW>
+__global__ void __launch_bounds__(64 * ROWCOL_WAVES) colsum_partial_kernel(ColsumJob cj)
+{
+    colsum_partial_body<T, CW>(cj, (int)blockIdx.x);
+}
+
+template <typename TO>
+__global__ void __launch_bounds__(1024) colsum_final_kernel(ColsumJob cj)
+{
+    colsum_final_body<TO, 16>(cj, (int)blockIdx.x);
+}
+
+ColsumJob make_colsum_job(const Problem& pb, const void* dy, void* dbias, void* ws)
+{
+    ColsumJob cj;
+    cj.dy = dy;
+    cj.part = (float*)ws;
+    cj.dbias = dbias;
+    cj.B = pb.B;
+    cj.n_out = pb.n_out();
+    cj.col_tiles = rowcol_col_tiles(cj.n_out);
+    cj.chunks = rowcol_chunks(pb.B, cj.n_out);
+    cj.out_f32 = pb.wgrad_f32() ? 1 : 0;
+    return cj;
+}
+
+// ws: colsum_workspace(pb) bytes.  dbias is fp32 when pb.wgrad_f32(), else of pb.dtype.
+int launch_colsum(const Problem& pb, const void* dy, void* dbias, void* ws, hipStream_t st)
+{
+    const int n_out = pb.n_out();
+    if (pb.B == 0) {
+        if (pb.wgrad_f32()) return launch_fill_zero_f32((float*)dbias, n_out, st);
+        return launch_fill_zero_u16((uint16_t*)dbias, n_out, st);
+    }
+    const ColsumJob cj = make_colsum_job(pb, dy, dbias, ws);
+    const dim3 grid((unsigned)colsum_partial_blocks(cj)), block(64 * ROWCOL_WAVES);
+    const bool cw4 = rowcol_cw(n_out) == 4;
+    if (pb.dtype == 0) {
+        if (cw4) hipLaunchKernelGGL((colsum_partial_kernel<float, 4>), grid, block, 0, st, cj);
+        else hipLaunchKernelGGL((colsum_partial_kernel<float, 1>), grid, block, 0, st, cj);
+    } else {
+        if (cw4) hipLaunchKernelGGL((colsum_partial_kernel<bf16_t, 4>), grid, block, 0, st, cj);
+        else hipLaunchKernelGGL((colsum_partial_kernel<bf16_t, 1>), grid, block, 0, st, cj);
+    }
+    if (hipGetLastError() != hipSuccess) return -4;
+    const dim3 g2((unsigned)colsum_final_blocks(cj));
+    if (cj.out_f32) hipLaunchKernelGGL(colsum_final_kernel<float>, g2, dim3(1024), 0, st, cj);
+    else hipLaunchKernelGGL(colsum_final_kernel<bf16_t>, g2, dim3(1024), 0, st, cj);
+    return hip_status(hipGetLastError());
+}
+
 // -------------------------------------------------------------------- forward ----
 //
 // LDS: xs[BM][n_in] and us[BM][k*q], both fp32.  Each thread owns one output column at a
@@ -261,7 +345,7 @@ int launch_to_dense(const Problem& pb, const void* R, const void* L, void* M, hi
 template <typename T, int BM>
 __global__ void __launch_bounds__(kThreads)
 generic_fwd_kernel(const T* __restrict__ x, const T* __restrict__ R, const T* __restrict__ L,
-                   T* __restrict__ y, int64_t B, int k, int p, int q, int s, int perm_b)
+                   const T* __restrict__ bias, T* __restrict__ y, int64_t B, int k, int p, int q, int s, int perm_b)
 {
     extern __shared__ float lds[];
     const int n_in = k * p, kq = k * q, n_out = k * s;
@@ -309,10 +393,11 @@ generic_fwd_kernel(const T* __restrict__ x, const T* __restrict__ R, const T* __
 #pragma unroll
             for (int b = 0; b < BM; ++b) acc[b] = fmaf(w, uc[b * kq + r], acc[b]);
         }
+        const float bo = bias ? Elem<T>::load(bias + o) : 0.f;
 #pragma unroll
         for (int b = 0; b < BM; ++b) {
             int64_t row = b0 + b;
-            if (row < B) Elem<T>::store(y + row * n_out + o, acc[b]);
+            if (row < B) Elem<T>::store(y + row * n_out + o, bias ? acc[b] + bo : acc[b]);
         }
     }
 }
@@ -463,7 +548,7 @@ static int launch_fwd(const Problem& pb, const void* x, const void* R, const voi
     if (e != hipSuccess) return -4;
     const int64_t grid = (pb.B + BM - 1) / BM;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, st, (const T*)x, (const T*)R,
-                       (const T*)L, (T*)y, pb.B, pb.k, pb.p, pb.q, pb.s, pb.perm_b() ? 1 : 0);
+                       (const T*)L, (const T*)pb.bias, (T*)y, pb.B, pb.k, pb.p, pb.q, pb.s, pb.perm_b() ? 1 : 0);
     return hip_status(hipGetLastError());
 }
 

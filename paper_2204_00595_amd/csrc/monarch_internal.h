@@ -11,6 +11,9 @@ struct Problem {
     int n_in, k, p, q, s;
     int dtype;       // 0 = f32, 1 = bf16
     unsigned flags;  // MONARCH_FLAG_*
+    const void* bias = nullptr;  // forward only: n_out values of `dtype` added to every output row (may be null)
+    void* dbias = nullptr;       // backward only: bias gradient wanted (fp32 when wgrad_f32(), else `dtype`)
+    void* colsum_ws = nullptr;   // backward only: colsum_workspace() bytes for the bias gradient's partial rows
     int n_out() const { return k * s; }
     int kq() const { return k * q; }
     size_t esize() const { return dtype == 0 ? 4 : 2; }
@@ -37,6 +40,14 @@ int generic_bwd(const Problem& pb, const void* dy, const void* x, const void* R,
 // dense form of the Monarch matrix, (k*s) x n_in row-major (any shape, both readings)
 int launch_to_dense(const Problem& pb, const void* R, const void* L, void* M, hipStream_t st);
 
+// bias: y += bias in place (shapes whose forward kernel has no bias epilogue; pb.bias must be set),
+// and dbias = column sums of dy (two deterministic passes through `ws` of colsum_workspace bytes)
+int launch_bias_add(const Problem& pb, void* y, hipStream_t st);
+size_t colsum_workspace(const Problem& pb);
+int launch_colsum(const Problem& pb, const void* dy, void* dbias, void* ws, hipStream_t st);
+struct ColsumJob;
+ColsumJob make_colsum_job(const Problem& pb, const void* dy, void* dbias, void* ws);
+
 // ---- MFMA kernels for the shapes they are instantiated for (bf16 / fp32 matrix cores) ----
 bool mfma_fwd_supported(const Problem& pb);
 bool mfma_bwd_supported(const Problem& pb);
@@ -49,6 +60,8 @@ bool mfma_fwd_ws_supported(const Problem& pb);
 size_t mfma_fwd_ws_workspace(const Problem& pb);
 const char* mfma_fwd_ws_name(const Problem& pb);
 int mfma_fwd_ws(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);
+bool mfma_fwd_fuses_bias(const Problem& pb, bool with_ws);
+bool mfma_bwd_fuses_dbias(const Problem& pb);  // the backward computes pb.dbias inside its own launches  // else the caller adds the bias in a second pass
 int mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L,
              void* dx, void* dR, void* dL, void* ws, hipStream_t st);
 
@@ -108,7 +121,9 @@ int wgrad_tiles(const WgradDesc& d);  // workgroups per batch chunk (0: shape no
 // both GEMMs over the same nz batch chunks (one launch when their tile shapes agree), then
 // one launch that sums the chunks of both and writes `out` (fp32 or bf16)
 int wgrad_gemm_pair(const WgradDesc& d0, const WgradDesc& d1, int nz, hipStream_t st);
-int wgrad_reduce_pair(const WgradDesc& d0, const WgradDesc& d1, bool out_f32, int nz, hipStream_t st);
+// `cj` (may be null): the second pass of the bias gradient runs as extra workgroups of the same launch
+int wgrad_reduce_pair(const WgradDesc& d0, const WgradDesc& d1, bool out_f32, int nz, hipStream_t st,
+                      const ColsumJob* cj = nullptr);
 
 // ---- small utility launches shared by the families ----
 int launch_fill_zero_f32(float* p, size_t n, hipStream_t st);

@@ -39,6 +39,16 @@ int mfma_fwd_ws(const Problem& pb, const void* x, const void* R, const void* L, 
     return -2;
 }
 
+// Which of the forward kernels add pb.bias in their own epilogue (the others need launch_bias_add).
+bool mfma_fwd_fuses_bias(const Problem& pb, bool with_ws)
+{
+    if (with_ws && fwd_frag_supported(pb)) return true;
+    if (with_ws && sq64_supported(pb)) return false;
+    return !fwd_wide_supported(pb) && !sq64_supported(pb) && sq16_supported(pb);
+}
+
+bool mfma_bwd_fuses_dbias(const Problem& pb) { return bwd_wide_supported(pb); }
+
 bool mfma_bwd_supported(const Problem& pb) { return bwd_wide_supported(pb) || bwd_sq64_supported(pb) || sq16_supported(pb); }
 size_t mfma_bwd_workspace(const Problem& pb)
 {

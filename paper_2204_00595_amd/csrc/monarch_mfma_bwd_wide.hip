@@ -18,6 +18,7 @@
 //             (monarch_mfma_wgrad.hip), split over the batch, then one reduction pass.
 #include "monarch_internal.h"
 #include "monarch_mfma_common.h"
+#include "monarch_colsum.h"
 #include "monarch_mfma_stage1.h"
 
 namespace monarch {
@@ -38,8 +39,14 @@ namespace {
 //       (dx stage, 16x16x32: R transposed, K-slots in the order the chained accumulators hold dY1)
 __global__ void __launch_bounds__(256)
 prep_frag_kernel(const uint16_t* __restrict__ L, const uint16_t* __restrict__ R, uint16_t* __restrict__ XF,
-                 uint16_t* __restrict__ LF, uint16_t* __restrict__ RF, int P, int Q, int S, int JG, int IG)
+                 uint16_t* __restrict__ LF, uint16_t* __restrict__ RF, int P, int Q, int S, int JG, int IG,
+                 ColsumJob cj, int nprep)
 {
+    // workgroups past the re-layout run the first pass of the bias gradient (column sums of dy)
+    if ((int)blockIdx.x >= nprep) {
+        colsum_partial_body<bf16_t, 4>(cj, (int)blockIdx.x - nprep);
+        return;
+    }
     const int nR = 4 * Q * P / 8, nL = 4 * S * Q / 8;  // pieces per array
     int pc = blockIdx.x * 256 + threadIdx.x;
     uint16_t v[8];
@@ -462,8 +469,12 @@ int bwd_wide(const Problem& pb, const void* dy, const void* x, const void* R, co
         return f32out ? launch_fill_zero_f32((float*)dL, pb.n_L(), st) : launch_fill_zero_u16((uint16_t*)dL, pb.n_L(), st);
     }
     const size_t pieces = (2 * pb.n_R() + pb.n_L()) / 8;
-    hipLaunchKernelGGL(prep_frag_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st, (const uint16_t*)L,
-                       (const uint16_t*)R, XF, LF, RF, pb.p, pb.q, pb.s, e->jg, e->ig);
+    const int nprep = (int)((pieces + 255) / 256);
+    ColsumJob cj{};
+    const bool want_db = pb.dbias != nullptr;
+    if (want_db) cj = make_colsum_job(pb, dy, pb.dbias, pb.colsum_ws);
+    hipLaunchKernelGGL(prep_frag_kernel, dim3((unsigned)(nprep + (want_db ? colsum_partial_blocks(cj) : 0))), dim3(256), 0,
+                       st, (const uint16_t*)L, (const uint16_t*)R, XF, LF, RF, pb.p, pb.q, pb.s, e->jg, e->ig, cj, nprep);
     if (hipGetLastError() != hipSuccess) return -4;
     int rc = e->fn(pb, dy, x, XF, LF, RF, dx, Y1ws, dY1ws, st);
     if (rc) return rc;
@@ -475,7 +486,7 @@ int bwd_wide(const Problem& pb, const void* dy, const void* x, const void* R, co
     dl.rows_per_chunk = dr.rows_per_chunk = pl.rows_per_chunk;
     rc = wgrad_gemm_pair(dl, dr, pl.nz, st);
     if (rc) return rc;
-    return wgrad_reduce_pair(dl, dr, f32out, pl.nz, st);
+    return wgrad_reduce_pair(dl, dr, f32out, pl.nz, st, want_db ? &cj : nullptr);
 }
 
 }  // namespace monarch

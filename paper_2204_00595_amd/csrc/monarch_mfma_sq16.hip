@@ -56,9 +56,10 @@ __device__ __forceinline__ void stage_weights(const float* __restrict__ W, unsig
     }
 }
 
+template <bool BIAS>
 __global__ void __launch_bounds__(512)
 fwd_sq16_kernel(const float* __restrict__ x, const float* __restrict__ R, const float* __restrict__ L,
-                float* __restrict__ y, int64_t B, int64_t ntiles)
+                const float* __restrict__ bias, float* __restrict__ y, int64_t B, int64_t ntiles)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char ldsb[];
     const int tid = threadIdx.x;
@@ -78,6 +79,8 @@ fwd_sq16_kernel(const float* __restrict__ x, const float* __restrict__ R, const 
     };
     f32x4 xa[16];
     if (tile < ntiles) load_x(tile, xa);  // in flight while the weights are staged
+    f32x4 bv = {0.f, 0.f, 0.f, 0.f};  // the lane stores y[b][4*lane .. 4*lane + 3] of every row
+    if constexpr (BIAS) bv = *reinterpret_cast<const f32x4*>(bias + 4 * lane);
     stage_weights(R, Rop, tid, 512);
     stage_weights(L, Lop, tid, 512);
     __syncthreads();
@@ -123,7 +126,8 @@ fwd_sq16_kernel(const float* __restrict__ x, const float* __restrict__ R, const 
         const int64_t b0 = tile * 16;
 #pragma unroll
         for (int k2 = 0; k2 < 16; ++k2) {
-            const f32x4 v = *reinterpret_cast<const f32x4*>(T + t_off(k2, lane));
+            f32x4 v = *reinterpret_cast<const f32x4*>(T + t_off(k2, lane));
+            if constexpr (BIAS) v += bv;
             if (b0 + k2 < B) stg128f_nt(y + (b0 + k2) * N16 + 4 * lane, v);
         }
         wave_lds_fence();  // the tile is free again for the next step 1
@@ -356,14 +360,14 @@ bool sq16_supported(const Problem& pb)
 int fwd_sq16(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
 {
     if (!sq16_supported(pb)) return -2;
-    auto kern = fwd_sq16_kernel;
+    auto kern = pb.bias ? fwd_sq16_kernel<true> : fwd_sq16_kernel<false>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ16_LDS) != hipSuccess)
         return -4;
     const int64_t ntiles = (pb.B + 15) / 16;
     int64_t grid = (ntiles + SQ16_WAVES - 1) / SQ16_WAVES;
     if (grid > 256) grid = 256;  // one persistent workgroup per CU
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), SQ16_LDS, st, (const float*)x, (const float*)R,
-                       (const float*)L, (float*)y, pb.B, ntiles);
+                       (const float*)L, (const float*)pb.bias, (float*)y, pb.B, ntiles);
     return hip_status(hipGetLastError());
 }
 

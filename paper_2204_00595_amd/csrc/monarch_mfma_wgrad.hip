@@ -17,6 +17,7 @@
 // output type.
 #include "monarch_internal.h"
 #include "monarch_mfma_common.h"
+#include "monarch_colsum.h"
 
 namespace monarch {
 
@@ -258,10 +259,16 @@ wgrad_gemm_kernel(WgradDesc d0, WgradDesc d1, int tiles0, int tiles)
 // out[g][m][col(n)] = sum_z P[z][g][m][n];  col(n) = (n % seg_w) * (N / seg_w) + n / seg_w
 // (identity when seg_w == N).  Blocks [0, blocks0) reduce d0, the rest d1; one element per
 // thread, the chunk loop unrolled so that eight loads are in flight.
+// Blocks from `blocks01` on (when cj.part is set) run the second pass of the bias gradient instead.
 template <bool OUT_F32>
 __global__ void __launch_bounds__(256)
-wgrad_reduce_kernel(WgradDesc d0, WgradDesc d1, int blocks0, int nz)
+wgrad_reduce_kernel(WgradDesc d0, WgradDesc d1, int blocks0, int nz, ColsumJob cj, int blocks01)
 {
+    if ((int)blockIdx.x >= blocks01) {
+        if (OUT_F32) colsum_final_body<float, 4>(cj, (int)blockIdx.x - blocks01);
+        else colsum_final_body<bf16_t, 4>(cj, (int)blockIdx.x - blocks01);
+        return;
+    }
     const bool first = (int)blockIdx.x < blocks0;
     const WgradDesc& d = first ? d0 : d1;
     const size_t total = (size_t)d.G * d.M * d.N;
@@ -350,14 +357,18 @@ int wgrad_gemm_pair(const WgradDesc& d0, const WgradDesc& d1, int nz, hipStream_
     return rc ? rc : launch_gemm_tile(tm1, tn1, d1, nullptr, nz, st);
 }
 
-int wgrad_reduce_pair(const WgradDesc& d0, const WgradDesc& d1, bool out_f32, int nz, hipStream_t st)
+int wgrad_reduce_pair(const WgradDesc& d0, const WgradDesc& d1, bool out_f32, int nz, hipStream_t st, const ColsumJob* cj)
 {
     const size_t b0 = ((size_t)d0.G * d0.M * d0.N + 255) / 256, b1 = ((size_t)d1.G * d1.M * d1.N + 255) / 256;
-    if (b0 + b1 > 0x7fffffffULL) return -2;
+    ColsumJob job{};
+    if (cj) job = *cj;
+    const size_t b2 = cj ? (size_t)colsum_final_blocks(job) : 0;
+    if (b0 + b1 + b2 > 0x7fffffffULL) return -2;
+    const dim3 grid((unsigned)(b0 + b1 + b2));
     if (out_f32)
-        hipLaunchKernelGGL(wgrad_reduce_kernel<true>, dim3((unsigned)(b0 + b1)), dim3(256), 0, st, d0, d1, (int)b0, nz);
+        hipLaunchKernelGGL(wgrad_reduce_kernel<true>, grid, dim3(256), 0, st, d0, d1, (int)b0, nz, job, (int)(b0 + b1));
     else
-        hipLaunchKernelGGL(wgrad_reduce_kernel<false>, dim3((unsigned)(b0 + b1)), dim3(256), 0, st, d0, d1, (int)b0, nz);
+        hipLaunchKernelGGL(wgrad_reduce_kernel<false>, grid, dim3(256), 0, st, d0, d1, (int)b0, nz, job, (int)(b0 + b1));
     return hip_status(hipGetLastError());
 }
 

@@ -271,6 +271,106 @@ def test_mlp_pair_end_to_end(B):
             ["h", "y", "dh", "dR2", "dL2", "dx", "dR1", "dL1"])
 
 
+# ---------------------------------------------------------------- affine layer ----
+
+def run_fwd_bias(B, sh, x, R, L, bias, flags=0):
+    ybuf, y = guarded((x.shape[0], sh.n_out), tdtype(sh.dtype))
+    code = 0 if sh.dtype == "f32" else 1
+    need = B.monarch_fwd_workspace_bytes(x.shape[0], sh.n_in, sh.k, sh.q, sh.s, code, flags)
+    wbuf = torch.full((need + 512 + 2 * GUARD,), 0x5A, dtype=torch.uint8, device="cuda")
+    off = (-(wbuf.data_ptr() + GUARD)) % 256 + GUARD
+    B.monarch_fwd_bias(dev(x, sh.dtype), dev(R, sh.dtype), dev(L, sh.dtype), dev(bias, sh.dtype), y,
+                       workspace=wbuf[off:off + need] if need else None, flags=flags)
+    torch.cuda.synchronize()
+    assert bool((wbuf[:off] == 0x5A).all()) and bool((wbuf[off + need:] == 0x5A).all()), "workspace: wrote out of bounds"
+    check_guard(ybuf, "y")
+    out = host(y)
+    assert np.isfinite(out).all(), "y has unwritten or non-finite entries"
+    return out
+
+
+def run_bwd_bias(B, sh, dy, x, R, L, flags=0):
+    dt = tdtype(sh.dtype)
+    gdt = torch.float32 if (flags & B.MONARCH_FLAG_WGRAD_F32) else dt
+    bx, dx = guarded((x.shape[0], sh.n_in), dt)
+    bR, dR = guarded(R.shape, gdt)
+    bL, dL = guarded(L.shape, gdt)
+    bb, db = guarded((sh.n_out,), gdt)
+    B.monarch_bwd_bias(dev(dy, sh.dtype), dev(x, sh.dtype), dev(R, sh.dtype), dev(L, sh.dtype), dx, dR, dL, db, flags=flags)
+    torch.cuda.synchronize()
+    for buf, name in ((bx, "dx"), (bR, "dR"), (bL, "dL"), (bb, "dbias")):
+        check_guard(buf, name)
+    outs = [host(t) for t in (dx, dR, dL, db)]
+    for o, name in zip(outs, ("dx", "dR", "dL", "dbias")):
+        assert np.isfinite(o).all(), name + " has unwritten or non-finite entries"
+    return outs
+
+
+def make_bias(sh):
+    return synth.quantize(synth.normal(synth.tensor_seed(sh.config, "x") + 991, (sh.n_out,)), sh.dtype)
+
+
+@pytest.mark.parametrize("generic", [False, True], ids=["dispatch", "generic"])
+@pytest.mark.parametrize("case", SMALL + [("odd_n_out", "f32", 300, 3, 4, 5, 7), ("odd_n_out_bf16", "bf16", 130, 3, 4, 5, 7)],
+                         ids=lambda c: c[0])
+def test_affine_layer_small_shapes(B, case, generic):
+    """monarch_fwd_bias / monarch_bwd_bias against the oracle's affine layer (bias of unit variance)."""
+    sh = small_shape(case)
+    flags = B.MONARCH_FLAG_GENERIC if generic else 0
+    x, R, L, dy = synth.make_inputs(sh)
+    bias = make_bias(sh)
+    y = run_fwd_bias(B, sh, x, R, L, bias, flags)
+    compare(sh, [y], [oracle.fwd_bias(x, R, L, bias)], ["y"])
+    want = oracle.bwd_bias(dy, x, R, L)
+    compare(sh, run_bwd_bias(B, sh, dy, x, R, L, flags), want, ["dx", "dR", "dL", "dbias"])
+    got32 = run_bwd_bias(B, sh, dy, x, R, L, flags | B.MONARCH_FLAG_WGRAD_F32)
+    compare(sh, got32, want, ["dx", "dR32", "dL32", "dbias32"])
+    # fp32 bias gradient: a sum of B exactly representable values in fp32, error far below the storage rounding
+    assert oracle.rel_fro(got32[3], want[3]) <= 1e-5
+
+
+def test_affine_layer_edge_cases(B):
+    # x = 0: every output row is the bias, bit for bit (0 + bias is exact)
+    for case in (("k4_192", "bf16", 70, 4, 192, 192, 192), ("sq_m16", "f32", 33, 16, 16, 16, 16), ("rect", "f32", 5, 3, 2, 6, 5),
+                 ("sq_m64", "bf16", 33, 64, 64, 64, 64)):
+        sh = small_shape(case)
+        x, R, L, dy = synth.make_inputs(sh)
+        bias = make_bias(sh)
+        y = run_fwd_bias(B, sh, np.zeros_like(x), R, L, bias)
+        assert np.array_equal(y, np.tile(bias.astype(np.float64), (sh.B, 1))), sh.name
+        # all-ones upstream gradient: the bias gradient counts the rows
+        db = run_bwd_bias(B, sh, np.ones_like(dy), x, R, L, B.MONARCH_FLAG_WGRAD_F32)[3]
+        assert np.array_equal(db, np.full(sh.n_out, float(sh.B))), sh.name
+    # empty batch: the bias gradient is zero-filled like the weight gradients
+    sh0 = synth.Shape("empty", "f32", 0, 4, 8, 8, 8)
+    x0, R0, L0, dy0 = synth.make_inputs(sh0)
+    assert run_fwd_bias(B, sh0, x0, R0, L0, make_bias(sh0)).shape == (0, 32)
+    dx, dR, dL, db = run_bwd_bias(B, sh0, dy0, x0, R0, L0)
+    assert not dR.any() and not dL.any() and not db.any()
+    # packed weights left in the workspace are reused with a different bias
+    sh = small_shape(("k4_192", "bf16", 200, 4, 192, 192, 192))
+    x, R, L, _ = synth.make_inputs(sh)
+    need = B.monarch_fwd_workspace_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, 1)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    b1, b2 = make_bias(sh), -make_bias(sh)
+    y1 = B.monarch_fwd_bias(dev(x, "bf16"), dev(R, "bf16"), dev(L, "bf16"), dev(b1, "bf16"), workspace=ws)
+    nanw = torch.full(R.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+    y2 = B.monarch_fwd_bias(dev(x, "bf16"), nanw, nanw.clone(), dev(b2, "bf16"), workspace=ws, flags=B.MONARCH_FLAG_WS_PACKED)
+    torch.cuda.synchronize()
+    compare(sh, [host(y1), host(y2)], [oracle.fwd_bias(x, R, L, b1), oracle.fwd_bias(x, R, L, b2)], ["y1", "y2"])
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_affine_layer_full_size(B, name):
+    sh = synth.WORKLOADS[name]
+    x, R, L, dy = synth.make_inputs(sh)
+    bias = make_bias(sh)
+    y = run_fwd_bias(B, sh, x, R, L, bias)
+    compare(sh, [y], [oracle.fwd_bias(x, R, L, bias)], ["y"])
+    got = run_bwd_bias(B, sh, dy, x, R, L)
+    compare(sh, got, oracle.bwd_bias(dy, x, R, L), ["dx", "dR", "dL", "dbias"])
+
+
 # Dense form of M: every entry is one fp32 sum of at most q products, rounded once to the storage type
 # (relative 2^-24 / 2^-9 per entry), so the bound is much tighter than for the multiply.
 DENSE_TOL = {"f32": 1e-6, "bf16": 3e-3}

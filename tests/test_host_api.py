@@ -139,6 +139,46 @@ def test_backward_rejects_bad_arguments_without_a_gpu(binding):
     assert binding.monarch_bwd_workspace_bytes(1, 769, 4, 192, 192, 1, 0) == 0
 
 
+def test_affine_layer_calls_reject_bad_arguments_without_a_gpu(binding):
+    L = binding.lib()
+    p = 4096  # never dereferenced
+    need = binding.monarch_fwd_workspace_bytes(0, 768, 4, 192, 192, 1)
+
+    def fwd(x=p, R=p, Lp=p, bias=p, y=p, ws=p, ws_bytes=need, flags=0, batch=0, n_in=768, k=4, q=192, s=192, dtype=1):
+        return L.monarch_fwd_bias(x, R, Lp, bias, y, batch, n_in, k, q, s, dtype, None, ws, ws_bytes, flags)
+
+    assert fwd() == binding.MONARCH_OK
+    assert fwd(bias=None) == binding.MONARCH_OK                      # the plain forward with workspace
+    assert fwd(bias=p + 8) == binding.MONARCH_ERR_INVALID            # not 16-byte aligned
+    assert fwd(R=None) == binding.MONARCH_ERR_INVALID
+    assert fwd(y=None, batch=3) == binding.MONARCH_ERR_INVALID
+    assert fwd(n_in=770) == binding.MONARCH_ERR_INVALID
+    assert fwd(flags=binding.MONARCH_FLAG_WGRAD_F32) == binding.MONARCH_ERR_INVALID
+    assert fwd(ws=None) == binding.MONARCH_ERR_WORKSPACE
+    assert fwd(ws_bytes=need - 1) == binding.MONARCH_ERR_WORKSPACE
+    assert fwd(ws=None, ws_bytes=0, flags=binding.MONARCH_FLAG_GENERIC) == binding.MONARCH_OK
+    assert fwd(ws=None, ws_bytes=0, n_in=6, k=2, q=4, s=2, dtype=0) == binding.MONARCH_OK
+
+    bneed = binding.monarch_bwd_workspace_bytes(1, 768, 4, 192, 192, 1, 0)
+
+    def bwd(ptrs=(p,) * 8, batch=1, ws=p, ws_bytes=bneed, flags=0, n_in=768):
+        return L.monarch_bwd_bias(*ptrs, batch, n_in, 4, 192, 192, 1, None, ws, ws_bytes, flags)
+
+    for bad in range(7):  # dbias (index 7) may be NULL, the others may not
+        ptrs = [p] * 8
+        ptrs[bad] = None
+        assert bwd(tuple(ptrs)) == binding.MONARCH_ERR_INVALID
+    assert bwd((p,) * 7 + (p + 4,)) == binding.MONARCH_ERR_INVALID   # dbias not 16-byte aligned
+    assert bwd(ws=None) == binding.MONARCH_ERR_WORKSPACE
+    assert bwd(ws_bytes=bneed - 1) == binding.MONARCH_ERR_WORKSPACE
+    assert bwd(n_in=770) == binding.MONARCH_ERR_INVALID
+    assert bwd(flags=binding.MONARCH_FLAG_WS_PACKED) == binding.MONARCH_ERR_INVALID
+    # the bias gradient's partial rows are part of the backward workspace: it grows with the batch up to 128 chunks
+    small = binding.monarch_bwd_workspace_bytes(64, 768, 4, 192, 192, 1, binding.MONARCH_FLAG_GENERIC)
+    big = binding.monarch_bwd_workspace_bytes(64 * 128, 768, 4, 192, 192, 1, binding.MONARCH_FLAG_GENERIC)
+    assert big - small >= 127 * 768 * 4
+
+
 def test_stream_copy_rejects_bad_arguments_without_a_gpu(binding):
     L = binding.lib()
     assert L.monarch_stream_copy(None, None, 0, None) == binding.MONARCH_OK          # empty copy: no-op
