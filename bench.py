@@ -58,7 +58,7 @@ def _events(n):
     return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
 
 
-def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True):
+def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True, with_extras: bool = True):
     import numpy as np
     import torch
     from paper_2204_00595_amd import binding, synth
@@ -139,33 +139,36 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True):
 
     fwd_ws_ms = float(np.mean([run_of(fwd_ws_only) for _ in range(3)])) if fneed else None
     fwd_ws_packed_ms = float(np.mean([run_of(fwd_ws_packed) for _ in range(3)])) if fneed else None
-    # affine layer: bias fused into the forward (where the kernel has the epilogue), bias gradient with the backward;
-    # beside them the unfused forms (the plain call, then a separate elementwise add / column sum by the framework)
-    biasd = torch.from_numpy(synth.quantize(synth.normal(4242, (sh.n_out,)), sh.dtype)).to(dev).to(dt)
-    dbias = torch.empty_like(biasd)
+    fwd_bias_ms = fwd_then_add_ms = bwd_bias_ms = to_dense_ms = to_dense_gbs = None
+    if with_extras:
+        # affine layer: bias fused into the forward (where the kernel has the epilogue), bias gradient with the backward;
+        # beside them the unfused forms (the plain call, then a separate elementwise add / column sum by the framework)
+        biasd = torch.from_numpy(synth.quantize(synth.normal(4242, (sh.n_out,)), sh.dtype)).to(dev).to(dt)
+        dbias = torch.empty_like(biasd)
 
-    def fwd_bias_only(i):
-        xs, _, y, _ = sets[i % nsets]
-        binding.monarch_fwd_bias(xs, Rd, Ld, biasd, y, workspace=fws if fneed else None)
+        def fwd_bias_only(i):
+            xs, _, y, _ = sets[i % nsets]
+            binding.monarch_fwd_bias(xs, Rd, Ld, biasd, y, workspace=fws if fneed else None)
 
-    def fwd_then_add(i):
-        xs, _, y, _ = sets[i % nsets]
-        if fneed:
-            binding.monarch_fwd_ws(xs, Rd, Ld, y, workspace=fws)
-        else:
-            binding.monarch_fwd(xs, Rd, Ld, y)
-        y.add_(biasd)
+        def fwd_then_add(i):
+            xs, _, y, _ = sets[i % nsets]
+            if fneed:
+                binding.monarch_fwd_ws(xs, Rd, Ld, y, workspace=fws)
+            else:
+                binding.monarch_fwd(xs, Rd, Ld, y)
+            y.add_(biasd)
 
-    def bwd_bias_only(i):
-        xs, dys, _, dx = sets[i % nsets]
-        binding.monarch_bwd_bias(dys, xs, Rd, Ld, dx, dR, dL, dbias, workspace=ws)
+        def bwd_bias_only(i):
+            xs, dys, _, dx = sets[i % nsets]
+            binding.monarch_bwd_bias(dys, xs, Rd, Ld, dx, dR, dL, dbias, workspace=ws)
 
-    fwd_bias_ms = float(np.mean([run_of(fwd_bias_only) for _ in range(3)]))
-    fwd_then_add_ms = float(np.mean([run_of(fwd_then_add) for _ in range(3)]))
-    bwd_bias_ms = float(np.mean([run_of(bwd_bias_only) for _ in range(3)]))
-    Mdense = torch.empty((sh.n_out, sh.n_in), dtype=Rd.dtype, device="cuda")
-    to_dense_ms = float(np.mean([run_of(lambda i: binding.monarch_to_dense(Rd, Ld, Mdense)) for _ in range(3)]))
-    dense_bytes = (sh.k * sh.q * sh.p + sh.k * sh.s * sh.q + sh.n_out * sh.n_in) * sh.esize
+        fwd_bias_ms = float(np.mean([run_of(fwd_bias_only) for _ in range(3)]))
+        fwd_then_add_ms = float(np.mean([run_of(fwd_then_add) for _ in range(3)]))
+        bwd_bias_ms = float(np.mean([run_of(bwd_bias_only) for _ in range(3)]))
+        Mdense = torch.empty((sh.n_out, sh.n_in), dtype=Rd.dtype, device="cuda")
+        to_dense_ms = float(np.mean([run_of(lambda i: binding.monarch_to_dense(Rd, Ld, Mdense)) for _ in range(3)]))
+        dense_bytes = (sh.k * sh.q * sh.p + sh.k * sh.s * sh.q + sh.n_out * sh.n_in) * sh.esize
+        to_dense_gbs = dense_bytes / (to_dense_ms * 1e-3) / 1e9
     fwd_runs = [run_of(fwd_only) for _ in range(3)]
     bwd_runs = [run_of(bwd_only) for _ in range(3)]
     fwd_ms, bwd_ms = float(np.mean(fwd_runs)), float(np.mean(bwd_runs))
@@ -187,7 +190,7 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True):
         # monarch_fwd_bias / monarch_bwd_bias (affine layer); fwd_then_add_ms = forward with workspace + a separate torch add
         "fwd_bias_ms": fwd_bias_ms, "fwd_then_add_ms": fwd_then_add_ms, "bwd_bias_ms": bwd_bias_ms,
         # monarch_to_dense: M written out as a dense (n_out, n_in) matrix; bytes = R + L read, M written
-        "to_dense_ms": to_dense_ms, "to_dense_gbs": dense_bytes / (to_dense_ms * 1e-3) / 1e9,
+        "to_dense_ms": to_dense_ms, "to_dense_gbs": to_dense_gbs,
         "fwd_kernel": binding.monarch_kernel_name(0, sh.n_in, sh.k, sh.q, sh.s, code),
         "bwd_kernel": binding.monarch_kernel_name(1, sh.n_in, sh.k, sh.q, sh.s, code),
         "fwd_tflops": sh.fwd_flops() / (fwd_ms * 1e-3) / 1e12,
@@ -263,6 +266,7 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other workloads (extra keys)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the timings of monarch_to_dense and of the bias calls")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.stderr.write("bench.py: this library runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -275,7 +279,7 @@ def main():
         sys.exit(2)
     binding.lib()
 
-    sh, r = run_workload(args.workload, args.steps, args.warmup, with_dense=not args.no_dense)
+    sh, r = run_workload(args.workload, args.steps, args.warmup, with_dense=not args.no_dense, with_extras=not args.no_extras)
     flops = sh.fwd_flops() + sh.bwd_flops()
     nbytes = sh.fwd_bytes() + sh.bwd_bytes()
     step_s = r["ms_per_step"] * 1e-3
@@ -320,7 +324,7 @@ def main():
         for name in ("sq256_f32", "sq256_f32_big", "gpt2s_fc1", "sq4096", "gpt2m_fc1", "gpt2m_fc2"):
             if name != args.workload:
                 others[name] = run_workload(name, max(5, args.steps // 2), max(2, args.warmup // 2),
-                                            with_dense=not args.no_dense)[1]
+                                            with_dense=not args.no_dense, with_extras=not args.no_extras)[1]
         line["other_workloads"] = others
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(args.workload)
