@@ -63,7 +63,7 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True, wi
     import torch
     from paper_2204_00595_amd import binding, synth
 
-    sh = synth.WORKLOADS[name]
+    sh = synth.workload(name)
     dt = torch.float32 if sh.dtype == "f32" else torch.bfloat16
     code = 0 if sh.dtype == "f32" else 1
     dev = torch.device("cuda:0")
@@ -266,6 +266,7 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other workloads (extra keys)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--layers", action="store_true", help="also time the other layer shapes of the same models (extra keys)")
     ap.add_argument("--no-extras", action="store_true", help="skip the timings of monarch_to_dense and of the bias calls")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -326,6 +327,11 @@ def main():
                 others[name] = run_workload(name, max(5, args.steps // 2), max(2, args.warmup // 2),
                                             with_dense=not args.no_dense, with_extras=not args.no_extras)[1]
         line["other_workloads"] = others
+    if args.layers:
+        from paper_2204_00595_amd import synth as _synth
+        line["model_layers"] = {name: run_workload(name, max(5, args.steps // 2), max(2, args.warmup // 2),
+                                                   with_dense=not args.no_dense, with_extras=not args.no_extras)[1]
+                                for name in _synth.MODEL_LAYERS}
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(line), flush=True)

@@ -379,6 +379,9 @@ const Entry kTable[] = {
     {256, 256, 1024, 4, 4, launch_data<BwdWide<256, 256, 1024, 4, 128, 4>>},
     {1024, 256, 256, 4, 4, launch_data<BwdWide<1024, 256, 256, 4, 128, 4>>},
     {768, 192, 192, 6, 4, launch_data<BwdWide<768, 192, 192, 6, 192, 4>>},
+    {256, 256, 256, 4, 4, launch_data<BwdWide<256, 256, 256, 4, 128, 4>>},
+    {192, 192, 576, 6, 4, launch_data<BwdWide<192, 192, 576, 6, 192, 4>>},
+    {256, 256, 768, 4, 4, launch_data<BwdWide<256, 256, 768, 4, 128, 4>>},
     {64, 64, 64, 2, 4, launch_data<BwdWide<64, 64, 64, 2, 64, 4>>},
     {64, 64, 128, 2, 4, launch_data<BwdWide<64, 64, 128, 2, 64, 4>>},
     {128, 64, 64, 2, 4, launch_data<BwdWide<128, 64, 64, 2, 64, 4>>},

@@ -291,6 +291,9 @@ const Entry kTable[] = {
     {256, 256, 1024, launch<FwdFrag<256, 256, 1024, 4, 8>>},  // GPT-2 medium fc1 1024 -> 4096
     {1024, 256, 256, launch<FwdFrag<1024, 256, 256, 4, 8>>},  // GPT-2 medium fc2 4096 -> 1024
     {768, 192, 192, launch<FwdFrag<768, 192, 192, 3, 6>>},    // GPT-2 small fc2 3072 -> 768
+    {256, 256, 256, launch<FwdFrag<256, 256, 256, 4, 8>>},    // GPT-2 medium projection 1024 -> 1024
+    {192, 192, 576, launch<FwdFrag<192, 192, 576, 3, 6>>},    // ViT-B / GPT-2 small fused q,k,v 768 -> 2304
+    {256, 256, 768, launch<FwdFrag<256, 256, 768, 4, 8>>},    // GPT-2 medium fused q,k,v 1024 -> 3072
     {64, 64, 64, launch<FwdFrag<64, 64, 64, 1, 4>>},          // small shapes (tests)
     {64, 64, 128, launch<FwdFrag<64, 64, 128, 2, 4>>},
     {128, 64, 64, launch<FwdFrag<128, 64, 64, 1, 4>>},

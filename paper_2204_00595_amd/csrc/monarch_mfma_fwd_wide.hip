@@ -498,6 +498,9 @@ const Entry kTable[] = {
     {256, 256, 1024, launch<FwdWide<256, 256, 1024, 2>>},  // GPT-2 medium fc1 1024 -> 4096
     {1024, 256, 256, launch<FwdWide<1024, 256, 256, 2>>},  // GPT-2 medium fc2 4096 -> 1024
     {768, 192, 192, launch<FwdWide<768, 192, 192, 3>>},    // GPT-2 small fc2 3072 -> 768
+    {256, 256, 256, launch<FwdWide<256, 256, 256, 2>>},    // GPT-2 medium projection 1024 -> 1024
+    {192, 192, 576, launch<FwdWide<192, 192, 576, 3>>},    // ViT-B / GPT-2 small fused q,k,v 768 -> 2304
+    {256, 256, 768, launch<FwdWide<256, 256, 768, 2>>},    // GPT-2 medium fused q,k,v 1024 -> 3072
     {64, 64, 64, launch<FwdWide<64, 64, 64, 1>>},          // small shapes (tests)
     {64, 64, 128, launch<FwdWide<64, 64, 128, 2>>},
     {128, 64, 64, launch<FwdWide<128, 64, 64, 1>>},

@@ -131,6 +131,21 @@ WORKLOADS = {
 }
 
 
+# The remaining four-block layer shapes of the same models (attention output projection of
+# GPT-2 medium, fused q,k,v projections, second MLP layer of GPT-2 small), at the batch of the
+# workload of the same model above.  Timed by `bench.py --layers`; not part of the headline step.
+MODEL_LAYERS = {
+    "vitb_qkv": Shape("vitb_qkv", "bf16", 64 * 197, 4, 192, 192, 576, config=6),
+    "gpt2s_fc2": Shape("gpt2s_fc2", "bf16", 8 * 1024, 4, 768, 192, 192, config=7),
+    "gpt2m_proj": Shape("gpt2m_proj", "bf16", 16384, 4, 256, 256, 256, config=8),
+    "gpt2m_qkv": Shape("gpt2m_qkv", "bf16", 16384, 4, 256, 256, 768, config=9),
+}
+
+
+def workload(name: str) -> Shape:
+    return WORKLOADS[name] if name in WORKLOADS else MODEL_LAYERS[name]
+
+
 def tensor_seed(config: int, which: str) -> int:
     return BASE_SEED + 1000 * config + _TENSOR_ID[which]
 

@@ -134,6 +134,31 @@ def test_small_shapes_fwd_bwd(B, case, generic):
     compare(sh, got32, oracle.bwd(dy, x, R, L), ["dx", "dR32", "dL32"])
 
 
+# The other Monarch layer shapes of the paper's ViT-B / GPT-2 small / GPT-2 medium models (four blocks):
+# attention output projection, fused q,k,v projection and the second MLP layer, at a batch of several
+# 64-row tiles plus a ragged tail.  All of them must be served by the matrix-core kernels.
+MODEL_LAYERS = [
+    ("gpt2m_proj_1024_1024", "bf16", 1100, 4, 256, 256, 256),
+    ("qkv_768_2304", "bf16", 1100, 4, 192, 192, 576),
+    ("gpt2m_qkv_1024_3072", "bf16", 1100, 4, 256, 256, 768),
+    ("gpt2s_fc2_3072_768", "bf16", 1100, 4, 768, 192, 192),
+]
+
+
+@pytest.mark.parametrize("case", MODEL_LAYERS, ids=lambda c: c[0])
+def test_model_layer_shapes_on_matrix_cores(B, case):
+    sh = small_shape(case)
+    names = [B.monarch_kernel_name(ps, sh.n_in, sh.k, sh.q, sh.s, 1) for ps in (0, 1, 2)]
+    assert names == ["mfma_fwd_wide_bf16", "mfma_bwd_wide_bf16", "mfma_fwd_frag_bf16"], names
+    x, R, L, dy = synth.make_inputs(sh)
+    yo = oracle.fwd(x, R, L)
+    compare(sh, [run_fwd(B, sh, x, R, L), run_fwd(B, sh, x, R, L, ws=True)], [yo, yo], ["y", "y_ws"])
+    bias = make_bias(sh)
+    compare(sh, [run_fwd_bias(B, sh, x, R, L, bias)], [oracle.fwd_bias(x, R, L, bias)], ["y_bias"])
+    compare(sh, run_bwd_bias(B, sh, dy, x, R, L), oracle.bwd_bias(dy, x, R, L), ["dx", "dR", "dL", "dbias"])
+    compare(sh, run_bwd(B, sh, dy, x, R, L, B.MONARCH_FLAG_WGRAD_F32), oracle.bwd(dy, x, R, L), ["dx", "dR32", "dL32"])
+
+
 @pytest.mark.parametrize("case", [c for c in SMALL if c[3] != c[5]][:5], ids=lambda c: c[0])
 def test_alternative_mid_permutation(B, case):
     sh = small_shape(case)
