@@ -453,6 +453,55 @@ def test_dense_form_full_size(B, name):
             assert abs(got[l * m + j, kk * m + i] - ref) <= 2.0 ** -8 * abs(ref) + 1e-30
 
 
+def test_random_small_shapes_every_entry_point(B):
+    """Seeded sweep over shapes nobody tuned for (k, p, q, s in 1..12, odd sizes, both readings, both
+    storage types): every entry point against the oracle."""
+    from oracle import dense
+    rng = np.random.default_rng(20240595)
+    for it in range(24):
+        k, p, q, s = (int(v) for v in rng.integers(1, 13, size=4))
+        rows = int(rng.integers(1, 150))
+        dtype = "bf16" if it % 2 else "f32"
+        reading = int(rng.integers(0, 2))
+        flags = B.MONARCH_FLAG_PERM_B if reading else 0
+        sh = synth.Shape("sweep%d_k%d_p%d_q%d_s%d_%s_r%d" % (it, k, p, q, s, dtype, reading), dtype, rows, k, p, q, s, config=40 + it)
+        print("\n  " + sh.name, flush=True)
+        x, R, L, dy = synth.make_inputs(sh)
+        bias = make_bias(sh)
+        compare(sh, [run_fwd(B, sh, x, R, L, flags), run_fwd_bias(B, sh, x, R, L, bias, flags)],
+                [oracle.fwd(x, R, L, reading), oracle.fwd_bias(x, R, L, bias, reading)], ["y", "y_bias"])
+        compare(sh, run_bwd_bias(B, sh, dy, x, R, L, flags), oracle.bwd_bias(dy, x, R, L, reading), ["dx", "dR", "dL", "dbias"])
+        M = run_dense(B, sh, R, L, flags)
+        assert oracle.rel_fro(M, dense.monarch_dense(R, L, reading)) <= DENSE_TOL[dtype]
+
+
+def test_rows_beyond_two_to_the_31_elements(B):
+    """Maximum size: a batch whose activations hold more than 2^31 elements (fp32 m = 16 kernels,
+    B = 2^23 + 21 rows of 256).  Sampled rows, including the last ones, against the oracle; the
+    weight gradients through the identity <dR, R> = <dL, L> = <dy, y>, which holds at any size."""
+    sh = synth.Shape("huge", "f32", (1 << 23) + 21, 16, 16, 16, 16, config=1)
+    blk = 1 << 16
+    xb, R, L, dyb = synth.make_inputs(sh, rows=blk)
+    reps = -(-sh.B // blk)
+    ramp = (torch.arange(sh.B, device="cuda", dtype=torch.float32) % 1009.0).mul_(1.0 / 1024).unsqueeze(1)
+    x = torch.from_numpy(xb).cuda().repeat(reps, 1)[:sh.B].contiguous().add_(ramp)    # every row differs from its
+    dy = torch.from_numpy(dyb).cuda().repeat(reps, 1)[:sh.B].contiguous().sub_(ramp)  # copies 65536 rows away
+    del ramp
+    Rd, Ld = dev(R, "f32"), dev(L, "f32")
+    assert x.numel() > 2 ** 31
+    y = B.monarch_fwd(x, Rd, Ld)
+    dx, dR, dL = B.monarch_bwd(dy, x, Rd, Ld)
+    torch.cuda.synchronize()
+    rows = torch.tensor([0, 1, 17, blk - 1, blk, 3 * blk + 5, (1 << 23) - 1, 1 << 23, sh.B - 2, sh.B - 1], device="cuda")
+    xs, dys = x[rows].cpu().numpy(), dy[rows].cpu().numpy()
+    compare(sh, [host(y[rows]), host(dx[rows])], [oracle.fwd(xs, R, L), oracle.bwd(dys, xs, R, L)[0]], ["y_rows", "dx_rows"])
+    ref = float((dy.double() * y.double()).sum())
+    for name, g, w in (("dR", dR, Rd), ("dL", dL, Ld)):
+        v = float((g.double() * w.double()).sum())
+        print("  <%s, weight> = %.6e, <dy, y> = %.6e" % (name, v, ref), flush=True)
+        assert abs(v - ref) <= 1e-4 * abs(ref), name
+
+
 def test_stream_copy_is_bit_exact(B):
     n = (1 << 20) + 48  # bytes: several grid strides plus a ragged tail of three 16-byte pieces
     src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
