@@ -18,6 +18,9 @@ Monarch matrix replaces (Section 4: the dense weight matrices are swapped for Mo
 of the layer stays; the appendix on BERT pretraining lists the matrix product with the bias add, and
 the bias gradient in the backward pass, as steps worth fusing with the product).
 
+``project`` (``project.py``) is Algorithm 1, the projection of a dense matrix onto the square Monarch
+matrices by one best-rank-1 approximation per slice.
+
 All arrays are float64, row-major.  Low-precision inputs must be converted
 exactly to float64 by the caller.
 """

@@ -340,3 +340,81 @@ def test_bias_gradient_matches_unit_step_differences(shape):
     # brute force, and the all-ones upstream gradient counts the rows
     assert np.allclose(db, [sum(dy[b, o] for b in range(5)) for o in range(k * s)], rtol=0, atol=1e-14)
     assert np.array_equal(oracle.bwd_bias(np.ones_like(dy), x, R, L)[3], np.full(k * s, 5.0))
+
+
+# -------------------------------------------------- projection (Algorithm 1) ----
+
+from oracle import project  # noqa: E402
+
+
+@pytest.mark.parametrize("m", [1, 2, 3, 4, 6])
+def test_projection_recovers_a_monarch_matrix(m):
+    """If A is itself Monarch the projection returns factors with P L P^T R = A (remark after
+    Theorem 1); A is built by the literal dense product, which shares nothing with the projection."""
+    rng = np.random.default_rng(40 + m)
+    R0, L0 = rng.standard_normal((m, m, m)), rng.standard_normal((m, m, m))
+    A = dense.monarch_dense(R0, L0)
+    L, R = project.project_square(A)
+    assert np.allclose(dense.monarch_dense(R, L), A, rtol=0, atol=1e-12)
+    assert np.allclose(project.monarch_square(L, R), A, rtol=0, atol=1e-12)  # the einsum helper agrees with Eq. (1)
+    assert np.allclose(project.monarch_square(L0, R0), dense.eq1_dense_square(R0, L0), rtol=0, atol=1e-14)
+
+
+def test_projection_of_a_hand_made_matrix():
+    """m = 2, slices with known singular triples: slice (j, k) = a_jk * e_(j) e_(k)^T + small second
+    term orthogonal to it, so the best rank-1 part can be read off."""
+    m = 2
+    At = np.zeros((m, m, m, m))
+    big = {(0, 0): 3.0, (0, 1): -2.0, (1, 0): 5.0, (1, 1): 0.5}
+    for (j, k), a in big.items():
+        # singular triples: sigma_1 = |a| on (e_j, e_k), sigma_2 = 0.25 on the other basis vectors
+        At[j, j, k, k] = a
+        At[1 - j, j, k, 1 - k] = 0.25
+    A = At.reshape(4, 4)
+    L, R = project.project_square(A)
+    M = project.monarch_square(L, R).reshape(m, m, m, m)
+    want = np.zeros_like(At)
+    for (j, k), a in big.items():
+        want[j, j, k, k] = a
+    assert np.allclose(M, want, rtol=0, atol=1e-14)
+    assert abs(np.sum((A - M.reshape(4, 4)) ** 2) - 4 * 0.25 ** 2) < 1e-14
+
+
+def test_projection_residual_for_two_by_two_slices_has_the_closed_form():
+    """m = 2: a 2 x 2 matrix with Frobenius norm^2 T and determinant D has sigma_2^2 =
+    (T - sqrt(T^2 - 4 D^2)) / 2, so the optimal objective of Equation (2)'s problem is the sum of that
+    over the four slices."""
+    rng = np.random.default_rng(77)
+    A = rng.standard_normal((4, 4))
+    L, R = project.project_square(A)
+    At = A.reshape(2, 2, 2, 2)
+    want = 0.0
+    for j in range(2):
+        for k in range(2):
+            S = At[:, j, k, :]
+            T, D = np.sum(S * S), S[0, 0] * S[1, 1] - S[0, 1] * S[1, 0]
+            want += (T - np.sqrt(T * T - 4 * D * D)) / 2
+    got = np.sum((A - project.monarch_square(L, R)) ** 2)
+    assert abs(got - want) < 1e-12
+
+
+@pytest.mark.parametrize("m", [2, 3, 5])
+def test_projection_is_stationary_and_not_beaten_by_perturbations(m):
+    """Optimality (Theorem 1): at the returned factors every slice's residual E satisfies E v = 0 and
+    E^T u = 0 (the normal equations of the rank-1 problem), and no perturbed pair of factors, small or
+    large, comes closer to A."""
+    rng = np.random.default_rng(90 + m)
+    n = m * m
+    A = rng.standard_normal((n, n))
+    L, R = project.project_square(A)
+    E = (A - project.monarch_square(L, R)).reshape(m, m, m, m)
+    for j in range(m):
+        for k in range(m):
+            assert np.allclose(E[:, j, k, :] @ R[k, j, :], 0, atol=1e-12)
+            assert np.allclose(E[:, j, k, :].T @ L[j, :, k], 0, atol=1e-12)
+    best = np.sum(E ** 2)
+    for scale in (1e-4, 1e-2, 0.3, 1.0):
+        for _ in range(20):
+            Lp = L + scale * rng.standard_normal(L.shape)
+            Rp = R + scale * rng.standard_normal(R.shape)
+            assert np.sum((A - project.monarch_square(Lp, Rp)) ** 2) >= best - 1e-12
