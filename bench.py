@@ -139,7 +139,7 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True, wi
 
     fwd_ws_ms = float(np.mean([run_of(fwd_ws_only) for _ in range(3)])) if fneed else None
     fwd_ws_packed_ms = float(np.mean([run_of(fwd_ws_packed) for _ in range(3)])) if fneed else None
-    fwd_bias_ms = fwd_then_add_ms = bwd_bias_ms = to_dense_ms = to_dense_gbs = None
+    fwd_bias_ms = fwd_then_add_ms = bwd_bias_ms = to_dense_ms = to_dense_gbs = project_ms = None
     if with_extras:
         # affine layer: bias fused into the forward (where the kernel has the epilogue), bias gradient with the backward;
         # beside them the unfused forms (the plain call, then a separate elementwise add / column sum by the framework)
@@ -169,6 +169,11 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True, wi
         to_dense_ms = float(np.mean([run_of(lambda i: binding.monarch_to_dense(Rd, Ld, Mdense)) for _ in range(3)]))
         dense_bytes = (sh.k * sh.q * sh.p + sh.k * sh.s * sh.q + sh.n_out * sh.n_in) * sh.esize
         to_dense_gbs = dense_bytes / (to_dense_ms * 1e-3) / 1e9
+        if sh.k == sh.p == sh.q == sh.s:
+            # Algorithm 1 on a dense Gaussian n x n matrix (square shapes only): one Jacobi SVD per slice
+            Adense = torch.from_numpy(synth.quantize(synth.normal(4343, (sh.n_in, sh.n_in)), sh.dtype)).to(dev).to(dt)
+            Rp, Lp = torch.empty_like(Rd), torch.empty_like(Ld)
+            project_ms = float(np.mean([run_of(lambda i: binding.monarch_project(Adense, Rp, Lp)) for _ in range(2)]))
     fwd_runs = [run_of(fwd_only) for _ in range(3)]
     bwd_runs = [run_of(bwd_only) for _ in range(3)]
     fwd_ms, bwd_ms = float(np.mean(fwd_runs)), float(np.mean(bwd_runs))
@@ -191,6 +196,7 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True, wi
         "fwd_bias_ms": fwd_bias_ms, "fwd_then_add_ms": fwd_then_add_ms, "bwd_bias_ms": bwd_bias_ms,
         # monarch_to_dense: M written out as a dense (n_out, n_in) matrix; bytes = R + L read, M written
         "to_dense_ms": to_dense_ms, "to_dense_gbs": to_dense_gbs,
+        "project_ms": project_ms,  # monarch_project of a dense n x n matrix (square shapes), else null
         "fwd_kernel": binding.monarch_kernel_name(0, sh.n_in, sh.k, sh.q, sh.s, code),
         "bwd_kernel": binding.monarch_kernel_name(1, sh.n_in, sh.k, sh.q, sh.s, code),
         "fwd_tflops": sh.fwd_flops() / (fwd_ms * 1e-3) / 1e12,

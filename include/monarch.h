@@ -178,6 +178,22 @@ int monarch_to_dense(const void* R, const void* L, void* M,
                      int n_in, int k, int q, int s,
                      monarch_dtype dtype, void* stream, unsigned flags);
 
+/* Projection of a dense matrix onto the square Monarch matrices (Section 3.3, "Projection on the Set
+ * M of Monarch Matrices", Theorem 1, Algorithm 1): the factors of the Monarch matrix closest to A in
+ * Frobenius norm.  A is n x n row-major with n = m*m; with At[l][j][k][i] = A[l*m + j][k*m + i] every
+ * slice At[:, j, k, :] (m x m) is replaced by its best rank-1 approximation sigma_1 u_1 v_1^T, and
+ *   L[j][l][k] = sqrt(sigma_1) * u_1[l],    R[k][j][i] = sqrt(sigma_1) * v_1[i]
+ * so that Equation (1), M[l*m + j][k*m + i] = L[j][l][k] * R[k][j][i], gives the projection (the
+ * dense-to-sparse step that precedes fine-tuning).  The sign of (u_1, v_1) is not fixed, and when the
+ * two largest singular values of a slice coincide any leading pair is a valid answer; only the
+ * products L*R are determined.  A zero slice gives zero factors.
+ * The singular triple is computed in fp32 by a one-sided Jacobi iteration (at most 40 sweeps, pairs
+ * orthogonal to 3e-7 relative).  A (n, n), R (m, m, m), L (m, m, m) are device pointers, 16-byte
+ * aligned, element type `dtype`; R and L are overwritten.  m <= 64; larger m returns
+ * MONARCH_ERR_UNSUPPORTED; n != m*m or flags != 0 returns MONARCH_ERR_INVALID.  No workspace. */
+int monarch_project(const void* A, void* R, void* L, int n, int m,
+                    monarch_dtype dtype, void* stream, unsigned flags);
+
 /* Name of the kernel family the dispatcher picks for this problem: pass 0 = forward
  * (monarch_fwd / monarch_fwd_ex), 1 = backward, 2 = forward with workspace (monarch_fwd_ws).  Static string, never NULL ("invalid" / "unsupported" on bad input). */
 const char* monarch_kernel_name(int pass, int n_in, int k, int q, int s,

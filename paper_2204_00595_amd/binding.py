@@ -32,7 +32,7 @@ EXPORTS = (
     "monarch_fwd", "monarch_fwd_ex", "monarch_fwd_ws", "monarch_fwd_bias", "monarch_fwd_workspace_bytes", "monarch_bwd",
     "monarch_bwd_bias",
     "monarch_bwd_workspace_bytes",
-    "monarch_to_dense", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy",
+    "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy",
 )
 
 _lib = None
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.monarch_bwd_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci, cu]
         L.monarch_to_dense.restype = ci
         L.monarch_to_dense.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp, cu]
+        L.monarch_project.restype = ci
+        L.monarch_project.argtypes = [vp, vp, vp, ci, ci, ci, vp, cu]
         L.monarch_kernel_name.restype = ctypes.c_char_p
         L.monarch_kernel_name.argtypes = [ci, ci, ci, ci, ci, ci, cu]
         L.monarch_status_string.restype = ctypes.c_char_p
@@ -318,3 +320,24 @@ def monarch_bwd_bias(dy: torch.Tensor, x: torch.Tensor, R: torch.Tensor, L: torc
     if rc != MONARCH_OK:
         raise MonarchError(rc, "monarch_bwd_bias")
     return dx, dR, dL, dbias
+
+
+def monarch_project(A: torch.Tensor, R: torch.Tensor | None = None, L: torch.Tensor | None = None, stream=None):
+    """(L, R): factors of the square Monarch matrix closest to the dense A (n, n), n = m*m, m <= 64."""
+    n = A.shape[0]
+    m = int(round(n ** 0.5))
+    dev, dt = A.device, A.dtype
+    if m * m != n:
+        raise ValueError("A must be n x n with n a perfect square, got %s" % (tuple(A.shape),))
+    _check(A, "A", (n, n), dt, dev)
+    if R is None:
+        R = torch.empty((m, m, m), dtype=dt, device=dev)
+    if L is None:
+        L = torch.empty((m, m, m), dtype=dt, device=dev)
+    _check(R, "R", (m, m, m), dt, dev)
+    _check(L, "L", (m, m, m), dt, dev)
+    with torch.cuda.device(dev):
+        rc = lib().monarch_project(A.data_ptr(), R.data_ptr(), L.data_ptr(), n, m, _dtype_code(A), _stream_ptr(stream), 0)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_project")
+    return L, R

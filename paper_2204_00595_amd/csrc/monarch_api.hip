@@ -205,6 +205,17 @@ int monarch_to_dense(const void* R, const void* L, void* M, int n_in, int k, int
     return launch_to_dense(pb, R, L, M, (hipStream_t)stream);
 }
 
+int monarch_project(const void* A, void* R, void* L, int n, int m, monarch_dtype dtype, void* stream, unsigned flags)
+{
+    if (n <= 0 || m <= 0 || (int64_t)m * m != (int64_t)n) return MONARCH_ERR_INVALID;
+    if (dtype != MONARCH_F32 && dtype != MONARCH_BF16) return MONARCH_ERR_INVALID;
+    if (flags != 0) return MONARCH_ERR_INVALID;
+    if (!A || !R || !L) return MONARCH_ERR_INVALID;
+    if (!aligned(A, 16) || !aligned(R, 16) || !aligned(L, 16)) return MONARCH_ERR_INVALID;
+    if (!project_supported(m)) return MONARCH_ERR_UNSUPPORTED;
+    return launch_project(A, R, L, m, (int)dtype, (hipStream_t)stream);
+}
+
 const char* monarch_kernel_name(int pass, int n_in, int k, int q, int s, monarch_dtype dtype, unsigned flags)
 {
     Problem pb;

@@ -48,6 +48,10 @@ int launch_colsum(const Problem& pb, const void* dy, void* dbias, void* ws, hipS
 struct ColsumJob;
 ColsumJob make_colsum_job(const Problem& pb, const void* dy, void* dbias, void* ws);
 
+// projection of a dense n x n matrix (n = m * m) onto the square Monarch matrices (monarch_project.hip)
+bool project_supported(int m);
+int launch_project(const void* A, void* R, void* L, int m, int dtype, hipStream_t st);
+
 // ---- MFMA kernels for the shapes they are instantiated for (bf16 / fp32 matrix cores) ----
 bool mfma_fwd_supported(const Problem& pb);
 bool mfma_bwd_supported(const Problem& pb);

@@ -502,6 +502,65 @@ def test_rows_beyond_two_to_the_31_elements(B):
         assert abs(v - ref) <= 1e-4 * abs(ref), name
 
 
+# ------------------------------------------------------ projection (Algorithm 1) ----
+# Only the products L[j][l][k] * R[k][j][i] are determined (sign and scaling of a singular pair are
+# free), so the Monarch matrix is compared, not the factors.  fp32 Jacobi against the fp64 SVD: the
+# leading singular pair of a slice is conditioned by its relative gap (about 1e-2 for 64 x 64 Gaussian
+# slices), hence 1e-4; the objective itself is insensitive to that and is held to 1e-5.
+PROJ_TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def run_project(B, A, dtype):
+    from oracle import project
+    n = A.shape[0]
+    m = int(round(n ** 0.5))
+    bR, R = guarded((m, m, m), tdtype(dtype))
+    bL, L = guarded((m, m, m), tdtype(dtype))
+    B.monarch_project(dev(A, dtype), R, L)
+    torch.cuda.synchronize()
+    check_guard(bR, "R")
+    check_guard(bL, "L")
+    Lh, Rh = host(L), host(R)
+    assert np.isfinite(Lh).all() and np.isfinite(Rh).all()
+    return Lh, Rh, project.monarch_square(Lh, Rh)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("m", [1, 2, 3, 5, 8, 16, 33, 64])
+def test_projection_of_dense_matrices(B, m, dtype):
+    from oracle import project
+    n = m * m
+    A = synth.quantize(synth.normal(7100 + m, (n, n)), dtype)
+    _, _, M = run_project(B, A, dtype)
+    Lo, Ro = project.project_square(A)
+    Mo = project.monarch_square(Lo, Ro)
+    err = oracle.rel_fro(M, Mo)
+    obj, obj_o = float(np.sum((A - M) ** 2)), float(np.sum((A - Mo) ** 2))
+    print("\n  m=%d %s: M err %.2e, objective %.8e (optimal %.8e)" % (m, dtype, err, obj, obj_o), flush=True)
+    assert err <= PROJ_TOL[dtype]
+    # distance to A: optimal up to 1e-5 relative, plus the rounding of the factors themselves
+    slack = (1e-6 if dtype == "f32" else 2.0 ** -7) * float(np.linalg.norm(Mo))
+    assert np.sqrt(obj) <= np.sqrt(obj_o) * (1 + 1e-5) + slack
+
+
+@pytest.mark.parametrize("m", [4, 16, 64])
+def test_projection_recovers_monarch_matrices_and_handles_zero_slices(B, m):
+    """A in M is a fixed point (remark after Theorem 1), through monarch_to_dense as well; slices that
+    are entirely zero give zero factors, not NaN."""
+    from oracle import project
+    sh = synth.Shape("proj%d" % m, "f32", 1, m, m, m, m, config=60)
+    _, R0, L0, _ = synth.make_inputs(sh)
+    L0[1, :, 2] = 0.0  # slice (j = 1, k = 2) of the Monarch matrix becomes zero
+    A = project.monarch_square(L0, R0)
+    L, R, M = run_project(B, A, "f32")
+    assert oracle.rel_fro(M, A) <= 1e-5
+    assert not L[1, :, 2].any() or not R[2, 1, :].any()
+    Md = run_dense(B, sh, R.astype(np.float32), L.astype(np.float32))
+    assert oracle.rel_fro(Md, A) <= 1e-5
+    Lz, Rz, Mz = run_project(B, np.zeros((m * m, m * m), dtype=np.float32), "f32")
+    assert not Lz.any() and not Rz.any()
+
+
 def test_stream_copy_is_bit_exact(B):
     n = (1 << 20) + 48  # bytes: several grid strides plus a ragged tail of three 16-byte pieces
     src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")

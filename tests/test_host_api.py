@@ -179,6 +179,24 @@ def test_affine_layer_calls_reject_bad_arguments_without_a_gpu(binding):
     assert big - small >= 127 * 768 * 4
 
 
+def test_projection_rejects_bad_arguments_without_a_gpu(binding):
+    L = binding.lib()
+    p = 4096  # never dereferenced
+
+    def call(A=p, R=p, Lp=p, n=256, m=16, dtype=0, flags=0):
+        return L.monarch_project(A, R, Lp, n, m, dtype, None, flags)
+
+    assert call(A=None) == binding.MONARCH_ERR_INVALID
+    assert call(R=None) == binding.MONARCH_ERR_INVALID
+    assert call(Lp=None) == binding.MONARCH_ERR_INVALID
+    assert call(A=p + 4) == binding.MONARCH_ERR_INVALID
+    assert call(n=255) == binding.MONARCH_ERR_INVALID            # n is not m * m
+    assert call(n=0, m=0) == binding.MONARCH_ERR_INVALID
+    assert call(dtype=3) == binding.MONARCH_ERR_INVALID
+    assert call(flags=binding.MONARCH_FLAG_PERM_B) == binding.MONARCH_ERR_INVALID
+    assert call(n=65 * 65, m=65) == binding.MONARCH_ERR_UNSUPPORTED
+
+
 def test_stream_copy_rejects_bad_arguments_without_a_gpu(binding):
     L = binding.lib()
     assert L.monarch_stream_copy(None, None, 0, None) == binding.MONARCH_OK          # empty copy: no-op
