@@ -561,6 +561,50 @@ def test_projection_recovers_monarch_matrices_and_handles_zero_slices(B, m):
     assert not Lz.any() and not Rz.any()
 
 
+@pytest.mark.parametrize("case", [("k4_192", "bf16", 1000, 4, 192, 192, 192), ("sq_m64", "bf16", 300, 64, 64, 64, 64),
+                                  ("sq_m16", "f32", 64, 16, 16, 16, 16), ("rect_generic", "f32", 50, 3, 4, 5, 7)],
+                         ids=lambda c: c[0])
+def test_calls_can_be_captured_in_a_graph(B, case):
+    """The library allocates nothing, clears memory with kernels only and enqueues everything on the
+    caller's stream, so a forward + backward (with bias gradient) can be captured in a HIP graph.
+    Four replays, with eager work and synchronisations between them, each against the eager result:
+    bit for bit on the matrix-core kernels, to fp32 summation order on the shape-generic backward
+    (its weight gradients are fp32 atomics)."""
+    sh = small_shape(case)
+    x, R, L, dy = synth.make_inputs(sh)
+    xd, Rd, Ld, dyd, bd = (dev(a, sh.dtype) for a in (x, R, L, dy, make_bias(sh)))
+    code = 0 if sh.dtype == "f32" else 1
+    outs = [torch.empty((sh.B, sh.n_out), dtype=xd.dtype, device="cuda"), torch.empty_like(xd), torch.empty_like(Rd),
+            torch.empty_like(Ld), torch.empty((sh.n_out,), dtype=xd.dtype, device="cuda")]
+    fneed = B.monarch_fwd_workspace_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, code)
+    fws = torch.empty(max(fneed, 256), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.monarch_bwd_workspace_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, code), dtype=torch.uint8, device="cuda")
+
+    def step():
+        B.monarch_fwd_bias(xd, Rd, Ld, bd, outs[0], workspace=fws if fneed else None)
+        B.monarch_bwd_bias(dyd, xd, Rd, Ld, outs[1], outs[2], outs[3], outs[4], workspace=ws)
+
+    step()  # eager: reference values, and every kernel is loaded before the capture
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in outs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    generic = B.monarch_kernel_name(1, sh.n_in, sh.k, sh.q, sh.s, code) == "generic_bwd"
+    for rep in range(4):
+        for t in outs:
+            t.fill_(float("nan"))  # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (got, want) in enumerate(zip(outs, ref)):
+            if generic and i in (2, 3):
+                assert oracle.rel_fro(host(got), host(want)) <= 1e-6, (rep, i)
+            else:
+                assert torch.equal(got, want), (rep, i)
+    compare(sh, [host(outs[0]), host(outs[4])], [oracle.fwd_bias(x, R, L, host(bd)), oracle.bwd_bias(dy, x, R, L)[3]], ["y", "dbias"])
+
+
 def test_stream_copy_is_bit_exact(B):
     n = (1 << 20) + 48  # bytes: several grid strides plus a ragged tail of three 16-byte pieces
     src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
