@@ -135,6 +135,21 @@ def bwd(dy, x, R, L, reading: int = READING_A):
     return dx, dR, dL
 
 
+def fwd_t(x, R, L, reading: int = READING_A):
+    """y = x M: the transposed Monarch matrix M^T = R^T P L^T P^T applied to every row (M* of
+    Section 3.1, "Products of Monarch Matrices", for real factors).  x (B, k*s) -> y (B, k*p).
+
+    These are the adjoint steps of the multiply taken in reverse order -- undo the outer permutation,
+    multiply by the transposed blocks of L, undo the mid permutation, multiply by the transposed blocks
+    of R -- which is exactly the input-gradient part of :func:`bwd`, whose C code is used here with the
+    upstream gradient set to x (the activations argument does not enter dx)."""
+    R = np.asarray(R)
+    L = np.asarray(L)
+    k, q, p = R.shape
+    x = np.asarray(x)
+    return bwd(x, np.zeros((x.shape[0], k * p)), R, L, reading)[0]
+
+
 def fwd_bias(x, R, L, bias, reading: int = READING_A):
     """y[b][o] = (x M^T)[b][o] + bias[o]: the affine layer built on the Monarch matrix."""
     y = fwd(x, R, L, reading)

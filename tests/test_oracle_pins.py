@@ -418,3 +418,30 @@ def test_projection_is_stationary_and_not_beaten_by_perturbations(m):
             Lp = L + scale * rng.standard_normal(L.shape)
             Rp = R + scale * rng.standard_normal(R.shape)
             assert np.sum((A - project.monarch_square(Lp, Rp)) ** 2) >= best - 1e-12
+
+
+# ------------------------------------------------- transposed multiply (M*) ----
+
+@pytest.mark.parametrize("reading", READINGS)
+@pytest.mark.parametrize("shape", [(3, 3, 3, 3)] + TINY_RECT)
+def test_transposed_multiply_is_the_dense_transpose(shape, reading):
+    """fwd_t(x) = x M with M the literal dense product of Definition 3.1, and it is the adjoint of the
+    multiply: <fwd_t(x), z> = <x, fwd(z)>."""
+    k, p, q, s = shape
+    rng = np.random.default_rng(55)
+    z, R, L, x = _rand(rng, k, p, q, s, B=4)   # z (4, k*p), x (4, k*s)
+    M = dense.monarch_dense(R, L, reading)
+    got = oracle.fwd_t(x, R, L, reading)
+    assert np.allclose(got, x @ M, rtol=0, atol=1e-12)
+    assert abs(np.sum(got * z) - np.sum(x * oracle.fwd(z, R, L, reading))) < 1e-10
+
+
+def test_hadamard_monarch_times_its_transpose_is_n_times_identity():
+    """M = H_n (all blocks H_m, Sylvester) is in the class M, and M M* = n I (the Hadamard transform
+    is in MM*, Proposition 3.2): applying M* and then M multiplies every vector by n, exactly."""
+    m = 8
+    H = scipy.linalg.hadamard(m).astype(np.float64)
+    blocks = np.broadcast_to(H, (m, m, m)).copy()
+    rng = np.random.default_rng(56)
+    x = rng.integers(-3, 4, size=(5, m * m)).astype(np.float64)
+    assert np.array_equal(oracle.fwd(oracle.fwd_t(x, blocks, blocks), blocks, blocks), m * m * x)
