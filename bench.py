@@ -139,7 +139,7 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True, wi
 
     fwd_ws_ms = float(np.mean([run_of(fwd_ws_only) for _ in range(3)])) if fneed else None
     fwd_ws_packed_ms = float(np.mean([run_of(fwd_ws_packed) for _ in range(3)])) if fneed else None
-    fwd_bias_ms = fwd_then_add_ms = bwd_bias_ms = to_dense_ms = to_dense_gbs = project_ms = None
+    fwd_bias_ms = fwd_then_add_ms = bwd_bias_ms = to_dense_ms = to_dense_gbs = project_ms = fwd_t_ms = None
     if with_extras:
         # affine layer: bias fused into the forward (where the kernel has the epilogue), bias gradient with the backward;
         # beside them the unfused forms (the plain call, then a separate elementwise add / column sum by the framework)
@@ -165,6 +165,15 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True, wi
         fwd_bias_ms = float(np.mean([run_of(fwd_bias_only) for _ in range(3)]))
         fwd_then_add_ms = float(np.mean([run_of(fwd_then_add) for _ in range(3)]))
         bwd_bias_ms = float(np.mean([run_of(bwd_bias_only) for _ in range(3)]))
+        # transposed multiply x M (monarch_fwd_t): input of the output's shape, result of the input's shape
+        tneed = binding.monarch_fwd_t_workspace_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, code, 0)
+        tws = torch.empty(max(tneed, 256), dtype=torch.uint8, device=dev)
+
+        def fwd_t_only(i):
+            _, dys, _, dx = sets[i % nsets]
+            binding.monarch_fwd_t(dys, Rd, Ld, dx, workspace=tws if tneed else None)
+
+        fwd_t_ms = float(np.mean([run_of(fwd_t_only) for _ in range(3)]))
         Mdense = torch.empty((sh.n_out, sh.n_in), dtype=Rd.dtype, device="cuda")
         to_dense_ms = float(np.mean([run_of(lambda i: binding.monarch_to_dense(Rd, Ld, Mdense)) for _ in range(3)]))
         dense_bytes = (sh.k * sh.q * sh.p + sh.k * sh.s * sh.q + sh.n_out * sh.n_in) * sh.esize
@@ -196,6 +205,7 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True, wi
         "fwd_bias_ms": fwd_bias_ms, "fwd_then_add_ms": fwd_then_add_ms, "bwd_bias_ms": bwd_bias_ms,
         # monarch_to_dense: M written out as a dense (n_out, n_in) matrix; bytes = R + L read, M written
         "to_dense_ms": to_dense_ms, "to_dense_gbs": to_dense_gbs,
+        "fwd_t_ms": fwd_t_ms, "fwd_t_kernel": binding.monarch_kernel_name(3, sh.n_in, sh.k, sh.q, sh.s, code),  # monarch_fwd_t
         "project_ms": project_ms,  # monarch_project of a dense n x n matrix (square shapes), else null
         "fwd_kernel": binding.monarch_kernel_name(0, sh.n_in, sh.k, sh.q, sh.s, code),
         "bwd_kernel": binding.monarch_kernel_name(1, sh.n_in, sh.k, sh.q, sh.s, code),

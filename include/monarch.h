@@ -162,6 +162,29 @@ int monarch_bwd_bias(const void* dy, const void* x, const void* R, const void* L
 size_t monarch_bwd_workspace_bytes(int64_t batch, int n_in, int k, int q, int s,
                                    monarch_dtype dtype, unsigned flags);
 
+/* Transposed multiply:  y = x M,  i.e. the transpose M^T = R^T P L^T P^T applied to every row (for
+ * real factors the M* of Section 3.1, "Products of Monarch Matrices": a matrix of the class MM* is
+ * applied as monarch_fwd_t with the factors of M2 followed by monarch_fwd with the factors of M1).
+ * Steps, for every row b:
+ *   W[b][c][l]     = x[b][l*k + c]
+ *   U[b][c*q + r]  = sum_l L[c][l][r] * W[b][c][l]
+ *   Y1[b][kk][j]   = U[b][position that the mid permutation gives stage-1 output (kk, j)]
+ *   y[b][kk*p + i] = sum_j R[kk][j][i] * Y1[b][kk][j]
+ * the same arithmetic as the dx part of monarch_bwd.  x (batch, k*s), y (batch, n_in), R and L as
+ * everywhere; flags: MONARCH_FLAG_PERM_B, MONARCH_FLAG_GENERIC.  `workspace` (device, 256-byte
+ * aligned) must hold monarch_fwd_t_workspace_bytes(...) bytes when that is non-zero (weights in
+ * matrix-core operand order; for m = 64 also one re-laid copy of x); contents on entry are ignored.
+ * In the bf16 path the vector between the two factors is rounded to bf16, as in monarch_fwd. */
+int monarch_fwd_t(const void* x, const void* R, const void* L, void* y,
+                  int64_t batch, int n_in, int k, int q, int s,
+                  monarch_dtype dtype, void* stream,
+                  void* workspace, size_t workspace_bytes, unsigned flags);
+
+/* Bytes of device scratch monarch_fwd_t needs (0 for the shape-generic kernels and the fp32 m = 16
+ * kernel, and on invalid arguments). */
+size_t monarch_fwd_t_workspace_bytes(int64_t batch, int n_in, int k, int q, int s,
+                                     monarch_dtype dtype, unsigned flags);
+
 /* The Monarch matrix itself as a dense array: M = P L P^T R (Definition 3.1), the matrix for which
  * monarch_fwd computes y = x M^T.  This is the conversion that sparse-to-dense training makes when it
  * switches from the Monarch layer to a dense one (Section 4: the factors multiplied out together
@@ -195,7 +218,8 @@ int monarch_project(const void* A, void* R, void* L, int n, int m,
                     monarch_dtype dtype, void* stream, unsigned flags);
 
 /* Name of the kernel family the dispatcher picks for this problem: pass 0 = forward
- * (monarch_fwd / monarch_fwd_ex), 1 = backward, 2 = forward with workspace (monarch_fwd_ws).  Static string, never NULL ("invalid" / "unsupported" on bad input). */
+ * (monarch_fwd / monarch_fwd_ex), 1 = backward, 2 = forward with workspace (monarch_fwd_ws),
+ * 3 = transposed multiply (monarch_fwd_t).  Static string, never NULL ("invalid" / "unsupported" on bad input). */
 const char* monarch_kernel_name(int pass, int n_in, int k, int q, int s,
                                 monarch_dtype dtype, unsigned flags);
 

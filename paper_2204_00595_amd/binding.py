@@ -32,7 +32,7 @@ EXPORTS = (
     "monarch_fwd", "monarch_fwd_ex", "monarch_fwd_ws", "monarch_fwd_bias", "monarch_fwd_workspace_bytes", "monarch_bwd",
     "monarch_bwd_bias",
     "monarch_bwd_workspace_bytes",
-    "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy",
+    "monarch_fwd_t", "monarch_fwd_t_workspace_bytes", "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy",
 )
 
 _lib = None
@@ -72,6 +72,10 @@ def lib() -> ctypes.CDLL:
         L.monarch_bwd_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci, cu]
         L.monarch_to_dense.restype = ci
         L.monarch_to_dense.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp, cu]
+        L.monarch_fwd_t.restype = ci
+        L.monarch_fwd_t.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
+        L.monarch_fwd_t_workspace_bytes.restype = sz
+        L.monarch_fwd_t_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci, cu]
         L.monarch_project.restype = ci
         L.monarch_project.argtypes = [vp, vp, vp, ci, ci, ci, vp, cu]
         L.monarch_kernel_name.restype = ctypes.c_char_p
@@ -341,3 +345,33 @@ def monarch_project(A: torch.Tensor, R: torch.Tensor | None = None, L: torch.Ten
     if rc != MONARCH_OK:
         raise MonarchError(rc, "monarch_project")
     return L, R
+
+
+def monarch_fwd_t_workspace_bytes(batch: int, n_in: int, k: int, q: int, s: int, dtype: int, flags: int = 0) -> int:
+    return int(lib().monarch_fwd_t_workspace_bytes(batch, n_in, k, q, s, dtype, flags))
+
+
+def monarch_fwd_t(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.Tensor | None = None,
+                  workspace: torch.Tensor | None = None, flags: int = 0, stream=None) -> torch.Tensor:
+    """y = x M (the transposed Monarch matrix applied to the rows).  x (B, k*s) -> y (B, k*p)."""
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    dev, dt = x.device, x.dtype
+    _check(x, "x", (B, k * s), dt, dev)
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    if y is None:
+        y = torch.empty((B, k * p), dtype=dt, device=dev)
+    _check(y, "y", (B, k * p), dt, dev)
+    need = monarch_fwd_t_workspace_bytes(B, k * p, k, q, s, _dtype_code(x), flags)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_ptr = workspace.data_ptr() if workspace is not None else 0
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(dev):
+        rc = lib().monarch_fwd_t(x.data_ptr(), R.data_ptr(), L.data_ptr(), y.data_ptr(), B, k * p, k, q, s,
+                                 _dtype_code(x), _stream_ptr(stream), ws_ptr, ws_len, flags)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_fwd_t")
+    return y

@@ -193,6 +193,35 @@ int monarch_bwd_bias(const void* dy, const void* x, const void* R, const void* L
     return generic_bwd(pb, dy, x, R, L, dx, dR, dL, workspace, st);
 }
 
+size_t monarch_fwd_t_workspace_bytes(int64_t batch, int n_in, int k, int q, int s, monarch_dtype dtype, unsigned flags)
+{
+    Problem pb;
+    if (make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags)) return 0;
+    if ((flags & MONARCH_FLAG_GENERIC) || !mfma_fwd_t_supported(pb)) return 0;
+    return mfma_fwd_t_workspace(pb);
+}
+
+int monarch_fwd_t(const void* x, const void* R, const void* L, void* y, int64_t batch, int n_in, int k, int q, int s,
+                  monarch_dtype dtype, void* stream, void* workspace, size_t workspace_bytes, unsigned flags)
+{
+    Problem pb;
+    int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
+    if (rc) return rc;
+    if (flags & (MONARCH_FLAG_WGRAD_F32 | MONARCH_FLAG_WS_PACKED)) return MONARCH_ERR_INVALID;  // flags of other calls
+    if (!R || !L || ((!x || !y) && batch > 0)) return MONARCH_ERR_INVALID;
+    if (!aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(y, 16)) return MONARCH_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    if (!(flags & MONARCH_FLAG_GENERIC) && mfma_fwd_t_supported(pb)) {
+        const size_t need = mfma_fwd_t_workspace(pb);
+        if (need > 0 && (!workspace || workspace_bytes < need || !aligned(workspace, 256))) return MONARCH_ERR_WORKSPACE;
+        if (batch == 0) return MONARCH_OK;
+        return mfma_fwd_t(pb, x, R, L, y, workspace, st);
+    }
+    if (!generic_fwd_t_supported(pb)) return MONARCH_ERR_UNSUPPORTED;
+    if (batch == 0) return MONARCH_OK;
+    return generic_fwd_t(pb, x, R, L, y, st);
+}
+
 int monarch_to_dense(const void* R, const void* L, void* M, int n_in, int k, int q, int s, monarch_dtype dtype,
                      void* stream, unsigned flags)
 {
@@ -221,7 +250,11 @@ const char* monarch_kernel_name(int pass, int n_in, int k, int q, int s, monarch
     Problem pb;
     int rc = make_problem(pb, 1, n_in, k, q, s, (int)dtype, flags);
     if (rc == MONARCH_ERR_UNSUPPORTED) return "unsupported";
-    if (rc || pass < 0 || pass > 2) return "invalid";
+    if (rc || pass < 0 || pass > 3) return "invalid";
+    if (pass == 3) {
+        if (!(flags & MONARCH_FLAG_GENERIC) && mfma_fwd_t_supported(pb)) return mfma_fwd_t_name(pb);
+        return generic_fwd_t_supported(pb) ? "generic_fwd_t" : "unsupported";
+    }
     const Family fam = pass != 1 ? pick_fwd(pb) : pick_bwd(pb);
     if (pass == 2) return (!(flags & MONARCH_FLAG_GENERIC) && mfma_fwd_ws_supported(pb)) ? mfma_fwd_ws_name(pb) : monarch_kernel_name(0, n_in, k, q, s, dtype, flags);
     if (fam == FAM_GENERIC) return pass == 0 ? "generic_fwd" : "generic_bwd";

@@ -402,6 +402,86 @@ generic_fwd_kernel(const T* __restrict__ x, const T* __restrict__ R, const T* __
     }
 }
 
+// ----------------------------------------------------------- transposed multiply ----
+//
+// y = x M (the rows of x have length k*s, those of y k*p): undo the outer permutation, multiply by the
+// transposed blocks of L, undo the mid permutation, multiply by the transposed blocks of R.
+// LDS (fp32): ws[BM][k*s] (W[b][c*s + l] = x[b][l*k + c]) and us[BM][k*q] (the vector between the factors).
+
+template <typename T, int BM>
+__global__ void __launch_bounds__(kThreads)
+generic_fwd_t_kernel(const T* __restrict__ x, const T* __restrict__ R, const T* __restrict__ L, T* __restrict__ y,
+                     int64_t B, int k, int p, int q, int s, int perm_b)
+{
+    extern __shared__ float lds[];
+    const int n_in = k * p, kq = k * q, n_out = k * s;
+    float* ws = lds;
+    float* us = ws + (size_t)BM * n_out;
+    const int64_t b0 = (int64_t)blockIdx.x * BM;
+    const int tid = threadIdx.x;
+    const bool pb = perm_b != 0;
+
+    for (int e = tid; e < BM * n_out; e += kThreads) {
+        int b = e / n_out, o = e - b * n_out;
+        int l = o / k, c = o - l * k;
+        int64_t row = b0 + b;
+        ws[b * n_out + c * s + l] = row < B ? Elem<T>::load(x + row * n_out + o) : 0.f;
+    }
+    __syncthreads();
+    // U[c*q + r] = sum_l L[c][l][r] W[c][l]
+    for (int g = tid; g < kq; g += kThreads) {
+        const int c = g / q, r = g - c * q;
+        const T* Lcol = L + (size_t)c * s * q + r;
+        const float* wc = ws + c * s;
+        float acc[BM];
+#pragma unroll
+        for (int b = 0; b < BM; ++b) acc[b] = 0.f;
+        for (int l = 0; l < s; ++l) {
+            const float w = Elem<T>::load(Lcol + (size_t)l * q);
+#pragma unroll
+            for (int b = 0; b < BM; ++b) acc[b] = fmaf(w, wc[b * n_out + l], acc[b]);
+        }
+#pragma unroll
+        for (int b = 0; b < BM; ++b) us[b * kq + g] = acc[b];
+    }
+    __syncthreads();
+    // y[kk*p + i] = sum_j R[kk][j][i] U[position that stage-1 output (kk, j) is moved to]
+    for (int n = tid; n < n_in; n += kThreads) {
+        const int kk = n / p, i = n - kk * p;
+        const T* Rcol = R + (size_t)kk * q * p + i;
+        float acc[BM];
+#pragma unroll
+        for (int b = 0; b < BM; ++b) acc[b] = 0.f;
+        for (int j = 0; j < q; ++j) {
+            const float w = Elem<T>::load(Rcol + (size_t)j * p);
+            const int g = mid_dest(kk * q + j, k, q, pb);
+#pragma unroll
+            for (int b = 0; b < BM; ++b) acc[b] = fmaf(w, us[b * kq + g], acc[b]);
+        }
+#pragma unroll
+        for (int b = 0; b < BM; ++b) {
+            int64_t row = b0 + b;
+            if (row < B) Elem<T>::store(y + row * n_in + n, acc[b]);
+        }
+    }
+}
+
+static size_t fwd_t_floats_per_row(const Problem& pb) { return (size_t)pb.n_out() + pb.kq(); }
+
+template <typename T, int BM>
+static int launch_fwd_t(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
+{
+    const size_t lds = (size_t)BM * fwd_t_floats_per_row(pb) * sizeof(float);
+    auto kern = generic_fwd_t_kernel<T, BM>;
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return -4;
+    const int64_t grid = (pb.B + BM - 1) / BM;
+    if (grid > 0x7fffffffLL) return -2;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, st, (const T*)x, (const T*)R, (const T*)L,
+                       (T*)y, pb.B, pb.k, pb.p, pb.q, pb.s, pb.perm_b() ? 1 : 0);
+    return hip_status(hipGetLastError());
+}
+
 // ------------------------------------------------------------------- backward ----
 //
 // LDS (fp32): xs[BM][n_in], us[BM][kq] (U recomputed), dws[BM][k*s] (dW[b][c*s+l]),
@@ -629,6 +709,29 @@ int generic_bwd(const Problem& pb, const void* dy, const void* x, const void* R,
         if (rc) return rc;
     }
     return 0;
+}
+
+bool generic_fwd_t_supported(const Problem& pb)
+{
+    for (int bm = 8; bm >= 1; bm >>= 1)
+        if ((size_t)bm * fwd_t_floats_per_row(pb) * sizeof(float) <= kMaxLdsBytes) return true;
+    return false;
+}
+
+template <typename T>
+static int generic_fwd_t_typed(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
+{
+    const size_t per_row = fwd_t_floats_per_row(pb) * sizeof(float);
+    if (8 * per_row <= kMaxLdsBytes) return launch_fwd_t<T, 8>(pb, x, R, L, y, st);
+    if (4 * per_row <= kMaxLdsBytes) return launch_fwd_t<T, 4>(pb, x, R, L, y, st);
+    if (2 * per_row <= kMaxLdsBytes) return launch_fwd_t<T, 2>(pb, x, R, L, y, st);
+    if (per_row <= kMaxLdsBytes) return launch_fwd_t<T, 1>(pb, x, R, L, y, st);
+    return -2;
+}
+
+int generic_fwd_t(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
+{
+    return pb.dtype == 0 ? generic_fwd_t_typed<float>(pb, x, R, L, y, st) : generic_fwd_t_typed<bf16_t>(pb, x, R, L, y, st);
 }
 
 }  // namespace monarch

@@ -52,6 +52,10 @@ ColsumJob make_colsum_job(const Problem& pb, const void* dy, void* dbias, void* 
 bool project_supported(int m);
 int launch_project(const void* A, void* R, void* L, int m, int dtype, hipStream_t st);
 
+// transposed multiply y = x M, shape-generic (x (B, k*s) -> y (B, k*p))
+bool generic_fwd_t_supported(const Problem& pb);
+int generic_fwd_t(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
+
 // ---- MFMA kernels for the shapes they are instantiated for (bf16 / fp32 matrix cores) ----
 bool mfma_fwd_supported(const Problem& pb);
 bool mfma_bwd_supported(const Problem& pb);
@@ -64,6 +68,11 @@ bool mfma_fwd_ws_supported(const Problem& pb);
 size_t mfma_fwd_ws_workspace(const Problem& pb);
 const char* mfma_fwd_ws_name(const Problem& pb);
 int mfma_fwd_ws(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);
+// transposed multiply y = x M (x (B, k*s), y (B, n_in)) on the matrix cores
+bool mfma_fwd_t_supported(const Problem& pb);
+size_t mfma_fwd_t_workspace(const Problem& pb);
+const char* mfma_fwd_t_name(const Problem& pb);
+int mfma_fwd_t(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);
 bool mfma_fwd_fuses_bias(const Problem& pb, bool with_ws);
 bool mfma_bwd_fuses_dbias(const Problem& pb);  // the backward computes pb.dbias inside its own launches  // else the caller adds the bias in a second pass
 int mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L,
@@ -85,11 +94,17 @@ size_t bwd_wide_workspace(const Problem& pb);
 int bwd_wide(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx,
              void* dR, void* dL, void* ws, hipStream_t st);
 
+// bf16, k = 4, wide blocks: transposed multiply y = x M on the backward's data kernel
+size_t fwd_t_wide_workspace(const Problem& pb);
+int fwd_t_wide(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);
+
 // bf16, square m = 64 (k = q = s = p = 64): fused forward and backward (monarch_mfma_sq64.hip)
 bool sq64_supported(const Problem& pb);
 int fwd_sq64(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
 size_t fwd_sq64_workspace(const Problem& pb);  // forward on factors packed in fragment order
 int fwd_sq64_ws(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);
+size_t fwd_t_sq64_workspace(const Problem& pb);  // transposed multiply y = x M
+int fwd_t_sq64(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);
 bool bwd_sq64_supported(const Problem& pb);
 size_t bwd_sq64_workspace(const Problem& pb);
 int bwd_sq64(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx,
@@ -98,6 +113,7 @@ int bwd_sq64(const Problem& pb, const void* dy, const void* x, const void* R, co
 // fp32, square m = 16 (k = q = s = p = 16): persistent MFMA kernels (monarch_mfma_sq16.hip)
 bool sq16_supported(const Problem& pb);
 int fwd_sq16(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
+int fwd_t_sq16(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);  // y = x M
 size_t bwd_sq16_workspace(const Problem& pb);
 int bwd_sq16(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx,
              void* dR, void* dL, void* ws, hipStream_t st);

@@ -39,6 +39,29 @@ int mfma_fwd_ws(const Problem& pb, const void* x, const void* R, const void* L, 
     return -2;
 }
 
+// Transposed multiply y = x M: the dx stages of the three backward families on their own.
+bool mfma_fwd_t_supported(const Problem& pb) { return bwd_wide_supported(pb) || sq64_supported(pb) || sq16_supported(pb); }
+size_t mfma_fwd_t_workspace(const Problem& pb)
+{
+    if (bwd_wide_supported(pb)) return fwd_t_wide_workspace(pb);
+    if (sq64_supported(pb)) return fwd_t_sq64_workspace(pb);
+    return 0;
+}
+const char* mfma_fwd_t_name(const Problem& pb)
+{
+    if (bwd_wide_supported(pb)) return "mfma_fwd_t_wide_bf16";
+    if (sq64_supported(pb)) return "mfma_fwd_t_sq64_bf16";
+    if (sq16_supported(pb)) return "mfma_fwd_t_sq16_f32";
+    return "unsupported";
+}
+int mfma_fwd_t(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
+{
+    if (bwd_wide_supported(pb)) return fwd_t_wide(pb, x, R, L, y, ws, st);
+    if (sq64_supported(pb)) return fwd_t_sq64(pb, x, R, L, y, ws, st);
+    if (sq16_supported(pb)) return fwd_t_sq16(pb, x, R, L, y, st);
+    return -2;
+}
+
 // Which of the forward kernels add pb.bias in their own epilogue (the others need launch_bias_add).
 bool mfma_fwd_fuses_bias(const Problem& pb, bool with_ws)
 {

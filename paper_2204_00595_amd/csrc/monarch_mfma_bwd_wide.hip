@@ -158,7 +158,9 @@ __device__ __forceinline__ void wave_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <typename C>
+// DX_ONLY: the transposed multiply y = x M on its own (dy is then the input x of that product, dx its
+// output): the recompute of step 1 and the workspace copies of the two intermediates are left out.
+template <typename C, bool DX_ONLY>
 __global__ void __launch_bounds__(256)
 bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ x,
                      const uint16_t* __restrict__ XF, const uint16_t* __restrict__ LF,
@@ -191,7 +193,9 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
     };
 
     // ------------------------------------------------- X: recompute step 1 -> workspace ----
-    {
+    if constexpr (DX_ONLY) {
+        load_dy(0);
+    } else {
         const int ln = lane & 31, g = lane >> 5;
         f32x16 acc[C::QT * C::NB];
         stage1_block<typename C::S1>(x, XF, b0, B, kk, lane, lds + (size_t)wave * C::S1::XR * 4096, acc);
@@ -290,14 +294,16 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
             dfr[J][bt] = u32x2{pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3])};
         }
     // dY1 -> workspace through LDS (natural layout [b][kk*Q + j])
+    if constexpr (!DX_ONLY) {
 #pragma unroll
-    for (int J = 0; J < C::K * C::JT; ++J)
+        for (int J = 0; J < C::K * C::JT; ++J)
 #pragma unroll
-        for (int bt = 0; bt < C::NBT; ++bt)
-            *reinterpret_cast<u32x2*>(lds + (size_t)(bt * 16 + l16) * C::Y1_STRIDE + kk * C::Q + J * 16 + 4 * h) = dfr[J][bt];
-    __syncthreads();
-    copy_out_tile<C::KQ, 256, false>(lds, C::Y1_STRIDE, dY1ws, C::KQ, b0, B, tid);
-    __syncthreads();
+            for (int bt = 0; bt < C::NBT; ++bt)
+                *reinterpret_cast<u32x2*>(lds + (size_t)(bt * 16 + l16) * C::Y1_STRIDE + kk * C::Q + J * 16 + 4 * h) = dfr[J][bt];
+        __syncthreads();
+        copy_out_tile<C::KQ, 256, false>(lds, C::Y1_STRIDE, dY1ws, C::KQ, b0, B, tid);
+        __syncthreads();
+    }
 
     // ------------------------------------------------- B: dx from the chained fragments ----
     // K-step u covers j in [32u, 32u+32): lane slots 0..3 <- tile 2u, slots 4..7 <- tile 2u+1;
@@ -356,7 +362,7 @@ template <typename C>
 int launch_data(const Problem& pb, const void* dy, const void* x, const uint16_t* XF, const uint16_t* LF,
                 const uint16_t* RF, void* dx, uint16_t* Y1ws, uint16_t* dY1ws, hipStream_t st)
 {
-    auto kern = bwd_wide_data_kernel<C>;
+    auto kern = Y1ws ? bwd_wide_data_kernel<C, false> : bwd_wide_data_kernel<C, true>;  // no workspace copies: dx only
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES) != hipSuccess)
         return -4;
     const int64_t grid = (pb.B + C::BM - 1) / C::BM;
@@ -450,6 +456,25 @@ Plan make_plan(const Problem& pb)
 }  // namespace
 
 bool bwd_wide_supported(const Problem& pb) { return find(pb) != nullptr && make_plan(pb).ok; }
+
+// Transposed multiply through the same data kernel (the weights in fragment order, then the dx stages).
+size_t fwd_t_wide_workspace(const Problem& pb) { return 2 * align_up(pb.n_R() * 2, 256) + align_up(pb.n_L() * 2, 256); }
+
+int fwd_t_wide(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
+{
+    const Entry* e = find(pb);
+    if (!e) return -2;
+    char* w = (char*)ws;
+    uint16_t* XF = (uint16_t*)w;
+    uint16_t* LF = (uint16_t*)(w + align_up(pb.n_R() * 2, 256));
+    uint16_t* RF = (uint16_t*)(w + align_up(pb.n_R() * 2, 256) + align_up(pb.n_L() * 2, 256));
+    const size_t pieces = (2 * pb.n_R() + pb.n_L()) / 8;
+    const int nprep = (int)((pieces + 255) / 256);
+    hipLaunchKernelGGL(prep_frag_kernel, dim3((unsigned)nprep), dim3(256), 0, st, (const uint16_t*)L, (const uint16_t*)R,
+                       XF, LF, RF, pb.p, pb.q, pb.s, e->jg, e->ig, ColsumJob{}, nprep);
+    if (hipGetLastError() != hipSuccess) return -4;
+    return e->fn(pb, x, nullptr, XF, LF, RF, y, nullptr, nullptr, st);
+}
 
 size_t bwd_wide_workspace(const Problem& pb) { return make_plan(pb).total; }
 

@@ -144,6 +144,84 @@ __device__ __forceinline__ void stage_weights_t(const float* __restrict__ W, uns
     }
 }
 
+// Transposed multiply y = x M for the same shape: the two dx stages of the backward kernel below on
+// their own (x plays the part of dy), in the forward kernel's persistent eight-wave form.
+//   dY1[b][kk = r][j = c] = sum_l L[c][l][r] x[b][16l + c]      -> tile [b][j][kk]
+//   y[b][16kk + i]        = sum_j R[kk][j][i] dY1[b][kk][j]     -> tile (row-major), full-row stores
+__global__ void __launch_bounds__(512)
+fwd_t_sq16_kernel(const float* __restrict__ x, const float* __restrict__ R, const float* __restrict__ L,
+                  float* __restrict__ y, int64_t B, int64_t ntiles)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char ldsb[];
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int bl = lane & 15, h = lane >> 4;
+    unsigned char* RTop = ldsb;
+    unsigned char* LTop = ldsb + SQ16_W_BYTES;
+    unsigned char* T = ldsb + 2 * SQ16_W_BYTES + (size_t)wave * SQ16_T_BYTES;
+    const int64_t stride = (int64_t)gridDim.x * SQ16_WAVES;
+    int64_t tile = (int64_t)blockIdx.x * SQ16_WAVES + wave;
+    // The operand of the first stage is xa[v] = x[b][64h + 4v .. +3] (element 16u + c is W[b][c][l = 4h + u]):
+    // 256 contiguous bytes per lane, which as direct loads would touch 64 cache lines per instruction.
+    // The rows are loaded one full 1 KiB row per instruction instead and turned through the tile.
+    auto load_rows = [&](int64_t tl, f32x4 (&raw)[16]) {
+#pragma unroll
+        for (int k2 = 0; k2 < 16; ++k2) {
+            int64_t row = tl * 16 + k2;
+            row = row < B ? row : B - 1;  // rows past the end are computed from a valid row and dropped
+            raw[k2] = ldg128f_nt(x + row * N16 + 4 * lane);
+        }
+    };
+    f32x4 raw[16];
+    if (tile < ntiles) load_rows(tile, raw);  // in flight while the weights are staged
+    stage_weights_t(R, RTop, tid, 512);
+    stage_weights_t(L, LTop, tid, 512);
+    __syncthreads();
+    for (; tile < ntiles; tile += stride) {
+#pragma unroll
+        for (int k2 = 0; k2 < 16; ++k2) *reinterpret_cast<f32x4*>(T + t_off(k2, lane)) = raw[k2];
+        const int64_t next = tile + stride;
+        if (next < ntiles) load_rows(next, raw);  // the next tile's rows are fetched early
+        wave_lds_fence();
+        f32x4 xa[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) xa[v] = *reinterpret_cast<const f32x4*>(T + t_off(bl, 16 * h + v));
+        wave_lds_fence();  // every lane has its operand: the tile is reused for dY1
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            const f32x4 la = *reinterpret_cast<const f32x4*>(LTop + ((size_t)c * 64 + lane) * 16);
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc = mfma4(la[u], xa[4 * u + (c >> 2)][c & 3], acc);
+            *reinterpret_cast<f32x4*>(T + t_off(bl, 4 * c + h)) = acc;
+        }
+        wave_lds_fence();
+        // lane (b, h): dY1[b][kk][j = 4h + u], four kk per read
+        f32x4 db[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) db[u][v] = *reinterpret_cast<const f32x4*>(T + t_off(bl, 4 * (4 * h + u) + v));
+        wave_lds_fence();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            const f32x4 rt = *reinterpret_cast<const f32x4*>(RTop + ((size_t)kk * 64 + lane) * 16);
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc = mfma4(rt[u], db[u][kk >> 2][kk & 3], acc);
+            *reinterpret_cast<f32x4*>(T + t_off(bl, 4 * kk + h)) = acc;
+        }
+        wave_lds_fence();
+        const int64_t b0 = tile * 16;
+#pragma unroll
+        for (int k2 = 0; k2 < 16; ++k2) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(T + t_off(k2, lane));
+            if (b0 + k2 < B) stg128f_nt(y + (b0 + k2) * N16 + 4 * lane, v);
+        }
+        wave_lds_fence();
+    }
+}
+
 // Backward: one persistent kernel for dx, dR and dL (adjoints of steps 3, 2, P^T, 1 of Section 3.3;
 // the paper leaves them to automatic differentiation, Section 4).  4 waves per workgroup, one per
 // SIMD, so that a wave can keep both weight gradients (2 x 4096 fp32 = 128 registers per lane) in
@@ -355,6 +433,20 @@ bool sq16_supported(const Problem& pb)
 {
     // both readings of the mid permutation coincide when k = q
     return pb.dtype == 0 && pb.k == 16 && pb.p == 16 && pb.q == 16 && pb.s == 16;
+}
+
+int fwd_t_sq16(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
+{
+    if (!sq16_supported(pb)) return -2;
+    auto kern = fwd_t_sq16_kernel;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ16_LDS) != hipSuccess)
+        return -4;
+    const int64_t ntiles = (pb.B + 15) / 16;
+    int64_t grid = (ntiles + SQ16_WAVES - 1) / SQ16_WAVES;
+    if (grid > 256) grid = 256;  // one persistent workgroup per CU
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), SQ16_LDS, st, (const float*)x, (const float*)R,
+                       (const float*)L, (float*)y, pb.B, ntiles);
+    return hip_status(hipGetLastError());
 }
 
 int fwd_sq16(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)

@@ -317,6 +317,9 @@ transpose64_kernel(const uint16_t* __restrict__ src, uint16_t* __restrict__ dst)
     }
 }
 
+// DX_ONLY: the transposed multiply y = x M on its own (dW is then the transposed input of that
+// product): no recompute of step 1, no workspace copies of the intermediates.
+template <bool DX_ONLY>
 __global__ void __launch_bounds__(512)
 bwd_sq64_data_kernel(const uint16_t* __restrict__ dW, const uint16_t* __restrict__ x,
                      const uint16_t* __restrict__ R /* packed */, const uint16_t* __restrict__ LT /* packed L^T */,
@@ -332,14 +335,16 @@ bwd_sq64_data_kernel(const uint16_t* __restrict__ dW, const uint16_t* __restrict
 
     uint32_t pk1[4][16];
     // ---- recompute step 1; the exchange layout T[b][j][kk] is U[b][c = j][r = kk]: to the workspace
-    block_stage<true>(t, x + row * N64 + 32 * g, R, ldsb, pk1);
-    __syncthreads();
-    copy_out<false>(t, ldsb, Uws, b0, B, 0);
-    __syncthreads();
-    exchange_write(t, ldsb, pk1);
-    __syncthreads();
-    copy_out<false>(t, ldsb, Uws, b0, B, 32);
-    __syncthreads();
+    if constexpr (!DX_ONLY) {
+        block_stage<true>(t, x + row * N64 + 32 * g, R, ldsb, pk1);
+        __syncthreads();
+        copy_out<false>(t, ldsb, Uws, b0, B, 0);
+        __syncthreads();
+        exchange_write(t, ldsb, pk1);
+        __syncthreads();
+        copy_out<false>(t, ldsb, Uws, b0, B, 32);
+        __syncthreads();
+    }
 
     // ---- adjoint of step 2: dU[b][c][r] = sum_l LT[c][r][l] dW[b][c][l]; as dY1[b][kk = r][j = c]
     // the exchange layout T[b][r][c] is dY1[b][kk][j]: operand order of the next stage, and the
@@ -352,7 +357,7 @@ bwd_sq64_data_kernel(const uint16_t* __restrict__ dW, const uint16_t* __restrict
     for (int h = 0; h < 2; ++h) {
         if (h) exchange_write(t, ldsb, pk1);
         __syncthreads();
-        copy_out<false>(t, ldsb, dY1ws, b0, B, 32 * h);
+        if constexpr (!DX_ONLY) copy_out<false>(t, ldsb, dY1ws, b0, B, 32 * h);
         // dxr[cc][i4]: dx[b = ln][kk = 32h + 8kg + cc][i = 32*it + 8*i4 + 4*g .. +3]
         u32x2 dxr[8][4];
         column_stage<true>(t, RT, ldsb, h, [&](int cc, const f32x16& acc) {
@@ -466,6 +471,33 @@ int fwd_sq64_ws(const Problem& pb, const void* x, const void* R, const void* L, 
 
 bool bwd_sq64_supported(const Problem& pb) { return sq64_supported(pb) && make_plan64(pb).ok; }
 
+// Transposed multiply: input rows re-laid [c][l] (one pass), L^T and R^T packed, then the dx stages.
+size_t fwd_t_sq64_workspace(const Problem& pb)
+{
+    return align_up((size_t)(pb.B > 0 ? pb.B : 1) * N64 * 2, 256) + 2 * align_up((size_t)M64 * M64 * M64 * 2, 256);
+}
+
+int fwd_t_sq64(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
+{
+    if (!sq64_supported(pb)) return -2;
+    const int64_t grid = (pb.B + SQ_BM - 1) / SQ_BM;
+    if (grid > 0x7fffffffLL || pb.B > 0x7fffffffLL) return -2;
+    char* w = (char*)ws;
+    uint16_t* xT = (uint16_t*)w;
+    uint16_t* LT = (uint16_t*)(w + align_up((size_t)pb.B * N64 * 2, 256));
+    uint16_t* RT = LT + align_up((size_t)M64 * M64 * M64 * 2, 256) / 2;
+    const Pack64Job jlt{(const uint16_t*)L, LT, 1}, jrt{(const uint16_t*)R, RT, 1};
+    hipLaunchKernelGGL(pack64_kernel, dim3(2 * 128), dim3(256), 0, st, jlt, jrt, jrt);
+    hipLaunchKernelGGL(transpose64_kernel, dim3((unsigned)pb.B), dim3(256), 0, st, (const uint16_t*)x, xT);
+    if (hipGetLastError() != hipSuccess) return -4;
+    auto kern = bwd_sq64_data_kernel<true>;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ_LDS) != hipSuccess)
+        return -4;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), SQ_LDS, st, xT, (const uint16_t*)nullptr,
+                       (const uint16_t*)nullptr, LT, RT, (uint16_t*)y, (uint16_t*)nullptr, (uint16_t*)nullptr, pb.B);
+    return hip_status(hipGetLastError());
+}
+
 size_t bwd_sq64_workspace(const Problem& pb) { return make_plan64(pb).total; }
 
 int bwd_sq64(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx,
@@ -493,7 +525,7 @@ int bwd_sq64(const Problem& pb, const void* dy, const void* x, const void* R, co
     hipLaunchKernelGGL(pack64_kernel, dim3(3 * 128), dim3(256), 0, st, jr, jlt, jrt);
     hipLaunchKernelGGL(transpose64_kernel, dim3((unsigned)pb.B), dim3(256), 0, st, (const uint16_t*)dy, dWws);
     if (hipGetLastError() != hipSuccess) return -4;
-    auto kern = bwd_sq64_data_kernel;
+    auto kern = bwd_sq64_data_kernel<false>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ_LDS) != hipSuccess)
         return -4;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), SQ_LDS, st, dWws, (const uint16_t*)x, Rp, LT, RT,

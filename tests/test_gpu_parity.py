@@ -502,6 +502,65 @@ def test_rows_beyond_two_to_the_31_elements(B):
         assert abs(v - ref) <= 1e-4 * abs(ref), name
 
 
+# ------------------------------------------------------ transposed multiply (M*) ----
+
+def run_fwd_t(B, sh, xin, R, L, flags=0):
+    """monarch_fwd_t with guarded output and a guarded, 256-byte aligned workspace."""
+    ybuf, y = guarded((xin.shape[0], sh.n_in), tdtype(sh.dtype))
+    code = 0 if sh.dtype == "f32" else 1
+    need = B.monarch_fwd_t_workspace_bytes(xin.shape[0], sh.n_in, sh.k, sh.q, sh.s, code, flags)
+    wbuf = torch.full((need + 512 + 2 * GUARD,), 0x5A, dtype=torch.uint8, device="cuda")
+    off = (-(wbuf.data_ptr() + GUARD)) % 256 + GUARD
+    B.monarch_fwd_t(dev(xin, sh.dtype), dev(R, sh.dtype), dev(L, sh.dtype), y, workspace=wbuf[off:off + need] if need else None, flags=flags)
+    torch.cuda.synchronize()
+    assert bool((wbuf[:off] == 0x5A).all()) and bool((wbuf[off + need:] == 0x5A).all()), "workspace: wrote out of bounds"
+    check_guard(ybuf, "y")
+    out = host(y)
+    assert np.isfinite(out).all(), "y has unwritten or non-finite entries"
+    return out
+
+
+@pytest.mark.parametrize("generic", [False, True], ids=["dispatch", "generic"])
+@pytest.mark.parametrize("case", SMALL + MODEL_LAYERS, ids=lambda c: c[0])
+def test_transposed_multiply_small_shapes(B, case, generic):
+    sh = small_shape(case)
+    flags = B.MONARCH_FLAG_GENERIC if generic else 0
+    _, R, L, xin = synth.make_inputs(sh)  # the upstream-gradient tensor has the input shape of x M
+    print("\n  kernel: %s" % B.monarch_kernel_name(3, sh.n_in, sh.k, sh.q, sh.s, 0 if sh.dtype == "f32" else 1, flags), flush=True)
+    compare(sh, [run_fwd_t(B, sh, xin, R, L, flags)], [oracle.fwd_t(xin, R, L)], ["xM"])
+    if sh.k != sh.q:
+        f = flags | B.MONARCH_FLAG_PERM_B
+        compare(sh, [run_fwd_t(B, sh, xin, R, L, f)], [oracle.fwd_t(xin, R, L, oracle.READING_B)], ["xM_reading_b"])
+    sh0 = synth.Shape("empty", sh.dtype, 0, sh.k, sh.p, sh.q, sh.s)
+    assert run_fwd_t(B, sh0, xin[:0], R, L, flags).shape == (0, sh.n_in)
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_transposed_multiply_full_size(B, name):
+    sh = synth.WORKLOADS[name]
+    z, R, L, xin = synth.make_inputs(sh)
+    got = run_fwd_t(B, sh, xin, R, L)
+    compare(sh, [got], [oracle.fwd_t(xin, R, L)], ["xM"])
+    # adjoint of the multiply, on GPU outputs: <x M, z> = <x, z M^T>
+    y = run_fwd(B, sh, z, R, L)
+    lhs, rhs = np.sum(got * z), np.sum(xin * y)
+    assert abs(lhs - rhs) < 2e-2 * abs(rhs) + 1e-2 * np.sqrt(z.size)
+
+
+def test_hadamard_monarch_times_its_transpose_is_n_times_identity_on_gpu(B):
+    """M = H_256 (all blocks Sylvester H_16): M* then M multiplies small-integer vectors by 256 exactly
+    (the Hadamard transform is in MM*, Proposition 3.2)."""
+    import scipy.linalg
+    m = 16
+    H = scipy.linalg.hadamard(m).astype(np.float32)
+    blocks = np.broadcast_to(H, (m, m, m)).copy()
+    sh = synth.Shape("hadamard_mm", "f32", 70, m, m, m, m)
+    x = np.random.default_rng(3).integers(-3, 4, size=(70, m * m)).astype(np.float32)
+    z = run_fwd_t(B, sh, x, blocks, blocks)
+    assert np.array_equal(z, x.astype(np.float64) @ scipy.linalg.hadamard(m * m).astype(np.float64))
+    assert np.array_equal(run_fwd(B, sh, z.astype(np.float32), blocks, blocks), 256.0 * x)
+
+
 # ------------------------------------------------------ projection (Algorithm 1) ----
 # Only the products L[j][l][k] * R[k][j][i] are determined (sign and scaling of a singular pair are
 # free), so the Monarch matrix is compared, not the factors.  fp32 Jacobi against the fp64 SVD: the

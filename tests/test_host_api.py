@@ -197,6 +197,32 @@ def test_projection_rejects_bad_arguments_without_a_gpu(binding):
     assert call(n=65 * 65, m=65) == binding.MONARCH_ERR_UNSUPPORTED
 
 
+def test_transposed_multiply_rejects_bad_arguments_without_a_gpu(binding):
+    L = binding.lib()
+    p = 4096  # never dereferenced
+    need = binding.monarch_fwd_t_workspace_bytes(0, 768, 4, 192, 192, 1)
+    assert need == 3 * 2 * 4 * 192 * 192                                    # three operand orders of the weights
+    assert binding.monarch_fwd_t_workspace_bytes(100, 4096, 64, 64, 64, 1) == 100 * 4096 * 2 + 2 * 2 * 64 ** 3
+    assert binding.monarch_fwd_t_workspace_bytes(0, 256, 16, 16, 16, 0) == 0
+    assert binding.monarch_fwd_t_workspace_bytes(0, 6, 2, 4, 2, 0) == 0
+    assert binding.monarch_fwd_t_workspace_bytes(0, 768, 4, 192, 192, 1, binding.MONARCH_FLAG_GENERIC) == 0
+
+    def call(x=p, R=p, Lp=p, y=p, ws=p, ws_bytes=need, flags=0, batch=0, n_in=768, k=4, q=192, s=192, dtype=1):
+        return L.monarch_fwd_t(x, R, Lp, y, batch, n_in, k, q, s, dtype, None, ws, ws_bytes, flags)
+
+    assert call() == binding.MONARCH_OK
+    assert call(ws=None) == binding.MONARCH_ERR_WORKSPACE
+    assert call(ws_bytes=need - 1) == binding.MONARCH_ERR_WORKSPACE
+    assert call(ws=p + 16) == binding.MONARCH_ERR_WORKSPACE
+    assert call(R=None) == binding.MONARCH_ERR_INVALID
+    assert call(x=None, batch=2) == binding.MONARCH_ERR_INVALID
+    assert call(n_in=770) == binding.MONARCH_ERR_INVALID
+    assert call(flags=binding.MONARCH_FLAG_WGRAD_F32) == binding.MONARCH_ERR_INVALID
+    assert call(flags=binding.MONARCH_FLAG_WS_PACKED) == binding.MONARCH_ERR_INVALID
+    assert call(ws=None, ws_bytes=0, flags=binding.MONARCH_FLAG_GENERIC) == binding.MONARCH_OK
+    assert call(ws=None, ws_bytes=0, n_in=6, k=2, q=4, s=2, dtype=0) == binding.MONARCH_OK
+
+
 def test_stream_copy_rejects_bad_arguments_without_a_gpu(binding):
     L = binding.lib()
     assert L.monarch_stream_copy(None, None, 0, None) == binding.MONARCH_OK          # empty copy: no-op
@@ -208,7 +234,11 @@ def test_stream_copy_rejects_bad_arguments_without_a_gpu(binding):
 
 def test_kernel_name_reports_dispatch(binding):
     assert binding.monarch_kernel_name(0, 770, 4, 192, 192, 1) == "invalid"
-    assert binding.monarch_kernel_name(3, 768, 4, 192, 192, 1) == "invalid"
+    assert binding.monarch_kernel_name(4, 768, 4, 192, 192, 1) == "invalid"
+    assert binding.monarch_kernel_name(3, 768, 4, 192, 192, 1) == "mfma_fwd_t_wide_bf16"
+    assert binding.monarch_kernel_name(3, 4096, 64, 64, 64, 1) == "mfma_fwd_t_sq64_bf16"
+    assert binding.monarch_kernel_name(3, 256, 16, 16, 16, 0) == "mfma_fwd_t_sq16_f32"
+    assert binding.monarch_kernel_name(3, 6, 2, 4, 2, 0) == "generic_fwd_t"
     assert binding.monarch_kernel_name(2, 768, 4, 192, 192, 1) == "mfma_fwd_frag_bf16"
     assert binding.monarch_kernel_name(2, 4096, 64, 64, 64, 1) == "mfma_fwd_sq64_packed_bf16"
     assert binding.monarch_kernel_name(2, 6, 2, 4, 2, 0) == "generic_fwd"   # no packed-weight kernel: same as pass 0
