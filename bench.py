@@ -140,7 +140,27 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True, wi
     fwd_ws_ms = float(np.mean([run_of(fwd_ws_only) for _ in range(3)])) if fneed else None
     fwd_ws_packed_ms = float(np.mean([run_of(fwd_ws_packed) for _ in range(3)])) if fneed else None
     fwd_bias_ms = fwd_then_add_ms = bwd_bias_ms = to_dense_ms = to_dense_gbs = project_ms = fwd_t_ms = None
+    fwd_save_ms = bwd_saved_ms = step_saved_ms = None
     if with_extras:
+        # forward that saves the vector between the factors + backward that reads it instead of recomputing
+        sneed = binding.monarch_saved_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, code, 0)
+        svs = [torch.empty(sneed, dtype=torch.uint8, device=dev) for _ in range(nsets)] if sneed else None
+
+        def fwd_save_only(i):
+            xs, _, y, _ = sets[i % nsets]
+            binding.monarch_fwd_save(xs, Rd, Ld, y, svs[i % nsets])
+
+        def bwd_saved_only(i):
+            xs, dys, _, dx = sets[i % nsets]
+            binding.monarch_bwd_saved(dys, xs, svs[i % nsets], Rd, Ld, dx, dR, dL, workspace=ws)
+
+        def step_saved(i):
+            fwd_save_only(i)
+            bwd_saved_only(i)
+
+        fwd_save_ms = float(np.mean([run_of(fwd_save_only) for _ in range(3)])) if sneed else None
+        bwd_saved_ms = float(np.mean([run_of(bwd_saved_only) for _ in range(3)])) if sneed else None
+        step_saved_ms = float(np.mean([run_of(step_saved) for _ in range(3)])) if sneed else None
         # affine layer: bias fused into the forward (where the kernel has the epilogue), bias gradient with the backward;
         # beside them the unfused forms (the plain call, then a separate elementwise add / column sum by the framework)
         biasd = torch.from_numpy(synth.quantize(synth.normal(4242, (sh.n_out,)), sh.dtype)).to(dev).to(dt)
@@ -207,6 +227,8 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True, wi
         "to_dense_ms": to_dense_ms, "to_dense_gbs": to_dense_gbs,
         "fwd_t_ms": fwd_t_ms, "fwd_t_kernel": binding.monarch_kernel_name(3, sh.n_in, sh.k, sh.q, sh.s, code),  # monarch_fwd_t
         "project_ms": project_ms,  # monarch_project of a dense n x n matrix (square shapes), else null
+        # monarch_fwd_save / monarch_bwd_saved (the intermediate goes through HBM once instead of being recomputed); null without that path
+        "fwd_save_ms": fwd_save_ms, "bwd_saved_ms": bwd_saved_ms, "step_saved_ms": step_saved_ms,
         "fwd_kernel": binding.monarch_kernel_name(0, sh.n_in, sh.k, sh.q, sh.s, code),
         "bwd_kernel": binding.monarch_kernel_name(1, sh.n_in, sh.k, sh.q, sh.s, code),
         "fwd_tflops": sh.fwd_flops() / (fwd_ms * 1e-3) / 1e12,
@@ -334,6 +356,11 @@ def main():
         "roofline": roof,
         "detail": r,
     }
+    if r.get("step_saved_ms"):
+        # the same step through monarch_fwd_save + monarch_bwd_saved (intermediate kept in HBM, not recomputed);
+        # same FLOP count as the headline (the recompute is not counted there either)
+        line["step_with_saved_intermediate"] = {"ms_per_step": r["step_saved_ms"],
+                                                "value": flops / (r["step_saved_ms"] * 1e-3) / 1e12, "unit": "TFLOP/s"}
     line["hbm_copy_gbs"] = copy_roof()
     roof["frac_of_copy_roof"] = (roof["achieved"] / line["hbm_copy_gbs"]) if roof["bound"] == "hbm" else None
     if args.all:

@@ -157,6 +157,30 @@ int monarch_bwd_bias(const void* dy, const void* x, const void* R, const void* L
                      monarch_dtype dtype, void* stream,
                      void* workspace, size_t workspace_bytes, unsigned flags);
 
+/* Forward and backward that share the vector between the two factors instead of recomputing it (the
+ * paper differentiates the multiply automatically, Section 4, which keeps the intermediate of step 1
+ * for the backward pass; monarch_bwd recomputes it from x).  monarch_fwd_save is monarch_fwd_ex that
+ * also writes that vector into `saved` (monarch_saved_bytes(...) bytes, device memory, 16-byte
+ * aligned, caller-owned, contents opaque); monarch_bwd_saved is monarch_bwd_bias that reads it from
+ * there and skips the recompute.  x is still needed (dR).  `saved` must come from monarch_fwd_save
+ * with the same x, R, L, shape and flags.  For shapes whose kernels have no such path
+ * monarch_saved_bytes returns 0, `saved` may be NULL and the two calls are monarch_fwd_ex and
+ * monarch_bwd_bias exactly; a NULL `saved` in monarch_bwd_saved always means "recompute".
+ * Errors as the calls they extend; a missing, misaligned or short `saved` buffer is
+ * MONARCH_ERR_WORKSPACE. */
+size_t monarch_saved_bytes(int64_t batch, int n_in, int k, int q, int s,
+                           monarch_dtype dtype, unsigned flags);
+int monarch_fwd_save(const void* x, const void* R, const void* L, void* y,
+                     void* saved, size_t saved_bytes,
+                     int64_t batch, int n_in, int k, int q, int s,
+                     monarch_dtype dtype, void* stream, unsigned flags);
+int monarch_bwd_saved(const void* dy, const void* x, const void* saved, size_t saved_bytes,
+                      const void* R, const void* L,
+                      void* dx, void* dR, void* dL, void* dbias,
+                      int64_t batch, int n_in, int k, int q, int s,
+                      monarch_dtype dtype, void* stream,
+                      void* workspace, size_t workspace_bytes, unsigned flags);
+
 /* Bytes of device scratch monarch_bwd and monarch_bwd_bias need for this problem (never 0 for a
  * valid problem; 0 on invalid arguments). */
 size_t monarch_bwd_workspace_bytes(int64_t batch, int n_in, int k, int q, int s,

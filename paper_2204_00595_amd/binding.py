@@ -32,7 +32,7 @@ EXPORTS = (
     "monarch_fwd", "monarch_fwd_ex", "monarch_fwd_ws", "monarch_fwd_bias", "monarch_fwd_workspace_bytes", "monarch_bwd",
     "monarch_bwd_bias",
     "monarch_bwd_workspace_bytes",
-    "monarch_fwd_t", "monarch_fwd_t_workspace_bytes", "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy",
+    "monarch_fwd_t", "monarch_fwd_t_workspace_bytes", "monarch_saved_bytes", "monarch_fwd_save", "monarch_bwd_saved", "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy",
 )
 
 _lib = None
@@ -76,6 +76,12 @@ def lib() -> ctypes.CDLL:
         L.monarch_fwd_t.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
         L.monarch_fwd_t_workspace_bytes.restype = sz
         L.monarch_fwd_t_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci, cu]
+        L.monarch_saved_bytes.restype = sz
+        L.monarch_saved_bytes.argtypes = [i64, ci, ci, ci, ci, ci, cu]
+        L.monarch_fwd_save.restype = ci
+        L.monarch_fwd_save.argtypes = [vp, vp, vp, vp, vp, sz, i64, ci, ci, ci, ci, ci, vp, cu]
+        L.monarch_bwd_saved.restype = ci
+        L.monarch_bwd_saved.argtypes = [vp, vp, vp, sz, vp, vp, vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
         L.monarch_project.restype = ci
         L.monarch_project.argtypes = [vp, vp, vp, ci, ci, ci, vp, cu]
         L.monarch_kernel_name.restype = ctypes.c_char_p
@@ -375,3 +381,78 @@ def monarch_fwd_t(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.Te
     if rc != MONARCH_OK:
         raise MonarchError(rc, "monarch_fwd_t")
     return y
+
+
+def monarch_saved_bytes(batch: int, n_in: int, k: int, q: int, s: int, dtype: int, flags: int = 0) -> int:
+    return int(lib().monarch_saved_bytes(batch, n_in, k, q, s, dtype, flags))
+
+
+def monarch_fwd_save(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.Tensor | None = None,
+                     saved: torch.Tensor | None = None, flags: int = 0, stream=None):
+    """(y, saved): y = x M^T, and the buffer monarch_bwd_saved reads instead of recomputing (None when
+    the shape has no such path)."""
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    dev, dt = x.device, x.dtype
+    _check(x, "x", (B, k * p), dt, dev)
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    if y is None:
+        y = torch.empty((B, k * s), dtype=dt, device=dev)
+    _check(y, "y", (B, k * s), dt, dev)
+    need = monarch_saved_bytes(B, k * p, k, q, s, _dtype_code(x), flags)
+    if saved is None and need:
+        saved = torch.empty(need, dtype=torch.uint8, device=dev)
+    sv_ptr = saved.data_ptr() if saved is not None else 0
+    sv_len = saved.numel() * saved.element_size() if saved is not None else 0
+    with torch.cuda.device(dev):
+        rc = lib().monarch_fwd_save(x.data_ptr(), R.data_ptr(), L.data_ptr(), y.data_ptr(), sv_ptr, sv_len, B, k * p,
+                                    k, q, s, _dtype_code(x), _stream_ptr(stream), flags)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_fwd_save")
+    return y, (saved if need else None)
+
+
+def monarch_bwd_saved(dy: torch.Tensor, x: torch.Tensor, saved: torch.Tensor | None, R: torch.Tensor, L: torch.Tensor,
+                      dx: torch.Tensor | None = None, dR: torch.Tensor | None = None, dL: torch.Tensor | None = None,
+                      dbias: torch.Tensor | None = None, want_dbias: bool = False,
+                      workspace: torch.Tensor | None = None, flags: int = 0, stream=None):
+    """(dx, dR, dL, dbias or None) with the vector saved by monarch_fwd_save (None: recompute)."""
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    dev, dt = x.device, x.dtype
+    _check(x, "x", (B, k * p), dt, dev)
+    _check(dy, "dy", (B, k * s), dt, dev)
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    gdt = torch.float32 if (flags & MONARCH_FLAG_WGRAD_F32) else dt
+    if dx is None:
+        dx = torch.empty_like(x)
+    if dR is None:
+        dR = torch.empty((k, q, p), dtype=gdt, device=dev)
+    if dL is None:
+        dL = torch.empty((k, s, q), dtype=gdt, device=dev)
+    if dbias is None and want_dbias:
+        dbias = torch.empty((k * s,), dtype=gdt, device=dev)
+    _check(dx, "dx", (B, k * p), dt, dev)
+    _check(dR, "dR", (k, q, p), gdt, dev)
+    _check(dL, "dL", (k, s, q), gdt, dev)
+    if dbias is not None:
+        _check(dbias, "dbias", (k * s,), gdt, dev)
+    need = monarch_bwd_workspace_bytes(B, k * p, k, q, s, _dtype_code(x), flags)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_ptr = workspace.data_ptr() if workspace is not None else 0
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    sv_ptr = saved.data_ptr() if saved is not None else 0
+    sv_len = saved.numel() * saved.element_size() if saved is not None else 0
+    with torch.cuda.device(dev):
+        rc = lib().monarch_bwd_saved(dy.data_ptr(), x.data_ptr(), sv_ptr, sv_len, R.data_ptr(), L.data_ptr(),
+                                     dx.data_ptr(), dR.data_ptr(), dL.data_ptr(),
+                                     dbias.data_ptr() if dbias is not None else 0, B, k * p, k, q, s,
+                                     _dtype_code(x), _stream_ptr(stream), ws_ptr, ws_len, flags)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_bwd_saved")
+    return dx, dR, dL, dbias

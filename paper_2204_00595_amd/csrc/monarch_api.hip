@@ -145,6 +145,31 @@ int monarch_fwd_bias(const void* x, const void* R, const void* L, const void* bi
     return launch_bias_add(pb, y, st);
 }
 
+size_t monarch_saved_bytes(int64_t batch, int n_in, int k, int q, int s, monarch_dtype dtype, unsigned flags)
+{
+    Problem pb;
+    if (make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags)) return 0;
+    if ((flags & MONARCH_FLAG_GENERIC) || !saved_supported(pb)) return 0;
+    return align_up((size_t)(batch > 0 ? batch : 1) * pb.kq() * pb.esize(), 256);
+}
+
+int monarch_fwd_save(const void* x, const void* R, const void* L, void* y, void* saved, size_t saved_bytes,
+                     int64_t batch, int n_in, int k, int q, int s, monarch_dtype dtype, void* stream, unsigned flags)
+{
+    const size_t need = monarch_saved_bytes(batch, n_in, k, q, s, dtype, flags);
+    if (need == 0) return monarch_fwd_ex(x, R, L, y, batch, n_in, k, q, s, dtype, stream, flags);
+    Problem pb;
+    int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
+    if (rc) return rc;
+    if (flags & (MONARCH_FLAG_WGRAD_F32 | MONARCH_FLAG_WS_PACKED)) return MONARCH_ERR_INVALID;
+    if (!R || !L || ((!x || !y) && batch > 0)) return MONARCH_ERR_INVALID;
+    if (!aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(y, 16)) return MONARCH_ERR_INVALID;
+    if (!saved || saved_bytes < need || !aligned(saved, 16)) return MONARCH_ERR_WORKSPACE;
+    if (batch == 0) return MONARCH_OK;
+    pb.saved = saved;
+    return mfma_fwd(pb, x, R, L, y, (hipStream_t)stream);
+}
+
 size_t monarch_bwd_workspace_bytes(int64_t batch, int n_in, int k, int q, int s, monarch_dtype dtype,
                                    unsigned flags)
 {
@@ -166,6 +191,14 @@ int monarch_bwd_bias(const void* dy, const void* x, const void* R, const void* L
                      void* dbias, int64_t batch, int n_in, int k, int q, int s, monarch_dtype dtype, void* stream,
                      void* workspace, size_t workspace_bytes, unsigned flags)
 {
+    return monarch_bwd_saved(dy, x, nullptr, 0, R, L, dx, dR, dL, dbias, batch, n_in, k, q, s, dtype, stream, workspace,
+                             workspace_bytes, flags);
+}
+
+int monarch_bwd_saved(const void* dy, const void* x, const void* saved, size_t saved_bytes, const void* R,
+                      const void* L, void* dx, void* dR, void* dL, void* dbias, int64_t batch, int n_in, int k, int q,
+                      int s, monarch_dtype dtype, void* stream, void* workspace, size_t workspace_bytes, unsigned flags)
+{
     Problem pb;
     int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
     if (rc) return rc;
@@ -176,6 +209,13 @@ int monarch_bwd_bias(const void* dy, const void* x, const void* R, const void* L
         return MONARCH_ERR_INVALID;
     const Family fam = pick_bwd(pb);
     if (fam == FAM_NONE) return MONARCH_ERR_UNSUPPORTED;
+    if (saved) {  // ignored by the kernel families that recompute
+        const size_t sneed = monarch_saved_bytes(batch, n_in, k, q, s, dtype, flags);
+        if (sneed > 0) {
+            if (saved_bytes < sneed || !aligned(saved, 16)) return MONARCH_ERR_WORKSPACE;
+            pb.saved = const_cast<void*>(saved);
+        }
+    }
     const size_t need = bwd_need(pb, fam);
     if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return MONARCH_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;

@@ -12,6 +12,7 @@ struct Problem {
     int dtype;       // 0 = f32, 1 = bf16
     unsigned flags;  // MONARCH_FLAG_*
     const void* bias = nullptr;  // forward only: n_out values of `dtype` added to every output row (may be null)
+    void* saved = nullptr;       // forward: also write the vector between the factors here; backward: read it from here
     void* dbias = nullptr;       // backward only: bias gradient wanted (fp32 when wgrad_f32(), else `dtype`)
     void* colsum_ws = nullptr;   // backward only: colsum_workspace() bytes for the bias gradient's partial rows
     int n_out() const { return k * s; }
@@ -88,6 +89,9 @@ bool fwd_frag_supported(const Problem& pb);
 size_t fwd_frag_workspace(const Problem& pb);
 int fwd_frag(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);
 
+// bf16, k = 4, wide blocks: the forward can save the vector between the two factors (B x k*q bf16, stage-2
+// order) and the backward can take it from there instead of recomputing it (pb.saved on both sides)
+bool saved_supported(const Problem& pb);
 // bf16, k = 4, wide blocks: backward (monarch_mfma_bwd_wide.hip)
 bool bwd_wide_supported(const Problem& pb);
 size_t bwd_wide_workspace(const Problem& pb);

@@ -158,9 +158,11 @@ __device__ __forceinline__ void wave_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// DX_ONLY: the transposed multiply y = x M on its own (dy is then the input x of that product, dx its
-// output): the recompute of step 1 and the workspace copies of the two intermediates are left out.
-template <typename C, bool DX_ONLY>
+// MODE 0: everything.  MODE 1: the transposed multiply y = x M on its own (dy is then the input x of
+// that product, dx its output): the recompute of step 1 and the workspace copies of both intermediates
+// are left out.  MODE 2: the forward saved the vector between the factors, so step 1 is not recomputed;
+// dY1 still goes to the workspace for the weight-gradient GEMM.
+template <typename C, int MODE>
 __global__ void __launch_bounds__(256)
 bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ x,
                      const uint16_t* __restrict__ XF, const uint16_t* __restrict__ LF,
@@ -193,7 +195,7 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
     };
 
     // ------------------------------------------------- X: recompute step 1 -> workspace ----
-    if constexpr (DX_ONLY) {
+    if constexpr (MODE != 0) {
         load_dy(0);
     } else {
         const int ln = lane & 31, g = lane >> 5;
@@ -294,7 +296,7 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
             dfr[J][bt] = u32x2{pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3])};
         }
     // dY1 -> workspace through LDS (natural layout [b][kk*Q + j])
-    if constexpr (!DX_ONLY) {
+    if constexpr (MODE != 1) {
 #pragma unroll
         for (int J = 0; J < C::K * C::JT; ++J)
 #pragma unroll
@@ -362,7 +364,8 @@ template <typename C>
 int launch_data(const Problem& pb, const void* dy, const void* x, const uint16_t* XF, const uint16_t* LF,
                 const uint16_t* RF, void* dx, uint16_t* Y1ws, uint16_t* dY1ws, hipStream_t st)
 {
-    auto kern = Y1ws ? bwd_wide_data_kernel<C, false> : bwd_wide_data_kernel<C, true>;  // no workspace copies: dx only
+    // no workspace for dY1: dx only; dY1 but no Y1 workspace: the forward saved that vector
+    auto kern = !dY1ws ? bwd_wide_data_kernel<C, 1> : (Y1ws ? bwd_wide_data_kernel<C, 0> : bwd_wide_data_kernel<C, 2>);
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES) != hipSuccess)
         return -4;
     const int64_t grid = (pb.B + C::BM - 1) / C::BM;
@@ -456,6 +459,7 @@ Plan make_plan(const Problem& pb)
 }  // namespace
 
 bool bwd_wide_supported(const Problem& pb) { return find(pb) != nullptr && make_plan(pb).ok; }
+bool saved_supported(const Problem& pb) { return bwd_wide_supported(pb) && fwd_wide_supported(pb); }
 
 // Transposed multiply through the same data kernel (the weights in fragment order, then the dx stages).
 size_t fwd_t_wide_workspace(const Problem& pb) { return 2 * align_up(pb.n_R() * 2, 256) + align_up(pb.n_L() * 2, 256); }
@@ -504,12 +508,17 @@ int bwd_wide(const Problem& pb, const void* dy, const void* x, const void* R, co
     hipLaunchKernelGGL(prep_frag_kernel, dim3((unsigned)(nprep + (want_db ? colsum_partial_blocks(cj) : 0))), dim3(256), 0,
                        st, (const uint16_t*)L, (const uint16_t*)R, XF, LF, RF, pb.p, pb.q, pb.s, e->jg, e->ig, cj, nprep);
     if (hipGetLastError() != hipSuccess) return -4;
-    int rc = e->fn(pb, dy, x, XF, LF, RF, dx, Y1ws, dY1ws, st);
+    int rc = e->fn(pb, dy, x, XF, LF, RF, dx, pb.saved ? nullptr : Y1ws, dY1ws, st);
     if (rc) return rc;
 
     WgradDesc dl, dr;
     fill_descs(pb, dl, dr);
     dl.A = (const uint16_t*)dy; dl.Bm = Y1ws; dl.P = (float*)(w + pl.off_partL); dl.out = dL;
+    if (pb.saved) {
+        // the saved vector is in stage-2 order: group c owns the Q contiguous columns c*Q .. of every row
+        dl.Bm = (const uint16_t*)pb.saved;
+        dl.b_g = pb.q; dl.b_seg = 0; dl.seg_w = pb.q;
+    }
     dr.A = dY1ws; dr.Bm = (const uint16_t*)x; dr.P = (float*)(w + pl.off_partR); dr.out = dR;
     dl.rows_per_chunk = dr.rows_per_chunk = pl.rows_per_chunk;
     rc = wgrad_gemm_pair(dl, dr, pl.nz, st);

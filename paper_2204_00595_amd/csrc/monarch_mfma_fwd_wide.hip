@@ -340,10 +340,12 @@ __device__ __forceinline__ void stage2_pass(const uint16_t* __restrict__ L, cons
     }
 }
 
-template <typename C>
+// SAVE: the vector between the two factors is also written out, in stage-2 order U[b][c*Q + r]
+// (r = 4*r1 + kk  <->  Y1[b][kk][c*Q/4 + r1]), for a backward that does not recompute it.
+template <typename C, bool SAVE>
 __global__ void __launch_bounds__(256)
 fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
-                const uint16_t* __restrict__ L, uint16_t* __restrict__ y, int64_t B)
+                const uint16_t* __restrict__ L, uint16_t* __restrict__ y, uint16_t* __restrict__ saved, int64_t B)
 {
     extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
     const int tid = threadIdx.x;
@@ -452,7 +454,6 @@ fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
                 }
     }
     __syncthreads();
-
     // ------------------------------------------------------------- stage 2 ----
     {
         uint16_t* stg = lds + C::LDS_Y1 / 2 + (size_t)wave * (C::STG2 / 2);
@@ -471,18 +472,48 @@ fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
             }
         }
     }
+    // Last, so that nothing in stage 2 queues behind these stores (Y1s is only read after stage 1).
+    if constexpr (SAVE) {
+        // Y1s holds, per row and per group of four j, the 16 values [kk][j % 4]; U wants them as [j % 4][kk]
+        // (U index 4*j + kk): a 4 x 4 transpose of 16-bit values inside each 32-byte group, then 32
+        // contiguous bytes per group and 2*K*Q contiguous bytes per row go out.
+        // Two lanes share a group, each writing one 16-byte half, so that a store instruction of a wave
+        // covers 1 KiB of contiguous output (full cache lines).
+        constexpr int PIECES = C::KQ / 8, TASKS = C::BM * PIECES;
+#pragma unroll 4
+        for (int t = tid; t < TASKS; t += 256) {
+            const int row = t / PIECES, pc = t - row * PIECES;
+            const int gq = pc >> 1, half = pc & 1;
+            if (b0 + row < B) {
+                const uint16_t* src = lds + (size_t)row * C::Y1_STRIDE + gq * 16;
+                const u32x4 a = lds128(src), b = lds128(src + 8);
+                const uint32_t in[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+                uint32_t o[4];
+#pragma unroll
+                for (int w4 = 0; w4 < 4; ++w4) {
+                    // output dword w = 4*half + w4 holds (j % 4 = w / 2; kk = 2*(w % 2), 2*(w % 2) + 1)
+                    const int k0 = 2 * (w4 & 1);
+                    const uint32_t lo0 = in[k0 * 2], hi0 = in[(k0 + 1) * 2];          // j % 4 in {0, 1}
+                    const uint32_t lo1 = in[k0 * 2 + 1], hi1 = in[(k0 + 1) * 2 + 1];  // j % 4 in {2, 3}
+                    const uint32_t lo = half ? lo1 : lo0, hi = half ? hi1 : hi0;
+                    o[w4] = (w4 >> 1) ? pick_hi16(lo, hi) : pick_lo16(lo, hi);
+                }
+                stg128_nt(saved + (b0 + row) * C::KQ + pc * 8, u32x4{o[0], o[1], o[2], o[3]});
+            }
+        }
+    }
 }
 
 template <typename C>
 int launch(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
 {
-    auto kern = fwd_wide_kernel<C>;
+    auto kern = pb.saved ? fwd_wide_kernel<C, true> : fwd_wide_kernel<C, false>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
     if (e != hipSuccess) return -4;
     const int64_t grid = (pb.B + C::BM - 1) / C::BM;
     if (grid > 0x7fffffffLL) return -2;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), C::LDS_BYTES, st, (const uint16_t*)x,
-                       (const uint16_t*)R, (const uint16_t*)L, (uint16_t*)y, pb.B);
+                       (const uint16_t*)R, (const uint16_t*)L, (uint16_t*)y, (uint16_t*)pb.saved, pb.B);
     return hip_status(hipGetLastError());
 }
 

@@ -502,6 +502,56 @@ def test_rows_beyond_two_to_the_31_elements(B):
         assert abs(v - ref) <= 1e-4 * abs(ref), name
 
 
+# --------------------------------------------- forward that saves, backward that reuses ----
+
+@pytest.mark.parametrize("case", [("k4_192", "bf16", 200, 4, 192, 192, 192), ("k4_64_128", "bf16", 97, 4, 64, 64, 128),
+                                  ("k4_128_64", "bf16", 65, 4, 128, 64, 64)] + MODEL_LAYERS +
+                         [("sq_m64", "bf16", 40, 64, 64, 64, 64), ("sq_m16", "f32", 70, 16, 16, 16, 16), ("rect", "f32", 19, 3, 2, 6, 5)],
+                         ids=lambda c: c[0])
+def test_saved_intermediate_forward_and_backward(B, case):
+    """monarch_fwd_save gives the same y as monarch_fwd; monarch_bwd_saved, fed its buffer, gives the
+    gradients of the recomputing backward (against the oracle; dx and dR even bit for bit: their path
+    does not change).  Shapes without the path fall back to the plain calls."""
+    sh = small_shape(case)
+    code = 0 if sh.dtype == "f32" else 1
+    x, R, L, dy = synth.make_inputs(sh)
+    xd, Rd, Ld, dyd = (dev(a, sh.dtype) for a in (x, R, L, dy))
+    need = B.monarch_saved_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, code)
+    assert (need > 0) == (sh.k == 4 and sh.dtype == "bf16")
+    sbuf = torch.full((need + 2 * GUARD,), 0x5A, dtype=torch.uint8, device="cuda")
+    saved = sbuf[GUARD:GUARD + need] if need else None
+    ybuf, y = guarded((sh.B, sh.n_out), tdtype(sh.dtype))
+    B.monarch_fwd_save(xd, Rd, Ld, y, saved)
+    torch.cuda.synchronize()
+    check_guard(ybuf, "y")
+    assert bool((sbuf[:GUARD] == 0x5A).all()) and bool((sbuf[GUARD + need:] == 0x5A).all()), "saved: wrote out of bounds"
+    assert torch.equal(y, B.monarch_fwd(xd, Rd, Ld))
+    compare(sh, [host(y)], [oracle.fwd(x, R, L)], ["y"])
+    want = oracle.bwd_bias(dy, x, R, L)
+    plain = B.monarch_bwd_bias(dyd, xd, Rd, Ld)
+    got = B.monarch_bwd_saved(dyd, xd, saved, Rd, Ld, want_dbias=True)
+    torch.cuda.synchronize()
+    compare(sh, [host(t) for t in got], want, ["dx", "dR", "dL", "dbias"])
+    if need:
+        assert torch.equal(got[0], plain[0]) and torch.equal(got[1], plain[1]) and torch.equal(got[3], plain[3])
+        # a NULL buffer means "recompute"
+        again = B.monarch_bwd_saved(dyd, xd, None, Rd, Ld)
+        assert all(torch.equal(a, b) for a, b in zip(again[:3], plain[:3]))
+    got32 = B.monarch_bwd_saved(dyd, xd, saved, Rd, Ld, flags=B.MONARCH_FLAG_WGRAD_F32)
+    compare(sh, [host(t) for t in got32[:3]], want[:3], ["dx", "dR32", "dL32"])
+
+
+@pytest.mark.parametrize("name", ["vitb_proj", "gpt2s_fc1", "gpt2m_fc1", "gpt2m_fc2"])
+def test_saved_intermediate_full_size(B, name):
+    sh = synth.WORKLOADS[name]
+    x, R, L, dy = synth.make_inputs(sh)
+    xd, Rd, Ld, dyd = (dev(a, sh.dtype) for a in (x, R, L, dy))
+    y, saved = B.monarch_fwd_save(xd, Rd, Ld)
+    got = B.monarch_bwd_saved(dyd, xd, saved, Rd, Ld)
+    torch.cuda.synchronize()
+    compare(sh, [host(y)] + [host(t) for t in got[:3]], [oracle.fwd(x, R, L)] + list(oracle.bwd(dy, x, R, L)), ["y", "dx", "dR", "dL"])
+
+
 # ------------------------------------------------------ transposed multiply (M*) ----
 
 def run_fwd_t(B, sh, xin, R, L, flags=0):

@@ -223,6 +223,41 @@ def test_transposed_multiply_rejects_bad_arguments_without_a_gpu(binding):
     assert call(ws=None, ws_bytes=0, n_in=6, k=2, q=4, s=2, dtype=0) == binding.MONARCH_OK
 
 
+def test_saved_intermediate_calls_reject_bad_arguments_without_a_gpu(binding):
+    L = binding.lib()
+    p = 4096  # never dereferenced
+    need = binding.monarch_saved_bytes(1000, 768, 4, 192, 192, 1)
+    assert need == 1000 * 768 * 2                                   # B x k*q bf16
+    assert binding.monarch_saved_bytes(1000, 4096, 64, 64, 64, 1) == 0   # kernels that recompute
+    assert binding.monarch_saved_bytes(1000, 256, 16, 16, 16, 0) == 0
+    assert binding.monarch_saved_bytes(1000, 768, 4, 192, 192, 1, binding.MONARCH_FLAG_GENERIC) == 0
+    assert binding.monarch_saved_bytes(1000, 770, 4, 192, 192, 1) == 0
+
+    def fwd(x=p, R=p, Lp=p, y=p, sv=p, sv_bytes=need, batch=1000, n_in=768, k=4, q=192, s=192, dtype=1, flags=0):
+        return L.monarch_fwd_save(x, R, Lp, y, sv, sv_bytes, batch, n_in, k, q, s, dtype, None, flags)
+
+    assert fwd(sv=None) == binding.MONARCH_ERR_WORKSPACE
+    assert fwd(sv_bytes=need - 1) == binding.MONARCH_ERR_WORKSPACE
+    assert fwd(sv=p + 8) == binding.MONARCH_ERR_WORKSPACE
+    assert fwd(R=None) == binding.MONARCH_ERR_INVALID
+    assert fwd(y=None) == binding.MONARCH_ERR_INVALID
+    assert fwd(n_in=770) == binding.MONARCH_ERR_INVALID
+    assert fwd(flags=binding.MONARCH_FLAG_WGRAD_F32) == binding.MONARCH_ERR_INVALID
+    assert fwd(batch=0, sv_bytes=binding.monarch_saved_bytes(0, 768, 4, 192, 192, 1)) == binding.MONARCH_OK
+    # shapes without the path: the plain forward, no buffer needed
+    assert fwd(sv=None, sv_bytes=0, batch=0, n_in=6, k=2, q=4, s=2, dtype=0) == binding.MONARCH_OK
+
+    bneed = binding.monarch_bwd_workspace_bytes(1000, 768, 4, 192, 192, 1, 0)
+
+    def bwd(sv=p, sv_bytes=need, ws=p, ws_bytes=bneed, flags=0, dbias=None):
+        return L.monarch_bwd_saved(p, p, sv, sv_bytes, p, p, p, p, p, dbias, 1000, 768, 4, 192, 192, 1, None, ws, ws_bytes, flags)
+
+    assert bwd(sv_bytes=need - 1) == binding.MONARCH_ERR_WORKSPACE
+    assert bwd(sv=p + 8) == binding.MONARCH_ERR_WORKSPACE
+    assert bwd(ws=None) == binding.MONARCH_ERR_WORKSPACE
+    assert bwd(flags=binding.MONARCH_FLAG_WS_PACKED) == binding.MONARCH_ERR_INVALID
+
+
 def test_stream_copy_rejects_bad_arguments_without_a_gpu(binding):
     L = binding.lib()
     assert L.monarch_stream_copy(None, None, 0, None) == binding.MONARCH_OK          # empty copy: no-op
