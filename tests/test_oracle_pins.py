@@ -445,3 +445,61 @@ def test_hadamard_monarch_times_its_transpose_is_n_times_identity():
     rng = np.random.default_rng(56)
     x = rng.integers(-3, 4, size=(5, m * m)).astype(np.float64)
     assert np.array_equal(oracle.fwd(oracle.fwd_t(x, blocks, blocks), blocks, blocks), m * m * x)
+
+
+# ------------------------------------------------------- complex-valued Monarch ----
+
+from oracle import complex_ref  # noqa: E402
+
+
+def _crand(rng, *shape):
+    return rng.standard_normal(shape) + 1j * rng.standard_normal(shape)
+
+
+@pytest.mark.parametrize("reading", READINGS)
+@pytest.mark.parametrize("shape", [(3, 3, 3, 3)] + TINY_RECT[:4])
+def test_complex_forward_is_the_literal_dense_product(shape, reading):
+    """Definition 3.1 with complex blocks: M = Pout BD(L) Pmid BD(R) from explicit permutation matrices
+    and scipy's block_diag; real inputs reduce to the real oracle."""
+    k, p, q, s = shape
+    rng = np.random.default_rng(61)
+    x, R, L = _crand(rng, 4, k * p), _crand(rng, k, q, p), _crand(rng, k, s, q)
+    M = dense.out_perm(k, s) @ scipy.linalg.block_diag(*L) @ dense.mid_perm(k, q, reading) @ scipy.linalg.block_diag(*R)
+    assert np.allclose(complex_ref.fwd(x, R, L, reading), x @ M.T, rtol=0, atol=1e-12)
+    got = complex_ref.fwd(x.real, R.real, L.real, reading)
+    assert np.allclose(got.imag, 0) and np.allclose(got.real, oracle.fwd(x.real, R.real, L.real, reading), rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("m", [2, 3, 4, 8])
+def test_dft_is_a_monarch_matrix(m):
+    """The 4-step splitting: Monarch(dft_factors) applied to x equals the library FFT of the grid-
+    transposed input, and the inverse factors undo it."""
+    n = m * m
+    rng = np.random.default_rng(62)
+    x = _crand(rng, 5, n)
+    xt = x.reshape(5, m, m).transpose(0, 2, 1).reshape(5, n)
+    R, L = complex_ref.dft_factors(m)
+    assert np.allclose(complex_ref.fwd(x, R, L), np.fft.fft(xt, axis=1), rtol=0, atol=1e-10)
+    Ri, Li = complex_ref.dft_factors(m, inverse=True)
+    assert np.allclose(complex_ref.fwd(x, Ri, Li), np.fft.ifft(xt, axis=1), rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("reading", READINGS)
+@pytest.mark.parametrize("shape", [(2, 2, 2, 2), (3, 2, 4, 2)])
+def test_complex_gradients_match_unit_step_differences(shape, reading):
+    """Loss = Re <dy, y> = sum Re(conj(dy) y) is real and linear in each of x, R, L: a unit step in the
+    real (imaginary) part of a coordinate changes it by the real (imaginary) part of the gradient."""
+    k, p, q, s = shape
+    rng = np.random.default_rng(63)
+    x, R, L, dy = _crand(rng, 3, k * p), _crand(rng, k, q, p), _crand(rng, k, s, q), _crand(rng, 3, k * s)
+    loss = lambda x_, R_, L_: float(np.sum((np.conj(dy) * complex_ref.fwd(x_, R_, L_, reading)).real))
+    base = loss(x, R, L)
+    grads = complex_ref.bwd(dy, x, R, L, reading)
+    for which, (arr, g) in enumerate(zip((x, R, L), grads)):
+        for idx in np.ndindex(arr.shape):
+            for step, part in ((1.0, g[idx].real), (1j, g[idx].imag)):
+                moved = arr.copy()
+                moved[idx] += step
+                args = [x, R, L]
+                args[which] = moved
+                assert abs(loss(*args) - base - part) < 1e-10, (which, idx, step)
