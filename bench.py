@@ -139,7 +139,7 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True, wi
 
     fwd_ws_ms = float(np.mean([run_of(fwd_ws_only) for _ in range(3)])) if fneed else None
     fwd_ws_packed_ms = float(np.mean([run_of(fwd_ws_packed) for _ in range(3)])) if fneed else None
-    fwd_bias_ms = fwd_then_add_ms = bwd_bias_ms = to_dense_ms = to_dense_gbs = project_ms = fwd_t_ms = None
+    fwd_bias_ms = fwd_then_add_ms = bwd_bias_ms = to_dense_ms = to_dense_gbs = project_ms = fwd_t_ms = c64_fwd_ms = c64_bwd_ms = c64_rows = None
     fwd_save_ms = bwd_saved_ms = step_saved_ms = None
     if with_extras:
         # forward that saves the vector between the factors + backward that reads it instead of recomputing
@@ -199,6 +199,14 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True, wi
         dense_bytes = (sh.k * sh.q * sh.p + sh.k * sh.s * sh.q + sh.n_out * sh.n_in) * sh.esize
         to_dense_gbs = dense_bytes / (to_dense_ms * 1e-3) / 1e9
         if sh.k == sh.p == sh.q == sh.s:
+            # complex64 multiply with the DFT factors (shape-generic SIMT kernels) on the first rows of the batch
+            crow = min(sh.B, 2048)
+            cx = torch.randn((crow, sh.n_in), dtype=torch.complex64, device=dev, generator=torch.Generator(device=dev).manual_seed(7))
+            cR, cL = binding.monarch_dft_factors(sh.k, False, device=dev)
+            cy = torch.empty_like(cx)
+            c64_fwd_ms = float(np.mean([run_of(lambda i: binding.monarch_fwd_c64(cx, cR, cL, cy)) for _ in range(2)]))
+            c64_bwd_ms = float(np.mean([run_of(lambda i: binding.monarch_bwd_c64(cy, cx, cR, cL)) for _ in range(2)]))
+            c64_rows = crow
             # Algorithm 1 on a dense Gaussian n x n matrix (square shapes only): one Jacobi SVD per slice
             Adense = torch.from_numpy(synth.quantize(synth.normal(4343, (sh.n_in, sh.n_in)), sh.dtype)).to(dev).to(dt)
             Rp, Lp = torch.empty_like(Rd), torch.empty_like(Ld)
@@ -226,6 +234,7 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True, wi
         # monarch_to_dense: M written out as a dense (n_out, n_in) matrix; bytes = R + L read, M written
         "to_dense_ms": to_dense_ms, "to_dense_gbs": to_dense_gbs,
         "fwd_t_ms": fwd_t_ms, "fwd_t_kernel": binding.monarch_kernel_name(3, sh.n_in, sh.k, sh.q, sh.s, code),  # monarch_fwd_t
+        "c64_fwd_ms": c64_fwd_ms, "c64_bwd_ms": c64_bwd_ms, "c64_rows": c64_rows,  # monarch_fwd_c64 / monarch_bwd_c64 on c64_rows rows
         "project_ms": project_ms,  # monarch_project of a dense n x n matrix (square shapes), else null
         # monarch_fwd_save / monarch_bwd_saved (the intermediate goes through HBM once instead of being recomputed); null without that path
         "fwd_save_ms": fwd_save_ms, "bwd_saved_ms": bwd_saved_ms, "step_saved_ms": step_saved_ms,

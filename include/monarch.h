@@ -241,6 +241,28 @@ int monarch_to_dense(const void* R, const void* L, void* M,
 int monarch_project(const void* A, void* R, void* L, int n, int m,
                     monarch_dtype dtype, void* stream, unsigned flags);
 
+/* Complex-valued Monarch multiply.  The paper's results hold over the complex numbers as well
+ * (Notation Review), and its MRI reconstruction model is a single complex Monarch matrix.  Same steps,
+ * shapes and layouts as monarch_fwd_ex / monarch_bwd, every element a complex64 (two fp32: real part,
+ * then imaginary part); products and sums in fp32.  The forward applies M^T (no conjugation).  The
+ * backward returns, for a real loss, grad z = dLoss/dRe z + i dLoss/dIm z (the convention of automatic
+ * differentiation):  dx = dy conj(M),  dL[c] = dW[c]^T conj(U[c]),  dR[kk] = dY1[kk]^T conj(x[kk]).
+ * Shape-generic kernels only; dR and dL are reduced with fp32 atomics (reproducible up to summation
+ * order); no workspace.  flags: MONARCH_FLAG_PERM_B only. */
+int monarch_fwd_c64(const void* x, const void* R, const void* L, void* y,
+                    int64_t batch, int n_in, int k, int q, int s, void* stream, unsigned flags);
+int monarch_bwd_c64(const void* dy, const void* x, const void* R, const void* L,
+                    void* dx, void* dR, void* dL,
+                    int64_t batch, int n_in, int k, int q, int s, void* stream, unsigned flags);
+
+/* Factors that make the square complex Monarch matrix a discrete Fourier transform (the model of the
+ * MRI experiment starts from the inverse FFT): with n = m*m and w = exp(-2 pi i / n),
+ *   R[kk][j][i] = w^(m*i*j),   L[j][l][kk] = w^(kk*j + m*kk*l)
+ * give  P L P^T R = F_n P  (the DFT of the input read as an m x m grid and transposed: the 4-step
+ * splitting).  inverse != 0: conjugate factors, L scaled by 1/n (F_n^{-1} P).  R and L are (m, m, m)
+ * complex64 device arrays, 16-byte aligned; m <= 1024. */
+int monarch_dft_factors(void* R, void* L, int m, int inverse, void* stream);
+
 /* Name of the kernel family the dispatcher picks for this problem: pass 0 = forward
  * (monarch_fwd / monarch_fwd_ex), 1 = backward, 2 = forward with workspace (monarch_fwd_ws),
  * 3 = transposed multiply (monarch_fwd_t).  Static string, never NULL ("invalid" / "unsupported" on bad input). */

@@ -32,7 +32,7 @@ EXPORTS = (
     "monarch_fwd", "monarch_fwd_ex", "monarch_fwd_ws", "monarch_fwd_bias", "monarch_fwd_workspace_bytes", "monarch_bwd",
     "monarch_bwd_bias",
     "monarch_bwd_workspace_bytes",
-    "monarch_fwd_t", "monarch_fwd_t_workspace_bytes", "monarch_saved_bytes", "monarch_fwd_save", "monarch_bwd_saved", "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy",
+    "monarch_fwd_t", "monarch_fwd_t_workspace_bytes", "monarch_saved_bytes", "monarch_fwd_save", "monarch_bwd_saved", "monarch_fwd_c64", "monarch_bwd_c64", "monarch_dft_factors", "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy",
 )
 
 _lib = None
@@ -82,6 +82,12 @@ def lib() -> ctypes.CDLL:
         L.monarch_fwd_save.argtypes = [vp, vp, vp, vp, vp, sz, i64, ci, ci, ci, ci, ci, vp, cu]
         L.monarch_bwd_saved.restype = ci
         L.monarch_bwd_saved.argtypes = [vp, vp, vp, sz, vp, vp, vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
+        L.monarch_fwd_c64.restype = ci
+        L.monarch_fwd_c64.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, vp, cu]
+        L.monarch_bwd_c64.restype = ci
+        L.monarch_bwd_c64.argtypes = [vp] * 7 + [i64, ci, ci, ci, ci, vp, cu]
+        L.monarch_dft_factors.restype = ci
+        L.monarch_dft_factors.argtypes = [vp, vp, ci, ci, vp]
         L.monarch_project.restype = ci
         L.monarch_project.argtypes = [vp, vp, vp, ci, ci, ci, vp, cu]
         L.monarch_kernel_name.restype = ctypes.c_char_p
@@ -456,3 +462,55 @@ def monarch_bwd_saved(dy: torch.Tensor, x: torch.Tensor, saved: torch.Tensor | N
     if rc != MONARCH_OK:
         raise MonarchError(rc, "monarch_bwd_saved")
     return dx, dR, dL, dbias
+
+
+def monarch_fwd_c64(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.Tensor | None = None,
+                    flags: int = 0, stream=None) -> torch.Tensor:
+    """y = x M^T for complex64 tensors (same shapes as monarch_fwd)."""
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    dev, dt = x.device, torch.complex64
+    _check(x, "x", (B, k * p), dt, dev)
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    if y is None:
+        y = torch.empty((B, k * s), dtype=dt, device=dev)
+    _check(y, "y", (B, k * s), dt, dev)
+    with torch.cuda.device(dev):
+        rc = lib().monarch_fwd_c64(x.data_ptr(), R.data_ptr(), L.data_ptr(), y.data_ptr(), B, k * p, k, q, s,
+                                   _stream_ptr(stream), flags)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_fwd_c64")
+    return y
+
+
+def monarch_bwd_c64(dy: torch.Tensor, x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, flags: int = 0, stream=None):
+    """(dx, dR, dL) for complex64 tensors, gradients in the dRe + i dIm convention."""
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    dev, dt = x.device, torch.complex64
+    _check(x, "x", (B, k * p), dt, dev)
+    _check(dy, "dy", (B, k * s), dt, dev)
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    dx, dR, dL = torch.empty_like(x), torch.empty_like(R), torch.empty_like(L)
+    with torch.cuda.device(dev):
+        rc = lib().monarch_bwd_c64(dy.data_ptr(), x.data_ptr(), R.data_ptr(), L.data_ptr(), dx.data_ptr(),
+                                   dR.data_ptr(), dL.data_ptr(), B, k * p, k, q, s, _stream_ptr(stream), flags)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_bwd_c64")
+    return dx, dR, dL
+
+
+def monarch_dft_factors(m: int, inverse: bool = False, device="cuda", stream=None):
+    """(R, L): complex64 factors with P L P^T R = F_n P (n = m*m), or its inverse."""
+    dev = torch.device(device)
+    R = torch.empty((m, m, m), dtype=torch.complex64, device=dev)
+    L = torch.empty((m, m, m), dtype=torch.complex64, device=dev)
+    with torch.cuda.device(dev):
+        rc = lib().monarch_dft_factors(R.data_ptr(), L.data_ptr(), m, 1 if inverse else 0, _stream_ptr(stream))
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_dft_factors")
+    return R, L

@@ -274,6 +274,42 @@ int monarch_to_dense(const void* R, const void* L, void* M, int n_in, int k, int
     return launch_to_dense(pb, R, L, M, (hipStream_t)stream);
 }
 
+int monarch_fwd_c64(const void* x, const void* R, const void* L, void* y, int64_t batch, int n_in, int k, int q, int s,
+                    void* stream, unsigned flags)
+{
+    Problem pb;
+    int rc = make_problem(pb, batch, n_in, k, q, s, MONARCH_F32, flags);
+    if (rc) return rc;
+    if (flags & ~MONARCH_FLAG_PERM_B) return MONARCH_ERR_INVALID;
+    if (!R || !L || ((!x || !y) && batch > 0)) return MONARCH_ERR_INVALID;
+    if (!aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(y, 16)) return MONARCH_ERR_INVALID;
+    if (!complex_fwd_supported(pb)) return MONARCH_ERR_UNSUPPORTED;
+    if (batch == 0) return MONARCH_OK;
+    return complex_fwd(pb, x, R, L, y, (hipStream_t)stream);
+}
+
+int monarch_bwd_c64(const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR, void* dL,
+                    int64_t batch, int n_in, int k, int q, int s, void* stream, unsigned flags)
+{
+    Problem pb;
+    int rc = make_problem(pb, batch, n_in, k, q, s, MONARCH_F32, flags);
+    if (rc) return rc;
+    if (flags & ~MONARCH_FLAG_PERM_B) return MONARCH_ERR_INVALID;
+    if (!R || !L || !dR || !dL || ((!dy || !x || !dx) && batch > 0)) return MONARCH_ERR_INVALID;
+    if (!aligned(dy, 16) || !aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(dx, 16) ||
+        !aligned(dR, 16) || !aligned(dL, 16))
+        return MONARCH_ERR_INVALID;
+    if (!complex_bwd_supported(pb)) return MONARCH_ERR_UNSUPPORTED;
+    return complex_bwd(pb, dy, x, R, L, dx, dR, dL, (hipStream_t)stream);
+}
+
+int monarch_dft_factors(void* R, void* L, int m, int inverse, void* stream)
+{
+    if (m <= 0 || !R || !L || !aligned(R, 16) || !aligned(L, 16)) return MONARCH_ERR_INVALID;
+    if (m > 1024) return MONARCH_ERR_UNSUPPORTED;  // m^3 factor entries, n = m^2 up to 2^20
+    return launch_dft_factors(R, L, m, inverse ? 1 : 0, (hipStream_t)stream);
+}
+
 int monarch_project(const void* A, void* R, void* L, int n, int m, monarch_dtype dtype, void* stream, unsigned flags)
 {
     if (n <= 0 || m <= 0 || (int64_t)m * m != (int64_t)n) return MONARCH_ERR_INVALID;

@@ -1,0 +1,294 @@
+// Complex-valued Monarch multiply (complex64: interleaved fp32 real and imaginary parts) and the
+// factors that make the Monarch matrix a DFT.  The paper's results hold over C as well (Notation
+// Review), and its MRI model is one complex Monarch matrix initialised to the inverse FFT.
+//
+// Same steps as the real kernels (Section 3.3 steps 1-3, permutations of Definition 3.1), in the
+// shape-generic SIMT form: one workgroup per tile of BM batch rows, the vectors between the steps in
+// LDS, one thread per output element with BM complex accumulators, so every weight is read once per
+// workgroup.  No transposes are conjugated in the forward (M^T, not M^*).  Gradients use the
+// convention of automatic differentiation for a real loss: grad z = dLoss/dRe z + i dLoss/dIm z, i.e.
+//   dU = dW conj(L),  dL = dW^T conj(U),  dx = dY1 conj(R),  dR = dY1^T conj(x).
+#include "monarch_internal.h"
+#include "monarch_device.h"
+
+namespace monarch {
+namespace {
+
+constexpr int kCThreads = 256;
+
+struct cf {
+    float re, im;
+};
+__device__ __forceinline__ cf cmul_acc(cf acc, cf a, cf b)  // acc + a * b
+{
+    acc.re = fmaf(a.re, b.re, fmaf(-a.im, b.im, acc.re));
+    acc.im = fmaf(a.re, b.im, fmaf(a.im, b.re, acc.im));
+    return acc;
+}
+__device__ __forceinline__ cf cmul_conj_acc(cf acc, cf a, cf b)  // acc + a * conj(b)
+{
+    acc.re = fmaf(a.re, b.re, fmaf(a.im, b.im, acc.re));
+    acc.im = fmaf(a.im, b.re, fmaf(-a.re, b.im, acc.im));
+    return acc;
+}
+__device__ __forceinline__ cf ldc(const float2* p) { const float2 v = *p; return cf{v.x, v.y}; }
+
+template <int BM>
+__global__ void __launch_bounds__(kCThreads)
+complex_fwd_kernel(const float2* __restrict__ x, const float2* __restrict__ R, const float2* __restrict__ L,
+                   float2* __restrict__ y, int64_t B, int k, int p, int q, int s, int perm_b)
+{
+    extern __shared__ float2 ldsc[];
+    const int n_in = k * p, kq = k * q, n_out = k * s;
+    float2* xs = ldsc;
+    float2* us = ldsc + (size_t)BM * n_in;
+    const int64_t b0 = (int64_t)blockIdx.x * BM;
+    const int tid = threadIdx.x;
+    for (int e = tid; e < BM * n_in; e += kCThreads) {
+        const int b = e / n_in, c = e - b * n_in;
+        const int64_t row = b0 + b;
+        xs[e] = row < B ? x[row * n_in + c] : make_float2(0.f, 0.f);
+    }
+    __syncthreads();
+    for (int f = tid; f < kq; f += kCThreads) {
+        const int kk = f / q;
+        const float2* Rrow = R + (size_t)f * p;
+        const float2* xk = xs + kk * p;
+        cf acc[BM];
+#pragma unroll
+        for (int b = 0; b < BM; ++b) acc[b] = cf{0.f, 0.f};
+        for (int i = 0; i < p; ++i) {
+            const cf w = ldc(Rrow + i);
+#pragma unroll
+            for (int b = 0; b < BM; ++b) acc[b] = cmul_acc(acc[b], w, ldc(xk + b * n_in + i));
+        }
+        const int g = mid_dest(f, k, q, perm_b != 0);
+#pragma unroll
+        for (int b = 0; b < BM; ++b) us[b * kq + g] = make_float2(acc[b].re, acc[b].im);
+    }
+    __syncthreads();
+    for (int o = tid; o < n_out; o += kCThreads) {
+        const int l = o / k, c = o - l * k;
+        const float2* Lrow = L + ((size_t)c * s + l) * q;
+        const float2* uc = us + c * q;
+        cf acc[BM];
+#pragma unroll
+        for (int b = 0; b < BM; ++b) acc[b] = cf{0.f, 0.f};
+        for (int r = 0; r < q; ++r) {
+            const cf w = ldc(Lrow + r);
+#pragma unroll
+            for (int b = 0; b < BM; ++b) acc[b] = cmul_acc(acc[b], w, ldc(uc + b * kq + r));
+        }
+#pragma unroll
+        for (int b = 0; b < BM; ++b) {
+            const int64_t row = b0 + b;
+            if (row < B) y[row * n_out + o] = make_float2(acc[b].re, acc[b].im);
+        }
+    }
+}
+
+// LDS: xs[BM][n_in], us[BM][kq] (U recomputed), dws[BM][k*s] (dW[b][c*s + l]), dus[BM][kq] (dU).
+// dx is written directly; the dR and dL contributions of the tile are added with fp32 atomics (one
+// per component) into dR / dL, which the host zero-filled before the launch.
+template <int BM>
+__global__ void __launch_bounds__(kCThreads)
+complex_bwd_kernel(const float2* __restrict__ dy, const float2* __restrict__ x, const float2* __restrict__ R,
+                   const float2* __restrict__ L, float2* __restrict__ dx, float* __restrict__ dRacc,
+                   float* __restrict__ dLacc, int64_t B, int k, int p, int q, int s, int perm_b)
+{
+    extern __shared__ float2 ldsc[];
+    const int n_in = k * p, kq = k * q, n_out = k * s;
+    float2* xs = ldsc;
+    float2* us = xs + (size_t)BM * n_in;
+    float2* dws = us + (size_t)BM * kq;
+    float2* dus = dws + (size_t)BM * n_out;
+    const int64_t b0 = (int64_t)blockIdx.x * BM;
+    const int tid = threadIdx.x;
+    const bool pb = perm_b != 0;
+    for (int e = tid; e < BM * n_in; e += kCThreads) {
+        const int b = e / n_in, c = e - b * n_in;
+        const int64_t row = b0 + b;
+        xs[e] = row < B ? x[row * n_in + c] : make_float2(0.f, 0.f);
+    }
+    for (int e = tid; e < BM * n_out; e += kCThreads) {
+        const int b = e / n_out, o = e - b * n_out;
+        const int l = o / k, c = o - l * k;
+        const int64_t row = b0 + b;
+        dws[b * n_out + c * s + l] = row < B ? dy[row * n_out + o] : make_float2(0.f, 0.f);
+    }
+    __syncthreads();
+    for (int f = tid; f < kq; f += kCThreads) {  // step 1 again, with the mid permutation
+        const int kk = f / q;
+        const float2* Rrow = R + (size_t)f * p;
+        const float2* xk = xs + kk * p;
+        cf acc[BM];
+#pragma unroll
+        for (int b = 0; b < BM; ++b) acc[b] = cf{0.f, 0.f};
+        for (int i = 0; i < p; ++i) {
+            const cf w = ldc(Rrow + i);
+#pragma unroll
+            for (int b = 0; b < BM; ++b) acc[b] = cmul_acc(acc[b], w, ldc(xk + b * n_in + i));
+        }
+        const int g = mid_dest(f, k, q, pb);
+#pragma unroll
+        for (int b = 0; b < BM; ++b) us[b * kq + g] = make_float2(acc[b].re, acc[b].im);
+    }
+    for (int g = tid; g < kq; g += kCThreads) {  // dU[c*q + r] = sum_l dW[c][l] conj(L[c][l][r])
+        const int c = g / q, r = g - c * q;
+        const float2* Lcol = L + (size_t)c * s * q + r;
+        const float2* dwc = dws + c * s;
+        cf acc[BM];
+#pragma unroll
+        for (int b = 0; b < BM; ++b) acc[b] = cf{0.f, 0.f};
+        for (int l = 0; l < s; ++l) {
+            const cf w = ldc(Lcol + (size_t)l * q);
+#pragma unroll
+            for (int b = 0; b < BM; ++b) acc[b] = cmul_conj_acc(acc[b], ldc(dwc + b * n_out + l), w);
+        }
+#pragma unroll
+        for (int b = 0; b < BM; ++b) dus[b * kq + g] = make_float2(acc[b].re, acc[b].im);
+    }
+    __syncthreads();
+    for (int n = tid; n < n_in; n += kCThreads) {  // dx[kk*p + i] = sum_j dY1[kk][j] conj(R[kk][j][i])
+        const int kk = n / p, i = n - kk * p;
+        const float2* Rcol = R + (size_t)kk * q * p + i;
+        cf acc[BM];
+#pragma unroll
+        for (int b = 0; b < BM; ++b) acc[b] = cf{0.f, 0.f};
+        for (int j = 0; j < q; ++j) {
+            const cf w = ldc(Rcol + (size_t)j * p);
+            const int g = mid_dest(kk * q + j, k, q, pb);
+#pragma unroll
+            for (int b = 0; b < BM; ++b) acc[b] = cmul_conj_acc(acc[b], ldc(dus + b * kq + g), w);
+        }
+#pragma unroll
+        for (int b = 0; b < BM; ++b) {
+            const int64_t row = b0 + b;
+            if (row < B) dx[row * n_in + n] = make_float2(acc[b].re, acc[b].im);
+        }
+    }
+    const int nL = k * s * q;
+    for (int e = tid; e < nL; e += kCThreads) {  // dL[c][l][r] += sum_b dW[b][c][l] conj(U[b][c][r])
+        const int cl = e / q, r = e - cl * q;
+        const int c = cl / s;
+        cf v = cf{0.f, 0.f};
+#pragma unroll
+        for (int b = 0; b < BM; ++b) v = cmul_conj_acc(v, ldc(dws + b * n_out + cl), ldc(us + b * kq + c * q + r));
+        unsafeAtomicAdd(dLacc + 2 * (size_t)e, v.re);
+        unsafeAtomicAdd(dLacc + 2 * (size_t)e + 1, v.im);
+    }
+    const int nR = kq * p;
+    for (int e = tid; e < nR; e += kCThreads) {  // dR[kk][j][i] += sum_b dY1[b][kk][j] conj(x[b][kk*p + i])
+        const int f = e / p, i = e - f * p;
+        const int kk = f / q;
+        const int g = mid_dest(f, k, q, pb);
+        cf v = cf{0.f, 0.f};
+#pragma unroll
+        for (int b = 0; b < BM; ++b) v = cmul_conj_acc(v, ldc(dus + b * kq + g), ldc(xs + b * n_in + kk * p + i));
+        unsafeAtomicAdd(dRacc + 2 * (size_t)e, v.re);
+        unsafeAtomicAdd(dRacc + 2 * (size_t)e + 1, v.im);
+    }
+}
+
+// R[kk][j][i] = w^(i*j*m),  L[j][l][kk] = w^(kk*j + kk*l*m) (times 1/n for the inverse),  w = exp(-+2 pi i / n):
+// the 4-step splitting of the DFT of the grid-transposed input, P L P^T R = F_n P.  Exponents are reduced
+// mod n in integers and the sine / cosine taken in double precision, then rounded to fp32.
+__global__ void __launch_bounds__(256) dft_factors_kernel(float2* __restrict__ R, float2* __restrict__ L, int m, int inverse)
+{
+    const int n = m * m;
+    const int64_t total = (int64_t)m * m * m;
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int a = (int)(e / n), b = (int)((e / m) % m), c = (int)(e % m);
+    const double sgn = inverse ? 2.0 : -2.0;
+    {  // R[kk = a][j = b][i = c]
+        const int64_t ex = ((int64_t)c * b * m) % n;
+        double sn, cs;
+        sincospi(sgn * (double)ex / (double)n, &sn, &cs);
+        R[e] = make_float2((float)cs, (float)sn);
+    }
+    {  // L[j = a][l = b][kk = c]
+        const int64_t ex = ((int64_t)c * a + (int64_t)c * b * m) % n;
+        double sn, cs;
+        sincospi(sgn * (double)ex / (double)n, &sn, &cs);
+        const double scale = inverse ? 1.0 / (double)n : 1.0;
+        L[e] = make_float2((float)(cs * scale), (float)(sn * scale));
+    }
+}
+
+size_t fwd_bytes_per_row(const Problem& pb) { return ((size_t)pb.n_in + pb.kq()) * sizeof(float2); }
+size_t bwd_bytes_per_row(const Problem& pb) { return ((size_t)pb.n_in + 2 * (size_t)pb.kq() + pb.n_out()) * sizeof(float2); }
+
+int pick_rows(size_t bytes_per_row)
+{
+    for (int bm = 4; bm >= 1; bm >>= 1)
+        if ((size_t)bm * bytes_per_row <= kMaxLdsBytes) return bm;
+    return 0;
+}
+
+template <int BM>
+int launch_cfwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
+{
+    const size_t lds = (size_t)BM * fwd_bytes_per_row(pb);
+    auto kern = complex_fwd_kernel<BM>;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return -4;
+    const int64_t grid = (pb.B + BM - 1) / BM;
+    if (grid > 0x7fffffffLL) return -2;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kCThreads), lds, st, (const float2*)x, (const float2*)R,
+                       (const float2*)L, (float2*)y, pb.B, pb.k, pb.p, pb.q, pb.s, pb.perm_b() ? 1 : 0);
+    return hip_status(hipGetLastError());
+}
+
+template <int BM>
+int launch_cbwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
+                void* dL, hipStream_t st)
+{
+    const size_t lds = (size_t)BM * bwd_bytes_per_row(pb);
+    auto kern = complex_bwd_kernel<BM>;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return -4;
+    const int64_t grid = (pb.B + BM - 1) / BM;
+    if (grid > 0x7fffffffLL) return -2;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kCThreads), lds, st, (const float2*)dy, (const float2*)x,
+                       (const float2*)R, (const float2*)L, (float2*)dx, (float*)dR, (float*)dL, pb.B, pb.k, pb.p, pb.q,
+                       pb.s, pb.perm_b() ? 1 : 0);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace
+
+bool complex_fwd_supported(const Problem& pb) { return pick_rows(fwd_bytes_per_row(pb)) > 0; }
+bool complex_bwd_supported(const Problem& pb) { return pick_rows(bwd_bytes_per_row(pb)) > 0; }
+
+int complex_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
+{
+    switch (pick_rows(fwd_bytes_per_row(pb))) {
+        case 4: return launch_cfwd<4>(pb, x, R, L, y, st);
+        case 2: return launch_cfwd<2>(pb, x, R, L, y, st);
+        case 1: return launch_cfwd<1>(pb, x, R, L, y, st);
+        default: return -2;
+    }
+}
+
+int complex_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
+                void* dL, hipStream_t st)
+{
+    int rc = launch_fill_zero_f32((float*)dR, 2 * pb.n_R(), st);
+    if (rc) return rc;
+    rc = launch_fill_zero_f32((float*)dL, 2 * pb.n_L(), st);
+    if (rc || pb.B == 0) return rc;
+    switch (pick_rows(bwd_bytes_per_row(pb))) {
+        case 4: return launch_cbwd<4>(pb, dy, x, R, L, dx, dR, dL, st);
+        case 2: return launch_cbwd<2>(pb, dy, x, R, L, dx, dR, dL, st);
+        case 1: return launch_cbwd<1>(pb, dy, x, R, L, dx, dR, dL, st);
+        default: return -2;
+    }
+}
+
+int launch_dft_factors(void* R, void* L, int m, int inverse, hipStream_t st)
+{
+    const int64_t total = (int64_t)m * m * m;
+    hipLaunchKernelGGL(dft_factors_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (float2*)R, (float2*)L, m, inverse);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace monarch

@@ -57,6 +57,14 @@ int launch_project(const void* A, void* R, void* L, int m, int dtype, hipStream_
 bool generic_fwd_t_supported(const Problem& pb);
 int generic_fwd_t(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
 
+// complex64 (interleaved fp32 pairs), shape-generic (monarch_complex.hip); Problem.dtype is ignored there
+bool complex_fwd_supported(const Problem& pb);
+bool complex_bwd_supported(const Problem& pb);
+int complex_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
+int complex_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
+                void* dL, hipStream_t st);
+int launch_dft_factors(void* R, void* L, int m, int inverse, hipStream_t st);
+
 // ---- MFMA kernels for the shapes they are instantiated for (bf16 / fp32 matrix cores) ----
 bool mfma_fwd_supported(const Problem& pb);
 bool mfma_bwd_supported(const Problem& pb);

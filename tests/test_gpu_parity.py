@@ -611,6 +611,70 @@ def test_hadamard_monarch_times_its_transpose_is_n_times_identity_on_gpu(B):
     assert np.array_equal(run_fwd(B, sh, z.astype(np.float32), blocks, blocks), 256.0 * x)
 
 
+# ------------------------------------------------------------- complex-valued ----
+
+def cdev(a):
+    return torch.from_numpy(np.ascontiguousarray(a.astype(np.complex64))).cuda()
+
+
+def cnormal(seed, shape, std=1.0):
+    """Complex Gaussian with fp32-representable parts (both sides consume the same complex64 values)."""
+    return (synth.normal(seed, shape, std) + 1j * synth.normal(seed + 1, shape, std)).astype(np.complex64)
+
+
+COMPLEX_CASES = [("c_sq4", 9, 4, 4, 4, 4), ("c_sq16", 70, 16, 16, 16, 16), ("c_rect", 33, 3, 4, 5, 2), ("c_k4", 130, 4, 32, 32, 48),
+                 ("c_one_row", 1, 2, 3, 4, 2)]
+
+
+@pytest.mark.parametrize("reading", [0, 1], ids=["reading_a", "reading_b"])
+@pytest.mark.parametrize("case", COMPLEX_CASES, ids=lambda c: c[0])
+def test_complex_forward_and_backward(B, case, reading):
+    from oracle import complex_ref
+    name, rows, k, p, q, s = case
+    x, R, L, dy = (cnormal(8000 + 10 * i, shp, std) for i, (shp, std) in enumerate(
+        (((rows, k * p), 1.0), ((k, q, p), p ** -0.5), ((k, s, q), q ** -0.5), ((rows, k * s), 1.0))))
+    flags = B.MONARCH_FLAG_PERM_B if reading else 0
+    y = B.monarch_fwd_c64(cdev(x), cdev(R), cdev(L), flags=flags)
+    dx, dR, dL = B.monarch_bwd_c64(cdev(dy), cdev(x), cdev(R), cdev(L), flags=flags)
+    torch.cuda.synchronize()
+    want = [complex_ref.fwd(x, R, L, reading)] + list(complex_ref.bwd(dy, x, R, L, reading))
+    errs = {}
+    for nm, got, w in zip(("y", "dx", "dR", "dL"), (y, dx, dR, dL), want):
+        g = got.cpu().numpy().astype(np.complex128)
+        errs[nm] = float(np.linalg.norm((g - w).ravel()) / np.linalg.norm(w.ravel()))
+    print("\n  %s %s" % (name, " ".join("%s=%.2e" % kv for kv in errs.items())), flush=True)
+    assert max(errs.values()) <= TOL["f32"], errs
+    # empty batch: no-op forward, zero gradients
+    e = B.monarch_bwd_c64(cdev(dy[:0]), cdev(x[:0]), cdev(R), cdev(L), flags=flags)
+    assert e[0].shape == (0, k * p) and not bool(e[1].any()) and not bool(e[2].any())
+
+
+@pytest.mark.parametrize("m", [2, 3, 8, 16, 64])
+def test_dft_factors_make_the_monarch_matrix_a_fourier_transform(B, m):
+    """monarch_dft_factors + monarch_fwd_c64 against the library FFT of the grid-transposed input (the
+    4-step splitting), forward and inverse; the inverse factors undo the forward ones."""
+    from oracle import complex_ref
+    n = m * m
+    x = cnormal(8100 + m, (11, n))
+    xt = x.astype(np.complex128).reshape(11, m, m).transpose(0, 2, 1).reshape(11, n)
+    for inverse in (False, True):
+        R, L = B.monarch_dft_factors(m, inverse)
+        Ro, Lo = complex_ref.dft_factors(m, inverse)
+        assert np.abs(R.cpu().numpy() - Ro).max() <= 2e-7 and np.abs(L.cpu().numpy() - Lo).max() <= 2e-7 / (n if inverse else 1) + 1e-12
+        y = B.monarch_fwd_c64(cdev(x), R, L).cpu().numpy().astype(np.complex128)
+        want = np.fft.ifft(xt, axis=1) if inverse else np.fft.fft(xt, axis=1)
+        err = float(np.linalg.norm(y - want) / np.linalg.norm(want))
+        print("\n  m=%d inverse=%s: %.2e" % (m, inverse, err), flush=True)
+        assert err <= TOL["f32"]
+    # F^-1 P applied to (F P x) un-transposed: P (F P)^-1 ... simply: ifft-Monarch of the transposed fft-Monarch output returns x
+    R, L = B.monarch_dft_factors(m, False)
+    Ri, Li = B.monarch_dft_factors(m, True)
+    y = B.monarch_fwd_c64(cdev(x), R, L)                                   # F P x
+    yt = y.reshape(11, m, m).transpose(1, 2).contiguous().reshape(11, n)   # P (F P x)
+    back = B.monarch_fwd_c64(yt, Ri, Li).cpu().numpy()                     # F^-1 P P F P x = P x
+    assert np.linalg.norm(back - xt) / np.linalg.norm(xt) <= TOL["f32"]
+
+
 # ------------------------------------------------------ projection (Algorithm 1) ----
 # Only the products L[j][l][k] * R[k][j][i] are determined (sign and scaling of a singular pair are
 # free), so the Monarch matrix is compared, not the factors.  fp32 Jacobi against the fp64 SVD: the

@@ -22,7 +22,7 @@ def binding():
 def test_library_exports_every_declared_symbol(binding):
     header = open(os.path.join(ROOT, "include", "monarch.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(monarch_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(monarch_[a-z_0-9]+)\s*\(", header))
     assert declared == set(binding.EXPORTS)
     lib = ctypes.CDLL(binding.LIB_PATH)
     for name in declared:
@@ -256,6 +256,37 @@ def test_saved_intermediate_calls_reject_bad_arguments_without_a_gpu(binding):
     assert bwd(sv=p + 8) == binding.MONARCH_ERR_WORKSPACE
     assert bwd(ws=None) == binding.MONARCH_ERR_WORKSPACE
     assert bwd(flags=binding.MONARCH_FLAG_WS_PACKED) == binding.MONARCH_ERR_INVALID
+
+
+def test_complex_calls_reject_bad_arguments_without_a_gpu(binding):
+    L = binding.lib()
+    p = 4096  # never dereferenced
+
+    def fwd(x=p, R=p, Lp=p, y=p, batch=0, n_in=16, k=4, q=4, s=4, flags=0):
+        return L.monarch_fwd_c64(x, R, Lp, y, batch, n_in, k, q, s, None, flags)
+
+    assert fwd() == binding.MONARCH_OK
+    assert fwd(R=None) == binding.MONARCH_ERR_INVALID
+    assert fwd(y=None, batch=1) == binding.MONARCH_ERR_INVALID
+    assert fwd(x=p + 8) == binding.MONARCH_ERR_INVALID
+    assert fwd(n_in=18) == binding.MONARCH_ERR_INVALID
+    assert fwd(flags=binding.MONARCH_FLAG_GENERIC) == binding.MONARCH_ERR_INVALID
+    assert fwd(n_in=4 * 40000, q=40000) == binding.MONARCH_ERR_UNSUPPORTED     # one row does not fit the LDS
+
+    def bwd(ptrs=(p,) * 7, batch=1, n_in=16, flags=0):
+        return L.monarch_bwd_c64(*ptrs, batch, n_in, 4, 4, 4, None, flags)
+
+    for bad in range(7):
+        ptrs = [p] * 7
+        ptrs[bad] = None
+        assert bwd(tuple(ptrs)) == binding.MONARCH_ERR_INVALID
+    assert bwd(n_in=18) == binding.MONARCH_ERR_INVALID
+    assert bwd(flags=binding.MONARCH_FLAG_WGRAD_F32) == binding.MONARCH_ERR_INVALID
+
+    assert L.monarch_dft_factors(None, p, 4, 0, None) == binding.MONARCH_ERR_INVALID
+    assert L.monarch_dft_factors(p, p, 0, 0, None) == binding.MONARCH_ERR_INVALID
+    assert L.monarch_dft_factors(p, p + 8, 4, 0, None) == binding.MONARCH_ERR_INVALID
+    assert L.monarch_dft_factors(p, p, 2000, 0, None) == binding.MONARCH_ERR_UNSUPPORTED
 
 
 def test_stream_copy_rejects_bad_arguments_without_a_gpu(binding):
