@@ -778,6 +778,39 @@ def test_calls_can_be_captured_in_a_graph(B, case):
     compare(sh, [host(outs[0]), host(outs[4])], [oracle.fwd_bias(x, R, L, host(bd)), oracle.bwd_bias(dy, x, R, L)[3]], ["y", "dbias"])
 
 
+@pytest.mark.parametrize("bias", [False, True], ids=["no_bias", "bias"])
+@pytest.mark.parametrize("case", [("k4_192", "bf16", 3 * 50, 4, 192, 192, 192), ("sq_m16", "f32", 3 * 7, 16, 16, 16, 16),
+                                  ("rect", "f32", 3 * 5, 3, 4, 5, 2)], ids=lambda c: c[0])
+def test_autograd_glue_matches_the_oracle(B, case, bias):
+    """torch.autograd through the library (no arithmetic in Python): a 3-D input, loss = <dy, y>, the
+    gradients torch hands back against the oracle's."""
+    from paper_2204_00595_amd import autograd as mag
+    sh = small_shape(case)
+    x, R, L, dy = synth.make_inputs(sh)
+    b = make_bias(sh) if bias else None
+    xd = dev(x, sh.dtype).reshape(3, sh.B // 3, sh.n_in).requires_grad_(True)
+    Rd, Ld = dev(R, sh.dtype).requires_grad_(True), dev(L, sh.dtype).requires_grad_(True)
+    bd = dev(b, sh.dtype).requires_grad_(True) if bias else None
+    y = mag.monarch_linear(xd, Rd, Ld, bd)
+    assert y.shape == (3, sh.B // 3, sh.n_out)
+    y.backward(dev(dy, sh.dtype).reshape(3, sh.B // 3, sh.n_out))
+    torch.cuda.synchronize()
+    want_y = oracle.fwd_bias(x, R, L, b) if bias else oracle.fwd(x, R, L)
+    want = oracle.bwd_bias(dy, x, R, L)
+    got = [host(y.detach().reshape(sh.B, -1)), host(xd.grad.reshape(sh.B, -1)), host(Rd.grad), host(Ld.grad)]
+    names = ["y", "dx", "dR", "dL"]
+    if bias:
+        got.append(host(bd.grad))
+        names.append("dbias")
+    compare(sh, got, [want_y] + list(want[:len(got) - 1]), names)
+    layer = mag.MonarchLinear(sh.n_in, sh.n_out, nblocks=sh.k, bias=bias, q=sh.q, device="cuda", dtype=tdtype(sh.dtype))
+    with torch.no_grad():
+        out = layer(xd.detach())
+        M = layer.to_dense()
+        ref = xd.detach().reshape(sh.B, -1).double() @ M.double().T + (layer.bias.double() if bias else 0.0)
+        assert float((out.reshape(sh.B, -1).double() - ref).norm() / ref.norm()) <= TOL[sh.dtype]
+
+
 def test_stream_copy_is_bit_exact(B):
     n = (1 << 20) + 48  # bytes: several grid strides plus a ragged tail of three 16-byte pieces
     src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
