@@ -391,6 +391,9 @@ const Entry kTable[] = {
     {256, 256, 256, 4, 4, launch_data<BwdWide<256, 256, 256, 4, 128, 4>>},
     {192, 192, 576, 6, 4, launch_data<BwdWide<192, 192, 576, 6, 192, 4>>},
     {256, 256, 768, 4, 4, launch_data<BwdWide<256, 256, 768, 4, 128, 4>>},
+    {128, 128, 128, 4, 4, launch_data<BwdWide<128, 128, 128, 4, 128, 4>>},
+    {128, 128, 512, 4, 4, launch_data<BwdWide<128, 128, 512, 4, 128, 4>>},
+    {512, 128, 128, 4, 4, launch_data<BwdWide<512, 128, 128, 4, 128, 4>>},
     {64, 64, 64, 2, 4, launch_data<BwdWide<64, 64, 64, 2, 64, 4>>},
     {64, 64, 128, 2, 4, launch_data<BwdWide<64, 64, 128, 2, 64, 4>>},
     {128, 64, 64, 2, 4, launch_data<BwdWide<128, 64, 64, 2, 64, 4>>},

@@ -294,6 +294,9 @@ const Entry kTable[] = {
     {256, 256, 256, launch<FwdFrag<256, 256, 256, 4, 8>>},    // GPT-2 medium projection 1024 -> 1024
     {192, 192, 576, launch<FwdFrag<192, 192, 576, 3, 6>>},    // ViT-B / GPT-2 small fused q,k,v 768 -> 2304
     {256, 256, 768, launch<FwdFrag<256, 256, 768, 4, 8>>},    // GPT-2 medium fused q,k,v 1024 -> 3072
+    {128, 128, 128, launch<FwdFrag<128, 128, 128, 2, 4>>},    // width 512 (MLP-Mixer-S): 512 -> 512
+    {128, 128, 512, launch<FwdFrag<128, 128, 512, 4, 4>>},    // 512 -> 2048
+    {512, 128, 128, launch<FwdFrag<512, 128, 128, 2, 4>>},    // 2048 -> 512
     {64, 64, 64, launch<FwdFrag<64, 64, 64, 1, 4>>},          // small shapes (tests)
     {64, 64, 128, launch<FwdFrag<64, 64, 128, 2, 4>>},
     {128, 64, 64, launch<FwdFrag<128, 64, 64, 1, 4>>},

@@ -532,6 +532,9 @@ const Entry kTable[] = {
     {256, 256, 256, launch<FwdWide<256, 256, 256, 2>>},    // GPT-2 medium projection 1024 -> 1024
     {192, 192, 576, launch<FwdWide<192, 192, 576, 3>>},    // ViT-B / GPT-2 small fused q,k,v 768 -> 2304
     {256, 256, 768, launch<FwdWide<256, 256, 768, 2>>},    // GPT-2 medium fused q,k,v 1024 -> 3072
+    {128, 128, 128, launch<FwdWide<128, 128, 128, 2>>},    // width 512 (MLP-Mixer-S): 512 -> 512
+    {128, 128, 512, launch<FwdWide<128, 128, 512, 4>>},    // 512 -> 2048
+    {512, 128, 128, launch<FwdWide<512, 128, 128, 2>>},    // 2048 -> 512
     {64, 64, 64, launch<FwdWide<64, 64, 64, 1>>},          // small shapes (tests)
     {64, 64, 128, launch<FwdWide<64, 64, 128, 2>>},
     {128, 64, 64, launch<FwdWide<128, 64, 64, 1>>},

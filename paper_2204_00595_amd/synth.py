@@ -139,6 +139,9 @@ MODEL_LAYERS = {
     "gpt2s_fc2": Shape("gpt2s_fc2", "bf16", 8 * 1024, 4, 768, 192, 192, config=7),
     "gpt2m_proj": Shape("gpt2m_proj", "bf16", 16384, 4, 256, 256, 256, config=8),
     "gpt2m_qkv": Shape("gpt2m_qkv", "bf16", 16384, 4, 256, 256, 768, config=9),
+    # width 512 (MLP-Mixer-S channel mixing, 64 images x 196 patches)
+    "w512_fc1": Shape("w512_fc1", "bf16", 64 * 196, 4, 128, 128, 512, config=10),
+    "w512_fc2": Shape("w512_fc2", "bf16", 64 * 196, 4, 512, 128, 128, config=11),
 }
 
 

@@ -135,13 +135,16 @@ def test_small_shapes_fwd_bwd(B, case, generic):
 
 
 # The other Monarch layer shapes of the paper's ViT-B / GPT-2 small / GPT-2 medium models (four blocks):
-# attention output projection, fused q,k,v projection and the second MLP layer, at a batch of several
-# 64-row tiles plus a ragged tail.  All of them must be served by the matrix-core kernels.
+# attention output projection, fused q,k,v projection and the second MLP layer, and the layers of a
+# width-512 model (MLP-Mixer-S channel mixing), at a batch of several 64-row tiles plus a ragged tail.  All of them must be served by the matrix-core kernels.
 MODEL_LAYERS = [
     ("gpt2m_proj_1024_1024", "bf16", 1100, 4, 256, 256, 256),
     ("qkv_768_2304", "bf16", 1100, 4, 192, 192, 576),
     ("gpt2m_qkv_1024_3072", "bf16", 1100, 4, 256, 256, 768),
     ("gpt2s_fc2_3072_768", "bf16", 1100, 4, 768, 192, 192),
+    ("w512_proj_512_512", "bf16", 1100, 4, 128, 128, 128),
+    ("w512_fc1_512_2048", "bf16", 1100, 4, 128, 128, 512),
+    ("w512_fc2_2048_512", "bf16", 1100, 4, 512, 128, 128),
 ]
 
 

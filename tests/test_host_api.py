@@ -314,7 +314,8 @@ def test_kernel_name_reports_dispatch(binding):
     assert binding.monarch_kernel_name(0, 4 * 2000000, 4, 2000000, 4, 1) == "unsupported"
     # every four-block layer shape of ViT-B, GPT-2 small and GPT-2 medium has matrix-core kernels
     for n_in, q, s in ((768, 192, 192), (768, 192, 576), (768, 192, 768), (3072, 192, 192),
-                       (1024, 256, 256), (1024, 256, 768), (1024, 256, 1024), (4096, 256, 256)):
+                       (1024, 256, 256), (1024, 256, 768), (1024, 256, 1024), (4096, 256, 256),
+                       (512, 128, 128), (512, 128, 512), (2048, 128, 128)):
         assert [binding.monarch_kernel_name(ps, n_in, 4, q, s, 1) for ps in (0, 1, 2)] == \
             ["mfma_fwd_wide_bf16", "mfma_bwd_wide_bf16", "mfma_fwd_frag_bf16"], (n_in, q, s)
 
