@@ -814,6 +814,39 @@ def test_autograd_glue_matches_the_oracle(B, case, bias):
         assert float((out.reshape(sh.B, -1).double() - ref).norm() / ref.norm()) <= TOL[sh.dtype]
 
 
+def test_calls_run_on_the_stream_they_are_given(B):
+    """Everything is enqueued on the caller's stream: on a side stream, behind a long-running copy on that
+    same stream, the results are those of the default stream; operands at 16-byte (not 256-byte) offsets."""
+    sh = small_shape(("k4_192", "bf16", 200, 4, 192, 192, 192))
+    x, R, L, dy = synth.make_inputs(sh)
+
+    def offset(a):  # a tensor that starts 16 bytes into its allocation
+        t = dev(a, sh.dtype)
+        buf = torch.empty(t.numel() + 8, dtype=t.dtype, device="cuda")
+        v = buf[8:8 + t.numel()].view(t.shape)
+        v.copy_(t)
+        assert v.data_ptr() % 256 == 16
+        return v
+
+    xd, Rd, Ld, dyd = offset(x), offset(R), offset(L), offset(dy)
+    y0 = B.monarch_fwd(xd, Rd, Ld)
+    g0 = B.monarch_bwd_bias(dyd, xd, Rd, Ld)
+    t0 = B.monarch_fwd_t(dyd, Rd, Ld)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    big = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    with torch.cuda.stream(side):
+        big2 = big.clone()  # keeps the side stream busy while the calls are enqueued behind it
+        y1 = B.monarch_fwd(xd, Rd, Ld, stream=side)
+        g1 = B.monarch_bwd_bias(dyd, xd, Rd, Ld, stream=side)
+        t1 = B.monarch_fwd_t(dyd, Rd, Ld, stream=side)
+    side.synchronize()
+    assert torch.equal(y0, y1) and torch.equal(t0, t1) and all(torch.equal(a, b) for a, b in zip(g0, g1))
+    compare(sh, [host(y1), host(t1)] + [host(t) for t in g1], [oracle.fwd(x, R, L), oracle.fwd_t(dy, R, L)] + list(oracle.bwd_bias(dy, x, R, L)),
+            ["y", "xM", "dx", "dR", "dL", "dbias"])
+    del big2
+
+
 def test_stream_copy_is_bit_exact(B):
     n = (1 << 20) + 48  # bytes: several grid strides plus a ragged tail of three 16-byte pieces
     src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
