@@ -273,17 +273,7 @@ bwd_sq16_kernel(const float* __restrict__ dy, const float* __restrict__ x, const
 #pragma unroll
         for (int v = 0; v < 16; ++v) dya[v] = *reinterpret_cast<const f32x4*>(p + 4 * v) * m;
     };
-    // daq[cq][u] = dy[b0 + 4h + u][16*bl + 4cq .. +3]: the same rows "down the batch" for the dL product
-    auto load_da = [&](int64_t tl, f32x4 (&daq)[4][4]) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int64_t row = tl * 16 + 4 * h + u;
-            const float m = row < B ? 1.f : 0.f;
-            row = row < B ? row : B - 1;
-#pragma unroll
-            for (int cq = 0; cq < 4; ++cq) daq[cq][u] = *reinterpret_cast<const f32x4*>(dy + row * N16 + 16 * bl + 4 * cq) * m;
-        }
-    };
+    // daq[cq][u] = dy[b0 + 4h + u][16*bl + 4cq .. +3]: the same rows "down the batch" for the dL product (read back from the tile)
     f32x4 xa[16], dya[16], daq[4][4];
     if (tile < ntiles) {  // in flight while the weights are staged
         load_x(tile, xa);
@@ -296,7 +286,16 @@ bwd_sq16_kernel(const float* __restrict__ dy, const float* __restrict__ x, const
     for (; tile < ntiles; tile += stride) {
         const int64_t b0 = tile * 16;
         const int64_t next = tile + stride;
-        load_da(tile, daq);  // second look at this tile's dy rows (cache hits), in flight during step 1
+        // the dL product wants the same dy rows "down the batch": turned through the wave's tile (free at
+        // this point) instead of a second look at global memory
+#pragma unroll
+        for (int v = 0; v < 16; ++v) *reinterpret_cast<f32x4*>(T + t_off(bl, 16 * h + v)) = dya[v];
+        wave_lds_fence();
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int cq = 0; cq < 4; ++cq) daq[cq][u] = *reinterpret_cast<const f32x4*>(T + t_off(4 * h + u, 4 * bl + cq));
+        wave_lds_fence();
         // ---- 1. Y1[b][kk][j = 4h + i] -> tile [b][kk][j]
 #pragma unroll
         for (int kk = 0; kk < 16; ++kk) {
