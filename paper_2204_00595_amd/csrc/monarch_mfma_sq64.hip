@@ -52,12 +52,12 @@ struct Lane {
 // Block stage.  act: the lane's row, at column 32*g; W[block][out][in] (64 x 64 each).
 // Results: bf16 pairs (block even, block odd) of T[b = ln][block][col], col = 32*jt + 8*(i/4) + 4*g + i%4.
 // The half col < 32 goes to the exchange buffer as it is produced (LDS must be idle), the half
-// col >= 32 is returned in pk1[t2][i].
+// col >= 32 is returned in pk1[i][t2].
 // PACKED: W is the factor in fragment order (pack64_kernel): a weight operand is then one contiguous
 // 1 KiB read per wave instruction instead of 32 lines touched twice.
 template <bool PACKED>
 __device__ __forceinline__ void block_stage(const Lane& t_, const uint16_t* __restrict__ act_row,
-                                            const uint16_t* __restrict__ W, unsigned char* ldsb, uint32_t (&pk1)[4][16])
+                                            const uint16_t* __restrict__ W, unsigned char* ldsb, u32x4 (&pk1)[16])
 {
     const int wave = t_.wave, ln = t_.ln, g = t_.g;
     const uint16_t* arow = act_row + (size_t)wave * 8 * M64;
@@ -78,7 +78,7 @@ __device__ __forceinline__ void block_stage(const Lane& t_, const uint16_t* __re
     load_r(0, 0);
     load_r(0, 1);
     f32x16 ev[2];
-    uint32_t q0[2][16];
+    u32x2 q0[16];
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         const int s = t & 1;
@@ -98,16 +98,16 @@ __device__ __forceinline__ void block_stage(const Lane& t_, const uint16_t* __re
                 ev[jt] = acc;
             } else if (jt == 1) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) pk1[t >> 1][i] = pack_bf16x2(ev[1][i], acc[i]);
+                for (int i = 0; i < 16; ++i) pk1[i][t >> 1] = pack_bf16x2(ev[1][i], acc[i]);
             } else {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) q0[(t >> 1) & 1][i] = pack_bf16x2(ev[0][i], acc[i]);
+                for (int i = 0; i < 16; ++i) q0[i][(t >> 1) & 1] = pack_bf16x2(ev[0][i], acc[i]);
                 if ((t & 3) == 3) {
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int jl = 8 * (i >> 2) + 4 * g + (i & 3);
                         *reinterpret_cast<u32x2*>(ldsb + (size_t)ln * SQ_ROWB + jl * 128 + 16 * wave + 8 * (t >> 2)) =
-                            u32x2{q0[0][i], q0[1][i]};
+                            q0[i];
                     }
                 }
             }
@@ -116,13 +116,13 @@ __device__ __forceinline__ void block_stage(const Lane& t_, const uint16_t* __re
 }
 
 // second half of the block-stage results -> exchange buffer
-__device__ __forceinline__ void exchange_write(const Lane& t_, unsigned char* ldsb, const uint32_t (&pk1)[4][16])
+__device__ __forceinline__ void exchange_write(const Lane& t_, unsigned char* ldsb, const u32x4 (&pk1)[16])
 {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int jl = 8 * (i >> 2) + 4 * t_.g + (i & 3);
         *reinterpret_cast<u32x4*>(ldsb + (size_t)t_.ln * SQ_ROWB + jl * 128 + 16 * t_.wave) =
-            u32x4{pk1[0][i], pk1[1][i], pk1[2][i], pk1[3][i]};
+            pk1[i];
     }
 }
 
@@ -212,7 +212,7 @@ fwd_sq64_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
     row = row < B ? row : B - 1;  // rows past the end are computed from a valid row and dropped
 
     // step 1: Y1[b][kk][j] -> exchange layout T[b][j][kk]
-    uint32_t pk1[4][16];
+    u32x4 pk1[16];  // pk1[i][t]: one 16-byte exchange piece per i, filled component by component
     block_stage<PACKED>(t, x + row * N64 + 32 * g, R, ldsb, pk1);
 
     // step 2 for the 32 blocks c = j of each half.
@@ -333,7 +333,7 @@ bwd_sq64_data_kernel(const uint16_t* __restrict__ dW, const uint16_t* __restrict
     int64_t row = b0 + ln;
     row = row < B ? row : B - 1;
 
-    uint32_t pk1[4][16];
+    u32x4 pk1[16];  // pk1[i][t]: one 16-byte exchange piece per i, filled component by component
     // ---- recompute step 1; the exchange layout T[b][j][kk] is U[b][c = j][r = kk]: to the workspace
     if constexpr (!DX_ONLY) {
         block_stage<true>(t, x + row * N64 + 32 * g, R, ldsb, pk1);
