@@ -129,7 +129,9 @@ __device__ __forceinline__ void copy_out_tile(const uint16_t* src, int stride, u
                                               int64_t b0, int64_t B, int tid)
 {
     constexpr int PER_ROW = COLS / 8, TASKS = 64 * PER_ROW, PER = (TASKS + NTHREADS - 1) / NTHREADS;
-#pragma unroll
+    // the rounds are not unrolled: unrolled, the compiler precomputes every round's addresses and, next
+    // to the accumulators that are live around the copies, spills them
+#pragma unroll 1
     for (int i0 = 0; i0 < PER; i0 += 8) {
         u32x4 v[8];
 #pragma unroll
