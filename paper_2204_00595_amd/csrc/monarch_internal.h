@@ -130,6 +130,15 @@ size_t bwd_sq16_workspace(const Problem& pb);
 int bwd_sq16(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx,
              void* dR, void* dL, void* ws, hipStream_t st);
 
+// shape-generic bf16 matrix-core kernels (any k; block sizes multiples of 16, the backward 32 and k % 4 == 0;
+// both permutation readings; the forward adds pb.bias)
+bool tiled_fwd_supported(const Problem& pb);
+int tiled_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
+bool tiled_bwd_supported(const Problem& pb);
+size_t tiled_bwd_workspace(const Problem& pb);
+int tiled_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
+              void* dL, void* ws, hipStream_t st);
+
 // Batch-contracted GEMM for the weight gradients (monarch_mfma_wgrad.hip):
 //   P[z][g][m][n] = sum over the rows of batch chunk z of  A[row][g, m] * Bm[row][g, n]
 // A column (g, m):  a_g * g + m            (or 4*m + g when the four groups are interleaved)

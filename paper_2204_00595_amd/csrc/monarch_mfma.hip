@@ -3,12 +3,16 @@
 
 namespace monarch {
 
-bool mfma_fwd_supported(const Problem& pb) { return fwd_wide_supported(pb) || sq64_supported(pb) || sq16_supported(pb); }
+bool mfma_fwd_supported(const Problem& pb)
+{
+    return fwd_wide_supported(pb) || sq64_supported(pb) || sq16_supported(pb) || tiled_fwd_supported(pb);
+}
 const char* mfma_fwd_name(const Problem& pb)
 {
     if (fwd_wide_supported(pb)) return "mfma_fwd_wide_bf16";
     if (sq64_supported(pb)) return "mfma_fwd_sq64_bf16";
     if (sq16_supported(pb)) return "mfma_fwd_sq16_f32";
+    if (tiled_fwd_supported(pb)) return "mfma_fwd_tiled_bf16";
     return "unsupported";
 }
 int mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
@@ -16,6 +20,7 @@ int mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, voi
     if (fwd_wide_supported(pb)) return fwd_wide(pb, x, R, L, y, st);
     if (sq64_supported(pb)) return fwd_sq64(pb, x, R, L, y, st);
     if (sq16_supported(pb)) return fwd_sq16(pb, x, R, L, y, st);
+    if (tiled_fwd_supported(pb)) return tiled_fwd(pb, x, R, L, y, st);
     return -2;
 }
 
@@ -67,17 +72,22 @@ bool mfma_fwd_fuses_bias(const Problem& pb, bool with_ws)
 {
     if (with_ws && fwd_frag_supported(pb)) return true;
     if (with_ws && sq64_supported(pb)) return false;
-    return !fwd_wide_supported(pb) && !sq64_supported(pb) && sq16_supported(pb);
+    // mfma_fwd's order of preference: wide, sq64 (no bias epilogue), then sq16 and the shape-generic kernel (both have one)
+    return !fwd_wide_supported(pb) && !sq64_supported(pb) && (sq16_supported(pb) || tiled_fwd_supported(pb));
 }
 
 bool mfma_bwd_fuses_dbias(const Problem& pb) { return bwd_wide_supported(pb); }
 
-bool mfma_bwd_supported(const Problem& pb) { return bwd_wide_supported(pb) || bwd_sq64_supported(pb) || sq16_supported(pb); }
+bool mfma_bwd_supported(const Problem& pb)
+{
+    return bwd_wide_supported(pb) || bwd_sq64_supported(pb) || sq16_supported(pb) || tiled_bwd_supported(pb);
+}
 size_t mfma_bwd_workspace(const Problem& pb)
 {
     if (bwd_wide_supported(pb)) return bwd_wide_workspace(pb);
     if (bwd_sq64_supported(pb)) return bwd_sq64_workspace(pb);
     if (sq16_supported(pb)) return bwd_sq16_workspace(pb);
+    if (tiled_bwd_supported(pb)) return tiled_bwd_workspace(pb);
     return 0;
 }
 const char* mfma_bwd_name(const Problem& pb)
@@ -85,6 +95,7 @@ const char* mfma_bwd_name(const Problem& pb)
     if (bwd_wide_supported(pb)) return "mfma_bwd_wide_bf16";
     if (bwd_sq64_supported(pb)) return "mfma_bwd_sq64_bf16";
     if (sq16_supported(pb)) return "mfma_bwd_sq16_f32";
+    if (tiled_bwd_supported(pb)) return "mfma_bwd_tiled_bf16";
     return "unsupported";
 }
 int mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
@@ -93,6 +104,7 @@ int mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, co
     if (bwd_wide_supported(pb)) return bwd_wide(pb, dy, x, R, L, dx, dR, dL, ws, st);
     if (bwd_sq64_supported(pb)) return bwd_sq64(pb, dy, x, R, L, dx, dR, dL, ws, st);
     if (sq16_supported(pb)) return bwd_sq16(pb, dy, x, R, L, dx, dR, dL, ws, st);
+    if (tiled_bwd_supported(pb)) return tiled_bwd(pb, dy, x, R, L, dx, dR, dL, ws, st);
     return -2;
 }
 

@@ -162,6 +162,40 @@ def test_model_layer_shapes_on_matrix_cores(B, case):
     compare(sh, run_bwd(B, sh, dy, x, R, L, B.MONARCH_FLAG_WGRAD_F32), oracle.bwd(dy, x, R, L), ["dx", "dR32", "dL32"])
 
 
+# Shapes without a tuned kernel that the shape-generic matrix-core kernels must serve: block sizes that are
+# multiples of 16 (forward; a size that is 16 mod 32 ends on a half-empty K-step) or of 32 with k % 4 == 0
+# (backward).  name, dtype, B, k, p, q, s, backward on matrix cores too
+TILED = [
+    ("vits_proj_384_384", "bf16", 300, 4, 96, 96, 96, True),
+    ("vits_fc1_384_1536", "bf16", 203, 4, 96, 96, 384, True),
+    ("vits_fc2_1536_384", "bf16", 140, 4, 384, 96, 96, True),
+    ("vits_few_rows", "bf16", 5, 4, 96, 96, 96, True),
+    ("k8_64_32_96", "bf16", 131, 8, 64, 32, 96, True),
+    ("k12_32_64_32", "bf16", 77, 12, 32, 64, 32, True),
+    ("k16_wide_mid", "bf16", 50, 16, 32, 256, 32, True),
+    ("k2_tail_48_80_48", "bf16", 90, 2, 48, 80, 48, False),
+    ("k3_32_48_16", "bf16", 67, 3, 32, 48, 16, False),
+    ("k1_dense_pair", "bf16", 33, 1, 64, 48, 80, False),
+]
+
+
+@pytest.mark.parametrize("reading", ["A", "B"])
+@pytest.mark.parametrize("case", TILED, ids=lambda c: c[0])
+def test_shape_generic_matrix_core_kernels(B, case, reading):
+    sh = small_shape(case[:7])
+    flags = B.MONARCH_FLAG_PERM_B if reading == "B" else 0
+    rd = oracle.READING_B if reading == "B" else oracle.READING_A
+    names = [B.monarch_kernel_name(ps, sh.n_in, sh.k, sh.q, sh.s, 1, flags) for ps in (0, 1)]
+    assert names == ["mfma_fwd_tiled_bf16", "mfma_bwd_tiled_bf16" if case[7] else "generic_bwd"], names
+    x, R, L, dy = synth.make_inputs(sh)
+    compare(sh, [run_fwd(B, sh, x, R, L, flags)], [oracle.fwd(x, R, L, rd)], ["y"])
+    bias = make_bias(sh)
+    compare(sh, [run_fwd_bias(B, sh, x, R, L, bias, flags)], [oracle.fwd_bias(x, R, L, bias, rd)], ["y_bias"])
+    compare(sh, run_bwd(B, sh, dy, x, R, L, flags), oracle.bwd(dy, x, R, L, rd), ["dx", "dR", "dL"])
+    compare(sh, run_bwd_bias(B, sh, dy, x, R, L, flags | B.MONARCH_FLAG_WGRAD_F32), oracle.bwd_bias(dy, x, R, L, rd),
+            ["dx", "dR32", "dL32", "dbias32"])
+
+
 @pytest.mark.parametrize("case", [c for c in SMALL if c[3] != c[5]][:5], ids=lambda c: c[0])
 def test_alternative_mid_permutation(B, case):
     sh = small_shape(case)
