@@ -3,7 +3,7 @@
 // also needs k % 4 == 0 for the weight-gradient GEMMs).  They serve the shapes that have no tuned
 // kernel; both readings of the permutation between the factors are handled.
 //
-// A workgroup (four waves) owns TB = 16 * RT rows.  A block-diagonal stage is a list of work items
+// A workgroup (eight waves) owns TB = 16 * RT rows.  A block-diagonal stage is a list of work items
 // (block, 16-column output tile) dealt round-robin to the waves; an item keeps RT accumulator tiles
 // (one per 16 rows) on v_mfma_f32_16x16x32_bf16, so a weight fragment is loaded once per K-step and
 // used RT times.  The vector between the factors lives in LDS only, stored in the order the next
@@ -25,7 +25,8 @@ namespace monarch {
 
 namespace {
 
-constexpr int TL_WAVES = 4, TL_THREADS = 64 * TL_WAVES;
+constexpr int TL_WAVES = 8, TL_THREADS = 64 * TL_WAVES;
+constexpr int KU = 4;  // K-steps (of 32) whose operand loads are in flight together
 
 struct TiledShape {
     int k, p, q, s, perm_b;
@@ -67,14 +68,22 @@ __device__ __forceinline__ void tiled_stage(int wave, int lane, int nblk, int no
         f32x4 acc[RT];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        for (int k0 = 0; k0 < nin; k0 += 32) {
-            const bool ok = k0 + 8 * kg < nin;
-            const u32x4 wf = ok ? ldg128(wrow + k0) : zero;
-            u32x4 af[RT];
+        // KU K-steps per round, all of their loads issued before the first MFMA: the waves have nothing else
+        // to hide the load latency behind
+        for (int k0 = 0; k0 < nin; k0 += 32 * KU) {
+            u32x4 wf[KU], af[KU][RT];
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt) af[rt] = ok ? load_a(rt, blk, k0 + 8 * kg) : zero;
+            for (int u = 0; u < KU; ++u) {
+                const int i0 = k0 + 32 * u + 8 * kg;
+                const bool ok = i0 < nin;
+                wf[u] = ok ? ldg128(wrow + k0 + 32 * u) : zero;
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt) acc[rt] = mfma16(as_bf16x8(af[rt]), as_bf16x8(wf), acc[rt]);
+                for (int rt = 0; rt < RT; ++rt) af[u][rt] = ok ? load_a(rt, blk, i0) : zero;
+            }
+#pragma unroll
+            for (int u = 0; u < KU; ++u)
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) acc[rt] = mfma16(as_bf16x8(af[u][rt]), as_bf16x8(wf[u]), acc[rt]);
         }
         emit(blk, t, acc);
     }
@@ -155,14 +164,19 @@ tiled_fwd_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
             const int c = cgi * CG + cc;
             const uint16_t* wrow = L + ((size_t)c * sh.s + 16 * lt + m) * sh.q + 8 * kg;
             const uint16_t* urow = lds + (size_t)m * ldu + c * sh.q + 8 * kg;
-            for (int k0 = 0; k0 < sh.q; k0 += 32) {
-                const bool ok = k0 + 8 * kg < sh.q;
-                const u32x4 wf = ok ? ldg128(wrow + k0) : zero;
+            for (int k0 = 0; k0 < sh.q; k0 += 32 * KU) {
+                u32x4 wf[KU], af[KU][RT];
 #pragma unroll
-                for (int rt = 0; rt < RT; ++rt) {
-                    const u32x4 af = ok ? lds128(urow + (size_t)16 * rt * ldu + k0) : zero;
-                    acc[cc][rt] = mfma16(as_bf16x8(af), as_bf16x8(wf), acc[cc][rt]);
+                for (int u = 0; u < KU; ++u) {
+                    const bool ok = k0 + 32 * u + 8 * kg < sh.q;
+                    wf[u] = ok ? ldg128(wrow + k0 + 32 * u) : zero;
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt) af[u][rt] = ok ? lds128(urow + (size_t)16 * rt * ldu + k0 + 32 * u) : zero;
                 }
+#pragma unroll
+                for (int u = 0; u < KU; ++u)
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt) acc[cc][rt] = mfma16(as_bf16x8(af[u][rt]), as_bf16x8(wf[u]), acc[cc][rt]);
             }
         }
         // the lane holds output index l = 16*lt + m of blocks c0 .. c0+CG-1: columns l*k + c0 .. are contiguous
@@ -341,12 +355,23 @@ int launch_fwd(const Problem& pb, const void* x, const void* R, const void* L, v
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
+// Blocks per stage-2 item: the most that divide k.  (Fewer blocks per item would deal the items more
+// evenly to the waves, e.g. 24 instead of 6 for s = 96, k = 4, but the narrower stores cost more: 18.7 vs 17.3 us.)
+int pick_cg(const Problem& pb)
+{
+    for (int c : {8, 4, 2})
+        if (pb.k % c == 0) return c;
+    return 1;
+}
+
 template <int RT>
 int launch_fwd_cg(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
 {
-    if (pb.k % 8 == 0) return launch_fwd<RT, 8>(pb, x, R, L, y, st);
-    if (pb.k % 4 == 0) return launch_fwd<RT, 4>(pb, x, R, L, y, st);
-    if (pb.k % 2 == 0) return launch_fwd<RT, 2>(pb, x, R, L, y, st);
+    switch (pick_cg(pb)) {
+        case 8: return launch_fwd<RT, 8>(pb, x, R, L, y, st);
+        case 4: return launch_fwd<RT, 4>(pb, x, R, L, y, st);
+        case 2: return launch_fwd<RT, 2>(pb, x, R, L, y, st);
+    }
     return launch_fwd<RT, 1>(pb, x, R, L, y, st);
 }
 

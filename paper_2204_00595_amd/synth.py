@@ -142,6 +142,11 @@ MODEL_LAYERS = {
     # width 512 (MLP-Mixer-S channel mixing, 64 images x 196 patches)
     "w512_fc1": Shape("w512_fc1", "bf16", 64 * 196, 4, 128, 128, 512, config=10),
     "w512_fc2": Shape("w512_fc2", "bf16", 64 * 196, 4, 512, 128, 128, config=11),
+    # ViT-S (width 384 = 4 x 96: no tuned kernel, served by the shape-generic matrix-core kernels)
+    "vits_proj": Shape("vits_proj", "bf16", 64 * 197, 4, 96, 96, 96, config=12),
+    "vits_qkv": Shape("vits_qkv", "bf16", 64 * 197, 4, 96, 96, 288, config=13),
+    "vits_fc1": Shape("vits_fc1", "bf16", 64 * 197, 4, 96, 96, 384, config=14),
+    "vits_fc2": Shape("vits_fc2", "bf16", 64 * 197, 4, 384, 96, 96, config=15),
 }
 
 
