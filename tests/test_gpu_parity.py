@@ -172,7 +172,7 @@ TILED = [
     ("vits_few_rows", "bf16", 5, 4, 96, 96, 96, True),
     ("k8_64_32_96", "bf16", 131, 8, 64, 32, 96, True),
     ("k12_32_64_32", "bf16", 77, 12, 32, 64, 32, True),
-    ("k16_wide_mid", "bf16", 50, 16, 32, 256, 32, True),
+    ("k16_wide_mid", "bf16", 50, 16, 32, 192, 32, True),
     ("k2_tail_48_80_48", "bf16", 90, 2, 48, 80, 48, False),
     ("k3_32_48_16", "bf16", 67, 3, 32, 48, 16, False),
     ("k1_dense_pair", "bf16", 33, 1, 64, 48, 80, False),
