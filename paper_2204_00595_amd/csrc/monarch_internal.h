@@ -138,6 +138,9 @@ bool tiled_bwd_supported(const Problem& pb);
 size_t tiled_bwd_workspace(const Problem& pb);
 int tiled_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
               void* dL, void* ws, hipStream_t st);
+bool tiled_fwd_t_supported(const Problem& pb);
+size_t tiled_fwd_t_workspace(const Problem& pb);
+int tiled_fwd_t(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);
 
 // Batch-contracted GEMM for the weight gradients (monarch_mfma_wgrad.hip):
 //   P[z][g][m][n] = sum over the rows of batch chunk z of  A[row][g, m] * Bm[row][g, n]

@@ -45,11 +45,16 @@ int mfma_fwd_ws(const Problem& pb, const void* x, const void* R, const void* L, 
 }
 
 // Transposed multiply y = x M: the dx stages of the three backward families on their own.
-bool mfma_fwd_t_supported(const Problem& pb) { return bwd_wide_supported(pb) || sq64_supported(pb) || sq16_supported(pb); }
+bool mfma_fwd_t_supported(const Problem& pb)
+{
+    return bwd_wide_supported(pb) || sq64_supported(pb) || sq16_supported(pb) || tiled_fwd_t_supported(pb);
+}
 size_t mfma_fwd_t_workspace(const Problem& pb)
 {
     if (bwd_wide_supported(pb)) return fwd_t_wide_workspace(pb);
     if (sq64_supported(pb)) return fwd_t_sq64_workspace(pb);
+    if (sq16_supported(pb)) return 0;
+    if (tiled_fwd_t_supported(pb)) return tiled_fwd_t_workspace(pb);
     return 0;
 }
 const char* mfma_fwd_t_name(const Problem& pb)
@@ -57,6 +62,7 @@ const char* mfma_fwd_t_name(const Problem& pb)
     if (bwd_wide_supported(pb)) return "mfma_fwd_t_wide_bf16";
     if (sq64_supported(pb)) return "mfma_fwd_t_sq64_bf16";
     if (sq16_supported(pb)) return "mfma_fwd_t_sq16_f32";
+    if (tiled_fwd_t_supported(pb)) return "mfma_fwd_t_tiled_bf16";
     return "unsupported";
 }
 int mfma_fwd_t(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
@@ -64,6 +70,7 @@ int mfma_fwd_t(const Problem& pb, const void* x, const void* R, const void* L, v
     if (bwd_wide_supported(pb)) return fwd_t_wide(pb, x, R, L, y, ws, st);
     if (sq64_supported(pb)) return fwd_t_sq64(pb, x, R, L, y, ws, st);
     if (sq16_supported(pb)) return fwd_t_sq16(pb, x, R, L, y, st);
+    if (tiled_fwd_t_supported(pb)) return tiled_fwd_t(pb, x, R, L, y, ws, st);
     return -2;
 }
 

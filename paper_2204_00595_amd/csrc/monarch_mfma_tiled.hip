@@ -218,7 +218,9 @@ __global__ void __launch_bounds__(256) transpose_blocks_kernel(TransposeJob j0, 
     j.dst[o] = j.src[blk * per + (size_t)r * j.cols + c];
 }
 
-template <int RT>
+// DX_ONLY: the transposed multiply y = x M on its own (dy is then its input, dx its output): no recompute
+// of step 1, no workspace copies.
+template <int RT, bool DX_ONLY>
 __global__ void __launch_bounds__(TL_THREADS)
 tiled_bwd_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
                  const uint16_t* __restrict__ LT /* [c][r][l] */, const uint16_t* __restrict__ RTr /* [kk][i][j] */,
@@ -256,7 +258,7 @@ tiled_bwd_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ x
     }
 
     // ---- step 1 again: U to T2, in stage-2 order
-    {
+    if constexpr (!DX_ONLY) {
         const uint16_t* xrow[RT];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
@@ -275,9 +277,11 @@ tiled_bwd_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ x
             });
     }
     __syncthreads();
-    copy_tile(T2, ldu, kq, TB, Uws, b0, B, tid, false);
-    copy_tile(T1, ld1, n_out, TB, dWws, b0, B, tid, false);
-    __syncthreads();  // U has left T2
+    if constexpr (!DX_ONLY) {
+        copy_tile(T2, ldu, kq, TB, Uws, b0, B, tid, false);
+        copy_tile(T1, ld1, n_out, TB, dWws, b0, B, tid, false);
+        __syncthreads();  // U has left T2
+    }
 
     // ---- adjoint of step 2: dU[b][c][r] = sum_l L[c][l][r] dW[b][c][l], written where dY1 has it
     tiled_stage<RT>(
@@ -291,7 +295,7 @@ tiled_bwd_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ x
                 for (int i = 0; i < 4; ++i) T2[(size_t)(16 * rt + 4 * kg + i) * ldu + g] = bf16_bits(acc[rt][i]);
         });
     __syncthreads();  // dY1 complete; nobody reads dW any more
-    copy_tile(T2, ldu, kq, TB, dY1ws, b0, B, tid, false);
+    if constexpr (!DX_ONLY) copy_tile(T2, ldu, kq, TB, dY1ws, b0, B, tid, false);
 
     // ---- adjoint of step 1: dx[b][kk*p + i] = sum_j R[kk][j][i] dY1[b][kk][j], staged in T1
     tiled_stage<RT>(
@@ -426,20 +430,40 @@ TiledPlan make_plan_tiled(const Problem& pb)
     return pl;
 }
 
-template <int RT>
-int launch_bwd(const Problem& pb, const TiledPlan& pl, const void* dy, const void* x, const void* R, char* w, void* dx,
-               hipStream_t st)
+template <int RT, bool DX_ONLY>
+int launch_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const uint16_t* LT, const uint16_t* RTr,
+               void* dx, uint16_t* Uws, uint16_t* dWws, uint16_t* dY1ws, hipStream_t st)
 {
     const int ld1 = bwd_ld1(pb), ldu = pb.kq() + 8;
     const size_t lds = (size_t)16 * RT * (ld1 + ldu) * 2;
-    auto kern = tiled_bwd_kernel<RT>;
+    auto kern = tiled_bwd_kernel<RT, DX_ONLY>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return -4;
     const int64_t grid = (pb.B + 16 * RT - 1) / (16 * RT);
     if (grid > 0x7fffffffLL) return -2;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(TL_THREADS), lds, st, (const uint16_t*)dy, (const uint16_t*)x,
-                       (const uint16_t*)R, (const uint16_t*)(w + pl.off_lt), (const uint16_t*)(w + pl.off_rt),
-                       (uint16_t*)dx, (uint16_t*)(w + pl.off_u), (uint16_t*)(w + pl.off_dw), (uint16_t*)(w + pl.off_dy1),
-                       pb.B, shape_of(pb), ld1, ldu);
+                       (const uint16_t*)R, LT, RTr, (uint16_t*)dx, Uws, dWws, dY1ws, pb.B, shape_of(pb), ld1, ldu);
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+template <bool DX_ONLY>
+int launch_bwd_rt(const Problem& pb, const void* dy, const void* x, const void* R, const uint16_t* LT, const uint16_t* RTr,
+                  void* dx, uint16_t* Uws, uint16_t* dWws, uint16_t* dY1ws, hipStream_t st)
+{
+    switch (pick_rt(bwd_row_bytes(pb), pb.B)) {
+        case 4: return launch_bwd<4, DX_ONLY>(pb, dy, x, R, LT, RTr, dx, Uws, dWws, dY1ws, st);
+        case 2: return launch_bwd<2, DX_ONLY>(pb, dy, x, R, LT, RTr, dx, Uws, dWws, dY1ws, st);
+        case 1: return launch_bwd<1, DX_ONLY>(pb, dy, x, R, LT, RTr, dx, Uws, dWws, dY1ws, st);
+    }
+    return -2;
+}
+
+// L^T and R^T (per block) into the workspace
+int launch_transposes(const Problem& pb, const void* R, const void* L, uint16_t* LT, uint16_t* RTr, hipStream_t st)
+{
+    const TransposeJob jl{(const uint16_t*)L, LT, pb.k, pb.s, pb.q};
+    const TransposeJob jr{(const uint16_t*)R, RTr, pb.k, pb.q, pb.p};
+    const size_t nmax = pb.n_L() > pb.n_R() ? pb.n_L() : pb.n_R();
+    hipLaunchKernelGGL(transpose_blocks_kernel, dim3((unsigned)((nmax + 255) / 256), 2), dim3(256), 0, st, jl, jr);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
@@ -478,19 +502,12 @@ int tiled_bwd(const Problem& pb, const void* dy, const void* x, const void* R, c
         return f32out ? launch_fill_zero_f32((float*)dL, pb.n_L(), st) : launch_fill_zero_u16((uint16_t*)dL, pb.n_L(), st);
     }
     char* w = (char*)ws;
-    {
-        const TransposeJob jl{(const uint16_t*)L, (uint16_t*)(w + pl.off_lt), pb.k, pb.s, pb.q};
-        const TransposeJob jr{(const uint16_t*)R, (uint16_t*)(w + pl.off_rt), pb.k, pb.q, pb.p};
-        const size_t nmax = pb.n_L() > pb.n_R() ? pb.n_L() : pb.n_R();
-        hipLaunchKernelGGL(transpose_blocks_kernel, dim3((unsigned)((nmax + 255) / 256), 2), dim3(256), 0, st, jl, jr);
-        if (hipGetLastError() != hipSuccess) return -4;
-    }
-    int rc = -2;
-    switch (pick_rt(bwd_row_bytes(pb), pb.B)) {
-        case 4: rc = launch_bwd<4>(pb, pl, dy, x, R, w, dx, st); break;
-        case 2: rc = launch_bwd<2>(pb, pl, dy, x, R, w, dx, st); break;
-        case 1: rc = launch_bwd<1>(pb, pl, dy, x, R, w, dx, st); break;
-    }
+    uint16_t* LT = (uint16_t*)(w + pl.off_lt);
+    uint16_t* RTr = (uint16_t*)(w + pl.off_rt);
+    int rc = launch_transposes(pb, R, L, LT, RTr, st);
+    if (rc) return rc;
+    rc = launch_bwd_rt<false>(pb, dy, x, R, LT, RTr, dx, (uint16_t*)(w + pl.off_u), (uint16_t*)(w + pl.off_dw),
+                              (uint16_t*)(w + pl.off_dy1), st);
     if (rc) return rc;
     WgradDesc dl, dr;
     fill_descs_tiled(pb, dl, dr);
@@ -502,6 +519,19 @@ int tiled_bwd(const Problem& pb, const void* dy, const void* x, const void* R, c
     rc = wgrad_gemm_pair(dl, dr, pl.nz, st);
     if (rc) return rc;
     return wgrad_reduce_pair(dl, dr, f32out, pl.nz, st);
+}
+
+// Transposed multiply y = x M (input rows of k*s values, output rows of n_in): the two adjoint stages alone.
+bool tiled_fwd_t_supported(const Problem& pb) { return base_ok(pb) && pick_rt(bwd_row_bytes(pb), pb.B > 0 ? pb.B : 1) > 0; }
+size_t tiled_fwd_t_workspace(const Problem& pb) { return align_up(pb.n_L() * 2, 256) + align_up(pb.n_R() * 2, 256); }
+int tiled_fwd_t(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
+{
+    if (!tiled_fwd_t_supported(pb)) return -2;
+    uint16_t* LT = (uint16_t*)ws;
+    uint16_t* RTr = (uint16_t*)((char*)ws + align_up(pb.n_L() * 2, 256));
+    const int rc = launch_transposes(pb, R, L, LT, RTr, st);
+    if (rc) return rc;
+    return launch_bwd_rt<true>(pb, x, nullptr, R, LT, RTr, y, nullptr, nullptr, nullptr, st);
 }
 
 }  // namespace monarch

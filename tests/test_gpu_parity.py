@@ -608,9 +608,11 @@ def run_fwd_t(B, sh, xin, R, L, flags=0):
 
 
 @pytest.mark.parametrize("generic", [False, True], ids=["dispatch", "generic"])
-@pytest.mark.parametrize("case", SMALL + MODEL_LAYERS, ids=lambda c: c[0])
+@pytest.mark.parametrize("case", SMALL + MODEL_LAYERS + [c[:7] for c in TILED], ids=lambda c: c[0])
 def test_transposed_multiply_small_shapes(B, case, generic):
     sh = small_shape(case)
+    if case[0] in [c[0] for c in TILED] and not generic:
+        assert B.monarch_kernel_name(3, sh.n_in, sh.k, sh.q, sh.s, 1, 0) == "mfma_fwd_t_tiled_bf16"
     flags = B.MONARCH_FLAG_GENERIC if generic else 0
     _, R, L, xin = synth.make_inputs(sh)  # the upstream-gradient tensor has the input shape of x M
     print("\n  kernel: %s" % B.monarch_kernel_name(3, sh.n_in, sh.k, sh.q, sh.s, 0 if sh.dtype == "f32" else 1, flags), flush=True)
