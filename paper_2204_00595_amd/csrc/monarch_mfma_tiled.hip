@@ -314,22 +314,17 @@ tiled_bwd_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ x
 
 // ---------------------------------------------------------------------------- host ----
 
-// Row tiles per workgroup: the most that keep the tile within half of the LDS (two workgroups per CU),
-// else the most that fit at all; not more rows than the batch has.  0: does not fit.
+// Row tiles per workgroup: the most whose LDS tile fits (every workgroup streams all the weights through
+// its L1 once, so fewer, larger tiles win over more resident workgroups); not more rows than the batch has.
+// 0: does not fit.
 int pick_rt(size_t row_bytes, int64_t B)
 {
     int rt = 0;
     for (int c : {4, 2, 1})
-        if ((size_t)16 * c * row_bytes <= kMaxLdsBytes / 2) {
+        if ((size_t)16 * c * row_bytes <= kMaxLdsBytes) {
             rt = c;
             break;
         }
-    if (!rt)
-        for (int c : {4, 2, 1})
-            if ((size_t)16 * c * row_bytes <= kMaxLdsBytes) {
-                rt = c;
-                break;
-            }
     while (rt > 1 && (int64_t)16 * (rt / 2) >= B) rt /= 2;
     return rt;
 }
