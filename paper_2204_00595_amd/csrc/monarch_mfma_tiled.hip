@@ -55,38 +55,63 @@ __device__ __forceinline__ float bf16_value(uint16_t b) { return __builtin_bit_c
 // One block-diagonal stage:  out[b][blk][n] = sum_i W[blk][n][i] * act[b][blk][i]  for the workgroup's rows.
 // load_a(rt, blk, i0) returns the eight activations i0 .. i0+7 of block blk for the lane's row of row tile rt;
 // emit(blk, t, acc) receives acc[rt][i] = out[b = 16*rt + 4*(lane/16) + i][blk][16*t + lane%16].
-template <int RT, typename LoadA, typename Emit>
-__device__ __forceinline__ void tiled_stage(int wave, int lane, int nblk, int nout, int nin,
-                                            const uint16_t* __restrict__ W, LoadA&& load_a, Emit&& emit)
+// An item is NT adjacent output tiles of one block: an activation fragment is then loaded once for NT
+// weight fragments: the stages are bound by the issue of operand loads, not by the matrix cores.
+template <int RT, int NT, typename LoadA, typename Emit>
+__device__ __forceinline__ void tiled_stage_nt(int wave, int lane, int nblk, int nout, int nin,
+                                               const uint16_t* __restrict__ W, LoadA&& load_a, Emit&& emit)
 {
     const int n = lane & 15, kg = lane >> 4;
-    const int ntile = nout >> 4, items = nblk * ntile;
+    const int ntile = (nout >> 4) / NT, items = nblk * ntile;
     const u32x4 zero = {0, 0, 0, 0};
     for (int item = wave; item < items; item += TL_WAVES) {
-        const int blk = item / ntile, t = item - blk * ntile;
+        const int blk = item / ntile, t = (item - blk * ntile) * NT;
         const uint16_t* wrow = W + ((size_t)blk * nout + 16 * t + n) * nin + 8 * kg;
-        f32x4 acc[RT];
+        f32x4 acc[NT][RT];
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) acc[j][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
         // KU K-steps per round, all of their loads issued before the first MFMA: the waves have nothing else
         // to hide the load latency behind
         for (int k0 = 0; k0 < nin; k0 += 32 * KU) {
-            u32x4 wf[KU], af[KU][RT];
+            u32x4 wf[KU][NT], af[KU][RT];
 #pragma unroll
             for (int u = 0; u < KU; ++u) {
                 const int i0 = k0 + 32 * u + 8 * kg;
                 const bool ok = i0 < nin;
-                wf[u] = ok ? ldg128(wrow + k0 + 32 * u) : zero;
+#pragma unroll
+                for (int j = 0; j < NT; ++j) wf[u][j] = ok ? ldg128(wrow + (size_t)16 * j * nin + k0 + 32 * u) : zero;
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt) af[u][rt] = ok ? load_a(rt, blk, i0) : zero;
             }
 #pragma unroll
             for (int u = 0; u < KU; ++u)
 #pragma unroll
-                for (int rt = 0; rt < RT; ++rt) acc[rt] = mfma16(as_bf16x8(af[u][rt]), as_bf16x8(wf[u]), acc[rt]);
+                for (int j = 0; j < NT; ++j)
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt)
+                        acc[j][rt] = mfma16(as_bf16x8(af[u][rt]), as_bf16x8(wf[u][j]), acc[j][rt]);
         }
-        emit(blk, t, acc);
+#pragma unroll
+        for (int j = 0; j < NT; ++j) emit(blk, t + j, acc[j]);
     }
+}
+
+template <int RT, typename LoadA, typename Emit>
+__device__ __forceinline__ void tiled_stage(int wave, int lane, int nblk, int nout, int nin,
+                                            const uint16_t* __restrict__ W, LoadA&& load_a, Emit&& emit)
+{
+    // as many tiles per item (at most four) as divide the tile count and still leave every wave an item
+    const int ntile = nout >> 4;
+    if (ntile % 4 == 0 && nblk * (ntile / 4) >= TL_WAVES)
+        tiled_stage_nt<RT, 4>(wave, lane, nblk, nout, nin, W, load_a, emit);
+    else if (ntile % 3 == 0 && nblk * (ntile / 3) >= TL_WAVES)
+        tiled_stage_nt<RT, 3>(wave, lane, nblk, nout, nin, W, load_a, emit);
+    else if (ntile % 2 == 0 && nblk * (ntile / 2) >= TL_WAVES)
+        tiled_stage_nt<RT, 2>(wave, lane, nblk, nout, nin, W, load_a, emit);
+    else
+        tiled_stage_nt<RT, 1>(wave, lane, nblk, nout, nin, W, load_a, emit);
 }
 
 // rows x cols LDS tile (row stride ld) -> dst[(b0 + row) * cols + ..] in 16-byte pieces, rows below B only
@@ -150,6 +175,7 @@ tiled_fwd_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
         });
     __syncthreads();
 
+    constexpr int KU2 = CG == 8 ? 2 : KU;  // eight blocks per item: fewer K-steps in flight, or the accumulators spill
     const int ncg = sh.k / CG, items = (sh.s >> 4) * ncg;
     const u32x4 zero = {0, 0, 0, 0};
     for (int item = wave; item < items; item += TL_WAVES) {
@@ -164,17 +190,17 @@ tiled_fwd_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
             const int c = cgi * CG + cc;
             const uint16_t* wrow = L + ((size_t)c * sh.s + 16 * lt + m) * sh.q + 8 * kg;
             const uint16_t* urow = lds + (size_t)m * ldu + c * sh.q + 8 * kg;
-            for (int k0 = 0; k0 < sh.q; k0 += 32 * KU) {
-                u32x4 wf[KU], af[KU][RT];
+            for (int k0 = 0; k0 < sh.q; k0 += 32 * KU2) {
+                u32x4 wf[KU2], af[KU2][RT];
 #pragma unroll
-                for (int u = 0; u < KU; ++u) {
+                for (int u = 0; u < KU2; ++u) {
                     const bool ok = k0 + 32 * u + 8 * kg < sh.q;
                     wf[u] = ok ? ldg128(wrow + k0 + 32 * u) : zero;
 #pragma unroll
                     for (int rt = 0; rt < RT; ++rt) af[u][rt] = ok ? lds128(urow + (size_t)16 * rt * ldu + k0 + 32 * u) : zero;
                 }
 #pragma unroll
-                for (int u = 0; u < KU; ++u)
+                for (int u = 0; u < KU2; ++u)
 #pragma unroll
                     for (int rt = 0; rt < RT; ++rt) acc[cc][rt] = mfma16(as_bf16x8(af[u][rt]), as_bf16x8(wf[u]), acc[cc][rt]);
             }
