@@ -146,6 +146,74 @@ __device__ __forceinline__ void store_run(uint16_t* p, const float (&v)[N])
 
 // ---------------------------------------------------------------------------- forward ----
 
+// Second stage of the forward for the workgroup's rows: y[b][l*k + c] = sum_r L[c][l][r] * U[b][c*q + r] (+ bias),
+// U in LDS (row stride ldu).
+template <int RT, int CG, int NL>
+__device__ __forceinline__ void fwd_stage2(int wave, int lane, const uint16_t* __restrict__ L, const uint16_t* lds, int ldu,
+                                           uint16_t* __restrict__ y, const uint16_t* __restrict__ bias, int64_t b0,
+                                           int64_t B, const TiledShape& sh)
+{
+    const int m = lane & 15, kg = lane >> 4;
+    const int n_out = sh.k * sh.s;
+    constexpr int KU2 = CG * NL >= 8 ? 2 : KU;  // many accumulators: fewer K-steps in flight, or they spill
+    const int ncg = sh.k / CG, items = ((sh.s >> 4) / NL) * ncg;
+    const u32x4 zero = {0, 0, 0, 0};
+    for (int item = wave; item < items; item += TL_WAVES) {
+        const int lt = (item / ncg) * NL, cgi = item % ncg;
+        f32x4 acc[CG][NL][RT];
+#pragma unroll
+        for (int cc = 0; cc < CG; ++cc)
+#pragma unroll
+            for (int j = 0; j < NL; ++j)
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) acc[cc][j][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int cc = 0; cc < CG; ++cc) {
+            const int c = cgi * CG + cc;
+            const uint16_t* wrow = L + ((size_t)c * sh.s + 16 * lt + m) * sh.q + 8 * kg;
+            const uint16_t* urow = lds + (size_t)m * ldu + c * sh.q + 8 * kg;
+            for (int k0 = 0; k0 < sh.q; k0 += 32 * KU2) {
+                u32x4 wf[KU2][NL], af[KU2][RT];
+#pragma unroll
+                for (int u = 0; u < KU2; ++u) {
+                    const bool ok = k0 + 32 * u + 8 * kg < sh.q;
+#pragma unroll
+                    for (int j = 0; j < NL; ++j) wf[u][j] = ok ? ldg128(wrow + (size_t)16 * j * sh.q + k0 + 32 * u) : zero;
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt) af[u][rt] = ok ? lds128(urow + (size_t)16 * rt * ldu + k0 + 32 * u) : zero;
+                }
+#pragma unroll
+                for (int u = 0; u < KU2; ++u)
+#pragma unroll
+                    for (int j = 0; j < NL; ++j)
+#pragma unroll
+                        for (int rt = 0; rt < RT; ++rt)
+                            acc[cc][j][rt] = mfma16(as_bf16x8(af[u][rt]), as_bf16x8(wf[u][j]), acc[cc][j][rt]);
+            }
+        }
+        // the lane holds output index l = 16*(lt + j) + m of blocks c0 .. c0+CG-1: columns l*k + c0 .. are contiguous
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const int col = (16 * (lt + j) + m) * sh.k + cgi * CG;
+            float bv[CG];
+#pragma unroll
+            for (int cc = 0; cc < CG; ++cc) bv[cc] = bias ? bf16_value(bias[col + cc]) : 0.f;
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int64_t row = b0 + 16 * rt + 4 * kg + i;
+                    if (row < B) {
+                        float v[CG];
+#pragma unroll
+                        for (int cc = 0; cc < CG; ++cc) v[cc] = acc[cc][j][rt][i] + bv[cc];
+                        store_run<CG>(y + (size_t)row * n_out + col, v);
+                    }
+                }
+        }
+    }
+}
+
 template <int RT, int CG>
 __global__ void __launch_bounds__(TL_THREADS)
 tiled_fwd_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R, const uint16_t* __restrict__ L,
@@ -154,7 +222,7 @@ tiled_fwd_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];  // U[TB][ldu]
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, m = lane & 15, kg = lane >> 4;
     const int64_t b0 = (int64_t)blockIdx.x * (16 * RT);
-    const int n_in = sh.k * sh.p, n_out = sh.k * sh.s;
+    const int n_in = sh.k * sh.p;
 
     // rows past the end are computed from the last valid row and dropped at the store
     const uint16_t* xrow[RT];
@@ -175,54 +243,13 @@ tiled_fwd_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
         });
     __syncthreads();
 
-    constexpr int KU2 = CG == 8 ? 2 : KU;  // eight blocks per item: fewer K-steps in flight, or the accumulators spill
-    const int ncg = sh.k / CG, items = (sh.s >> 4) * ncg;
-    const u32x4 zero = {0, 0, 0, 0};
-    for (int item = wave; item < items; item += TL_WAVES) {
-        const int lt = item / ncg, cgi = item - lt * ncg;
-        f32x4 acc[CG][RT];
-#pragma unroll
-        for (int cc = 0; cc < CG; ++cc)
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt) acc[cc][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int cc = 0; cc < CG; ++cc) {
-            const int c = cgi * CG + cc;
-            const uint16_t* wrow = L + ((size_t)c * sh.s + 16 * lt + m) * sh.q + 8 * kg;
-            const uint16_t* urow = lds + (size_t)m * ldu + c * sh.q + 8 * kg;
-            for (int k0 = 0; k0 < sh.q; k0 += 32 * KU2) {
-                u32x4 wf[KU2], af[KU2][RT];
-#pragma unroll
-                for (int u = 0; u < KU2; ++u) {
-                    const bool ok = k0 + 32 * u + 8 * kg < sh.q;
-                    wf[u] = ok ? ldg128(wrow + k0 + 32 * u) : zero;
-#pragma unroll
-                    for (int rt = 0; rt < RT; ++rt) af[u][rt] = ok ? lds128(urow + (size_t)16 * rt * ldu + k0 + 32 * u) : zero;
-                }
-#pragma unroll
-                for (int u = 0; u < KU2; ++u)
-#pragma unroll
-                    for (int rt = 0; rt < RT; ++rt) acc[cc][rt] = mfma16(as_bf16x8(af[u][rt]), as_bf16x8(wf[u]), acc[cc][rt]);
-            }
-        }
-        // the lane holds output index l = 16*lt + m of blocks c0 .. c0+CG-1: columns l*k + c0 .. are contiguous
-        const int col = (16 * lt + m) * sh.k + cgi * CG;
-        float bv[CG];
-#pragma unroll
-        for (int cc = 0; cc < CG; ++cc) bv[cc] = bias ? bf16_value(bias[col + cc]) : 0.f;
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int64_t row = b0 + 16 * rt + 4 * kg + i;
-                if (row < B) {
-                    float v[CG];
-#pragma unroll
-                    for (int cc = 0; cc < CG; ++cc) v[cc] = acc[cc][rt][i] + bv[cc];
-                    store_run<CG>(y + (size_t)row * n_out + col, v);
-                }
-            }
-    }
+    // An item: CG consecutive blocks c of NL adjacent 16-row output tiles l.  NL = 2 (an activation fragment
+    // from LDS then serves two weight fragments) where the accumulators fit and every wave still gets an item.
+    const int ltiles = sh.s >> 4, ncg = sh.k / CG;
+    if (CG <= 4 && (ltiles & 1) == 0 && (ltiles >> 1) * ncg >= TL_WAVES)
+        fwd_stage2<RT, CG, 2>(wave, lane, L, lds, ldu, y, bias, b0, B, sh);
+    else
+        fwd_stage2<RT, CG, 1>(wave, lane, L, lds, ldu, y, bias, b0, B, sh);
 }
 
 // ---------------------------------------------------------------------------- backward ----
