@@ -269,7 +269,44 @@ def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True, wi
         out["dense_fwd_ms"] = float(np.mean([run_of(dense_fwd) for _ in range(2)]))
         out["dense_bwd_ms"] = float(np.mean([run_of(dense_bwd) for _ in range(2)]))
         out["speedup_vs_dense"] = (out["dense_fwd_ms"] + out["dense_bwd_ms"]) / (fwd_ms + bwd_ms)
+
+        # The multiply as the paper runs it (Section 3.3): two framework batched matmuls with the reshapes and
+        # transposes between them as separate passes, the intermediate in HBM.  Context for what the fusion buys.
+        k, p, q, s_ = sh.k, sh.p, sh.q, sh.s
+        Rt = torch.randn(k, q, p, device=dev, dtype=dt)
+        Lt = torch.randn(k, s_, q, device=dev, dtype=dt)
+
+        def unfused_fwd(i):
+            xs = sets[i % nsets][0]
+            y1 = torch.bmm(xs.view(-1, k, p).transpose(0, 1), Rt.transpose(1, 2))        # (k, B, q)
+            u = y1.permute(1, 2, 0).reshape(-1, k, q).transpose(0, 1)                      # (q, k) grid, k chunks of q
+            w = torch.bmm(u, Lt.transpose(1, 2))                                           # (k, B, s)
+            return w.permute(1, 2, 0).reshape(-1, s_ * k)                                  # y[b, l*k + c]
+
+        unfused_fwd(0)
+        torch.cuda.synchronize()
+        out["unfused_bmm_fwd_ms"] = float(np.mean([run_of(unfused_fwd) for _ in range(2)]))
     return sh, out
+
+
+def mfma_roof(n: int = 8192, reps: int = 10):
+    """TFLOP/s of the vendor library's dense GEMM at a large square shape: the empirical matrix-core roof."""
+    import torch
+    res = {}
+    for name, dt in (("bf16", torch.bfloat16), ("f32", torch.float32)):
+        a = torch.randn(n, n, device="cuda", dtype=dt)
+        b = torch.randn(n, n, device="cuda", dtype=dt)
+        for _ in range(2):
+            a @ b
+        torch.cuda.synchronize()
+        e0, e1 = _events(2)
+        e0.record()
+        for _ in range(reps):
+            a @ b
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = 2.0 * n ** 3 * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return res
 
 
 def cpu_baseline(name: str, cpu_seconds: float = 20.0):
@@ -372,6 +409,10 @@ def main():
                                                 "value": flops / (r["step_saved_ms"] * 1e-3) / 1e12, "unit": "TFLOP/s"}
     line["hbm_copy_gbs"] = copy_roof()
     roof["frac_of_copy_roof"] = (roof["achieved"] / line["hbm_copy_gbs"]) if roof["bound"] == "hbm" else None
+    if not args.no_dense:
+        # empirical matrix-core roof (vendor GEMM, n = 8192) and the step's share of it
+        line["dense_gemm_roof_tflops"] = mfma_roof()
+        line["frac_of_dense_gemm_roof"] = line["value"] / line["dense_gemm_roof_tflops"][sh.dtype]
     if args.all:
         others = {}
         for name in ("sq256_f32", "sq256_f32_big", "gpt2s_fc1", "sq4096", "gpt2m_fc1", "gpt2m_fc2"):
