@@ -130,7 +130,7 @@ size_t bwd_sq16_workspace(const Problem& pb);
 int bwd_sq16(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx,
              void* dR, void* dL, void* ws, hipStream_t st);
 
-// shape-generic bf16 matrix-core kernels (any k; block sizes multiples of 16, the backward 32 and k % 4 == 0;
+// shape-generic bf16 matrix-core kernels (any k; block sizes multiples of 16, the backward 32;
 // both permutation readings; the forward adds pb.bias)
 bool tiled_fwd_supported(const Problem& pb);
 int tiled_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);

@@ -1,6 +1,6 @@
 // Shape-generic bf16 matrix-core kernels: the Monarch multiply of Section 3.3 and its backward for
-// any number of blocks, with block sizes that are multiples of 16 (forward) or 32 (backward, which
-// also needs k % 4 == 0 for the weight-gradient GEMMs).  They serve the shapes that have no tuned
+// any number of blocks, with block sizes that are multiples of 16 (forward) or 32 (backward: the tile
+// sizes of the weight-gradient GEMMs).  They serve the shapes that have no tuned
 // kernel; both readings of the permutation between the factors are handled.
 //
 // A workgroup (eight waves) owns TB = 16 * RT rows.  A block-diagonal stage is a list of work items
@@ -532,7 +532,7 @@ int tiled_fwd(const Problem& pb, const void* x, const void* R, const void* L, vo
 
 bool tiled_bwd_supported(const Problem& pb)
 {
-    return base_ok(pb) && pb.k % 4 == 0 && pb.p % 32 == 0 && pb.q % 32 == 0 && pb.s % 32 == 0 &&
+    return base_ok(pb) && pb.p % 32 == 0 && pb.q % 32 == 0 && pb.s % 32 == 0 &&
            pick_rt(bwd_row_bytes(pb), pb.B > 0 ? pb.B : 1) > 0 && make_plan_tiled(pb).ok;
 }
 

@@ -93,7 +93,7 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
         } else {
             const int g = task / (KB * TM / 8), rem = task % (KB * TM / 8);
             const int r = rem / (TM / 8), u = rem % (TM / 8);
-            ra[t] = tid + t * NTHR < A_TASKS ? r : (1 << 30);
+            ra[t] = tid + t * NTHR < A_TASKS && g0 + g < d.G ? r : (1 << 30);  // a group past the last one: zeros
             pa[t] = d.A + (row_lo + r) * d.lda + (size_t)(g0 + g) * d.a_g + m0 + 8 * u;
             la[t] = (g * KB + r) * SA + 8 * u;
         }
@@ -104,7 +104,7 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
         const int g = task / (KB * TN / 8), rem = task % (KB * TN / 8);
         const int r = rem / (TN / 8), u = rem % (TN / 8);
         const int n = n0 + 8 * u;
-        rb[t] = tid + t * NTHR < B_TASKS ? r : (1 << 30);
+        rb[t] = tid + t * NTHR < B_TASKS && g0 + g < d.G ? r : (1 << 30);
         pb[t] = d.Bm + (row_lo + r) * d.ldb + (size_t)(g0 + g) * d.b_g + (size_t)(n / d.seg_w) * d.b_seg + (n % d.seg_w);
         lb[t] = 4 * KB * SA + (g * KB + r) * SB + 8 * u;
     }
@@ -219,7 +219,7 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
             }
         }
     }
-    if (kh != 0) return;
+    if (kh != 0 || g0 + grp >= d.G) return;  // (the group count need not be a multiple of four)
 
     // partial tile: P[z][g][m][n]
     const int ln = lane & 31, h = lane >> 5;
@@ -297,7 +297,7 @@ wgrad_reduce_kernel(WgradDesc d0, WgradDesc d1, int blocks0, int nz, ColsumJob c
     }
 }
 
-int tiles_of(const WgradDesc& d, int tm, int tn) { return (d.M / tm) * (d.N / tn) * (d.G / 4); }
+int tiles_of(const WgradDesc& d, int tm, int tn) { return (d.M / tm) * (d.N / tn) * ((d.G + 3) / 4); }
 
 template <int TM, int TN>
 int launch_gemm(const WgradDesc& d0, const WgradDesc* d1, int nz, hipStream_t st)
@@ -343,15 +343,15 @@ bool wgrad_tile_ok(int M, int N, int seg_w, int* tm, int* tn)
 int wgrad_tiles(const WgradDesc& d)
 {
     int tm, tn;
-    if (!wgrad_tile_ok(d.M, d.N, d.seg_w, &tm, &tn) || d.G % 4 != 0) return 0;
+    if (!wgrad_tile_ok(d.M, d.N, d.seg_w, &tm, &tn) || (d.deint && d.G != 4)) return 0;
     return tiles_of(d, tm, tn);
 }
 
 int wgrad_gemm_pair(const WgradDesc& d0, const WgradDesc& d1, int nz, hipStream_t st)
 {
     int tm0, tn0, tm1, tn1;
-    if (!wgrad_tile_ok(d0.M, d0.N, d0.seg_w, &tm0, &tn0) || d0.G % 4 != 0) return -2;
-    if (!wgrad_tile_ok(d1.M, d1.N, d1.seg_w, &tm1, &tn1) || d1.G % 4 != 0) return -2;
+    if (!wgrad_tile_ok(d0.M, d0.N, d0.seg_w, &tm0, &tn0) || (d0.deint && d0.G != 4)) return -2;
+    if (!wgrad_tile_ok(d1.M, d1.N, d1.seg_w, &tm1, &tn1) || (d1.deint && d1.G != 4)) return -2;
     if (tm0 == tm1 && tn0 == tn1) return launch_gemm_tile(tm0, tn0, d0, &d1, nz, st);
     const int rc = launch_gemm_tile(tm0, tn0, d0, nullptr, nz, st);
     return rc ? rc : launch_gemm_tile(tm1, tn1, d1, nullptr, nz, st);

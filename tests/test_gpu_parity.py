@@ -163,8 +163,8 @@ def test_model_layer_shapes_on_matrix_cores(B, case):
 
 
 # Shapes without a tuned kernel that the shape-generic matrix-core kernels must serve: block sizes that are
-# multiples of 16 (forward; a size that is 16 mod 32 ends on a half-empty K-step) or of 32 with k % 4 == 0
-# (backward).  name, dtype, B, k, p, q, s, backward on matrix cores too
+# multiples of 16 (forward; a size that is 16 mod 32 ends on a half-empty K-step) or of 32 (backward; any k:
+# the weight-gradient GEMM takes four blocks per workgroup and masks the ones past the last).  name, dtype, B, k, p, q, s, backward on matrix cores too
 TILED = [
     ("vits_proj_384_384", "bf16", 300, 4, 96, 96, 96, True),
     ("vits_fc1_384_1536", "bf16", 203, 4, 96, 96, 384, True),
@@ -173,6 +173,9 @@ TILED = [
     ("k8_64_32_96", "bf16", 131, 8, 64, 32, 96, True),
     ("k12_32_64_32", "bf16", 77, 12, 32, 64, 32, True),
     ("k16_wide_mid", "bf16", 50, 16, 32, 192, 32, True),
+    ("k2_64_32_96", "bf16", 150, 2, 64, 32, 96, True),
+    ("k6_32_64_32", "bf16", 101, 6, 32, 64, 32, True),
+    ("k1_dense_pair_32", "bf16", 70, 1, 64, 96, 32, True),
     ("k2_tail_48_80_48", "bf16", 90, 2, 48, 80, 48, False),
     ("k3_32_48_16", "bf16", 67, 3, 32, 48, 16, False),
     ("k1_dense_pair", "bf16", 33, 1, 64, 48, 80, False),
