@@ -199,6 +199,29 @@ def test_shape_generic_matrix_core_kernels(B, case, reading):
             ["dx", "dR32", "dL32", "dbias32"])
 
 
+def test_shape_generic_kernels_on_random_shapes(B):
+    """Seeded random shapes with blocks that are multiples of 32 and any block count (odd ones too): forward,
+    backward and transposed multiply must run on the shape-generic matrix-core kernels and match the oracle."""
+    rng = np.random.default_rng(20220400595)
+    done = 0
+    while done < 10:
+        k = int(rng.integers(1, 10))
+        p, q, s = (int(32 * rng.integers(1, 6)) for _ in range(3))
+        Bn = int(rng.integers(1, 200))
+        reading = int(rng.integers(0, 2))
+        flags = B.MONARCH_FLAG_PERM_B if reading else 0
+        names = [B.monarch_kernel_name(ps, k * p, k, q, s, 1, flags) for ps in (0, 1, 3)]
+        if names != ["mfma_fwd_tiled_bf16", "mfma_bwd_tiled_bf16", "mfma_fwd_t_tiled_bf16"]:
+            continue  # a shape with a tuned kernel
+        done += 1
+        sh = synth.Shape("rand%d_k%d_%d_%d_%d_B%d_r%d" % (done, k, p, q, s, Bn, reading), "bf16", Bn, k, p, q, s, config=200 + done)
+        rd = oracle.READING_B if reading else oracle.READING_A
+        x, R, L, dy = synth.make_inputs(sh)
+        compare(sh, [run_fwd(B, sh, x, R, L, flags)], [oracle.fwd(x, R, L, rd)], ["y"])
+        compare(sh, run_bwd(B, sh, dy, x, R, L, flags), oracle.bwd(dy, x, R, L, rd), ["dx", "dR", "dL"])
+        compare(sh, [run_fwd_t(B, sh, dy, R, L, flags)], [oracle.fwd_t(dy, R, L, rd)], ["xM"])
+
+
 @pytest.mark.parametrize("case", [c for c in SMALL if c[3] != c[5]][:5], ids=lambda c: c[0])
 def test_alternative_mid_permutation(B, case):
     sh = small_shape(case)
