@@ -360,7 +360,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.stderr.write("bench.py: this library runs on ONE GPU; --gpus N with N > 1 is not supported "
-                         "(the path shards over batch rows only, see DESIGN.md).\n")
+                         "(a multi-GPU run would shard the batch rows and all-reduce dR, dL; nothing of that is built).\n")
         sys.exit(2)
     import torch
     from paper_2204_00595_amd import binding
