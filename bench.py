@@ -1,17 +1,24 @@
 #!/usr/bin/env python3
 """Benchmark of the Monarch multiply hot path (forward + backward) on one MI355X.
 
-A "step" is one pass of the whole hot path over one batch of synthetic input:
-monarch_fwd followed by monarch_bwd on the workload's shape, inputs resident in HBM.
-Prints ONE JSON line (see the keys below).  `--gpus N` with N > 1 is refused: the
-library is a single-GPU kernel library.
+Headline ("step"): the GPT-2-medium-style MLP pair 1024 -> 4096 -> 1024 on 16384 tokens, the largest
+of the five stated configurations: forward of both layers, then backward of both (no nonlinearity
+between the two multiplies, the hidden activation stored in bf16 in HBM between the calls):
+    h = fwd(x; fc1)   y = fwd(h; fc2)   (dh, dR2, dL2) = bwd(dy, h; fc2)   (dx, dR1, dL1) = bwd(dh, x; fc1)
+`--workload NAME` times one layer's forward + backward as the step instead.
 
-Timing: K steps bracketed by torch.cuda.synchronize(); per-call durations come from HIP
-events recorded on the stream the kernels are launched on (torch's current stream) around a
-run of K consecutive calls of one entry point.
-Buffers rotate through enough distinct (x, y, dy, dx) sets that the footprint exceeds the
-256 MB Infinity Cache, so repeats are served from HBM; the weights stay hot, as they would
-in training.
+Prints ONE JSON line.  Besides the headline it carries, under detail.configs, one block for every
+stated configuration (and the n = 256 fp32 shape at 2^20 rows): forward and backward time per call
+(median and minimum over >= 100 timed calls), TFLOP/s, GB/s, fraction of the nominal roofline and of the
+measured copy rate, HBM traffic from the committed counter profiles, the vendor dense GEMM of the same
+(B, n_in, n_out), and the kernels the dispatcher picked.  `--gpus N` with N > 1 is refused: the library is
+a single-GPU kernel library.
+
+Timing: the K steps are bracketed by torch.cuda.synchronize(); per-call durations come from HIP events
+recorded on the stream the kernels are launched on (torch's current stream) around runs of consecutive
+calls of one entry point, so that the events (3-10 us each) sit outside the timed launches.  Buffers
+rotate through enough distinct sets that the footprint exceeds the 256 MB Infinity Cache, so repeats are
+served from HBM; the weights stay hot, as they would in training.
 """
 from __future__ import annotations
 
@@ -30,6 +37,37 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 ROTATE_BYTES = 1 << 30
 COPY_BYTES = 1 << 30           # size of the plain copy timed as the empirical HBM roof
 TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
+PAIR = "gpt2m_pair"
+CONFIGS = ("sq256_f32", "sq256_f32_big", "vitb_proj", "gpt2s_fc1", "sq4096", "gpt2m_fc1", "gpt2m_fc2")
+TIMED_CALLS = 100              # per entry point and configuration, split into RUNS runs
+RUNS = 10
+
+
+def _events(n):
+    import torch
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def timed_runs(fn, calls: int = TIMED_CALLS, runs: int = RUNS, untimed: int = 3):
+    """`runs` runs of calls/runs consecutive calls of fn(i), each run between two events on the launch
+    stream; returns (median, min, mean) over the runs of the time per call, in ms, and the calls timed."""
+    import numpy as np
+    import torch
+    per = max(1, -(-calls // runs))
+    for i in range(untimed):   # first launches of a kernel pay for loading it
+        fn(i)
+    out = []
+    n = untimed
+    for _ in range(runs):
+        e0, e1 = _events(2)
+        e0.record()
+        for _ in range(per):
+            fn(n)
+            n += 1
+        e1.record()
+        torch.cuda.synchronize()
+        out.append(e0.elapsed_time(e1) / per)
+    return float(np.median(out)), float(np.min(out)), float(np.mean(out)), per * runs
 
 
 def copy_roof(reps: int = 5):
@@ -53,245 +91,11 @@ def copy_roof(reps: int = 5):
     return 2.0 * COPY_BYTES / (best * 1e-3) / 1e9
 
 
-def _events(n):
-    import torch
-    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
-
-
-def run_workload(name: str, steps: int, warmup: int, with_dense: bool = True, with_extras: bool = True):
-    import numpy as np
-    import torch
-    from paper_2204_00595_amd import binding, synth
-
-    sh = synth.workload(name)
-    dt = torch.float32 if sh.dtype == "f32" else torch.bfloat16
-    code = 0 if sh.dtype == "f32" else 1
-    dev = torch.device("cuda:0")
-    gen_rows = min(sh.B, 65536)  # larger batches repeat a generated block (timing only)
-    x, R, L, dy = synth.make_inputs(sh, rows=gen_rows)
-    Rd, Ld = (torch.from_numpy(a).to(dev).to(dt) for a in (R, L))
-    x0 = torch.from_numpy(x).to(dev).to(dt).repeat(sh.B // gen_rows, 1)
-    dy0 = torch.from_numpy(dy).to(dev).to(dt).repeat(sh.B // gen_rows, 1)
-    per_set = sh.esize * sh.B * (2 * sh.n_in + 2 * sh.n_out)
-    nsets = max(2, min(64, -(-ROTATE_BYTES // per_set)))
-    sets = []
-    for i in range(nsets):
-        xs = x0 if i == 0 else x0.roll(i, 0).contiguous()
-        dys = dy0 if i == 0 else dy0.roll(i, 0).contiguous()
-        sets.append((xs, dys, torch.empty((sh.B, sh.n_out), dtype=dt, device=dev), torch.empty_like(xs)))
-    dR = torch.empty_like(Rd)
-    dL = torch.empty_like(Ld)
-    need = binding.monarch_bwd_workspace_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, code, 0)
-    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
-
-    def step(i, ev=None):
-        xs, dys, y, dx = sets[i % nsets]
-        if ev:
-            ev[0].record()
-        binding.monarch_fwd(xs, Rd, Ld, y)
-        if ev:
-            ev[1].record()
-        binding.monarch_bwd(dys, xs, Rd, Ld, dx, dR, dL, workspace=ws)
-        if ev:
-            ev[2].record()
-
-    for i in range(warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        step(i)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-
-    # per-call durations: HIP events on the launch stream around a run of `steps` consecutive calls of
-    # one entry point (same rotation), so that the events themselves sit outside the timed launches;
-    # a single step with an event after every call is kept as the "evented" figure
-    def run_of(fn):
-        for i in range(3):  # untimed: first launches of a kernel pay for loading it
-            fn(i)
-        e0, e1 = _events(2)
-        e0.record()
-        for i in range(steps):
-            fn(i)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / steps
-
-    def fwd_only(i):
-        xs, _, y, _ = sets[i % nsets]
-        binding.monarch_fwd(xs, Rd, Ld, y)
-
-    def bwd_only(i):
-        xs, dys, _, dx = sets[i % nsets]
-        binding.monarch_bwd(dys, xs, Rd, Ld, dx, dR, dL, workspace=ws)
-
-    # the same calls on one buffer set ("warm": repeats can be served by the 256 MB Infinity Cache)
-    fwd_warm = run_of(lambda i: fwd_only(0))
-    bwd_warm = run_of(lambda i: bwd_only(0))
-
-    fneed = binding.monarch_fwd_workspace_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, code, 0)
-    fws = torch.empty(max(fneed, 256), dtype=torch.uint8, device=dev)
-
-    def fwd_ws_only(i):
-        xs, _, y, _ = sets[i % nsets]
-        binding.monarch_fwd_ws(xs, Rd, Ld, y, workspace=fws)
-
-    def fwd_ws_packed(i):
-        xs, _, y, _ = sets[i % nsets]
-        binding.monarch_fwd_ws(xs, Rd, Ld, y, workspace=fws, flags=binding.MONARCH_FLAG_WS_PACKED)
-
-    fwd_ws_ms = float(np.mean([run_of(fwd_ws_only) for _ in range(3)])) if fneed else None
-    fwd_ws_packed_ms = float(np.mean([run_of(fwd_ws_packed) for _ in range(3)])) if fneed else None
-    fwd_bias_ms = fwd_then_add_ms = bwd_bias_ms = to_dense_ms = to_dense_gbs = project_ms = fwd_t_ms = c64_fwd_ms = c64_bwd_ms = c64_rows = None
-    fwd_save_ms = bwd_saved_ms = step_saved_ms = None
-    if with_extras:
-        # forward that saves the vector between the factors + backward that reads it instead of recomputing
-        sneed = binding.monarch_saved_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, code, 0)
-        svs = [torch.empty(sneed, dtype=torch.uint8, device=dev) for _ in range(nsets)] if sneed else None
-
-        def fwd_save_only(i):
-            xs, _, y, _ = sets[i % nsets]
-            binding.monarch_fwd_save(xs, Rd, Ld, y, svs[i % nsets])
-
-        def bwd_saved_only(i):
-            xs, dys, _, dx = sets[i % nsets]
-            binding.monarch_bwd_saved(dys, xs, svs[i % nsets], Rd, Ld, dx, dR, dL, workspace=ws)
-
-        def step_saved(i):
-            fwd_save_only(i)
-            bwd_saved_only(i)
-
-        fwd_save_ms = float(np.mean([run_of(fwd_save_only) for _ in range(3)])) if sneed else None
-        bwd_saved_ms = float(np.mean([run_of(bwd_saved_only) for _ in range(3)])) if sneed else None
-        step_saved_ms = float(np.mean([run_of(step_saved) for _ in range(3)])) if sneed else None
-        # affine layer: bias fused into the forward (where the kernel has the epilogue), bias gradient with the backward;
-        # beside them the unfused forms (the plain call, then a separate elementwise add / column sum by the framework)
-        biasd = torch.from_numpy(synth.quantize(synth.normal(4242, (sh.n_out,)), sh.dtype)).to(dev).to(dt)
-        dbias = torch.empty_like(biasd)
-
-        def fwd_bias_only(i):
-            xs, _, y, _ = sets[i % nsets]
-            binding.monarch_fwd_bias(xs, Rd, Ld, biasd, y, workspace=fws if fneed else None)
-
-        def fwd_then_add(i):
-            xs, _, y, _ = sets[i % nsets]
-            if fneed:
-                binding.monarch_fwd_ws(xs, Rd, Ld, y, workspace=fws)
-            else:
-                binding.monarch_fwd(xs, Rd, Ld, y)
-            y.add_(biasd)
-
-        def bwd_bias_only(i):
-            xs, dys, _, dx = sets[i % nsets]
-            binding.monarch_bwd_bias(dys, xs, Rd, Ld, dx, dR, dL, dbias, workspace=ws)
-
-        fwd_bias_ms = float(np.mean([run_of(fwd_bias_only) for _ in range(3)]))
-        fwd_then_add_ms = float(np.mean([run_of(fwd_then_add) for _ in range(3)]))
-        bwd_bias_ms = float(np.mean([run_of(bwd_bias_only) for _ in range(3)]))
-        # transposed multiply x M (monarch_fwd_t): input of the output's shape, result of the input's shape
-        tneed = binding.monarch_fwd_t_workspace_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, code, 0)
-        tws = torch.empty(max(tneed, 256), dtype=torch.uint8, device=dev)
-
-        def fwd_t_only(i):
-            _, dys, _, dx = sets[i % nsets]
-            binding.monarch_fwd_t(dys, Rd, Ld, dx, workspace=tws if tneed else None)
-
-        fwd_t_ms = float(np.mean([run_of(fwd_t_only) for _ in range(3)]))
-        Mdense = torch.empty((sh.n_out, sh.n_in), dtype=Rd.dtype, device="cuda")
-        to_dense_ms = float(np.mean([run_of(lambda i: binding.monarch_to_dense(Rd, Ld, Mdense)) for _ in range(3)]))
-        dense_bytes = (sh.k * sh.q * sh.p + sh.k * sh.s * sh.q + sh.n_out * sh.n_in) * sh.esize
-        to_dense_gbs = dense_bytes / (to_dense_ms * 1e-3) / 1e9
-        if sh.k == sh.p == sh.q == sh.s:
-            # complex64 multiply with the DFT factors (shape-generic SIMT kernels) on the first rows of the batch
-            crow = min(sh.B, 2048)
-            cx = torch.randn((crow, sh.n_in), dtype=torch.complex64, device=dev, generator=torch.Generator(device=dev).manual_seed(7))
-            cR, cL = binding.monarch_dft_factors(sh.k, False, device=dev)
-            cy = torch.empty_like(cx)
-            c64_fwd_ms = float(np.mean([run_of(lambda i: binding.monarch_fwd_c64(cx, cR, cL, cy)) for _ in range(2)]))
-            c64_bwd_ms = float(np.mean([run_of(lambda i: binding.monarch_bwd_c64(cy, cx, cR, cL)) for _ in range(2)]))
-            c64_rows = crow
-            # Algorithm 1 on a dense Gaussian n x n matrix (square shapes only): one Jacobi SVD per slice
-            Adense = torch.from_numpy(synth.quantize(synth.normal(4343, (sh.n_in, sh.n_in)), sh.dtype)).to(dev).to(dt)
-            Rp, Lp = torch.empty_like(Rd), torch.empty_like(Ld)
-            project_ms = float(np.mean([run_of(lambda i: binding.monarch_project(Adense, Rp, Lp)) for _ in range(2)]))
-    fwd_runs = [run_of(fwd_only) for _ in range(3)]
-    bwd_runs = [run_of(bwd_only) for _ in range(3)]
-    fwd_ms, bwd_ms = float(np.mean(fwd_runs)), float(np.mean(bwd_runs))
-    fwd_min, bwd_min = float(np.min(fwd_runs)), float(np.min(bwd_runs))
-    evs = [_events(3) for _ in range(steps)]
-    for i in range(steps):
-        step(i, evs[i])
-    torch.cuda.synchronize()
-    fwd_ev = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
-    bwd_ev = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
-
-    out = {
-        "workload": name, "ms_per_step": wall / steps * 1e3,
-        "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "fwd_ms_min": fwd_min, "bwd_ms_min": bwd_min,
-        "fwd_ms_evented": fwd_ev, "bwd_ms_evented": bwd_ev,
-        "fwd_ms_warm": fwd_warm, "bwd_ms_warm": bwd_warm,  # one buffer set instead of the rotation: cache-assisted, not the headline
-        # monarch_fwd_ws (weights packed into a caller workspace, pack included); null when the shape has no such kernel
-        "fwd_ws_ms": fwd_ws_ms, "fwd_ws_packed_ms": fwd_ws_packed_ms,  # the latter: pack pass skipped (weights unchanged)
-        "fwd_ws_kernel": binding.monarch_kernel_name(2, sh.n_in, sh.k, sh.q, sh.s, code),
-        # monarch_fwd_bias / monarch_bwd_bias (affine layer); fwd_then_add_ms = forward with workspace + a separate torch add
-        "fwd_bias_ms": fwd_bias_ms, "fwd_then_add_ms": fwd_then_add_ms, "bwd_bias_ms": bwd_bias_ms,
-        # monarch_to_dense: M written out as a dense (n_out, n_in) matrix; bytes = R + L read, M written
-        "to_dense_ms": to_dense_ms, "to_dense_gbs": to_dense_gbs,
-        "fwd_t_ms": fwd_t_ms, "fwd_t_kernel": binding.monarch_kernel_name(3, sh.n_in, sh.k, sh.q, sh.s, code),  # monarch_fwd_t
-        "c64_fwd_ms": c64_fwd_ms, "c64_bwd_ms": c64_bwd_ms, "c64_rows": c64_rows,  # monarch_fwd_c64 / monarch_bwd_c64 on c64_rows rows
-        "project_ms": project_ms,  # monarch_project of a dense n x n matrix (square shapes), else null
-        # monarch_fwd_save / monarch_bwd_saved (the intermediate goes through HBM once instead of being recomputed); null without that path
-        "fwd_save_ms": fwd_save_ms, "bwd_saved_ms": bwd_saved_ms, "step_saved_ms": step_saved_ms,
-        "fwd_kernel": binding.monarch_kernel_name(0, sh.n_in, sh.k, sh.q, sh.s, code),
-        "bwd_kernel": binding.monarch_kernel_name(1, sh.n_in, sh.k, sh.q, sh.s, code),
-        "fwd_tflops": sh.fwd_flops() / (fwd_ms * 1e-3) / 1e12,
-        "bwd_tflops": sh.bwd_flops() / (bwd_ms * 1e-3) / 1e12,
-        "fwd_gbs": sh.fwd_bytes() / (fwd_ms * 1e-3) / 1e9,
-        "bwd_gbs": sh.bwd_bytes() / (bwd_ms * 1e-3) / 1e9,
-        "rotating_sets": nsets,
-    }
-    for ps, flops, nbytes, ms in (("fwd", sh.fwd_flops(), sh.fwd_bytes(), fwd_ms), ("bwd", sh.bwd_flops(), sh.bwd_bytes(), bwd_ms)):
-        t_hbm = nbytes / (HBM_PEAK_GBS * 1e9)
-        t_mfma = flops / (MFMA_PEAK_TFLOPS[sh.dtype] * 1e12)
-        out[ps + "_roofline_frac"] = max(t_hbm, t_mfma) / (ms * 1e-3)
-        out[ps + "_bound"] = "hbm" if t_hbm >= t_mfma else "mfma"
-
-    if with_dense:
-        # vendor dense GEMM of the same (B, n_in, n_out): 1 GEMM forward, 2 GEMMs backward
-        W = torch.randn(sh.n_out, sh.n_in, device=dev, dtype=dt)
-        for _ in range(3):
-            sets[0][0] @ W.t()
-        torch.cuda.synchronize()
-        def dense_fwd(i):
-            sets[i % nsets][0] @ W.t()
-
-        def dense_bwd(i):
-            xs, dys, _, _ = sets[i % nsets]
-            dys @ W
-            dys.t() @ xs
-
-        out["dense_fwd_ms"] = float(np.mean([run_of(dense_fwd) for _ in range(2)]))
-        out["dense_bwd_ms"] = float(np.mean([run_of(dense_bwd) for _ in range(2)]))
-        out["speedup_vs_dense"] = (out["dense_fwd_ms"] + out["dense_bwd_ms"]) / (fwd_ms + bwd_ms)
-
-        # The multiply as the paper runs it (Section 3.3): two framework batched matmuls with the reshapes and
-        # transposes between them as separate passes, the intermediate in HBM.  Context for what the fusion buys.
-        k, p, q, s_ = sh.k, sh.p, sh.q, sh.s
-        Rt = torch.randn(k, q, p, device=dev, dtype=dt)
-        Lt = torch.randn(k, s_, q, device=dev, dtype=dt)
-
-        def unfused_fwd(i):
-            xs = sets[i % nsets][0]
-            y1 = torch.bmm(xs.view(-1, k, p).transpose(0, 1), Rt.transpose(1, 2))        # (k, B, q)
-            u = y1.permute(1, 2, 0).reshape(-1, k, q).transpose(0, 1)                      # (q, k) grid, k chunks of q
-            w = torch.bmm(u, Lt.transpose(1, 2))                                           # (k, B, s)
-            return w.permute(1, 2, 0).reshape(-1, s_ * k)                                  # y[b, l*k + c]
-
-        unfused_fwd(0)
-        torch.cuda.synchronize()
-        out["unfused_bmm_fwd_ms"] = float(np.mean([run_of(unfused_fwd) for _ in range(2)]))
-    return sh, out
+def launch_floor():
+    """Time per launch of a run of empty kernels on the launch stream, in us (median and min of 10 runs of 200)."""
+    from paper_2204_00595_amd import binding
+    med, mn, _, _ = timed_runs(lambda i: binding.monarch_launch_probe(), calls=2000, runs=10)
+    return {"median_us": med * 1e3, "min_us": mn * 1e3}
 
 
 def mfma_roof(n: int = 8192, reps: int = 10):
@@ -314,122 +118,481 @@ def mfma_roof(n: int = 8192, reps: int = 10):
     return res
 
 
-def cpu_baseline(name: str, cpu_seconds: float = 20.0):
-    """The CPU oracle as it stands, timed on this host: forward + backward over the first rows of the
-    workload (the whole batch when it is cheap enough, then repeated), sized to about `cpu_seconds`
-    core-seconds of work in total."""
+def traffic_of(workload: str, call: str):
+    """HBM bytes per call from the committed rocprofv3 counter profile of the workload, or None."""
+    if not os.path.exists(TRAFFIC_JSON):
+        return None
+    t = json.load(open(TRAFFIC_JSON)).get(workload, {}).get(call)
+    return (t["fetch_bytes"] + t["write_bytes"]) if t else None
+
+
+def roofline_of(sh, ps: str, ms: float):
+    """Nominal roofline of one call: max(T_hbm, T_mfma) / measured, and which of the two bounds it."""
+    flops = sh.fwd_flops() if ps == "fwd" else sh.bwd_flops()
+    nbytes = sh.fwd_bytes() if ps == "fwd" else sh.bwd_bytes()
+    t_hbm = nbytes / (HBM_PEAK_GBS * 1e9)
+    t_mfma = flops / (MFMA_PEAK_TFLOPS[sh.dtype] * 1e12)
+    return max(t_hbm, t_mfma) / (ms * 1e-3), ("hbm" if t_hbm >= t_mfma else "mfma")
+
+
+def _gen_rows(B: int, cap: int = 2048) -> int:
+    """Largest divisor of B that is <= cap: rows drawn from the generator; the rest of the batch repeats them
+    (the kernels' time does not depend on the values, and generating 10^8 normals on the host takes minutes)."""
+    return max(d for d in range(1, min(B, cap) + 1) if B % d == 0)
+
+
+class Layer:
+    """Device tensors of one workload: weights, gradients, workspaces, and rotating activation sets."""
+
+    def __init__(self, name: str, rotate_bytes: int = ROTATE_BYTES):
+        import torch
+        from paper_2204_00595_amd import binding, synth
+        self.name = name
+        self.sh = sh = synth.workload(name)
+        self.dt = torch.float32 if sh.dtype == "f32" else torch.bfloat16
+        self.code = 0 if sh.dtype == "f32" else 1
+        dev = torch.device("cuda:0")
+        gen_rows = _gen_rows(sh.B)  # the batch repeats a generated block of rows (timing only)
+        x, R, L, dy = synth.make_inputs(sh, rows=gen_rows)
+        self.R, self.L = (torch.from_numpy(a).to(dev).to(self.dt) for a in (R, L))
+        x0 = torch.from_numpy(x).to(dev).to(self.dt).repeat(sh.B // gen_rows, 1)
+        dy0 = torch.from_numpy(dy).to(dev).to(self.dt).repeat(sh.B // gen_rows, 1)
+        per_set = sh.esize * sh.B * (2 * sh.n_in + 2 * sh.n_out)
+        self.nsets = max(2, min(64, -(-rotate_bytes // per_set)))
+        self.sets = []
+        for i in range(self.nsets):
+            xs = x0 if i == 0 else x0.roll(i, 0).contiguous()
+            dys = dy0 if i == 0 else dy0.roll(i, 0).contiguous()
+            self.sets.append((xs, dys, torch.empty((sh.B, sh.n_out), dtype=self.dt, device=dev), torch.empty_like(xs)))
+        self.dR = torch.empty_like(self.R)
+        self.dL = torch.empty_like(self.L)
+        need = binding.monarch_bwd_workspace_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, self.code, 0)
+        self.ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+        self.fneed = binding.monarch_fwd_workspace_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, self.code, 0)
+        self.fws = torch.empty(max(self.fneed, 256), dtype=torch.uint8, device=dev)
+
+    def fwd(self, i):
+        from paper_2204_00595_amd import binding
+        xs, _, y, _ = self.sets[i % self.nsets]
+        binding.monarch_fwd(xs, self.R, self.L, y)
+
+    def bwd(self, i):
+        from paper_2204_00595_amd import binding
+        xs, dys, _, dx = self.sets[i % self.nsets]
+        binding.monarch_bwd(dys, xs, self.R, self.L, dx, self.dR, self.dL, workspace=self.ws)
+
+    def step(self, i):
+        self.fwd(i)
+        self.bwd(i)
+
+
+def measure_layer(name: str, with_dense: bool = True, with_extras: bool = False, layer: Layer | None = None,
+                  calls: int = TIMED_CALLS, copy_gbs: float | None = None):
+    """One configuration's block: per-call times of monarch_fwd and monarch_bwd (and of the variants with a
+    workspace / a saved intermediate), rooflines, counter traffic, dense comparator."""
+    import numpy as np
+    import torch
+    from paper_2204_00595_amd import binding
+
+    ly = layer or Layer(name)
+    sh, code, dev, dt = ly.sh, ly.code, torch.device("cuda:0"), ly.dt
+    nsets, sets, Rd, Ld, dR, dL, ws, fws, fneed = ly.nsets, ly.sets, ly.R, ly.L, ly.dR, ly.dL, ly.ws, ly.fws, ly.fneed
+    small = sh.fwd_bytes() < (8 << 20)
+    if small:
+        calls = max(calls, 500)  # microsecond calls: longer runs
+    fwd_med, fwd_min, fwd_mean, ncalls = timed_runs(ly.fwd, calls)
+    bwd_med, bwd_min, bwd_mean, _ = timed_runs(ly.bwd, calls)
+    # the same calls on one buffer set ("warm": repeats can be served by the 256 MB Infinity Cache)
+    fwd_warm = timed_runs(lambda i: ly.fwd(0), calls // 2)[0]
+    bwd_warm = timed_runs(lambda i: ly.bwd(0), calls // 2)[0]
+
+    def fwd_ws_only(i):
+        xs, _, y, _ = sets[i % nsets]
+        binding.monarch_fwd_ws(xs, Rd, Ld, y, workspace=fws)
+
+    def fwd_ws_packed(i):
+        xs, _, y, _ = sets[i % nsets]
+        binding.monarch_fwd_ws(xs, Rd, Ld, y, workspace=fws, flags=binding.MONARCH_FLAG_WS_PACKED)
+
+    fwd_ws_ms = timed_runs(fwd_ws_only, calls // 2)[0] if fneed else None
+    fwd_ws_packed_ms = timed_runs(fwd_ws_packed, calls // 2)[0] if fneed else None
+
+    # forward that saves the vector between the factors + backward that reads it instead of recomputing
+    sneed = binding.monarch_saved_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, code, 0)
+    fwd_save_ms = bwd_saved_ms = None
+    if sneed:
+        svs = [torch.empty(sneed, dtype=torch.uint8, device=dev) for _ in range(nsets)]
+
+        def fwd_save_only(i):
+            xs, _, y, _ = sets[i % nsets]
+            binding.monarch_fwd_save(xs, Rd, Ld, y, svs[i % nsets])
+
+        def bwd_saved_only(i):
+            xs, dys, _, dx = sets[i % nsets]
+            binding.monarch_bwd_saved(dys, xs, svs[i % nsets], Rd, Ld, dx, dR, dL, workspace=ws)
+
+        fwd_save_ms = timed_runs(fwd_save_only, calls // 2)[0]
+        bwd_saved_ms = timed_runs(bwd_saved_only, calls // 2)[0]
+        del svs
+
+    out = {
+        "workload": name, "shape": "k=%d p=%d q=%d s=%d (%d->%d), B=%d, %s" % (sh.k, sh.p, sh.q, sh.s, sh.n_in, sh.n_out, sh.B, sh.dtype),
+        "timed_calls": ncalls, "statistic": "median / min over %d runs of %d consecutive calls (time per call of a run)" % (RUNS, ncalls // RUNS),
+        "fwd_us": fwd_med * 1e3, "fwd_us_min": fwd_min * 1e3, "bwd_us": bwd_med * 1e3, "bwd_us_min": bwd_min * 1e3,
+        "fwd_us_warm": fwd_warm * 1e3, "bwd_us_warm": bwd_warm * 1e3,  # one buffer set instead of the rotation: cache-assisted
+        "fwd_kernel": binding.monarch_kernel_name(0, sh.n_in, sh.k, sh.q, sh.s, code),
+        "bwd_kernel": binding.monarch_kernel_name(1, sh.n_in, sh.k, sh.q, sh.s, code),
+        # monarch_fwd_ws (weights packed into a caller workspace, pack included / pack skipped); null without such a kernel
+        "fwd_ws_us": fwd_ws_ms and fwd_ws_ms * 1e3, "fwd_ws_packed_us": fwd_ws_packed_ms and fwd_ws_packed_ms * 1e3,
+        "fwd_ws_kernel": binding.monarch_kernel_name(2, sh.n_in, sh.k, sh.q, sh.s, code),
+        # monarch_fwd_save / monarch_bwd_saved (the intermediate goes through HBM once instead of being recomputed)
+        "fwd_save_us": fwd_save_ms and fwd_save_ms * 1e3, "bwd_saved_us": bwd_saved_ms and bwd_saved_ms * 1e3,
+        "fwd_tflops": sh.fwd_flops() / (fwd_med * 1e-3) / 1e12, "bwd_tflops": sh.bwd_flops() / (bwd_med * 1e-3) / 1e12,
+        "fwd_gbs": sh.fwd_bytes() / (fwd_med * 1e-3) / 1e9, "bwd_gbs": sh.bwd_bytes() / (bwd_med * 1e-3) / 1e9,
+        "fwd_algorithmic_bytes": sh.fwd_bytes(), "bwd_algorithmic_bytes": sh.bwd_bytes(),
+        "rotating_sets": nsets,
+    }
+    for ps, ms in (("fwd", fwd_med), ("bwd", bwd_med)):
+        frac, bound = roofline_of(sh, ps, ms)
+        out[ps + "_roofline_frac"] = frac
+        out[ps + "_bound"] = bound
+        if copy_gbs:
+            # the same fraction with the measured copy rate in place of the nominal 8 TB/s
+            out[ps + "_frac_of_copy_roof"] = out[ps + "_gbs"] / copy_gbs if bound == "hbm" else None
+        t = traffic_of(name, "monarch_" + ps)
+        out[ps + "_traffic_bytes"] = t  # rocprofv3 FETCH_SIZE + WRITE_SIZE per call (profiles/), null if not profiled
+        out[ps + "_traffic_ratio"] = (t / out[ps + "_algorithmic_bytes"]) if t else None
+    if small:
+        out["note"] = "launch-latency bound: %d KB and %.1f MFLOP per forward; see launch_floor_us" % (sh.fwd_bytes() // 1000, sh.fwd_flops() / 1e6)
+
+    if with_dense:
+        # vendor dense GEMM of the same (B, n_in, n_out): 1 GEMM forward, 2 GEMMs backward
+        W = torch.randn(sh.n_out, sh.n_in, device=dev, dtype=dt)
+
+        def dense_fwd(i):
+            sets[i % nsets][0] @ W.t()
+
+        def dense_bwd(i):
+            xs, dys, _, _ = sets[i % nsets]
+            dys @ W
+            dys.t() @ xs
+
+        out["dense_fwd_us"] = timed_runs(dense_fwd, calls // 2)[0] * 1e3
+        out["dense_bwd_us"] = timed_runs(dense_bwd, calls // 2)[0] * 1e3
+        out["speedup_vs_dense"] = (out["dense_fwd_us"] + out["dense_bwd_us"]) / (out["fwd_us"] + out["bwd_us"])
+        # The multiply as the paper runs it (Section 3.3): two framework batched matmuls with the reshapes and
+        # transposes between them as separate passes, the intermediate in HBM.  Context for what the fusion buys.
+        k, p, q, s_ = sh.k, sh.p, sh.q, sh.s
+        Rt = torch.randn(k, q, p, device=dev, dtype=dt)
+        Lt = torch.randn(k, s_, q, device=dev, dtype=dt)
+
+        def unfused_fwd(i):
+            xs = sets[i % nsets][0]
+            y1 = torch.bmm(xs.view(-1, k, p).transpose(0, 1), Rt.transpose(1, 2))        # (k, B, q)
+            u = y1.permute(1, 2, 0).reshape(-1, k, q).transpose(0, 1)                      # (q, k) grid, k chunks of q
+            w = torch.bmm(u, Lt.transpose(1, 2))                                           # (k, B, s)
+            return w.permute(1, 2, 0).reshape(-1, s_ * k)                                  # y[b, l*k + c]
+
+        out["unfused_bmm_fwd_us"] = timed_runs(unfused_fwd, max(20, calls // 5))[0] * 1e3
+
+    if with_extras:
+        out["extras"] = measure_extras(ly, calls // 2)
+    return out
+
+
+def measure_extras(ly: Layer, calls: int):
+    """Per-call times of the other entry points on the workload's shape (ms): affine layer, transposed multiply,
+    dense form, and for square shapes the complex multiply and the projection."""
+    import torch
+    from paper_2204_00595_amd import binding, synth
+    sh, code, dev, dt = ly.sh, ly.code, torch.device("cuda:0"), ly.dt
+    nsets, sets, Rd, Ld, dR, dL, ws, fws, fneed = ly.nsets, ly.sets, ly.R, ly.L, ly.dR, ly.dL, ly.ws, ly.fws, ly.fneed
+    ex = {}
+    biasd = torch.from_numpy(synth.quantize(synth.normal(4242, (sh.n_out,)), sh.dtype)).to(dev).to(dt)
+    dbias = torch.empty_like(biasd)
+
+    def fwd_bias_only(i):
+        xs, _, y, _ = sets[i % nsets]
+        binding.monarch_fwd_bias(xs, Rd, Ld, biasd, y, workspace=fws if fneed else None)
+
+    def fwd_then_add(i):
+        xs, _, y, _ = sets[i % nsets]
+        if fneed:
+            binding.monarch_fwd_ws(xs, Rd, Ld, y, workspace=fws)
+        else:
+            binding.monarch_fwd(xs, Rd, Ld, y)
+        y.add_(biasd)
+
+    def bwd_bias_only(i):
+        xs, dys, _, dx = sets[i % nsets]
+        binding.monarch_bwd_bias(dys, xs, Rd, Ld, dx, dR, dL, dbias, workspace=ws)
+
+    ex["fwd_bias_ms"] = timed_runs(fwd_bias_only, calls)[0]
+    ex["fwd_then_add_ms"] = timed_runs(fwd_then_add, calls)[0]   # forward with workspace + a separate framework add
+    ex["bwd_bias_ms"] = timed_runs(bwd_bias_only, calls)[0]
+    tneed = binding.monarch_fwd_t_workspace_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, code, 0)
+    tws = torch.empty(max(tneed, 256), dtype=torch.uint8, device=dev)
+
+    def fwd_t_only(i):
+        _, dys, _, dx = sets[i % nsets]
+        binding.monarch_fwd_t(dys, Rd, Ld, dx, workspace=tws if tneed else None)
+
+    ex["fwd_t_ms"] = timed_runs(fwd_t_only, calls)[0]
+    ex["fwd_t_kernel"] = binding.monarch_kernel_name(3, sh.n_in, sh.k, sh.q, sh.s, code)
+    Mdense = torch.empty((sh.n_out, sh.n_in), dtype=Rd.dtype, device="cuda")
+    ex["to_dense_ms"] = timed_runs(lambda i: binding.monarch_to_dense(Rd, Ld, Mdense), calls)[0]
+    dense_bytes = (sh.k * sh.q * sh.p + sh.k * sh.s * sh.q + sh.n_out * sh.n_in) * sh.esize
+    ex["to_dense_gbs"] = dense_bytes / (ex["to_dense_ms"] * 1e-3) / 1e9
+    if sh.k == sh.p == sh.q == sh.s:
+        # complex64 multiply with the DFT factors on the first rows of the batch
+        crow = min(sh.B, 2048)
+        cx = torch.randn((crow, sh.n_in), dtype=torch.complex64, device=dev, generator=torch.Generator(device=dev).manual_seed(7))
+        cR, cL = binding.monarch_dft_factors(sh.k, False, device=dev)
+        cy = torch.empty_like(cx)
+        ex["c64_fwd_ms"] = timed_runs(lambda i: binding.monarch_fwd_c64(cx, cR, cL, cy), 20, 2)[0]
+        ex["c64_bwd_ms"] = timed_runs(lambda i: binding.monarch_bwd_c64(cy, cx, cR, cL), 20, 2)[0]
+        ex["c64_rows"] = crow
+        # Algorithm 1 on a dense Gaussian n x n matrix: one Jacobi SVD per slice
+        Adense = torch.from_numpy(synth.quantize(synth.normal(4343, (sh.n_in, sh.n_in)), sh.dtype)).to(dev).to(dt)
+        Rp, Lp = torch.empty_like(Rd), torch.empty_like(Ld)
+        ex["project_ms"] = timed_runs(lambda i: binding.monarch_project(Adense, Rp, Lp), 20, 2)[0]
+    return ex
+
+
+class Pair:
+    """The MLP pair: fc1 and fc2 chained through the hidden activation, with rotating buffer sets."""
+
+    def __init__(self):
+        import torch
+        from paper_2204_00595_amd import binding, synth
+        s1, s2 = synth.WORKLOADS["gpt2m_fc1"], synth.WORKLOADS["gpt2m_fc2"]
+        self.s1, self.s2 = s1, s2
+        dev, dt = torch.device("cuda:0"), torch.bfloat16
+        B = s1.B
+        g = _gen_rows(B)
+        x, R1, L1, _ = synth.make_inputs(s1, rows=g)
+        _, R2, L2, dy = synth.make_inputs(s2, rows=g)
+        self.R1, self.L1, self.R2, self.L2 = (torch.from_numpy(a).to(dev).to(dt) for a in (R1, L1, R2, L2))
+        x0, dy0 = (torch.from_numpy(a).to(dev).to(dt).repeat(B // g, 1) for a in (x, dy))
+        per_set = 2 * B * (3 * s1.n_in + 2 * s1.n_out + 0) + 2 * B * s2.n_out
+        self.nsets = max(2, -(-ROTATE_BYTES // per_set))
+        self.sets = []
+        for i in range(self.nsets):
+            xs = x0 if i == 0 else x0.roll(i, 0).contiguous()
+            dys = dy0 if i == 0 else dy0.roll(i, 0).contiguous()
+            h = torch.empty((B, s1.n_out), dtype=dt, device=dev)
+            self.sets.append((xs, dys, h, torch.empty((B, s2.n_out), dtype=dt, device=dev), torch.empty_like(h), torch.empty_like(xs)))
+        self.g = [torch.empty_like(t) for t in (self.R1, self.L1, self.R2, self.L2)]
+        need = max(binding.monarch_bwd_workspace_bytes(B, s.n_in, s.k, s.q, s.s, 1, 0) for s in (s1, s2))
+        self.ws = torch.empty(need, dtype=torch.uint8, device=dev)
+
+    def flops(self):
+        return sum(s.fwd_flops() + s.bwd_flops() for s in (self.s1, self.s2))
+
+    def nbytes(self):
+        return sum(s.fwd_bytes() + s.bwd_bytes() for s in (self.s1, self.s2))
+
+    def calls(self, i):
+        """The four calls of step i as (label, shape, pass, thunk)."""
+        from paper_2204_00595_amd import binding
+        xs, dys, h, y, dh, dx = self.sets[i % self.nsets]
+        dR1, dL1, dR2, dL2 = self.g
+        return (
+            ("fwd_fc1", self.s1, "fwd", lambda: binding.monarch_fwd(xs, self.R1, self.L1, h)),
+            ("fwd_fc2", self.s2, "fwd", lambda: binding.monarch_fwd(h, self.R2, self.L2, y)),
+            ("bwd_fc2", self.s2, "bwd", lambda: binding.monarch_bwd(dys, h, self.R2, self.L2, dh, dR2, dL2, workspace=self.ws)),
+            ("bwd_fc1", self.s1, "bwd", lambda: binding.monarch_bwd(dh, xs, self.R1, self.L1, dx, dR1, dL1, workspace=self.ws)),
+        )
+
+    def step(self, i):
+        for _, _, _, fn in self.calls(i):
+            fn()
+
+
+def cpu_baseline(workload: str, cpu_seconds: float = 20.0):
+    """The CPU oracle as it stands, timed on this host: the same step (for the pair: both layers, forward and
+    backward, chained in fp64) over the first rows of the workload, sized to about `cpu_seconds` core-seconds."""
     import oracle
     from paper_2204_00595_amd import synth
 
-    sh = synth.WORKLOADS[name]
     cores = oracle.num_threads()
-    rows = min(sh.B, 2048)
-    x, R, L, dy = synth.make_inputs(sh, rows=rows)
+    if workload == PAIR:
+        shapes = [synth.WORKLOADS["gpt2m_fc1"], synth.WORKLOADS["gpt2m_fc2"]]
+    else:
+        shapes = [synth.workload(workload)]
+    Bfull = shapes[0].B
+
+    def make(rows):
+        ins = [synth.make_inputs(s, rows=rows) for s in shapes]
+        return ins
+
+    def run(ins):
+        if len(ins) == 1:
+            x, R, L, dy = ins[0]
+            oracle.fwd(x, R, L)
+            oracle.bwd(dy, x, R, L)
+        else:
+            (x, R1, L1, _), (_, R2, L2, dy) = ins
+            h = oracle.fwd(x, R1, L1)
+            oracle.fwd(h, R2, L2)
+            dh = oracle.bwd(dy, h, R2, L2)[0]
+            oracle.bwd(dh, x, R1, L1)
+
+    rows = min(Bfull, 256 if workload == PAIR else 2048)
+    ins = make(rows)
     t0 = time.perf_counter()
-    oracle.fwd(x, R, L)
-    oracle.bwd(dy, x, R, L)
+    run(ins)
     probe = time.perf_counter() - t0
     wall_budget = cpu_seconds / max(cores, 1)
-    rows2 = max(rows, min(sh.B, min(65536, int(rows * wall_budget / max(probe, 1e-4)))))
+    rows2 = max(rows, min(Bfull, min(65536, int(rows * wall_budget / max(probe, 1e-4)))))
     if rows2 != rows:
-        x, R, L, dy = synth.make_inputs(sh, rows=rows2)
+        ins = make(rows2)
     reps, dt_s = 0, 0.0
     while reps == 0 or (dt_s < wall_budget and reps < 200):
         t0 = time.perf_counter()
-        oracle.fwd(x, R, L)
-        oracle.bwd(dy, x, R, L)
+        run(ins)
         dt_s += time.perf_counter() - t0
         reps += 1
-    flops = (sh.fwd_flops() + sh.bwd_flops()) * rows2 / sh.B * reps
+    flops = sum(s.fwd_flops() + s.bwd_flops() for s in shapes) * rows2 / Bfull * reps
     return {"value": flops / dt_s / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": "fwd+bwd of the first %d of %d rows of %s, fp64, %d repetition(s), %.2f s wall on %d threads"
-                      % (rows2, sh.B, name, reps, dt_s, cores)}
+            "sample": "fwd+bwd (%s) of the first %d of %d rows of %s, fp64, %d repetition(s), %.2f s wall on %d threads"
+                      % ("both layers chained" if len(shapes) == 2 else "one layer", rows2, Bfull, workload, reps, dt_s, cores)}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="vitb_proj")
-    ap.add_argument("--all", action="store_true", help="also time the other workloads (extra keys)")
+    ap.add_argument("--workload", default=PAIR, help="the step: %s (default) or one of %s" % (PAIR, ", ".join(CONFIGS)))
+    ap.add_argument("--only", action="store_true", help="measure the step's workload only, not every configuration")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--extras", action="store_true", help="also time the other entry points (bias, transposed, dense form, complex, projection)")
     ap.add_argument("--layers", action="store_true", help="also time the other layer shapes of the same models (extra keys)")
-    ap.add_argument("--no-extras", action="store_true", help="skip the timings of monarch_to_dense and of the bias calls")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.stderr.write("bench.py: this library runs on ONE GPU; --gpus N with N > 1 is not supported "
                          "(a multi-GPU run would shard the batch rows and all-reduce dR, dL; nothing of that is built).\n")
         sys.exit(2)
+    import numpy as np
     import torch
-    from paper_2204_00595_amd import binding
+    from paper_2204_00595_amd import binding, synth
     if not torch.cuda.is_available():
         sys.stderr.write("bench.py needs a GPU\n")
         sys.exit(2)
     binding.lib()
+    copy_gbs = copy_roof()
+    detail = {}
 
-    sh, r = run_workload(args.workload, args.steps, args.warmup, with_dense=not args.no_dense, with_extras=not args.no_extras)
-    flops = sh.fwd_flops() + sh.bwd_flops()
-    nbytes = sh.fwd_bytes() + sh.bwd_bytes()
-    step_s = r["ms_per_step"] * 1e-3
-    # roofline of the dominant call (the one with the larger duration)
-    dom = "bwd" if r["bwd_ms"] >= r["fwd_ms"] else "fwd"
-    dom_bytes = sh.bwd_bytes() if dom == "bwd" else sh.fwd_bytes()
-    dom_flops = sh.bwd_flops() if dom == "bwd" else sh.fwd_flops()
-    dom_ms = r[dom + "_ms"]
-    if r[dom + "_bound"] == "hbm":
-        roof = {"bound": "hbm", "achieved": dom_bytes / (dom_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    if args.workload == PAIR:
+        job = Pair()
+        step, flops, nbytes, dtype = job.step, job.flops(), job.nbytes(), "bf16"
+        s1, s2 = job.s1, job.s2
+        wl_text = ("%s: MLP pair 1024->4096->1024 (fc1 k=4 p=q=256 s=1024; fc2 k=4 p=1024 q=s=256), B=%d rows, bf16, "
+                   "fwd fc1 + fwd fc2 + bwd fc2 + bwd fc1, no nonlinearity between the multiplies" % (PAIR, s1.B))
     else:
-        roof = {"bound": "mfma", "achieved": dom_flops / (dom_ms * 1e-3) / 1e12,
-                "peak": MFMA_PEAK_TFLOPS[sh.dtype], "unit": "TFLOP/s"}
+        job = Layer(args.workload)
+        step, sh = job.step, job.sh
+        flops, nbytes, dtype = sh.fwd_flops() + sh.bwd_flops(), sh.fwd_bytes() + sh.bwd_bytes(), sh.dtype
+        wl_text = "%s: k=%d p=%d q=%d s=%d (%d->%d), B=%d rows, fwd+bwd" % (sh.name, sh.k, sh.p, sh.q, sh.s, sh.n_in, sh.n_out, sh.B)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+
+    # per-call durations of the step's calls: runs of consecutive calls of one entry point between two events
+    if args.workload == PAIR:
+        # the hidden activation and its gradient must exist before the backward calls are timed alone
+        for i in range(job.nsets):
+            job.step(i)
+        per_call = {}
+        for idx in range(4):
+            label, shp, ps, _ = job.calls(0)[idx]
+            med, mn, _, n = timed_runs(lambda i, idx=idx: job.calls(i)[idx][3](), TIMED_CALLS)
+            frac, bound = roofline_of(shp, ps, med)
+            per_call[label] = {"us": med * 1e3, "us_min": mn * 1e3, "timed_calls": n, "roofline_frac": frac, "bound": bound,
+                               "workload": shp.name, "pass": ps,
+                               "flops": shp.fwd_flops() if ps == "fwd" else shp.bwd_flops(),
+                               "bytes": shp.fwd_bytes() if ps == "fwd" else shp.bwd_bytes()}
+        detail["step_calls"] = per_call
+        dom_label = max(per_call, key=lambda k_: per_call[k_]["us"])
+        dom = per_call[dom_label]
+        dom_sh, dom_ps = (s2 if dom["workload"] == "gpt2m_fc2" else s1), dom["pass"]
+    else:
+        fmed, fmin, _, n = timed_runs(job.fwd, TIMED_CALLS)
+        bmed, bmin, _, _ = timed_runs(job.bwd, TIMED_CALLS)
+        per_call = {}
+        for label, ps, med, mn in (("fwd", "fwd", fmed, fmin), ("bwd", "bwd", bmed, bmin)):
+            frac, bound = roofline_of(sh, ps, med)
+            per_call[label] = {"us": med * 1e3, "us_min": mn * 1e3, "timed_calls": n, "roofline_frac": frac, "bound": bound,
+                               "workload": sh.name, "pass": ps,
+                               "flops": sh.fwd_flops() if ps == "fwd" else sh.bwd_flops(),
+                               "bytes": sh.fwd_bytes() if ps == "fwd" else sh.bwd_bytes()}
+        detail["step_calls"] = per_call
+        dom_label = max(per_call, key=lambda k_: per_call[k_]["us"])
+        dom = per_call[dom_label]
+        dom_sh, dom_ps = sh, dom["pass"]
+
+    # roofline of the dominant call (the one with the largest duration)
+    dom_ms = dom["us"] * 1e-3
+    if dom["bound"] == "hbm":
+        roof = {"bound": "hbm", "achieved": dom["bytes"] / (dom_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": dom["flops"] / (dom_ms * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS[dom_sh.dtype], "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    # HBM bytes per call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (calibrated on the copy
-    # kernel) by the committed profile of this workload; null when no such profile has been taken
-    roof["traffic"] = None
-    if os.path.exists(TRAFFIC_JSON):
-        t = json.load(open(TRAFFIC_JSON)).get(args.workload, {}).get("monarch_" + dom)
-        if t:
-            roof["traffic"] = t["fetch_bytes"] + t["write_bytes"]
-            roof["traffic_unit"] = "bytes per call"
-            roof["algorithmic_bytes"] = dom_bytes
-    roof["kernel"] = r[dom + "_kernel"]
-    roof["call"] = "monarch_" + dom
+    # HBM bytes per call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (calibrated on the copy kernel)
+    # by the committed profile of this workload; null when no such profile has been taken
+    roof["traffic"] = traffic_of(dom_sh.name, "monarch_" + dom_ps)
+    roof["traffic_unit"] = "bytes per call"
+    roof["algorithmic_bytes"] = dom["bytes"]
+    roof["algorithmic_flops"] = dom["flops"]
+    code = 0 if dom_sh.dtype == "f32" else 1
+    roof["kernel"] = binding.monarch_kernel_name(0 if dom_ps == "fwd" else 1, dom_sh.n_in, dom_sh.k, dom_sh.q, dom_sh.s, code)
+    roof["call"] = "monarch_%s on %s" % (dom_ps, dom_sh.name)
     roof["avg_ms"] = dom_ms
+    roof["frac_of_copy_roof"] = (roof["achieved"] / copy_gbs) if roof["bound"] == "hbm" else None
+    del job
+    torch.cuda.empty_cache()
+
+    floor = launch_floor()
+    detail["launch_floor_us"] = floor
+    names = [args.workload] if (args.only and args.workload != PAIR) else ([] if args.only else list(CONFIGS))
+    configs = {}
+    for name in names:
+        configs[name] = measure_layer(name, with_dense=not args.no_dense, with_extras=args.extras, copy_gbs=copy_gbs)
+        if name == "sq256_f32":
+            configs[name]["launch_floor_us"] = floor["median_us"]
+        torch.cuda.empty_cache()
+    detail["configs"] = configs
+    if args.layers:
+        detail["model_layers"] = {}
+        for name in synth.MODEL_LAYERS:
+            detail["model_layers"][name] = measure_layer(name, with_dense=not args.no_dense, with_extras=args.extras, copy_gbs=copy_gbs)
+            torch.cuda.empty_cache()
+
+    step_s = ms_per_step * 1e-3
     line = {
         "metric": "monarch_fwd_bwd_tflops", "value": flops / step_s / 1e12, "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": sh.dtype, "data": "synthetic",
-        "config": {"workload": "%s: k=%d p=%d q=%d s=%d (%d->%d), B=%d rows, fwd+bwd" % (
-            sh.name, sh.k, sh.p, sh.q, sh.s, sh.n_in, sh.n_out, sh.B)},
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": wl_text},
         "gb_per_s": nbytes / step_s / 1e9,
         "roofline": roof,
-        "detail": r,
+        "hbm_copy_gbs": copy_gbs,
+        "detail": detail,
     }
-    if r.get("step_saved_ms"):
-        # the same step through monarch_fwd_save + monarch_bwd_saved (intermediate kept in HBM, not recomputed);
-        # same FLOP count as the headline (the recompute is not counted there either)
-        line["step_with_saved_intermediate"] = {"ms_per_step": r["step_saved_ms"],
-                                                "value": flops / (r["step_saved_ms"] * 1e-3) / 1e12, "unit": "TFLOP/s"}
-    line["hbm_copy_gbs"] = copy_roof()
-    roof["frac_of_copy_roof"] = (roof["achieved"] / line["hbm_copy_gbs"]) if roof["bound"] == "hbm" else None
     if not args.no_dense:
         # empirical matrix-core roof (vendor GEMM, n = 8192) and the step's share of it
         line["dense_gemm_roof_tflops"] = mfma_roof()
-        line["frac_of_dense_gemm_roof"] = line["value"] / line["dense_gemm_roof_tflops"][sh.dtype]
-    if args.all:
-        others = {}
-        for name in ("sq256_f32", "sq256_f32_big", "gpt2s_fc1", "sq4096", "gpt2m_fc1", "gpt2m_fc2"):
-            if name != args.workload:
-                others[name] = run_workload(name, max(5, args.steps // 2), max(2, args.warmup // 2),
-                                            with_dense=not args.no_dense, with_extras=not args.no_extras)[1]
-        line["other_workloads"] = others
-    if args.layers:
-        from paper_2204_00595_amd import synth as _synth
-        line["model_layers"] = {name: run_workload(name, max(5, args.steps // 2), max(2, args.warmup // 2),
-                                                   with_dense=not args.no_dense, with_extras=not args.no_extras)[1]
-                                for name in _synth.MODEL_LAYERS}
+        line["frac_of_dense_gemm_roof"] = line["value"] / line["dense_gemm_roof_tflops"][dtype]
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(line), flush=True)

@@ -277,6 +277,13 @@ const char* monarch_kernel_name(int pass, int n_in, int k, int q, int s,
  * Returns MONARCH_ERR_INVALID otherwise; nbytes == 0 is a successful no-op. */
 int monarch_stream_copy(void* dst, const void* src, size_t nbytes, void* stream);
 
+/* Measurement aid, not part of the method: enqueues one empty kernel (one wavefront, no
+ * arguments, no memory access) on `stream`.  The time per launch of a run of these is the
+ * floor under any call on that stream; the n = 256, 64-row workload (Definition 3.1 with
+ * m = 16), whose ideal time is tens of nanoseconds, is reported next to it.
+ * Returns MONARCH_OK or MONARCH_ERR_HIP. */
+int monarch_launch_probe(void* stream);
+
 /* Human-readable text for a status code.  Static string, never NULL. */
 const char* monarch_status_string(int status);
 

@@ -32,7 +32,7 @@ EXPORTS = (
     "monarch_fwd", "monarch_fwd_ex", "monarch_fwd_ws", "monarch_fwd_bias", "monarch_fwd_workspace_bytes", "monarch_bwd",
     "monarch_bwd_bias",
     "monarch_bwd_workspace_bytes",
-    "monarch_fwd_t", "monarch_fwd_t_workspace_bytes", "monarch_saved_bytes", "monarch_fwd_save", "monarch_bwd_saved", "monarch_fwd_c64", "monarch_bwd_c64", "monarch_dft_factors", "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy",
+    "monarch_fwd_t", "monarch_fwd_t_workspace_bytes", "monarch_saved_bytes", "monarch_fwd_save", "monarch_bwd_saved", "monarch_fwd_c64", "monarch_bwd_c64", "monarch_dft_factors", "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy", "monarch_launch_probe",
 )
 
 _lib = None
@@ -98,6 +98,8 @@ def lib() -> ctypes.CDLL:
         L.monarch_version.argtypes = []
         L.monarch_stream_copy.restype = ci
         L.monarch_stream_copy.argtypes = [vp, vp, sz, vp]
+        L.monarch_launch_probe.restype = ci
+        L.monarch_launch_probe.argtypes = [vp]
         _lib = L
     return _lib
 
@@ -121,6 +123,16 @@ def _check(t: torch.Tensor, name: str, shape, dtype, device):
         raise ValueError("%s must be contiguous" % name)
 
 
+def _scratch(nbytes: int, dev, stream) -> torch.Tensor:
+    """A temporary buffer for kernels that run on `stream`.  It is allocated with `stream` current, so the
+    caching allocator hands its block, once released, only to later work of that same stream: a buffer
+    released on return while the kernels are still running cannot be given to another stream."""
+    if stream is None:
+        return torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    with torch.cuda.stream(stream):
+        return torch.empty(nbytes, dtype=torch.uint8, device=dev)
+
+
 def _stream_ptr(stream) -> int:
     st = torch.cuda.current_stream() if stream is None else stream
     return int(st.cuda_stream)
@@ -138,6 +150,13 @@ def monarch_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> to
     if rc != MONARCH_OK:
         raise MonarchError(rc, "monarch_stream_copy")
     return dst
+
+
+def monarch_launch_probe(stream=None) -> None:
+    """Enqueue one empty kernel on the stream (the launch floor of the machine, for the benchmark)."""
+    rc = lib().monarch_launch_probe(_stream_ptr(stream))
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_launch_probe")
 
 
 def monarch_version() -> int:
@@ -177,7 +196,7 @@ def monarch_fwd_ws(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.T
     if workspace is None and need:
         if flags & MONARCH_FLAG_WS_PACKED:
             raise ValueError("MONARCH_FLAG_WS_PACKED needs the workspace of the earlier call")
-        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+        workspace = _scratch(need, dev, stream)
     ws_ptr = workspace.data_ptr() if workspace is not None else 0
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
     with torch.cuda.device(dev):
@@ -256,7 +275,7 @@ def monarch_bwd(dy: torch.Tensor, x: torch.Tensor, R: torch.Tensor, L: torch.Ten
     _check(dL, "dL", (k, s, q), gdt, dev)
     need = monarch_bwd_workspace_bytes(B, k * p, k, q, s, _dtype_code(x), flags)
     if workspace is None and need:
-        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+        workspace = _scratch(need, dev, stream)
     ws_ptr = workspace.data_ptr() if workspace is not None else 0
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
     with torch.cuda.device(dev):
@@ -287,7 +306,7 @@ def monarch_fwd_bias(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, bias: to
     if workspace is None and need:
         if flags & MONARCH_FLAG_WS_PACKED:
             raise ValueError("MONARCH_FLAG_WS_PACKED needs the workspace of the earlier call")
-        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+        workspace = _scratch(need, dev, stream)
     ws_ptr = workspace.data_ptr() if workspace is not None else 0
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
     with torch.cuda.device(dev):
@@ -326,7 +345,7 @@ def monarch_bwd_bias(dy: torch.Tensor, x: torch.Tensor, R: torch.Tensor, L: torc
     _check(dbias, "dbias", (k * s,), gdt, dev)
     need = monarch_bwd_workspace_bytes(B, k * p, k, q, s, _dtype_code(x), flags)
     if workspace is None and need:
-        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+        workspace = _scratch(need, dev, stream)
     ws_ptr = workspace.data_ptr() if workspace is not None else 0
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
     with torch.cuda.device(dev):
@@ -378,7 +397,7 @@ def monarch_fwd_t(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.Te
     _check(y, "y", (B, k * p), dt, dev)
     need = monarch_fwd_t_workspace_bytes(B, k * p, k, q, s, _dtype_code(x), flags)
     if workspace is None and need:
-        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+        workspace = _scratch(need, dev, stream)
     ws_ptr = workspace.data_ptr() if workspace is not None else 0
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
     with torch.cuda.device(dev):
@@ -449,7 +468,7 @@ def monarch_bwd_saved(dy: torch.Tensor, x: torch.Tensor, saved: torch.Tensor | N
         _check(dbias, "dbias", (k * s,), gdt, dev)
     need = monarch_bwd_workspace_bytes(B, k * p, k, q, s, _dtype_code(x), flags)
     if workspace is None and need:
-        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+        workspace = _scratch(need, dev, stream)
     ws_ptr = workspace.data_ptr() if workspace is not None else 0
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
     sv_ptr = saved.data_ptr() if saved is not None else 0

@@ -3,7 +3,39 @@
 #include "../../include/monarch.h"
 #include "monarch_internal.h"
 
+#include <mutex>
+#include <vector>
+
 using namespace monarch;
+
+namespace monarch {
+
+hipError_t allow_dynamic_lds(const void* kernel, size_t bytes)
+{
+    struct Slot {
+        const void* kernel;
+        int device;
+        size_t bytes;
+    };
+    static std::mutex mu;
+    static std::vector<Slot> table;  // a few dozen kernels: a linear scan is cheaper than the runtime call it saves
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> guard(mu);
+    for (Slot& s : table) {
+        if (s.kernel != kernel || s.device != device) continue;
+        if (s.bytes >= bytes) return hipSuccess;
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e == hipSuccess) s.bytes = bytes;
+        return e;
+    }
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) table.push_back(Slot{kernel, device, bytes});
+    return e;
+}
+
+}  // namespace monarch
 
 namespace {
 
@@ -58,6 +90,8 @@ size_t bwd_need(const Problem& pb, Family fam)
 }
 
 bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+__global__ void empty_kernel() {}
 
 }  // namespace
 
@@ -346,6 +380,12 @@ int monarch_stream_copy(void* dst, const void* src, size_t nbytes, void* stream)
     const char* s = (const char*)src;
     if (d < s + nbytes && s < d + nbytes) return MONARCH_ERR_INVALID;  // overlap
     return launch_stream_copy(dst, src, nbytes, (hipStream_t)stream);
+}
+
+int monarch_launch_probe(void* stream)
+{
+    hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream);
+    return hip_status(hipGetLastError());
 }
 
 const char* monarch_status_string(int status)

@@ -231,7 +231,7 @@ int launch_cfwd(const Problem& pb, const void* x, const void* R, const void* L, 
 {
     const size_t lds = (size_t)BM * fwd_bytes_per_row(pb);
     auto kern = complex_fwd_kernel<BM>;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return -4;
+    if (allow_dynamic_lds((const void*)kern, lds) != hipSuccess) return -4;
     const int64_t grid = (pb.B + BM - 1) / BM;
     if (grid > 0x7fffffffLL) return -2;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kCThreads), lds, st, (const float2*)x, (const float2*)R,
@@ -245,7 +245,7 @@ int launch_cbwd(const Problem& pb, const void* dy, const void* x, const void* R,
 {
     const size_t lds = (size_t)BM * bwd_bytes_per_row(pb);
     auto kern = complex_bwd_kernel<BM>;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return -4;
+    if (allow_dynamic_lds((const void*)kern, lds) != hipSuccess) return -4;
     const int64_t grid = (pb.B + BM - 1) / BM;
     if (grid > 0x7fffffffLL) return -2;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kCThreads), lds, st, (const float2*)dy, (const float2*)x,

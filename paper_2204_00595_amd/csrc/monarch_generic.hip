@@ -473,7 +473,7 @@ static int launch_fwd_t(const Problem& pb, const void* x, const void* R, const v
 {
     const size_t lds = (size_t)BM * fwd_t_floats_per_row(pb) * sizeof(float);
     auto kern = generic_fwd_t_kernel<T, BM>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = allow_dynamic_lds((const void*)kern, lds);
     if (e != hipSuccess) return -4;
     const int64_t grid = (pb.B + BM - 1) / BM;
     if (grid > 0x7fffffffLL) return -2;
@@ -624,7 +624,7 @@ static int launch_fwd(const Problem& pb, const void* x, const void* R, const voi
 {
     const size_t lds = (size_t)BM * fwd_floats_per_row(pb) * sizeof(float);
     auto kern = generic_fwd_kernel<T, BM>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = allow_dynamic_lds((const void*)kern, lds);
     if (e != hipSuccess) return -4;
     const int64_t grid = (pb.B + BM - 1) / BM;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, st, (const T*)x, (const T*)R,
@@ -658,7 +658,7 @@ static int launch_bwd(const Problem& pb, const void* dy, const void* x, const vo
 {
     const size_t lds = (size_t)BM * bwd_floats_per_row(pb) * sizeof(float);
     auto kern = generic_bwd_kernel<T, BM>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = allow_dynamic_lds((const void*)kern, lds);
     if (e != hipSuccess) return -4;
     const int64_t grid = (pb.B + BM - 1) / BM;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, st, (const T*)dy, (const T*)x,

@@ -177,4 +177,10 @@ int launch_stream_copy(void* dst, const void* src, size_t nbytes, hipStream_t st
 
 static inline int hip_status(hipError_t e) { return e == hipSuccess ? 0 : -4; }
 
+// Permission for `kernel` to be launched with up to `bytes` of dynamic LDS on the current device
+// (hipFuncAttributeMaxDynamicSharedMemorySize).  The attribute belongs to the (kernel, device) pair and
+// never has to shrink, so the runtime is asked only the first time a pair needs it (or needs more);
+// later launches cost one table lookup.  Returns hipSuccess or the runtime's error.
+hipError_t allow_dynamic_lds(const void* kernel, size_t bytes);
+
 }  // namespace monarch

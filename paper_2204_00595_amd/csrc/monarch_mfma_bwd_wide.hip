@@ -368,7 +368,7 @@ int launch_data(const Problem& pb, const void* dy, const void* x, const uint16_t
 {
     // no workspace for dY1: dx only; dY1 but no Y1 workspace: the forward saved that vector
     auto kern = !dY1ws ? bwd_wide_data_kernel<C, 1> : (Y1ws ? bwd_wide_data_kernel<C, 0> : bwd_wide_data_kernel<C, 2>);
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES) != hipSuccess)
+    if (allow_dynamic_lds((const void*)kern, C::LDS_BYTES) != hipSuccess)
         return -4;
     const int64_t grid = (pb.B + C::BM - 1) / C::BM;
     if (grid > 0x7fffffffLL) return -2;

@@ -270,7 +270,7 @@ template <typename C>
 int launch(const Problem& pb, const void* x, const uint16_t* RF1, const uint16_t* LF2, void* y, hipStream_t st)
 {
     auto kern = pb.bias ? fwd_frag_kernel<C, true> : fwd_frag_kernel<C, false>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
+    hipError_t e = allow_dynamic_lds((const void*)kern, C::LDS_BYTES);
     if (e != hipSuccess) return -4;
     const int64_t grid = (pb.B + C::BM - 1) / C::BM;
     if (grid > 0x7fffffffLL) return -2;

@@ -508,7 +508,7 @@ template <typename C>
 int launch(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
 {
     auto kern = pb.saved ? fwd_wide_kernel<C, true> : fwd_wide_kernel<C, false>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
+    hipError_t e = allow_dynamic_lds((const void*)kern, C::LDS_BYTES);
     if (e != hipSuccess) return -4;
     const int64_t grid = (pb.B + C::BM - 1) / C::BM;
     if (grid > 0x7fffffffLL) return -2;

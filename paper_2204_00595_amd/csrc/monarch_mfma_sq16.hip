@@ -438,7 +438,7 @@ int fwd_t_sq16(const Problem& pb, const void* x, const void* R, const void* L, v
 {
     if (!sq16_supported(pb)) return -2;
     auto kern = fwd_t_sq16_kernel;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ16_LDS) != hipSuccess)
+    if (allow_dynamic_lds((const void*)kern, SQ16_LDS) != hipSuccess)
         return -4;
     const int64_t ntiles = (pb.B + 15) / 16;
     int64_t grid = (ntiles + SQ16_WAVES - 1) / SQ16_WAVES;
@@ -452,7 +452,7 @@ int fwd_sq16(const Problem& pb, const void* x, const void* R, const void* L, voi
 {
     if (!sq16_supported(pb)) return -2;
     auto kern = pb.bias ? fwd_sq16_kernel<true> : fwd_sq16_kernel<false>;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ16_LDS) != hipSuccess)
+    if (allow_dynamic_lds((const void*)kern, SQ16_LDS) != hipSuccess)
         return -4;
     const int64_t ntiles = (pb.B + 15) / 16;
     int64_t grid = (ntiles + SQ16_WAVES - 1) / SQ16_WAVES;
@@ -477,7 +477,7 @@ int bwd_sq16(const Problem& pb, const void* dy, const void* x, const void* R, co
         return rc ? rc : launch_fill_zero_f32((float*)dL, pb.n_L(), st);
     }
     auto kern = bwd_sq16_kernel;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ16B_LDS) != hipSuccess)
+    if (allow_dynamic_lds((const void*)kern, SQ16B_LDS) != hipSuccess)
         return -4;
     const int grid = bwd_sq16_grid(pb);
     const int64_t ntiles = (pb.B + 15) / 16;

@@ -438,7 +438,7 @@ int fwd_sq64(const Problem& pb, const void* x, const void* R, const void* L, voi
 {
     if (!sq64_supported(pb)) return -2;
     auto kern = fwd_sq64_kernel<false>;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ_LDS) != hipSuccess)
+    if (allow_dynamic_lds((const void*)kern, SQ_LDS) != hipSuccess)
         return -4;
     const int64_t grid = (pb.B + SQ_BM - 1) / SQ_BM;
     if (grid > 0x7fffffffLL) return -2;
@@ -461,7 +461,7 @@ int fwd_sq64_ws(const Problem& pb, const void* x, const void* R, const void* L, 
         if (hipGetLastError() != hipSuccess) return -4;
     }
     auto kern = fwd_sq64_kernel<true>;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ_LDS) != hipSuccess)
+    if (allow_dynamic_lds((const void*)kern, SQ_LDS) != hipSuccess)
         return -4;
     const int64_t grid = (pb.B + SQ_BM - 1) / SQ_BM;
     if (grid > 0x7fffffffLL) return -2;
@@ -491,7 +491,7 @@ int fwd_t_sq64(const Problem& pb, const void* x, const void* R, const void* L, v
     hipLaunchKernelGGL(transpose64_kernel, dim3((unsigned)pb.B), dim3(256), 0, st, (const uint16_t*)x, xT);
     if (hipGetLastError() != hipSuccess) return -4;
     auto kern = bwd_sq64_data_kernel<true>;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ_LDS) != hipSuccess)
+    if (allow_dynamic_lds((const void*)kern, SQ_LDS) != hipSuccess)
         return -4;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), SQ_LDS, st, xT, (const uint16_t*)nullptr,
                        (const uint16_t*)nullptr, LT, RT, (uint16_t*)y, (uint16_t*)nullptr, (uint16_t*)nullptr, pb.B);
@@ -526,7 +526,7 @@ int bwd_sq64(const Problem& pb, const void* dy, const void* x, const void* R, co
     hipLaunchKernelGGL(transpose64_kernel, dim3((unsigned)pb.B), dim3(256), 0, st, (const uint16_t*)dy, dWws);
     if (hipGetLastError() != hipSuccess) return -4;
     auto kern = bwd_sq64_data_kernel<false>;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SQ_LDS) != hipSuccess)
+    if (allow_dynamic_lds((const void*)kern, SQ_LDS) != hipSuccess)
         return -4;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), SQ_LDS, st, dWws, (const uint16_t*)x, Rp, LT, RT,
                        (uint16_t*)dx, Uws, dY1ws, pb.B);

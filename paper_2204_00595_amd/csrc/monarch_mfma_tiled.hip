@@ -399,7 +399,7 @@ int launch_fwd(const Problem& pb, const void* x, const void* R, const void* L, v
     const int ldu = pb.kq() + 8;
     const size_t lds = (size_t)16 * RT * ldu * 2;
     auto kern = tiled_fwd_kernel<RT, CG>;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return -4;
+    if (allow_dynamic_lds((const void*)kern, lds) != hipSuccess) return -4;
     const int64_t grid = (pb.B + 16 * RT - 1) / (16 * RT);
     if (grid > 0x7fffffffLL) return -2;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(TL_THREADS), lds, st, (const uint16_t*)x, (const uint16_t*)R,
@@ -485,7 +485,7 @@ int launch_bwd(const Problem& pb, const void* dy, const void* x, const void* R, 
     const int ld1 = bwd_ld1(pb), ldu = pb.kq() + 8;
     const size_t lds = (size_t)16 * RT * (ld1 + ldu) * 2;
     auto kern = tiled_bwd_kernel<RT, DX_ONLY>;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return -4;
+    if (allow_dynamic_lds((const void*)kern, lds) != hipSuccess) return -4;
     const int64_t grid = (pb.B + 16 * RT - 1) / (16 * RT);
     if (grid > 0x7fffffffLL) return -2;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(TL_THREADS), lds, st, (const uint16_t*)dy, (const uint16_t*)x,

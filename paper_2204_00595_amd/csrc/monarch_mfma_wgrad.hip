@@ -304,7 +304,7 @@ int launch_gemm(const WgradDesc& d0, const WgradDesc* d1, int nz, hipStream_t st
 {
     constexpr size_t lds = (size_t)2 * 4 * KB * (TM + 8 + TN + 8) * 2;  // two pipeline buffers
     auto kern = wgrad_gemm_kernel<TM, TN>;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+    if (allow_dynamic_lds((const void*)kern, lds) != hipSuccess)
         return -4;
     const int t0 = tiles_of(d0, TM, TN), t1 = d1 ? tiles_of(*d1, TM, TN) : 0;
     hipLaunchKernelGGL(kern, dim3((t0 + t1) * nz), dim3(NTHR), lds, st, d0, d1 ? *d1 : d0, t0, t0 + t1);

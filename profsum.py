@@ -1,7 +1,7 @@
 """Turns rocprofv3 CSV output into the short text summaries kept under profiles/.
 
-    python -m paper_2204_00595_amd.profsum kernels <dir with *_kernel_stats.csv>
-    python -m paper_2204_00595_amd.profsum traffic <FETCH_SIZE counter csv> <WRITE_SIZE counter csv> \
+    python profsum.py kernels <dir with *_kernel_stats.csv>
+    python profsum.py traffic <FETCH_SIZE counter csv> <WRITE_SIZE counter csv> \
         --copy-bytes N --workload NAME [--json profiles/traffic.json]
 
 `traffic` scales the FETCH_SIZE / WRITE_SIZE readings (KiB per dispatch) by what the same counter

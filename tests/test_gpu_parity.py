@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 
 import oracle
+import parity_util
 from paper_2204_00595_amd import synth
 
 torch = pytest.importorskip("torch")
@@ -82,10 +83,12 @@ def run_bwd(B, sh, dy, x, R, L, flags=0):
 
 
 def compare(sh, got, want, names):
+    """Global relative Frobenius error <= the tolerance, and every row (activations) / block (weight
+    gradients) within 4x of it: see parity_util.check."""
     errs = {n: oracle.rel_fro(g, w) for n, g, w in zip(names, got, want)}
-    worst = max(errs.values())
     print("  %s %s" % (sh.name, " ".join("%s=%.2e" % kv for kv in errs.items())), flush=True)
-    assert worst <= TOL[sh.dtype], errs
+    for n, g, w in zip(names, got, want):
+        parity_util.check("%s.%s" % (sh.name, n), g, w, TOL[sh.dtype])
     return errs
 
 
@@ -113,7 +116,7 @@ SMALL = [
 
 def small_shape(case):
     name, dtype, Bn, k, p, q, s = case
-    return synth.Shape(name, dtype, Bn, k, p, q, s, config=90 + (hash(name) % 7))
+    return synth.Shape(name, dtype, Bn, k, p, q, s, config=90 + parity_util.stable_seed(name))
 
 
 @pytest.mark.parametrize("generic", [False, True], ids=["dispatch", "generic"])
@@ -907,6 +910,24 @@ def test_calls_run_on_the_stream_they_are_given(B):
     compare(sh, [host(y1), host(t1)] + [host(t) for t in g1], [oracle.fwd(x, R, L), oracle.fwd_t(dy, R, L)] + list(oracle.bwd_bias(dy, x, R, L)),
             ["y", "xM", "dx", "dR", "dL", "dbias"])
     del big2
+    # the same with `stream=side` only (the side stream is NOT torch's current stream): the binding's own
+    # temporary workspaces must belong to the side stream, or the default stream's next allocations --
+    # made and overwritten here while the side stream is still busy -- would land in them
+    ev = torch.cuda.Event()
+    ev.record()
+    side.wait_event(ev)
+    with torch.cuda.stream(side):
+        big3 = big.clone()
+    outs = [torch.empty_like(y0), torch.empty_like(t0)] + [torch.empty_like(t) for t in g0]
+    B.monarch_fwd(xd, Rd, Ld, outs[0], stream=side)
+    B.monarch_bwd_bias(dyd, xd, Rd, Ld, outs[2], outs[3], outs[4], outs[5], stream=side)
+    B.monarch_fwd_t(dyd, Rd, Ld, outs[1], stream=side)
+    need = B.monarch_bwd_workspace_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, 1, 0)
+    junk = [torch.full((need,), 0xFF, dtype=torch.uint8, device="cuda") for _ in range(3)]  # default stream, runs at once
+    side.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(y0, outs[0]) and torch.equal(t0, outs[1]) and all(torch.equal(a, b) for a, b in zip(g0, outs[2:]))
+    del big3, junk
 
 
 def test_stream_copy_is_bit_exact(B):

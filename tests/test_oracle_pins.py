@@ -1,6 +1,8 @@
 """Pins for the CPU oracle: it is checked against what the paper and the mathematics fix,
 never against itself.  Each test names the passage or fact it rests on.
 """
+import os
+
 import numpy as np
 import pytest
 import scipy.linalg
@@ -292,15 +294,38 @@ def test_empty_batch_and_bad_shapes():
         oracle.fwd(np.zeros((1, 6)), R, np.zeros((2, 2, 5)))
 
 
-def test_thread_count_does_not_change_results():
-    """The OpenMP split is over rows only; the weight-gradient partials are summed in a fixed
-    order, so results are reproducible run to run."""
-    rng = np.random.default_rng(9)
-    x, R, L, dy = _rand(rng, 4, 8, 8, 8, B=37)
-    a = oracle.bwd(dy, x, R, L)
-    b = oracle.bwd(dy, x, R, L)
-    for u, v in zip(a, b):
-        assert np.array_equal(u, v)
+def test_thread_count_changes_only_the_summation_order(tmp_path):
+    """The OpenMP split is over rows only.  Run the same backward in fresh processes with 1, 3 and 8
+    threads: y and dx are row-local and must agree bit for bit; dR and dL are sums of per-thread
+    partials, so they may differ in the order of fp64 additions only (<= 1e-13 relative), and two
+    runs at the same thread count must agree bit for bit."""
+    import subprocess
+    import sys
+    script = (
+        "import sys, numpy as np\n"
+        "sys.path.insert(0, %r)\n"
+        "import oracle\n"
+        "rng = np.random.default_rng(9)\n"
+        "k, p, q, s, B = 4, 8, 8, 8, 37\n"
+        "x = rng.standard_normal((B, k * p)); R = rng.standard_normal((k, q, p))\n"
+        "L = rng.standard_normal((k, s, q)); dy = rng.standard_normal((B, k * s))\n"
+        "y = oracle.fwd(x, R, L); dx, dR, dL = oracle.bwd(dy, x, R, L)\n"
+        "np.savez(sys.argv[1], y=y, dx=dx, dR=dR, dL=dL, threads=oracle.num_threads())\n"
+    ) % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    runs = {}
+    for tag, threads in (("t1", 1), ("t3", 3), ("t8", 8), ("t3_again", 3)):
+        out = str(tmp_path / (tag + ".npz"))
+        env = dict(os.environ, OMP_NUM_THREADS=str(threads))
+        subprocess.check_call([sys.executable, "-c", script, out], env=env)
+        runs[tag] = np.load(out)
+        assert int(runs[tag]["threads"]) == threads
+    base = runs["t1"]
+    for tag in ("t3", "t8"):
+        assert np.array_equal(runs[tag]["y"], base["y"]) and np.array_equal(runs[tag]["dx"], base["dx"]), tag
+        for name in ("dR", "dL"):
+            assert oracle.rel_fro(runs[tag][name], base[name]) < 1e-13, (tag, name)
+    for name in ("y", "dx", "dR", "dL"):
+        assert np.array_equal(runs["t3"][name], runs["t3_again"][name]), name
 
 
 # ------------------------------------------------------------ affine layer ----
