@@ -280,21 +280,6 @@ def measure_layer(name: str, with_dense: bool = True, with_extras: bool = False,
         out["dense_fwd_us"] = timed_runs(dense_fwd, calls // 2)[0] * 1e3
         out["dense_bwd_us"] = timed_runs(dense_bwd, calls // 2)[0] * 1e3
         out["speedup_vs_dense"] = (out["dense_fwd_us"] + out["dense_bwd_us"]) / (out["fwd_us"] + out["bwd_us"])
-        # The multiply as the paper runs it (Section 3.3): two framework batched matmuls with the reshapes and
-        # transposes between them as separate passes, the intermediate in HBM.  Context for what the fusion buys.
-        k, p, q, s_ = sh.k, sh.p, sh.q, sh.s
-        Rt = torch.randn(k, q, p, device=dev, dtype=dt)
-        Lt = torch.randn(k, s_, q, device=dev, dtype=dt)
-
-        def unfused_fwd(i):
-            xs = sets[i % nsets][0]
-            y1 = torch.bmm(xs.view(-1, k, p).transpose(0, 1), Rt.transpose(1, 2))        # (k, B, q)
-            u = y1.permute(1, 2, 0).reshape(-1, k, q).transpose(0, 1)                      # (q, k) grid, k chunks of q
-            w = torch.bmm(u, Lt.transpose(1, 2))                                           # (k, B, s)
-            return w.permute(1, 2, 0).reshape(-1, s_ * k)                                  # y[b, l*k + c]
-
-        out["unfused_bmm_fwd_us"] = timed_runs(unfused_fwd, max(20, calls // 5))[0] * 1e3
-
     if with_extras:
         out["extras"] = measure_extras(ly, calls // 2)
     return out
@@ -459,7 +444,27 @@ def cpu_baseline(workload: str, cpu_seconds: float = 20.0):
                       % ("both layers chained" if len(shapes) == 2 else "one layer", rows2, Bfull, workload, reps, dt_s, cores)}
 
 
+def progress(msg: str):
+    """One line on stderr per stage (flushed): if a run dies, the last line names the stage."""
+    sys.stderr.write("[bench] %s\n" % msg)
+    sys.stderr.flush()
+
+
 def main():
+    try:
+        _main()
+    finally:
+        # never leave the process with kernels still queued (an exception above included): the library's code
+        # objects are unloaded at exit
+        try:
+            import torch
+            if torch.cuda.is_available():
+                torch.cuda.synchronize()
+        except Exception as e:  # the original error, if any, is the one to report
+            sys.stderr.write("[bench] synchronize at exit failed: %r\n" % (e,))
+
+
+def _main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
@@ -482,8 +487,10 @@ def main():
         sys.stderr.write("bench.py needs a GPU\n")
         sys.exit(2)
     binding.lib()
+    progress("copy roof")
     copy_gbs = copy_roof()
     detail = {}
+    progress("building inputs of %s" % args.workload)
 
     if args.workload == PAIR:
         job = Pair()
@@ -497,15 +504,18 @@ def main():
         flops, nbytes, dtype = sh.fwd_flops() + sh.bwd_flops(), sh.fwd_bytes() + sh.bwd_bytes(), sh.dtype
         wl_text = "%s: k=%d p=%d q=%d s=%d (%d->%d), B=%d rows, fwd+bwd" % (sh.name, sh.k, sh.p, sh.q, sh.s, sh.n_in, sh.n_out, sh.B)
 
+    progress("warm-up: %d steps" % args.warmup)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    progress("timed: %d steps" % args.steps)
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(args.warmup + i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
+    progress("%.4f ms per step; per-call timings" % ms_per_step)
 
     # per-call durations of the step's calls: runs of consecutive calls of one entry point between two events
     if args.workload == PAIR:
@@ -561,11 +571,13 @@ def main():
     del job
     torch.cuda.empty_cache()
 
+    progress("launch floor")
     floor = launch_floor()
     detail["launch_floor_us"] = floor
     names = [args.workload] if (args.only and args.workload != PAIR) else ([] if args.only else list(CONFIGS))
     configs = {}
     for name in names:
+        progress("configuration %s" % name)
         configs[name] = measure_layer(name, with_dense=not args.no_dense, with_extras=args.extras, copy_gbs=copy_gbs)
         if name == "sq256_f32":
             configs[name]["launch_floor_us"] = floor["median_us"]
@@ -591,9 +603,12 @@ def main():
     }
     if not args.no_dense:
         # empirical matrix-core roof (vendor GEMM, n = 8192) and the step's share of it
+        progress("dense GEMM roof")
         line["dense_gemm_roof_tflops"] = mfma_roof()
         line["frac_of_dense_gemm_roof"] = line["value"] / line["dense_gemm_roof_tflops"][dtype]
     if not args.no_cpu:
+        torch.cuda.synchronize()
+        progress("CPU oracle baseline")
         line["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(line), flush=True)
 

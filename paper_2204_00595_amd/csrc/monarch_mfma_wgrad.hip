@@ -49,16 +49,23 @@ __device__ __forceinline__ bf16x8 frag_tr(const uint16_t* T, int stride, int k0,
     return as_bf16x8(v);
 }
 
-template <int TM, int TN, bool DEINT>
+// MSPLIT = false: the two waves of a group split the K-steps (each keeps the whole TM x TN tile, summed at the end);
+// MSPLIT = true (large tiles): they split the tile's rows m instead, each taking both K-steps of a pipeline step on
+// its own half of the accumulators -- 128 x 128 per group in 2 x 128 accumulator registers, which halves the operand
+// bytes fetched per flop against the 64 x 128 tile.
+template <int TM, int TN, bool DEINT, bool MSPLIT>
 __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int tile, const int zi)
 {
     constexpr int MT = TM / 32, NT = TN / 32;
+    constexpr int MTW = MSPLIT ? MT / 2 : MT;  // m tiles of one wave
+    static_assert(!MSPLIT || MT % 2 == 0, "row split");
     constexpr int SA = TM + 8, SB = TN + 8;  // LDS row strides (bf16 elements)
     constexpr int BUF = 4 * KB * (SA + SB);  // one pipeline buffer: As [4][KB][SA], then Bs [4][KB][SB]
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
 
-    // eight waves: wave = (group g, K half kh); the two waves of a group each take one 16-row K-step of every
-    // 32-row pipeline step on their own accumulators, which are summed through LDS at the end
+    // eight waves: wave = (group g, half kh); the two waves of a group each take one 16-row K-step of every
+    // 32-row pipeline step on their own accumulators, which are summed through LDS at the end (MSPLIT: each
+    // takes half of the tile's rows m over both K-steps, and nothing is summed)
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int grp = wave & 3, kh = wave >> 2;
     const int tiles_n = d.N / TN;
@@ -155,9 +162,9 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
         }
     };
 
-    f32x16 acc[MT * NT];
+    f32x16 acc[MTW * NT];
 #pragma unroll
-    for (int t = 0; t < MT * NT; ++t)
+    for (int t = 0; t < MTW * NT; ++t)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
@@ -178,26 +185,38 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
             const uint16_t* cur = lds + k * BUF;
             uint16_t* nxt = lds + (k ^ 1) * BUF;
             __syncthreads();
-            bf16x8 af[MT], bfr[NT];
+            bf16x8 af[MTW], bfr[NT];
+            const int krow = MSPLIT ? 0 : 16 * kh, mcol = MSPLIT ? kh * MTW * 32 : 0;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) af[mt] = frag_tr(cur + woff_a, SA, 16 * kh, mt * 32, lane);
+            for (int mt = 0; mt < MTW; ++mt) af[mt] = frag_tr(cur + woff_a, SA, krow, mcol + mt * 32, lane);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) bfr[nt] = frag_tr(cur + woff_b, SB, 16 * kh, nt * 32, lane);
+            for (int nt = 0; nt < NT; ++nt) bfr[nt] = frag_tr(cur + woff_b, SB, krow, nt * 32, lane);
             __builtin_amdgcn_sched_barrier(0);
             store_step(r0 + (k + 1) * KB, 0, nxt);
             load_step(r0 + (k + 2) * KB, 0);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+            for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) acc[mt * NT + nt] = mfma32(af[mt], bfr[nt], acc[mt * NT + nt]);
+            if constexpr (MSPLIT) {
+                // second K-step of the pipeline step (rows 16 .. 31 of the buffer)
+#pragma unroll
+                for (int mt = 0; mt < MTW; ++mt) af[mt] = frag_tr(cur + woff_a, SA, 16, mcol + mt * 32, lane);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) bfr[nt] = frag_tr(cur + woff_b, SB, 16, nt * 32, lane);
+#pragma unroll
+                for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) acc[mt * NT + nt] = mfma32(af[mt], bfr[nt], acc[mt * NT + nt]);
+            }
         }
     }
     }
 
     // sum the two K halves of every group through LDS (fp32, in two rounds of at most R1 tiles per
     // wave: the staging buffers hold 4 x R1 tiles), then the kh = 0 wave owns the group's partial tile
-    {
+    if constexpr (!MSPLIT) {
         constexpr int NTILE = MT * NT, R1 = (NTILE + 1) / 2;
         static_assert((size_t)4 * R1 * 4096 <= (size_t)2 * BUF * 2, "reduction staging fits the pipeline buffers");
         float* red = reinterpret_cast<float*>(lds) + (size_t)grp * R1 * 1024 + lane;
@@ -218,19 +237,21 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
                     for (int i = 0; i < 16; ++i) acc[t][i] += red[(t - t0) * 1024 + i * 64];
             }
         }
+        if (kh != 0) return;
     }
-    if (kh != 0 || g0 + grp >= d.G) return;  // (the group count need not be a multiple of four)
+    if (g0 + grp >= d.G) return;  // (the group count need not be a multiple of four)
 
     // partial tile: P[z][g][m][n]
     const int ln = lane & 31, h = lane >> 5;
+    const int mw = m0 + (MSPLIT ? kh * MTW * 32 : 0);  // first row of this wave's accumulators
     float* Pg = d.P + (((size_t)zi * d.G + g0 + grp) * d.M) * d.N;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int m = m0 + mt * 32 + 8 * (i / 4) + 4 * h + (i % 4);
+                const int m = mw + mt * 32 + 8 * (i / 4) + 4 * h + (i % 4);
                 Pg[(size_t)m * d.N + n0 + nt * 32 + ln] = acc[mt * NT + nt][i];
             }
 }
@@ -247,12 +268,13 @@ wgrad_gemm_kernel(WgradDesc d0, WgradDesc d1, int tiles0, int tiles)
     const int per = nwg >> 3, rem = nwg & 7;
     const int v = xcd * per + (xcd < rem ? xcd : rem) + slot;
     const int t = v % tiles, zi = v / tiles;
+    constexpr bool MSPLIT = (TM / 32) * (TN / 32) > 9;  // more accumulators than one wave of a pair can hold
     if (t < tiles0) {
-        if (d0.deint) wgrad_gemm_body<TM, TN, true>(d0, t, zi);
-        else wgrad_gemm_body<TM, TN, false>(d0, t, zi);
+        if (d0.deint) wgrad_gemm_body<TM, TN, true, MSPLIT>(d0, t, zi);
+        else wgrad_gemm_body<TM, TN, false, MSPLIT>(d0, t, zi);
     } else {
-        if (d1.deint) wgrad_gemm_body<TM, TN, true>(d1, t - tiles0, zi);
-        else wgrad_gemm_body<TM, TN, false>(d1, t - tiles0, zi);
+        if (d1.deint) wgrad_gemm_body<TM, TN, true, MSPLIT>(d1, t - tiles0, zi);
+        else wgrad_gemm_body<TM, TN, false, MSPLIT>(d1, t - tiles0, zi);
     }
 }
 
@@ -315,6 +337,7 @@ int launch_gemm_tile(int tm, int tn, const WgradDesc& d0, const WgradDesc* d1, i
 {
 #define MONARCH_WG_CASE(TM_, TN_) \
     if (tm == TM_ && tn == TN_) return launch_gemm<TM_, TN_>(d0, d1, nz, st);
+    MONARCH_WG_CASE(128, 128)
     MONARCH_WG_CASE(96, 96)
     MONARCH_WG_CASE(64, 128)
     MONARCH_WG_CASE(128, 64)
@@ -330,7 +353,7 @@ bool wgrad_tile_ok(int M, int N, int seg_w, int* tm, int* tn)
 {
     // tile shapes instantiated above; a tile's 8-column pieces must not straddle a segment
     if (seg_w % 8 != 0) return false;
-    const int cand[][2] = {{96, 96}, {64, 128}, {128, 64}, {64, 64}, {32, 32}};
+    const int cand[][2] = {{128, 128}, {96, 96}, {64, 128}, {128, 64}, {64, 64}, {32, 32}};
     for (auto& c : cand)
         if (M % c[0] == 0 && N % c[1] == 0) {
             *tm = c[0];
