@@ -105,6 +105,23 @@ int monarch_fwd_ws(const void* x, const void* R, const void* L, void* y,
                    monarch_dtype dtype, void* stream,
                    void* workspace, size_t workspace_bytes, unsigned flags);
 
+/* monarch_fwd_ws for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * operation, arguments, kernels and result as monarch_fwd_ws (bit for bit), but the scratch
+ * memory is an array inside the library that exists from program load: MONARCH_STATIC_WORKSPACE_BYTES
+ * bytes per GPU, held by every GPU the library runs on until the process ends.  The call
+ * allocates and frees nothing.  Shapes whose monarch_fwd_workspace_bytes(...) exceeds that limit
+ * return MONARCH_ERR_WORKSPACE (every shape with a packed-weight kernel in this build fits);
+ * MONARCH_FLAG_WS_PACKED is refused with MONARCH_ERR_INVALID, because the array belongs to no
+ * caller between calls.  All calls on one GPU share the array and overwrite it: two calls that may
+ * overlap in time on one GPU (different streams, different threads) race and must be serialised by
+ * the caller; calls on one stream are ordered and safe.  The first call on a device looks up the
+ * array's device address (no allocation; make that call outside graph capture). */
+#define MONARCH_STATIC_WORKSPACE_BYTES (8u << 20)
+int monarch_fwd_static(const void* x, const void* R, const void* L, void* y,
+                       int64_t batch, int n_in, int k, int q, int s,
+                       monarch_dtype dtype, void* stream, unsigned flags);
+
 /* Forward of the affine layer built on the Monarch matrix:  y[b][o] = (x M^T)[b][o] + bias[o].
  * Section 4 swaps a layer's dense weight matrix for a Monarch one and keeps the rest of the layer;
  * the appendix on BERT pretraining lists the bias add as a step to fuse into the matrix product.

@@ -29,7 +29,7 @@ MONARCH_FLAG_WS_PACKED = 8
 
 # every symbol include/monarch.h declares
 EXPORTS = (
-    "monarch_fwd", "monarch_fwd_ex", "monarch_fwd_ws", "monarch_fwd_bias", "monarch_fwd_workspace_bytes", "monarch_bwd",
+    "monarch_fwd", "monarch_fwd_ex", "monarch_fwd_ws", "monarch_fwd_static", "monarch_fwd_bias", "monarch_fwd_workspace_bytes", "monarch_bwd",
     "monarch_bwd_bias",
     "monarch_bwd_workspace_bytes",
     "monarch_fwd_t", "monarch_fwd_t_workspace_bytes", "monarch_saved_bytes", "monarch_fwd_save", "monarch_bwd_saved", "monarch_fwd_c64", "monarch_bwd_c64", "monarch_dft_factors", "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy", "monarch_launch_probe",
@@ -60,6 +60,8 @@ def lib() -> ctypes.CDLL:
         L.monarch_fwd_ex.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp, cu]
         L.monarch_fwd_ws.restype = ci
         L.monarch_fwd_ws.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
+        L.monarch_fwd_static.restype = ci
+        L.monarch_fwd_static.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp, cu]
         L.monarch_fwd_bias.restype = ci
         L.monarch_fwd_bias.argtypes = [vp, vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
         L.monarch_bwd_bias.restype = ci
@@ -204,6 +206,29 @@ def monarch_fwd_ws(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.T
                                   _dtype_code(x), _stream_ptr(stream), ws_ptr, ws_len, flags)
     if rc != MONARCH_OK:
         raise MonarchError(rc, "monarch_fwd_ws")
+    return y
+
+
+MONARCH_STATIC_WORKSPACE_BYTES = 8 << 20
+
+
+def monarch_fwd_static(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.Tensor, flags: int = 0,
+                       stream=None) -> torch.Tensor:
+    """y = x M^T through monarch_fwd_static (the library's own static workspace; nothing is allocated,
+    so `y` must be given)."""
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    dev, dt = x.device, x.dtype
+    _check(x, "x", (B, k * p), dt, dev)
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    _check(y, "y", (B, k * s), dt, dev)
+    with torch.cuda.device(dev):
+        rc = lib().monarch_fwd_static(x.data_ptr(), R.data_ptr(), L.data_ptr(), y.data_ptr(), B, k * p, k, q, s,
+                                      _dtype_code(x), _stream_ptr(stream), flags)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_fwd_static")
     return y
 
 

@@ -93,6 +93,31 @@ bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
 __global__ void empty_kernel() {}
 
+// ---- workspace of monarch_fwd_static: device memory that exists from program load, one copy per GPU ----
+constexpr size_t kStaticWorkspaceBytes = MONARCH_STATIC_WORKSPACE_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
+
+// Device address of `scratch` on the current device.  In host code the array's name is only a handle
+// for the runtime; the address a kernel can use comes from hipGetSymbolAddress, asked once per device
+// (every GPU holds its own copy at its own address) and kept.
+int static_workspace(void** out)
+{
+    static std::mutex mu;
+    static void* ptr[kMaxDevices] = {};
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return MONARCH_ERR_HIP;
+    if (device < 0 || device >= kMaxDevices) return MONARCH_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> guard(mu);
+    if (!ptr[device]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MONARCH_ERR_HIP;
+        ptr[device] = p;
+    }
+    *out = ptr[device];
+    return MONARCH_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -144,6 +169,21 @@ int monarch_fwd_ws(const void* x, const void* R, const void* L, void* y, int64_t
         return MONARCH_ERR_WORKSPACE;
     if (batch == 0) return MONARCH_OK;
     return mfma_fwd_ws(pb, x, R, L, y, workspace, (hipStream_t)stream);
+}
+
+int monarch_fwd_static(const void* x, const void* R, const void* L, void* y, int64_t batch, int n_in, int k,
+                       int q, int s, monarch_dtype dtype, void* stream, unsigned flags)
+{
+    if (flags & MONARCH_FLAG_WS_PACKED) return MONARCH_ERR_INVALID;  // the shared array is nobody's to keep between calls
+    const size_t need = monarch_fwd_workspace_bytes(batch, n_in, k, q, s, dtype, flags);
+    if (need > kStaticWorkspaceBytes) return MONARCH_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if (need > 0) {
+        const int rc = static_workspace(&ws);
+        if (rc) return rc;
+    }
+    // need == 0: monarch_fwd_ws takes the kernels that use no workspace and ignores the pointer
+    return monarch_fwd_ws(x, R, L, y, batch, n_in, k, q, s, dtype, stream, ws, need, flags);
 }
 
 int monarch_fwd_bias(const void* x, const void* R, const void* L, const void* bias, void* y, int64_t batch,
