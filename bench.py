@@ -70,6 +70,33 @@ def timed_runs(fn, calls: int = TIMED_CALLS, runs: int = RUNS, untimed: int = 3)
     return float(np.median(out)), float(np.min(out)), float(np.mean(out)), per * runs
 
 
+def graph_time(fn, calls_per_graph: int = 50, replays: int = 10):
+    """Time per call (ms) of fn(i) when `calls_per_graph` consecutive calls are captured into one HIP graph and the
+    graph is replayed: the host's share of a launch (interpreter, binding, runtime) is paid at capture, not at
+    replay, so for microsecond kernels this is the GPU's own time per call.  Median and min over the replays."""
+    import numpy as np
+    import torch
+    for i in range(3):
+        fn(i)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(calls_per_graph):
+            fn(i)
+    g.replay()
+    torch.cuda.synchronize()
+    out = []
+    for _ in range(replays):
+        e0, e1 = _events(2)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        out.append(e0.elapsed_time(e1) / calls_per_graph)
+    del g
+    return float(np.median(out)), float(np.min(out))
+
+
 def copy_roof(reps: int = 5):
     """GB/s (read + write) of the library's plain streaming copy over COPY_BYTES: the empirical HBM roof.
     A profiler run of this script also uses this kernel's known traffic to calibrate its counters."""
@@ -263,7 +290,11 @@ def measure_layer(name: str, with_dense: bool = True, with_extras: bool = False,
         out[ps + "_traffic_bytes"] = t  # rocprofv3 FETCH_SIZE + WRITE_SIZE per call (profiles/), null if not profiled
         out[ps + "_traffic_ratio"] = (t / out[ps + "_algorithmic_bytes"]) if t else None
     if small:
-        out["note"] = "launch-latency bound: %d KB and %.1f MFLOP per forward; see launch_floor_us" % (sh.fwd_bytes() // 1000, sh.fwd_flops() / 1e6)
+        out["note"] = ("launch-latency bound: %d KB and %.1f MFLOP per forward; the eager per-call times above include the host's "
+                       "cost of issuing a launch from Python (see launch_floor_us); *_us_graph are the same calls replayed from a "
+                       "captured HIP graph" % (sh.fwd_bytes() // 1000, sh.fwd_flops() / 1e6))
+        out["fwd_us_graph"], out["fwd_us_graph_min"] = (v * 1e3 for v in graph_time(ly.fwd))
+        out["bwd_us_graph"], out["bwd_us_graph_min"] = (v * 1e3 for v in graph_time(ly.bwd))
 
     if with_dense:
         # vendor dense GEMM of the same (B, n_in, n_out): 1 GEMM forward, 2 GEMMs backward

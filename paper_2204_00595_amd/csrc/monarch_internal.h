@@ -154,7 +154,9 @@ struct WgradDesc {
     int64_t ldb;
     int b_g, b_seg, seg_w;
     int M, N, G;
-    float* P;        // partial tiles, nz * G * M * N floats
+    float* P;        // partial tiles, nz * G * M * N floats (or as many bf16 values in the same space: p_bf16)
+    int p_bf16;      // partial tiles are stored rounded to bf16: half the bytes written by the GEMM and read by the
+                     // reduction; used when the gradients themselves are returned in bf16
     int64_t rows;
     int rows_per_chunk;
     int deint;       // A holds the four groups interleaved

@@ -46,14 +46,21 @@ __device__ __forceinline__ void wave_lds_fence()
 // tile T: 16 rows of 64 16-byte pieces; piece index XOR-ed with row % 8 (bank spreading)
 __device__ __forceinline__ int t_off(int row, int piece) { return row * 1024 + ((piece ^ (row & 7)) << 4); }
 
-// W[block][row][col] (fp32, 16 x 16 x 16) -> LDS operand order: dst[block][lane] = W[block][lane % 16][4 * (lane / 16) .. +3]
-__device__ __forceinline__ void stage_weights(const float* __restrict__ W, unsigned char* dst, int tid, int nthreads)
+// W[block][row][col] (fp32, 16 x 16 x 16) -> LDS operand order: dst[block][lane] = W[block][lane % 16][4 * (lane / 16) .. +3].
+// NT threads take 1024 / NT pieces each; all of a thread's loads are issued before its first LDS store, so the
+// staging costs one memory latency (a launch with a handful of tiles is mostly this latency).
+template <int NT>
+__device__ __forceinline__ void stage_weights(const float* __restrict__ W, unsigned char* dst, int tid)
 {
-    for (int e = tid; e < 16 * 64; e += nthreads) {
-        const int blk = e >> 6, lane = e & 63;
-        *reinterpret_cast<f32x4*>(dst + (size_t)e * 16) =
-            *reinterpret_cast<const f32x4*>(W + ((size_t)blk * 16 + (lane & 15)) * 16 + 4 * (lane >> 4));
+    constexpr int PER = 16 * 64 / NT;
+    f32x4 v[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int e = tid + k * NT, blk = e >> 6, lane = e & 63;
+        v[k] = *reinterpret_cast<const f32x4*>(W + ((size_t)blk * 16 + (lane & 15)) * 16 + 4 * (lane >> 4));
     }
+#pragma unroll
+    for (int k = 0; k < PER; ++k) *reinterpret_cast<f32x4*>(dst + (size_t)(tid + k * NT) * 16) = v[k];
 }
 
 template <bool BIAS>
@@ -81,8 +88,8 @@ fwd_sq16_kernel(const float* __restrict__ x, const float* __restrict__ R, const 
     if (tile < ntiles) load_x(tile, xa);  // in flight while the weights are staged
     f32x4 bv = {0.f, 0.f, 0.f, 0.f};  // the lane stores y[b][4*lane .. 4*lane + 3] of every row
     if constexpr (BIAS) bv = *reinterpret_cast<const f32x4*>(bias + 4 * lane);
-    stage_weights(R, Rop, tid, 512);
-    stage_weights(L, Lop, tid, 512);
+    stage_weights<512>(R, Rop, tid);
+    stage_weights<512>(L, Lop, tid);
     __syncthreads();
     for (; tile < ntiles; tile += stride) {
         // ---- step 1: Y1[b][kk][j = 4h + i] -> T[b][kk][j]
@@ -134,14 +141,88 @@ fwd_sq16_kernel(const float* __restrict__ x, const float* __restrict__ R, const 
     }
 }
 
-// W[block][row][col] -> transposed operand order: dst[block][lane] = W[block][4 * (lane / 16) + u][lane % 16], u = 0..3
-__device__ __forceinline__ void stage_weights_t(const float* __restrict__ W, unsigned char* dst, int tid, int nthreads)
+// Small batches (at most one 16-row tile per CU): one single-wave workgroup per tile.  The persistent kernel
+// above pays, per launch, for staging both factors into LDS behind a workgroup barrier, which is the price of a
+// launch that has more tiles than waves; here every wave reads its operands of R and L (2 x 16 registers of
+// 16 bytes, the same operand order) straight from global memory while its rows of x are in flight, and the
+// only LDS is the wave's own 16 KiB tile.
+template <bool BIAS>
+__global__ void __launch_bounds__(64)
+fwd_sq16_small_kernel(const float* __restrict__ x, const float* __restrict__ R, const float* __restrict__ L,
+                      const float* __restrict__ bias, float* __restrict__ y, int64_t B)
 {
-    for (int e = tid; e < 16 * 64; e += nthreads) {
-        const int blk = e >> 6, lane = e & 63;
-        const float* p = W + ((size_t)blk * 16 + 4 * (lane >> 4)) * 16 + (lane & 15);
-        *reinterpret_cast<f32x4*>(dst + (size_t)e * 16) = f32x4{p[0], p[16], p[32], p[48]};
+    __shared__ __attribute__((aligned(16))) unsigned char T[SQ16_T_BYTES];
+    const int lane = threadIdx.x & 63;
+    const int bl = lane & 15, h = lane >> 4;
+    const int64_t b0 = (int64_t)blockIdx.x * 16;
+    int64_t row = b0 + bl;
+    row = row < B ? row : B - 1;  // rows past the end are computed from a valid row and dropped
+    f32x4 xa[16], ra[16], la[16];
+    const float* px = x + row * N16 + 4 * h;
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) xa[kk] = ldg128f_nt(px + 16 * kk);
+    // operand order of stage_weights: block blk, lane -> W[blk][lane % 16][4 * (lane / 16) .. +3]
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) ra[kk] = *reinterpret_cast<const f32x4*>(R + ((size_t)kk * 16 + bl) * 16 + 4 * h);
+#pragma unroll
+    for (int c = 0; c < 16; ++c) la[c] = *reinterpret_cast<const f32x4*>(L + ((size_t)c * 16 + bl) * 16 + 4 * h);
+    f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (BIAS) bv = *reinterpret_cast<const f32x4*>(bias + 4 * lane);
+    __builtin_amdgcn_sched_barrier(0);  // all 48 loads are issued before the first use (one memory latency, not three)
+    // ---- step 1: Y1[b][kk][j = 4h + i] -> T[b][kk][j]
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc = mfma4(ra[kk][u], xa[kk][u], acc);
+        *reinterpret_cast<f32x4*>(T + t_off(bl, 4 * kk + h)) = acc;
     }
+    wave_lds_fence();
+    // ---- step 2 operand: ub[u][c] = U[b][c][r = 4h + u] = Y1[b][kk = 4h + u][j = c]
+    f32x4 ub[4][4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) ub[u][v] = *reinterpret_cast<const f32x4*>(T + t_off(bl, 4 * (4 * h + u) + v));
+    f32x4 w[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc = mfma4(la[c][u], ub[u][c >> 2][c & 3], acc);
+        w[c] = acc;
+    }
+    wave_lds_fence();  // every lane has read its operands: the tile is reused for y
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int cq = 0; cq < 4; ++cq)
+            *reinterpret_cast<f32x4*>(T + t_off(bl, 16 * h + 4 * i + cq)) =
+                f32x4{w[4 * cq][i], w[4 * cq + 1][i], w[4 * cq + 2][i], w[4 * cq + 3][i]};
+    wave_lds_fence();
+    // ---- step 3: one full row (1 KiB) per store instruction
+#pragma unroll
+    for (int k2 = 0; k2 < 16; ++k2) {
+        f32x4 v = *reinterpret_cast<const f32x4*>(T + t_off(k2, lane));
+        if constexpr (BIAS) v += bv;
+        if (b0 + k2 < B) stg128f_nt(y + (b0 + k2) * N16 + 4 * lane, v);
+    }
+}
+
+// W[block][row][col] -> transposed operand order: dst[block][lane] = W[block][4 * (lane / 16) + u][lane % 16], u = 0..3
+template <int NT>
+__device__ __forceinline__ void stage_weights_t(const float* __restrict__ W, unsigned char* dst, int tid)
+{
+    constexpr int PER = 16 * 64 / NT;
+    f32x4 v[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int e = tid + k * NT, blk = e >> 6, lane = e & 63;
+        const float* p = W + ((size_t)blk * 16 + 4 * (lane >> 4)) * 16 + (lane & 15);
+        v[k] = f32x4{p[0], p[16], p[32], p[48]};
+    }
+#pragma unroll
+    for (int k = 0; k < PER; ++k) *reinterpret_cast<f32x4*>(dst + (size_t)(tid + k * NT) * 16) = v[k];
 }
 
 // Transposed multiply y = x M for the same shape: the two dx stages of the backward kernel below on
@@ -174,8 +255,8 @@ fwd_t_sq16_kernel(const float* __restrict__ x, const float* __restrict__ R, cons
     };
     f32x4 raw[16];
     if (tile < ntiles) load_rows(tile, raw);  // in flight while the weights are staged
-    stage_weights_t(R, RTop, tid, 512);
-    stage_weights_t(L, LTop, tid, 512);
+    stage_weights_t<512>(R, RTop, tid);
+    stage_weights_t<512>(L, LTop, tid);
     __syncthreads();
     for (; tile < ntiles; tile += stride) {
 #pragma unroll
@@ -279,9 +360,9 @@ bwd_sq16_kernel(const float* __restrict__ dy, const float* __restrict__ x, const
         load_x(tile, xa);
         load_dy(tile, dya);
     }
-    stage_weights(R, Rop, tid, 256);
-    stage_weights_t(R, RTop, tid, 256);
-    stage_weights_t(L, LTop, tid, 256);
+    stage_weights<256>(R, Rop, tid);
+    stage_weights_t<256>(R, RTop, tid);
+    stage_weights_t<256>(L, LTop, tid);
     __syncthreads();
     for (; tile < ntiles; tile += stride) {
         const int64_t b0 = tile * 16;
@@ -389,6 +470,147 @@ bwd_sq16_kernel(const float* __restrict__ dy, const float* __restrict__ x, const
         }
 }
 
+// Backward for a batch of at most four 16-row tiles (one workgroup): the five MFMA groups of a tile are split
+// over four waves (wave = (tile t, part q)), each taking a quarter of every group's sixteen blocks -- block kk or c
+// in 4q .. 4q+3, or the quarter cq = q / kq = q of the two gradient products -- so a tile takes a quarter of the
+// time it takes one wave, the weights come straight from global memory in operand order (no staging pass, no
+// second launch), and every wave holds only its quarter of the operands (4 of the 16 pieces of x and dy) and
+// of the gradients.  The exchanges through the tile are the ones of bwd_sq16_kernel, with workgroup barriers in
+// place of the wave fences.  At the end the four tiles' gradients are summed through LDS in a fixed order and
+// written to dR and dL: no workspace, no reduction launch.
+constexpr int SQ16S_TILES = 4;
+constexpr size_t SQ16S_LDS = SQ16S_TILES * 8192 * sizeof(float);  // 128 KiB: four tiles first, the four gradient copies at the end
+
+__global__ void __launch_bounds__(1024)
+bwd_sq16_small_kernel(const float* __restrict__ dy, const float* __restrict__ x, const float* __restrict__ R,
+                      const float* __restrict__ L, float* __restrict__ dx, float* __restrict__ dR, float* __restrict__ dL,
+                      int64_t B)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char ldsb[];
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int t = wave >> 2, q = wave & 3;
+    const int bl = lane & 15, h = lane >> 4;
+    unsigned char* T = ldsb + (size_t)t * SQ16_T_BYTES;
+    const int64_t b0 = (int64_t)t * 16;
+    int64_t row = b0 + bl;
+    const float msk = row < B ? 1.f : 0.f;  // rows past the end count as zero in dy (and are computed from a valid row of x)
+    row = row < B ? row : B - 1;
+    // this wave's quarter of the tile's operands: x[b][16kk + 4h ..] for kk = 4q + w; dy[b][64h + 4(4u + q) ..] for u = 0..3
+    f32x4 xa[4], dya[4], ra[4], rt[4], lt[4];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) xa[w] = ldg128f_nt(x + row * N16 + 16 * (4 * q + w) + 4 * h);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) dya[u] = *reinterpret_cast<const f32x4*>(dy + row * N16 + 64 * h + 4 * (4 * u + q)) * msk;
+    // weights in operand order, blocks 4q .. 4q+3: R[kk][j = bl][i = 4h + u];  R[kk][j = 4h + u][i = bl];  L[c][l = 4h + u][r = bl]
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const int blk = 4 * q + w;
+        ra[w] = *reinterpret_cast<const f32x4*>(R + ((size_t)blk * 16 + bl) * 16 + 4 * h);
+        const float* pr = R + ((size_t)blk * 16 + 4 * h) * 16 + bl;
+        rt[w] = f32x4{pr[0], pr[16], pr[32], pr[48]};
+        const float* pl = L + ((size_t)blk * 16 + 4 * h) * 16 + bl;
+        lt[w] = f32x4{pl[0], pl[16], pl[32], pl[48]};
+    }
+    __builtin_amdgcn_sched_barrier(0);  // every load is issued before the first use
+    // dy "down the batch" for the dL product: through the tile
+#pragma unroll
+    for (int u = 0; u < 4; ++u) *reinterpret_cast<f32x4*>(T + t_off(bl, 16 * h + 4 * u + q)) = dya[u];
+    __syncthreads();
+    f32x4 daq[4];  // daq[u] = dy[b0 + 4h + u][16 bl + 4q .. +3]
+#pragma unroll
+    for (int u = 0; u < 4; ++u) daq[u] = *reinterpret_cast<const f32x4*>(T + t_off(4 * h + u, 4 * bl + q));
+    __syncthreads();
+    // ---- 1. Y1[b][kk][j = 4h + i] -> tile [b][kk][j], kk = 4q + w
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc = mfma4(ra[w][u], xa[w][u], acc);
+        *reinterpret_cast<f32x4*>(T + t_off(bl, 4 * (4 * q + w) + h)) = acc;
+    }
+    __syncthreads();
+    // ---- 2. dL[c = 4q + e][l][r] += sum_b dy[b][16l + c] Y1[b][r][c]
+    f32x4 accL[4], accR[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) accL[e] = accR[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+    {
+        f32x4 ub[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) ub[u] = *reinterpret_cast<const f32x4*>(T + t_off(4 * h + u, 4 * bl + q));
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) accL[e] = mfma4(daq[u][e], ub[u][e], accL[e]);
+    }
+    __syncthreads();  // Y1 has been read: the tile is reused
+    // ---- 3. dY1[b][kk = 4h + i][j = c] -> tile [b][j][kk], c = 4q + w (dW[b][c][l = 4h + u] = dya[u][w])
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc = mfma4(lt[w][u], dya[u][w], acc);
+        *reinterpret_cast<f32x4*>(T + t_off(bl, 4 * (4 * q + w) + h)) = acc;
+    }
+    __syncthreads();
+    // operands of 4 (lane (j, h): dY1[b0 + 4h + u][kk = 4q + e][j]) and of 5 (lane (b, h): dY1[b][kk = 4q + e][j = 4h + u])
+    f32x4 a2[4], db[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        a2[u] = *reinterpret_cast<const f32x4*>(T + t_off(4 * h + u, 4 * bl + q));
+        db[u] = *reinterpret_cast<const f32x4*>(T + t_off(bl, 4 * (4 * h + u) + q));
+    }
+    __syncthreads();
+    // x re-laid as tile [b][i][kk]: this wave holds kk = 4q .. 4q+3, i = 4h + e
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        *reinterpret_cast<f32x4*>(T + t_off(bl, 4 * (4 * h + e) + q)) = f32x4{xa[0][e], xa[1][e], xa[2][e], xa[3][e]};
+    __syncthreads();
+    // ---- 4. dR[kk = 4q + e][j][i] += sum_b dY1[b][kk][j] x[b][16kk + i]
+    {
+        f32x4 xb[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) xb[u] = *reinterpret_cast<const f32x4*>(T + t_off(4 * h + u, 4 * bl + q));
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) accR[e] = mfma4(a2[u][e], xb[u][e], accR[e]);
+    }
+    __syncthreads();
+    // ---- 5. dx[b][16kk + 4h + i], kk = 4q + w -> tile (row-major), then one full row per store instruction
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc = mfma4(rt[w][u], db[u][w], acc);
+        *reinterpret_cast<f32x4*>(T + t_off(bl, 4 * (4 * q + w) + h)) = acc;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const int k2 = 4 * q + w;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(T + t_off(k2, lane));
+        if (b0 + k2 < B) stg128f_nt(dx + (b0 + k2) * N16 + 4 * lane, v);
+    }
+    __syncthreads();  // the tiles are dead: the whole LDS takes the four tiles' gradients, [tile][dR then dL]
+    float* red = reinterpret_cast<float*>(ldsb) + (size_t)t * 8192;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            // accR[e] is block kk = 4q + e, accL[e] block c = 4q + e; element i is row 4h + i, column bl
+            red[(4 * q + e) * 256 + (4 * h + i) * 16 + bl] = accR[e][i];
+            red[4096 + (4 * q + e) * 256 + (4 * h + i) * 16 + bl] = accL[e][i];
+        }
+    __syncthreads();
+    const float* all = reinterpret_cast<const float*>(ldsb);
+    for (int e = tid; e < 8192; e += 1024) {
+        const float tot = ((all[e] + all[8192 + e]) + all[2 * 8192 + e]) + all[3 * 8192 + e];
+        if (e < 4096) dR[e] = tot;
+        else dL[e - 4096] = tot;
+    }
+}
+
 // out[e] = sum_z P[z][e] for the 8192 gradient entries (dR then dL); 16 entries x 16 z-lanes per block
 __global__ void __launch_bounds__(256)
 reduce_sq16_kernel(const float* __restrict__ P, float* __restrict__ dR, float* __restrict__ dL, int nz)
@@ -428,6 +650,8 @@ int bwd_sq16_grid(const Problem& pb)
 
 }  // namespace
 
+constexpr int64_t kSmallTiles = 256;  // forward: batches of at most this many 16-row tiles take the single-wave kernel
+
 bool sq16_supported(const Problem& pb)
 {
     // both readings of the mid permutation coincide when k = q
@@ -451,10 +675,16 @@ int fwd_t_sq16(const Problem& pb, const void* x, const void* R, const void* L, v
 int fwd_sq16(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
 {
     if (!sq16_supported(pb)) return -2;
+    const int64_t ntiles = (pb.B + 15) / 16;
+    if (ntiles <= kSmallTiles) {  // at most one tile per CU: single-wave workgroups, no weight staging
+        auto small = pb.bias ? fwd_sq16_small_kernel<true> : fwd_sq16_small_kernel<false>;
+        hipLaunchKernelGGL(small, dim3((unsigned)ntiles), dim3(64), 0, st, (const float*)x, (const float*)R,
+                           (const float*)L, (const float*)pb.bias, (float*)y, pb.B);
+        return hip_status(hipGetLastError());
+    }
     auto kern = pb.bias ? fwd_sq16_kernel<true> : fwd_sq16_kernel<false>;
     if (allow_dynamic_lds((const void*)kern, SQ16_LDS) != hipSuccess)
         return -4;
-    const int64_t ntiles = (pb.B + 15) / 16;
     int64_t grid = (ntiles + SQ16_WAVES - 1) / SQ16_WAVES;
     if (grid > 256) grid = 256;  // one persistent workgroup per CU
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), SQ16_LDS, st, (const float*)x, (const float*)R,
@@ -476,11 +706,18 @@ int bwd_sq16(const Problem& pb, const void* dy, const void* x, const void* R, co
         const int rc = launch_fill_zero_f32((float*)dR, pb.n_R(), st);
         return rc ? rc : launch_fill_zero_f32((float*)dL, pb.n_L(), st);
     }
+    const int grid = bwd_sq16_grid(pb);
+    const int64_t ntiles = (pb.B + 15) / 16;
+    if (ntiles <= SQ16S_TILES) {  // the batch fits one workgroup: tiles split over four waves each, gradients summed in the kernel
+        auto small = bwd_sq16_small_kernel;
+        if (allow_dynamic_lds((const void*)small, SQ16S_LDS) != hipSuccess) return -4;
+        hipLaunchKernelGGL(small, dim3(1), dim3(1024), SQ16S_LDS, st, (const float*)dy, (const float*)x, (const float*)R,
+                           (const float*)L, (float*)dx, (float*)dR, (float*)dL, pb.B);
+        return hip_status(hipGetLastError());
+    }
     auto kern = bwd_sq16_kernel;
     if (allow_dynamic_lds((const void*)kern, SQ16B_LDS) != hipSuccess)
         return -4;
-    const int grid = bwd_sq16_grid(pb);
-    const int64_t ntiles = (pb.B + 15) / 16;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), SQ16B_LDS, st, (const float*)dy, (const float*)x, (const float*)R,
                        (const float*)L, (float*)dx, (float*)ws, pb.B, ntiles);
     if (hipGetLastError() != hipSuccess) return -4;

@@ -564,6 +564,7 @@ int tiled_bwd(const Problem& pb, const void* dy, const void* x, const void* R, c
     dr.A = (const uint16_t*)(w + pl.off_dy1); dr.Bm = (const uint16_t*)x;
     dr.P = (float*)(w + pl.off_partR); dr.out = dR;
     dl.rows_per_chunk = dr.rows_per_chunk = pl.rows_per_chunk;
+    dl.p_bf16 = dr.p_bf16 = f32out ? 0 : 1;  // bf16 gradients: bf16 partial tiles
     rc = wgrad_gemm_pair(dl, dr, pl.nz, st);
     if (rc) return rc;
     return wgrad_reduce_pair(dl, dr, f32out, pl.nz, st);

@@ -244,7 +244,21 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
     // partial tile: P[z][g][m][n]
     const int ln = lane & 31, h = lane >> 5;
     const int mw = m0 + (MSPLIT ? kh * MTW * 32 : 0);  // first row of this wave's accumulators
-    float* Pg = d.P + (((size_t)zi * d.G + g0 + grp) * d.M) * d.N;
+    const size_t pbase = (((size_t)zi * d.G + g0 + grp) * d.M) * d.N;
+    if (d.p_bf16) {
+        uint16_t* Pg = reinterpret_cast<uint16_t*>(d.P) + pbase;
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int m = mw + mt * 32 + 8 * (i / 4) + 4 * h + (i % 4);
+                    Pg[(size_t)m * d.N + n0 + nt * 32 + ln] = (uint16_t)(pack_bf16x2(acc[mt * NT + nt][i], 0.f) & 0xffffu);
+                }
+        return;
+    }
+    float* Pg = d.P + pbase;
 #pragma unroll
     for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
@@ -296,17 +310,29 @@ wgrad_reduce_kernel(WgradDesc d0, WgradDesc d1, int blocks0, int nz, ColsumJob c
     const size_t total = (size_t)d.G * d.M * d.N;
     const size_t e = (size_t)(blockIdx.x - (first ? 0 : blocks0)) * 256 + threadIdx.x;
     if (e >= total) return;
-    const float* P = d.P + e;
     float s = 0.f;
     int z = 0;
-    for (; z + 8 <= nz; z += 8) {
-        float v[8];
+    if (d.p_bf16) {
+        const uint16_t* P = reinterpret_cast<const uint16_t*>(d.P) + e;
+        for (; z + 8 <= nz; z += 8) {
+            uint16_t v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = P[(size_t)(z + u) * total];
+            for (int u = 0; u < 8; ++u) v[u] = P[(size_t)(z + u) * total];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) s += v[u];
+            for (int u = 0; u < 8; ++u) s += bf16_to_f32(v[u]);
+        }
+        for (; z < nz; ++z) s += bf16_to_f32(P[(size_t)z * total]);
+    } else {
+        const float* P = d.P + e;
+        for (; z + 8 <= nz; z += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = P[(size_t)(z + u) * total];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; z < nz; ++z) s += P[(size_t)z * total];
     }
-    for (; z < nz; ++z) s += P[(size_t)z * total];
     const int nseg = d.N / d.seg_w;
     const size_t rowbase = e / d.N * d.N;
     const int n = (int)(e - rowbase);
