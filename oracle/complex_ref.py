@@ -90,6 +90,32 @@ def bwd(dy, x, R, L, reading: int = 0):
     return dx, dR, dL
 
 
+def fwd_h(x, R, L, reading: int = 0):
+    """y = x conj(M): every row multiplied by the conjugate transpose M* of the Monarch matrix, the second factor
+    of the products M1 M2* of Section 3.1 ("Products of Monarch Matrices"; M* = conjugate transpose, Notation
+    Review).  x (B, k*s) -> y (B, k*p).  With M = Pout BD(L) Pmid BD(R), M* = BD(R)* Pmid^T BD(L)* Pout^T: undo the
+    outer permutation, multiply by the conjugate-transposed blocks of L, undo the mid permutation, multiply by the
+    conjugate-transposed blocks of R."""
+    x = np.asarray(x, dtype=np.complex128)
+    R = np.asarray(R, dtype=np.complex128)
+    L = np.asarray(L, dtype=np.complex128)
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    V = np.zeros((B, k * q), dtype=np.complex128)        # BD(L)* applied to Pout^T x
+    for c in range(k):
+        Wc = np.stack([x[:, l * k + c] for l in range(s)], axis=1)   # (B, s): entries (c, l) of the (k, s) grid
+        V[:, c * q:(c + 1) * q] = Wc @ np.conj(L[c])                  # sum_l conj(L[c][l][r]) W[c][l]
+    T = np.zeros((B, k, q), dtype=np.complex128)         # Pmid^T: position f of the stage-2 input goes back to (kk, j)
+    for f in range(k * q):
+        kk, j = _mid_source(f, k, q, reading)
+        T[:, kk, j] = V[:, f]
+    y = np.zeros((B, k * p), dtype=np.complex128)
+    for kk in range(k):
+        y[:, kk * p:(kk + 1) * p] = T[:, kk, :] @ np.conj(R[kk])     # sum_j conj(R[kk][j][i]) T[kk][j]
+    return y
+
+
 def dft_factors(m: int, inverse: bool = False):
     """(R, L), each (m, m, m) complex128, with  P L P^T R = F_n P  (or F_n^{-1} P), n = m*m."""
     n = m * m

@@ -495,6 +495,35 @@ def test_complex_forward_is_the_literal_dense_product(shape, reading):
     assert np.allclose(got.imag, 0) and np.allclose(got.real, oracle.fwd(x.real, R.real, L.real, reading), rtol=0, atol=1e-12)
 
 
+@pytest.mark.parametrize("reading", READINGS)
+@pytest.mark.parametrize("shape", [(3, 3, 3, 3)] + TINY_RECT[:4])
+def test_conjugate_transpose_apply_is_the_dense_adjoint(shape, reading):
+    """M* of Section 3.1 (conjugate transpose): against x conj(M) with the literal dense M; the adjoint identity
+    <M a, b> = <a, M* b> of the Hermitian inner product; real factors reduce to the real transposed multiply."""
+    k, p, q, s = shape
+    rng = np.random.default_rng(63)
+    a, b = _crand(rng, 4, k * p), _crand(rng, 4, k * s)
+    R, L = _crand(rng, k, q, p), _crand(rng, k, s, q)
+    M = dense.out_perm(k, s) @ scipy.linalg.block_diag(*L) @ dense.mid_perm(k, q, reading) @ scipy.linalg.block_diag(*R)
+    assert np.allclose(complex_ref.fwd_h(b, R, L, reading), b @ np.conj(M), rtol=0, atol=1e-12)
+    lhs = np.sum(complex_ref.fwd(a, R, L, reading) * np.conj(b), axis=1)          # <M a, b>, conjugate-linear in b
+    rhs = np.sum(a * np.conj(complex_ref.fwd_h(b, R, L, reading)), axis=1)        # <a, M* b>
+    assert np.allclose(lhs, rhs, rtol=0, atol=1e-11)
+    got = complex_ref.fwd_h(b.real, R.real, L.real, reading)
+    assert np.allclose(got.imag, 0) and np.allclose(got.real, oracle.fwd_t(b.real, R.real, L.real, reading), rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("m", [2, 3, 4, 8])
+def test_unitary_dft_monarch_times_its_conjugate_transpose_is_n(m):
+    """F F* = n I: the DFT factors applied, then their conjugate transpose, return n times the input (the grid
+    transposition inside the Monarch form is a permutation and cancels with its own transpose)."""
+    n = m * m
+    rng = np.random.default_rng(64)
+    x = _crand(rng, 3, n)
+    R, L = complex_ref.dft_factors(m)
+    assert np.allclose(complex_ref.fwd_h(complex_ref.fwd(x, R, L), R, L), n * x, rtol=0, atol=1e-9 * n)
+
+
 @pytest.mark.parametrize("m", [2, 3, 4, 8])
 def test_dft_is_a_monarch_matrix(m):
     """The 4-step splitting: Monarch(dft_factors) applied to x equals the library FFT of the grid-
