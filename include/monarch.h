@@ -268,6 +268,13 @@ int monarch_project(const void* A, void* R, void* L, int n, int m,
  * order); no workspace.  flags: MONARCH_FLAG_PERM_B only. */
 int monarch_fwd_c64(const void* x, const void* R, const void* L, void* y,
                     int64_t batch, int n_in, int k, int q, int s, void* stream, unsigned flags);
+/* Conjugate transpose applied to every row:  y = x conj(M),  x (batch, k*s) -> y (batch, n_in), complex64.
+ * M* is the second factor of the products M1 M2* of Section 3.1 ("Products of Monarch Matrices"; the star is
+ * the conjugate transpose, Notation Review): M1 M2* x is monarch_fwd_h_c64 with the factors of M2, then
+ * monarch_fwd_c64 with those of M1.  For real factors it is monarch_fwd_t.  Same shapes, layouts, flags and
+ * errors as monarch_fwd_c64 with input and output sizes exchanged; no workspace. */
+int monarch_fwd_h_c64(const void* x, const void* R, const void* L, void* y,
+                      int64_t batch, int n_in, int k, int q, int s, void* stream, unsigned flags);
 int monarch_bwd_c64(const void* dy, const void* x, const void* R, const void* L,
                     void* dx, void* dR, void* dL,
                     int64_t batch, int n_in, int k, int q, int s, void* stream, unsigned flags);

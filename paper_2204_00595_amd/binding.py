@@ -32,7 +32,7 @@ EXPORTS = (
     "monarch_fwd", "monarch_fwd_ex", "monarch_fwd_ws", "monarch_fwd_static", "monarch_fwd_bias", "monarch_fwd_workspace_bytes", "monarch_bwd",
     "monarch_bwd_bias",
     "monarch_bwd_workspace_bytes",
-    "monarch_fwd_t", "monarch_fwd_t_workspace_bytes", "monarch_saved_bytes", "monarch_fwd_save", "monarch_bwd_saved", "monarch_fwd_c64", "monarch_bwd_c64", "monarch_dft_factors", "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy", "monarch_launch_probe",
+    "monarch_fwd_t", "monarch_fwd_t_workspace_bytes", "monarch_saved_bytes", "monarch_fwd_save", "monarch_bwd_saved", "monarch_fwd_c64", "monarch_fwd_h_c64", "monarch_bwd_c64", "monarch_dft_factors", "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy", "monarch_launch_probe",
 )
 
 _lib = None
@@ -86,6 +86,8 @@ def lib() -> ctypes.CDLL:
         L.monarch_bwd_saved.argtypes = [vp, vp, vp, sz, vp, vp, vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
         L.monarch_fwd_c64.restype = ci
         L.monarch_fwd_c64.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, vp, cu]
+        L.monarch_fwd_h_c64.restype = ci
+        L.monarch_fwd_h_c64.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, vp, cu]
         L.monarch_bwd_c64.restype = ci
         L.monarch_bwd_c64.argtypes = [vp] * 7 + [i64, ci, ci, ci, ci, vp, cu]
         L.monarch_dft_factors.restype = ci
@@ -526,6 +528,27 @@ def monarch_fwd_c64(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.
                                    _stream_ptr(stream), flags)
     if rc != MONARCH_OK:
         raise MonarchError(rc, "monarch_fwd_c64")
+    return y
+
+
+def monarch_fwd_h_c64(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.Tensor | None = None,
+                      flags: int = 0, stream=None) -> torch.Tensor:
+    """y = x conj(M) (the conjugate transpose applied to every row) for complex64 tensors: x (B, k*s) -> y (B, k*p)."""
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    dev, dt = x.device, torch.complex64
+    _check(x, "x", (B, k * s), dt, dev)
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    if y is None:
+        y = torch.empty((B, k * p), dtype=dt, device=dev)
+    _check(y, "y", (B, k * p), dt, dev)
+    with torch.cuda.device(dev):
+        rc = lib().monarch_fwd_h_c64(x.data_ptr(), R.data_ptr(), L.data_ptr(), y.data_ptr(), B, k * p, k, q, s,
+                                     _stream_ptr(stream), flags)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_fwd_h_c64")
     return y
 
 

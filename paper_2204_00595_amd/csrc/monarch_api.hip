@@ -362,6 +362,20 @@ int monarch_fwd_c64(const void* x, const void* R, const void* L, void* y, int64_
     return complex_fwd(pb, x, R, L, y, (hipStream_t)stream);
 }
 
+int monarch_fwd_h_c64(const void* x, const void* R, const void* L, void* y, int64_t batch, int n_in, int k, int q, int s,
+                      void* stream, unsigned flags)
+{
+    Problem pb;
+    int rc = make_problem(pb, batch, n_in, k, q, s, MONARCH_F32, flags);
+    if (rc) return rc;
+    if (flags & ~MONARCH_FLAG_PERM_B) return MONARCH_ERR_INVALID;
+    if (!R || !L || ((!x || !y) && batch > 0)) return MONARCH_ERR_INVALID;
+    if (!aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(y, 16)) return MONARCH_ERR_INVALID;
+    if (!complex_fwd_h_supported(pb)) return MONARCH_ERR_UNSUPPORTED;
+    if (batch == 0) return MONARCH_OK;
+    return complex_fwd_h(pb, x, R, L, y, (hipStream_t)stream);
+}
+
 int monarch_bwd_c64(const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR, void* dL,
                     int64_t batch, int n_in, int k, int q, int s, void* stream, unsigned flags)
 {

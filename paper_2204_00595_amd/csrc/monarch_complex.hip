@@ -190,6 +190,64 @@ complex_bwd_kernel(const float2* __restrict__ dy, const float2* __restrict__ x, 
     }
 }
 
+// y = x conj(M): the conjugate transpose M* applied to every row (the second factor of a product M1 M2* of
+// Section 3.1), i.e. the two dx stages of the kernel above on their own: x (B, k*s) -> y (B, k*p).
+// LDS: dws[BM][k*s] (the input with the outer permutation undone), dus[BM][kq].
+template <int BM>
+__global__ void __launch_bounds__(kCThreads)
+complex_fwd_h_kernel(const float2* __restrict__ x, const float2* __restrict__ R, const float2* __restrict__ L,
+                     float2* __restrict__ y, int64_t B, int k, int p, int q, int s, int perm_b)
+{
+    extern __shared__ float2 ldsc[];
+    const int n_in = k * p, kq = k * q, n_out = k * s;
+    float2* dws = ldsc;
+    float2* dus = dws + (size_t)BM * n_out;
+    const int64_t b0 = (int64_t)blockIdx.x * BM;
+    const int tid = threadIdx.x;
+    const bool pb = perm_b != 0;
+    for (int e = tid; e < BM * n_out; e += kCThreads) {
+        const int b = e / n_out, o = e - b * n_out;
+        const int l = o / k, c = o - l * k;
+        const int64_t row = b0 + b;
+        dws[b * n_out + c * s + l] = row < B ? x[row * n_out + o] : make_float2(0.f, 0.f);
+    }
+    __syncthreads();
+    for (int g = tid; g < kq; g += kCThreads) {  // V[c*q + r] = sum_l W[c][l] conj(L[c][l][r])
+        const int c = g / q, r = g - c * q;
+        const float2* Lcol = L + (size_t)c * s * q + r;
+        const float2* dwc = dws + c * s;
+        cf acc[BM];
+#pragma unroll
+        for (int b = 0; b < BM; ++b) acc[b] = cf{0.f, 0.f};
+        for (int l = 0; l < s; ++l) {
+            const cf w = ldc(Lcol + (size_t)l * q);
+#pragma unroll
+            for (int b = 0; b < BM; ++b) acc[b] = cmul_conj_acc(acc[b], ldc(dwc + b * n_out + l), w);
+        }
+#pragma unroll
+        for (int b = 0; b < BM; ++b) dus[b * kq + g] = make_float2(acc[b].re, acc[b].im);
+    }
+    __syncthreads();
+    for (int n = tid; n < n_in; n += kCThreads) {  // y[kk*p + i] = sum_j T[kk][j] conj(R[kk][j][i])
+        const int kk = n / p, i = n - kk * p;
+        const float2* Rcol = R + (size_t)kk * q * p + i;
+        cf acc[BM];
+#pragma unroll
+        for (int b = 0; b < BM; ++b) acc[b] = cf{0.f, 0.f};
+        for (int j = 0; j < q; ++j) {
+            const cf w = ldc(Rcol + (size_t)j * p);
+            const int g = mid_dest(kk * q + j, k, q, pb);
+#pragma unroll
+            for (int b = 0; b < BM; ++b) acc[b] = cmul_conj_acc(acc[b], ldc(dus + b * kq + g), w);
+        }
+#pragma unroll
+        for (int b = 0; b < BM; ++b) {
+            const int64_t row = b0 + b;
+            if (row < B) y[row * n_in + n] = make_float2(acc[b].re, acc[b].im);
+        }
+    }
+}
+
 // R[kk][j][i] = w^(i*j*m),  L[j][l][kk] = w^(kk*j + kk*l*m) (times 1/n for the inverse),  w = exp(-+2 pi i / n):
 // the 4-step splitting of the DFT of the grid-transposed input, P L P^T R = F_n P.  Exponents are reduced
 // mod n in integers and the sine / cosine taken in double precision, then rounded to fp32.
@@ -217,6 +275,7 @@ __global__ void __launch_bounds__(256) dft_factors_kernel(float2* __restrict__ R
 }
 
 size_t fwd_bytes_per_row(const Problem& pb) { return ((size_t)pb.n_in + pb.kq()) * sizeof(float2); }
+size_t fwd_h_bytes_per_row(const Problem& pb) { return ((size_t)pb.n_out() + pb.kq()) * sizeof(float2); }
 size_t bwd_bytes_per_row(const Problem& pb) { return ((size_t)pb.n_in + 2 * (size_t)pb.kq() + pb.n_out()) * sizeof(float2); }
 
 int pick_rows(size_t bytes_per_row)
@@ -231,6 +290,19 @@ int launch_cfwd(const Problem& pb, const void* x, const void* R, const void* L, 
 {
     const size_t lds = (size_t)BM * fwd_bytes_per_row(pb);
     auto kern = complex_fwd_kernel<BM>;
+    if (allow_dynamic_lds((const void*)kern, lds) != hipSuccess) return -4;
+    const int64_t grid = (pb.B + BM - 1) / BM;
+    if (grid > 0x7fffffffLL) return -2;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kCThreads), lds, st, (const float2*)x, (const float2*)R,
+                       (const float2*)L, (float2*)y, pb.B, pb.k, pb.p, pb.q, pb.s, pb.perm_b() ? 1 : 0);
+    return hip_status(hipGetLastError());
+}
+
+template <int BM>
+int launch_cfwd_h(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
+{
+    const size_t lds = (size_t)BM * fwd_h_bytes_per_row(pb);
+    auto kern = complex_fwd_h_kernel<BM>;
     if (allow_dynamic_lds((const void*)kern, lds) != hipSuccess) return -4;
     const int64_t grid = (pb.B + BM - 1) / BM;
     if (grid > 0x7fffffffLL) return -2;
@@ -258,6 +330,17 @@ int launch_cbwd(const Problem& pb, const void* dy, const void* x, const void* R,
 
 bool complex_fwd_supported(const Problem& pb) { return pick_rows(fwd_bytes_per_row(pb)) > 0; }
 bool complex_bwd_supported(const Problem& pb) { return pick_rows(bwd_bytes_per_row(pb)) > 0; }
+bool complex_fwd_h_supported(const Problem& pb) { return pick_rows(fwd_h_bytes_per_row(pb)) > 0; }
+
+int complex_fwd_h(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
+{
+    switch (pick_rows(fwd_h_bytes_per_row(pb))) {
+        case 4: return launch_cfwd_h<4>(pb, x, R, L, y, st);
+        case 2: return launch_cfwd_h<2>(pb, x, R, L, y, st);
+        case 1: return launch_cfwd_h<1>(pb, x, R, L, y, st);
+        default: return -2;
+    }
+}
 
 int complex_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st)
 {

@@ -63,6 +63,9 @@ bool complex_bwd_supported(const Problem& pb);
 int complex_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
 int complex_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
                 void* dL, hipStream_t st);
+// y = x conj(M) (the conjugate transpose applied to every row): x (B, k*s) -> y (B, k*p)
+bool complex_fwd_h_supported(const Problem& pb);
+int complex_fwd_h(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
 int launch_dft_factors(void* R, void* L, int m, int inverse, hipStream_t st);
 
 // ---- MFMA kernels for the shapes they are instantiated for (bf16 / fp32 matrix cores) ----

@@ -705,9 +705,11 @@ def test_complex_forward_and_backward(B, case, reading):
     y = B.monarch_fwd_c64(cdev(x), cdev(R), cdev(L), flags=flags)
     dx, dR, dL = B.monarch_bwd_c64(cdev(dy), cdev(x), cdev(R), cdev(L), flags=flags)
     torch.cuda.synchronize()
-    want = [complex_ref.fwd(x, R, L, reading)] + list(complex_ref.bwd(dy, x, R, L, reading))
+    yh = B.monarch_fwd_h_c64(cdev(dy), cdev(R), cdev(L), flags=flags)   # conjugate transpose applied to the rows of dy
+    torch.cuda.synchronize()
+    want = [complex_ref.fwd(x, R, L, reading)] + list(complex_ref.bwd(dy, x, R, L, reading)) + [complex_ref.fwd_h(dy, R, L, reading)]
     errs = {}
-    for nm, got, w in zip(("y", "dx", "dR", "dL"), (y, dx, dR, dL), want):
+    for nm, got, w in zip(("y", "dx", "dR", "dL", "xMh"), (y, dx, dR, dL, yh), want):
         g = got.cpu().numpy().astype(np.complex128)
         errs[nm] = float(np.linalg.norm((g - w).ravel()) / np.linalg.norm(w.ravel()))
     print("\n  %s %s" % (name, " ".join("%s=%.2e" % kv for kv in errs.items())), flush=True)
@@ -715,6 +717,20 @@ def test_complex_forward_and_backward(B, case, reading):
     # empty batch: no-op forward, zero gradients
     e = B.monarch_bwd_c64(cdev(dy[:0]), cdev(x[:0]), cdev(R), cdev(L), flags=flags)
     assert e[0].shape == (0, k * p) and not bool(e[1].any()) and not bool(e[2].any())
+    assert B.monarch_fwd_h_c64(cdev(dy[:0]), cdev(R), cdev(L), flags=flags).shape == (0, k * p)
+
+
+@pytest.mark.parametrize("m", [4, 16, 64])
+def test_dft_monarch_times_its_conjugate_transpose_is_n(B, m):
+    """F F* = n I on the GPU: monarch_fwd_c64 with the DFT factors, then monarch_fwd_h_c64 with the same factors,
+    returns n x (the product M M* of Section 3.1 with M1 = M2 = the DFT Monarch matrix, applied right to left)."""
+    n = m * m
+    x = cnormal(8200 + m, (13, n))
+    R, L = B.monarch_dft_factors(m, False)
+    back = B.monarch_fwd_h_c64(B.monarch_fwd_c64(cdev(x), R, L), R, L).cpu().numpy().astype(np.complex128)
+    err = float(np.linalg.norm(back - n * x) / np.linalg.norm(n * x))
+    print("\n  m=%d: %.2e" % (m, err), flush=True)
+    assert err <= TOL["f32"]
 
 
 @pytest.mark.parametrize("m", [2, 3, 8, 16, 64])

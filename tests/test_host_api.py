@@ -273,6 +273,17 @@ def test_complex_calls_reject_bad_arguments_without_a_gpu(binding):
     assert fwd(flags=binding.MONARCH_FLAG_GENERIC) == binding.MONARCH_ERR_INVALID
     assert fwd(n_in=4 * 40000, q=40000) == binding.MONARCH_ERR_UNSUPPORTED     # one row does not fit the LDS
 
+    def fwd_h(x=p, R=p, Lp=p, y=p, batch=0, n_in=16, k=4, q=4, s=4, flags=0):
+        return L.monarch_fwd_h_c64(x, R, Lp, y, batch, n_in, k, q, s, None, flags)
+
+    assert fwd_h() == binding.MONARCH_OK
+    assert fwd_h(Lp=None) == binding.MONARCH_ERR_INVALID
+    assert fwd_h(x=None, batch=1) == binding.MONARCH_ERR_INVALID
+    assert fwd_h(y=p + 8) == binding.MONARCH_ERR_INVALID
+    assert fwd_h(n_in=18) == binding.MONARCH_ERR_INVALID
+    assert fwd_h(flags=binding.MONARCH_FLAG_WGRAD_F32) == binding.MONARCH_ERR_INVALID
+    assert fwd_h(n_in=4 * 4, s=40000, q=40000) == binding.MONARCH_ERR_UNSUPPORTED     # one row does not fit the LDS
+
     def bwd(ptrs=(p,) * 7, batch=1, n_in=16, flags=0):
         return L.monarch_bwd_c64(*ptrs, batch, n_in, 4, 4, 4, None, flags)
 
