@@ -214,7 +214,7 @@ class Layer:
 
 
 def measure_layer(name: str, with_dense: bool = True, with_extras: bool = False, layer: Layer | None = None,
-                  calls: int = TIMED_CALLS, copy_gbs: float | None = None):
+                  calls: int = TIMED_CALLS, copy_gbs: float | None = None, variants: bool = True):
     """One configuration's block: per-call times of monarch_fwd and monarch_bwd (and of the variants with a
     workspace / a saved intermediate), rooflines, counter traffic, dense comparator."""
     import numpy as np
@@ -230,8 +230,8 @@ def measure_layer(name: str, with_dense: bool = True, with_extras: bool = False,
     fwd_med, fwd_min, fwd_mean, ncalls = timed_runs(ly.fwd, calls)
     bwd_med, bwd_min, bwd_mean, _ = timed_runs(ly.bwd, calls)
     # the same calls on one buffer set ("warm": repeats can be served by the 256 MB Infinity Cache)
-    fwd_warm = timed_runs(lambda i: ly.fwd(0), calls // 2)[0]
-    bwd_warm = timed_runs(lambda i: ly.bwd(0), calls // 2)[0]
+    fwd_warm = timed_runs(lambda i: ly.fwd(0), calls // 2)[0] if variants else None
+    bwd_warm = timed_runs(lambda i: ly.bwd(0), calls // 2)[0] if variants else None
 
     def fwd_ws_only(i):
         xs, _, y, _ = sets[i % nsets]
@@ -245,7 +245,7 @@ def measure_layer(name: str, with_dense: bool = True, with_extras: bool = False,
     fwd_ws_packed_ms = timed_runs(fwd_ws_packed, calls // 2)[0] if fneed else None
 
     # forward that saves the vector between the factors + backward that reads it instead of recomputing
-    sneed = binding.monarch_saved_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, code, 0)
+    sneed = binding.monarch_saved_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, code, 0) if variants else 0
     fwd_save_ms = bwd_saved_ms = None
     if sneed:
         svs = [torch.empty(sneed, dtype=torch.uint8, device=dev) for _ in range(nsets)]
@@ -266,7 +266,7 @@ def measure_layer(name: str, with_dense: bool = True, with_extras: bool = False,
         "workload": name, "shape": "k=%d p=%d q=%d s=%d (%d->%d), B=%d, %s" % (sh.k, sh.p, sh.q, sh.s, sh.n_in, sh.n_out, sh.B, sh.dtype),
         "timed_calls": ncalls, "statistic": "median / min over %d runs of %d consecutive calls (time per call of a run)" % (RUNS, ncalls // RUNS),
         "fwd_us": fwd_med * 1e3, "fwd_us_min": fwd_min * 1e3, "bwd_us": bwd_med * 1e3, "bwd_us_min": bwd_min * 1e3,
-        "fwd_us_warm": fwd_warm * 1e3, "bwd_us_warm": bwd_warm * 1e3,  # one buffer set instead of the rotation: cache-assisted
+        "fwd_us_warm": fwd_warm and fwd_warm * 1e3, "bwd_us_warm": bwd_warm and bwd_warm * 1e3,  # one buffer set instead of the rotation: cache-assisted
         "fwd_kernel": binding.monarch_kernel_name(0, sh.n_in, sh.k, sh.q, sh.s, code),
         "bwd_kernel": binding.monarch_kernel_name(1, sh.n_in, sh.k, sh.q, sh.s, code),
         # monarch_fwd_ws (weights packed into a caller workspace, pack included / pack skipped); null without such a kernel
@@ -289,7 +289,7 @@ def measure_layer(name: str, with_dense: bool = True, with_extras: bool = False,
         t = traffic_of(name, "monarch_" + ps)
         out[ps + "_traffic_bytes"] = t  # rocprofv3 FETCH_SIZE + WRITE_SIZE per call (profiles/), null if not profiled
         out[ps + "_traffic_ratio"] = (t / out[ps + "_algorithmic_bytes"]) if t else None
-    if small:
+    if small and variants:
         out["note"] = ("launch-latency bound: %d KB and %.1f MFLOP per forward; the eager per-call times above include the host's "
                        "cost of issuing a launch from Python (see launch_floor_us); *_us_graph are the same calls replayed from a "
                        "captured HIP graph" % (sh.fwd_bytes() // 1000, sh.fwd_flops() / 1e6))
@@ -505,6 +505,8 @@ def _main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--extras", action="store_true", help="also time the other entry points (bias, transposed, dense form, complex, projection)")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="time monarch_fwd, monarch_fwd_ws and monarch_bwd only (profiler runs: one kernel set per call)")
     ap.add_argument("--layers", action="store_true", help="also time the other layer shapes of the same models (extra keys)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -609,7 +611,8 @@ def _main():
     configs = {}
     for name in names:
         progress("configuration %s" % name)
-        configs[name] = measure_layer(name, with_dense=not args.no_dense, with_extras=args.extras, copy_gbs=copy_gbs)
+        configs[name] = measure_layer(name, with_dense=not args.no_dense, with_extras=args.extras, copy_gbs=copy_gbs,
+                                      variants=not args.no_variants)
         if name == "sq256_f32":
             configs[name]["launch_floor_us"] = floor["median_us"]
         torch.cuda.empty_cache()
