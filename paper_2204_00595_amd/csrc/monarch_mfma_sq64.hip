@@ -163,11 +163,52 @@ __device__ __forceinline__ void column_stage(const Lane& t_, const uint16_t* __r
     }
 }
 
+// Column stage of the backward for half h, in place: wave w multiplies the four blocks c = 32h + 4w + cc of the packed
+// factor W2 (both 32-row output tiles) with line (b, 4w + cc) of the exchange buffer and writes the 64 results over that
+// same line: out[b][4w + cc][i], 128 bytes.  Every lane reads and writes its own row b = ln only and no other wave
+// touches these four lines, so the order of one wave's LDS operations is all the synchronisation the overwrite needs;
+// the results never wait in registers for the buffer to die (64 registers, which the kernel otherwise spills).
+__device__ __forceinline__ void column_stage_inplace(const Lane& t_, const uint16_t* __restrict__ W2, unsigned char* ldsb, int h)
+{
+    unsigned char* line0 = ldsb + (size_t)t_.ln * SQ_ROWB + (4 * t_.wave) * 128;
+    // fragment (block c, tile lt, K-step u) at ((c*2 + lt)*4 + u) * 512 elements, + lane * 8: the eight (block, tile)
+    // steps of this wave are contiguous, n = 2*cc + lt
+    const uint16_t* Wrow = W2 + ((size_t)(32 * h + 4 * t_.wave) * 2 * 4 * 64 + t_.lane) * 8;
+    u32x4 la[2][4], ua[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) la[0][u] = ldg128(Wrow + (size_t)u * 512);
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+        const int cc = n >> 1, lt = n & 1, s = n & 1;
+        unsigned char* line = line0 + cc * 128;
+        __builtin_amdgcn_sched_barrier(0);
+        if (n + 1 < 8) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) la[s ^ 1][u] = ldg128(Wrow + (size_t)((n + 1) * 4 + u) * 512);
+        }
+        if (lt == 0) {  // the operand line is read once, before either tile's results are written over it
+#pragma unroll
+            for (int u = 0; u < 4; ++u) ua[u] = *reinterpret_cast<const u32x4*>(line + 64 * t_.g + 16 * u);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        f32x16 acc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc = mfma32(as_bf16x8(la[s][u]), as_bf16x8(ua[u]), acc);
+        // acc[i] = D[out = 32*lt + 8*(i/4) + 4*g + i%4][b = ln]
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4)
+            *reinterpret_cast<u32x2*>(line + (32 * lt + 8 * i4 + 4 * t_.g) * 2) =
+                u32x2{pack_bf16x2(acc[4 * i4], acc[4 * i4 + 1]), pack_bf16x2(acc[4 * i4 + 2], acc[4 * i4 + 3])};
+    }
+}
+
 // Copies a 32 x 32-line LDS tile to global memory in full lines: wave w takes rows b = 4w..4w+3,
 // 128 lines, eight per instruction (1 KiB contiguous).  Line (b, jl) goes to
 // dst[(b0 + b) * 4096 + (col0 + jl) * 64 ..].  SWZ: tile rows are 4096 bytes and the 16-byte piece
 // index is XOR-ed with b % 8; otherwise rows are SQ_ROWB bytes, pieces in order.
-template <bool SWZ>
+template <bool SWZ, bool NT = SWZ>
 __device__ __forceinline__ void copy_out(const Lane& t_, const unsigned char* ldsb, uint16_t* __restrict__ dst,
                                          int64_t b0, int64_t B, int col0)
 {
@@ -180,7 +221,7 @@ __device__ __forceinline__ void copy_out(const Lane& t_, const unsigned char* ld
         const u32x4 v = *reinterpret_cast<const u32x4*>(src);
         if (b0 + b < B) {
             uint16_t* p = dst + (b0 + b) * N64 + (size_t)(col0 + jl) * M64 + 8 * pc;
-            if (SWZ) stg128_nt(p, v);  // final outputs: streamed; workspace copies stay cacheable for the next kernel
+            if (NT) stg128_nt(p, v);  // final outputs: streamed; workspace copies stay cacheable for the next kernel
             else *reinterpret_cast<u32x4*>(p) = v;
         }
     }
@@ -351,31 +392,20 @@ bwd_sq64_data_kernel(const uint16_t* __restrict__ dW, const uint16_t* __restrict
     // layout of the workspace copy
     block_stage<true>(t, dW + row * N64 + 32 * g, LT, ldsb, pk1);
 
-    // ---- adjoint of step 1: dx[b][kk*64 + i] = sum_j RT[kk][i][j] dY1[b][kk][j]
-    const int kg = t.wave & 3, it = t.wave >> 2;
+    // ---- adjoint of step 1: dx[b][kk*64 + i] = sum_j RT[kk][i][j] dY1[b][kk][j], written over the dY1 lines (see
+    // column_stage_inplace): line (b, kk) of the buffer becomes dx[b][kk*64 ..], which is also the layout of dx itself
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         if (h) exchange_write(t, ldsb, pk1);
         __syncthreads();
-        if constexpr (!DX_ONLY) copy_out<false>(t, ldsb, dY1ws, b0, B, 32 * h);
-        // dxr[cc][i4]: dx[b = ln][kk = 32h + 8kg + cc][i = 32*it + 8*i4 + 4*g .. +3]
-        u32x2 dxr[8][4];
-        column_stage<true>(t, RT, ldsb, h, [&](int cc, const f32x16& acc) {
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4)
-                dxr[cc][i4] = u32x2{pack_bf16x2(acc[4 * i4], acc[4 * i4 + 1]), pack_bf16x2(acc[4 * i4 + 2], acc[4 * i4 + 3])};
-        });
-        __syncthreads();  // every wave is done with the dY1 half: the space becomes the dx tile
-#pragma unroll
-        for (int cc = 0; cc < 8; ++cc)
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                const int piece = (4 * it + i4) ^ (ln & 7);
-                *reinterpret_cast<u32x2*>(ldsb + (size_t)ln * 4096 + (8 * kg + cc) * 128 + piece * 16 + 8 * g) = dxr[cc][i4];
-            }
+        if constexpr (!DX_ONLY) {
+            copy_out<false>(t, ldsb, dY1ws, b0, B, 32 * h);
+            __syncthreads();  // every wave has copied its share of the dY1 half before lines are overwritten
+        }
+        column_stage_inplace(t, RT, ldsb, h);
         __syncthreads();
-        copy_out<true>(t, ldsb, dx, b0, B, 32 * h);
-        __syncthreads();  // the tile is read before the second half overwrites it
+        copy_out<false, true>(t, ldsb, dx, b0, B, 32 * h);
+        __syncthreads();  // the lines are read before the second half overwrites them
     }
 }
 
