@@ -557,3 +557,83 @@ def test_complex_gradients_match_unit_step_differences(shape, reading):
                 args = [x, R, L]
                 args[which] = moved
                 assert abs(loss(*args) - base - part) < 1e-10, (which, idx, step)
+
+
+# ----------------------------------------------------- the block's nonlinearity ----
+
+def test_gelu_tanh_form_against_the_exact_form_and_the_library():
+    """gelu(v) = v Phi(v) (Hendrycks & Gimpel) with Phi from scipy's erf; the tanh form stays within 1e-3
+    of it; torch's own tanh-form routine (float64, CPU) agrees to rounding."""
+    import scipy.special
+    torch = pytest.importorskip("torch")
+    from oracle import activation
+    v = np.linspace(-12.0, 12.0, 4801)
+    exact = 0.5 * v * (1.0 + scipy.special.erf(v / np.sqrt(2.0)))
+    got = activation.gelu(v)
+    assert np.max(np.abs(got - exact)) < 1e-3
+    assert np.max(np.abs(got - exact)) > 1e-5  # it is the approximation, not the exact form
+    lib = torch.nn.functional.gelu(torch.tensor(v, dtype=torch.float64), approximate="tanh").numpy()
+    assert np.max(np.abs(got - lib)) < 1e-14
+
+
+def test_gelu_special_values_and_reflection_identity():
+    """gelu(0) = 0, gelu(v) -> v and gelu(-v) -> 0 for large v; tanh is odd, so
+    gelu(v) - gelu(-v) = v exactly, and differentiating that, gelu'(v) + gelu'(-v) = 1; gelu'(0) = 1/2."""
+    from oracle import activation
+    assert activation.gelu(0.0) == 0.0
+    assert abs(activation.gelu(20.0) - 20.0) < 1e-12 and abs(activation.gelu(-20.0)) < 1e-12
+    v = np.linspace(0.0, 9.0, 901)
+    assert np.max(np.abs(activation.gelu(v) - activation.gelu(-v) - v)) < 1e-14
+    assert np.max(np.abs(activation.gelu_grad(v) + activation.gelu_grad(-v) - 1.0)) < 1e-14
+    assert activation.gelu_grad(0.0) == 0.5
+    # the minimum of gelu sits where its derivative changes sign, near v = -0.75 (value about -0.17)
+    vv = np.linspace(-2.0, 0.0, 20001)
+    i = int(np.argmin(activation.gelu(vv)))
+    assert abs(vv[i] + 0.7525) < 2e-3 and abs(activation.gelu(vv[i]) + 0.17) < 1e-3
+    assert abs(activation.gelu_grad(vv[i])) < 1e-3
+
+
+def test_gelu_grad_matches_central_differences():
+    from oracle import activation
+    v = np.linspace(-6.0, 6.0, 241)
+    h = 1e-5
+    fd = (activation.gelu(v + h) - activation.gelu(v - h)) / (2 * h)
+    assert np.max(np.abs(activation.gelu_grad(v) - fd)) < 1e-9
+
+
+@pytest.mark.parametrize("reading", READINGS)
+@pytest.mark.parametrize("shape", [(3, 3, 3, 3)] + TINY_RECT[:4])
+def test_layer_with_gelu_matches_autograd_through_the_dense_matrix(shape, reading):
+    """Both layers of a feed-forward block in one graph, float64 torch on the CPU, with the explicit dense
+    matrices: h = x M1^T + b1, g = gelu(h), y = g M2^T + b2.  The first layer's forward gives (h, g); the
+    second layer's backward at input g = gelu(h) gives d/dh, dR2, dL2, db2."""
+    torch = pytest.importorskip("torch")
+    from oracle import activation
+    k, p, q, s = shape
+    rng = np.random.default_rng(101 + 13 * sum(shape) + reading)
+    B = 4
+    x, R1, L1, _ = _rand(rng, k, p, q, s, B=B)
+    b1 = rng.standard_normal(k * s)
+    # second layer: n_in = k*s -> blocks of p2 = s inputs, q outputs, then p outputs per block
+    R2, L2 = rng.standard_normal((k, q, s)), rng.standard_normal((k, p, q))
+    b2 = rng.standard_normal(k * p)
+    dy = rng.standard_normal((B, k * p))
+
+    h, g = activation.fwd_bias_gelu(x, R1, L1, b1, reading)
+    M1 = torch.tensor(dense.monarch_dense(R1, L1, reading))
+    ht = torch.tensor(x) @ M1.T + torch.tensor(b1)
+    assert oracle.rel_fro(h, ht.numpy()) < 1e-13
+    assert oracle.rel_fro(g, torch.nn.functional.gelu(ht, approximate="tanh").numpy()) < 1e-13
+
+    hl = torch.tensor(h, requires_grad=True)
+    R2t, L2t, b2t = (torch.tensor(a, requires_grad=True) for a in (R2, L2, b2))
+    Pmid = torch.tensor(dense.mid_perm(k, q, reading))
+    Pout = torch.tensor(dense.out_perm(k, p))
+    M2 = Pout @ torch.block_diag(*L2t) @ Pmid @ torch.block_diag(*R2t)
+    y = torch.nn.functional.gelu(hl, approximate="tanh") @ M2.T + b2t
+    y.backward(torch.tensor(dy))
+    dh, dR2, dL2, db2 = activation.bwd_bias_gelu_in(dy, h, R2, L2, reading)
+    assert oracle.rel_fro(dh, hl.grad.numpy()) < 1e-13
+    assert oracle.rel_fro(dR2, R2t.grad.numpy()) < 1e-13
+    assert oracle.rel_fro(dL2, L2t.grad.numpy()) < 1e-13
+    assert oracle.rel_fro(db2, b2t.grad.numpy()) < 1e-13
