@@ -425,6 +425,62 @@ class Pair:
             fn()
 
 
+def measure_ffn_block():
+    """The feed-forward block of GPT-2 medium around the pair: biases and the nonlinearity (tanh-form GELU) between
+    the layers, forward and backward, 16384 rows.  `fused`: the nonlinearity runs in the layers' own epilogues
+    (monarch_fwd_bias_gelu, monarch_bwd_bias_gelu_in); `separate_passes`: the plain layer calls with the
+    framework's elementwise gelu / gelu_backward kernels between them."""
+    import torch
+    from paper_2204_00595_amd import binding, synth
+    s1, s2 = synth.WORKLOADS["gpt2m_fc1"], synth.WORKLOADS["gpt2m_fc2"]
+    dev, dt = torch.device("cuda:0"), torch.bfloat16
+    B = s1.B
+    g = _gen_rows(B)
+    x, R1, L1, _ = synth.make_inputs(s1, rows=g)
+    _, R2, L2, dy = synth.make_inputs(s2, rows=g)
+    R1, L1, R2, L2 = (torch.from_numpy(a).to(dev).to(dt) for a in (R1, L1, R2, L2))
+    b1 = torch.from_numpy(synth.quantize(synth.normal(811, (s1.n_out,)), "bf16")).to(dev).to(dt)
+    b2 = torch.from_numpy(synth.quantize(synth.normal(812, (s2.n_out,)), "bf16")).to(dev).to(dt)
+    x0, dy0 = (torch.from_numpy(a).to(dev).to(dt).repeat(B // g, 1) for a in (x, dy))
+    sets = []
+    for i in range(2):
+        xs = x0 if i == 0 else x0.roll(i, 0).contiguous()
+        dys = dy0 if i == 0 else dy0.roll(i, 0).contiguous()
+        hid = lambda: torch.empty((B, s1.n_out), dtype=dt, device=dev)
+        sets.append((xs, dys, hid(), hid(), torch.empty((B, s2.n_out), dtype=dt, device=dev), hid(), torch.empty_like(xs)))
+    gR1, gL1, gR2, gL2, gb1, gb2 = (torch.empty_like(t) for t in (R1, L1, R2, L2, b1, b2))
+    fneed = max(binding.monarch_fwd_workspace_bytes(B, s.n_in, s.k, s.q, s.s, 1, 0) for s in (s1, s2))
+    bneed = max(binding.monarch_bwd_workspace_bytes(B, s.n_in, s.k, s.q, s.s, 1, 0) for s in (s1, s2))
+    ws = torch.empty(max(fneed, bneed), dtype=torch.uint8, device=dev)
+
+    def fused(i):
+        xs, dys, h, a, y, dh, dx = sets[i % 2]
+        binding.monarch_fwd_bias_gelu(xs, R1, L1, b1, h, a, workspace=ws)
+        binding.monarch_fwd_bias(a, R2, L2, b2, y, workspace=ws)
+        binding.monarch_bwd_bias_gelu_in(dys, a, h, R2, L2, dh, gR2, gL2, gb2, workspace=ws)
+        binding.monarch_bwd_bias(dh, xs, R1, L1, dx, gR1, gL1, gb1, workspace=ws)
+
+    def separate(i):
+        xs, dys, h, a, y, dh, dx = sets[i % 2]
+        binding.monarch_fwd_bias(xs, R1, L1, b1, h, workspace=ws)
+        torch.ops.aten.gelu.out(h, approximate="tanh", out=a)
+        binding.monarch_fwd_bias(a, R2, L2, b2, y, workspace=ws)
+        binding.monarch_bwd_bias(dys, a, R2, L2, dh, gR2, gL2, gb2, workspace=ws)
+        torch.ops.aten.gelu_backward.grad_input(dh, h, approximate="tanh", grad_input=dh)
+        binding.monarch_bwd_bias(dh, xs, R1, L1, dx, gR1, gL1, gb1, workspace=ws)
+
+    fmed, fmin, _, n = timed_runs(fused, 50)
+    smed, smin, _, _ = timed_runs(separate, 50)
+    flops = sum(s.fwd_flops() + s.bwd_flops() for s in (s1, s2))
+    return {"workload": "gpt2m feed-forward block 1024->4096->gelu->1024 with biases, B=%d, bf16, fwd+bwd" % B,
+            "fused_epilogues_us": fmed * 1e3, "fused_epilogues_us_min": fmin * 1e3,
+            "separate_passes_us": smed * 1e3, "separate_passes_us_min": smin * 1e3,
+            "timed_steps": n, "fused_tflops": flops / (fmed * 1e-3) / 1e12,
+            "note": "separate_passes = the same layer calls with the framework's elementwise gelu and gelu_backward "
+                    "kernels between them (one more read and one more write of the hidden activation forward, "
+                    "two reads and a write backward)"}
+
+
 def cpu_baseline(workload: str, cpu_seconds: float = 20.0):
     """The CPU oracle as it stands, timed on this host: the same step (for the pair: both layers, forward and
     backward, chained in fp64) over the first rows of the workload, sized to about `cpu_seconds` core-seconds."""
@@ -617,6 +673,10 @@ def _main():
             configs[name]["launch_floor_us"] = floor["median_us"]
         torch.cuda.empty_cache()
     detail["configs"] = configs
+    if not args.only and not args.no_variants:
+        progress("feed-forward block with the nonlinearity")
+        detail["ffn_block"] = measure_ffn_block()
+        torch.cuda.empty_cache()
     if args.layers:
         detail["model_layers"] = {}
         for name in synth.MODEL_LAYERS:

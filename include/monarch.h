@@ -174,6 +174,40 @@ int monarch_bwd_bias(const void* dy, const void* x, const void* R, const void* L
                      monarch_dtype dtype, void* stream,
                      void* workspace, size_t workspace_bytes, unsigned flags);
 
+/* The two layers of a feed-forward block with the nonlinearity between them applied inside the layers'
+ * own kernels, so that the block's hidden activation is not read and re-written by separate elementwise
+ * passes.  Section 4 replaces the dense weight matrices of the feed-forward blocks of ViT, MLP-Mixer,
+ * BERT and GPT-2 by Monarch matrices and leaves the blocks otherwise unchanged; the paper does not
+ * write the blocks' nonlinearity down (it names kernel fusion as a further speed-up it expects, at
+ * the end of Section 5.2).  All four models use GELU; taken here in its tanh form (GPT-2's),
+ *     gelu(v) = v/2 * (1 + tanh( sqrt(2/pi) * (v + 0.044715 v^3) )).
+ *
+ * monarch_fwd_bias_gelu (the block's first layer):
+ *     y_pre[b][o] = (x M^T)[b][o] + bias[o],    y[b][o] = gelu(y_pre[b][o]).
+ * Arguments as monarch_fwd_bias.  `bias` may be NULL (no bias).  `y_pre` (batch x k*s elements of
+ * `dtype`, 16-byte aligned) receives the value before the nonlinearity, which the backward pass
+ * needs; NULL skips it (inference).  In the kernels with the fused epilogue (bf16, k = 4 wide blocks,
+ * with workspace) gelu is applied to the fp32 sum before its rounding to `dtype`; for every other
+ * shape y_pre is rounded to `dtype` first and a second pass computes y from it.
+ *
+ * monarch_bwd_bias_gelu_in (the block's second layer, whose input is x = gelu(x_pre)):
+ *     dx_pre[b][i] = (dy M)[b][i] * gelu'(x_pre[b][i]),
+ * dR, dL, dbias exactly as monarch_bwd_bias for the input x.  `x` is what the first layer wrote as y,
+ * `x_pre` what it wrote as y_pre (same shape as x; 16-byte aligned; required).  dx_pre is then the
+ * upstream gradient dy of the first layer's monarch_bwd_bias.  Fused into the dx epilogue of the
+ * bf16 k = 4 backward; a second pass over dx elsewhere.  Workspace and errors as monarch_bwd_bias. */
+int monarch_fwd_bias_gelu(const void* x, const void* R, const void* L, const void* bias,
+                          void* y_pre, void* y,
+                          int64_t batch, int n_in, int k, int q, int s,
+                          monarch_dtype dtype, void* stream,
+                          void* workspace, size_t workspace_bytes, unsigned flags);
+int monarch_bwd_bias_gelu_in(const void* dy, const void* x, const void* x_pre,
+                             const void* R, const void* L,
+                             void* dx_pre, void* dR, void* dL, void* dbias,
+                             int64_t batch, int n_in, int k, int q, int s,
+                             monarch_dtype dtype, void* stream,
+                             void* workspace, size_t workspace_bytes, unsigned flags);
+
 /* Forward and backward that share the vector between the two factors instead of recomputing it (the
  * paper differentiates the multiply automatically, Section 4, which keeps the intermediate of step 1
  * for the backward pass; monarch_bwd recomputes it from x).  monarch_fwd_save is monarch_fwd_ex that

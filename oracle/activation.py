@@ -50,12 +50,15 @@ def fwd_bias_gelu(x, R, L, bias, reading: int = READING_A):
     return y_pre, gelu(y_pre)
 
 
-def bwd_bias_gelu_in(dy, x_pre, R, L, reading: int = READING_A):
+def bwd_bias_gelu_in(dy, x_pre, R, L, reading: int = READING_A, x=None):
     """Gradients of  y = gelu(x_pre) M^T + bias  for the upstream gradient dy.
 
     The multiply sees x = gelu(x_pre): dR, dL and dbias are those of the plain layer at that x, and the
     gradient with respect to x goes through gelu elementwise:  dx_pre = dx * gelu'(x_pre).
+    `x`: the layer's input as the caller holds it (gelu(x_pre) rounded to a storage type), used in place
+    of the exact gelu(x_pre) when given.
     """
     x_pre = np.asarray(x_pre, dtype=np.float64)
-    dx, dR, dL, dbias = bwd_bias(dy, gelu(x_pre), R, L, reading)
+    x = gelu(x_pre) if x is None else np.asarray(x, dtype=np.float64)
+    dx, dR, dL, dbias = bwd_bias(dy, x, R, L, reading)
     return dx * gelu_grad(x_pre), dR, dL, dbias

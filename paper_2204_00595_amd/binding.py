@@ -30,7 +30,7 @@ MONARCH_FLAG_WS_PACKED = 8
 # every symbol include/monarch.h declares
 EXPORTS = (
     "monarch_fwd", "monarch_fwd_ex", "monarch_fwd_ws", "monarch_fwd_static", "monarch_fwd_bias", "monarch_fwd_workspace_bytes", "monarch_bwd",
-    "monarch_bwd_bias",
+    "monarch_bwd_bias", "monarch_fwd_bias_gelu", "monarch_bwd_bias_gelu_in",
     "monarch_bwd_workspace_bytes",
     "monarch_fwd_t", "monarch_fwd_t_workspace_bytes", "monarch_saved_bytes", "monarch_fwd_save", "monarch_bwd_saved", "monarch_fwd_c64", "monarch_fwd_h_c64", "monarch_bwd_c64", "monarch_dft_factors", "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy", "monarch_launch_probe",
 )
@@ -66,6 +66,10 @@ def lib() -> ctypes.CDLL:
         L.monarch_fwd_bias.argtypes = [vp, vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
         L.monarch_bwd_bias.restype = ci
         L.monarch_bwd_bias.argtypes = [vp] * 8 + [i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
+        L.monarch_fwd_bias_gelu.restype = ci
+        L.monarch_fwd_bias_gelu.argtypes = [vp] * 6 + [i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
+        L.monarch_bwd_bias_gelu_in.restype = ci
+        L.monarch_bwd_bias_gelu_in.argtypes = [vp] * 9 + [i64, ci, ci, ci, ci, ci, vp, vp, sz, cu]
         L.monarch_fwd_workspace_bytes.restype = sz
         L.monarch_fwd_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci, cu]
         L.monarch_bwd.restype = ci
@@ -382,6 +386,88 @@ def monarch_bwd_bias(dy: torch.Tensor, x: torch.Tensor, R: torch.Tensor, L: torc
     if rc != MONARCH_OK:
         raise MonarchError(rc, "monarch_bwd_bias")
     return dx, dR, dL, dbias
+
+
+def monarch_fwd_bias_gelu(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, bias: torch.Tensor | None = None,
+                          y_pre: torch.Tensor | None = None, y: torch.Tensor | None = None, want_pre: bool = True,
+                          workspace: torch.Tensor | None = None, flags: int = 0, stream=None):
+    """(y_pre, y) with y_pre = x M^T + bias and y = gelu(y_pre) (tanh form).  `want_pre=False` and no y_pre
+    buffer: the pre-activation is not written and None is returned in its place."""
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    dev, dt = x.device, x.dtype
+    _check(x, "x", (B, k * p), dt, dev)
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    if bias is not None:
+        _check(bias, "bias", (k * s,), dt, dev)
+    if y is None:
+        y = torch.empty((B, k * s), dtype=dt, device=dev)
+    if y_pre is None and want_pre:
+        y_pre = torch.empty((B, k * s), dtype=dt, device=dev)
+    _check(y, "y", (B, k * s), dt, dev)
+    if y_pre is not None:
+        _check(y_pre, "y_pre", (B, k * s), dt, dev)
+    need = monarch_fwd_workspace_bytes(B, k * p, k, q, s, _dtype_code(x), flags)
+    if workspace is None and need:
+        if flags & MONARCH_FLAG_WS_PACKED:
+            raise ValueError("MONARCH_FLAG_WS_PACKED needs the workspace of the earlier call")
+        workspace = _scratch(need, dev, stream)
+    ws_ptr = workspace.data_ptr() if workspace is not None else 0
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(dev):
+        rc = lib().monarch_fwd_bias_gelu(x.data_ptr(), R.data_ptr(), L.data_ptr(),
+                                         bias.data_ptr() if bias is not None else 0,
+                                         y_pre.data_ptr() if y_pre is not None else 0, y.data_ptr(), B, k * p,
+                                         k, q, s, _dtype_code(x), _stream_ptr(stream), ws_ptr, ws_len, flags)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_fwd_bias_gelu")
+    return y_pre, y
+
+
+def monarch_bwd_bias_gelu_in(dy: torch.Tensor, x: torch.Tensor, x_pre: torch.Tensor, R: torch.Tensor, L: torch.Tensor,
+                             dx_pre: torch.Tensor | None = None, dR: torch.Tensor | None = None,
+                             dL: torch.Tensor | None = None, dbias: torch.Tensor | None = None, want_dbias: bool = True,
+                             workspace: torch.Tensor | None = None, flags: int = 0, stream=None):
+    """(dx_pre, dR, dL, dbias) of the layer y = x M^T + bias whose input is x = gelu(x_pre): dx_pre is the
+    gradient with respect to x_pre.  Buffers are allocated when not given."""
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    dev, dt = x.device, x.dtype
+    _check(x, "x", (B, k * p), dt, dev)
+    _check(x_pre, "x_pre", (B, k * p), dt, dev)
+    _check(dy, "dy", (B, k * s), dt, dev)
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    gdt = torch.float32 if (flags & MONARCH_FLAG_WGRAD_F32) else dt
+    if dx_pre is None:
+        dx_pre = torch.empty_like(x)
+    if dR is None:
+        dR = torch.empty((k, q, p), dtype=gdt, device=dev)
+    if dL is None:
+        dL = torch.empty((k, s, q), dtype=gdt, device=dev)
+    if dbias is None and want_dbias:
+        dbias = torch.empty((k * s,), dtype=gdt, device=dev)
+    _check(dx_pre, "dx_pre", (B, k * p), dt, dev)
+    _check(dR, "dR", (k, q, p), gdt, dev)
+    _check(dL, "dL", (k, s, q), gdt, dev)
+    if dbias is not None:
+        _check(dbias, "dbias", (k * s,), gdt, dev)
+    need = monarch_bwd_workspace_bytes(B, k * p, k, q, s, _dtype_code(x), flags)
+    if workspace is None and need:
+        workspace = _scratch(need, dev, stream)
+    ws_ptr = workspace.data_ptr() if workspace is not None else 0
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(dev):
+        rc = lib().monarch_bwd_bias_gelu_in(dy.data_ptr(), x.data_ptr(), x_pre.data_ptr(), R.data_ptr(), L.data_ptr(),
+                                            dx_pre.data_ptr(), dR.data_ptr(), dL.data_ptr(),
+                                            dbias.data_ptr() if dbias is not None else 0, B, k * p, k, q, s,
+                                            _dtype_code(x), _stream_ptr(stream), ws_ptr, ws_len, flags)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_bwd_bias_gelu_in")
+    return dx_pre, dR, dL, dbias
 
 
 def monarch_project(A: torch.Tensor, R: torch.Tensor | None = None, L: torch.Tensor | None = None, stream=None):

@@ -118,6 +118,106 @@ int static_workspace(void** out)
     return MONARCH_OK;
 }
 
+// The affine layer, optionally followed by the nonlinearity: y = act(x M^T + bias).  Whatever the chosen
+// kernel does not do in its own epilogue follows as a pass over y.
+int fwd_layer(const void* x, const void* R, const void* L, const void* bias, bool act, void* y_pre, void* y,
+              int64_t batch, int n_in, int k, int q, int s, monarch_dtype dtype, void* stream, void* workspace,
+              size_t workspace_bytes, unsigned flags)
+{
+    Problem pb;
+    int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
+    if (rc) return rc;
+    if (flags & MONARCH_FLAG_WGRAD_F32) return MONARCH_ERR_INVALID;  // backward-only flag
+    if (!R || !L || ((!x || !y) && batch > 0)) return MONARCH_ERR_INVALID;
+    if (!aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(y, 16) || !aligned(bias, 16) ||
+        !aligned(y_pre, 16))
+        return MONARCH_ERR_INVALID;
+    if (y_pre && y_pre == y) return MONARCH_ERR_INVALID;
+    pb.bias = bias;
+    hipStream_t st = (hipStream_t)stream;
+    const bool generic = (flags & MONARCH_FLAG_GENERIC) != 0;
+    bool bias_done = bias == nullptr, act_done = !act;
+    if (!generic && mfma_fwd_ws_supported(pb)) {
+        if (!workspace || workspace_bytes < mfma_fwd_ws_workspace(pb) || !aligned(workspace, 256))
+            return MONARCH_ERR_WORKSPACE;
+        if (batch == 0) return MONARCH_OK;
+        if (act && mfma_fwd_fuses_act(pb, true)) {
+            pb.act = 1;
+            pb.y_pre = y_pre;
+            act_done = true;
+        }
+        rc = mfma_fwd_ws(pb, x, R, L, y, workspace, st);
+        bias_done = bias_done || mfma_fwd_fuses_bias(pb, true);
+    } else {
+        pb.flags &= ~MONARCH_FLAG_WS_PACKED;  // no packed-weight kernel: nothing to reuse
+        const Family fam = pick_fwd(pb);
+        if (fam == FAM_NONE) return MONARCH_ERR_UNSUPPORTED;
+        if (batch == 0) return MONARCH_OK;
+        if (fam == FAM_GENERIC) {
+            rc = generic_fwd(pb, x, R, L, y, st);
+            bias_done = true;
+        } else {
+            rc = mfma_fwd(pb, x, R, L, y, st);
+            bias_done = bias_done || mfma_fwd_fuses_bias(pb, false);
+        }
+    }
+    if (rc) return rc;
+    if (!bias_done) {
+        rc = launch_bias_add(pb, y, st);
+        if (rc) return rc;
+    }
+    if (!act_done) rc = launch_gelu_fwd(pb, y, y_pre, st);
+    return rc;
+}
+
+// Backward of the affine layer; `saved` (may be null): the vector between the factors kept by monarch_fwd_save;
+// `x_pre` (may be null): the layer's input is gelu(x_pre) and dx is wanted with respect to x_pre.
+int bwd_layer(const void* dy, const void* x, const void* x_pre, const void* saved, size_t saved_bytes, const void* R,
+              const void* L, void* dx, void* dR, void* dL, void* dbias, int64_t batch, int n_in, int k, int q,
+              int s, monarch_dtype dtype, void* stream, void* workspace, size_t workspace_bytes, unsigned flags)
+{
+    Problem pb;
+    int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
+    if (rc) return rc;
+    if (flags & MONARCH_FLAG_WS_PACKED) return MONARCH_ERR_INVALID;  // forward-with-workspace flag
+    if (!R || !L || !dR || !dL || ((!dy || !x || !dx) && batch > 0)) return MONARCH_ERR_INVALID;
+    if (!aligned(dy, 16) || !aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(dx, 16) ||
+        !aligned(dR, 16) || !aligned(dL, 16) || !aligned(dbias, 16))
+        return MONARCH_ERR_INVALID;
+    const Family fam = pick_bwd(pb);
+    if (fam == FAM_NONE) return MONARCH_ERR_UNSUPPORTED;
+    if (saved) {  // ignored by the kernel families that recompute
+        const size_t sneed = monarch_saved_bytes(batch, n_in, k, q, s, dtype, flags);
+        if (sneed > 0) {
+            if (saved_bytes < sneed || !aligned(saved, 16)) return MONARCH_ERR_WORKSPACE;
+            pb.saved = const_cast<void*>(saved);
+        }
+    }
+    const size_t need = bwd_need(pb, fam);
+    if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return MONARCH_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    if (dbias) {
+        void* cws = (char*)workspace + bwd_kernel_need(pb, fam);
+        if (batch > 0 && fam == FAM_MFMA && mfma_bwd_fuses_dbias(pb)) {
+            pb.dbias = dbias;  // computed at the tail of the backward's own launches
+            pb.colsum_ws = cws;
+        } else {
+            rc = launch_colsum(pb, dy, dbias, cws, st);
+            if (rc) return rc;
+        }
+    }
+    if (fam == FAM_MFMA) {
+        const bool fused = x_pre && mfma_bwd_fuses_act(pb);
+        if (fused) pb.x_pre = x_pre;
+        rc = mfma_bwd(pb, dy, x, R, L, dx, dR, dL, workspace, st);
+        if (rc || fused || !x_pre) return rc;
+    } else {
+        rc = generic_bwd(pb, dy, x, R, L, dx, dR, dL, workspace, st);
+        if (rc || !x_pre) return rc;
+    }
+    return launch_gelu_bwd(pb, dx, x_pre, st);  // the input was gelu(x_pre): chain rule, in place on dx
+}
+
 }  // namespace
 
 extern "C" {
@@ -191,32 +291,14 @@ int monarch_fwd_bias(const void* x, const void* R, const void* L, const void* bi
                      size_t workspace_bytes, unsigned flags)
 {
     if (!bias) return monarch_fwd_ws(x, R, L, y, batch, n_in, k, q, s, dtype, stream, workspace, workspace_bytes, flags);
-    Problem pb;
-    int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
-    if (rc) return rc;
-    if (flags & MONARCH_FLAG_WGRAD_F32) return MONARCH_ERR_INVALID;  // backward-only flag
-    if (!R || !L || ((!x || !y) && batch > 0)) return MONARCH_ERR_INVALID;
-    if (!aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(y, 16) || !aligned(bias, 16))
-        return MONARCH_ERR_INVALID;
-    pb.bias = bias;
-    hipStream_t st = (hipStream_t)stream;
-    const bool generic = (flags & MONARCH_FLAG_GENERIC) != 0;
-    if (!generic && mfma_fwd_ws_supported(pb)) {
-        if (!workspace || workspace_bytes < mfma_fwd_ws_workspace(pb) || !aligned(workspace, 256))
-            return MONARCH_ERR_WORKSPACE;
-        if (batch == 0) return MONARCH_OK;
-        rc = mfma_fwd_ws(pb, x, R, L, y, workspace, st);
-        if (rc || mfma_fwd_fuses_bias(pb, true)) return rc;
-        return launch_bias_add(pb, y, st);
-    }
-    pb.flags &= ~MONARCH_FLAG_WS_PACKED;  // no packed-weight kernel: nothing to reuse
-    const Family fam = pick_fwd(pb);
-    if (fam == FAM_NONE) return MONARCH_ERR_UNSUPPORTED;
-    if (batch == 0) return MONARCH_OK;
-    if (fam == FAM_GENERIC) return generic_fwd(pb, x, R, L, y, st);
-    rc = mfma_fwd(pb, x, R, L, y, st);
-    if (rc || mfma_fwd_fuses_bias(pb, false)) return rc;
-    return launch_bias_add(pb, y, st);
+    return fwd_layer(x, R, L, bias, false, nullptr, y, batch, n_in, k, q, s, dtype, stream, workspace, workspace_bytes, flags);
+}
+
+int monarch_fwd_bias_gelu(const void* x, const void* R, const void* L, const void* bias, void* y_pre, void* y,
+                          int64_t batch, int n_in, int k, int q, int s, monarch_dtype dtype, void* stream,
+                          void* workspace, size_t workspace_bytes, unsigned flags)
+{
+    return fwd_layer(x, R, L, bias, true, y_pre, y, batch, n_in, k, q, s, dtype, stream, workspace, workspace_bytes, flags);
 }
 
 size_t monarch_saved_bytes(int64_t batch, int n_in, int k, int q, int s, monarch_dtype dtype, unsigned flags)
@@ -273,38 +355,18 @@ int monarch_bwd_saved(const void* dy, const void* x, const void* saved, size_t s
                       const void* L, void* dx, void* dR, void* dL, void* dbias, int64_t batch, int n_in, int k, int q,
                       int s, monarch_dtype dtype, void* stream, void* workspace, size_t workspace_bytes, unsigned flags)
 {
-    Problem pb;
-    int rc = make_problem(pb, batch, n_in, k, q, s, (int)dtype, flags);
-    if (rc) return rc;
-    if (flags & MONARCH_FLAG_WS_PACKED) return MONARCH_ERR_INVALID;  // forward-with-workspace flag
-    if (!R || !L || !dR || !dL || ((!dy || !x || !dx) && batch > 0)) return MONARCH_ERR_INVALID;
-    if (!aligned(dy, 16) || !aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(dx, 16) ||
-        !aligned(dR, 16) || !aligned(dL, 16) || !aligned(dbias, 16))
-        return MONARCH_ERR_INVALID;
-    const Family fam = pick_bwd(pb);
-    if (fam == FAM_NONE) return MONARCH_ERR_UNSUPPORTED;
-    if (saved) {  // ignored by the kernel families that recompute
-        const size_t sneed = monarch_saved_bytes(batch, n_in, k, q, s, dtype, flags);
-        if (sneed > 0) {
-            if (saved_bytes < sneed || !aligned(saved, 16)) return MONARCH_ERR_WORKSPACE;
-            pb.saved = const_cast<void*>(saved);
-        }
-    }
-    const size_t need = bwd_need(pb, fam);
-    if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return MONARCH_ERR_WORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
-    if (dbias) {
-        void* cws = (char*)workspace + bwd_kernel_need(pb, fam);
-        if (batch > 0 && fam == FAM_MFMA && mfma_bwd_fuses_dbias(pb)) {
-            pb.dbias = dbias;  // computed at the tail of the backward's own launches
-            pb.colsum_ws = cws;
-        } else {
-            rc = launch_colsum(pb, dy, dbias, cws, st);
-            if (rc) return rc;
-        }
-    }
-    if (fam == FAM_MFMA) return mfma_bwd(pb, dy, x, R, L, dx, dR, dL, workspace, st);
-    return generic_bwd(pb, dy, x, R, L, dx, dR, dL, workspace, st);
+    return bwd_layer(dy, x, nullptr, saved, saved_bytes, R, L, dx, dR, dL, dbias, batch, n_in, k, q, s, dtype, stream,
+                     workspace, workspace_bytes, flags);
+}
+
+int monarch_bwd_bias_gelu_in(const void* dy, const void* x, const void* x_pre, const void* R, const void* L,
+                             void* dx_pre, void* dR, void* dL, void* dbias, int64_t batch, int n_in, int k, int q, int s,
+                             monarch_dtype dtype, void* stream, void* workspace, size_t workspace_bytes, unsigned flags)
+{
+    if (!x_pre && batch > 0) return MONARCH_ERR_INVALID;
+    if (!aligned(x_pre, 16) || (x_pre && x_pre == dx_pre)) return MONARCH_ERR_INVALID;
+    return bwd_layer(dy, x, x_pre, nullptr, 0, R, L, dx_pre, dR, dL, dbias, batch, n_in, k, q, s, dtype, stream,
+                     workspace, workspace_bytes, flags);
 }
 
 size_t monarch_fwd_t_workspace_bytes(int64_t batch, int n_in, int k, int q, int s, monarch_dtype dtype, unsigned flags)

@@ -15,6 +15,9 @@ struct Problem {
     void* saved = nullptr;       // forward: also write the vector between the factors here; backward: read it from here
     void* dbias = nullptr;       // backward only: bias gradient wanted (fp32 when wgrad_f32(), else `dtype`)
     void* colsum_ws = nullptr;   // backward only: colsum_workspace() bytes for the bias gradient's partial rows
+    int act = 0;                 // forward only: 1 = the output is gelu(product + bias)
+    void* y_pre = nullptr;       // forward with act: the value before the nonlinearity also goes here (may be null)
+    const void* x_pre = nullptr; // backward only: the layer's input is gelu(x_pre); dx is returned with respect to x_pre
     int n_out() const { return k * s; }
     int kq() const { return k * q; }
     size_t esize() const { return dtype == 0 ? 4 : 2; }
@@ -46,6 +49,11 @@ int launch_to_dense(const Problem& pb, const void* R, const void* L, void* M, hi
 int launch_bias_add(const Problem& pb, void* y, hipStream_t st);
 size_t colsum_workspace(const Problem& pb);
 int launch_colsum(const Problem& pb, const void* dy, void* dbias, void* ws, hipStream_t st);
+// the feed-forward block's nonlinearity as passes of their own (monarch_act.hip), for the kernel families that do
+// not apply it in their epilogues: y (holding the pre-activation) -> y_pre (if not null) and y = gelu(y);
+// dx *= gelu'(x_pre)
+int launch_gelu_fwd(const Problem& pb, void* y, void* y_pre, hipStream_t st);
+int launch_gelu_bwd(const Problem& pb, void* dx, const void* x_pre, hipStream_t st);
 struct ColsumJob;
 ColsumJob make_colsum_job(const Problem& pb, const void* dy, void* dbias, void* ws);
 
@@ -86,6 +94,10 @@ size_t mfma_fwd_t_workspace(const Problem& pb);
 const char* mfma_fwd_t_name(const Problem& pb);
 int mfma_fwd_t(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);
 bool mfma_fwd_fuses_bias(const Problem& pb, bool with_ws);
+// the forward applies pb.act (and writes pb.y_pre) in its epilogue / the backward multiplies dx by gelu'(pb.x_pre)
+// in its epilogue; else the caller runs launch_gelu_fwd / launch_gelu_bwd afterwards
+bool mfma_fwd_fuses_act(const Problem& pb, bool with_ws);
+bool mfma_bwd_fuses_act(const Problem& pb);
 bool mfma_bwd_fuses_dbias(const Problem& pb);  // the backward computes pb.dbias inside its own launches  // else the caller adds the bias in a second pass
 int mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L,
              void* dx, void* dR, void* dL, void* ws, hipStream_t st);

@@ -85,6 +85,11 @@ bool mfma_fwd_fuses_bias(const Problem& pb, bool with_ws)
 
 bool mfma_bwd_fuses_dbias(const Problem& pb) { return bwd_wide_supported(pb); }
 
+// The nonlinearity of the feed-forward block: applied in the epilogue of the packed-weight forward for the
+// four-block layer shapes, and in the dx epilogue of their (recomputing) backward.
+bool mfma_fwd_fuses_act(const Problem& pb, bool with_ws) { return with_ws && fwd_frag_supported(pb); }
+bool mfma_bwd_fuses_act(const Problem& pb) { return bwd_wide_supported(pb) && !pb.saved; }
+
 bool mfma_bwd_supported(const Problem& pb)
 {
     return bwd_wide_supported(pb) || bwd_sq64_supported(pb) || sq16_supported(pb) || tiled_bwd_supported(pb);

@@ -20,6 +20,7 @@
 #include "monarch_mfma_common.h"
 #include "monarch_colsum.h"
 #include "monarch_mfma_stage1.h"
+#include "monarch_act.h"
 
 namespace monarch {
 
@@ -152,6 +153,46 @@ __device__ __forceinline__ void copy_out_tile(const uint16_t* src, int stride, u
     }
 }
 
+// The wave-private dx tile ([64][COLS] bf16 in LDS) goes out multiplied elementwise by gelu'(x_pre): the layer's
+// input was gelu(x_pre) and the caller wants the gradient with respect to x_pre.  Lane task i is row
+// lane / (COLS/8) + (512/COLS) * i, 16-byte piece lane % (COLS/8); `pre` holds the x_pre pieces of the same tasks
+// (fetched by load_pre_tile before the MFMA loop, so that their latency is hidden).
+template <int COLS>
+__device__ __forceinline__ void load_pre_tile(const uint16_t* pre, int64_t ld, int64_t b0, int64_t B, int lane,
+                                              u32x4 (&hp)[COLS / 8])
+{
+    constexpr int PER_ROW = COLS / 8;
+    static_assert(64 % PER_ROW == 0, "whole rows per round");
+#pragma unroll
+    for (int i = 0; i < PER_ROW; ++i) {
+        const int t = lane + i * 64;
+        int64_t row = b0 + t / PER_ROW;
+        row = row < B ? row : B - 1;  // rows past the end are read from a valid row and never stored
+        hp[i] = ldg128_nt(pre + row * ld + 8 * (t % PER_ROW));
+    }
+}
+
+template <int COLS>
+__device__ __forceinline__ void copy_out_tile_gelu(const uint16_t* src, int stride, uint16_t* dst, int64_t ld,
+                                                   int64_t b0, int64_t B, int lane, const u32x4 (&hp)[COLS / 8])
+{
+    constexpr int PER_ROW = COLS / 8;
+#pragma unroll
+    for (int i = 0; i < PER_ROW; ++i) {
+        const int t = lane + i * 64;
+        const int r = t / PER_ROW, u = t % PER_ROW;
+        const u32x4 v = lds128(src + (size_t)r * stride + 8 * u);
+        u32x4 o;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float g0 = __uint_as_float(v[w] << 16), g1 = __uint_as_float(v[w] & 0xffff0000u);
+            const float h0 = __uint_as_float(hp[i][w] << 16), h1 = __uint_as_float(hp[i][w] & 0xffff0000u);
+            o[w] = pack_bf16x2(g0 * gelu_grad_f(h0), g1 * gelu_grad_f(h1));
+        }
+        if (b0 + r < B) stg128_nt(dst + (b0 + r) * ld + 8 * u, o);
+    }
+}
+
 // orders the LDS traffic of one wave (what its lanes wrote is visible to its later reads)
 __device__ __forceinline__ void wave_fence()
 {
@@ -164,12 +205,14 @@ __device__ __forceinline__ void wave_fence()
 // that product, dx its output): the recompute of step 1 and the workspace copies of both intermediates
 // are left out.  MODE 2: the forward saved the vector between the factors, so step 1 is not recomputed;
 // dY1 still goes to the workspace for the weight-gradient GEMM.
-template <typename C, int MODE>
+// ACT: dx leaves multiplied by gelu'(x_pre) (the layer's input was x = gelu(x_pre)).
+template <typename C, int MODE, bool ACT>
 __global__ void __launch_bounds__(256)
 bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ x,
                      const uint16_t* __restrict__ XF, const uint16_t* __restrict__ LF,
                      const uint16_t* __restrict__ RF, uint16_t* __restrict__ dx,
-                     uint16_t* __restrict__ Y1ws, uint16_t* __restrict__ dY1ws, int64_t B)
+                     uint16_t* __restrict__ Y1ws, uint16_t* __restrict__ dY1ws, const uint16_t* __restrict__ x_pre,
+                     int64_t B)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
     const int tid = threadIdx.x;
@@ -331,6 +374,8 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
         f32x4 acc[C::IG * C::NBT];
 #pragma unroll
         for (int t = 0; t < C::IG * C::NBT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        u32x4 hp[C::DX_COLS / 8];
+        if constexpr (ACT) load_pre_tile<C::DX_COLS>(x_pre + kk * C::P + ig * C::DX_COLS, C::N_IN, b0, B, lane, hp);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int n = ig * U + u;
@@ -357,7 +402,10 @@ bwd_wide_data_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict
             }
         // the staging tile is private to the wave: no workgroup barrier
         wave_fence();
-        copy_out_tile<C::DX_COLS, 64, true>(stage, C::DX_STRIDE, dx + kk * C::P + ig * C::DX_COLS, C::N_IN, b0, B, lane);
+        if constexpr (ACT)
+            copy_out_tile_gelu<C::DX_COLS>(stage, C::DX_STRIDE, dx + kk * C::P + ig * C::DX_COLS, C::N_IN, b0, B, lane, hp);
+        else
+            copy_out_tile<C::DX_COLS, 64, true>(stage, C::DX_STRIDE, dx + kk * C::P + ig * C::DX_COLS, C::N_IN, b0, B, lane);
         wave_fence();
     }
 }
@@ -367,13 +415,17 @@ int launch_data(const Problem& pb, const void* dy, const void* x, const uint16_t
                 const uint16_t* RF, void* dx, uint16_t* Y1ws, uint16_t* dY1ws, hipStream_t st)
 {
     // no workspace for dY1: dx only; dY1 but no Y1 workspace: the forward saved that vector
-    auto kern = !dY1ws ? bwd_wide_data_kernel<C, 1> : (Y1ws ? bwd_wide_data_kernel<C, 0> : bwd_wide_data_kernel<C, 2>);
+    // (the nonlinearity's factor is applied here only by the recomputing backward)
+    auto kern = !dY1ws ? bwd_wide_data_kernel<C, 1, false>
+                       : (Y1ws ? (pb.x_pre ? bwd_wide_data_kernel<C, 0, true> : bwd_wide_data_kernel<C, 0, false>)
+                               : bwd_wide_data_kernel<C, 2, false>);
+    if (pb.x_pre && !(dY1ws && Y1ws)) return -2;
     if (allow_dynamic_lds((const void*)kern, C::LDS_BYTES) != hipSuccess)
         return -4;
     const int64_t grid = (pb.B + C::BM - 1) / C::BM;
     if (grid > 0x7fffffffLL) return -2;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), C::LDS_BYTES, st, (const uint16_t*)dy,
-                       (const uint16_t*)x, XF, LF, RF, (uint16_t*)dx, Y1ws, dY1ws, pb.B);
+                       (const uint16_t*)x, XF, LF, RF, (uint16_t*)dx, Y1ws, dY1ws, (const uint16_t*)pb.x_pre, pb.B);
     return hip_status(hipGetLastError());
 }
 

@@ -31,6 +31,7 @@
 #include "monarch_internal.h"
 #include "monarch_mfma_common.h"
 #include "monarch_mfma_stage1.h"
+#include "monarch_act.h"
 
 namespace monarch {
 
@@ -125,9 +126,12 @@ __device__ __forceinline__ void stage2_issue_w(const uint16_t* const (&wbase)[C:
 // One stage-2 pass of one wave: work units u0 .. u0+UPW-1, unit w = (l tile w / 2, row tile w % 2).
 // PRE: the caller has already issued the weights of steps 0 .. RW-2 into `wr` (first pass: they
 // are fetched while the workgroup is still exchanging Y1 through LDS).
-template <typename C, bool ODD, bool PRE, bool BIAS>
+// BIAS: the bias (when the pointer is not null) is added to the product.  ACT: the sum also goes to y_pre
+// (when not null) and y receives gelu of it.
+template <typename C, bool ODD, bool PRE, bool BIAS, bool ACT>
 __device__ __forceinline__ void stage2_pass(const uint16_t* __restrict__ LF2, const uint16_t* y1s,
-                                            const uint16_t* __restrict__ bias, uint16_t* __restrict__ y, int64_t b0,
+                                            const uint16_t* __restrict__ bias, uint16_t* __restrict__ y,
+                                            uint16_t* __restrict__ y_pre, int64_t b0,
                                             int64_t B, int u0, int lane, u32x4 (&wr)[C::RW2][C::NLT])
 {
     constexpr int UPW = C::UPW, K = 4, NLT = C::NLT, RW = C::RW2, KS = C::KS;
@@ -186,7 +190,7 @@ __device__ __forceinline__ void stage2_pass(const uint16_t* __restrict__ LF2, co
         const int ww = i + (ODD ? 1 : 0);
         const int l = (lt_lo + (ww >> 1)) * 32 + ln;
         float bv[K] = {0.f, 0.f, 0.f, 0.f};
-        if constexpr (BIAS) {
+        if (BIAS && bias) {
             // the lane's four outputs of a row are y[row][4*l .. 4*l+3]: one 8-byte piece of the bias
             const u32x2 bb = *reinterpret_cast<const u32x2*>(bias + (size_t)l * K);
             bv[0] = __uint_as_float(bb[0] << 16), bv[1] = __uint_as_float(bb[0] & 0xffff0000u);
@@ -201,6 +205,14 @@ __device__ __forceinline__ void stage2_pass(const uint16_t* __restrict__ LF2, co
 #pragma unroll
                     for (int c = 0; c < K; ++c) o[c] += bv[c];
                 }
+                if constexpr (ACT) {
+                    if (y_pre) {
+                        u32x2 h = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+                        __builtin_nontemporal_store(h, reinterpret_cast<u32x2*>(y_pre + row * C::N_OUT + (size_t)l * K));
+                    }
+#pragma unroll
+                    for (int c = 0; c < K; ++c) o[c] = gelu_f(o[c]);
+                }
                 u32x2 v = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
                 __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(y + row * C::N_OUT + (size_t)l * K));
             }
@@ -208,10 +220,11 @@ __device__ __forceinline__ void stage2_pass(const uint16_t* __restrict__ LF2, co
     }
 }
 
-template <typename C, bool BIAS>
+template <typename C, bool BIAS, bool ACT>
 __global__ void __launch_bounds__(256)
 fwd_frag_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ RF1,
-                const uint16_t* __restrict__ LF2, const uint16_t* __restrict__ bias, uint16_t* __restrict__ y, int64_t B)
+                const uint16_t* __restrict__ LF2, const uint16_t* __restrict__ bias, uint16_t* __restrict__ y,
+                uint16_t* __restrict__ y_pre, int64_t B)
 {
     extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
     const int tid = threadIdx.x;
@@ -253,29 +266,30 @@ fwd_frag_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ RF1
     {
         const int u0 = wave * C::UPW;
         if (u0 & 1)
-            stage2_pass<C, true, true, BIAS>(LF2, lds, bias, y, b0, B, u0, lane, wr2);
+            stage2_pass<C, true, true, BIAS, ACT>(LF2, lds, bias, y, y_pre, b0, B, u0, lane, wr2);
         else
-            stage2_pass<C, false, true, BIAS>(LF2, lds, bias, y, b0, B, u0, lane, wr2);
+            stage2_pass<C, false, true, BIAS, ACT>(LF2, lds, bias, y, y_pre, b0, B, u0, lane, wr2);
     }
     for (int ps = 1; ps < C::PASSES; ++ps) {
         const int u0 = (ps * 4 + wave) * C::UPW;
         if (u0 & 1)
-            stage2_pass<C, true, false, BIAS>(LF2, lds, bias, y, b0, B, u0, lane, wr2);
+            stage2_pass<C, true, false, BIAS, ACT>(LF2, lds, bias, y, y_pre, b0, B, u0, lane, wr2);
         else
-            stage2_pass<C, false, false, BIAS>(LF2, lds, bias, y, b0, B, u0, lane, wr2);
+            stage2_pass<C, false, false, BIAS, ACT>(LF2, lds, bias, y, y_pre, b0, B, u0, lane, wr2);
     }
 }
 
 template <typename C>
 int launch(const Problem& pb, const void* x, const uint16_t* RF1, const uint16_t* LF2, void* y, hipStream_t st)
 {
-    auto kern = pb.bias ? fwd_frag_kernel<C, true> : fwd_frag_kernel<C, false>;
+    // with the nonlinearity the bias pointer is tested inside the kernel (one variant for both cases)
+    auto kern = pb.act ? fwd_frag_kernel<C, true, true> : (pb.bias ? fwd_frag_kernel<C, true, false> : fwd_frag_kernel<C, false, false>);
     hipError_t e = allow_dynamic_lds((const void*)kern, C::LDS_BYTES);
     if (e != hipSuccess) return -4;
     const int64_t grid = (pb.B + C::BM - 1) / C::BM;
     if (grid > 0x7fffffffLL) return -2;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), C::LDS_BYTES, st, (const uint16_t*)x, RF1, LF2,
-                       (const uint16_t*)pb.bias, (uint16_t*)y, pb.B);
+                       (const uint16_t*)pb.bias, (uint16_t*)y, (uint16_t*)pb.y_pre, pb.B);
     return hip_status(hipGetLastError());
 }
 

@@ -462,6 +462,137 @@ def test_affine_layer_full_size(B, name):
     compare(sh, got, oracle.bwd_bias(dy, x, R, L), ["dx", "dR", "dL", "dbias"])
 
 
+# ---------------------------------------------------------------- layer with the block's nonlinearity ----
+
+def run_fwd_gelu(B, sh, x, R, L, bias, flags=0, want_pre=True):
+    """monarch_fwd_bias_gelu with guarded outputs and workspace: (y_pre or None, y) on the host."""
+    dt = tdtype(sh.dtype)
+    ybuf, y = guarded((x.shape[0], sh.n_out), dt)
+    pbuf, y_pre = guarded((x.shape[0], sh.n_out), dt) if want_pre else (None, None)
+    code = 0 if sh.dtype == "f32" else 1
+    need = B.monarch_fwd_workspace_bytes(x.shape[0], sh.n_in, sh.k, sh.q, sh.s, code, flags)
+    wbuf = torch.full((need + 512 + 2 * GUARD,), 0x5A, dtype=torch.uint8, device="cuda")
+    off = (-(wbuf.data_ptr() + GUARD)) % 256 + GUARD
+    B.monarch_fwd_bias_gelu(dev(x, sh.dtype), dev(R, sh.dtype), dev(L, sh.dtype),
+                            dev(bias, sh.dtype) if bias is not None else None, y_pre, y, want_pre=want_pre,
+                            workspace=wbuf[off:off + need] if need else None, flags=flags)
+    torch.cuda.synchronize()
+    assert bool((wbuf[:off] == 0x5A).all()) and bool((wbuf[off + need:] == 0x5A).all()), "workspace: wrote out of bounds"
+    check_guard(ybuf, "y")
+    outs = [host(y)]
+    if want_pre:
+        check_guard(pbuf, "y_pre")
+        outs.insert(0, host(y_pre))
+    for o in outs:
+        assert np.isfinite(o).all(), "an output has unwritten or non-finite entries"
+    return outs if want_pre else [None] + outs
+
+
+def run_bwd_gelu_in(B, sh, dy, x, x_pre, R, L, flags=0):
+    dt = tdtype(sh.dtype)
+    gdt = torch.float32 if (flags & B.MONARCH_FLAG_WGRAD_F32) else dt
+    bx, dx = guarded((x.shape[0], sh.n_in), dt)
+    bR, dR = guarded(R.shape, gdt)
+    bL, dL = guarded(L.shape, gdt)
+    bb, db = guarded((sh.n_out,), gdt)
+    B.monarch_bwd_bias_gelu_in(dev(dy, sh.dtype), dev(x, sh.dtype), dev(x_pre, sh.dtype), dev(R, sh.dtype), dev(L, sh.dtype),
+                               dx, dR, dL, db, flags=flags)
+    torch.cuda.synchronize()
+    for buf, name in ((bx, "dx_pre"), (bR, "dR"), (bL, "dL"), (bb, "dbias")):
+        check_guard(buf, name)
+    outs = [host(t) for t in (dx, dR, dL, db)]
+    for o, name in zip(outs, ("dx_pre", "dR", "dL", "dbias")):
+        assert np.isfinite(o).all(), name + " has unwritten or non-finite entries"
+    return outs
+
+
+def gelu_layer_case(B, sh, flags=0):
+    """Both calls of one shape against the oracle: the layer as a block's first layer (forward) and as its
+    second (backward, its input being gelu of a stored pre-activation)."""
+    from oracle import activation
+    x, R, L, dy = synth.make_inputs(sh)
+    bias = make_bias(sh)
+    want_pre, want_y = activation.fwd_bias_gelu(x, R, L, bias)
+    compare(sh, run_fwd_gelu(B, sh, x, R, L, bias, flags), [want_pre, want_y], ["y_pre", "y"])
+    # the layer's input as a first layer would have stored it: pre-activation x, activation gelu(x), both rounded
+    xin = synth.quantize(activation.gelu(x), sh.dtype)
+    want = activation.bwd_bias_gelu_in(dy, x, R, L, x=xin)
+    compare(sh, run_bwd_gelu_in(B, sh, dy, xin, x, R, L, flags), want, ["dx_pre", "dR", "dL", "dbias"])
+
+
+@pytest.mark.parametrize("generic", [False, True], ids=["dispatch", "generic"])
+@pytest.mark.parametrize("case", SMALL + [("odd_n_out", "f32", 300, 3, 4, 5, 7), ("odd_n_out_bf16", "bf16", 130, 3, 4, 5, 7)],
+                         ids=lambda c: c[0])
+def test_layer_with_nonlinearity_small_shapes(B, case, generic):
+    """monarch_fwd_bias_gelu / monarch_bwd_bias_gelu_in against oracle.activation: the fused epilogues (bf16, k = 4)
+    and the separate elementwise passes (every other shape, and everything under MONARCH_FLAG_GENERIC)."""
+    gelu_layer_case(B, small_shape(case), B.MONARCH_FLAG_GENERIC if generic else 0)
+
+
+@pytest.mark.parametrize("case", MODEL_LAYERS, ids=lambda c: c[0])
+def test_layer_with_nonlinearity_model_layer_shapes(B, case):
+    name, dtype, Bn, k, p, q, s = case[:7]
+    gelu_layer_case(B, synth.Shape(name, dtype, min(Bn, 333), k, p, q, s, config=70 + parity_util.stable_seed(name)))
+
+
+def test_layer_with_nonlinearity_edge_cases(B):
+    from oracle import activation
+    for case in (("k4_192", "bf16", 70, 4, 192, 192, 192), ("sq_m16", "f32", 33, 16, 16, 16, 16), ("rect", "f32", 5, 3, 2, 6, 5)):
+        sh = small_shape(case)
+        x, R, L, dy = synth.make_inputs(sh)
+        bias = make_bias(sh)
+        # no bias; and no pre-activation output: the same y bit for bit
+        want_pre, want_y = activation.fwd_bias_gelu(x, R, L, np.zeros(sh.n_out))
+        pre, y = run_fwd_gelu(B, sh, x, R, L, None)
+        compare(sh, [pre, y], [want_pre, want_y], ["y_pre_nobias", "y_nobias"])
+        _, y2 = run_fwd_gelu(B, sh, x, R, L, None, want_pre=False)
+        assert np.array_equal(y, y2), sh.name
+        # x = 0: every row is gelu(bias); a large negative bias gives exact zeros, a large positive one the bias itself
+        big = np.where(np.arange(sh.n_out) % 2 == 0, 40.0, -40.0)
+        pre, y = run_fwd_gelu(B, sh, np.zeros_like(x), R, L, big)
+        assert np.array_equal(pre, np.tile(big, (sh.B, 1))) and np.array_equal(y, np.tile(np.maximum(big, 0.0), (sh.B, 1))), sh.name
+        # backward at x_pre = 0: gelu'(0) = 1/2 exactly, so dx_pre is half the plain dx (a power of two: same rounding)
+        zeros = np.zeros_like(x)
+        dxh = run_bwd_gelu_in(B, sh, dy, zeros, zeros, R, L)[0]
+        dx = run_bwd_bias(B, sh, dy, zeros, R, L)[0]
+        assert np.array_equal(dxh, 0.5 * dx), sh.name
+    sh0 = synth.Shape("empty", "bf16", 0, 4, 64, 64, 64)
+    x0, R0, L0, dy0 = synth.make_inputs(sh0)
+    assert run_fwd_gelu(B, sh0, x0, R0, L0, make_bias(sh0))[1].shape == (0, 256)
+    dx, dR, dL, db = run_bwd_gelu_in(B, sh0, dy0, x0, x0, R0, L0)
+    assert dx.shape == (0, 256) and not dR.any() and not dL.any() and not db.any()
+
+
+@pytest.mark.parametrize("name", ["sq256_f32", "vitb_proj", "sq4096", "gpt2m_fc1", "gpt2m_fc2"])
+def test_layer_with_nonlinearity_full_size(B, name):
+    gelu_layer_case(B, synth.WORKLOADS[name])
+
+
+def test_feed_forward_block_end_to_end(B):
+    """GPT-2-medium-style block 1024 -> 4096 -> gelu -> 1024 with biases, forward and backward through the four
+    layer calls, against the oracle's chain in fp64 (2048 rows)."""
+    from oracle import activation
+    s1, s2 = synth.WORKLOADS["gpt2m_fc1"], synth.WORKLOADS["gpt2m_fc2"]
+    rows = 2048
+    x, R1, L1, _ = synth.make_inputs(s1, rows=rows)
+    _, R2, L2, dy = synth.make_inputs(s2, rows=rows)
+    b1, b2 = make_bias(s1), make_bias(s2)
+    xd, R1d, L1d, R2d, L2d, dyd, b1d, b2d = (dev(a, "bf16") for a in (x, R1, L1, R2, L2, dy, b1, b2))
+    h, g = B.monarch_fwd_bias_gelu(xd, R1d, L1d, b1d)
+    y = B.monarch_fwd_bias(g, R2d, L2d, b2d)
+    dh, dR2, dL2, db2 = B.monarch_bwd_bias_gelu_in(dyd, g, h, R2d, L2d)
+    dx, dR1, dL1, db1 = B.monarch_bwd_bias(dh, xd, R1d, L1d)
+    torch.cuda.synchronize()
+    ho, go = activation.fwd_bias_gelu(x, R1, L1, b1)
+    yo = oracle.fwd_bias(go, R2, L2, b2)
+    dho, dR2o, dL2o, db2o = activation.bwd_bias_gelu_in(dy, ho, R2, L2)
+    dxo, dR1o, dL1o, db1o = oracle.bwd_bias(dho, x, R1, L1)
+    sh = synth.Shape("ffn_block", "bf16", rows, 4, 256, 256, 1024)
+    compare(sh, [host(t) for t in (h, g, y, dh, dR2, dL2, db2, dx, dR1, dL1, db1)],
+            [ho, go, yo, dho, dR2o, dL2o, db2o, dxo, dR1o, dL1o, db1o],
+            ["h", "g", "y", "dh", "dR2", "dL2", "db2", "dx", "dR1", "dL1", "db1"])
+
+
 # Dense form of M: every entry is one fp32 sum of at most q products, rounded once to the storage type
 # (relative 2^-24 / 2^-9 per entry), so the bound is much tighter than for the multiply.
 DENSE_TOL = {"f32": 1e-6, "bf16": 3e-3}

@@ -179,6 +179,49 @@ def test_affine_layer_calls_reject_bad_arguments_without_a_gpu(binding):
     assert big - small >= 127 * 768 * 4
 
 
+def test_layer_with_nonlinearity_rejects_bad_arguments_without_a_gpu(binding):
+    L = binding.lib()
+    p = 4096  # never dereferenced
+    need = binding.monarch_fwd_workspace_bytes(0, 768, 4, 192, 192, 1)
+
+    def fwd(x=p, R=p, Lp=p, bias=p, y_pre=p + 64, y=p, ws=p, ws_bytes=need, flags=0, batch=0, n_in=768, k=4, q=192,
+            s=192, dtype=1):
+        return L.monarch_fwd_bias_gelu(x, R, Lp, bias, y_pre, y, batch, n_in, k, q, s, dtype, None, ws, ws_bytes, flags)
+
+    assert fwd() == binding.MONARCH_OK
+    assert fwd(bias=None) == binding.MONARCH_OK                      # no bias
+    assert fwd(y_pre=None) == binding.MONARCH_OK                     # pre-activation not wanted
+    assert fwd(y_pre=p) == binding.MONARCH_ERR_INVALID               # the two outputs may not be one buffer
+    assert fwd(y_pre=p + 8) == binding.MONARCH_ERR_INVALID           # not 16-byte aligned
+    assert fwd(bias=p + 8) == binding.MONARCH_ERR_INVALID
+    assert fwd(Lp=None) == binding.MONARCH_ERR_INVALID
+    assert fwd(y=None, batch=3) == binding.MONARCH_ERR_INVALID
+    assert fwd(n_in=770) == binding.MONARCH_ERR_INVALID
+    assert fwd(flags=binding.MONARCH_FLAG_WGRAD_F32) == binding.MONARCH_ERR_INVALID
+    assert fwd(ws=None) == binding.MONARCH_ERR_WORKSPACE
+    assert fwd(ws_bytes=need - 1) == binding.MONARCH_ERR_WORKSPACE
+    assert fwd(ws=None, ws_bytes=0, flags=binding.MONARCH_FLAG_GENERIC) == binding.MONARCH_OK
+    assert fwd(ws=None, ws_bytes=0, n_in=6, k=2, q=4, s=2, dtype=0) == binding.MONARCH_OK
+
+    bneed = binding.monarch_bwd_workspace_bytes(1, 768, 4, 192, 192, 1, 0)
+
+    def bwd(ptrs=(p,) * 9, batch=1, ws=p, ws_bytes=bneed, flags=0, n_in=768):
+        return L.monarch_bwd_bias_gelu_in(*ptrs, batch, n_in, 4, 192, 192, 1, None, ws, ws_bytes, flags)
+
+    for bad in range(8):  # dy, x, x_pre, R, L, dx_pre, dR, dL; dbias (index 8) may be NULL
+        ptrs = [p] * 9
+        ptrs[5] = p + 64  # dx_pre is a buffer of its own
+        ptrs[bad] = None
+        assert bwd(tuple(ptrs)) == binding.MONARCH_ERR_INVALID, bad
+    assert bwd((p, p, p, p, p, p, p, p, p)) == binding.MONARCH_ERR_INVALID        # dx_pre over x_pre
+    assert bwd((p, p, p + 8, p, p, p + 64, p, p, p)) == binding.MONARCH_ERR_INVALID   # x_pre not 16-byte aligned
+    ok = (p, p, p, p, p, p + 64, p, p, None)
+    assert bwd(ok, ws=None) == binding.MONARCH_ERR_WORKSPACE
+    assert bwd(ok, ws_bytes=bneed - 1) == binding.MONARCH_ERR_WORKSPACE
+    assert bwd(ok, n_in=770) == binding.MONARCH_ERR_INVALID
+    assert bwd(ok, flags=binding.MONARCH_FLAG_WS_PACKED) == binding.MONARCH_ERR_INVALID
+
+
 def test_projection_rejects_bad_arguments_without_a_gpu(binding):
     L = binding.lib()
     p = 4096  # never dereferenced
