@@ -279,6 +279,100 @@ fwd_frag_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ RF1
     }
 }
 
+// ---- eight waves per workgroup (two per SIMD) for the shapes with 256-wide blocks ----
+// Same tiling of the work (64 rows per workgroup, all of R and L streamed once per workgroup), but each
+// block of stage 1 is shared by two waves (column halves, stage1_half) and stage 2 runs eight waves on
+// units of one l tile x two row tiles: half the accumulators per wave, so two waves fit a SIMD and one
+// computes while the other waits for its weight fragments.
+// PRIV: every wave keeps an x ring of its own (two slots; x passes through the L1 twice, no barriers in
+// stage 1) instead of sharing one with its partner (stage1_half: one barrier per 64-column chunk).
+template <int P_, int Q_, int S_, int RW2_, bool PRIV_>
+struct FwdFrag8 {
+    static constexpr int K = 4, P = P_, Q = Q_, S = S_;
+    static constexpr int BM = 64, NB = 2, NW = 8;
+    static constexpr int UPW = 2;             // one l tile, both row tiles
+    static constexpr int RW2 = RW2_;
+    static constexpr int QT = Q / 32, QH = QT / 2;
+    static constexpr int KQ = K * Q;
+    static constexpr int N_IN = K * P, N_OUT = K * S;
+    static constexpr bool PRIV = PRIV_;
+    using S1 = Stage1<P_, Q_>;                        // shared ring: the pair's columns together
+    using S1P = Stage1<P_, Q_ / 2, Q_ / 32, 2>;       // private rings: this wave's half of the columns
+    static constexpr int XR = PRIV ? S1P::XR : 3;
+    static constexpr int KS = Q / 16;
+    static constexpr int NLT_ALL = S / 32;
+    static constexpr int UNITS = NLT_ALL * NB;
+    static constexpr int PASSES = UNITS / (NW * UPW);
+    static constexpr int NLT = 1;
+    static constexpr int Y1_STRIDE = KQ + 8;
+    static constexpr size_t LDS_Y1 = (size_t)BM * Y1_STRIDE * 2;
+    static constexpr size_t LDS_X = (size_t)(PRIV ? 8 : 4) * XR * 8192;  // one ring per wave / per pair of waves
+    static constexpr size_t LDS_BYTES = LDS_Y1 > LDS_X ? LDS_Y1 : LDS_X;
+    static_assert(P % 64 == 0 && P / 64 >= XR && Q % 64 == 0 && S % 32 == 0, "tile shapes");
+    static_assert(UNITS % (NW * UPW) == 0, "stage-2 split");
+    static_assert(KS % RW2 == 0 && RW2 % 2 == 0 && RW2 >= 2, "stage-2 ring");
+    static_assert(LDS_BYTES <= kMaxLdsBytes, "LDS");
+};
+
+template <typename C, bool BIAS, bool ACT>
+__global__ void __launch_bounds__(512)
+fwd_frag8_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ RF1,
+                 const uint16_t* __restrict__ LF2, const uint16_t* __restrict__ bias, uint16_t* __restrict__ y,
+                 uint16_t* __restrict__ y_pre, int64_t B)
+{
+    extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int ln = lane & 31, g = lane >> 5;
+    const int64_t b0 = (int64_t)blockIdx.x * C::BM;
+
+    u32x4 wr2[C::RW2][C::NLT];  // stage-2 weight ring
+    {
+        const int kk = wave & 3, half = wave >> 2;
+        f32x16 acc[C::QH * C::NB];
+        if constexpr (C::PRIV)
+            stage1_block<typename C::S1P>(x, RF1, b0, B, kk, lane, lds + (size_t)wave * C::XR * 4096, acc, half * C::QH);
+        else
+            stage1_half<typename C::S1>(x, RF1, b0, B, kk, half, lane, lds + (size_t)kk * C::XR * 4096, acc);
+        __builtin_amdgcn_sched_barrier(0);
+        {
+            const uint16_t* wbase[C::NLT];
+            stage2_wbase<C>(LF2, wave * C::UPW, lane, wbase);
+#pragma unroll
+            for (int d = 0; d < C::RW2 - 1; ++d) stage2_issue_w<C>(wbase, wr2, d / C::KS, d % C::KS, d);
+        }
+        __syncthreads();  // every wave is done with the x rings: the space becomes Y1s
+#pragma unroll
+        for (int jl = 0; jl < C::QH; ++jl)
+#pragma unroll
+            for (int nb = 0; nb < C::NB; ++nb)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const f32x16& a = acc[jl * C::NB + nb];
+                    const int j = (half * C::QH + jl) * 32 + 8 * i4 + 4 * g;
+                    *reinterpret_cast<u32x2*>(lds + (size_t)(nb * 32 + ln) * C::Y1_STRIDE + (j >> 2) * 16 + kk * 4) =
+                        u32x2{pack_bf16x2(a[4 * i4 + 0], a[4 * i4 + 1]), pack_bf16x2(a[4 * i4 + 2], a[4 * i4 + 3])};
+                }
+    }
+    __syncthreads();
+    stage2_pass<C, false, true, BIAS, ACT>(LF2, lds, bias, y, y_pre, b0, B, wave * C::UPW, lane, wr2);
+    for (int ps = 1; ps < C::PASSES; ++ps)
+        stage2_pass<C, false, false, BIAS, ACT>(LF2, lds, bias, y, y_pre, b0, B, (ps * C::NW + wave) * C::UPW, lane, wr2);
+}
+
+template <typename C>
+int launch8(const Problem& pb, const void* x, const uint16_t* RF1, const uint16_t* LF2, void* y, hipStream_t st)
+{
+    auto kern = pb.act ? fwd_frag8_kernel<C, true, true> : (pb.bias ? fwd_frag8_kernel<C, true, false> : fwd_frag8_kernel<C, false, false>);
+    hipError_t e = allow_dynamic_lds((const void*)kern, C::LDS_BYTES);
+    if (e != hipSuccess) return -4;
+    const int64_t grid = (pb.B + C::BM - 1) / C::BM;
+    if (grid > 0x7fffffffLL) return -2;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), C::LDS_BYTES, st, (const uint16_t*)x, RF1, LF2,
+                       (const uint16_t*)pb.bias, (uint16_t*)y, (uint16_t*)pb.y_pre, pb.B);
+    return hip_status(hipGetLastError());
+}
+
 template <typename C>
 int launch(const Problem& pb, const void* x, const uint16_t* RF1, const uint16_t* LF2, void* y, hipStream_t st)
 {
@@ -301,13 +395,13 @@ struct Entry {
 //                                 P     Q     S  UPW RW2
 const Entry kTable[] = {
     {192, 192, 192, launch<FwdFrag<192, 192, 192, 3, 6>>},    // ViT-B projection 768 -> 768
-    {192, 192, 768, launch<FwdFrag<192, 192, 768, 4, 6>>},    // GPT-2 small fc1 768 -> 3072
-    {256, 256, 1024, launch<FwdFrag<256, 256, 1024, 4, 8>>},  // GPT-2 medium fc1 1024 -> 4096
+    {192, 192, 768, launch8<FwdFrag8<192, 192, 768, 6, false>>},    // GPT-2 small fc1 768 -> 3072
+    {256, 256, 1024, launch8<FwdFrag8<256, 256, 1024, 8, false>>},  // GPT-2 medium fc1 1024 -> 4096
     {1024, 256, 256, launch<FwdFrag<1024, 256, 256, 4, 8>>},  // GPT-2 medium fc2 4096 -> 1024
     {768, 192, 192, launch<FwdFrag<768, 192, 192, 3, 6>>},    // GPT-2 small fc2 3072 -> 768
-    {256, 256, 256, launch<FwdFrag<256, 256, 256, 4, 8>>},    // GPT-2 medium projection 1024 -> 1024
+    {256, 256, 256, launch8<FwdFrag8<256, 256, 256, 8, false>>},    // GPT-2 medium projection 1024 -> 1024
     {192, 192, 576, launch<FwdFrag<192, 192, 576, 3, 6>>},    // ViT-B / GPT-2 small fused q,k,v 768 -> 2304
-    {256, 256, 768, launch<FwdFrag<256, 256, 768, 4, 8>>},    // GPT-2 medium fused q,k,v 1024 -> 3072
+    {256, 256, 768, launch8<FwdFrag8<256, 256, 768, 8, false>>},    // GPT-2 medium fused q,k,v 1024 -> 3072
     {128, 128, 128, launch<FwdFrag<128, 128, 128, 2, 4>>},    // width 512 (MLP-Mixer-S): 512 -> 512
     {128, 128, 512, launch<FwdFrag<128, 128, 512, 4, 4>>},    // 512 -> 2048
     {512, 128, 128, launch<FwdFrag<512, 128, 128, 2, 4>>},    // 2048 -> 512
