@@ -293,8 +293,8 @@ wgrad_gemm_kernel(WgradDesc d0, WgradDesc d1, int tiles0, int tiles)
 }
 
 // out[g][m][col(n)] = sum_z P[z][g][m][n];  col(n) = (n % seg_w) * (N / seg_w) + n / seg_w
-// (identity when seg_w == N).  Blocks [0, blocks0) reduce d0, the rest d1; one element per
-// thread, the chunk loop unrolled so that eight loads are in flight.
+// (identity when seg_w == N).  Blocks [0, blocks0) reduce d0, the rest d1; eight consecutive elements per
+// thread (16-byte loads of bf16 partial tiles, two 16-byte loads of fp32 ones), four chunks in flight.
 // Blocks from `blocks01` on (when cj.part is set) run the second pass of the bias gradient instead.
 template <bool OUT_F32>
 __global__ void __launch_bounds__(256)
@@ -307,41 +307,74 @@ wgrad_reduce_kernel(WgradDesc d0, WgradDesc d1, int blocks0, int nz, ColsumJob c
     }
     const bool first = (int)blockIdx.x < blocks0;
     const WgradDesc& d = first ? d0 : d1;
-    const size_t total = (size_t)d.G * d.M * d.N;
-    const size_t e = (size_t)(blockIdx.x - (first ? 0 : blocks0)) * 256 + threadIdx.x;
+    const size_t total = (size_t)d.G * d.M * d.N;  // a multiple of 8: N is a multiple of 32
+    const size_t e = ((size_t)(blockIdx.x - (first ? 0 : blocks0)) * 256 + threadIdx.x) * 8;
     if (e >= total) return;
-    float s = 0.f;
+    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     int z = 0;
     if (d.p_bf16) {
         const uint16_t* P = reinterpret_cast<const uint16_t*>(d.P) + e;
-        for (; z + 8 <= nz; z += 8) {
-            uint16_t v[8];
+        for (; z + 4 <= nz; z += 4) {
+            u32x4 v[4];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = P[(size_t)(z + u) * total];
+            for (int u = 0; u < 4; ++u) v[u] = ldg128(P + (size_t)(z + u) * total);
 #pragma unroll
-            for (int u = 0; u < 8; ++u) s += bf16_to_f32(v[u]);
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    s[2 * w] += __uint_as_float(v[u][w] << 16);
+                    s[2 * w + 1] += __uint_as_float(v[u][w] & 0xffff0000u);
+                }
         }
-        for (; z < nz; ++z) s += bf16_to_f32(P[(size_t)z * total]);
+        for (; z < nz; ++z) {
+            const u32x4 v = ldg128(P + (size_t)z * total);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                s[2 * w] += __uint_as_float(v[w] << 16);
+                s[2 * w + 1] += __uint_as_float(v[w] & 0xffff0000u);
+            }
+        }
     } else {
         const float* P = d.P + e;
-        for (; z + 8 <= nz; z += 8) {
-            float v[8];
+        for (; z + 4 <= nz; z += 4) {
+            f32x4 v[4][2];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = P[(size_t)(z + u) * total];
+            for (int u = 0; u < 4; ++u) {
+                v[u][0] = *reinterpret_cast<const f32x4*>(P + (size_t)(z + u) * total);
+                v[u][1] = *reinterpret_cast<const f32x4*>(P + (size_t)(z + u) * total + 4);
+            }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) s += v[u];
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int w = 0; w < 8; ++w) s[w] += v[u][w >> 2][w & 3];
         }
-        for (; z < nz; ++z) s += P[(size_t)z * total];
+        for (; z < nz; ++z)
+#pragma unroll
+            for (int w = 0; w < 8; ++w) s[w] += P[(size_t)z * total + w];
     }
+    // the eight elements share a row and (seg_w being a multiple of 8) a segment: their outputs are nseg apart
     const int nseg = d.N / d.seg_w;
     const size_t rowbase = e / d.N * d.N;
     const int n = (int)(e - rowbase);
     const size_t o = rowbase + (size_t)(n % d.seg_w) * nseg + n / d.seg_w;
     if (OUT_F32) {
-        ((float*)d.out)[o] = s;
+        float* out = (float*)d.out + o;
+        if (nseg == 1) {
+            *reinterpret_cast<f32x4*>(out) = f32x4{s[0], s[1], s[2], s[3]};
+            *reinterpret_cast<f32x4*>(out + 4) = f32x4{s[4], s[5], s[6], s[7]};
+        } else {
+#pragma unroll
+            for (int w = 0; w < 8; ++w) out[(size_t)w * nseg] = s[w];
+        }
     } else {
-        const uint32_t pk = pack_bf16x2(s, 0.f);
-        ((uint16_t*)d.out)[o] = (uint16_t)(pk & 0xffffu);
+        uint16_t* out = (uint16_t*)d.out + o;
+        if (nseg == 1) {
+            *reinterpret_cast<u32x4*>(out) =
+                u32x4{pack_bf16x2(s[0], s[1]), pack_bf16x2(s[2], s[3]), pack_bf16x2(s[4], s[5]), pack_bf16x2(s[6], s[7])};
+        } else {
+#pragma unroll
+            for (int w = 0; w < 8; ++w) out[(size_t)w * nseg] = (uint16_t)(pack_bf16x2(s[w], 0.f) & 0xffffu);
+        }
     }
 }
 
@@ -408,7 +441,8 @@ int wgrad_gemm_pair(const WgradDesc& d0, const WgradDesc& d1, int nz, hipStream_
 
 int wgrad_reduce_pair(const WgradDesc& d0, const WgradDesc& d1, bool out_f32, int nz, hipStream_t st, const ColsumJob* cj)
 {
-    const size_t b0 = ((size_t)d0.G * d0.M * d0.N + 255) / 256, b1 = ((size_t)d1.G * d1.M * d1.N + 255) / 256;
+    if (d0.seg_w % 8 != 0 || d1.seg_w % 8 != 0 || d0.N % 8 != 0 || d1.N % 8 != 0) return -2;  // eight elements per thread
+    const size_t b0 = ((size_t)d0.G * d0.M * d0.N / 8 + 255) / 256, b1 = ((size_t)d1.G * d1.M * d1.N / 8 + 255) / 256;
     ColsumJob job{};
     if (cj) job = *cj;
     const size_t b2 = cj ? (size_t)colsum_final_blocks(job) : 0;
