@@ -29,6 +29,12 @@ constexpr int KB = 32;    // batch rows per pipeline step (two 16-row K-steps, o
 constexpr int NTHR = 512;  // eight waves per workgroup
 constexpr int NSTG = 1;     // register stages of the operand loads (rows fetched NSTG steps before they are stored)
 
+// Padding of the LDS rows (bf16 elements).  A half wave of a transposing read touches four consecutive rows,
+// 64 bytes (16 banks) of each: with a row stride of an odd multiple of 64 bytes the four rows fall on disjoint
+// quarters of the 64 banks.  Strides: 128 -> 160, 96 -> 96, 64 -> 96, 32 -> 32 elements.  (The 16-byte writes stay
+// conflict-free: 16 lanes write 256 bytes that are either contiguous or in two disjoint bank ranges.)
+constexpr int lds_pad(int tile) { return (tile == 128 || tile == 64) ? 32 : 0; }
+
 // Transposing LDS read: within each 16 lanes, lane i receives element (i % 4) of lanes
 // i/4, 4 + i/4, 8 + i/4, 12 + i/4.
 __device__ __forceinline__ u32x2 lds_tr16(const uint16_t* p)
@@ -59,7 +65,7 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
     constexpr int MT = TM / 32, NT = TN / 32;
     constexpr int MTW = MSPLIT ? MT / 2 : MT;  // m tiles of one wave
     static_assert(!MSPLIT || MT % 2 == 0, "row split");
-    constexpr int SA = TM + 8, SB = TN + 8;  // LDS row strides (bf16 elements)
+    constexpr int SA = TM + lds_pad(TM), SB = TN + lds_pad(TN);  // LDS row strides (bf16 elements)
     constexpr int BUF = 4 * KB * (SA + SB);  // one pipeline buffer: As [4][KB][SA], then Bs [4][KB][SB]
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
 
@@ -187,14 +193,22 @@ __device__ __forceinline__ void wgrad_gemm_body(const WgradDesc& d, const int ti
             __syncthreads();
             bf16x8 af[MTW], bfr[NT];
             const int krow = MSPLIT ? 0 : 16 * kh, mcol = MSPLIT ? kh * MTW * 32 : 0;
+            if constexpr (MSPLIT) {
+                // large tiles: the next rows are requested first, so that they travel during the fragment reads too
+                store_step(r0 + (k + 1) * KB, 0, nxt);
+                load_step(r0 + (k + 2) * KB, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
 #pragma unroll
             for (int mt = 0; mt < MTW; ++mt) af[mt] = frag_tr(cur + woff_a, SA, krow, mcol + mt * 32, lane);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) bfr[nt] = frag_tr(cur + woff_b, SB, krow, nt * 32, lane);
             __builtin_amdgcn_sched_barrier(0);
-            store_step(r0 + (k + 1) * KB, 0, nxt);
-            load_step(r0 + (k + 2) * KB, 0);
-            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (!MSPLIT) {
+                store_step(r0 + (k + 1) * KB, 0, nxt);
+                load_step(r0 + (k + 2) * KB, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
 #pragma unroll
             for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
@@ -383,7 +397,8 @@ int tiles_of(const WgradDesc& d, int tm, int tn) { return (d.M / tm) * (d.N / tn
 template <int TM, int TN>
 int launch_gemm(const WgradDesc& d0, const WgradDesc* d1, int nz, hipStream_t st)
 {
-    constexpr size_t lds = (size_t)2 * 4 * KB * (TM + 8 + TN + 8) * 2;  // two pipeline buffers
+    constexpr size_t lds = (size_t)2 * 4 * KB * (TM + lds_pad(TM) + TN + lds_pad(TN)) * 2;  // two pipeline buffers
+    static_assert(lds <= kMaxLdsBytes, "LDS");
     auto kern = wgrad_gemm_kernel<TM, TN>;
     if (allow_dynamic_lds((const void*)kern, lds) != hipSuccess)
         return -4;
