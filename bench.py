@@ -343,6 +343,21 @@ def measure_extras(ly: Layer, calls: int):
         xs, dys, _, dx = sets[i % nsets]
         binding.monarch_bwd_bias(dys, xs, Rd, Ld, dx, dR, dL, dbias, workspace=ws)
 
+    # the layer with the block's nonlinearity: forward writing pre-activation and activation, backward taking both
+    hbuf = [torch.empty_like(st[2]) for st in sets[:min(nsets, 2)]]
+    xpre = [torch.empty_like(st[0]).normal_() for st in sets[:min(nsets, 2)]]
+
+    def fwd_gelu_only(i):
+        xs, _, y, _ = sets[i % nsets]
+        binding.monarch_fwd_bias_gelu(xs, Rd, Ld, biasd, hbuf[i % len(hbuf)], y, workspace=fws if fneed else None)
+
+    def bwd_gelu_in_only(i):
+        xs, dys, _, dx = sets[i % nsets]
+        binding.monarch_bwd_bias_gelu_in(dys, xs, xpre[i % len(xpre)], Rd, Ld, dx, dR, dL, dbias, workspace=ws)
+
+    ex["fwd_bias_gelu_ms"] = timed_runs(fwd_gelu_only, calls)[0]
+    ex["bwd_bias_gelu_in_ms"] = timed_runs(bwd_gelu_in_only, calls)[0]
+    del hbuf, xpre
     ex["fwd_bias_ms"] = timed_runs(fwd_bias_only, calls)[0]
     ex["fwd_then_add_ms"] = timed_runs(fwd_then_add, calls)[0]   # forward with workspace + a separate framework add
     ex["bwd_bias_ms"] = timed_runs(bwd_bias_only, calls)[0]

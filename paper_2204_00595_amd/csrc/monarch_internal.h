@@ -121,6 +121,11 @@ size_t bwd_wide_workspace(const Problem& pb);
 int bwd_wide(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx,
              void* dR, void* dL, void* ws, hipStream_t st);
 
+// bf16, k = 4, wide blocks with long blocks (p >= 768): step 1 as a GEMM of its own, Y1[b][kk*q + j] (B x k*q bf16) from x and the
+// packed R of the backward's prep pass (monarch_mfma_y1.hip)
+bool y1_gemm_supported(const Problem& pb);
+int y1_gemm(const Problem& pb, const void* x, const uint16_t* XF, uint16_t* Y1, hipStream_t st);
+
 // bf16, k = 4, wide blocks: transposed multiply y = x M on the backward's data kernel
 size_t fwd_t_wide_workspace(const Problem& pb);
 int fwd_t_wide(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);

@@ -418,8 +418,8 @@ int launch_data(const Problem& pb, const void* dy, const void* x, const uint16_t
     // (the nonlinearity's factor is applied here only by the recomputing backward)
     auto kern = !dY1ws ? bwd_wide_data_kernel<C, 1, false>
                        : (Y1ws ? (pb.x_pre ? bwd_wide_data_kernel<C, 0, true> : bwd_wide_data_kernel<C, 0, false>)
-                               : bwd_wide_data_kernel<C, 2, false>);
-    if (pb.x_pre && !(dY1ws && Y1ws)) return -2;
+                               : (pb.x_pre ? bwd_wide_data_kernel<C, 2, true> : bwd_wide_data_kernel<C, 2, false>));
+    if (pb.x_pre && !dY1ws) return -2;
     if (allow_dynamic_lds((const void*)kern, C::LDS_BYTES) != hipSuccess)
         return -4;
     const int64_t grid = (pb.B + C::BM - 1) / C::BM;
@@ -565,7 +565,15 @@ int bwd_wide(const Problem& pb, const void* dy, const void* x, const void* R, co
     hipLaunchKernelGGL(prep_frag_kernel, dim3((unsigned)(nprep + (want_db ? colsum_partial_blocks(cj) : 0))), dim3(256), 0,
                        st, (const uint16_t*)L, (const uint16_t*)R, XF, LF, RF, pb.p, pb.q, pb.s, e->jg, e->ig, cj, nprep);
     if (hipGetLastError() != hipSuccess) return -4;
-    int rc = e->fn(pb, dy, x, XF, LF, RF, dx, pb.saved ? nullptr : Y1ws, dY1ws, st);
+    // Step 1 (Y1, for dL) is recomputed either by the data kernel itself or, for the shapes that have it, by a
+    // GEMM of its own with four times the rows per workgroup (monarch_mfma_y1.hip); not at all when the forward saved it.
+    const bool y1_apart = !pb.saved && y1_gemm_supported(pb);
+    int rc = 0;
+    if (y1_apart) {
+        rc = y1_gemm(pb, x, XF, Y1ws, st);
+        if (rc) return rc;
+    }
+    rc = e->fn(pb, dy, x, XF, LF, RF, dx, (pb.saved || y1_apart) ? nullptr : Y1ws, dY1ws, st);
     if (rc) return rc;
 
     WgradDesc dl, dr;

@@ -52,6 +52,23 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
+// Workgroup barrier for data handed over through LDS, which leaves global loads in flight.
+// __syncthreads() carries workgroup-scope fences, for which the compiler makes the wave wait until every
+// outstanding global load has returned (s_waitcnt vmcnt(0)) -- a fence restricted to LDS does the same for
+// global_load_lds requests, which count as LDS writes.  A prefetch that is meant to stay in flight across the
+// barrier is drained there, and the wave pays the full memory latency at every barrier.  Here the wave waits
+// for its own LDS operations only (lgkmcnt(0)); the empty asm statements keep the compiler from moving memory
+// operations across.  What global_load_lds (DMA) writes into LDS is NOT covered: the wave that requested it
+// waits for it explicitly (s_waitcnt vmcnt(n)) before it arrives here.  Keep __syncthreads() wherever global
+// memory written by one wave is read by another after the barrier.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 // (lo16 of a) | (lo16 of b) << 16   and   (hi16 of a) | (hi16 of b) << 16
 __device__ __forceinline__ uint32_t pick_lo16(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
 __device__ __forceinline__ uint32_t pick_hi16(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }

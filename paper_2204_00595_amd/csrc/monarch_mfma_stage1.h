@@ -210,7 +210,7 @@ __device__ __forceinline__ void stage1_half(const uint16_t* __restrict__ x, cons
         else if (c64 + 1 < C::C1) wait_vmcnt<8 * QH + 4>();
         else wait_vmcnt<8 * QH>();
         __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();  // the partner's rows are there too, and nobody reads chunk c64-1 any more
+        lds_barrier();  // the partner's rows are there too, and nobody reads chunk c64-1 any more (loads stay in flight)
         if (c64 + 2 < C::C1) issue_x(c64 + 2);
         read_x(c64, 0, 0);
 #pragma unroll
