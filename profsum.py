@@ -69,7 +69,7 @@ def cmd_traffic(args):
     calls = {"monarch_fwd": [0.0, 0.0], "monarch_fwd_ws": [0.0, 0.0], "monarch_bwd": [0.0, 0.0]}
     per_kernel = {}
     for k in sorted(fetch):
-        if k == COPY_KERNEL or not any(t in k for t in ("fwd_", "bwd_", "wgrad_", "prep_", "pack64", "transpose64", "transpose_blocks", "reduce_sq16", "generic_", "fill_zero", "f32_to_bf16")):
+        if k == COPY_KERNEL or not any(t in k for t in ("fwd_", "bwd_", "wgrad_", "prep_", "y1_gemm", "pack64", "transpose64", "transpose_blocks", "reduce_sq16", "generic_", "fill_zero", "f32_to_bf16")):
             continue
         fb, wb = fetch[k] * f_scale * 1024.0, write.get(k, 0.0) * w_scale * 1024.0
         per_kernel[k] = {"fetch_bytes": fb, "write_bytes": wb}
