@@ -145,6 +145,7 @@ MODEL_LAYERS = [
     ("qkv_768_2304", "bf16", 1100, 4, 192, 192, 576),
     ("gpt2m_qkv_1024_3072", "bf16", 1100, 4, 256, 256, 768),
     ("gpt2s_fc2_3072_768", "bf16", 1100, 4, 768, 192, 192),
+    ("gpt2m_fc2_4096_1024", "bf16", 333, 4, 1024, 256, 256),   # ragged against the 256-row tiles of the step-1 GEMM
     ("w512_proj_512_512", "bf16", 1100, 4, 128, 128, 128),
     ("w512_fc1_512_2048", "bf16", 1100, 4, 128, 128, 512),
     ("w512_fc2_2048_512", "bf16", 1100, 4, 512, 128, 128),
