@@ -299,7 +299,7 @@ int monarch_project(const void* A, void* R, void* L, int n, int m,
  * backward returns, for a real loss, grad z = dLoss/dRe z + i dLoss/dIm z (the convention of automatic
  * differentiation):  dx = dy conj(M),  dL[c] = dW[c]^T conj(U[c]),  dR[kk] = dY1[kk]^T conj(x[kk]).
  * Shape-generic kernels only; dR and dL are reduced with fp32 atomics (reproducible up to summation
- * order); no workspace.  flags: MONARCH_FLAG_PERM_B only. */
+ * order); no workspace (monarch_bwd_c64_ws takes one).  flags: MONARCH_FLAG_PERM_B only. */
 int monarch_fwd_c64(const void* x, const void* R, const void* L, void* y,
                     int64_t batch, int n_in, int k, int q, int s, void* stream, unsigned flags);
 /* Conjugate transpose applied to every row:  y = x conj(M),  x (batch, k*s) -> y (batch, n_in), complex64.
@@ -312,6 +312,18 @@ int monarch_fwd_h_c64(const void* x, const void* R, const void* L, void* y,
 int monarch_bwd_c64(const void* dy, const void* x, const void* R, const void* L,
                     void* dx, void* dR, void* dL,
                     int64_t batch, int n_in, int k, int q, int s, void* stream, unsigned flags);
+/* monarch_bwd_c64 with a workspace, for batches where the atomics of the call above dominate (every row tile
+ * adds a full copy of dR and dL): with `workspace` (device memory, 256-byte aligned, at least
+ * monarch_bwd_c64_workspace_bytes(...) bytes; contents ignored on entry, unspecified on exit) the three
+ * batch-major operands of the weight gradients (U, dY1, dW) are written there by the data kernel and one tiled
+ * launch contracts them over the batch; only the partial sums of its batch chunks meet in atomics.  Same
+ * results up to fp32 summation order.  workspace == NULL: exactly monarch_bwd_c64.  A short or misaligned
+ * workspace returns MONARCH_ERR_WORKSPACE; other errors as monarch_bwd_c64. */
+size_t monarch_bwd_c64_workspace_bytes(int64_t batch, int n_in, int k, int q, int s, unsigned flags);
+int monarch_bwd_c64_ws(const void* dy, const void* x, const void* R, const void* L,
+                       void* dx, void* dR, void* dL,
+                       int64_t batch, int n_in, int k, int q, int s, void* stream,
+                       void* workspace, size_t workspace_bytes, unsigned flags);
 
 /* Factors that make the square complex Monarch matrix a discrete Fourier transform (the model of the
  * MRI experiment starts from the inverse FFT): with n = m*m and w = exp(-2 pi i / n),

@@ -32,7 +32,7 @@ EXPORTS = (
     "monarch_fwd", "monarch_fwd_ex", "monarch_fwd_ws", "monarch_fwd_static", "monarch_fwd_bias", "monarch_fwd_workspace_bytes", "monarch_bwd",
     "monarch_bwd_bias", "monarch_fwd_bias_gelu", "monarch_bwd_bias_gelu_in",
     "monarch_bwd_workspace_bytes",
-    "monarch_fwd_t", "monarch_fwd_t_workspace_bytes", "monarch_saved_bytes", "monarch_fwd_save", "monarch_bwd_saved", "monarch_fwd_c64", "monarch_fwd_h_c64", "monarch_bwd_c64", "monarch_dft_factors", "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy", "monarch_launch_probe",
+    "monarch_fwd_t", "monarch_fwd_t_workspace_bytes", "monarch_saved_bytes", "monarch_fwd_save", "monarch_bwd_saved", "monarch_fwd_c64", "monarch_fwd_h_c64", "monarch_bwd_c64", "monarch_bwd_c64_ws", "monarch_bwd_c64_workspace_bytes", "monarch_dft_factors", "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy", "monarch_launch_probe",
 )
 
 _lib = None
@@ -94,6 +94,10 @@ def lib() -> ctypes.CDLL:
         L.monarch_fwd_h_c64.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, vp, cu]
         L.monarch_bwd_c64.restype = ci
         L.monarch_bwd_c64.argtypes = [vp] * 7 + [i64, ci, ci, ci, ci, vp, cu]
+        L.monarch_bwd_c64_ws.restype = ci
+        L.monarch_bwd_c64_ws.argtypes = [vp] * 7 + [i64, ci, ci, ci, ci, vp, vp, sz, cu]
+        L.monarch_bwd_c64_workspace_bytes.restype = sz
+        L.monarch_bwd_c64_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, cu]
         L.monarch_dft_factors.restype = ci
         L.monarch_dft_factors.argtypes = [vp, vp, ci, ci, vp]
         L.monarch_project.restype = ci
@@ -654,6 +658,35 @@ def monarch_bwd_c64(dy: torch.Tensor, x: torch.Tensor, R: torch.Tensor, L: torch
                                    dR.data_ptr(), dL.data_ptr(), B, k * p, k, q, s, _stream_ptr(stream), flags)
     if rc != MONARCH_OK:
         raise MonarchError(rc, "monarch_bwd_c64")
+    return dx, dR, dL
+
+
+def monarch_bwd_c64_workspace_bytes(batch: int, n_in: int, k: int, q: int, s: int, flags: int = 0) -> int:
+    return int(lib().monarch_bwd_c64_workspace_bytes(batch, n_in, k, q, s, flags))
+
+
+def monarch_bwd_c64_ws(dy: torch.Tensor, x: torch.Tensor, R: torch.Tensor, L: torch.Tensor,
+                       workspace: torch.Tensor | None = None, flags: int = 0, stream=None):
+    """monarch_bwd_c64 with the weight gradients contracted by a GEMM over operands kept in a workspace
+    (allocated when not given)."""
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    dev, dt = x.device, torch.complex64
+    _check(x, "x", (B, k * p), dt, dev)
+    _check(dy, "dy", (B, k * s), dt, dev)
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    dx, dR, dL = torch.empty_like(x), torch.empty_like(R), torch.empty_like(L)
+    need = monarch_bwd_c64_workspace_bytes(B, k * p, k, q, s, flags)
+    if workspace is None:
+        workspace = _scratch(max(need, 256), dev, stream)
+    with torch.cuda.device(dev):
+        rc = lib().monarch_bwd_c64_ws(dy.data_ptr(), x.data_ptr(), R.data_ptr(), L.data_ptr(), dx.data_ptr(),
+                                      dR.data_ptr(), dL.data_ptr(), B, k * p, k, q, s, _stream_ptr(stream),
+                                      workspace.data_ptr(), workspace.numel() * workspace.element_size(), flags)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, "monarch_bwd_c64_ws")
     return dx, dR, dL
 
 

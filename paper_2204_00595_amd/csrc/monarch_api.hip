@@ -441,6 +441,21 @@ int monarch_fwd_h_c64(const void* x, const void* R, const void* L, void* y, int6
 int monarch_bwd_c64(const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR, void* dL,
                     int64_t batch, int n_in, int k, int q, int s, void* stream, unsigned flags)
 {
+    return monarch_bwd_c64_ws(dy, x, R, L, dx, dR, dL, batch, n_in, k, q, s, stream, nullptr, 0, flags);
+}
+
+size_t monarch_bwd_c64_workspace_bytes(int64_t batch, int n_in, int k, int q, int s, unsigned flags)
+{
+    Problem pb;
+    if (make_problem(pb, batch, n_in, k, q, s, MONARCH_F32, flags)) return 0;
+    if ((flags & ~MONARCH_FLAG_PERM_B) || !complex_bwd_supported(pb)) return 0;
+    return complex_bwd_workspace(pb);
+}
+
+int monarch_bwd_c64_ws(const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR, void* dL,
+                       int64_t batch, int n_in, int k, int q, int s, void* stream, void* workspace,
+                       size_t workspace_bytes, unsigned flags)
+{
     Problem pb;
     int rc = make_problem(pb, batch, n_in, k, q, s, MONARCH_F32, flags);
     if (rc) return rc;
@@ -450,7 +465,8 @@ int monarch_bwd_c64(const void* dy, const void* x, const void* R, const void* L,
         !aligned(dR, 16) || !aligned(dL, 16))
         return MONARCH_ERR_INVALID;
     if (!complex_bwd_supported(pb)) return MONARCH_ERR_UNSUPPORTED;
-    return complex_bwd(pb, dy, x, R, L, dx, dR, dL, (hipStream_t)stream);
+    if (workspace && (workspace_bytes < complex_bwd_workspace(pb) || !aligned(workspace, 256))) return MONARCH_ERR_WORKSPACE;
+    return complex_bwd(pb, dy, x, R, L, dx, dR, dL, workspace, (hipStream_t)stream);
 }
 
 int monarch_dft_factors(void* R, void* L, int m, int inverse, void* stream)

@@ -3,7 +3,7 @@
 // Review), and its MRI model is one complex Monarch matrix initialised to the inverse FFT.
 //
 // Same steps as the real kernels (Section 3.3 steps 1-3, permutations of Definition 3.1), in the
-// shape-generic SIMT form: one workgroup per tile of BM batch rows, the vectors between the steps in
+// shape-generic SIMT form: one workgroup per tile of BM batch rows, the vector between the two factors in
 // LDS, one thread per output element with BM complex accumulators, so every weight is read once per
 // workgroup.  No transposes are conjugated in the forward (M^T, not M^*).  Gradients use the
 // convention of automatic differentiation for a real loss: grad z = dLoss/dRe z + i dLoss/dIm z, i.e.
@@ -33,6 +33,10 @@ __device__ __forceinline__ cf cmul_conj_acc(cf acc, cf a, cf b)  // acc + a * co
 }
 __device__ __forceinline__ cf ldc(const float2* p) { const float2 v = *p; return cf{v.x, v.y}; }
 
+// Only the vector between the two factors is kept in LDS (BM rows of k*q values): the inputs of a stage are read
+// from global memory where all lanes of a wave that work on one block ask for the same address (one broadcast load),
+// which leaves room for four rows per workgroup at n = 4096 and so a quarter of the weight traffic per row.
+// Rows past the end of the batch are computed from the last row and not stored.
 template <int BM>
 __global__ void __launch_bounds__(kCThreads)
 complex_fwd_kernel(const float2* __restrict__ x, const float2* __restrict__ R, const float2* __restrict__ L,
@@ -40,27 +44,22 @@ complex_fwd_kernel(const float2* __restrict__ x, const float2* __restrict__ R, c
 {
     extern __shared__ float2 ldsc[];
     const int n_in = k * p, kq = k * q, n_out = k * s;
-    float2* xs = ldsc;
-    float2* us = ldsc + (size_t)BM * n_in;
+    float2* us = ldsc;
     const int64_t b0 = (int64_t)blockIdx.x * BM;
     const int tid = threadIdx.x;
-    for (int e = tid; e < BM * n_in; e += kCThreads) {
-        const int b = e / n_in, c = e - b * n_in;
-        const int64_t row = b0 + b;
-        xs[e] = row < B ? x[row * n_in + c] : make_float2(0.f, 0.f);
-    }
-    __syncthreads();
+    const float2* xrow[BM];
+#pragma unroll
+    for (int b = 0; b < BM; ++b) xrow[b] = x + (b0 + b < B ? b0 + b : B - 1) * n_in;
     for (int f = tid; f < kq; f += kCThreads) {
         const int kk = f / q;
         const float2* Rrow = R + (size_t)f * p;
-        const float2* xk = xs + kk * p;
         cf acc[BM];
 #pragma unroll
         for (int b = 0; b < BM; ++b) acc[b] = cf{0.f, 0.f};
         for (int i = 0; i < p; ++i) {
             const cf w = ldc(Rrow + i);
 #pragma unroll
-            for (int b = 0; b < BM; ++b) acc[b] = cmul_acc(acc[b], w, ldc(xk + b * n_in + i));
+            for (int b = 0; b < BM; ++b) acc[b] = cmul_acc(acc[b], w, ldc(xrow[b] + kk * p + i));
         }
         const int g = mid_dest(f, k, q, perm_b != 0);
 #pragma unroll
@@ -87,63 +86,58 @@ complex_fwd_kernel(const float2* __restrict__ x, const float2* __restrict__ R, c
     }
 }
 
-// LDS: xs[BM][n_in], us[BM][kq] (U recomputed), dws[BM][k*s] (dW[b][c*s + l]), dus[BM][kq] (dU).
-// dx is written directly; the dR and dL contributions of the tile are added with fp32 atomics (one
-// per component) into dR / dL, which the host zero-filled before the launch.
-template <int BM>
+// LDS: us[BM][kq] (U recomputed) and dus[BM][kq] (dU); x and dy are read from global memory (see above).
+// dx is written directly.  WS = false: the dR and dL contributions of the tile are added with fp32 atomics (one per
+// component) into dR / dL, which the host zero-filled before the launch.  WS = true: the three batch-major operands of
+// the weight gradients go to the workspace instead -- U[b][c*q + r], dY1[b][kk*q + j] (mid permutation undone) and
+// dW[b][c*s + l] (outer permutation undone) -- and complex_wgrad_kernel contracts them over the batch.
+template <int BM, bool WS>
 __global__ void __launch_bounds__(kCThreads)
 complex_bwd_kernel(const float2* __restrict__ dy, const float2* __restrict__ x, const float2* __restrict__ R,
                    const float2* __restrict__ L, float2* __restrict__ dx, float* __restrict__ dRacc,
-                   float* __restrict__ dLacc, int64_t B, int k, int p, int q, int s, int perm_b)
+                   float* __restrict__ dLacc, float2* __restrict__ Uws, float2* __restrict__ dY1ws,
+                   float2* __restrict__ dWws, int64_t B, int k, int p, int q, int s, int perm_b)
 {
     extern __shared__ float2 ldsc[];
     const int n_in = k * p, kq = k * q, n_out = k * s;
-    float2* xs = ldsc;
-    float2* us = xs + (size_t)BM * n_in;
-    float2* dws = us + (size_t)BM * kq;
-    float2* dus = dws + (size_t)BM * n_out;
+    float2* us = ldsc;
+    float2* dus = us + (size_t)BM * kq;
     const int64_t b0 = (int64_t)blockIdx.x * BM;
     const int tid = threadIdx.x;
     const bool pb = perm_b != 0;
-    for (int e = tid; e < BM * n_in; e += kCThreads) {
-        const int b = e / n_in, c = e - b * n_in;
-        const int64_t row = b0 + b;
-        xs[e] = row < B ? x[row * n_in + c] : make_float2(0.f, 0.f);
+    const float2* xrow[BM];
+    const float2* dyrow[BM];
+#pragma unroll
+    for (int b = 0; b < BM; ++b) {
+        const int64_t row = b0 + b < B ? b0 + b : B - 1;
+        xrow[b] = x + row * n_in;
+        dyrow[b] = dy + row * n_out;
     }
-    for (int e = tid; e < BM * n_out; e += kCThreads) {
-        const int b = e / n_out, o = e - b * n_out;
-        const int l = o / k, c = o - l * k;
-        const int64_t row = b0 + b;
-        dws[b * n_out + c * s + l] = row < B ? dy[row * n_out + o] : make_float2(0.f, 0.f);
-    }
-    __syncthreads();
     for (int f = tid; f < kq; f += kCThreads) {  // step 1 again, with the mid permutation
         const int kk = f / q;
         const float2* Rrow = R + (size_t)f * p;
-        const float2* xk = xs + kk * p;
         cf acc[BM];
 #pragma unroll
         for (int b = 0; b < BM; ++b) acc[b] = cf{0.f, 0.f};
         for (int i = 0; i < p; ++i) {
             const cf w = ldc(Rrow + i);
 #pragma unroll
-            for (int b = 0; b < BM; ++b) acc[b] = cmul_acc(acc[b], w, ldc(xk + b * n_in + i));
+            for (int b = 0; b < BM; ++b) acc[b] = cmul_acc(acc[b], w, ldc(xrow[b] + kk * p + i));
         }
         const int g = mid_dest(f, k, q, pb);
 #pragma unroll
         for (int b = 0; b < BM; ++b) us[b * kq + g] = make_float2(acc[b].re, acc[b].im);
     }
-    for (int g = tid; g < kq; g += kCThreads) {  // dU[c*q + r] = sum_l dW[c][l] conj(L[c][l][r])
+    for (int g = tid; g < kq; g += kCThreads) {  // dU[c*q + r] = sum_l dW[c][l] conj(L[c][l][r]),  dW[c][l] = dy[l*k + c]
         const int c = g / q, r = g - c * q;
         const float2* Lcol = L + (size_t)c * s * q + r;
-        const float2* dwc = dws + c * s;
         cf acc[BM];
 #pragma unroll
         for (int b = 0; b < BM; ++b) acc[b] = cf{0.f, 0.f};
         for (int l = 0; l < s; ++l) {
             const cf w = ldc(Lcol + (size_t)l * q);
 #pragma unroll
-            for (int b = 0; b < BM; ++b) acc[b] = cmul_conj_acc(acc[b], ldc(dwc + b * n_out + l), w);
+            for (int b = 0; b < BM; ++b) acc[b] = cmul_conj_acc(acc[b], ldc(dyrow[b] + (size_t)l * k + c), w);
         }
 #pragma unroll
         for (int b = 0; b < BM; ++b) dus[b * kq + g] = make_float2(acc[b].re, acc[b].im);
@@ -167,13 +161,31 @@ complex_bwd_kernel(const float2* __restrict__ dy, const float2* __restrict__ x, 
             if (row < B) dx[row * n_in + n] = make_float2(acc[b].re, acc[b].im);
         }
     }
+    if constexpr (WS) {
+        for (int e = tid; e < BM * kq; e += kCThreads) {
+            const int b = e / kq, f = e - b * kq;
+            const int64_t row = b0 + b;
+            if (row < B) {
+                Uws[row * kq + f] = us[e];
+                dY1ws[row * kq + f] = dus[b * kq + mid_dest(f, k, q, pb)];
+            }
+        }
+        for (int e = tid; e < BM * n_out; e += kCThreads) {
+            const int b = e / n_out, cl = e - b * n_out;
+            const int c = cl / s, l = cl - c * s;
+            const int64_t row = b0 + b;
+            if (row < B) dWws[row * n_out + cl] = dy[row * n_out + (size_t)l * k + c];
+        }
+        return;
+    }
     const int nL = k * s * q;
     for (int e = tid; e < nL; e += kCThreads) {  // dL[c][l][r] += sum_b dW[b][c][l] conj(U[b][c][r])
         const int cl = e / q, r = e - cl * q;
-        const int c = cl / s;
+        const int c = cl / s, l = cl - c * s;
         cf v = cf{0.f, 0.f};
 #pragma unroll
-        for (int b = 0; b < BM; ++b) v = cmul_conj_acc(v, ldc(dws + b * n_out + cl), ldc(us + b * kq + c * q + r));
+        for (int b = 0; b < BM; ++b)
+            if (b0 + b < B) v = cmul_conj_acc(v, ldc(dyrow[b] + (size_t)l * k + c), ldc(us + b * kq + c * q + r));
         unsafeAtomicAdd(dLacc + 2 * (size_t)e, v.re);
         unsafeAtomicAdd(dLacc + 2 * (size_t)e + 1, v.im);
     }
@@ -184,15 +196,91 @@ complex_bwd_kernel(const float2* __restrict__ dy, const float2* __restrict__ x, 
         const int g = mid_dest(f, k, q, pb);
         cf v = cf{0.f, 0.f};
 #pragma unroll
-        for (int b = 0; b < BM; ++b) v = cmul_conj_acc(v, ldc(dus + b * kq + g), ldc(xs + b * n_in + kk * p + i));
+        for (int b = 0; b < BM; ++b)
+            if (b0 + b < B) v = cmul_conj_acc(v, ldc(dus + b * kq + g), ldc(xrow[b] + kk * p + i));
         unsafeAtomicAdd(dRacc + 2 * (size_t)e, v.re);
         unsafeAtomicAdd(dRacc + 2 * (size_t)e + 1, v.im);
     }
 }
 
+// out[g][m][n] += sum over the rows b of batch chunk blockIdx.y of  A[b][g*a_g + m] * conj(Bm[b][g*b_g + n])
+// (complex64, fp32 arithmetic): both weight gradients of the complex backward, dL[c] = dW[c]^T conj(U[c]) and
+// dR[kk] = dY1[kk]^T conj(x[kk]), in one launch.  A workgroup owns a 64 x 64 tile of one group: 16 x 16 threads with
+// 4 x 4 accumulators each, the operands of 16 batch rows at a time staged in LDS; entries beyond M, N or the batch
+// read as zeros.  The chunks' partial tiles are added with fp32 atomics into the zero-filled outputs.
+struct CGemm {
+    const float2* A;
+    int64_t lda;
+    int a_g;
+    const float2* Bm;
+    int64_t ldb;
+    int b_g;
+    int M, N, G;
+    float* out;
+};
+constexpr int kCT = 64, kCK = 16;
+
+__global__ void __launch_bounds__(256)
+complex_wgrad_kernel(CGemm d0, CGemm d1, int tiles0, int64_t rows, int64_t rows_per_chunk)
+{
+    __shared__ float2 As[kCK][kCT + 1], Bs[kCK][kCT + 1];
+    const bool first = (int)blockIdx.x < tiles0;
+    const CGemm& d = first ? d0 : d1;
+    int t = (int)blockIdx.x - (first ? 0 : tiles0);
+    const int tn_count = (d.N + kCT - 1) / kCT, tm_count = (d.M + kCT - 1) / kCT;
+    const int tn = t % tn_count; t /= tn_count;
+    const int tm = t % tm_count;
+    const int g = t / tm_count;
+    const int m0 = tm * kCT, n0 = tn * kCT;
+    const int64_t row_lo = (int64_t)blockIdx.y * rows_per_chunk;
+    const int64_t row_hi = row_lo + rows_per_chunk < rows ? row_lo + rows_per_chunk : rows;
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    cf acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = cf{0.f, 0.f};
+    const float2 zero = make_float2(0.f, 0.f);
+    for (int64_t r0 = row_lo; r0 < row_hi; r0 += kCK) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = tid + i * 256;
+            const int rr = idx / kCT, cc = idx % kCT;
+            const int64_t row = r0 + rr;
+            As[rr][cc] = (row < row_hi && m0 + cc < d.M) ? d.A[row * d.lda + (size_t)g * d.a_g + m0 + cc] : zero;
+            Bs[rr][cc] = (row < row_hi && n0 + cc < d.N) ? d.Bm[row * d.ldb + (size_t)g * d.b_g + n0 + cc] : zero;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kb = 0; kb < kCK; ++kb) {
+            cf a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = ldc(&As[kb][ty * 4 + i]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = ldc(&Bs[kb][tx * 4 + j]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = cmul_conj_acc(acc[i][j], a[i], b[j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+            if (m < d.M && n < d.N) {
+                float* o = d.out + 2 * (((size_t)g * d.M + m) * d.N + n);
+                unsafeAtomicAdd(o, acc[i][j].re);
+                unsafeAtomicAdd(o + 1, acc[i][j].im);
+            }
+        }
+}
+
 // y = x conj(M): the conjugate transpose M* applied to every row (the second factor of a product M1 M2* of
 // Section 3.1), i.e. the two dx stages of the kernel above on their own: x (B, k*s) -> y (B, k*p).
-// LDS: dws[BM][k*s] (the input with the outer permutation undone), dus[BM][kq].
+// LDS: dus[BM][kq].
 template <int BM>
 __global__ void __launch_bounds__(kCThreads)
 complex_fwd_h_kernel(const float2* __restrict__ x, const float2* __restrict__ R, const float2* __restrict__ L,
@@ -200,29 +288,23 @@ complex_fwd_h_kernel(const float2* __restrict__ x, const float2* __restrict__ R,
 {
     extern __shared__ float2 ldsc[];
     const int n_in = k * p, kq = k * q, n_out = k * s;
-    float2* dws = ldsc;
-    float2* dus = dws + (size_t)BM * n_out;
+    float2* dus = ldsc;
     const int64_t b0 = (int64_t)blockIdx.x * BM;
     const int tid = threadIdx.x;
     const bool pb = perm_b != 0;
-    for (int e = tid; e < BM * n_out; e += kCThreads) {
-        const int b = e / n_out, o = e - b * n_out;
-        const int l = o / k, c = o - l * k;
-        const int64_t row = b0 + b;
-        dws[b * n_out + c * s + l] = row < B ? x[row * n_out + o] : make_float2(0.f, 0.f);
-    }
-    __syncthreads();
-    for (int g = tid; g < kq; g += kCThreads) {  // V[c*q + r] = sum_l W[c][l] conj(L[c][l][r])
+    const float2* xrow[BM];
+#pragma unroll
+    for (int b = 0; b < BM; ++b) xrow[b] = x + (b0 + b < B ? b0 + b : B - 1) * n_out;
+    for (int g = tid; g < kq; g += kCThreads) {  // V[c*q + r] = sum_l W[c][l] conj(L[c][l][r]),  W[c][l] = x[l*k + c]
         const int c = g / q, r = g - c * q;
         const float2* Lcol = L + (size_t)c * s * q + r;
-        const float2* dwc = dws + c * s;
         cf acc[BM];
 #pragma unroll
         for (int b = 0; b < BM; ++b) acc[b] = cf{0.f, 0.f};
         for (int l = 0; l < s; ++l) {
             const cf w = ldc(Lcol + (size_t)l * q);
 #pragma unroll
-            for (int b = 0; b < BM; ++b) acc[b] = cmul_conj_acc(acc[b], ldc(dwc + b * n_out + l), w);
+            for (int b = 0; b < BM; ++b) acc[b] = cmul_conj_acc(acc[b], ldc(xrow[b] + (size_t)l * k + c), w);
         }
 #pragma unroll
         for (int b = 0; b < BM; ++b) dus[b * kq + g] = make_float2(acc[b].re, acc[b].im);
@@ -274,9 +356,9 @@ __global__ void __launch_bounds__(256) dft_factors_kernel(float2* __restrict__ R
     }
 }
 
-size_t fwd_bytes_per_row(const Problem& pb) { return ((size_t)pb.n_in + pb.kq()) * sizeof(float2); }
-size_t fwd_h_bytes_per_row(const Problem& pb) { return ((size_t)pb.n_out() + pb.kq()) * sizeof(float2); }
-size_t bwd_bytes_per_row(const Problem& pb) { return ((size_t)pb.n_in + 2 * (size_t)pb.kq() + pb.n_out()) * sizeof(float2); }
+size_t fwd_bytes_per_row(const Problem& pb) { return (size_t)pb.kq() * sizeof(float2); }
+size_t fwd_h_bytes_per_row(const Problem& pb) { return (size_t)pb.kq() * sizeof(float2); }
+size_t bwd_bytes_per_row(const Problem& pb) { return 2 * (size_t)pb.kq() * sizeof(float2); }
 
 int pick_rows(size_t bytes_per_row)
 {
@@ -311,18 +393,39 @@ int launch_cfwd_h(const Problem& pb, const void* x, const void* R, const void* L
     return hip_status(hipGetLastError());
 }
 
+// ws == nullptr: weight gradients by atomics from the data kernel; else: operands to the workspace, then the GEMM
 template <int BM>
 int launch_cbwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
-                void* dL, hipStream_t st)
+                void* dL, void* ws, hipStream_t st)
 {
     const size_t lds = (size_t)BM * bwd_bytes_per_row(pb);
-    auto kern = complex_bwd_kernel<BM>;
+    auto kern = ws ? complex_bwd_kernel<BM, true> : complex_bwd_kernel<BM, false>;
     if (allow_dynamic_lds((const void*)kern, lds) != hipSuccess) return -4;
     const int64_t grid = (pb.B + BM - 1) / BM;
     if (grid > 0x7fffffffLL) return -2;
+    const size_t act = align_up((size_t)pb.B * pb.kq() * sizeof(float2), 256);
+    float2* Uws = (float2*)ws;
+    float2* dY1ws = ws ? (float2*)((char*)ws + act) : nullptr;
+    float2* dWws = ws ? (float2*)((char*)ws + 2 * act) : nullptr;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kCThreads), lds, st, (const float2*)dy, (const float2*)x,
-                       (const float2*)R, (const float2*)L, (float2*)dx, (float*)dR, (float*)dL, pb.B, pb.k, pb.p, pb.q,
-                       pb.s, pb.perm_b() ? 1 : 0);
+                       (const float2*)R, (const float2*)L, (float2*)dx, (float*)dR, (float*)dL, Uws, dY1ws, dWws, pb.B,
+                       pb.k, pb.p, pb.q, pb.s, pb.perm_b() ? 1 : 0);
+    int rc = hip_status(hipGetLastError());
+    if (rc || !ws) return rc;
+    CGemm gl{dWws, pb.n_out(), pb.s, Uws, pb.kq(), pb.q, pb.s, pb.q, pb.k, (float*)dL};
+    CGemm gr{dY1ws, pb.kq(), pb.q, (const float2*)x, pb.n_in, pb.p, pb.q, pb.p, pb.k, (float*)dR};
+    auto tiles = [](const CGemm& d) { return (int64_t)d.G * ((d.M + kCT - 1) / kCT) * ((d.N + kCT - 1) / kCT); };
+    const int64_t t0 = tiles(gl), t1 = tiles(gr);
+    int64_t nz = 1024 / (t0 + t1);  // about four workgroups per CU
+    const int64_t maxz = (pb.B + 63) / 64;
+    if (nz > maxz) nz = maxz;
+    if (nz < 1) nz = 1;
+    if (nz > 65535) nz = 65535;
+    const int64_t rpc = ((pb.B + nz - 1) / nz + kCK - 1) / kCK * kCK;
+    nz = (pb.B + rpc - 1) / rpc;
+    if (t0 + t1 > 0x7fffffffLL) return -2;
+    hipLaunchKernelGGL(complex_wgrad_kernel, dim3((unsigned)(t0 + t1), (unsigned)nz), dim3(256), 0, st, gl, gr, (int)t0,
+                       pb.B, rpc);
     return hip_status(hipGetLastError());
 }
 
@@ -352,17 +455,23 @@ int complex_fwd(const Problem& pb, const void* x, const void* R, const void* L, 
     }
 }
 
+size_t complex_bwd_workspace(const Problem& pb)
+{
+    const size_t rows = pb.B > 0 ? (size_t)pb.B : 1;
+    return 2 * align_up(rows * pb.kq() * sizeof(float2), 256) + align_up(rows * pb.n_out() * sizeof(float2), 256);
+}
+
 int complex_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
-                void* dL, hipStream_t st)
+                void* dL, void* ws, hipStream_t st)
 {
     int rc = launch_fill_zero_f32((float*)dR, 2 * pb.n_R(), st);
     if (rc) return rc;
     rc = launch_fill_zero_f32((float*)dL, 2 * pb.n_L(), st);
     if (rc || pb.B == 0) return rc;
     switch (pick_rows(bwd_bytes_per_row(pb))) {
-        case 4: return launch_cbwd<4>(pb, dy, x, R, L, dx, dR, dL, st);
-        case 2: return launch_cbwd<2>(pb, dy, x, R, L, dx, dR, dL, st);
-        case 1: return launch_cbwd<1>(pb, dy, x, R, L, dx, dR, dL, st);
+        case 4: return launch_cbwd<4>(pb, dy, x, R, L, dx, dR, dL, ws, st);
+        case 2: return launch_cbwd<2>(pb, dy, x, R, L, dx, dR, dL, ws, st);
+        case 1: return launch_cbwd<1>(pb, dy, x, R, L, dx, dR, dL, ws, st);
         default: return -2;
     }
 }

@@ -69,8 +69,11 @@ int generic_fwd_t(const Problem& pb, const void* x, const void* R, const void* L
 bool complex_fwd_supported(const Problem& pb);
 bool complex_bwd_supported(const Problem& pb);
 int complex_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
+// ws == nullptr: dR / dL by fp32 atomics from every row tile; else (complex_bwd_workspace bytes): the batch-major
+// operands go through the workspace and one tiled GEMM launch contracts them over the batch
+size_t complex_bwd_workspace(const Problem& pb);
 int complex_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
-                void* dL, hipStream_t st);
+                void* dL, void* ws, hipStream_t st);
 // y = x conj(M) (the conjugate transpose applied to every row): x (B, k*s) -> y (B, k*p)
 bool complex_fwd_h_supported(const Problem& pb);
 int complex_fwd_h(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);

@@ -823,7 +823,7 @@ def cnormal(seed, shape, std=1.0):
 
 
 COMPLEX_CASES = [("c_sq4", 9, 4, 4, 4, 4), ("c_sq16", 70, 16, 16, 16, 16), ("c_rect", 33, 3, 4, 5, 2), ("c_k4", 130, 4, 32, 32, 48),
-                 ("c_one_row", 1, 2, 3, 4, 2)]
+                 ("c_one_row", 1, 2, 3, 4, 2), ("c_wide", 77, 2, 70, 130, 66), ("c_sq64", 21, 64, 64, 64, 64)]
 
 
 @pytest.mark.parametrize("reading", [0, 1], ids=["reading_a", "reading_b"])
@@ -838,16 +838,26 @@ def test_complex_forward_and_backward(B, case, reading):
     dx, dR, dL = B.monarch_bwd_c64(cdev(dy), cdev(x), cdev(R), cdev(L), flags=flags)
     torch.cuda.synchronize()
     yh = B.monarch_fwd_h_c64(cdev(dy), cdev(R), cdev(L), flags=flags)   # conjugate transpose applied to the rows of dy
+    # the backward with a (guarded) workspace: weight gradients by the batch-contracted GEMM
+    need = B.monarch_bwd_c64_workspace_bytes(rows, k * p, k, q, s, flags)
+    wbuf = torch.full((need + 512 + 2 * GUARD,), 0x5A, dtype=torch.uint8, device="cuda")
+    off = (-(wbuf.data_ptr() + GUARD)) % 256 + GUARD
+    dx2, dR2, dL2 = B.monarch_bwd_c64_ws(cdev(dy), cdev(x), cdev(R), cdev(L), workspace=wbuf[off:off + need], flags=flags)
     torch.cuda.synchronize()
-    want = [complex_ref.fwd(x, R, L, reading)] + list(complex_ref.bwd(dy, x, R, L, reading)) + [complex_ref.fwd_h(dy, R, L, reading)]
+    assert bool((wbuf[:off] == 0x5A).all()) and bool((wbuf[off + need:] == 0x5A).all()), "workspace: wrote out of bounds"
+    assert torch.equal(dx2, dx), "the data path is the same kernel code with or without the workspace"
+    ref = list(complex_ref.bwd(dy, x, R, L, reading))
+    want = [complex_ref.fwd(x, R, L, reading)] + ref + [complex_ref.fwd_h(dy, R, L, reading)] + ref[1:]
     errs = {}
-    for nm, got, w in zip(("y", "dx", "dR", "dL", "xMh"), (y, dx, dR, dL, yh), want):
+    for nm, got, w in zip(("y", "dx", "dR", "dL", "xMh", "dR_ws", "dL_ws"), (y, dx, dR, dL, yh, dR2, dL2), want):
         g = got.cpu().numpy().astype(np.complex128)
         errs[nm] = float(np.linalg.norm((g - w).ravel()) / np.linalg.norm(w.ravel()))
     print("\n  %s %s" % (name, " ".join("%s=%.2e" % kv for kv in errs.items())), flush=True)
     assert max(errs.values()) <= TOL["f32"], errs
     # empty batch: no-op forward, zero gradients
     e = B.monarch_bwd_c64(cdev(dy[:0]), cdev(x[:0]), cdev(R), cdev(L), flags=flags)
+    assert e[0].shape == (0, k * p) and not bool(e[1].any()) and not bool(e[2].any())
+    e = B.monarch_bwd_c64_ws(cdev(dy[:0]), cdev(x[:0]), cdev(R), cdev(L), flags=flags)
     assert e[0].shape == (0, k * p) and not bool(e[1].any()) and not bool(e[2].any())
     assert B.monarch_fwd_h_c64(cdev(dy[:0]), cdev(R), cdev(L), flags=flags).shape == (0, k * p)
 

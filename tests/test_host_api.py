@@ -337,6 +337,23 @@ def test_complex_calls_reject_bad_arguments_without_a_gpu(binding):
     assert bwd(n_in=18) == binding.MONARCH_ERR_INVALID
     assert bwd(flags=binding.MONARCH_FLAG_WGRAD_F32) == binding.MONARCH_ERR_INVALID
 
+    cneed = binding.monarch_bwd_c64_workspace_bytes(5, 16, 4, 4, 4, 0)
+    assert cneed >= 5 * (2 * 16 + 16) * 8
+    assert binding.monarch_bwd_c64_workspace_bytes(5, 18, 4, 4, 4, 0) == 0                      # n_in not k*p
+    assert binding.monarch_bwd_c64_workspace_bytes(5, 16, 4, 4, 4, binding.MONARCH_FLAG_GENERIC) == 0
+
+    def bwd_ws(ptrs=(p,) * 7, batch=5, n_in=16, ws=p, ws_bytes=cneed, flags=0):
+        return L.monarch_bwd_c64_ws(*ptrs, batch, n_in, 4, 4, 4, None, ws, ws_bytes, flags)
+
+    for bad in range(7):
+        ptrs = [p] * 7
+        ptrs[bad] = None
+        assert bwd_ws(tuple(ptrs)) == binding.MONARCH_ERR_INVALID
+    assert bwd_ws(ws_bytes=cneed - 1) == binding.MONARCH_ERR_WORKSPACE
+    assert bwd_ws(ws=p + 16) == binding.MONARCH_ERR_WORKSPACE                                   # not 256-byte aligned
+    assert bwd_ws(n_in=18) == binding.MONARCH_ERR_INVALID
+    assert bwd_ws(flags=binding.MONARCH_FLAG_WGRAD_F32) == binding.MONARCH_ERR_INVALID
+
     assert L.monarch_dft_factors(None, p, 4, 0, None) == binding.MONARCH_ERR_INVALID
     assert L.monarch_dft_factors(p, p, 0, 0, None) == binding.MONARCH_ERR_INVALID
     assert L.monarch_dft_factors(p, p + 8, 4, 0, None) == binding.MONARCH_ERR_INVALID
