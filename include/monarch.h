@@ -298,28 +298,40 @@ int monarch_project(const void* A, void* R, void* L, int n, int m,
  * then imaginary part); products and sums in fp32.  The forward applies M^T (no conjugation).  The
  * backward returns, for a real loss, grad z = dLoss/dRe z + i dLoss/dIm z (the convention of automatic
  * differentiation):  dx = dy conj(M),  dL[c] = dW[c]^T conj(U[c]),  dR[kk] = dY1[kk]^T conj(x[kk]).
- * Shape-generic kernels only; dR and dL are reduced with fp32 atomics (reproducible up to summation
- * order); no workspace (monarch_bwd_c64_ws takes one).  flags: MONARCH_FLAG_PERM_B only. */
+ * These three calls take no workspace and run shape-generic fp32 kernels; dR and dL are reduced with fp32
+ * atomics (reproducible up to summation order).  flags: MONARCH_FLAG_PERM_B only. */
 int monarch_fwd_c64(const void* x, const void* R, const void* L, void* y,
                     int64_t batch, int n_in, int k, int q, int s, void* stream, unsigned flags);
 /* Conjugate transpose applied to every row:  y = x conj(M),  x (batch, k*s) -> y (batch, n_in), complex64.
  * M* is the second factor of the products M1 M2* of Section 3.1 ("Products of Monarch Matrices"; the star is
  * the conjugate transpose, Notation Review): M1 M2* x is monarch_fwd_h_c64 with the factors of M2, then
  * monarch_fwd_c64 with those of M1.  For real factors it is monarch_fwd_t.  Same shapes, layouts, flags and
- * errors as monarch_fwd_c64 with input and output sizes exchanged; no workspace. */
+ * errors as monarch_fwd_c64 with input and output sizes exchanged. */
 int monarch_fwd_h_c64(const void* x, const void* R, const void* L, void* y,
                       int64_t batch, int n_in, int k, int q, int s, void* stream, unsigned flags);
 int monarch_bwd_c64(const void* dy, const void* x, const void* R, const void* L,
                     void* dx, void* dR, void* dL,
                     int64_t batch, int n_in, int k, int q, int s, void* stream, unsigned flags);
-/* monarch_bwd_c64 with a workspace, for batches where the atomics of the call above dominate (every row tile
- * adds a full copy of dR and dL): with `workspace` (device memory, 256-byte aligned, at least
- * monarch_bwd_c64_workspace_bytes(...) bytes; contents ignored on entry, unspecified on exit) the three
- * batch-major operands of the weight gradients (U, dY1, dW) are written there by the data kernel and one tiled
- * launch contracts them over the batch; only the partial sums of its batch chunks meet in atomics.  Same
- * results up to fp32 summation order.  workspace == NULL: exactly monarch_bwd_c64.  A short or misaligned
- * workspace returns MONARCH_ERR_WORKSPACE; other errors as monarch_bwd_c64. */
-size_t monarch_bwd_c64_workspace_bytes(int64_t batch, int n_in, int k, int q, int s, unsigned flags);
+/* The same three operations with a workspace (device memory, 256-byte aligned, at least
+ * monarch_c64_workspace_bytes(pass, ...) bytes with pass 0 = monarch_fwd_c64_ws, 1 = monarch_bwd_c64_ws,
+ * 2 = monarch_fwd_h_c64_ws; contents ignored on entry, unspecified on exit).
+ * Square blocks p = q = s in {16, 32, 64} (any k; the DFT-initialised matrices of the MRI model are of this
+ * kind) run on the matrix cores: one launch per block-diagonal factor, the vector between the factors kept
+ * in the workspace in a tiled order that makes the permutation between them long contiguous runs; the weight
+ * gradients are contracted over the batch on the matrix cores too and their partial sums added in a fixed
+ * order (bit-reproducible, no atomics).  fp32 products and sums, as above.
+ * Other shapes: the forward calls ignore the workspace; the backward writes the batch-major operands of the
+ * weight gradients there and contracts them in one tiled launch whose batch chunks meet in fp32 atomics.
+ * workspace == NULL: exactly the calls above.  A short or misaligned workspace returns MONARCH_ERR_WORKSPACE;
+ * other errors as above.  monarch_c64_workspace_bytes returns 0 for arguments the calls reject (and for the
+ * forward calls on shapes that use no workspace). */
+size_t monarch_c64_workspace_bytes(int pass, int64_t batch, int n_in, int k, int q, int s, unsigned flags);
+int monarch_fwd_c64_ws(const void* x, const void* R, const void* L, void* y,
+                       int64_t batch, int n_in, int k, int q, int s, void* stream,
+                       void* workspace, size_t workspace_bytes, unsigned flags);
+int monarch_fwd_h_c64_ws(const void* x, const void* R, const void* L, void* y,
+                         int64_t batch, int n_in, int k, int q, int s, void* stream,
+                         void* workspace, size_t workspace_bytes, unsigned flags);
 int monarch_bwd_c64_ws(const void* dy, const void* x, const void* R, const void* L,
                        void* dx, void* dR, void* dL,
                        int64_t batch, int n_in, int k, int q, int s, void* stream,

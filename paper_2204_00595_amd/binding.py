@@ -32,7 +32,7 @@ EXPORTS = (
     "monarch_fwd", "monarch_fwd_ex", "monarch_fwd_ws", "monarch_fwd_static", "monarch_fwd_bias", "monarch_fwd_workspace_bytes", "monarch_bwd",
     "monarch_bwd_bias", "monarch_fwd_bias_gelu", "monarch_bwd_bias_gelu_in",
     "monarch_bwd_workspace_bytes",
-    "monarch_fwd_t", "monarch_fwd_t_workspace_bytes", "monarch_saved_bytes", "monarch_fwd_save", "monarch_bwd_saved", "monarch_fwd_c64", "monarch_fwd_h_c64", "monarch_bwd_c64", "monarch_bwd_c64_ws", "monarch_bwd_c64_workspace_bytes", "monarch_dft_factors", "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy", "monarch_launch_probe",
+    "monarch_fwd_t", "monarch_fwd_t_workspace_bytes", "monarch_saved_bytes", "monarch_fwd_save", "monarch_bwd_saved", "monarch_fwd_c64", "monarch_fwd_h_c64", "monarch_bwd_c64", "monarch_fwd_c64_ws", "monarch_fwd_h_c64_ws", "monarch_bwd_c64_ws", "monarch_c64_workspace_bytes", "monarch_dft_factors", "monarch_to_dense", "monarch_project", "monarch_kernel_name", "monarch_status_string", "monarch_version", "monarch_stream_copy", "monarch_launch_probe",
 )
 
 _lib = None
@@ -96,8 +96,12 @@ def lib() -> ctypes.CDLL:
         L.monarch_bwd_c64.argtypes = [vp] * 7 + [i64, ci, ci, ci, ci, vp, cu]
         L.monarch_bwd_c64_ws.restype = ci
         L.monarch_bwd_c64_ws.argtypes = [vp] * 7 + [i64, ci, ci, ci, ci, vp, vp, sz, cu]
-        L.monarch_bwd_c64_workspace_bytes.restype = sz
-        L.monarch_bwd_c64_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, cu]
+        L.monarch_fwd_c64_ws.restype = ci
+        L.monarch_fwd_c64_ws.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, vp, vp, sz, cu]
+        L.monarch_fwd_h_c64_ws.restype = ci
+        L.monarch_fwd_h_c64_ws.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, vp, vp, sz, cu]
+        L.monarch_c64_workspace_bytes.restype = sz
+        L.monarch_c64_workspace_bytes.argtypes = [ci, i64, ci, ci, ci, ci, cu]
         L.monarch_dft_factors.restype = ci
         L.monarch_dft_factors.argtypes = [vp, vp, ci, ci, vp]
         L.monarch_project.restype = ci
@@ -661,14 +665,53 @@ def monarch_bwd_c64(dy: torch.Tensor, x: torch.Tensor, R: torch.Tensor, L: torch
     return dx, dR, dL
 
 
-def monarch_bwd_c64_workspace_bytes(batch: int, n_in: int, k: int, q: int, s: int, flags: int = 0) -> int:
-    return int(lib().monarch_bwd_c64_workspace_bytes(batch, n_in, k, q, s, flags))
+C64_FWD, C64_BWD, C64_FWD_H = 0, 1, 2
+
+
+def monarch_c64_workspace_bytes(pass_: int, batch: int, n_in: int, k: int, q: int, s: int, flags: int = 0) -> int:
+    """Workspace of monarch_fwd_c64_ws (C64_FWD), monarch_bwd_c64_ws (C64_BWD), monarch_fwd_h_c64_ws (C64_FWD_H)."""
+    return int(lib().monarch_c64_workspace_bytes(pass_, batch, n_in, k, q, s, flags))
+
+
+def _c64_apply_ws(name: str, pass_: int, x, R, L, y, workspace, flags, stream):
+    k, q, p = R.shape
+    s = L.shape[1]
+    B = x.shape[0]
+    n_from, n_to = (k * s, k * p) if pass_ == C64_FWD_H else (k * p, k * s)
+    dev, dt = x.device, torch.complex64
+    _check(x, "x", (B, n_from), dt, dev)
+    _check(R, "R", (k, q, p), dt, dev)
+    _check(L, "L", (k, s, q), dt, dev)
+    if y is None:
+        y = torch.empty((B, n_to), dtype=dt, device=dev)
+    _check(y, "y", (B, n_to), dt, dev)
+    if workspace is None:
+        workspace = _scratch(max(monarch_c64_workspace_bytes(pass_, B, k * p, k, q, s, flags), 256), dev, stream)
+    with torch.cuda.device(dev):
+        rc = getattr(lib(), name)(x.data_ptr(), R.data_ptr(), L.data_ptr(), y.data_ptr(), B, k * p, k, q, s,
+                                  _stream_ptr(stream), workspace.data_ptr(),
+                                  workspace.numel() * workspace.element_size(), flags)
+    if rc != MONARCH_OK:
+        raise MonarchError(rc, name)
+    return y
+
+
+def monarch_fwd_c64_ws(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.Tensor | None = None,
+                       workspace: torch.Tensor | None = None, flags: int = 0, stream=None) -> torch.Tensor:
+    """monarch_fwd_c64 with a workspace (allocated when not given): matrix-core kernels for square blocks."""
+    return _c64_apply_ws("monarch_fwd_c64_ws", C64_FWD, x, R, L, y, workspace, flags, stream)
+
+
+def monarch_fwd_h_c64_ws(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: torch.Tensor | None = None,
+                         workspace: torch.Tensor | None = None, flags: int = 0, stream=None) -> torch.Tensor:
+    """monarch_fwd_h_c64 with a workspace (allocated when not given): matrix-core kernels for square blocks."""
+    return _c64_apply_ws("monarch_fwd_h_c64_ws", C64_FWD_H, x, R, L, y, workspace, flags, stream)
 
 
 def monarch_bwd_c64_ws(dy: torch.Tensor, x: torch.Tensor, R: torch.Tensor, L: torch.Tensor,
                        workspace: torch.Tensor | None = None, flags: int = 0, stream=None):
-    """monarch_bwd_c64 with the weight gradients contracted by a GEMM over operands kept in a workspace
-    (allocated when not given)."""
+    """monarch_bwd_c64 with a workspace (allocated when not given): matrix-core kernels for square blocks, else
+    the weight gradients contracted by a GEMM over operands kept in the workspace."""
     k, q, p = R.shape
     s = L.shape[1]
     B = x.shape[0]
@@ -678,7 +721,7 @@ def monarch_bwd_c64_ws(dy: torch.Tensor, x: torch.Tensor, R: torch.Tensor, L: to
     _check(R, "R", (k, q, p), dt, dev)
     _check(L, "L", (k, s, q), dt, dev)
     dx, dR, dL = torch.empty_like(x), torch.empty_like(R), torch.empty_like(L)
-    need = monarch_bwd_c64_workspace_bytes(B, k * p, k, q, s, flags)
+    need = monarch_c64_workspace_bytes(C64_BWD, B, k * p, k, q, s, flags)
     if workspace is None:
         workspace = _scratch(max(need, 256), dev, stream)
     with torch.cuda.device(dev):

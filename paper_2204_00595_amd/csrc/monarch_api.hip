@@ -410,8 +410,31 @@ int monarch_to_dense(const void* R, const void* L, void* M, int n_in, int k, int
     return launch_to_dense(pb, R, L, M, (hipStream_t)stream);
 }
 
-int monarch_fwd_c64(const void* x, const void* R, const void* L, void* y, int64_t batch, int n_in, int k, int q, int s,
-                    void* stream, unsigned flags)
+// pass: 0 forward, 1 backward, 2 conjugate-transpose forward.  The matrix-core kernels take the square block sizes
+// they are built for whenever a workspace is given; everything else runs the shape-generic kernels.
+static size_t c64_workspace(const Problem& pb, int pass)
+{
+    if (complex_mfma_supported(pb)) return complex_mfma_workspace(pb, pass);
+    return pass == 1 ? complex_bwd_workspace(pb) : 0;
+}
+
+static int c64_check_workspace(const Problem& pb, int pass, const void* workspace, size_t workspace_bytes)
+{
+    if (workspace && (workspace_bytes < c64_workspace(pb, pass) || !aligned(workspace, 256))) return MONARCH_ERR_WORKSPACE;
+    return MONARCH_OK;
+}
+
+size_t monarch_c64_workspace_bytes(int pass, int64_t batch, int n_in, int k, int q, int s, unsigned flags)
+{
+    Problem pb;
+    if (pass < 0 || pass > 2 || make_problem(pb, batch, n_in, k, q, s, MONARCH_F32, flags)) return 0;
+    if (flags & ~MONARCH_FLAG_PERM_B) return 0;
+    if (!(pass == 0 ? complex_fwd_supported(pb) : pass == 1 ? complex_bwd_supported(pb) : complex_fwd_h_supported(pb))) return 0;
+    return c64_workspace(pb, pass);
+}
+
+int monarch_fwd_c64_ws(const void* x, const void* R, const void* L, void* y, int64_t batch, int n_in, int k, int q, int s,
+                       void* stream, void* workspace, size_t workspace_bytes, unsigned flags)
 {
     Problem pb;
     int rc = make_problem(pb, batch, n_in, k, q, s, MONARCH_F32, flags);
@@ -420,12 +443,20 @@ int monarch_fwd_c64(const void* x, const void* R, const void* L, void* y, int64_
     if (!R || !L || ((!x || !y) && batch > 0)) return MONARCH_ERR_INVALID;
     if (!aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(y, 16)) return MONARCH_ERR_INVALID;
     if (!complex_fwd_supported(pb)) return MONARCH_ERR_UNSUPPORTED;
+    if ((rc = c64_check_workspace(pb, 0, workspace, workspace_bytes))) return rc;
     if (batch == 0) return MONARCH_OK;
+    if (workspace && complex_mfma_supported(pb)) return complex_mfma_fwd(pb, x, R, L, y, workspace, (hipStream_t)stream);
     return complex_fwd(pb, x, R, L, y, (hipStream_t)stream);
 }
 
-int monarch_fwd_h_c64(const void* x, const void* R, const void* L, void* y, int64_t batch, int n_in, int k, int q, int s,
-                      void* stream, unsigned flags)
+int monarch_fwd_c64(const void* x, const void* R, const void* L, void* y, int64_t batch, int n_in, int k, int q, int s,
+                    void* stream, unsigned flags)
+{
+    return monarch_fwd_c64_ws(x, R, L, y, batch, n_in, k, q, s, stream, nullptr, 0, flags);
+}
+
+int monarch_fwd_h_c64_ws(const void* x, const void* R, const void* L, void* y, int64_t batch, int n_in, int k, int q,
+                         int s, void* stream, void* workspace, size_t workspace_bytes, unsigned flags)
 {
     Problem pb;
     int rc = make_problem(pb, batch, n_in, k, q, s, MONARCH_F32, flags);
@@ -434,22 +465,16 @@ int monarch_fwd_h_c64(const void* x, const void* R, const void* L, void* y, int6
     if (!R || !L || ((!x || !y) && batch > 0)) return MONARCH_ERR_INVALID;
     if (!aligned(x, 16) || !aligned(R, 16) || !aligned(L, 16) || !aligned(y, 16)) return MONARCH_ERR_INVALID;
     if (!complex_fwd_h_supported(pb)) return MONARCH_ERR_UNSUPPORTED;
+    if ((rc = c64_check_workspace(pb, 2, workspace, workspace_bytes))) return rc;
     if (batch == 0) return MONARCH_OK;
+    if (workspace && complex_mfma_supported(pb)) return complex_mfma_fwd_h(pb, x, R, L, y, workspace, (hipStream_t)stream);
     return complex_fwd_h(pb, x, R, L, y, (hipStream_t)stream);
 }
 
-int monarch_bwd_c64(const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR, void* dL,
-                    int64_t batch, int n_in, int k, int q, int s, void* stream, unsigned flags)
+int monarch_fwd_h_c64(const void* x, const void* R, const void* L, void* y, int64_t batch, int n_in, int k, int q, int s,
+                      void* stream, unsigned flags)
 {
-    return monarch_bwd_c64_ws(dy, x, R, L, dx, dR, dL, batch, n_in, k, q, s, stream, nullptr, 0, flags);
-}
-
-size_t monarch_bwd_c64_workspace_bytes(int64_t batch, int n_in, int k, int q, int s, unsigned flags)
-{
-    Problem pb;
-    if (make_problem(pb, batch, n_in, k, q, s, MONARCH_F32, flags)) return 0;
-    if ((flags & ~MONARCH_FLAG_PERM_B) || !complex_bwd_supported(pb)) return 0;
-    return complex_bwd_workspace(pb);
+    return monarch_fwd_h_c64_ws(x, R, L, y, batch, n_in, k, q, s, stream, nullptr, 0, flags);
 }
 
 int monarch_bwd_c64_ws(const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR, void* dL,
@@ -465,8 +490,16 @@ int monarch_bwd_c64_ws(const void* dy, const void* x, const void* R, const void*
         !aligned(dR, 16) || !aligned(dL, 16))
         return MONARCH_ERR_INVALID;
     if (!complex_bwd_supported(pb)) return MONARCH_ERR_UNSUPPORTED;
-    if (workspace && (workspace_bytes < complex_bwd_workspace(pb) || !aligned(workspace, 256))) return MONARCH_ERR_WORKSPACE;
+    if ((rc = c64_check_workspace(pb, 1, workspace, workspace_bytes))) return rc;
+    if (workspace && batch > 0 && complex_mfma_supported(pb))
+        return complex_mfma_bwd(pb, dy, x, R, L, dx, dR, dL, workspace, (hipStream_t)stream);
     return complex_bwd(pb, dy, x, R, L, dx, dR, dL, workspace, (hipStream_t)stream);
+}
+
+int monarch_bwd_c64(const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR, void* dL,
+                    int64_t batch, int n_in, int k, int q, int s, void* stream, unsigned flags)
+{
+    return monarch_bwd_c64_ws(dy, x, R, L, dx, dR, dL, batch, n_in, k, q, s, stream, nullptr, 0, flags);
 }
 
 int monarch_dft_factors(void* R, void* L, int m, int inverse, void* stream)

@@ -1,0 +1,498 @@
+// Complex-valued Monarch multiply on the matrix cores (complex64, fp32 arithmetic), for square blocks
+// p = q = s in {16, 32, 64} and any k.  The paper's results hold over C (Notation Review); the steps are
+// those of Section 3.3 with the permutations of Definition 3.1, the gradients those of monarch_complex.hip.
+//
+// A complex product is a real product of twice the size: with a vector stored as interleaved (re, im) pairs,
+// y = W x over C is  y' = W' x'  over R, where W'[2j+e][2i+t] = (Wr, -Wi; Wi, Wr)[e][t].  The activations are
+// therefore used exactly as they lie in memory, and the weights are expanded as they are loaded.
+//
+// One block-diagonal factor is one launch ("stage"), and the vector between the two factors goes through a
+// workspace: at n = 4096 a row of it takes 32 KiB, so a 32-row tile does not fit LDS next to anything else.  A
+// workgroup owns one block g and a share of the row tiles: its wave w keeps the expanded weights of 16 outputs
+// (32 real rows, the M extent of v_mfma_f32_32x32x2_f32) in registers for the whole launch and streams 32-row
+// activation tiles (the N extent) past them; a K = 2 step contracts one component of two complex inputs.
+//   D (32 x 32): acc[r] = D[8*(r/4) + 4*(lane/32) + r%4][lane%32]: a lane holds whole complex outputs of one row.
+//
+// The permutation between the factors is an 8-byte transposition, so it is done where the pieces can be made
+// long: the workspace holds the intermediate in tiles  T[row tile][block][index in block][32 rows]  (the
+// producer writes, per output index, the 32 rows of its tile as one 256-byte run into the block the consumer
+// will read; the consumer's tile is then one contiguous block).  Only the outer permutation (y[b][l*k + c], and
+// dy read the same way) moves 8-byte pieces; the workgroups of one row range run on one XCD so that these meet in
+// one L2.
+//
+// Weight gradients: dL[c] = dW[c]^T conj(U[c]),  dR[kk] = dY1[kk]^T conj(x[kk]),  contracted over the batch by the
+// same MFMA (K = two rows x one component); a workgroup owns one block and a share of the row tiles, the shares'
+// partial results go to the workspace and are summed in a fixed order (no atomics).
+#include "monarch_internal.h"
+#include "monarch_device.h"
+#include "monarch_mfma_common.h"
+
+namespace monarch {
+namespace {
+
+constexpr int kRT = 32;  // batch rows per tile
+
+__device__ __forceinline__ f32x16 mfma_f32(float a, float b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+enum : int { kInNat = 0, kInGather = 1, kInT = 2 };
+enum : int { kOutTFwd = 0, kOutTBwd = 1, kOutNat = 2, kOutScatter = 3 };
+
+// stage-1 output f = kk*q + j that lands at position g of the permuted vector (inverse of mid_dest)
+__device__ __forceinline__ int mid_src(int g, int k, int q, bool perm_b)
+{
+    if (!perm_b) { const int j = g / k, kk = g - j * k; return kk * q + j; }
+    const int c = g / q, r = g - c * q;
+    return r * k + c;
+}
+
+__device__ __forceinline__ void lds_store_c2(float2* dst, u32x4 v)  // two complex values to an 8-byte aligned place
+{
+    dst[0] = make_float2(__uint_as_float(v.x), __uint_as_float(v.y));
+    dst[1] = make_float2(__uint_as_float(v.z), __uint_as_float(v.w));
+}
+
+// A 32-row tile of one block's complex values, P per row, fetched into registers and later written to LDS.
+//   kInNat:    src[row][g*P + i]                          LDS [row][P + 1]
+//   kInGather: src[row][i*k + g]                          LDS [row][P + 1]
+//   kInT:      src tile (rt, g): [i][32 rows], contiguous LDS [i][32]
+// Rows past the end of the batch read as zeros (kInT: the producer wrote zeros there).
+template <int P, int NTHR, int IN>
+struct ActTile {
+    static constexpr int kPieces = (IN == kInGather) ? kRT * P / NTHR : kRT * P / 2 / NTHR;  // per thread
+    static constexpr int kStride = (IN == kInT) ? kRT : P + 1;
+    static constexpr int kLen = (IN == kInT) ? P * kRT : kRT * (P + 1);
+    static_assert((IN == kInGather ? kRT * P : kRT * P / 2) % NTHR == 0, "tile does not divide over the threads");
+    u32x4 v[IN == kInGather ? (kPieces + 1) / 2 : kPieces];
+
+    __device__ __forceinline__ void fetch(const float2* __restrict__ src, int64_t rt, int g, int k, int64_t ld, int64_t B, int tid)
+    {
+        const int64_t row0 = rt * kRT;
+        if constexpr (IN == kInNat) {
+#pragma unroll
+            for (int n = 0; n < kPieces; ++n) {
+                const int idx = tid + n * NTHR, row = idx / (P / 2), c2 = idx - row * (P / 2);
+                v[n] = (row0 + row < B) ? ldg128(src + (row0 + row) * ld + (size_t)g * P + 2 * c2) : u32x4{0, 0, 0, 0};
+            }
+        } else if constexpr (IN == kInGather) {
+#pragma unroll
+            for (int n = 0; n < kPieces; ++n) {
+                const int idx = tid + n * NTHR, row = idx / P, i = idx - row * P;
+                float2 t = make_float2(0.f, 0.f);
+                if (row0 + row < B) t = src[(row0 + row) * ld + (size_t)i * k + g];
+                if (n & 1) { v[n / 2].z = __float_as_uint(t.x); v[n / 2].w = __float_as_uint(t.y); }
+                else { v[n / 2].x = __float_as_uint(t.x); v[n / 2].y = __float_as_uint(t.y); }
+            }
+        } else {
+            const float2* tile = src + ((size_t)rt * k + g) * (P * kRT);
+#pragma unroll
+            for (int n = 0; n < kPieces; ++n) v[n] = ldg128(tile + 2 * (tid + n * NTHR));
+        }
+    }
+
+    __device__ __forceinline__ void to_lds(float2* act, int tid) const
+    {
+        if constexpr (IN == kInNat) {
+#pragma unroll
+            for (int n = 0; n < kPieces; ++n) {
+                const int idx = tid + n * NTHR, row = idx / (P / 2), c2 = idx - row * (P / 2);
+                lds_store_c2(act + row * kStride + 2 * c2, v[n]);
+            }
+        } else if constexpr (IN == kInGather) {
+#pragma unroll
+            for (int n = 0; n < kPieces; ++n) {
+                const int idx = tid + n * NTHR, row = idx / P, i = idx - row * P;
+                const u32x4 w = v[n / 2];
+                act[row * kStride + i] = (n & 1) ? make_float2(__uint_as_float(w.z), __uint_as_float(w.w))
+                                                 : make_float2(__uint_as_float(w.x), __uint_as_float(w.y));
+            }
+        } else {
+#pragma unroll
+            for (int n = 0; n < kPieces; ++n) *reinterpret_cast<u32x4*>(act + 2 * (tid + n * NTHR)) = v[n];
+        }
+    }
+
+    // element i of row `row`
+    static __device__ __forceinline__ float2 at(const float2* act, int i, int row)
+    {
+        return (IN == kInT) ? act[i * kRT + row] : act[row * kStride + i];
+    }
+};
+
+// out[b][block g][n] = sum_m in[b][block g][m] * Wop[g][n][m],  n < Q, m < P;
+// Wop[n][m] = W[g][n][m] (W stored [g][Q][P]) or, CONJT, conj(W[g][m][n]) (W stored [g][P][Q]).
+//   kOutTFwd:    element (g, n) is stage-1 output f = g*Q + n; it goes to block c, index r of the permuted vector
+//   kOutTBwd:    element (g, n) is position g*Q + n of the permuted vector; it goes to block kk, index j of stage 1
+//   kOutNat:     out[row][g*Q + n]
+//   kOutScatter: out[row][n*k + g]
+// Grid: k * nsplit workgroups of Q/16 waves; workgroup (g, split) takes the row tiles split, split + nsplit, ...
+// (split = blockIdx % nsplit with nsplit a multiple of 8 keeps the blocks of one row range on one XCD).
+template <int P, int Q, int IN, int OUT, bool CONJT>
+__global__ void __launch_bounds__(4 * Q)
+cstage_kernel(const float2* __restrict__ in, const float2* __restrict__ W, float2* __restrict__ out, int64_t B,
+              int k, int nsplit, int perm_b)
+{
+    constexpr int NTHR = 4 * Q;
+    using Tile = ActTile<P, NTHR, IN>;
+    constexpr int OSTR = Q + 1;
+    __shared__ __align__(16) float2 act[2][Tile::kLen];
+    __shared__ __align__(16) float2 ost[OUT == kOutNat ? kRT * OSTR : 1];
+
+    const int g = (int)blockIdx.x / nsplit, split = (int)blockIdx.x - g * nsplit;
+    const int tid = threadIdx.x, lane = tid & 63, mt = tid >> 6;
+    const int col = lane & 31, kh = lane >> 5, e = lane & 1;
+    const int64_t ntiles = (B + kRT - 1) / kRT;
+    const int64_t ld_in = (int64_t)k * P, ld_out = (int64_t)k * Q;
+    const bool pb = perm_b != 0;
+
+    // this lane's rows of the expanded weights: real row 2*jw + e, for the inputs i = 2u + kh
+    float A0[P / 2], A1[P / 2];
+    {
+        const int jw = 16 * mt + (col >> 1);
+        const float2* Wg = W + (size_t)g * P * Q;
+        constexpr float sgn = CONJT ? -1.f : 1.f;
+#pragma unroll
+        for (int u = 0; u < P / 2; ++u) {
+            const int i = 2 * u + kh;
+            const float2 w = CONJT ? Wg[i * Q + jw] : Wg[jw * P + i];
+            A0[u] = e ? sgn * w.y : w.x;
+            A1[u] = e ? w.x : -sgn * w.y;
+        }
+    }
+
+    Tile pre;
+    int64_t rt = split;
+    if (rt < ntiles) pre.fetch(in, rt, g, k, ld_in, B, tid);
+    for (int it = 0; rt < ntiles; rt += nsplit, ++it) {
+        float2* a = act[it & 1];
+        pre.to_lds(a, tid);
+        lds_barrier();
+        if (rt + nsplit < ntiles) pre.fetch(in, rt + nsplit, g, k, ld_in, B, tid);
+
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+        for (int u = 0; u < P / 2; ++u) {
+            const float2 xv = Tile::at(a, 2 * u + kh, col);
+            acc = mfma_f32(A0[u], xv.x, acc);
+            acc = mfma_f32(A1[u], xv.y, acc);
+        }
+
+        const int64_t row = rt * kRT + col;
+        if constexpr (OUT == kOutNat) {
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    ost[col * OSTR + 16 * mt + 4 * q4 + 2 * kh + h] = make_float2(acc[4 * q4 + 2 * h], acc[4 * q4 + 2 * h + 1]);
+            lds_barrier();
+            constexpr int kPieces = kRT * Q / 2 / NTHR;
+#pragma unroll
+            for (int n = 0; n < kPieces; ++n) {
+                const int idx = tid + n * NTHR, r = idx / (Q / 2), c2 = idx - r * (Q / 2);
+                const float2 v0 = ost[r * OSTR + 2 * c2], v1 = ost[r * OSTR + 2 * c2 + 1];
+                if (rt * kRT + r < B)
+                    *reinterpret_cast<f32x4*>(out + (rt * kRT + r) * ld_out + (size_t)g * Q + 2 * c2) = f32x4{v0.x, v0.y, v1.x, v1.y};
+            }
+        } else {
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int j = 16 * mt + 4 * q4 + 2 * kh + h;
+                    const float2 v = make_float2(acc[4 * q4 + 2 * h], acc[4 * q4 + 2 * h + 1]);
+                    if constexpr (OUT == kOutScatter) {
+                        if (row < B) out[row * ld_out + (size_t)j * k + g] = v;
+                    } else {
+                        const int d = (OUT == kOutTFwd) ? mid_dest(g * Q + j, k, Q, pb) : mid_src(g * Q + j, k, Q, pb);
+                        const int blk = d / Q, idx = d - blk * Q;
+                        out[(((size_t)rt * k + blk) * Q + idx) * kRT + col] = v;
+                    }
+                }
+        }
+    }
+}
+
+// part[z][g][ma][nb] = sum over the rows b of the tiles z, z + Z, ... of  A[b][g][ma] * conj(Bv[b][g][nb])
+// A: dW (kInGather from dy) or dY1 (kInT);  Bv: U (kInT) or x (kInNat).  M = 2*MA real rows (re and im of the
+// result), N = NB columns, K = (row, component): with B'[(b,t)][nb] = component t of Bv[b][nb],
+//   A'[2ma][(b,0)] = ar,  A'[2ma][(b,1)] = ai,  A'[2ma+1][(b,0)] = ai,  A'[2ma+1][(b,1)] = -ar.
+// Wave w owns the 16 values ma = 16w .. 16w+15 and every column.  LDS holds each operand so that the lanes of a
+// wave read consecutive addresses for one row: [row][len] for row-major sources, [idx][32 + 1] for the tiled ones.
+template <int LEN, int NTHR, int MODE>
+struct WgTile {
+    static constexpr int kPieces = (MODE == kInGather) ? kRT * LEN / NTHR : kRT * LEN / 2 / NTHR;
+    static constexpr int kLen = (MODE == kInT) ? LEN * (kRT + 1) : kRT * LEN;
+    u32x4 v[MODE == kInGather ? (kPieces + 1) / 2 : kPieces];
+
+    __device__ __forceinline__ void fetch(const float2* __restrict__ src, int64_t rt, int g, int k, int64_t ld, int64_t B, int tid)
+    {
+        const int64_t row0 = rt * kRT;
+        if constexpr (MODE == kInNat) {
+#pragma unroll
+            for (int n = 0; n < kPieces; ++n) {
+                const int idx = tid + n * NTHR, row = idx / (LEN / 2), c2 = idx - row * (LEN / 2);
+                v[n] = (row0 + row < B) ? ldg128(src + (row0 + row) * ld + (size_t)g * LEN + 2 * c2) : u32x4{0, 0, 0, 0};
+            }
+        } else if constexpr (MODE == kInGather) {
+#pragma unroll
+            for (int n = 0; n < kPieces; ++n) {
+                const int idx = tid + n * NTHR, row = idx / LEN, i = idx - row * LEN;
+                float2 t = make_float2(0.f, 0.f);
+                if (row0 + row < B) t = src[(row0 + row) * ld + (size_t)i * k + g];
+                if (n & 1) { v[n / 2].z = __float_as_uint(t.x); v[n / 2].w = __float_as_uint(t.y); }
+                else { v[n / 2].x = __float_as_uint(t.x); v[n / 2].y = __float_as_uint(t.y); }
+            }
+        } else {
+            const float2* tile = src + ((size_t)rt * k + g) * (LEN * kRT);
+#pragma unroll
+            for (int n = 0; n < kPieces; ++n) v[n] = ldg128(tile + 2 * (tid + n * NTHR));
+        }
+    }
+
+    __device__ __forceinline__ void to_lds(float2* t, int tid) const
+    {
+        if constexpr (MODE == kInNat) {
+#pragma unroll
+            for (int n = 0; n < kPieces; ++n) *reinterpret_cast<u32x4*>(t + 2 * (tid + n * NTHR)) = v[n];
+        } else if constexpr (MODE == kInGather) {
+#pragma unroll
+            for (int n = 0; n < kPieces; ++n) {
+                const u32x4 w = v[n / 2];
+                t[tid + n * NTHR] = (n & 1) ? make_float2(__uint_as_float(w.z), __uint_as_float(w.w))
+                                            : make_float2(__uint_as_float(w.x), __uint_as_float(w.y));
+            }
+        } else {
+#pragma unroll
+            for (int n = 0; n < kPieces; ++n) {
+                const int idx = tid + n * NTHR, i = idx / (kRT / 2), rp = idx - i * (kRT / 2);
+                lds_store_c2(t + i * (kRT + 1) + 2 * rp, v[n]);
+            }
+        }
+    }
+
+    static __device__ __forceinline__ float2 at(const float2* t, int idx, int row)
+    {
+        return (MODE == kInT) ? t[idx * (kRT + 1) + row] : t[row * LEN + idx];
+    }
+};
+
+template <int MA, int NB, int AMODE, int BMODE>
+__global__ void __launch_bounds__(4 * MA)
+cwgrad_kernel(const float2* __restrict__ A, const float2* __restrict__ Bv, float2* __restrict__ part, int64_t B, int k,
+              int Z, int64_t lda, int64_t ldb)
+{
+    constexpr int NTHR = 4 * MA;
+    constexpr int NTN = (NB + 31) / 32;
+    using TA = WgTile<MA, NTHR, AMODE>;
+    using TB = WgTile<NB, NTHR, BMODE>;
+    extern __shared__ __align__(16) float2 wg_lds[];  // two buffers of each operand: 2 * (TA::kLen + TB::kLen) values
+
+    const int g = (int)blockIdx.x / Z, z = (int)blockIdx.x - g * Z;
+    const int tid = threadIdx.x, lane = tid & 63, mt = tid >> 6;
+    const int col = lane & 31, kh = lane >> 5, e = lane & 1;
+    const int ma = 16 * mt + (col >> 1);
+    const int64_t ntiles = (B + kRT - 1) / kRT;
+
+    f32x16 acc[NTN];
+#pragma unroll
+    for (int nt = 0; nt < NTN; ++nt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
+
+    TA pa;
+    TB pbv;
+    int64_t rt = z;
+    if (rt < ntiles) {
+        pa.fetch(A, rt, g, k, lda, B, tid);
+        pbv.fetch(Bv, rt, g, k, ldb, B, tid);
+    }
+    for (int it = 0; rt < ntiles; rt += Z, ++it) {
+        float2* ta = wg_lds + (it & 1) * TA::kLen;
+        float2* tb = wg_lds + 2 * TA::kLen + (it & 1) * TB::kLen;
+        pa.to_lds(ta, tid);
+        pbv.to_lds(tb, tid);
+        lds_barrier();
+        if (rt + Z < ntiles) {
+            pa.fetch(A, rt + Z, g, k, lda, B, tid);
+            pbv.fetch(Bv, rt + Z, g, k, ldb, B, tid);
+        }
+#pragma unroll
+        for (int u = 0; u < kRT / 2; ++u) {
+            const int b = 2 * u + kh;
+            const float2 av = TA::at(ta, ma, b);
+            const float a0 = e ? av.y : av.x;
+            const float a1 = e ? -av.x : av.y;
+#pragma unroll
+            for (int nt = 0; nt < NTN; ++nt) {
+                const int nb = 32 * nt + col;
+                const float2 bv = (NB % 32 == 0 || nb < NB) ? TB::at(tb, nb, b) : make_float2(0.f, 0.f);
+                acc[nt] = mfma_f32(a0, bv.x, acc[nt]);
+                acc[nt] = mfma_f32(a1, bv.y, acc[nt]);
+            }
+        }
+    }
+    float2* o = part + ((size_t)z * k + g) * (MA * NB);
+#pragma unroll
+    for (int nt = 0; nt < NTN; ++nt) {
+        const int nb = 32 * nt + col;
+        if (NB % 32 != 0 && nb >= NB) continue;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                o[(16 * mt + 4 * q4 + 2 * kh + h) * NB + nb] = make_float2(acc[nt][4 * q4 + 2 * h], acc[nt][4 * q4 + 2 * h + 1]);
+    }
+}
+
+// out[e] = part[0][e] + part[1][e] + ... + part[Z-1][e], in that order; e counts float4s
+__global__ void __launch_bounds__(256) csum_kernel(const f32x4* __restrict__ part, f32x4* __restrict__ out, size_t n4, int Z)
+{
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n4) return;
+    f32x4 s = part[e];
+    for (int z = 1; z < Z; ++z) {
+        const f32x4 t = part[(size_t)z * n4 + e];
+        s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+    }
+    out[e] = s;
+}
+
+int64_t tiles_of(const Problem& pb) { return (pb.B + kRT - 1) / kRT; }
+size_t t_bytes(const Problem& pb) { return align_up((size_t)tiles_of(pb) * kRT * pb.kq() * sizeof(float2), 256); }
+
+// workgroups of one block: enough for about sixteen waves per CU in all, a multiple of 8, at most one per tile
+int splits_for(const Problem& pb, int waves_per_wg, int target_waves)
+{
+    int64_t n = (target_waves / waves_per_wg + pb.k - 1) / pb.k;
+    n = (n + 7) / 8 * 8;
+    const int64_t t = tiles_of(pb);
+    if (n > t) n = t;
+    return (int)(n < 1 ? 1 : n);
+}
+
+int wgrad_chunks(const Problem& pb)
+{
+    int64_t z = (512 + pb.k - 1) / pb.k;
+    z = (z + 7) / 8 * 8;
+    const int64_t t = tiles_of(pb);
+    if (z > t) z = t;
+    return (int)(z < 1 ? 1 : z);
+}
+
+template <int M, int IN, int OUT, bool CONJT>
+int launch_stage(const Problem& pb, const void* in, const void* W, void* out, hipStream_t st)
+{
+    const int nsplit = splits_for(pb, M / 16, 4096);
+    const int64_t grid = (int64_t)pb.k * nsplit;
+    if (grid > 0x7fffffffLL) return -2;
+    hipLaunchKernelGGL((cstage_kernel<M, M, IN, OUT, CONJT>), dim3((unsigned)grid), dim3(4 * M), 0, st, (const float2*)in,
+                       (const float2*)W, (float2*)out, pb.B, pb.k, nsplit, pb.perm_b() ? 1 : 0);
+    return hip_status(hipGetLastError());
+}
+
+template <int M, int AMODE, int BMODE>
+int launch_wgrad(const Problem& pb, const void* A, const void* Bv, void* out, void* part, int64_t lda, int64_t ldb,
+                 hipStream_t st)
+{
+    const int Z = wgrad_chunks(pb);
+    const int64_t grid = (int64_t)pb.k * Z;
+    if (grid > 0x7fffffffLL) return -2;
+    float2* dst = Z == 1 ? (float2*)out : (float2*)part;
+    auto kern = cwgrad_kernel<M, M, AMODE, BMODE>;
+    const size_t lds = 2 * (size_t)(WgTile<M, 4 * M, AMODE>::kLen + WgTile<M, 4 * M, BMODE>::kLen) * sizeof(float2);
+    if (allow_dynamic_lds((const void*)kern, lds) != hipSuccess) return -4;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(4 * M), lds, st, (const float2*)A, (const float2*)Bv, dst, pb.B,
+                       pb.k, Z, lda, ldb);
+    int rc = hip_status(hipGetLastError());
+    if (rc || Z == 1) return rc;
+    const size_t n4 = (size_t)pb.k * M * M / 2;
+    hipLaunchKernelGGL(csum_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, (const f32x4*)part, (f32x4*)out, n4, Z);
+    return hip_status(hipGetLastError());
+}
+
+template <int M>
+int run_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
+{
+    int rc = launch_stage<M, kInNat, kOutTFwd, false>(pb, x, R, ws, st);
+    if (rc) return rc;
+    return launch_stage<M, kInT, kOutScatter, false>(pb, ws, L, y, st);
+}
+
+template <int M>
+int run_fwd_h(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
+{
+    int rc = launch_stage<M, kInGather, kOutTBwd, true>(pb, x, L, ws, st);
+    if (rc) return rc;
+    return launch_stage<M, kInT, kOutNat, true>(pb, ws, R, y, st);
+}
+
+template <int M>
+int run_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR, void* dL,
+            void* ws, hipStream_t st)
+{
+    char* w = (char*)ws;
+    void* Ut = w;
+    void* dY1t = w + t_bytes(pb);
+    void* part = w + 2 * t_bytes(pb);
+    int rc = launch_stage<M, kInNat, kOutTFwd, false>(pb, x, R, Ut, st);
+    if (rc) return rc;
+    rc = launch_stage<M, kInGather, kOutTBwd, true>(pb, dy, L, dY1t, st);
+    if (rc) return rc;
+    rc = launch_stage<M, kInT, kOutNat, true>(pb, dY1t, R, dx, st);
+    if (rc) return rc;
+    rc = launch_wgrad<M, kInGather, kInT>(pb, dy, Ut, dL, part, pb.n_out(), 0, st);
+    if (rc) return rc;
+    return launch_wgrad<M, kInT, kInNat>(pb, dY1t, x, dR, part, 0, pb.n_in, st);
+}
+
+}  // namespace
+
+bool complex_mfma_supported(const Problem& pb)
+{
+    return pb.p == pb.q && pb.q == pb.s && (pb.p == 16 || pb.p == 32 || pb.p == 64);
+}
+
+// pass: 0 forward, 1 backward, 2 conjugate-transpose forward
+size_t complex_mfma_workspace(const Problem& pb, int pass)
+{
+    if (pass != 1) return t_bytes(pb);
+    const int Z = wgrad_chunks(pb);
+    return 2 * t_bytes(pb) + (Z > 1 ? align_up((size_t)Z * pb.n_L() * sizeof(float2), 256) : 0);
+}
+
+int complex_mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
+{
+    switch (pb.p) {
+        case 16: return run_fwd<16>(pb, x, R, L, y, ws, st);
+        case 32: return run_fwd<32>(pb, x, R, L, y, ws, st);
+        case 64: return run_fwd<64>(pb, x, R, L, y, ws, st);
+        default: return -2;
+    }
+}
+
+int complex_mfma_fwd_h(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
+{
+    switch (pb.p) {
+        case 16: return run_fwd_h<16>(pb, x, R, L, y, ws, st);
+        case 32: return run_fwd_h<32>(pb, x, R, L, y, ws, st);
+        case 64: return run_fwd_h<64>(pb, x, R, L, y, ws, st);
+        default: return -2;
+    }
+}
+
+int complex_mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
+                     void* dL, void* ws, hipStream_t st)
+{
+    switch (pb.p) {
+        case 16: return run_bwd<16>(pb, dy, x, R, L, dx, dR, dL, ws, st);
+        case 32: return run_bwd<32>(pb, dy, x, R, L, dx, dR, dL, ws, st);
+        case 64: return run_bwd<64>(pb, dy, x, R, L, dx, dR, dL, ws, st);
+        default: return -2;
+    }
+}
+
+}  // namespace monarch

@@ -76,6 +76,14 @@ int complex_bwd(const Problem& pb, const void* dy, const void* x, const void* R,
                 void* dL, void* ws, hipStream_t st);
 // y = x conj(M) (the conjugate transpose applied to every row): x (B, k*s) -> y (B, k*p)
 bool complex_fwd_h_supported(const Problem& pb);
+// matrix-core complex kernels (monarch_complex_mfma.hip): square blocks p = q = s in {16, 32, 64}; every call needs
+// complex_mfma_workspace(pb, pass) bytes (pass: 0 forward, 1 backward, 2 conjugate-transpose forward); B > 0
+bool complex_mfma_supported(const Problem& pb);
+size_t complex_mfma_workspace(const Problem& pb, int pass);
+int complex_mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);
+int complex_mfma_fwd_h(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);
+int complex_mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
+                     void* dL, void* ws, hipStream_t st);
 int complex_fwd_h(const Problem& pb, const void* x, const void* R, const void* L, void* y, hipStream_t st);
 int launch_dft_factors(void* R, void* L, int m, int inverse, hipStream_t st);
 

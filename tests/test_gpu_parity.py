@@ -823,7 +823,22 @@ def cnormal(seed, shape, std=1.0):
 
 
 COMPLEX_CASES = [("c_sq4", 9, 4, 4, 4, 4), ("c_sq16", 70, 16, 16, 16, 16), ("c_rect", 33, 3, 4, 5, 2), ("c_k4", 130, 4, 32, 32, 48),
-                 ("c_one_row", 1, 2, 3, 4, 2), ("c_wide", 77, 2, 70, 130, 66), ("c_sq64", 21, 64, 64, 64, 64)]
+                 ("c_one_row", 1, 2, 3, 4, 2), ("c_wide", 77, 2, 70, 130, 66), ("c_sq64", 21, 64, 64, 64, 64),
+                 # square blocks of 16 / 32 / 64 with a block count that is not the block size, and batches long enough
+                 # that a workgroup of the matrix-core kernels takes several row tiles (the last one ragged)
+                 ("c_m32", 100, 32, 32, 32, 32), ("c_k3_m64", 67, 3, 64, 64, 64), ("c_k5_m16", 200, 5, 16, 16, 16),
+                 ("c_m32_long", 8219, 8, 32, 32, 32), ("c_m64_long", 16421, 2, 64, 64, 64), ("c_m16_long", 33003, 4, 16, 16, 16)]
+
+
+def guarded_workspace(need):
+    """(buffer, view): `need` bytes, 256-byte aligned, between two runs of canary bytes."""
+    wbuf = torch.full((need + 512 + 2 * GUARD,), 0x5A, dtype=torch.uint8, device="cuda")
+    off = (-(wbuf.data_ptr() + GUARD)) % 256 + GUARD
+    return wbuf, off, wbuf[off:off + need]
+
+
+def workspace_untouched_outside(wbuf, off, need):
+    return bool((wbuf[:off] == 0x5A).all()) and bool((wbuf[off + need:] == 0x5A).all())
 
 
 @pytest.mark.parametrize("reading", [0, 1], ids=["reading_a", "reading_b"])
@@ -834,32 +849,54 @@ def test_complex_forward_and_backward(B, case, reading):
     x, R, L, dy = (cnormal(8000 + 10 * i, shp, std) for i, (shp, std) in enumerate(
         (((rows, k * p), 1.0), ((k, q, p), p ** -0.5), ((k, s, q), q ** -0.5), ((rows, k * s), 1.0))))
     flags = B.MONARCH_FLAG_PERM_B if reading else 0
-    y = B.monarch_fwd_c64(cdev(x), cdev(R), cdev(L), flags=flags)
-    dx, dR, dL = B.monarch_bwd_c64(cdev(dy), cdev(x), cdev(R), cdev(L), flags=flags)
+    xd, Rd, Ld, dyd = cdev(x), cdev(R), cdev(L), cdev(dy)
+    y = B.monarch_fwd_c64(xd, Rd, Ld, flags=flags)
+    dx, dR, dL = B.monarch_bwd_c64(dyd, xd, Rd, Ld, flags=flags)
     torch.cuda.synchronize()
-    yh = B.monarch_fwd_h_c64(cdev(dy), cdev(R), cdev(L), flags=flags)   # conjugate transpose applied to the rows of dy
-    # the backward with a (guarded) workspace: weight gradients by the batch-contracted GEMM
-    need = B.monarch_bwd_c64_workspace_bytes(rows, k * p, k, q, s, flags)
-    wbuf = torch.full((need + 512 + 2 * GUARD,), 0x5A, dtype=torch.uint8, device="cuda")
-    off = (-(wbuf.data_ptr() + GUARD)) % 256 + GUARD
-    dx2, dR2, dL2 = B.monarch_bwd_c64_ws(cdev(dy), cdev(x), cdev(R), cdev(L), workspace=wbuf[off:off + need], flags=flags)
-    torch.cuda.synchronize()
-    assert bool((wbuf[:off] == 0x5A).all()) and bool((wbuf[off + need:] == 0x5A).all()), "workspace: wrote out of bounds"
-    assert torch.equal(dx2, dx), "the data path is the same kernel code with or without the workspace"
+    yh = B.monarch_fwd_h_c64(dyd, Rd, Ld, flags=flags)   # conjugate transpose applied to the rows of dy
+    # the same three calls with a (guarded) workspace: matrix-core kernels for the square blocks of 16 / 32 / 64,
+    # elsewhere the same data kernels and the weight gradients by a batch-contracted GEMM
+    outs_ws = []
+    for pass_, call in ((B.C64_FWD, lambda w: (B.monarch_fwd_c64_ws(xd, Rd, Ld, workspace=w, flags=flags),)),
+                        (B.C64_BWD, lambda w: B.monarch_bwd_c64_ws(dyd, xd, Rd, Ld, workspace=w, flags=flags)),
+                        (B.C64_FWD_H, lambda w: (B.monarch_fwd_h_c64_ws(dyd, Rd, Ld, workspace=w, flags=flags),))):
+        need = B.monarch_c64_workspace_bytes(pass_, rows, k * p, k, q, s, flags)
+        wbuf, off, view = guarded_workspace(need)
+        print("\n  %s pass %d workspace %d bytes" % (name, pass_, need), flush=True)
+        outs_ws += list(call(view))
+        torch.cuda.synchronize()
+        assert workspace_untouched_outside(wbuf, off, need), "workspace: wrote out of bounds (pass %d)" % pass_
+    on_matrix_cores = p == q == s and p in (16, 32, 64)
+    if not on_matrix_cores:
+        assert torch.equal(outs_ws[0], y) and torch.equal(outs_ws[1], dx) and torch.equal(outs_ws[4], yh), \
+            "the data path is the same kernel code with or without the workspace"
     ref = list(complex_ref.bwd(dy, x, R, L, reading))
-    want = [complex_ref.fwd(x, R, L, reading)] + ref + [complex_ref.fwd_h(dy, R, L, reading)] + ref[1:]
+    y_ref, yh_ref = complex_ref.fwd(x, R, L, reading), complex_ref.fwd_h(dy, R, L, reading)
+    want = [y_ref] + ref + [yh_ref] + [y_ref] + ref + [yh_ref]
+    names = ("y", "dx", "dR", "dL", "xMh", "y_ws", "dx_ws", "dR_ws", "dL_ws", "xMh_ws")
     errs = {}
-    for nm, got, w in zip(("y", "dx", "dR", "dL", "xMh", "dR_ws", "dL_ws"), (y, dx, dR, dL, yh, dR2, dL2), want):
+    for nm, got, w in zip(names, [y, dx, dR, dL, yh] + outs_ws, want):
         g = got.cpu().numpy().astype(np.complex128)
         errs[nm] = float(np.linalg.norm((g - w).ravel()) / np.linalg.norm(w.ravel()))
-    print("\n  %s %s" % (name, " ".join("%s=%.2e" % kv for kv in errs.items())), flush=True)
+        if nm in ("y_ws", "dx_ws", "xMh_ws"):   # no batch row may be wrong as a whole either
+            rel = np.linalg.norm(g - w, axis=1) / np.linalg.norm(w, axis=1)
+            assert float(rel.max()) <= 4 * TOL["f32"], (nm, int(rel.argmax()), float(rel.max()))
+        if nm in ("dR_ws", "dL_ws"):             # ... and no block of a weight gradient
+            rel = np.linalg.norm((g - w).reshape(k, -1), axis=1) / np.linalg.norm(w.reshape(k, -1), axis=1)
+            assert float(rel.max()) <= 4 * TOL["f32"], (nm, int(rel.argmax()), float(rel.max()))
+    print("  %s %s" % (name, " ".join("%s=%.2e" % kv for kv in errs.items())), flush=True)
     assert max(errs.values()) <= TOL["f32"], errs
+    if on_matrix_cores:   # fixed summation order: the same bits on a second call
+        again = B.monarch_bwd_c64_ws(dyd, xd, Rd, Ld, flags=flags)
+        assert all(torch.equal(u, v) for u, v in zip(again, outs_ws[1:4]))
     # empty batch: no-op forward, zero gradients
-    e = B.monarch_bwd_c64(cdev(dy[:0]), cdev(x[:0]), cdev(R), cdev(L), flags=flags)
+    e = B.monarch_bwd_c64(dyd[:0], xd[:0], Rd, Ld, flags=flags)
     assert e[0].shape == (0, k * p) and not bool(e[1].any()) and not bool(e[2].any())
-    e = B.monarch_bwd_c64_ws(cdev(dy[:0]), cdev(x[:0]), cdev(R), cdev(L), flags=flags)
+    e = B.monarch_bwd_c64_ws(dyd[:0], xd[:0], Rd, Ld, flags=flags)
     assert e[0].shape == (0, k * p) and not bool(e[1].any()) and not bool(e[2].any())
-    assert B.monarch_fwd_h_c64(cdev(dy[:0]), cdev(R), cdev(L), flags=flags).shape == (0, k * p)
+    assert B.monarch_fwd_h_c64(dyd[:0], Rd, Ld, flags=flags).shape == (0, k * p)
+    assert B.monarch_fwd_c64_ws(xd[:0], Rd, Ld, flags=flags).shape == (0, k * s)
+    assert B.monarch_fwd_h_c64_ws(dyd[:0], Rd, Ld, flags=flags).shape == (0, k * p)
 
 
 @pytest.mark.parametrize("m", [4, 16, 64])

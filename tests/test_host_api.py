@@ -337,10 +337,30 @@ def test_complex_calls_reject_bad_arguments_without_a_gpu(binding):
     assert bwd(n_in=18) == binding.MONARCH_ERR_INVALID
     assert bwd(flags=binding.MONARCH_FLAG_WGRAD_F32) == binding.MONARCH_ERR_INVALID
 
-    cneed = binding.monarch_bwd_c64_workspace_bytes(5, 16, 4, 4, 4, 0)
+    cneed = binding.monarch_c64_workspace_bytes(binding.C64_BWD, 5, 16, 4, 4, 4, 0)
     assert cneed >= 5 * (2 * 16 + 16) * 8
-    assert binding.monarch_bwd_c64_workspace_bytes(5, 18, 4, 4, 4, 0) == 0                      # n_in not k*p
-    assert binding.monarch_bwd_c64_workspace_bytes(5, 16, 4, 4, 4, binding.MONARCH_FLAG_GENERIC) == 0
+    assert binding.monarch_c64_workspace_bytes(binding.C64_BWD, 5, 18, 4, 4, 4, 0) == 0          # n_in not k*p
+    assert binding.monarch_c64_workspace_bytes(binding.C64_BWD, 5, 16, 4, 4, 4, binding.MONARCH_FLAG_GENERIC) == 0
+    assert binding.monarch_c64_workspace_bytes(3, 5, 16, 4, 4, 4, 0) == 0                        # no such pass
+    assert binding.monarch_c64_workspace_bytes(binding.C64_FWD, 5, 16, 4, 4, 4, 0) == 0          # shape-generic forward: none
+    # square blocks of 16 / 32 / 64: the tiled intermediate, whole 32-row tiles
+    mneed = binding.monarch_c64_workspace_bytes(binding.C64_FWD, 33, 4 * 16, 4, 16, 16, 0)
+    assert mneed == 2 * 32 * 4 * 16 * 8
+    assert binding.monarch_c64_workspace_bytes(binding.C64_FWD_H, 33, 4 * 16, 4, 16, 16, 0) == mneed
+    assert binding.monarch_c64_workspace_bytes(binding.C64_BWD, 33, 4 * 16, 4, 16, 16, 0) >= 2 * mneed
+
+    def fwd_ws(fn, ptrs=(p,) * 4, ws=p, ws_bytes=mneed, flags=0, n_in=64):
+        return fn(*ptrs, 33, n_in, 4, 16, 16, None, ws, ws_bytes, flags)
+
+    for fn in (L.monarch_fwd_c64_ws, L.monarch_fwd_h_c64_ws):
+        for bad in range(4):
+            ptrs = [p] * 4
+            ptrs[bad] = None
+            assert fwd_ws(fn, tuple(ptrs)) == binding.MONARCH_ERR_INVALID
+        assert fwd_ws(fn, ws_bytes=mneed - 1) == binding.MONARCH_ERR_WORKSPACE
+        assert fwd_ws(fn, ws=p + 16) == binding.MONARCH_ERR_WORKSPACE
+        assert fwd_ws(fn, n_in=66) == binding.MONARCH_ERR_INVALID
+        assert fwd_ws(fn, flags=binding.MONARCH_FLAG_GENERIC) == binding.MONARCH_ERR_INVALID
 
     def bwd_ws(ptrs=(p,) * 7, batch=5, n_in=16, ws=p, ws_bytes=cneed, flags=0):
         return L.monarch_bwd_c64_ws(*ptrs, batch, n_in, 4, 4, 4, None, ws, ws_bytes, flags)
