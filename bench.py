@@ -380,9 +380,21 @@ def measure_extras(ly: Layer, calls: int):
         cx = torch.randn((crow, sh.n_in), dtype=torch.complex64, device=dev, generator=torch.Generator(device=dev).manual_seed(7))
         cR, cL = binding.monarch_dft_factors(sh.k, False, device=dev)
         cy = torch.empty_like(cx)
-        ex["c64_fwd_ms"] = timed_runs(lambda i: binding.monarch_fwd_c64(cx, cR, cL, cy), 20, 2)[0]
-        ex["c64_bwd_ms"] = timed_runs(lambda i: binding.monarch_bwd_c64(cy, cx, cR, cL), 20, 2)[0]
+        cdx, cdR, cdL = torch.empty_like(cx), torch.empty_like(cR), torch.empty_like(cL)
+        cneed = binding.monarch_c64_workspace_bytes(binding.C64_BWD, crow, sh.n_in, sh.k, sh.q, sh.s)
+        cws = torch.empty(max(cneed, 256), dtype=torch.uint8, device=dev)
+        ex["c64_fwd_ms"] = timed_runs(lambda i: binding.monarch_fwd_c64_ws(cx, cR, cL, cy, workspace=cws), 20, 2)[0]
+        ex["c64_fwd_h_ms"] = timed_runs(lambda i: binding.monarch_fwd_h_c64_ws(cx, cR, cL, cy, workspace=cws), 20, 2)[0]
+        ex["c64_bwd_ms"] = timed_runs(lambda i: binding.monarch_bwd_c64_ws(cy, cx, cR, cL, cdx, cdR, cdL, workspace=cws), 20, 2)[0]
+        # the calls without a workspace (shape-generic fp32 kernels, weight gradients through atomics)
+        ex["c64_fwd_noworkspace_ms"] = timed_runs(lambda i: binding.monarch_fwd_c64(cx, cR, cL, cy), 5, 2)[0]
+        ex["c64_bwd_noworkspace_ms"] = timed_runs(lambda i: binding.monarch_bwd_c64(cy, cx, cR, cL), 5, 2)[0]
         ex["c64_rows"] = crow
+        # 8 real flops per complex multiply-add, two factors forward, six block products backward
+        cflops = 8.0 * crow * sh.k * (sh.q * sh.p + sh.s * sh.q)
+        ex["c64_fwd_tflops"] = cflops / (ex["c64_fwd_ms"] * 1e-3) / 1e12
+        ex["c64_bwd_tflops"] = 2.5 * cflops / (ex["c64_bwd_ms"] * 1e-3) / 1e12
+        del cws, cdx
         # Algorithm 1 on a dense Gaussian n x n matrix: one Jacobi SVD per slice
         Adense = torch.from_numpy(synth.quantize(synth.normal(4343, (sh.n_in, sh.n_in)), sh.dtype)).to(dev).to(dt)
         Rp, Lp = torch.empty_like(Rd), torch.empty_like(Ld)

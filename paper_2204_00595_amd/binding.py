@@ -709,6 +709,7 @@ def monarch_fwd_h_c64_ws(x: torch.Tensor, R: torch.Tensor, L: torch.Tensor, y: t
 
 
 def monarch_bwd_c64_ws(dy: torch.Tensor, x: torch.Tensor, R: torch.Tensor, L: torch.Tensor,
+                       dx: torch.Tensor | None = None, dR: torch.Tensor | None = None, dL: torch.Tensor | None = None,
                        workspace: torch.Tensor | None = None, flags: int = 0, stream=None):
     """monarch_bwd_c64 with a workspace (allocated when not given): matrix-core kernels for square blocks, else
     the weight gradients contracted by a GEMM over operands kept in the workspace."""
@@ -720,7 +721,12 @@ def monarch_bwd_c64_ws(dy: torch.Tensor, x: torch.Tensor, R: torch.Tensor, L: to
     _check(dy, "dy", (B, k * s), dt, dev)
     _check(R, "R", (k, q, p), dt, dev)
     _check(L, "L", (k, s, q), dt, dev)
-    dx, dR, dL = torch.empty_like(x), torch.empty_like(R), torch.empty_like(L)
+    dx = torch.empty_like(x) if dx is None else dx
+    dR = torch.empty_like(R) if dR is None else dR
+    dL = torch.empty_like(L) if dL is None else dL
+    _check(dx, "dx", (B, k * p), dt, dev)
+    _check(dR, "dR", (k, q, p), dt, dev)
+    _check(dL, "dL", (k, s, q), dt, dev)
     need = monarch_c64_workspace_bytes(C64_BWD, B, k * p, k, q, s, flags)
     if workspace is None:
         workspace = _scratch(max(need, 256), dev, stream)
