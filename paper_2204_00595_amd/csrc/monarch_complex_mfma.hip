@@ -354,7 +354,15 @@ __global__ void __launch_bounds__(256) csum_kernel(const f32x4* __restrict__ par
     const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= n4) return;
     f32x4 s = part[e];
-    for (int z = 1; z < Z; ++z) {
+    int z = 1;
+    for (; z + 8 <= Z; z += 8) {  // eight loads in flight, added in order
+        f32x4 t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = part[(size_t)(z + u) * n4 + e];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { s.x += t[u].x; s.y += t[u].y; s.z += t[u].z; s.w += t[u].w; }
+    }
+    for (; z < Z; ++z) {
         const f32x4 t = part[(size_t)z * n4 + e];
         s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
     }

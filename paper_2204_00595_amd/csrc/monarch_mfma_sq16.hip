@@ -470,29 +470,28 @@ bwd_sq16_kernel(const float* __restrict__ dy, const float* __restrict__ x, const
         }
 }
 
-// Backward for a batch of at most four 16-row tiles (one workgroup): the five MFMA groups of a tile are split
-// over four waves (wave = (tile t, part q)), each taking a quarter of every group's sixteen blocks -- block kk or c
-// in 4q .. 4q+3, or the quarter cq = q / kq = q of the two gradient products -- so a tile takes a quarter of the
-// time it takes one wave, the weights come straight from global memory in operand order (no staging pass, no
-// second launch), and every wave holds only its quarter of the operands (4 of the 16 pieces of x and dy) and
-// of the gradients.  The exchanges through the tile are the ones of bwd_sq16_kernel, with workgroup barriers in
-// place of the wave fences.  At the end the four tiles' gradients are summed through LDS in a fixed order and
-// written to dR and dL: no workspace, no reduction launch.
-constexpr int SQ16S_TILES = 4;
-constexpr size_t SQ16S_LDS = SQ16S_TILES * 8192 * sizeof(float);  // 128 KiB: four tiles first, the four gradient copies at the end
+// Backward with one workgroup per 16-row tile, for batches of up to 1024 tiles: the five MFMA groups of the tile
+// are split over four waves (wave q), each taking a quarter of every group's sixteen blocks -- block kk or c in
+// 4q .. 4q+3 -- so a tile takes a quarter of the time it takes one wave and the tiles of a short batch run on
+// different CUs; the weights come straight from global memory in operand order (no staging pass) and every wave
+// holds only its quarter of the operands (4 of the 16 pieces of x and dy) and of the gradients.  The exchanges
+// through the tile are the ones of bwd_sq16_kernel, with workgroup barriers in place of the wave fences.  Every
+// workgroup writes its tile's gradients to P[tile][8192] and reduce_sq16_kernel sums them in tile order.  Each
+// workgroup reads all of R and L (48 KiB against 32 KiB of activations), which is why long batches take the
+// persistent kernel.
+constexpr int64_t SQ16T_TILES = 1024;
 
-__global__ void __launch_bounds__(1024)
-bwd_sq16_small_kernel(const float* __restrict__ dy, const float* __restrict__ x, const float* __restrict__ R,
-                      const float* __restrict__ L, float* __restrict__ dx, float* __restrict__ dR, float* __restrict__ dL,
-                      int64_t B)
+__global__ void __launch_bounds__(256)
+bwd_sq16_tile_kernel(const float* __restrict__ dy, const float* __restrict__ x, const float* __restrict__ R,
+                      const float* __restrict__ L, float* __restrict__ dx, float* __restrict__ P,
+                     int64_t B)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char ldsb[];
+    __shared__ __attribute__((aligned(16))) unsigned char T[SQ16_T_BYTES];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int t = wave >> 2, q = wave & 3;
+    const int q = wave;
     const int bl = lane & 15, h = lane >> 4;
-    unsigned char* T = ldsb + (size_t)t * SQ16_T_BYTES;
-    const int64_t b0 = (int64_t)t * 16;
+    const int64_t b0 = (int64_t)blockIdx.x * 16;
     int64_t row = b0 + bl;
     const float msk = row < B ? 1.f : 0.f;  // rows past the end count as zero in dy (and are computed from a valid row of x)
     row = row < B ? row : B - 1;
@@ -592,23 +591,16 @@ bwd_sq16_small_kernel(const float* __restrict__ dy, const float* __restrict__ x,
         const f32x4 v = *reinterpret_cast<const f32x4*>(T + t_off(k2, lane));
         if (b0 + k2 < B) stg128f_nt(dx + (b0 + k2) * N16 + 4 * lane, v);
     }
-    __syncthreads();  // the tiles are dead: the whole LDS takes the four tiles' gradients, [tile][dR then dL]
-    float* red = reinterpret_cast<float*>(ldsb) + (size_t)t * 8192;
+    // this wave's quarter of the tile's gradients: P[tile][dR then dL][block][row][column]
+    float* Pt = P + (size_t)blockIdx.x * 8192;
 #pragma unroll
     for (int e = 0; e < 4; ++e)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             // accR[e] is block kk = 4q + e, accL[e] block c = 4q + e; element i is row 4h + i, column bl
-            red[(4 * q + e) * 256 + (4 * h + i) * 16 + bl] = accR[e][i];
-            red[4096 + (4 * q + e) * 256 + (4 * h + i) * 16 + bl] = accL[e][i];
+            Pt[(4 * q + e) * 256 + (4 * h + i) * 16 + bl] = accR[e][i];
+            Pt[4096 + (4 * q + e) * 256 + (4 * h + i) * 16 + bl] = accL[e][i];
         }
-    __syncthreads();
-    const float* all = reinterpret_cast<const float*>(ldsb);
-    for (int e = tid; e < 8192; e += 1024) {
-        const float tot = ((all[e] + all[8192 + e]) + all[2 * 8192 + e]) + all[3 * 8192 + e];
-        if (e < 4096) dR[e] = tot;
-        else dL[e - 4096] = tot;
-    }
 }
 
 // out[e] = sum_z P[z][e] for the 8192 gradient entries (dR then dL); 16 entries x 16 z-lanes per block
@@ -708,11 +700,13 @@ int bwd_sq16(const Problem& pb, const void* dy, const void* x, const void* R, co
     }
     const int grid = bwd_sq16_grid(pb);
     const int64_t ntiles = (pb.B + 15) / 16;
-    if (ntiles <= SQ16S_TILES) {  // the batch fits one workgroup: tiles split over four waves each, gradients summed in the kernel
-        auto small = bwd_sq16_small_kernel;
-        if (allow_dynamic_lds((const void*)small, SQ16S_LDS) != hipSuccess) return -4;
-        hipLaunchKernelGGL(small, dim3(1), dim3(1024), SQ16S_LDS, st, (const float*)dy, (const float*)x, (const float*)R,
-                           (const float*)L, (float*)dx, (float*)dR, (float*)dL, pb.B);
+    if (ntiles <= SQ16T_TILES) {  // one workgroup per tile, then the sum over tiles
+        if ((size_t)ntiles * 8192 * sizeof(float) > bwd_sq16_workspace(pb)) return -2;
+        hipLaunchKernelGGL(bwd_sq16_tile_kernel, dim3((unsigned)ntiles), dim3(256), 0, st, (const float*)dy, (const float*)x,
+                           (const float*)R, (const float*)L, (float*)dx, (float*)ws, pb.B);
+        if (hipGetLastError() != hipSuccess) return -4;
+        hipLaunchKernelGGL(reduce_sq16_kernel, dim3(8192 / 16), dim3(256), 0, st, (const float*)ws, (float*)dR, (float*)dL,
+                           (int)ntiles);
         return hip_status(hipGetLastError());
     }
     auto kern = bwd_sq16_kernel;
