@@ -216,6 +216,200 @@ cstage_kernel(const float2* __restrict__ in, const float2* __restrict__ W, float
     }
 }
 
+// The two stages that touch the outer permutation (y[b][l*k + c] written, dy read the same way), for k a multiple
+// of 8: eight blocks per workgroup, wave w = block 8*oct + w, every wave the same 16 outputs (one M tile) of its own
+// block, so that the pieces of the permuted side are the eight blocks' values of one (row, l): 64 contiguous bytes
+// instead of 8.  The workgroups that differ only in the M tile read the same activations; they sit on one XCD.
+//
+// cscatter8_kernel: tiled workspace -> y.  The activations of a wave's block are MFMA operands exactly as they lie
+// in the workspace (lane = row, 512 contiguous bytes per wave load), so they go from global memory to registers
+// directly, one tile ahead of the MFMAs; the results are exchanged through LDS as [row][l][block].
+template <int P, int Q>
+struct Scatter8 {
+    static constexpr int kRow = 16 * 8 + 1;  // values per row of the exchange buffer
+    static constexpr size_t kLds = 2 * (size_t)kRT * kRow * sizeof(float2);
+};
+
+template <int P, int Q>
+__global__ void __launch_bounds__(512)
+cscatter8_kernel(const float2* __restrict__ T, const float2* __restrict__ W, float2* __restrict__ out, int64_t B, int k,
+                 int nsplit)
+{
+    constexpr int MT = Q / 16;
+    constexpr int OROW = Scatter8<P, Q>::kRow;
+    extern __shared__ __align__(16) float2 ost8[];
+
+    int bid = (int)blockIdx.x;
+    const int split = bid % nsplit;
+    bid /= nsplit;
+    const int mt = bid % MT, oct = bid / MT;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int g = 8 * oct + w;
+    const int col = lane & 31, kh = lane >> 5, e = lane & 1;
+    const int64_t ntiles = (B + kRT - 1) / kRT;
+    const int64_t ld_out = (int64_t)k * Q;
+
+    float A0[P / 2], A1[P / 2];
+    {
+        const int jw = 16 * mt + (col >> 1);
+        const float2* Wg = W + (size_t)g * P * Q;
+#pragma unroll
+        for (int u = 0; u < P / 2; ++u) {
+            const float2 wv = Wg[jw * P + 2 * u + kh];
+            A0[u] = e ? wv.y : wv.x;
+            A1[u] = e ? wv.x : -wv.y;
+        }
+    }
+    auto load = [&](float2 (&buf)[P / 2], int64_t rt) {
+        const float2* src = T + ((size_t)rt * k + g) * (P * kRT) + (size_t)kh * kRT + col;
+#pragma unroll
+        for (int u = 0; u < P / 2; ++u) buf[u] = src[2 * u * kRT];
+    };
+    // the products of one tile, then the exchange through LDS buffer `it & 1` and the 64-byte pieces of y
+    auto tile = [&](const float2 (&buf)[P / 2], int64_t rt, int it) {
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+        for (int u = 0; u < P / 2; ++u) {
+            acc = mfma_f32(A0[u], buf[u].x, acc);
+            acc = mfma_f32(A1[u], buf[u].y, acc);
+        }
+        float2* o = ost8 + (it & 1) * (kRT * OROW);
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                o[col * OROW + (4 * q4 + 2 * kh + h) * 8 + w] = make_float2(acc[4 * q4 + 2 * h], acc[4 * q4 + 2 * h + 1]);
+        lds_barrier();
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {  // 32 rows x 16 outputs x 4 pairs of blocks, 16 bytes each
+            const int idx = tid + n * 512, c2 = idx & 3, ll = (idx >> 2) & 15, r = idx >> 6;
+            const float2 v0 = o[r * OROW + ll * 8 + 2 * c2], v1 = o[r * OROW + ll * 8 + 2 * c2 + 1];
+            if (rt * kRT + r < B)
+                *reinterpret_cast<f32x4*>(out + (rt * kRT + r) * ld_out + (size_t)(16 * mt + ll) * k + 8 * oct + 2 * c2) =
+                    f32x4{v0.x, v0.y, v1.x, v1.y};
+        }
+    };
+
+    // two register sets: the tile after the one being multiplied is on its way
+    float2 xa[P / 2], xb[P / 2];
+    int64_t rt = split;
+    if (rt < ntiles) load(xa, rt);
+    for (int it = 0; rt < ntiles; it += 2) {
+        if (rt + nsplit < ntiles) load(xb, rt + nsplit);
+        tile(xa, rt, it);
+        rt += nsplit;
+        if (rt >= ntiles) break;
+        if (rt + nsplit < ntiles) load(xa, rt + nsplit);
+        tile(xb, rt, it + 1);
+        rt += nsplit;
+    }
+}
+
+// cgather8_kernel: dy (read through the outer permutation) -> tiled workspace, weights conj(L[c])^T.  The eight
+// blocks' values of 32 rows x 16 inputs come in as 64-byte pieces and are laid out in LDS as one plane per block,
+// [row][16 + 1]; a wave takes its operands from its own plane.  Four (P = 64) such chunks make a tile; the next
+// chunk is fetched into registers while the current one is multiplied.  EMIT: the workgroups of M tile 0 also write
+// the chunk to the workspace in the tiled order (dW[row tile][block][l][32 rows]), the operand of the weight-gradient
+// kernel, which then does not have to gather dy again.
+template <int P>
+struct Gather8 {
+    static constexpr int kPlane = kRT * 17 + 1;
+    static constexpr size_t kLds = 2 * (size_t)8 * kPlane * sizeof(float2);
+};
+
+template <int P, int Q, bool EMIT>
+__global__ void __launch_bounds__(512)
+cgather8_kernel(const float2* __restrict__ in, const float2* __restrict__ W, float2* __restrict__ out,
+                float2* __restrict__ dwt, int64_t B, int k, int nsplit, int perm_b)
+{
+    constexpr int MT = Q / 16;
+    constexpr int NCHUNK = P / 16;
+    constexpr int PLANE = Gather8<P>::kPlane;
+    extern __shared__ __align__(16) float2 gat8[];
+
+    int bid = (int)blockIdx.x;
+    const int split = bid % nsplit;
+    bid /= nsplit;
+    const int mt = bid % MT, oct = bid / MT;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int g = 8 * oct + w;
+    const int col = lane & 31, kh = lane >> 5, e = lane & 1;
+    const int64_t ntiles = (B + kRT - 1) / kRT;
+    const int64_t ld_in = (int64_t)k * P;
+    const bool pb = perm_b != 0;
+
+    float A0[P / 2], A1[P / 2];
+    {
+        const int jw = 16 * mt + (col >> 1);
+        const float2* Wg = W + (size_t)g * P * Q;
+#pragma unroll
+        for (int u = 0; u < P / 2; ++u) {
+            const float2 wv = Wg[(2 * u + kh) * Q + jw];
+            A0[u] = e ? -wv.y : wv.x;
+            A1[u] = e ? wv.x : wv.y;
+        }
+    }
+    u32x4 pre[4];
+    auto fetch = [&](int64_t rt, int ch) {
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+            const int idx = tid + n * 512, c2 = idx & 3, ll = (idx >> 2) & 15, r = idx >> 6;
+            const int64_t row = rt * kRT + r;
+            pre[n] = row < B ? ldg128(in + row * ld_in + (size_t)(16 * ch + ll) * k + 8 * oct + 2 * c2) : u32x4{0, 0, 0, 0};
+        }
+    };
+    auto to_lds = [&](float2* buf) {
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+            const int idx = tid + n * 512, c2 = idx & 3, ll = (idx >> 2) & 15, r = idx >> 6;
+            buf[(2 * c2) * PLANE + r * 17 + ll] = make_float2(__uint_as_float(pre[n].x), __uint_as_float(pre[n].y));
+            buf[(2 * c2 + 1) * PLANE + r * 17 + ll] = make_float2(__uint_as_float(pre[n].z), __uint_as_float(pre[n].w));
+        }
+    };
+
+    int64_t rt = split;
+    if (rt < ntiles) fetch(rt, 0);
+    int cnt = 0;
+    for (; rt < ntiles; rt += nsplit) {
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+        for (int ch = 0; ch < NCHUNK; ++ch, ++cnt) {
+            float2* buf = gat8 + (cnt & 1) * (8 * PLANE);
+            to_lds(buf);
+            lds_barrier();
+            if (ch + 1 < NCHUNK) fetch(rt, ch + 1);
+            else if (rt + nsplit < ntiles) fetch(rt + nsplit, 0);
+            const float2* mine = buf + w * PLANE;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float2 xv = mine[col * 17 + 2 * u + kh];
+                acc = mfma_f32(A0[ch * 8 + u], xv.x, acc);
+                acc = mfma_f32(A1[ch * 8 + u], xv.y, acc);
+            }
+            if constexpr (EMIT) {
+                if (mt == 0) {
+                    float2* dst = dwt + (((size_t)rt * k + g) * P + 16 * ch) * kRT;
+#pragma unroll
+                    for (int n = 0; n < 8; ++n) dst[(2 * n + kh) * kRT + col] = mine[col * 17 + 2 * n + kh];
+                }
+            }
+        }
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int j = 16 * mt + 4 * q4 + 2 * kh + h;
+                const int d = mid_src(g * Q + j, k, Q, pb);
+                const int blk = d / Q, idx = d - blk * Q;
+                out[(((size_t)rt * k + blk) * Q + idx) * kRT + col] = make_float2(acc[4 * q4 + 2 * h], acc[4 * q4 + 2 * h + 1]);
+            }
+    }
+}
+
 // part[z][g][ma][nb] = sum over the rows b of the tiles z, z + Z, ... of  A[b][g][ma] * conj(Bv[b][g][nb])
 // A: dW (kInGather from dy) or dY1 (kInT);  Bv: U (kInT) or x (kInNat).  M = 2*MA real rows (re and im of the
 // result), N = NB columns, K = (row, component): with B'[(b,t)][nb] = component t of Bv[b][nb],
@@ -402,6 +596,44 @@ int launch_stage(const Problem& pb, const void* in, const void* W, void* out, hi
     return hip_status(hipGetLastError());
 }
 
+// the eight-blocks-per-workgroup stages: about two workgroups per CU, a multiple of 8 per (block octet, M tile)
+int splits8_for(const Problem& pb, int mtiles)
+{
+    int64_t n = (512 + (pb.k / 8) * mtiles - 1) / ((pb.k / 8) * mtiles);
+    n = (n + 7) / 8 * 8;
+    const int64_t t = tiles_of(pb);
+    if (n > t) n = t;
+    return (int)(n < 1 ? 1 : n);
+}
+
+template <int M>
+int launch_scatter8(const Problem& pb, const void* T, const void* W, void* out, hipStream_t st)
+{
+    const int nsplit = splits8_for(pb, M / 16);
+    const int64_t grid = (int64_t)(pb.k / 8) * (M / 16) * nsplit;
+    if (grid > 0x7fffffffLL) return -2;
+    auto kern = cscatter8_kernel<M, M>;
+    constexpr size_t lds = Scatter8<M, M>::kLds;
+    if (allow_dynamic_lds((const void*)kern, lds) != hipSuccess) return -4;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), lds, st, (const float2*)T, (const float2*)W,
+                       (float2*)out, pb.B, pb.k, nsplit);
+    return hip_status(hipGetLastError());
+}
+
+template <int M, bool EMIT>
+int launch_gather8(const Problem& pb, const void* in, const void* W, void* out, void* dwt, hipStream_t st)
+{
+    const int nsplit = splits8_for(pb, M / 16);
+    const int64_t grid = (int64_t)(pb.k / 8) * (M / 16) * nsplit;
+    if (grid > 0x7fffffffLL) return -2;
+    auto kern = cgather8_kernel<M, M, EMIT>;
+    constexpr size_t lds = Gather8<M>::kLds;
+    if (allow_dynamic_lds((const void*)kern, lds) != hipSuccess) return -4;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), lds, st, (const float2*)in, (const float2*)W,
+                       (float2*)out, (float2*)dwt, pb.B, pb.k, nsplit, pb.perm_b() ? 1 : 0);
+    return hip_status(hipGetLastError());
+}
+
 template <int M, int AMODE, int BMODE>
 int launch_wgrad(const Problem& pb, const void* A, const void* Bv, void* out, void* part, int64_t lda, int64_t ldb,
                  hipStream_t st)
@@ -427,13 +659,15 @@ int run_fwd(const Problem& pb, const void* x, const void* R, const void* L, void
 {
     int rc = launch_stage<M, kInNat, kOutTFwd, false>(pb, x, R, ws, st);
     if (rc) return rc;
+    if (pb.k % 8 == 0) return launch_scatter8<M>(pb, ws, L, y, st);
     return launch_stage<M, kInT, kOutScatter, false>(pb, ws, L, y, st);
 }
 
 template <int M>
 int run_fwd_h(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
 {
-    int rc = launch_stage<M, kInGather, kOutTBwd, true>(pb, x, L, ws, st);
+    int rc = pb.k % 8 == 0 ? launch_gather8<M, false>(pb, x, L, ws, nullptr, st)
+                           : launch_stage<M, kInGather, kOutTBwd, true>(pb, x, L, ws, st);
     if (rc) return rc;
     return launch_stage<M, kInT, kOutNat, true>(pb, ws, R, y, st);
 }
@@ -445,14 +679,17 @@ int run_bwd(const Problem& pb, const void* dy, const void* x, const void* R, con
     char* w = (char*)ws;
     void* Ut = w;
     void* dY1t = w + t_bytes(pb);
-    void* part = w + 2 * t_bytes(pb);
+    void* dWt = w + 2 * t_bytes(pb);
+    void* part = w + 3 * t_bytes(pb);
+    const bool eight = pb.k % 8 == 0;
     int rc = launch_stage<M, kInNat, kOutTFwd, false>(pb, x, R, Ut, st);
     if (rc) return rc;
-    rc = launch_stage<M, kInGather, kOutTBwd, true>(pb, dy, L, dY1t, st);
+    rc = eight ? launch_gather8<M, true>(pb, dy, L, dY1t, dWt, st) : launch_stage<M, kInGather, kOutTBwd, true>(pb, dy, L, dY1t, st);
     if (rc) return rc;
     rc = launch_stage<M, kInT, kOutNat, true>(pb, dY1t, R, dx, st);
     if (rc) return rc;
-    rc = launch_wgrad<M, kInGather, kInT>(pb, dy, Ut, dL, part, pb.n_out(), 0, st);
+    rc = eight ? launch_wgrad<M, kInT, kInT>(pb, dWt, Ut, dL, part, 0, 0, st)
+               : launch_wgrad<M, kInGather, kInT>(pb, dy, Ut, dL, part, pb.n_out(), 0, st);
     if (rc) return rc;
     return launch_wgrad<M, kInT, kInNat>(pb, dY1t, x, dR, part, 0, pb.n_in, st);
 }
@@ -469,7 +706,7 @@ size_t complex_mfma_workspace(const Problem& pb, int pass)
 {
     if (pass != 1) return t_bytes(pb);
     const int Z = wgrad_chunks(pb);
-    return 2 * t_bytes(pb) + (Z > 1 ? align_up((size_t)Z * pb.n_L() * sizeof(float2), 256) : 0);
+    return 3 * t_bytes(pb) + (Z > 1 ? align_up((size_t)Z * pb.n_L() * sizeof(float2), 256) : 0);
 }
 
 int complex_mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
