@@ -233,6 +233,10 @@ fwd_frag_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ RF1
     const int64_t b0 = (int64_t)blockIdx.x * C::BM;
 
     u32x4 wr2[C::RW2][C::NLT];  // stage-2 weight ring
+    // Short batches leave CUs without a row tile: gridDim.y workgroups then share a row tile, each taking a
+    // contiguous share of the stage-2 passes (its own columns of y, its own part of the L stream) after computing
+    // stage 1 for itself.
+    const int ps_lo = (int)blockIdx.y * C::PASSES / (int)gridDim.y, ps_hi = ((int)blockIdx.y + 1) * C::PASSES / (int)gridDim.y;
     // ------------------------------------------------------------- stage 1 ----
     {
         const int kk = wave;
@@ -242,7 +246,7 @@ fwd_frag_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ RF1
         {
             // the first stage-2 weights travel while the workgroup exchanges Y1 through LDS
             const uint16_t* wbase[C::NLT];
-            stage2_wbase<C>(LF2, wave * C::UPW, lane, wbase);
+            stage2_wbase<C>(LF2, (ps_lo * 4 + wave) * C::UPW, lane, wbase);
 #pragma unroll
             for (int d = 0; d < C::RW2 - 1; ++d) stage2_issue_w<C>(wbase, wr2, d / C::KS, d % C::KS, d);
         }
@@ -264,13 +268,13 @@ fwd_frag_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ RF1
 
     // ------------------------------------------------------------- stage 2 ----
     {
-        const int u0 = wave * C::UPW;
+        const int u0 = (ps_lo * 4 + wave) * C::UPW;
         if (u0 & 1)
             stage2_pass<C, true, true, BIAS, ACT>(LF2, lds, bias, y, y_pre, b0, B, u0, lane, wr2);
         else
             stage2_pass<C, false, true, BIAS, ACT>(LF2, lds, bias, y, y_pre, b0, B, u0, lane, wr2);
     }
-    for (int ps = 1; ps < C::PASSES; ++ps) {
+    for (int ps = ps_lo + 1; ps < ps_hi; ++ps) {
         const int u0 = (ps * 4 + wave) * C::UPW;
         if (u0 & 1)
             stage2_pass<C, true, false, BIAS, ACT>(LF2, lds, bias, y, y_pre, b0, B, u0, lane, wr2);
@@ -327,6 +331,8 @@ fwd_frag8_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ RF
     const int64_t b0 = (int64_t)blockIdx.x * C::BM;
 
     u32x4 wr2[C::RW2][C::NLT];  // stage-2 weight ring
+    // gridDim.y workgroups share a row tile, each with a contiguous share of the stage-2 passes (see fwd_frag_kernel)
+    const int ps_lo = (int)blockIdx.y * C::PASSES / (int)gridDim.y, ps_hi = ((int)blockIdx.y + 1) * C::PASSES / (int)gridDim.y;
     {
         const int kk = wave & 3, half = wave >> 2;
         f32x16 acc[C::QH * C::NB];
@@ -337,7 +343,7 @@ fwd_frag8_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ RF
         __builtin_amdgcn_sched_barrier(0);
         {
             const uint16_t* wbase[C::NLT];
-            stage2_wbase<C>(LF2, wave * C::UPW, lane, wbase);
+            stage2_wbase<C>(LF2, (ps_lo * C::NW + wave) * C::UPW, lane, wbase);
 #pragma unroll
             for (int d = 0; d < C::RW2 - 1; ++d) stage2_issue_w<C>(wbase, wr2, d / C::KS, d % C::KS, d);
         }
@@ -355,9 +361,16 @@ fwd_frag8_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ RF
                 }
     }
     __syncthreads();
-    stage2_pass<C, false, true, BIAS, ACT>(LF2, lds, bias, y, y_pre, b0, B, wave * C::UPW, lane, wr2);
-    for (int ps = 1; ps < C::PASSES; ++ps)
+    stage2_pass<C, false, true, BIAS, ACT>(LF2, lds, bias, y, y_pre, b0, B, (ps_lo * C::NW + wave) * C::UPW, lane, wr2);
+    for (int ps = ps_lo + 1; ps < ps_hi; ++ps)
         stage2_pass<C, false, false, BIAS, ACT>(LF2, lds, bias, y, y_pre, b0, B, (ps * C::NW + wave) * C::UPW, lane, wr2);
+}
+
+// Workgroups per row tile: as many as keep the launch within one workgroup per CU, at most one per stage-2 pass.
+inline int pass_split(int64_t row_tiles, int passes)
+{
+    const int64_t room = row_tiles > 0 ? 256 / row_tiles : 1;
+    return (int)(room < 1 ? 1 : (room > passes ? passes : room));
 }
 
 template <typename C>
@@ -368,7 +381,7 @@ int launch8(const Problem& pb, const void* x, const uint16_t* RF1, const uint16_
     if (e != hipSuccess) return -4;
     const int64_t grid = (pb.B + C::BM - 1) / C::BM;
     if (grid > 0x7fffffffLL) return -2;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), C::LDS_BYTES, st, (const uint16_t*)x, RF1, LF2,
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid, (unsigned)pass_split(grid, C::PASSES)), dim3(512), C::LDS_BYTES, st, (const uint16_t*)x, RF1, LF2,
                        (const uint16_t*)pb.bias, (uint16_t*)y, (uint16_t*)pb.y_pre, pb.B);
     return hip_status(hipGetLastError());
 }
@@ -382,7 +395,7 @@ int launch(const Problem& pb, const void* x, const uint16_t* RF1, const uint16_t
     if (e != hipSuccess) return -4;
     const int64_t grid = (pb.B + C::BM - 1) / C::BM;
     if (grid > 0x7fffffffLL) return -2;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), C::LDS_BYTES, st, (const uint16_t*)x, RF1, LF2,
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid, (unsigned)pass_split(grid, C::PASSES)), dim3(256), C::LDS_BYTES, st, (const uint16_t*)x, RF1, LF2,
                        (const uint16_t*)pb.bias, (uint16_t*)y, (uint16_t*)pb.y_pre, pb.B);
     return hip_status(hipGetLastError());
 }
