@@ -94,7 +94,10 @@ int monarch_fwd_ex(const void* x, const void* R, const void* L, void* y,
  * Section 3.3 steps 1-3).  For the shapes that have a packed-weight kernel (bf16: k = 4 wide
  * blocks, and the square m = 64 case) the call first re-lays R and L in matrix-core fragment order into `workspace` and then
  * runs the fused forward on the packed copies, which removes the weights from the LDS traffic of
- * the kernel; every other shape runs exactly as monarch_fwd_ex and ignores the workspace.
+ * the kernel.  fp32 layers with square blocks p = q = s of 32 or 64 (any k) run on the fp32 matrix cores, one
+ * launch per block-diagonal factor with the vector between the factors kept in `workspace` (the packed flag
+ * means nothing to them and is ignored).  Every other shape runs exactly as monarch_fwd_ex and ignores the
+ * workspace.
  * `workspace` (device memory, 256-byte aligned, caller-owned) must hold at least
  * monarch_fwd_workspace_bytes(...) bytes when that is non-zero.  Without MONARCH_FLAG_WS_PACKED its
  * contents on entry are ignored; on exit it holds the packed copies of R and L, and a later call with
@@ -255,7 +258,7 @@ int monarch_fwd_t(const void* x, const void* R, const void* L, void* y,
                   monarch_dtype dtype, void* stream,
                   void* workspace, size_t workspace_bytes, unsigned flags);
 
-/* Bytes of device scratch monarch_fwd_t needs (0 for the shape-generic kernels and the fp32 m = 16
+/* Bytes of device scratch monarch_fwd_t needs (0 for the shape-generic SIMT kernels and the fp32 m = 16
  * kernel, and on invalid arguments). */
 size_t monarch_fwd_t_workspace_bytes(int64_t batch, int n_in, int k, int q, int s,
                                      monarch_dtype dtype, unsigned flags);

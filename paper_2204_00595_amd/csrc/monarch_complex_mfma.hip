@@ -59,7 +59,9 @@ __device__ __forceinline__ void lds_store_c2(float2* dst, u32x4 v)  // two compl
 //   kInGather: src[row][i*k + g]                          LDS [row][P + 1]
 //   kInT:      src tile (rt, g): [i][32 rows], contiguous LDS [i][32]
 // Rows past the end of the batch read as zeros (kInT: the producer wrote zeros there).
-template <int P, int NTHR, int IN>
+// REAL (real fp32 data, two consecutive values per float2): only the gathering form differs, whose pieces are then
+// single floats, src[row][i'*k + g] for the 2P real indices i' of the block.
+template <int P, int NTHR, int IN, bool REAL = false>
 struct ActTile {
     static constexpr int kPieces = (IN == kInGather) ? kRT * P / NTHR : kRT * P / 2 / NTHR;  // per thread
     static constexpr int kStride = (IN == kInT) ? kRT : P + 1;
@@ -75,6 +77,15 @@ struct ActTile {
             for (int n = 0; n < kPieces; ++n) {
                 const int idx = tid + n * NTHR, row = idx / (P / 2), c2 = idx - row * (P / 2);
                 v[n] = (row0 + row < B) ? ldg128(src + (row0 + row) * ld + (size_t)g * P + 2 * c2) : u32x4{0, 0, 0, 0};
+            }
+        } else if constexpr (IN == kInGather && REAL) {
+            const float* srcf = reinterpret_cast<const float*>(src);
+#pragma unroll
+            for (int n = 0; n < 2 * kPieces; ++n) {
+                const int idx = tid + n * NTHR, row = idx / (2 * P), i = idx - row * (2 * P);
+                float t = 0.f;
+                if (row0 + row < B) t = srcf[(row0 + row) * (2 * ld) + (size_t)i * k + g];
+                v[n / 4][n % 4] = __float_as_uint(t);
             }
         } else if constexpr (IN == kInGather) {
 #pragma unroll
@@ -99,6 +110,13 @@ struct ActTile {
             for (int n = 0; n < kPieces; ++n) {
                 const int idx = tid + n * NTHR, row = idx / (P / 2), c2 = idx - row * (P / 2);
                 lds_store_c2(act + row * kStride + 2 * c2, v[n]);
+            }
+        } else if constexpr (IN == kInGather && REAL) {
+            float* actf = reinterpret_cast<float*>(act);
+#pragma unroll
+            for (int n = 0; n < 2 * kPieces; ++n) {
+                const int idx = tid + n * NTHR, row = idx / (2 * P), i = idx - row * (2 * P);
+                actf[row * (2 * kStride) + i] = __uint_as_float(v[n / 4][n % 4]);
             }
         } else if constexpr (IN == kInGather) {
 #pragma unroll
@@ -129,13 +147,17 @@ struct ActTile {
 //   kOutScatter: out[row][n*k + g]
 // Grid: k * nsplit workgroups of Q/16 waves; workgroup (g, split) takes the row tiles split, split + nsplit, ...
 // (split = blockIdx % nsplit with nsplit a multiple of 8 keeps the blocks of one row range on one XCD).
-template <int P, int Q, int IN, int OUT, bool CONJT>
+// REAL: real fp32 data and weights, block sizes 2P -> 2Q.  A float2 is then two consecutive values of a row, which
+// is what one pair of K = 2 steps contracts, so the activation side is unchanged; the weights are used as they are
+// (CONJT: transposed), and since the permutations move single values, the two values of a result pair go to their
+// places separately (in the tiled workspace, to the pair slot [index / 2][row][index % 2] of the consumer's block).
+template <int P, int Q, int IN, int OUT, bool CONJT, bool REAL = false>
 __global__ void __launch_bounds__(4 * Q)
 cstage_kernel(const float2* __restrict__ in, const float2* __restrict__ W, float2* __restrict__ out, int64_t B,
               int k, int nsplit, int perm_b)
 {
     constexpr int NTHR = 4 * Q;
-    using Tile = ActTile<P, NTHR, IN>;
+    using Tile = ActTile<P, NTHR, IN, REAL>;
     constexpr int OSTR = Q + 1;
     __shared__ __align__(16) float2 act[2][Tile::kLen];
     __shared__ __align__(16) float2 ost[OUT == kOutNat ? kRT * OSTR : 1];
@@ -150,15 +172,32 @@ cstage_kernel(const float2* __restrict__ in, const float2* __restrict__ W, float
     // this lane's rows of the expanded weights: real row 2*jw + e, for the inputs i = 2u + kh
     float A0[P / 2], A1[P / 2];
     {
-        const int jw = 16 * mt + (col >> 1);
-        const float2* Wg = W + (size_t)g * P * Q;
-        constexpr float sgn = CONJT ? -1.f : 1.f;
+        if constexpr (REAL) {
+            const int nw = 32 * mt + col;  // this lane's output of the block
+            const float* Wf = reinterpret_cast<const float*>(W) + (size_t)g * (4 * P * Q);
 #pragma unroll
-        for (int u = 0; u < P / 2; ++u) {
-            const int i = 2 * u + kh;
-            const float2 w = CONJT ? Wg[i * Q + jw] : Wg[jw * P + i];
-            A0[u] = e ? sgn * w.y : w.x;
-            A1[u] = e ? w.x : -sgn * w.y;
+            for (int u = 0; u < P / 2; ++u) {
+                const int i = 2 * u + kh;  // inputs 2i and 2i + 1
+                if constexpr (CONJT) {
+                    A0[u] = Wf[(size_t)(2 * i) * (2 * Q) + nw];
+                    A1[u] = Wf[(size_t)(2 * i + 1) * (2 * Q) + nw];
+                } else {
+                    const float2 w = *reinterpret_cast<const float2*>(Wf + (size_t)nw * (2 * P) + 2 * i);
+                    A0[u] = w.x;
+                    A1[u] = w.y;
+                }
+            }
+        } else {
+            const int jw = 16 * mt + (col >> 1);
+            const float2* Wg = W + (size_t)g * P * Q;
+            constexpr float sgn = CONJT ? -1.f : 1.f;
+#pragma unroll
+            for (int u = 0; u < P / 2; ++u) {
+                const int i = 2 * u + kh;
+                const float2 w = CONJT ? Wg[i * Q + jw] : Wg[jw * P + i];
+                A0[u] = e ? sgn * w.y : w.x;
+                A1[u] = e ? w.x : -sgn * w.y;
+            }
         }
     }
 
@@ -204,7 +243,21 @@ cstage_kernel(const float2* __restrict__ in, const float2* __restrict__ W, float
                 for (int h = 0; h < 2; ++h) {
                     const int j = 16 * mt + 4 * q4 + 2 * kh + h;
                     const float2 v = make_float2(acc[4 * q4 + 2 * h], acc[4 * q4 + 2 * h + 1]);
-                    if constexpr (OUT == kOutScatter) {
+                    if constexpr (REAL) {
+                        float* outf = reinterpret_cast<float*>(out);
+#pragma unroll
+                        for (int t = 0; t < 2; ++t) {
+                            const int n = 2 * j + t;  // output of the block, 0 .. 2Q-1
+                            const float val = t ? v.y : v.x;
+                            if constexpr (OUT == kOutScatter) {
+                                if (row < B) outf[row * (2 * ld_out) + (size_t)n * k + g] = val;
+                            } else {
+                                const int d = (OUT == kOutTFwd) ? mid_dest(g * 2 * Q + n, k, 2 * Q, pb) : mid_src(g * 2 * Q + n, k, 2 * Q, pb);
+                                const int blk = d / (2 * Q), idx = d - blk * (2 * Q);
+                                outf[((((size_t)rt * k + blk) * Q + (idx >> 1)) * kRT + col) * 2 + (idx & 1)] = val;
+                            }
+                        }
+                    } else if constexpr (OUT == kOutScatter) {
                         if (row < B) out[row * ld_out + (size_t)j * k + g] = v;
                     } else {
                         const int d = (OUT == kOutTFwd) ? mid_dest(g * Q + j, k, Q, pb) : mid_src(g * Q + j, k, Q, pb);
@@ -230,7 +283,8 @@ struct Scatter8 {
     static constexpr size_t kLds = 2 * (size_t)kRT * kRow * sizeof(float2);
 };
 
-template <int P, int Q>
+// REAL (see cstage_kernel): the pieces of y are the eight blocks' values of one (row, output), 32 bytes.
+template <int P, int Q, bool REAL = false>
 __global__ void __launch_bounds__(512)
 cscatter8_kernel(const float2* __restrict__ T, const float2* __restrict__ W, float2* __restrict__ out, int64_t B, int k,
                  int nsplit)
@@ -250,7 +304,15 @@ cscatter8_kernel(const float2* __restrict__ T, const float2* __restrict__ W, flo
     const int64_t ld_out = (int64_t)k * Q;
 
     float A0[P / 2], A1[P / 2];
-    {
+    if constexpr (REAL) {
+        const float* Wf = reinterpret_cast<const float*>(W) + (size_t)g * (4 * P * Q) + (size_t)(32 * mt + col) * (2 * P);
+#pragma unroll
+        for (int u = 0; u < P / 2; ++u) {
+            const float2 wv = *reinterpret_cast<const float2*>(Wf + 2 * (2 * u + kh));
+            A0[u] = wv.x;
+            A1[u] = wv.y;
+        }
+    } else {
         const int jw = 16 * mt + (col >> 1);
         const float2* Wg = W + (size_t)g * P * Q;
 #pragma unroll
@@ -276,19 +338,37 @@ cscatter8_kernel(const float2* __restrict__ T, const float2* __restrict__ W, flo
             acc = mfma_f32(A1[u], buf[u].y, acc);
         }
         float2* o = ost8 + (it & 1) * (kRT * OROW);
+        if constexpr (REAL) {
+            // [row][32 outputs][8 blocks] floats in the same space; acc[r] is output 8*(r/4) + 4*kh + r%4 of the M tile
+            float* of = reinterpret_cast<float*>(o);
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4)
+            for (int r = 0; r < 16; ++r) of[col * (2 * OROW) + (8 * (r / 4) + 4 * kh + (r % 4)) * 8 + w] = acc[r];
+            lds_barrier();
+            float* outf = reinterpret_cast<float*>(out);
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
-                o[col * OROW + (4 * q4 + 2 * kh + h) * 8 + w] = make_float2(acc[4 * q4 + 2 * h], acc[4 * q4 + 2 * h + 1]);
-        lds_barrier();
+            for (int n = 0; n < 4; ++n) {  // 32 rows x 32 outputs x 2 halves of the eight blocks, 16 bytes each
+                const int idx = tid + n * 512, part = idx & 1, nl = (idx >> 1) & 31, r = idx >> 6;
+                const float2 v0 = *reinterpret_cast<const float2*>(of + r * (2 * OROW) + nl * 8 + 4 * part);
+                const float2 v1 = *reinterpret_cast<const float2*>(of + r * (2 * OROW) + nl * 8 + 4 * part + 2);
+                if (rt * kRT + r < B)
+                    *reinterpret_cast<f32x4*>(outf + (rt * kRT + r) * (2 * ld_out) + (size_t)(32 * mt + nl) * k + 8 * oct + 4 * part) =
+                        f32x4{v0.x, v0.y, v1.x, v1.y};
+            }
+        } else {
 #pragma unroll
-        for (int n = 0; n < 4; ++n) {  // 32 rows x 16 outputs x 4 pairs of blocks, 16 bytes each
-            const int idx = tid + n * 512, c2 = idx & 3, ll = (idx >> 2) & 15, r = idx >> 6;
-            const float2 v0 = o[r * OROW + ll * 8 + 2 * c2], v1 = o[r * OROW + ll * 8 + 2 * c2 + 1];
-            if (rt * kRT + r < B)
-                *reinterpret_cast<f32x4*>(out + (rt * kRT + r) * ld_out + (size_t)(16 * mt + ll) * k + 8 * oct + 2 * c2) =
-                    f32x4{v0.x, v0.y, v1.x, v1.y};
+            for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    o[col * OROW + (4 * q4 + 2 * kh + h) * 8 + w] = make_float2(acc[4 * q4 + 2 * h], acc[4 * q4 + 2 * h + 1]);
+            lds_barrier();
+#pragma unroll
+            for (int n = 0; n < 4; ++n) {  // 32 rows x 16 outputs x 4 pairs of blocks, 16 bytes each
+                const int idx = tid + n * 512, c2 = idx & 3, ll = (idx >> 2) & 15, r = idx >> 6;
+                const float2 v0 = o[r * OROW + ll * 8 + 2 * c2], v1 = o[r * OROW + ll * 8 + 2 * c2 + 1];
+                if (rt * kRT + r < B)
+                    *reinterpret_cast<f32x4*>(out + (rt * kRT + r) * ld_out + (size_t)(16 * mt + ll) * k + 8 * oct + 2 * c2) =
+                        f32x4{v0.x, v0.y, v1.x, v1.y};
+            }
         }
     };
 
@@ -319,7 +399,9 @@ struct Gather8 {
     static constexpr size_t kLds = 2 * (size_t)8 * kPlane * sizeof(float2);
 };
 
-template <int P, int Q, bool EMIT>
+// REAL (see cstage_kernel): the pieces of dy are 32 bytes (eight blocks' values of one (row, input)), a chunk is
+// 32 inputs = 16 pairs, and the weights are L[c]^T as stored.
+template <int P, int Q, bool EMIT, bool REAL = false>
 __global__ void __launch_bounds__(512)
 cgather8_kernel(const float2* __restrict__ in, const float2* __restrict__ W, float2* __restrict__ out,
                 float2* __restrict__ dwt, int64_t B, int k, int nsplit, int perm_b)
@@ -341,7 +423,14 @@ cgather8_kernel(const float2* __restrict__ in, const float2* __restrict__ W, flo
     const bool pb = perm_b != 0;
 
     float A0[P / 2], A1[P / 2];
-    {
+    if constexpr (REAL) {
+        const float* Wf = reinterpret_cast<const float*>(W) + (size_t)g * (4 * P * Q) + 32 * mt + col;
+#pragma unroll
+        for (int u = 0; u < P / 2; ++u) {
+            A0[u] = Wf[(size_t)(2 * (2 * u + kh)) * (2 * Q)];
+            A1[u] = Wf[(size_t)(2 * (2 * u + kh) + 1) * (2 * Q)];
+        }
+    } else {
         const int jw = 16 * mt + (col >> 1);
         const float2* Wg = W + (size_t)g * P * Q;
 #pragma unroll
@@ -355,17 +444,32 @@ cgather8_kernel(const float2* __restrict__ in, const float2* __restrict__ W, flo
     auto fetch = [&](int64_t rt, int ch) {
 #pragma unroll
         for (int n = 0; n < 4; ++n) {
-            const int idx = tid + n * 512, c2 = idx & 3, ll = (idx >> 2) & 15, r = idx >> 6;
-            const int64_t row = rt * kRT + r;
-            pre[n] = row < B ? ldg128(in + row * ld_in + (size_t)(16 * ch + ll) * k + 8 * oct + 2 * c2) : u32x4{0, 0, 0, 0};
+            const int idx = tid + n * 512;
+            const int64_t row = rt * kRT + (idx >> 6);
+            if constexpr (REAL) {
+                const int part = idx & 1, il = (idx >> 1) & 31;
+                const float* srcf = reinterpret_cast<const float*>(in);
+                pre[n] = row < B ? ldg128(srcf + row * (2 * ld_in) + (size_t)(32 * ch + il) * k + 8 * oct + 4 * part) : u32x4{0, 0, 0, 0};
+            } else {
+                const int c2 = idx & 3, ll = (idx >> 2) & 15;
+                pre[n] = row < B ? ldg128(in + row * ld_in + (size_t)(16 * ch + ll) * k + 8 * oct + 2 * c2) : u32x4{0, 0, 0, 0};
+            }
         }
     };
     auto to_lds = [&](float2* buf) {
 #pragma unroll
         for (int n = 0; n < 4; ++n) {
-            const int idx = tid + n * 512, c2 = idx & 3, ll = (idx >> 2) & 15, r = idx >> 6;
-            buf[(2 * c2) * PLANE + r * 17 + ll] = make_float2(__uint_as_float(pre[n].x), __uint_as_float(pre[n].y));
-            buf[(2 * c2 + 1) * PLANE + r * 17 + ll] = make_float2(__uint_as_float(pre[n].z), __uint_as_float(pre[n].w));
+            const int idx = tid + n * 512, r = idx >> 6;
+            if constexpr (REAL) {
+                const int part = idx & 1, il = (idx >> 1) & 31;
+                float* bf = reinterpret_cast<float*>(buf);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) bf[(4 * part + t) * (2 * PLANE) + r * 34 + il] = __uint_as_float(pre[n][t]);
+            } else {
+                const int c2 = idx & 3, ll = (idx >> 2) & 15;
+                buf[(2 * c2) * PLANE + r * 17 + ll] = make_float2(__uint_as_float(pre[n].x), __uint_as_float(pre[n].y));
+                buf[(2 * c2 + 1) * PLANE + r * 17 + ll] = make_float2(__uint_as_float(pre[n].z), __uint_as_float(pre[n].w));
+            }
         }
     };
 
@@ -398,15 +502,26 @@ cgather8_kernel(const float2* __restrict__ in, const float2* __restrict__ W, flo
                 }
             }
         }
+        if constexpr (REAL) {
+            float* outf = reinterpret_cast<float*>(out);
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4)
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int j = 16 * mt + 4 * q4 + 2 * kh + h;
-                const int d = mid_src(g * Q + j, k, Q, pb);
-                const int blk = d / Q, idx = d - blk * Q;
-                out[(((size_t)rt * k + blk) * Q + idx) * kRT + col] = make_float2(acc[4 * q4 + 2 * h], acc[4 * q4 + 2 * h + 1]);
+            for (int r = 0; r < 16; ++r) {
+                const int n = 32 * mt + 8 * (r / 4) + 4 * kh + (r % 4);
+                const int d = mid_src(g * 2 * Q + n, k, 2 * Q, pb);
+                const int blk = d / (2 * Q), idx = d - blk * (2 * Q);
+                outf[((((size_t)rt * k + blk) * Q + (idx >> 1)) * kRT + col) * 2 + (idx & 1)] = acc[r];
             }
+        } else {
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int j = 16 * mt + 4 * q4 + 2 * kh + h;
+                    const int d = mid_src(g * Q + j, k, Q, pb);
+                    const int blk = d / Q, idx = d - blk * Q;
+                    out[(((size_t)rt * k + blk) * Q + idx) * kRT + col] = make_float2(acc[4 * q4 + 2 * h], acc[4 * q4 + 2 * h + 1]);
+                }
+        }
     }
 }
 
@@ -416,7 +531,7 @@ cgather8_kernel(const float2* __restrict__ in, const float2* __restrict__ W, flo
 //   A'[2ma][(b,0)] = ar,  A'[2ma][(b,1)] = ai,  A'[2ma+1][(b,0)] = ai,  A'[2ma+1][(b,1)] = -ar.
 // Wave w owns the 16 values ma = 16w .. 16w+15 and every column.  LDS holds each operand so that the lanes of a
 // wave read consecutive addresses for one row: [row][len] for row-major sources, [idx][32 + 1] for the tiled ones.
-template <int LEN, int NTHR, int MODE>
+template <int LEN, int NTHR, int MODE, bool REAL = false>
 struct WgTile {
     static constexpr int kPieces = (MODE == kInGather) ? kRT * LEN / NTHR : kRT * LEN / 2 / NTHR;
     static constexpr int kLen = (MODE == kInT) ? LEN * (kRT + 1) : kRT * LEN;
@@ -430,6 +545,15 @@ struct WgTile {
             for (int n = 0; n < kPieces; ++n) {
                 const int idx = tid + n * NTHR, row = idx / (LEN / 2), c2 = idx - row * (LEN / 2);
                 v[n] = (row0 + row < B) ? ldg128(src + (row0 + row) * ld + (size_t)g * LEN + 2 * c2) : u32x4{0, 0, 0, 0};
+            }
+        } else if constexpr (MODE == kInGather && REAL) {
+            const float* srcf = reinterpret_cast<const float*>(src);
+#pragma unroll
+            for (int n = 0; n < 2 * kPieces; ++n) {
+                const int idx = tid + n * NTHR, row = idx / (2 * LEN), i = idx - row * (2 * LEN);
+                float t = 0.f;
+                if (row0 + row < B) t = srcf[(row0 + row) * (2 * ld) + (size_t)i * k + g];
+                v[n / 4][n % 4] = __float_as_uint(t);
             }
         } else if constexpr (MODE == kInGather) {
 #pragma unroll
@@ -452,6 +576,10 @@ struct WgTile {
         if constexpr (MODE == kInNat) {
 #pragma unroll
             for (int n = 0; n < kPieces; ++n) *reinterpret_cast<u32x4*>(t + 2 * (tid + n * NTHR)) = v[n];
+        } else if constexpr (MODE == kInGather && REAL) {
+            float* tf = reinterpret_cast<float*>(t);
+#pragma unroll
+            for (int n = 0; n < 2 * kPieces; ++n) tf[tid + n * NTHR] = __uint_as_float(v[n / 4][n % 4]);
         } else if constexpr (MODE == kInGather) {
 #pragma unroll
             for (int n = 0; n < kPieces; ++n) {
@@ -474,15 +602,17 @@ struct WgTile {
     }
 };
 
-template <int MA, int NB, int AMODE, int BMODE>
+// REAL: real fp32 operands, two consecutive values per float2: out[g][ma'][nb'] = sum_b A[b][g][ma'] * Bv[b][g][nb'] for
+// the 2*MA x 2*NB real indices; a K = 2 step contracts two batch rows, each lane picking its component of the pair.
+template <int MA, int NB, int AMODE, int BMODE, bool REAL = false>
 __global__ void __launch_bounds__(4 * MA)
 cwgrad_kernel(const float2* __restrict__ A, const float2* __restrict__ Bv, float2* __restrict__ part, int64_t B, int k,
               int Z, int64_t lda, int64_t ldb)
 {
     constexpr int NTHR = 4 * MA;
-    constexpr int NTN = (NB + 31) / 32;
-    using TA = WgTile<MA, NTHR, AMODE>;
-    using TB = WgTile<NB, NTHR, BMODE>;
+    constexpr int NTN = REAL ? (2 * NB + 31) / 32 : (NB + 31) / 32;
+    using TA = WgTile<MA, NTHR, AMODE, REAL>;
+    using TB = WgTile<NB, NTHR, BMODE, REAL>;
     extern __shared__ __align__(16) float2 wg_lds[];  // two buffers of each operand: 2 * (TA::kLen + TB::kLen) values
 
     const int g = (int)blockIdx.x / Z, z = (int)blockIdx.x - g * Z;
@@ -518,27 +648,47 @@ cwgrad_kernel(const float2* __restrict__ A, const float2* __restrict__ Bv, float
         for (int u = 0; u < kRT / 2; ++u) {
             const int b = 2 * u + kh;
             const float2 av = TA::at(ta, ma, b);
-            const float a0 = e ? av.y : av.x;
-            const float a1 = e ? -av.x : av.y;
+            if constexpr (REAL) {
+                const float as = e ? av.y : av.x;
 #pragma unroll
-            for (int nt = 0; nt < NTN; ++nt) {
-                const int nb = 32 * nt + col;
-                const float2 bv = (NB % 32 == 0 || nb < NB) ? TB::at(tb, nb, b) : make_float2(0.f, 0.f);
-                acc[nt] = mfma_f32(a0, bv.x, acc[nt]);
-                acc[nt] = mfma_f32(a1, bv.y, acc[nt]);
+                for (int nt = 0; nt < NTN; ++nt) {
+                    const int nbp = 16 * nt + (col >> 1);  // the pair holding real column 32*nt + col
+                    const float2 bv = (NB % 16 == 0 || nbp < NB) ? TB::at(tb, nbp, b) : make_float2(0.f, 0.f);
+                    acc[nt] = mfma_f32(as, e ? bv.y : bv.x, acc[nt]);
+                }
+            } else {
+                const float a0 = e ? av.y : av.x;
+                const float a1 = e ? -av.x : av.y;
+#pragma unroll
+                for (int nt = 0; nt < NTN; ++nt) {
+                    const int nb = 32 * nt + col;
+                    const float2 bv = (NB % 32 == 0 || nb < NB) ? TB::at(tb, nb, b) : make_float2(0.f, 0.f);
+                    acc[nt] = mfma_f32(a0, bv.x, acc[nt]);
+                    acc[nt] = mfma_f32(a1, bv.y, acc[nt]);
+                }
             }
         }
     }
-    float2* o = part + ((size_t)z * k + g) * (MA * NB);
+    if constexpr (REAL) {
+        // acc[nt][r]: row 32*mt + 8*(r/4) + 4*kh + r%4, column 32*nt + col of the (2*MA) x (2*NB) block
+        float* o = reinterpret_cast<float*>(part) + ((size_t)z * k + g) * (4 * MA * NB);
 #pragma unroll
-    for (int nt = 0; nt < NTN; ++nt) {
-        const int nb = 32 * nt + col;
-        if (NB % 32 != 0 && nb >= NB) continue;
+        for (int nt = 0; nt < NTN; ++nt)
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4)
+            for (int r = 0; r < 16; ++r)
+                o[(size_t)(32 * mt + 8 * (r / 4) + 4 * kh + (r % 4)) * (2 * NB) + 32 * nt + col] = acc[nt][r];
+    } else {
+        float2* o = part + ((size_t)z * k + g) * (MA * NB);
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
-                o[(16 * mt + 4 * q4 + 2 * kh + h) * NB + nb] = make_float2(acc[nt][4 * q4 + 2 * h], acc[nt][4 * q4 + 2 * h + 1]);
+        for (int nt = 0; nt < NTN; ++nt) {
+            const int nb = 32 * nt + col;
+            if (NB % 32 != 0 && nb >= NB) continue;
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    o[(16 * mt + 4 * q4 + 2 * kh + h) * NB + nb] = make_float2(acc[nt][4 * q4 + 2 * h], acc[nt][4 * q4 + 2 * h + 1]);
+        }
     }
 }
 
@@ -585,13 +735,13 @@ int wgrad_chunks(const Problem& pb)
     return (int)(z < 1 ? 1 : z);
 }
 
-template <int M, int IN, int OUT, bool CONJT>
+template <int M, int IN, int OUT, bool CONJT, bool REAL = false>
 int launch_stage(const Problem& pb, const void* in, const void* W, void* out, hipStream_t st)
 {
     const int nsplit = splits_for(pb, M / 16, 4096);
     const int64_t grid = (int64_t)pb.k * nsplit;
     if (grid > 0x7fffffffLL) return -2;
-    hipLaunchKernelGGL((cstage_kernel<M, M, IN, OUT, CONJT>), dim3((unsigned)grid), dim3(4 * M), 0, st, (const float2*)in,
+    hipLaunchKernelGGL((cstage_kernel<M, M, IN, OUT, CONJT, REAL>), dim3((unsigned)grid), dim3(4 * M), 0, st, (const float2*)in,
                        (const float2*)W, (float2*)out, pb.B, pb.k, nsplit, pb.perm_b() ? 1 : 0);
     return hip_status(hipGetLastError());
 }
@@ -606,13 +756,13 @@ int splits8_for(const Problem& pb, int mtiles)
     return (int)(n < 1 ? 1 : n);
 }
 
-template <int M>
+template <int M, bool REAL = false>
 int launch_scatter8(const Problem& pb, const void* T, const void* W, void* out, hipStream_t st)
 {
     const int nsplit = splits8_for(pb, M / 16);
     const int64_t grid = (int64_t)(pb.k / 8) * (M / 16) * nsplit;
     if (grid > 0x7fffffffLL) return -2;
-    auto kern = cscatter8_kernel<M, M>;
+    auto kern = cscatter8_kernel<M, M, REAL>;
     constexpr size_t lds = Scatter8<M, M>::kLds;
     if (allow_dynamic_lds((const void*)kern, lds) != hipSuccess) return -4;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), lds, st, (const float2*)T, (const float2*)W,
@@ -620,13 +770,13 @@ int launch_scatter8(const Problem& pb, const void* T, const void* W, void* out, 
     return hip_status(hipGetLastError());
 }
 
-template <int M, bool EMIT>
+template <int M, bool EMIT, bool REAL = false>
 int launch_gather8(const Problem& pb, const void* in, const void* W, void* out, void* dwt, hipStream_t st)
 {
     const int nsplit = splits8_for(pb, M / 16);
     const int64_t grid = (int64_t)(pb.k / 8) * (M / 16) * nsplit;
     if (grid > 0x7fffffffLL) return -2;
-    auto kern = cgather8_kernel<M, M, EMIT>;
+    auto kern = cgather8_kernel<M, M, EMIT, REAL>;
     constexpr size_t lds = Gather8<M>::kLds;
     if (allow_dynamic_lds((const void*)kern, lds) != hipSuccess) return -4;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), lds, st, (const float2*)in, (const float2*)W,
@@ -634,7 +784,8 @@ int launch_gather8(const Problem& pb, const void* in, const void* W, void* out, 
     return hip_status(hipGetLastError());
 }
 
-template <int M, int AMODE, int BMODE>
+// lda, ldb: row lengths of row-major operands in float2 units
+template <int M, int AMODE, int BMODE, bool REAL = false>
 int launch_wgrad(const Problem& pb, const void* A, const void* Bv, void* out, void* part, int64_t lda, int64_t ldb,
                  hipStream_t st)
 {
@@ -642,14 +793,14 @@ int launch_wgrad(const Problem& pb, const void* A, const void* Bv, void* out, vo
     const int64_t grid = (int64_t)pb.k * Z;
     if (grid > 0x7fffffffLL) return -2;
     float2* dst = Z == 1 ? (float2*)out : (float2*)part;
-    auto kern = cwgrad_kernel<M, M, AMODE, BMODE>;
-    const size_t lds = 2 * (size_t)(WgTile<M, 4 * M, AMODE>::kLen + WgTile<M, 4 * M, BMODE>::kLen) * sizeof(float2);
+    auto kern = cwgrad_kernel<M, M, AMODE, BMODE, REAL>;
+    const size_t lds = 2 * (size_t)(WgTile<M, 4 * M, AMODE, REAL>::kLen + WgTile<M, 4 * M, BMODE, REAL>::kLen) * sizeof(float2);
     if (allow_dynamic_lds((const void*)kern, lds) != hipSuccess) return -4;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(4 * M), lds, st, (const float2*)A, (const float2*)Bv, dst, pb.B,
                        pb.k, Z, lda, ldb);
     int rc = hip_status(hipGetLastError());
     if (rc || Z == 1) return rc;
-    const size_t n4 = (size_t)pb.k * M * M / 2;
+    const size_t n4 = (size_t)pb.k * M * M / (REAL ? 1 : 2);  // float4s of one gradient: (2M)^2 floats, or M^2 complex values, per block
     hipLaunchKernelGGL(csum_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, (const f32x4*)part, (f32x4*)out, n4, Z);
     return hip_status(hipGetLastError());
 }
@@ -694,7 +845,84 @@ int run_bwd(const Problem& pb, const void* dy, const void* x, const void* R, con
     return launch_wgrad<M, kInT, kInNat>(pb, dY1t, x, dR, part, 0, pb.n_in, st);
 }
 
+// ---- real fp32 layers with square blocks of 32 or 64 on the same kernels (REAL): M = block size / 2 ----
+size_t rt_bytes(const Problem& pb) { return align_up((size_t)tiles_of(pb) * kRT * pb.kq() * sizeof(float), 256); }
+
+template <int M>
+int run_real_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
+{
+    int rc = launch_stage<M, kInNat, kOutTFwd, false, true>(pb, x, R, ws, st);
+    if (rc) return rc;
+    if (pb.k % 8 == 0) return launch_scatter8<M, true>(pb, ws, L, y, st);
+    return launch_stage<M, kInT, kOutScatter, false, true>(pb, ws, L, y, st);
+}
+
+template <int M>
+int run_real_fwd_t(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
+{
+    int rc = pb.k % 8 == 0 ? launch_gather8<M, false, true>(pb, x, L, ws, nullptr, st)
+                           : launch_stage<M, kInGather, kOutTBwd, true, true>(pb, x, L, ws, st);
+    if (rc) return rc;
+    return launch_stage<M, kInT, kOutNat, true, true>(pb, ws, R, y, st);
+}
+
+template <int M>
+int run_real_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
+                 void* dL, void* ws, hipStream_t st)
+{
+    char* w = (char*)ws;
+    void* Ut = w;
+    void* dY1t = w + rt_bytes(pb);
+    void* dWt = w + 2 * rt_bytes(pb);
+    void* part = w + 3 * rt_bytes(pb);
+    const bool eight = pb.k % 8 == 0;
+    int rc = launch_stage<M, kInNat, kOutTFwd, false, true>(pb, x, R, Ut, st);
+    if (rc) return rc;
+    rc = eight ? launch_gather8<M, true, true>(pb, dy, L, dY1t, dWt, st)
+               : launch_stage<M, kInGather, kOutTBwd, true, true>(pb, dy, L, dY1t, st);
+    if (rc) return rc;
+    rc = launch_stage<M, kInT, kOutNat, true, true>(pb, dY1t, R, dx, st);
+    if (rc) return rc;
+    rc = eight ? launch_wgrad<M, kInT, kInT, true>(pb, dWt, Ut, dL, part, 0, 0, st)
+               : launch_wgrad<M, kInGather, kInT, true>(pb, dy, Ut, dL, part, pb.n_out() / 2, 0, st);
+    if (rc) return rc;
+    return launch_wgrad<M, kInT, kInNat, true>(pb, dY1t, x, dR, part, 0, pb.n_in / 2, st);
+}
+
 }  // namespace
+
+bool real32_mfma_supported(const Problem& pb)
+{
+    return pb.dtype == 0 && pb.p == pb.q && pb.q == pb.s && (pb.p == 32 || pb.p == 64);
+}
+
+// pass: 0 forward, 1 backward, 2 transposed multiply
+size_t real32_mfma_workspace(const Problem& pb, int pass)
+{
+    if (pass != 1) return rt_bytes(pb);
+    const int Z = wgrad_chunks(pb);
+    return 3 * rt_bytes(pb) + (Z > 1 ? align_up((size_t)Z * pb.n_L() * sizeof(float), 256) : 0);
+}
+
+int real32_mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
+{
+    return pb.p == 32 ? run_real_fwd<16>(pb, x, R, L, y, ws, st) : run_real_fwd<32>(pb, x, R, L, y, ws, st);
+}
+
+int real32_mfma_fwd_t(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
+{
+    return pb.p == 32 ? run_real_fwd_t<16>(pb, x, R, L, y, ws, st) : run_real_fwd_t<32>(pb, x, R, L, y, ws, st);
+}
+
+int real32_mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
+                    void* dL, void* ws, hipStream_t st)
+{
+    if (pb.B == 0) {
+        const int rc = launch_fill_zero_f32((float*)dR, pb.n_R(), st);
+        return rc ? rc : launch_fill_zero_f32((float*)dL, pb.n_L(), st);
+    }
+    return pb.p == 32 ? run_real_bwd<16>(pb, dy, x, R, L, dx, dR, dL, ws, st) : run_real_bwd<32>(pb, dy, x, R, L, dx, dR, dL, ws, st);
+}
 
 bool complex_mfma_supported(const Problem& pb)
 {

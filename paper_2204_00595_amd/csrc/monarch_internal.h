@@ -78,6 +78,14 @@ int complex_bwd(const Problem& pb, const void* dy, const void* x, const void* R,
 bool complex_fwd_h_supported(const Problem& pb);
 // matrix-core complex kernels (monarch_complex_mfma.hip): square blocks p = q = s in {16, 32, 64}; every call needs
 // complex_mfma_workspace(pb, pass) bytes (pass: 0 forward, 1 backward, 2 conjugate-transpose forward); B > 0
+// the same kernels on real fp32 layers with square blocks p = q = s in {32, 64} (any k, both readings); every call
+// takes real32_mfma_workspace(pb, pass) bytes (pass: 0 forward, 1 backward, 2 transposed multiply)
+bool real32_mfma_supported(const Problem& pb);
+size_t real32_mfma_workspace(const Problem& pb, int pass);
+int real32_mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);
+int real32_mfma_fwd_t(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);
+int real32_mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
+                    void* dL, void* ws, hipStream_t st);
 bool complex_mfma_supported(const Problem& pb);
 size_t complex_mfma_workspace(const Problem& pb, int pass);
 int complex_mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st);

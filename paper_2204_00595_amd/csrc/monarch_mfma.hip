@@ -24,30 +24,33 @@ int mfma_fwd(const Problem& pb, const void* x, const void* R, const void* L, voi
     return -2;
 }
 
-bool mfma_fwd_ws_supported(const Problem& pb) { return fwd_frag_supported(pb) || sq64_supported(pb); }
+bool mfma_fwd_ws_supported(const Problem& pb) { return fwd_frag_supported(pb) || sq64_supported(pb) || real32_mfma_supported(pb); }
 size_t mfma_fwd_ws_workspace(const Problem& pb)
 {
     if (fwd_frag_supported(pb)) return fwd_frag_workspace(pb);
     if (sq64_supported(pb)) return fwd_sq64_workspace(pb);
+    if (real32_mfma_supported(pb)) return real32_mfma_workspace(pb, 0);
     return 0;
 }
 const char* mfma_fwd_ws_name(const Problem& pb)
 {
     if (fwd_frag_supported(pb)) return "mfma_fwd_frag_bf16";
     if (sq64_supported(pb)) return "mfma_fwd_sq64_packed_bf16";
+    if (real32_mfma_supported(pb)) return "mfma_fwd_stages_f32";
     return "unsupported";
 }
 int mfma_fwd_ws(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
 {
     if (fwd_frag_supported(pb)) return fwd_frag(pb, x, R, L, y, ws, st);
     if (sq64_supported(pb)) return fwd_sq64_ws(pb, x, R, L, y, ws, st);
+    if (real32_mfma_supported(pb)) return real32_mfma_fwd(pb, x, R, L, y, ws, st);
     return -2;
 }
 
 // Transposed multiply y = x M: the dx stages of the three backward families on their own.
 bool mfma_fwd_t_supported(const Problem& pb)
 {
-    return bwd_wide_supported(pb) || sq64_supported(pb) || sq16_supported(pb) || tiled_fwd_t_supported(pb);
+    return bwd_wide_supported(pb) || sq64_supported(pb) || sq16_supported(pb) || tiled_fwd_t_supported(pb) || real32_mfma_supported(pb);
 }
 size_t mfma_fwd_t_workspace(const Problem& pb)
 {
@@ -55,6 +58,7 @@ size_t mfma_fwd_t_workspace(const Problem& pb)
     if (sq64_supported(pb)) return fwd_t_sq64_workspace(pb);
     if (sq16_supported(pb)) return 0;
     if (tiled_fwd_t_supported(pb)) return tiled_fwd_t_workspace(pb);
+    if (real32_mfma_supported(pb)) return real32_mfma_workspace(pb, 2);
     return 0;
 }
 const char* mfma_fwd_t_name(const Problem& pb)
@@ -63,6 +67,7 @@ const char* mfma_fwd_t_name(const Problem& pb)
     if (sq64_supported(pb)) return "mfma_fwd_t_sq64_bf16";
     if (sq16_supported(pb)) return "mfma_fwd_t_sq16_f32";
     if (tiled_fwd_t_supported(pb)) return "mfma_fwd_t_tiled_bf16";
+    if (real32_mfma_supported(pb)) return "mfma_fwd_t_stages_f32";
     return "unsupported";
 }
 int mfma_fwd_t(const Problem& pb, const void* x, const void* R, const void* L, void* y, void* ws, hipStream_t st)
@@ -71,6 +76,7 @@ int mfma_fwd_t(const Problem& pb, const void* x, const void* R, const void* L, v
     if (sq64_supported(pb)) return fwd_t_sq64(pb, x, R, L, y, ws, st);
     if (sq16_supported(pb)) return fwd_t_sq16(pb, x, R, L, y, st);
     if (tiled_fwd_t_supported(pb)) return tiled_fwd_t(pb, x, R, L, y, ws, st);
+    if (real32_mfma_supported(pb)) return real32_mfma_fwd_t(pb, x, R, L, y, ws, st);
     return -2;
 }
 
@@ -92,7 +98,7 @@ bool mfma_bwd_fuses_act(const Problem& pb) { return bwd_wide_supported(pb) && !p
 
 bool mfma_bwd_supported(const Problem& pb)
 {
-    return bwd_wide_supported(pb) || bwd_sq64_supported(pb) || sq16_supported(pb) || tiled_bwd_supported(pb);
+    return bwd_wide_supported(pb) || bwd_sq64_supported(pb) || sq16_supported(pb) || tiled_bwd_supported(pb) || real32_mfma_supported(pb);
 }
 size_t mfma_bwd_workspace(const Problem& pb)
 {
@@ -100,6 +106,7 @@ size_t mfma_bwd_workspace(const Problem& pb)
     if (bwd_sq64_supported(pb)) return bwd_sq64_workspace(pb);
     if (sq16_supported(pb)) return bwd_sq16_workspace(pb);
     if (tiled_bwd_supported(pb)) return tiled_bwd_workspace(pb);
+    if (real32_mfma_supported(pb)) return real32_mfma_workspace(pb, 1);
     return 0;
 }
 const char* mfma_bwd_name(const Problem& pb)
@@ -108,6 +115,7 @@ const char* mfma_bwd_name(const Problem& pb)
     if (bwd_sq64_supported(pb)) return "mfma_bwd_sq64_bf16";
     if (sq16_supported(pb)) return "mfma_bwd_sq16_f32";
     if (tiled_bwd_supported(pb)) return "mfma_bwd_tiled_bf16";
+    if (real32_mfma_supported(pb)) return "mfma_bwd_stages_f32";
     return "unsupported";
 }
 int mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, const void* L, void* dx, void* dR,
@@ -117,6 +125,7 @@ int mfma_bwd(const Problem& pb, const void* dy, const void* x, const void* R, co
     if (bwd_sq64_supported(pb)) return bwd_sq64(pb, dy, x, R, L, dx, dR, dL, ws, st);
     if (sq16_supported(pb)) return bwd_sq16(pb, dy, x, R, L, dx, dR, dL, ws, st);
     if (tiled_bwd_supported(pb)) return tiled_bwd(pb, dy, x, R, L, dx, dR, dL, ws, st);
+    if (real32_mfma_supported(pb)) return real32_mfma_bwd(pb, dy, x, R, L, dx, dR, dL, ws, st);
     return -2;
 }
 

@@ -206,6 +206,34 @@ def test_shape_generic_matrix_core_kernels(B, case, reading):
             ["dx", "dR32", "dL32", "dbias32"])
 
 
+# fp32 layers with square blocks of 32 or 64: every call that takes a workspace runs on the fp32 matrix-core stage
+# kernels (any block count, both readings); batches long enough that a workgroup takes several 32-row tiles, the last
+# one ragged.  name, B, k, m
+F32_STAGE_CASES = [("f32_m32", 100, 32, 32), ("f32_k3_m64", 67, 3, 64), ("f32_k5_m32", 333, 5, 32), ("f32_m64", 40, 64, 64),
+                   ("f32_k8_m32_long", 8219, 8, 32), ("f32_k2_m64_long", 16421, 2, 64)]
+
+
+@pytest.mark.parametrize("reading", ["A", "B"])
+@pytest.mark.parametrize("case", F32_STAGE_CASES, ids=lambda c: c[0])
+def test_fp32_square_blocks_on_matrix_cores(B, case, reading):
+    name, Bn, k, m = case
+    sh = synth.Shape(name, "f32", Bn, k, m, m, m, config=300 + parity_util.stable_seed(name))
+    flags = B.MONARCH_FLAG_PERM_B if reading == "B" else 0
+    rd = oracle.READING_B if reading == "B" else oracle.READING_A
+    names = [B.monarch_kernel_name(ps, sh.n_in, k, m, m, 0, flags) for ps in (1, 2, 3)]
+    assert names == ["mfma_bwd_stages_f32", "mfma_fwd_stages_f32", "mfma_fwd_t_stages_f32"], names
+    x, R, L, dy = synth.make_inputs(sh)
+    compare(sh, [run_fwd(B, sh, x, R, L, flags, ws=True)], [oracle.fwd(x, R, L, rd)], ["y_ws"])
+    compare(sh, run_bwd(B, sh, dy, x, R, L, flags), oracle.bwd(dy, x, R, L, rd), ["dx", "dR", "dL"])
+    compare(sh, [run_fwd_t(B, sh, dy, R, L, flags)], [oracle.fwd_t(dy, R, L, rd)], ["xM"])
+    compare(sh, run_bwd_bias(B, sh, dy, x, R, L, flags), oracle.bwd_bias(dy, x, R, L, rd), ["dx", "dR", "dL", "dbias"])
+    for u, v in zip(run_bwd(B, sh, dy, x, R, L, flags), run_bwd(B, sh, dy, x, R, L, flags)):   # fixed summation order
+        assert np.array_equal(u, v)
+    # empty batch: zero gradients
+    e = run_bwd(B, sh, dy[:0], x[:0], R, L, flags)
+    assert e[0].shape == (0, sh.n_in) and not e[1].any() and not e[2].any()
+
+
 def test_shape_generic_kernels_on_random_shapes(B):
     """Seeded random shapes with blocks that are multiples of 32 and any block count (odd ones too): forward,
     backward and transposed multiply must run on the shape-generic matrix-core kernels and match the oracle."""
