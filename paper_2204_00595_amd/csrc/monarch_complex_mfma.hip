@@ -23,6 +23,10 @@
 // Weight gradients: dL[c] = dW[c]^T conj(U[c]),  dR[kk] = dY1[kk]^T conj(x[kk]),  contracted over the batch by the
 // same MFMA (K = two rows x one component); a workgroup owns one block and a share of the row tiles, the shares'
 // partial results go to the workspace and are summed in a fixed order (no atomics).
+//
+// Real fp32 layers with square blocks of 32 or 64 run on the same kernels (template flag REAL): a float2 is then two
+// consecutive values of a row, the activation side is unchanged, the weights are taken as stored and the
+// permutations move single values (see cstage_kernel).
 #include "monarch_internal.h"
 #include "monarch_device.h"
 #include "monarch_mfma_common.h"
