@@ -395,6 +395,19 @@ def measure_extras(ly: Layer, calls: int):
         ex["c64_fwd_tflops"] = cflops / (ex["c64_fwd_ms"] * 1e-3) / 1e12
         ex["c64_bwd_tflops"] = 2.5 * cflops / (ex["c64_bwd_ms"] * 1e-3) / 1e12
         del cws, cdx
+        if sh.p in (32, 64):
+            # the same layer in fp32 (fp32 matrix-core stage kernels), whole batch
+            fx = torch.randn((sh.B, sh.n_in), dtype=torch.float32, device=dev, generator=torch.Generator(device=dev).manual_seed(8))
+            fR, fL = Rd.float(), Ld.float()
+            fy, fdx, fdR, fdL = torch.empty_like(fx), torch.empty_like(fx), torch.empty_like(fR), torch.empty_like(fL)
+            fwn = binding.monarch_fwd_workspace_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, 0, 0)
+            bwn = binding.monarch_bwd_workspace_bytes(sh.B, sh.n_in, sh.k, sh.q, sh.s, 0, 0)
+            fws2 = torch.empty(max(fwn, bwn, 256), dtype=torch.uint8, device=dev)
+            ex["f32_fwd_ms"] = timed_runs(lambda i: binding.monarch_fwd_ws(fx, fR, fL, fy, workspace=fws2), 10, 2)[0]
+            ex["f32_bwd_ms"] = timed_runs(lambda i: binding.monarch_bwd(fy, fx, fR, fL, fdx, fdR, fdL, workspace=fws2), 10, 2)[0]
+            ex["f32_fwd_kernel"] = binding.monarch_kernel_name(2, sh.n_in, sh.k, sh.q, sh.s, 0)
+            ex["f32_fwd_tflops"] = sh.fwd_flops() / (ex["f32_fwd_ms"] * 1e-3) / 1e12
+            del fx, fy, fdx, fws2
         # Algorithm 1 on a dense Gaussian n x n matrix: one Jacobi SVD per slice
         Adense = torch.from_numpy(synth.quantize(synth.normal(4343, (sh.n_in, sh.n_in)), sh.dtype)).to(dev).to(dt)
         Rp, Lp = torch.empty_like(Rd), torch.empty_like(Ld)
