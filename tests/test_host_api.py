@@ -93,6 +93,15 @@ def test_forward_with_workspace_rejects_bad_arguments_without_a_gpu(binding):
     assert call(flags=binding.MONARCH_FLAG_WGRAD_F32) == binding.MONARCH_ERR_INVALID
     assert call(flags=binding.MONARCH_FLAG_WS_PACKED) == binding.MONARCH_OK
     assert call(flags=binding.MONARCH_FLAG_WS_PACKED, ws=None) == binding.MONARCH_ERR_WORKSPACE
+    # fp32 layers with square blocks of 32 / 64: the vector between the factors goes through the workspace, in whole 32-row tiles
+    fneed = binding.monarch_fwd_workspace_bytes(33, 3 * 64, 3, 64, 64, 0)
+    assert fneed == 2 * 32 * 3 * 64 * 4
+    assert binding.monarch_fwd_t_workspace_bytes(33, 3 * 64, 3, 64, 64, 0, 0) == fneed
+    assert binding.monarch_bwd_workspace_bytes(33, 3 * 64, 3, 64, 64, 0, 0) >= 3 * fneed
+    assert binding.monarch_fwd_workspace_bytes(33, 3 * 64, 3, 64, 64, 0, binding.MONARCH_FLAG_GENERIC) == 0
+    assert call(ws_bytes=fneed - 1, batch=33, n_in=192, k=3, q=64, s=64, dtype=0) == binding.MONARCH_ERR_WORKSPACE
+    assert call(ws=None, ws_bytes=0, batch=33, n_in=192, k=3, q=64, s=64, dtype=0) == binding.MONARCH_ERR_WORKSPACE
+    assert call(ws_bytes=fneed, batch=0, n_in=192, k=3, q=64, s=64, dtype=0) == binding.MONARCH_OK
     # shapes without a packed-weight kernel behave as monarch_fwd_ex and need no workspace
     assert call(ws=None, ws_bytes=0, n_in=6, k=2, q=4, s=2, dtype=0) == binding.MONARCH_OK
     assert call(ws=None, ws_bytes=0, flags=binding.MONARCH_FLAG_GENERIC) == binding.MONARCH_OK
@@ -398,6 +407,8 @@ def test_kernel_name_reports_dispatch(binding):
     assert binding.monarch_kernel_name(3, 6, 2, 4, 2, 0) == "generic_fwd_t"
     assert binding.monarch_kernel_name(2, 768, 4, 192, 192, 1) == "mfma_fwd_frag_bf16"
     assert binding.monarch_kernel_name(2, 4096, 64, 64, 64, 1) == "mfma_fwd_sq64_packed_bf16"
+    assert [binding.monarch_kernel_name(ps, 5 * 32, 5, 32, 32, 0, binding.MONARCH_FLAG_PERM_B) for ps in (0, 1, 2, 3)] == \
+        ["generic_fwd", "mfma_bwd_stages_f32", "mfma_fwd_stages_f32", "mfma_fwd_t_stages_f32"]
     assert binding.monarch_kernel_name(2, 6, 2, 4, 2, 0) == "generic_fwd"   # no packed-weight kernel: same as pass 0
     assert binding.monarch_kernel_name(0, 6, 2, 4, 2, 0) == "generic_fwd"
     assert binding.monarch_kernel_name(1, 6, 2, 4, 2, 0) == "generic_bwd"
