@@ -33,6 +33,15 @@ constexpr size_t kMaxLdsBytes = 160 * 1024;
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Forward kernels of the k = 4 layer shapes: workgroups that share one 64-row tile when a short batch leaves CUs
+// without a tile of their own -- as many as keep the launch within one workgroup per CU (256 CUs), at most one
+// per stage-2 pass.
+static inline int pass_split(int64_t row_tiles, int passes)
+{
+    const int64_t room = row_tiles > 0 ? 256 / row_tiles : 1;
+    return (int)(room < 1 ? 1 : (room > passes ? passes : room));
+}
+
 // ---- shape-generic SIMT kernels (any k, p, q, s; both permutation readings) ----
 bool generic_fwd_supported(const Problem& pb);
 bool generic_bwd_supported(const Problem& pb);

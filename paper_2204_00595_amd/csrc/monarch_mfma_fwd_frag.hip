@@ -366,13 +366,6 @@ fwd_frag8_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ RF
         stage2_pass<C, false, false, BIAS, ACT>(LF2, lds, bias, y, y_pre, b0, B, (ps * C::NW + wave) * C::UPW, lane, wr2);
 }
 
-// Workgroups per row tile: as many as keep the launch within one workgroup per CU, at most one per stage-2 pass.
-inline int pass_split(int64_t row_tiles, int passes)
-{
-    const int64_t room = row_tiles > 0 ? 256 / row_tiles : 1;
-    return (int)(room < 1 ? 1 : (room > passes ? passes : room));
-}
-
 template <typename C>
 int launch8(const Problem& pb, const void* x, const uint16_t* RF1, const uint16_t* LF2, void* y, hipStream_t st)
 {

@@ -457,7 +457,10 @@ fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
     // ------------------------------------------------------------- stage 2 ----
     {
         uint16_t* stg = lds + C::LDS_Y1 / 2 + (size_t)wave * (C::STG2 / 2);
-        for (int ps = 0; ps < C::PASSES; ++ps) {
+        // short batches: gridDim.y workgroups share a row tile, each with a contiguous share of the stage-2 passes
+        // (its own columns of y and part of L) after computing stage 1 for itself
+        const int ps_lo = (int)blockIdx.y * C::PASSES / (int)gridDim.y, ps_hi = ((int)blockIdx.y + 1) * C::PASSES / (int)gridDim.y;
+        for (int ps = ps_lo; ps < ps_hi; ++ps) {
             const int u0 = (ps * 4 + wave) * C::UPW;
             if constexpr (C::S2_LINES) {
                 if (u0 & 1)
@@ -474,6 +477,7 @@ fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ R,
     }
     // Last, so that nothing in stage 2 queues behind these stores (Y1s is only read after stage 1).
     if constexpr (SAVE) {
+        if (blockIdx.y != 0) return;  // one of the workgroups that share the row tile writes the saved vector
         // Y1s holds, per row and per group of four j, the 16 values [kk][j % 4]; U wants them as [j % 4][kk]
         // (U index 4*j + kk): a 4 x 4 transpose of 16-bit values inside each 32-byte group, then 32
         // contiguous bytes per group and 2*K*Q contiguous bytes per row go out.
@@ -512,8 +516,8 @@ int launch(const Problem& pb, const void* x, const void* R, const void* L, void*
     if (e != hipSuccess) return -4;
     const int64_t grid = (pb.B + C::BM - 1) / C::BM;
     if (grid > 0x7fffffffLL) return -2;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), C::LDS_BYTES, st, (const uint16_t*)x,
-                       (const uint16_t*)R, (const uint16_t*)L, (uint16_t*)y, (uint16_t*)pb.saved, pb.B);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid, (unsigned)pass_split(grid, C::PASSES)), dim3(256), C::LDS_BYTES, st,
+                       (const uint16_t*)x, (const uint16_t*)R, (const uint16_t*)L, (uint16_t*)y, (uint16_t*)pb.saved, pb.B);
     return hip_status(hipGetLastError());
 }
 
