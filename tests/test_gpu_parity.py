@@ -930,6 +930,36 @@ def test_complex_forward_and_backward(B, case, reading):
     assert B.monarch_fwd_h_c64_ws(dyd[:0], Rd, Ld, flags=flags).shape == (0, k * p)
 
 
+def test_stage_kernels_on_random_block_counts(B):
+    """Seeded random block counts (multiples of 8 and not), batches and readings through the matrix-core stage kernels:
+    the complex calls with a workspace for blocks of 16 / 32 / 64 and the fp32 layer calls for blocks of 32 / 64."""
+    from oracle import complex_ref
+    rng = np.random.default_rng(2204005950)
+    for it in range(10):
+        m = int(rng.choice([16, 32, 64]))
+        k = int(rng.integers(1, 41))
+        rows = int(rng.integers(1, 1200))
+        reading = int(rng.integers(0, 2))
+        flags = B.MONARCH_FLAG_PERM_B if reading else 0
+        x, R, L, dy = (cnormal(8600 + 10 * it + 2 * i, shp, std) for i, (shp, std) in enumerate(
+            (((rows, k * m), 1.0), ((k, m, m), m ** -0.5), ((k, m, m), m ** -0.5), ((rows, k * m), 1.0))))
+        xd, Rd, Ld, dyd = cdev(x), cdev(R), cdev(L), cdev(dy)
+        got = [B.monarch_fwd_c64_ws(xd, Rd, Ld, flags=flags), B.monarch_fwd_h_c64_ws(dyd, Rd, Ld, flags=flags)]
+        got += list(B.monarch_bwd_c64_ws(dyd, xd, Rd, Ld, flags=flags))
+        want = [complex_ref.fwd(x, R, L, reading), complex_ref.fwd_h(dy, R, L, reading)] + list(complex_ref.bwd(dy, x, R, L, reading))
+        errs = [float(np.linalg.norm(g.cpu().numpy().astype(np.complex128) - w) / np.linalg.norm(w)) for g, w in zip(got, want)]
+        print("\n  c64 m=%d k=%d rows=%d reading=%d: %s" % (m, k, rows, reading, " ".join("%.1e" % e for e in errs)), flush=True)
+        assert max(errs) <= TOL["f32"], (m, k, rows, reading, errs)
+        if m == 16:
+            continue
+        sh = synth.Shape("stage_rand%d_k%d_m%d_B%d_r%d" % (it, k, m, rows, reading), "f32", rows, k, m, m, m, config=400 + it)
+        rd = oracle.READING_B if reading else oracle.READING_A
+        xr, Rr, Lr, dyr = synth.make_inputs(sh)
+        compare(sh, [run_fwd(B, sh, xr, Rr, Lr, flags, ws=True)], [oracle.fwd(xr, Rr, Lr, rd)], ["y_ws"])
+        compare(sh, run_bwd(B, sh, dyr, xr, Rr, Lr, flags), oracle.bwd(dyr, xr, Rr, Lr, rd), ["dx", "dR", "dL"])
+        compare(sh, [run_fwd_t(B, sh, dyr, Rr, Lr, flags)], [oracle.fwd_t(dyr, Rr, Lr, rd)], ["xM"])
+
+
 @pytest.mark.parametrize("m", [4, 16, 64])
 def test_dft_monarch_times_its_conjugate_transpose_is_n(B, m):
     """F F* = n I on the GPU: monarch_fwd_c64 with the DFT factors, then monarch_fwd_h_c64 with the same factors,
