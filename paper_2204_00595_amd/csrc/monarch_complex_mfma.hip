@@ -274,16 +274,26 @@ cstage_kernel(const float2* __restrict__ in, const float2* __restrict__ W, float
 }
 
 // The two stages that touch the outer permutation (y[b][l*k + c] written, dy read the same way), for k a multiple
-// of 8: eight blocks per workgroup, wave w = block 8*oct + w, every wave the same 16 outputs (one M tile) of its own
-// block, so that the pieces of the permuted side are the eight blocks' values of one (row, l): 64 contiguous bytes
-// instead of 8.  The workgroups that differ only in the M tile read the same activations; they sit on one XCD.
+// of 8: eight blocks per workgroup, wave w = block 8*oct + w, every wave the same MTW M tiles (16 outputs each) of its
+// own block, so that the pieces of the permuted side are the eight blocks' values of one (row, l): 64 contiguous bytes
+// instead of 8.  Workgroups that differ only in their M tiles read the same activations (they sit on one XCD); where
+// that re-reading costs more than the lost occupancy a wave takes two M tiles (measured: the scattering stage at blocks
+// of 64, four M tiles; the gathering stage at blocks of 32).
 //
 // cscatter8_kernel: tiled workspace -> y.  The activations of a wave's block are MFMA operands exactly as they lie
 // in the workspace (lane = row, 512 contiguous bytes per wave load), so they go from global memory to registers
-// directly, one tile ahead of the MFMAs; the results are exchanged through LDS as [row][l][block].
+// directly, ahead of the MFMAs; the results are exchanged through LDS as [row][l][block].
+template <int P>
+constexpr int kMTilesPerWave = P >= 64 ? 2 : 1;
+// the gathering stage has less room (its chunk staging registers): two M tiles per wave would spill at blocks of 64,
+// and only pay at the batch sizes of the real fp32 layers with blocks of 64 (P = 32 pairs)
+template <int P, bool REAL>
+constexpr int kMTilesPerWaveGather = (REAL && P == 32) ? 2 : 1;
+
 template <int P, int Q>
 struct Scatter8 {
-    static constexpr int kRow = 16 * 8 + 1;  // values per row of the exchange buffer
+    static constexpr int MTW = kMTilesPerWave<Q>;
+    static constexpr int kRow = 16 * MTW * 8 + 1;  // values per row of the exchange buffer
     static constexpr size_t kLds = 2 * (size_t)kRT * kRow * sizeof(float2);
 };
 
@@ -293,108 +303,148 @@ __global__ void __launch_bounds__(512)
 cscatter8_kernel(const float2* __restrict__ T, const float2* __restrict__ W, float2* __restrict__ out, int64_t B, int k,
                  int nsplit)
 {
-    constexpr int MT = Q / 16;
+    constexpr int MTW = Scatter8<P, Q>::MTW;
+    constexpr int MTG = Q / 16 / MTW;  // groups of M tiles = workgroups per (block octet, split)
+    constexpr int NCH = MTW == 1 ? 1 : 4;  // pieces a tile's activations are fetched in
+    constexpr int CH = P / 2 / NCH;        // input pairs per piece
     constexpr int OROW = Scatter8<P, Q>::kRow;
     extern __shared__ __align__(16) float2 ost8[];
 
     int bid = (int)blockIdx.x;
     const int split = bid % nsplit;
     bid /= nsplit;
-    const int mt = bid % MT, oct = bid / MT;
+    const int mt0 = (bid % MTG) * MTW, oct = bid / MTG;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int g = 8 * oct + w;
     const int col = lane & 31, kh = lane >> 5, e = lane & 1;
     const int64_t ntiles = (B + kRT - 1) / kRT;
     const int64_t ld_out = (int64_t)k * Q;
 
-    float A0[P / 2], A1[P / 2];
-    if constexpr (REAL) {
-        const float* Wf = reinterpret_cast<const float*>(W) + (size_t)g * (4 * P * Q) + (size_t)(32 * mt + col) * (2 * P);
+    float A0[MTW][P / 2], A1[MTW][P / 2];
 #pragma unroll
-        for (int u = 0; u < P / 2; ++u) {
-            const float2 wv = *reinterpret_cast<const float2*>(Wf + 2 * (2 * u + kh));
-            A0[u] = wv.x;
-            A1[u] = wv.y;
-        }
-    } else {
-        const int jw = 16 * mt + (col >> 1);
-        const float2* Wg = W + (size_t)g * P * Q;
+    for (int m = 0; m < MTW; ++m) {
+        if constexpr (REAL) {
+            const float* Wf = reinterpret_cast<const float*>(W) + (size_t)g * (4 * P * Q) + (size_t)(32 * (mt0 + m) + col) * (2 * P);
 #pragma unroll
-        for (int u = 0; u < P / 2; ++u) {
-            const float2 wv = Wg[jw * P + 2 * u + kh];
-            A0[u] = e ? wv.y : wv.x;
-            A1[u] = e ? wv.x : -wv.y;
+            for (int u = 0; u < P / 2; ++u) {
+                const float2 wv = *reinterpret_cast<const float2*>(Wf + 2 * (2 * u + kh));
+                A0[m][u] = wv.x;
+                A1[m][u] = wv.y;
+            }
+        } else {
+            const int jw = 16 * (mt0 + m) + (col >> 1);
+            const float2* Wg = W + (size_t)g * P * Q;
+#pragma unroll
+            for (int u = 0; u < P / 2; ++u) {
+                const float2 wv = Wg[jw * P + 2 * u + kh];
+                A0[m][u] = e ? wv.y : wv.x;
+                A1[m][u] = e ? wv.x : -wv.y;
+            }
         }
     }
-    auto load = [&](float2 (&buf)[P / 2], int64_t rt) {
-        const float2* src = T + ((size_t)rt * k + g) * (P * kRT) + (size_t)kh * kRT + col;
+    auto load = [&](float2 (&buf)[CH], int64_t rt, int part) {
+        const float2* src = T + ((size_t)rt * k + g) * (P * kRT) + (size_t)(2 * part * CH + kh) * kRT + col;
 #pragma unroll
-        for (int u = 0; u < P / 2; ++u) buf[u] = src[2 * u * kRT];
+        for (int u = 0; u < CH; ++u) buf[u] = src[2 * u * kRT];
     };
-    // the products of one tile, then the exchange through LDS buffer `it & 1` and the 64-byte pieces of y
-    auto tile = [&](const float2 (&buf)[P / 2], int64_t rt, int it) {
-        f32x16 acc;
+    f32x16 acc[MTW];
+    auto zero = [&]() {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        for (int m = 0; m < MTW; ++m)
 #pragma unroll
-        for (int u = 0; u < P / 2; ++u) {
-            acc = mfma_f32(A0[u], buf[u].x, acc);
-            acc = mfma_f32(A1[u], buf[u].y, acc);
-        }
+            for (int r = 0; r < 16; ++r) acc[m][r] = 0.f;
+    };
+    auto mma = [&](const float2 (&buf)[CH], int part) {
+#pragma unroll
+        for (int u = 0; u < CH; ++u)
+#pragma unroll
+            for (int m = 0; m < MTW; ++m) {
+                acc[m] = mfma_f32(A0[m][part * CH + u], buf[u].x, acc[m]);
+                acc[m] = mfma_f32(A1[m][part * CH + u], buf[u].y, acc[m]);
+            }
+    };
+    // the results of one tile: exchange through LDS buffer it & 1 (one barrier per tile), then the 64-byte (REAL:
+    // 32-byte) pieces of y
+    auto emit = [&](int64_t rt, int it) {
         float2* o = ost8 + (it & 1) * (kRT * OROW);
         if constexpr (REAL) {
-            // [row][32 outputs][8 blocks] floats in the same space; acc[r] is output 8*(r/4) + 4*kh + r%4 of the M tile
+            // [row][32 * MTW outputs][8 blocks] floats in the same space; acc[m][r] is output 8*(r/4) + 4*kh + r%4 of M tile m
             float* of = reinterpret_cast<float*>(o);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) of[col * (2 * OROW) + (8 * (r / 4) + 4 * kh + (r % 4)) * 8 + w] = acc[r];
+            for (int m = 0; m < MTW; ++m)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) of[col * (2 * OROW) + (32 * m + 8 * (r / 4) + 4 * kh + (r % 4)) * 8 + w] = acc[m][r];
             lds_barrier();
             float* outf = reinterpret_cast<float*>(out);
 #pragma unroll
-            for (int n = 0; n < 4; ++n) {  // 32 rows x 32 outputs x 2 halves of the eight blocks, 16 bytes each
-                const int idx = tid + n * 512, part = idx & 1, nl = (idx >> 1) & 31, r = idx >> 6;
+            for (int n = 0; n < 4 * MTW; ++n) {  // 32 rows x 32 * MTW outputs x 2 halves of the eight blocks, 16 bytes each
+                const int idx = tid + n * 512, part = idx & 1, nl = (idx >> 1) % (32 * MTW), r = idx / (64 * MTW);
                 const float2 v0 = *reinterpret_cast<const float2*>(of + r * (2 * OROW) + nl * 8 + 4 * part);
                 const float2 v1 = *reinterpret_cast<const float2*>(of + r * (2 * OROW) + nl * 8 + 4 * part + 2);
                 if (rt * kRT + r < B)
-                    *reinterpret_cast<f32x4*>(outf + (rt * kRT + r) * (2 * ld_out) + (size_t)(32 * mt + nl) * k + 8 * oct + 4 * part) =
+                    *reinterpret_cast<f32x4*>(outf + (rt * kRT + r) * (2 * ld_out) + (size_t)(32 * mt0 + nl) * k + 8 * oct + 4 * part) =
                         f32x4{v0.x, v0.y, v1.x, v1.y};
             }
         } else {
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4)
+            for (int m = 0; m < MTW; ++m)
 #pragma unroll
-                for (int h = 0; h < 2; ++h)
-                    o[col * OROW + (4 * q4 + 2 * kh + h) * 8 + w] = make_float2(acc[4 * q4 + 2 * h], acc[4 * q4 + 2 * h + 1]);
+                for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+                        o[col * OROW + (16 * m + 4 * q4 + 2 * kh + h) * 8 + w] = make_float2(acc[m][4 * q4 + 2 * h], acc[m][4 * q4 + 2 * h + 1]);
             lds_barrier();
 #pragma unroll
-            for (int n = 0; n < 4; ++n) {  // 32 rows x 16 outputs x 4 pairs of blocks, 16 bytes each
-                const int idx = tid + n * 512, c2 = idx & 3, ll = (idx >> 2) & 15, r = idx >> 6;
+            for (int n = 0; n < 4 * MTW; ++n) {  // 32 rows x 16 * MTW outputs x 4 pairs of blocks, 16 bytes each
+                const int idx = tid + n * 512, c2 = idx & 3, ll = (idx >> 2) % (16 * MTW), r = idx / (64 * MTW);
                 const float2 v0 = o[r * OROW + ll * 8 + 2 * c2], v1 = o[r * OROW + ll * 8 + 2 * c2 + 1];
                 if (rt * kRT + r < B)
-                    *reinterpret_cast<f32x4*>(out + (rt * kRT + r) * ld_out + (size_t)(16 * mt + ll) * k + 8 * oct + 2 * c2) =
+                    *reinterpret_cast<f32x4*>(out + (rt * kRT + r) * ld_out + (size_t)(16 * mt0 + ll) * k + 8 * oct + 2 * c2) =
                         f32x4{v0.x, v0.y, v1.x, v1.y};
             }
         }
     };
 
-    // two register sets: the tile after the one being multiplied is on its way
-    float2 xa[P / 2], xb[P / 2];
+    // two register sets: the next piece of the activations (a whole tile, or a quarter where the weights of two M
+    // tiles leave less room) is on its way while the current one is multiplied
+    float2 xa[CH], xb[CH];
     int64_t rt = split;
-    if (rt < ntiles) load(xa, rt);
-    for (int it = 0; rt < ntiles; it += 2) {
-        if (rt + nsplit < ntiles) load(xb, rt + nsplit);
-        tile(xa, rt, it);
-        rt += nsplit;
-        if (rt >= ntiles) break;
-        if (rt + nsplit < ntiles) load(xa, rt + nsplit);
-        tile(xb, rt, it + 1);
-        rt += nsplit;
+    if (rt < ntiles) load(xa, rt, 0);
+    if constexpr (NCH == 1) {
+        for (int it = 0; rt < ntiles; it += 2) {
+            if (rt + nsplit < ntiles) load(xb, rt + nsplit, 0);
+            zero();
+            mma(xa, 0);
+            emit(rt, it);
+            rt += nsplit;
+            if (rt >= ntiles) break;
+            if (rt + nsplit < ntiles) load(xa, rt + nsplit, 0);
+            zero();
+            mma(xb, 0);
+            emit(rt, it + 1);
+            rt += nsplit;
+        }
+    } else {
+        for (int it = 0; rt < ntiles; rt += nsplit, ++it) {
+            zero();
+            load(xb, rt, 1);
+            mma(xa, 0);
+            load(xa, rt, 2);
+            mma(xb, 1);
+            load(xb, rt, 3);
+            mma(xa, 2);
+            if (rt + nsplit < ntiles) load(xa, rt + nsplit, 0);
+            mma(xb, 3);
+            emit(rt, it);
+        }
     }
 }
 
 // cgather8_kernel: dy (read through the outer permutation) -> tiled workspace, weights conj(L[c])^T.  The eight
 // blocks' values of 32 rows x 16 inputs come in as 64-byte pieces and are laid out in LDS as one plane per block,
 // [row][16 + 1]; a wave takes its operands from its own plane.  Four (P = 64) such chunks make a tile; the next
-// chunk is fetched into registers while the current one is multiplied.  EMIT: the workgroups of M tile 0 also write
+// chunk is fetched into registers while the current one is multiplied.  A wave takes kMTilesPerWaveGather M tiles (see
+// cscatter8_kernel).  EMIT: the workgroups of M tile 0 also write
 // the chunk to the workspace in the tiled order (dW[row tile][block][l][32 rows]), the operand of the weight-gradient
 // kernel, which then does not have to gather dy again.
 template <int P>
@@ -410,7 +460,8 @@ __global__ void __launch_bounds__(512)
 cgather8_kernel(const float2* __restrict__ in, const float2* __restrict__ W, float2* __restrict__ out,
                 float2* __restrict__ dwt, int64_t B, int k, int nsplit, int perm_b)
 {
-    constexpr int MT = Q / 16;
+    constexpr int MTW = kMTilesPerWaveGather<Q, REAL>;
+    constexpr int MTG = Q / 16 / MTW;
     constexpr int NCHUNK = P / 16;
     constexpr int PLANE = Gather8<P>::kPlane;
     extern __shared__ __align__(16) float2 gat8[];
@@ -418,7 +469,7 @@ cgather8_kernel(const float2* __restrict__ in, const float2* __restrict__ W, flo
     int bid = (int)blockIdx.x;
     const int split = bid % nsplit;
     bid /= nsplit;
-    const int mt = bid % MT, oct = bid / MT;
+    const int mt0 = (bid % MTG) * MTW, oct = bid / MTG;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int g = 8 * oct + w;
     const int col = lane & 31, kh = lane >> 5, e = lane & 1;
@@ -426,22 +477,25 @@ cgather8_kernel(const float2* __restrict__ in, const float2* __restrict__ W, flo
     const int64_t ld_in = (int64_t)k * P;
     const bool pb = perm_b != 0;
 
-    float A0[P / 2], A1[P / 2];
-    if constexpr (REAL) {
-        const float* Wf = reinterpret_cast<const float*>(W) + (size_t)g * (4 * P * Q) + 32 * mt + col;
+    float A0[MTW][P / 2], A1[MTW][P / 2];
 #pragma unroll
-        for (int u = 0; u < P / 2; ++u) {
-            A0[u] = Wf[(size_t)(2 * (2 * u + kh)) * (2 * Q)];
-            A1[u] = Wf[(size_t)(2 * (2 * u + kh) + 1) * (2 * Q)];
-        }
-    } else {
-        const int jw = 16 * mt + (col >> 1);
-        const float2* Wg = W + (size_t)g * P * Q;
+    for (int m = 0; m < MTW; ++m) {
+        if constexpr (REAL) {
+            const float* Wf = reinterpret_cast<const float*>(W) + (size_t)g * (4 * P * Q) + 32 * (mt0 + m) + col;
 #pragma unroll
-        for (int u = 0; u < P / 2; ++u) {
-            const float2 wv = Wg[(2 * u + kh) * Q + jw];
-            A0[u] = e ? -wv.y : wv.x;
-            A1[u] = e ? wv.x : wv.y;
+            for (int u = 0; u < P / 2; ++u) {
+                A0[m][u] = Wf[(size_t)(2 * (2 * u + kh)) * (2 * Q)];
+                A1[m][u] = Wf[(size_t)(2 * (2 * u + kh) + 1) * (2 * Q)];
+            }
+        } else {
+            const int jw = 16 * (mt0 + m) + (col >> 1);
+            const float2* Wg = W + (size_t)g * P * Q;
+#pragma unroll
+            for (int u = 0; u < P / 2; ++u) {
+                const float2 wv = Wg[(2 * u + kh) * Q + jw];
+                A0[m][u] = e ? -wv.y : wv.x;
+                A1[m][u] = e ? wv.x : wv.y;
+            }
         }
     }
     u32x4 pre[4];
@@ -481,9 +535,11 @@ cgather8_kernel(const float2* __restrict__ in, const float2* __restrict__ W, flo
     if (rt < ntiles) fetch(rt, 0);
     int cnt = 0;
     for (; rt < ntiles; rt += nsplit) {
-        f32x16 acc;
+        f32x16 acc[MTW];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        for (int m = 0; m < MTW; ++m)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[m][r] = 0.f;
 #pragma unroll
         for (int ch = 0; ch < NCHUNK; ++ch, ++cnt) {
             float2* buf = gat8 + (cnt & 1) * (8 * PLANE);
@@ -495,36 +551,43 @@ cgather8_kernel(const float2* __restrict__ in, const float2* __restrict__ W, flo
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const float2 xv = mine[col * 17 + 2 * u + kh];
-                acc = mfma_f32(A0[ch * 8 + u], xv.x, acc);
-                acc = mfma_f32(A1[ch * 8 + u], xv.y, acc);
+#pragma unroll
+                for (int m = 0; m < MTW; ++m) {
+                    acc[m] = mfma_f32(A0[m][ch * 8 + u], xv.x, acc[m]);
+                    acc[m] = mfma_f32(A1[m][ch * 8 + u], xv.y, acc[m]);
+                }
             }
             if constexpr (EMIT) {
-                if (mt == 0) {
+                if (mt0 == 0) {
                     float2* dst = dwt + (((size_t)rt * k + g) * P + 16 * ch) * kRT;
 #pragma unroll
                     for (int n = 0; n < 8; ++n) dst[(2 * n + kh) * kRT + col] = mine[col * 17 + 2 * n + kh];
                 }
             }
         }
-        if constexpr (REAL) {
-            float* outf = reinterpret_cast<float*>(out);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int n = 32 * mt + 8 * (r / 4) + 4 * kh + (r % 4);
-                const int d = mid_src(g * 2 * Q + n, k, 2 * Q, pb);
-                const int blk = d / (2 * Q), idx = d - blk * (2 * Q);
-                outf[((((size_t)rt * k + blk) * Q + (idx >> 1)) * kRT + col) * 2 + (idx & 1)] = acc[r];
-            }
-        } else {
+        for (int m = 0; m < MTW; ++m) {
+            if constexpr (REAL) {
+                float* outf = reinterpret_cast<float*>(out);
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int j = 16 * mt + 4 * q4 + 2 * kh + h;
-                    const int d = mid_src(g * Q + j, k, Q, pb);
-                    const int blk = d / Q, idx = d - blk * Q;
-                    out[(((size_t)rt * k + blk) * Q + idx) * kRT + col] = make_float2(acc[4 * q4 + 2 * h], acc[4 * q4 + 2 * h + 1]);
+                for (int r = 0; r < 16; ++r) {
+                    const int n = 32 * (mt0 + m) + 8 * (r / 4) + 4 * kh + (r % 4);
+                    const int d = mid_src(g * 2 * Q + n, k, 2 * Q, pb);
+                    const int blk = d / (2 * Q), idx = d - blk * (2 * Q);
+                    outf[((((size_t)rt * k + blk) * Q + (idx >> 1)) * kRT + col) * 2 + (idx & 1)] = acc[m][r];
                 }
+            } else {
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const int j = 16 * (mt0 + m) + 4 * q4 + 2 * kh + h;
+                        const int d = mid_src(g * Q + j, k, Q, pb);
+                        const int blk = d / Q, idx = d - blk * Q;
+                        out[(((size_t)rt * k + blk) * Q + idx) * kRT + col] =
+                            make_float2(acc[m][4 * q4 + 2 * h], acc[m][4 * q4 + 2 * h + 1]);
+                    }
+            }
         }
     }
 }
@@ -763,8 +826,9 @@ int splits8_for(const Problem& pb, int mtiles)
 template <int M, bool REAL = false>
 int launch_scatter8(const Problem& pb, const void* T, const void* W, void* out, hipStream_t st)
 {
-    const int nsplit = splits8_for(pb, M / 16);
-    const int64_t grid = (int64_t)(pb.k / 8) * (M / 16) * nsplit;
+    constexpr int MTG = M / 16 / Scatter8<M, M>::MTW;
+    const int nsplit = splits8_for(pb, MTG);
+    const int64_t grid = (int64_t)(pb.k / 8) * MTG * nsplit;
     if (grid > 0x7fffffffLL) return -2;
     auto kern = cscatter8_kernel<M, M, REAL>;
     constexpr size_t lds = Scatter8<M, M>::kLds;
@@ -777,8 +841,9 @@ int launch_scatter8(const Problem& pb, const void* T, const void* W, void* out, 
 template <int M, bool EMIT, bool REAL = false>
 int launch_gather8(const Problem& pb, const void* in, const void* W, void* out, void* dwt, hipStream_t st)
 {
-    const int nsplit = splits8_for(pb, M / 16);
-    const int64_t grid = (int64_t)(pb.k / 8) * (M / 16) * nsplit;
+    constexpr int MTG = M / 16 / kMTilesPerWaveGather<M, REAL>;
+    const int nsplit = splits8_for(pb, MTG);
+    const int64_t grid = (int64_t)(pb.k / 8) * MTG * nsplit;
     if (grid > 0x7fffffffLL) return -2;
     auto kern = cgather8_kernel<M, M, EMIT, REAL>;
     constexpr size_t lds = Gather8<M>::kLds;
