@@ -227,6 +227,10 @@ def test_fp32_square_blocks_on_matrix_cores(B, case, reading):
     compare(sh, run_bwd(B, sh, dy, x, R, L, flags), oracle.bwd(dy, x, R, L, rd), ["dx", "dR", "dL"])
     compare(sh, [run_fwd_t(B, sh, dy, R, L, flags)], [oracle.fwd_t(dy, R, L, rd)], ["xM"])
     compare(sh, run_bwd_bias(B, sh, dy, x, R, L, flags), oracle.bwd_bias(dy, x, R, L, rd), ["dx", "dR", "dL", "dbias"])
+    bias = make_bias(sh)   # the layer calls around the multiply: bias and nonlinearity as passes of their own
+    compare(sh, [run_fwd_bias(B, sh, x, R, L, bias, flags)], [oracle.fwd_bias(x, R, L, bias, rd)], ["y_bias"])
+    if reading == "A" and Bn < 1000:
+        gelu_layer_case(B, sh, flags)
     for u, v in zip(run_bwd(B, sh, dy, x, R, L, flags), run_bwd(B, sh, dy, x, R, L, flags)):   # fixed summation order
         assert np.array_equal(u, v)
     # empty batch: zero gradients
