@@ -1063,7 +1063,8 @@ def test_projection_recovers_monarch_matrices_and_handles_zero_slices(B, m):
 
 
 @pytest.mark.parametrize("case", [("k4_192", "bf16", 1000, 4, 192, 192, 192), ("sq_m64", "bf16", 300, 64, 64, 64, 64),
-                                  ("sq_m16", "f32", 64, 16, 16, 16, 16), ("rect_generic", "f32", 50, 3, 4, 5, 7)],
+                                  ("sq_m16", "f32", 64, 16, 16, 16, 16), ("rect_generic", "f32", 50, 3, 4, 5, 7),
+                                  ("f32_stage_k8_m32", "f32", 300, 8, 32, 32, 32)],
                          ids=lambda c: c[0])
 def test_calls_can_be_captured_in_a_graph(B, case):
     """The library allocates nothing, clears memory with kernels only and enqueues everything on the
@@ -1104,6 +1105,36 @@ def test_calls_can_be_captured_in_a_graph(B, case):
             else:
                 assert torch.equal(got, want), (rep, i)
     compare(sh, [host(outs[0]), host(outs[4])], [oracle.fwd_bias(x, R, L, host(bd)), oracle.bwd_bias(dy, x, R, L)[3]], ["y", "dbias"])
+
+
+def test_complex_calls_with_workspace_can_be_captured_in_a_graph(B):
+    """The complex calls with a workspace only enqueue kernels (no clearing by memset, no allocation): forward,
+    conjugate-transpose forward and backward captured in one HIP graph, four replays bit for bit against eager."""
+    rows, k, m = 200, 16, 32
+    x, R, L, dy = (cdev(cnormal(8800 + 2 * i, shp, std)) for i, (shp, std) in enumerate(
+        (((rows, k * m), 1.0), ((k, m, m), m ** -0.5), ((k, m, m), m ** -0.5), ((rows, k * m), 1.0))))
+    ws = torch.empty(B.monarch_c64_workspace_bytes(B.C64_BWD, rows, k * m, k, m, m), dtype=torch.uint8, device="cuda")
+    outs = [torch.empty_like(x), torch.empty_like(x), torch.empty_like(x), torch.empty_like(R), torch.empty_like(L)]
+
+    def step():
+        B.monarch_fwd_c64_ws(x, R, L, outs[0], workspace=ws)
+        B.monarch_fwd_h_c64_ws(dy, R, L, outs[1], workspace=ws)
+        B.monarch_bwd_c64_ws(dy, x, R, L, outs[2], outs[3], outs[4], workspace=ws)
+
+    step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in outs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(4):
+        for t in outs:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (got, want) in enumerate(zip(outs, ref)):
+            assert torch.equal(got, want), (rep, i)
 
 
 @pytest.mark.parametrize("bias", [False, True], ids=["no_bias", "bias"])
