@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmonarch.so")
-SOURCES = ["monarch_api.hip", "monarch_generic.hip", "monarch_mfma.hip", "monarch_mfma_fwd_wide.hip", "monarch_mfma_fwd_frag.hip", "monarch_mfma_tiled.hip", "monarch_project.hip", "monarch_complex.hip", "monarch_complex_mfma.hip", "monarch_act.hip",
+SOURCES = ["monarch_api.hip", "monarch_generic.hip", "monarch_mfma.hip", "monarch_mfma_fwd_wide.hip", "monarch_mfma_fwd_frag.hip", "monarch_mfma_tiled.hip", "monarch_project.hip", "monarch_complex.hip", "monarch_stage_mfma.hip", "monarch_act.hip",
            "monarch_mfma_bwd_wide.hip", "monarch_mfma_y1.hip", "monarch_mfma_wgrad.hip", "monarch_mfma_sq64.hip", "monarch_mfma_sq16.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -85,7 +85,7 @@ int complex_bwd(const Problem& pb, const void* dy, const void* x, const void* R,
                 void* dL, void* ws, hipStream_t st);
 // y = x conj(M) (the conjugate transpose applied to every row): x (B, k*s) -> y (B, k*p)
 bool complex_fwd_h_supported(const Problem& pb);
-// matrix-core complex kernels (monarch_complex_mfma.hip): square blocks p = q = s in {16, 32, 64}; every call needs
+// matrix-core complex kernels (monarch_stage_mfma.hip): square blocks p = q = s in {16, 32, 64}; every call needs
 // complex_mfma_workspace(pb, pass) bytes (pass: 0 forward, 1 backward, 2 conjugate-transpose forward); B > 0
 // the same kernels on real fp32 layers with square blocks p = q = s in {32, 64} (any k, both readings); every call
 // takes real32_mfma_workspace(pb, pass) bytes (pass: 0 forward, 1 backward, 2 transposed multiply)
