@@ -100,6 +100,9 @@ SMALL = [
     # the backward takes one workgroup per 16-row tile up to 1024 tiles and persistent workgroups beyond
     ("sq_m16_1024_tiles", "f32", 16384 - 5, 16, 16, 16, 16),
     ("sq_m16_1025_tiles", "f32", 16384 + 3, 16, 16, 16, 16),
+    # ... and the forward up to 2048 tiles
+    ("sq_m16_2048_tiles", "f32", 32768 - 7, 16, 16, 16, 16),
+    ("sq_m16_2049_tiles", "f32", 32768 + 5, 16, 16, 16, 16),
     ("rect_2_3_4_2", "f32", 37, 2, 3, 4, 2),
     ("rect_3_2_6_5", "f32", 19, 3, 2, 6, 5),
     ("rect_4_3_8_2", "f32", 70, 4, 3, 8, 2),
